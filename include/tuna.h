@@ -1,0 +1,195 @@
+/*
+ * tuna.h -- C ABI of the MI355X (gfx950) tunable-radix non-uniform all-to-all library.
+ *
+ * The library runs TuNA (Section "Tunable-radix Non-uniform All-to-all", Algorithm "TuNA") and
+ * its hierarchical coalesced variant TuNA_l^g (Section "Hierarchical Tunable Non-uniform
+ * All-to-all", Algorithm "Coalesced TuNA_l^g") for P *virtual ranks* whose send and receive
+ * buffers all live in one GPU's memory.  Every digit phase is device work: metadata (block
+ * size) exchange, size/displacement scan, gather-pack of the blocks whose base-r digit is
+ * non-zero, the exchange as an HBM-to-HBM move of the packed messages, scatter-unpack into the
+ * receive buffer R or the temporary buffer T.
+ *
+ * Conventions for every entry point
+ *   - Pointers named `sendbuf`, `recvbuf`, `*counts`, `*displs`, `workspace` are DEVICE pointers.
+ *     Pointers to result structs / size_t outputs are HOST pointers.
+ *   - Count and displacement matrices are row-major P x P, row = owning virtual rank:
+ *       sendcounts[i*P + j], sdispls[i*P + j] : the block rank i sends to rank j
+ *       recvcounts[j*P + i], rdispls[j*P + i] : where rank j receives the block from rank i
+ *     Counts are BYTES (int32, >= 0); displacements are BYTES (int64) from `sendbuf` / `recvbuf`,
+ *     one allocation each holding all P ranks' buffers; regions may come in any order, with gaps.
+ *     Receive regions must not overlap each other.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - The caller owns all arrays and keeps them alive until the stream work has completed.
+ *     The library never writes `sendbuf` or the four matrices, and writes `recvbuf` only inside
+ *     the receive regions (MPI_Alltoallv semantics).
+ *   - Return value: TUNA_OK (0) or a negative TUNA_ERR_* code.  Nothing throws or aborts.  When
+ *     an error is returned no payload byte has been moved.
+ *   - The library keeps one grow-only workspace and the statistics of the last call per process;
+ *     calls are not thread-safe against each other, and two calls in flight on different streams
+ *     share the workspace and therefore race.
+ *   - There is no CPU fallback: without a HIP device every compute entry point returns
+ *     TUNA_ERR_HIP.
+ */
+#ifndef TUNA_H
+#define TUNA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TUNA_OK 0
+#define TUNA_ERR_ARG -1              /* null pointer, P < 1, radix < 2, ranks_per_node does not divide P */
+#define TUNA_ERR_COUNT_MISMATCH -2   /* recvcounts[j][i] != sendcounts[i][j] for some i, j */
+#define TUNA_ERR_NEGATIVE_COUNT -3   /* a negative count */
+#define TUNA_ERR_NOMEM -4            /* the library could not allocate its workspace */
+#define TUNA_ERR_WORKSPACE_TOO_SMALL -5 /* a caller-supplied workspace is smaller than needed */
+#define TUNA_ERR_HIP -6              /* a HIP call failed; tuna_stats_t.last_hip_error has the code */
+#define TUNA_ERR_TOO_LARGE -7        /* P or a per-rank byte total exceeds the supported range */
+
+#define TUNA_MAX_PHASES 64
+#define TUNA_MAX_RANKS 32768
+
+/* One digit phase x: all rounds (x, z), 1 <= z < r, z*r^x below the dimension's size.  They
+ * touch disjoint index sets and are issued together (Section "Tunable Radix"). */
+typedef struct tuna_phase_stats {
+    int32_t dim;            /* 0: local / flat phase over the Q ranks of a node; 1: global phase over the N nodes */
+    int32_t x;              /* digit position */
+    int32_t radix;          /* r of this phase */
+    int32_t rounds;         /* number of point-to-point rounds (valid z) in this phase */
+    int64_t blocks;         /* blocks moved, all ranks, empty ones included */
+    int64_t payload_bytes;  /* b_x: payload bytes of those blocks */
+    int64_t staged_bytes;   /* bytes they occupy in a staging buffer (every block padded to 16 B) */
+    float ms_metadata;      /* metadata exchange + scans (profiling mode only, else 0) */
+    float ms_pack;
+    float ms_exchange;
+    float ms_unpack;
+} tuna_phase_stats_t;
+
+typedef struct tuna_stats {
+    int32_t P, Q, N;                 /* ranks, ranks per node, nodes (flat: Q = P, N = 1) */
+    int32_t local_radix, global_radix;
+    int32_t w_local, w_global;       /* digits: ceil(log_r Q), ceil(log_r N) */
+    int32_t K_local, K_global;       /* point-to-point rounds */
+    int32_t B_local, B_global;       /* T slots of the paper's bound, B = size - (K + 1), per dimension */
+    int32_t n_phases;
+    int32_t granularity;             /* 16, 4 or 1: common divisor of all counts/displacements/base addresses */
+    int32_t fused;                   /* 1 when the fused single-kernel rounds were used */
+    int32_t last_hip_error;
+    int32_t reserved;
+    int64_t max_block_bytes;         /* M (Algorithm "TuNA", line 1) */
+    int64_t total_payload_bytes;     /* sum of sendcounts */
+    int64_t temp_slots_per_rank;     /* slots of T actually laid out per rank */
+    int64_t temp_bytes;              /* bytes of T */
+    int64_t staging_bytes;           /* bytes of the send + receive staging buffers */
+    int64_t workspace_bytes;         /* total device bytes the call needed */
+    float ms_prepare;                /* validation, sizing, initial rotation (profiling mode only) */
+    float ms_self;                   /* own-block copy */
+    float ms_total;                  /* first to last kernel of the call */
+    float reserved_f;
+    tuna_phase_stats_t phase[TUNA_MAX_PHASES];
+} tuna_stats_t;
+
+/* Host-only description of the schedule for (P, ranks_per_node, radices); no GPU is touched.
+ * Section "Tunable Radix" (w, K), Section "Estimating temporary buffer size" (B, the T map). */
+typedef struct tuna_plan_info {
+    int32_t P, Q, N;
+    int32_t local_radix, global_radix;   /* after clamping to [2, Q] and [2, N] */
+    int32_t w_local, w_global;
+    int32_t K_local, K_global;
+    int32_t B_local, B_global;
+    int32_t n_phases;
+    int64_t temp_slots_per_rank;
+    int64_t blocks_sent_per_rank;        /* D for one rank: one send per non-zero digit of each index */
+} tuna_plan_info_t;
+
+/*
+ * The non-uniform all-to-all, MPI_Alltoallv's statement of the problem (abstract; Section
+ * "Graph Mining": same function signature as MPI_Alltoallv plus the tunables): when the work
+ * enqueued on `stream` has completed,
+ *     recvbuf[rdispls[j][i] .. +recvcounts[j][i])  ==  sendbuf[sdispls[i][j] .. +sendcounts[i][j])
+ * for all ranks i, j.
+ *   radix           r of Algorithm "TuNA", 2..P; larger values are clamped to P (r = P is the
+ *                   linear algorithm: one block per round, no temporary buffer).
+ *   ranks_per_node  Q.  0, 1 or P: flat TuNA over all P ranks.  Otherwise Q must divide P, rank
+ *                   p lives on node p / Q with local id p % Q, and the hierarchical variant runs
+ *                   with local radix min(radix, Q) and global radix min(radix, N), N = P / Q.
+ * The call validates the counts on the device, reads a few integers back (one stream
+ * synchronisation), sizes or grows the workspace, then enqueues all phases on `stream` and
+ * returns without waiting for them.
+ */
+int tuna_alltoallv(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls,
+                   void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls,
+                   int P, int radix, int ranks_per_node, void* stream);
+
+/*
+ * The same with the two radices chosen separately (Section "Hierarchical TuNA": the intra-node
+ * phase is TuNA with a radix up to Q; the inter-node phase exchanges the Q-block super-blocks
+ * between ranks of equal local id).  global_radix >= N gives the paper's coalesced schedule
+ * (N - 1 rounds, Q blocks per message); a smaller global_radix runs the same digit rounds over
+ * the N node-ranks with super-blocks as the unit.
+ */
+int tuna_alltoallv_hier(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls,
+                        void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls,
+                        int P, int ranks_per_node, int local_radix, int global_radix, void* stream);
+
+/*
+ * Device bytes a call with these counts and parameters needs (Algorithm "TuNA", lines 1-2:
+ * maximum block size M by a reduction over all ranks, T sized from it).  The reduction runs on
+ * the device; the call synchronises.  *bytes is a host pointer.
+ */
+int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node,
+                         int local_radix, int global_radix, size_t* bytes);
+
+/*
+ * Optional caller-owned workspace (device memory, 256-byte aligned).  While set, the library
+ * allocates nothing and returns TUNA_ERR_WORKSPACE_TOO_SMALL when it does not suffice.
+ * tuna_set_workspace(NULL, 0) returns to the library-owned, grow-only workspace.
+ */
+int tuna_set_workspace(void* workspace, size_t bytes);
+
+/* Frees the library-owned workspace and cached schedules (after the caller has synchronised). */
+int tuna_release(void);
+
+/*
+ * Options.  TUNA_OPT_PROFILE: 1 = bracket every kernel with HIP events on the call's stream so
+ * that tuna_get_stats reports per-phase times (the breakdown categories of Section "Performance
+ * analysis of coalesced and staggered TuNA_l^g": prepare, metadata, data, replace).
+ * TUNA_OPT_FUSED: 1 = move every block of a phase straight from its source (S or T) to its
+ * destination (R or the other copy of T) in one kernel instead of pack -> exchange -> unpack.
+ */
+#define TUNA_OPT_PROFILE 1
+#define TUNA_OPT_FUSED 2
+int tuna_set_option(int option, int value);
+
+/* Statistics of the last tuna_alltoallv* call (host struct).  Synchronises with that call's
+ * stream work when profiling is on. */
+int tuna_get_stats(tuna_stats_t* out);
+
+/* Schedule description, host only. */
+int tuna_plan_info(int P, int ranks_per_node, int local_radix, int global_radix,
+                   tuna_plan_info_t* out);
+
+/* Host only: phase `phase` (0 <= phase < n_phases) of the schedule.  header[0..5] receives
+ * {dim, x, radix, rounds, moving blocks per rank, r^x}; when `seg` is not NULL it receives, for
+ * the first min(seg_capacity, moving blocks) blocks in message order (digit value z ascending,
+ * then slot index ascending; Algorithm "TuNA", lines 8-11), six int32 each:
+ * {slot index e = j*Q + l, j, l, z, source T slot or -1 (send buffer), destination T slot or
+ * -1 (final: receive buffer)}. */
+int tuna_plan_phase(int P, int ranks_per_node, int local_radix, int global_radix, int phase,
+                    int32_t* header, int32_t* seg, int seg_capacity);
+
+/* Slot of block index o (1 <= o, not a direct block) in T for radix r:
+ * t = o - 1 - dx (r - 1) - dz with dx the position and dz the value of o's highest base-r digit
+ * (Section "Estimating temporary buffer size").  Returns -1 for o <= 0 or a direct block. */
+int tuna_t_index(int o, int radix);
+
+const char* tuna_strerror(int code);
+int tuna_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TUNA_H */

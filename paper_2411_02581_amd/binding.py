@@ -1,0 +1,204 @@
+"""ctypes binding of libtuna.so: argument marshalling only.
+
+Every function has the name and the argument order of its C entry point in include/tuna.h.
+Device arrays may be given as torch tensors (their data_ptr() is passed) or as integer device
+addresses.  Nothing here computes: if the HIP library is missing and cannot be built the import
+of the entry points fails loudly; there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Any, Optional
+
+from . import build as _build
+
+TUNA_OK = 0
+TUNA_ERR_ARG = -1
+TUNA_ERR_COUNT_MISMATCH = -2
+TUNA_ERR_NEGATIVE_COUNT = -3
+TUNA_ERR_NOMEM = -4
+TUNA_ERR_WORKSPACE_TOO_SMALL = -5
+TUNA_ERR_HIP = -6
+TUNA_ERR_TOO_LARGE = -7
+TUNA_OPT_PROFILE = 1
+TUNA_OPT_FUSED = 2
+TUNA_MAX_PHASES = 64
+
+EXPORTS = ("tuna_alltoallv", "tuna_alltoallv_hier", "tuna_workspace_bytes", "tuna_set_workspace",
+           "tuna_release", "tuna_set_option", "tuna_get_stats", "tuna_plan_info", "tuna_plan_phase",
+           "tuna_t_index",
+           "tuna_strerror", "tuna_version")
+
+
+class tuna_phase_stats_t(ctypes.Structure):
+    _fields_ = [("dim", ctypes.c_int32), ("x", ctypes.c_int32), ("radix", ctypes.c_int32),
+                ("rounds", ctypes.c_int32), ("blocks", ctypes.c_int64),
+                ("payload_bytes", ctypes.c_int64), ("staged_bytes", ctypes.c_int64),
+                ("ms_metadata", ctypes.c_float), ("ms_pack", ctypes.c_float),
+                ("ms_exchange", ctypes.c_float), ("ms_unpack", ctypes.c_float)]
+
+
+class tuna_stats_t(ctypes.Structure):
+    _fields_ = [("P", ctypes.c_int32), ("Q", ctypes.c_int32), ("N", ctypes.c_int32),
+                ("local_radix", ctypes.c_int32), ("global_radix", ctypes.c_int32),
+                ("w_local", ctypes.c_int32), ("w_global", ctypes.c_int32),
+                ("K_local", ctypes.c_int32), ("K_global", ctypes.c_int32),
+                ("B_local", ctypes.c_int32), ("B_global", ctypes.c_int32),
+                ("n_phases", ctypes.c_int32), ("granularity", ctypes.c_int32),
+                ("fused", ctypes.c_int32), ("last_hip_error", ctypes.c_int32),
+                ("reserved", ctypes.c_int32),
+                ("max_block_bytes", ctypes.c_int64), ("total_payload_bytes", ctypes.c_int64),
+                ("temp_slots_per_rank", ctypes.c_int64), ("temp_bytes", ctypes.c_int64),
+                ("staging_bytes", ctypes.c_int64), ("workspace_bytes", ctypes.c_int64),
+                ("ms_prepare", ctypes.c_float), ("ms_self", ctypes.c_float),
+                ("ms_total", ctypes.c_float), ("reserved_f", ctypes.c_float),
+                ("phase", tuna_phase_stats_t * TUNA_MAX_PHASES)]
+
+
+class tuna_plan_info_t(ctypes.Structure):
+    _fields_ = [("P", ctypes.c_int32), ("Q", ctypes.c_int32), ("N", ctypes.c_int32),
+                ("local_radix", ctypes.c_int32), ("global_radix", ctypes.c_int32),
+                ("w_local", ctypes.c_int32), ("w_global", ctypes.c_int32),
+                ("K_local", ctypes.c_int32), ("K_global", ctypes.c_int32),
+                ("B_local", ctypes.c_int32), ("B_global", ctypes.c_int32),
+                ("n_phases", ctypes.c_int32),
+                ("temp_slots_per_rank", ctypes.c_int64), ("blocks_sent_per_rank", ctypes.c_int64)]
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def load() -> ctypes.CDLL:
+    """Load libtuna.so (building it first only when no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build_library(force=True)
+    lib = ctypes.CDLL(_build.LIB)
+    vp, i, i64p = ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p
+    lib.tuna_alltoallv.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, vp]
+    lib.tuna_alltoallv_hier.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
+    lib.tuna_workspace_bytes.argtypes = [vp, i, i, i, i, ctypes.POINTER(ctypes.c_size_t)]
+    lib.tuna_set_workspace.argtypes = [vp, ctypes.c_size_t]
+    lib.tuna_release.argtypes = []
+    lib.tuna_set_option.argtypes = [i, i]
+    lib.tuna_get_stats.argtypes = [ctypes.POINTER(tuna_stats_t)]
+    lib.tuna_plan_info.argtypes = [i, i, i, i, ctypes.POINTER(tuna_plan_info_t)]
+    lib.tuna_plan_phase.argtypes = [i, i, i, i, i, vp, vp, i]
+    lib.tuna_t_index.argtypes = [i, i]
+    lib.tuna_strerror.argtypes = [i]
+    lib.tuna_strerror.restype = ctypes.c_char_p
+    lib.tuna_version.argtypes = []
+    for name in EXPORTS:
+        if name != "tuna_strerror":
+            getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _ptr(a: Any, dtype=None) -> Optional[int]:
+    """Device address of a torch tensor (checked) or a plain integer address."""
+    if a is None:
+        return None
+    if isinstance(a, int):
+        return a
+    if not a.is_cuda:
+        raise TypeError("device tensor expected")
+    if not a.is_contiguous():
+        raise TypeError("contiguous tensor expected")
+    if dtype is not None and a.dtype != dtype:
+        raise TypeError("tensor dtype %s, expected %s" % (a.dtype, dtype))
+    return a.data_ptr()
+
+
+def _stream(stream: Any) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def tuna_alltoallv(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P: int, radix: int,
+                   ranks_per_node: int = 0, stream=None) -> int:
+    import torch
+    return load().tuna_alltoallv(_ptr(sendbuf), _ptr(sendcounts, torch.int32), _ptr(sdispls, torch.int64),
+                                 _ptr(recvbuf), _ptr(recvcounts, torch.int32), _ptr(rdispls, torch.int64),
+                                 P, radix, ranks_per_node, _stream(stream))
+
+
+def tuna_alltoallv_hier(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P: int,
+                        ranks_per_node: int, local_radix: int, global_radix: int, stream=None) -> int:
+    import torch
+    return load().tuna_alltoallv_hier(_ptr(sendbuf), _ptr(sendcounts, torch.int32), _ptr(sdispls, torch.int64),
+                                      _ptr(recvbuf), _ptr(recvcounts, torch.int32), _ptr(rdispls, torch.int64),
+                                      P, ranks_per_node, local_radix, global_radix, _stream(stream))
+
+
+def tuna_workspace_bytes(sendcounts, P: int, ranks_per_node: int, local_radix: int, global_radix: int):
+    """Returns (code, bytes)."""
+    import torch
+    out = ctypes.c_size_t(0)
+    rc = load().tuna_workspace_bytes(_ptr(sendcounts, torch.int32), P, ranks_per_node, local_radix,
+                                     global_radix, ctypes.byref(out))
+    return rc, int(out.value)
+
+
+def tuna_set_workspace(workspace, nbytes: int) -> int:
+    return load().tuna_set_workspace(_ptr(workspace), nbytes)
+
+
+def tuna_release() -> int:
+    return load().tuna_release()
+
+
+def tuna_set_option(option: int, value: int) -> int:
+    return load().tuna_set_option(option, value)
+
+
+def tuna_get_stats() -> tuna_stats_t:
+    st = tuna_stats_t()
+    rc = load().tuna_get_stats(ctypes.byref(st))
+    if rc != TUNA_OK:
+        raise RuntimeError("tuna_get_stats: " + tuna_strerror(rc))
+    return st
+
+
+def tuna_plan_info(P: int, ranks_per_node: int, local_radix: int, global_radix: int):
+    """Returns (code, tuna_plan_info_t).  Host only."""
+    info = tuna_plan_info_t()
+    rc = load().tuna_plan_info(P, ranks_per_node, local_radix, global_radix, ctypes.byref(info))
+    return rc, info
+
+
+def tuna_plan_phase(P: int, ranks_per_node: int, local_radix: int, global_radix: int, phase: int):
+    """Returns (code, header[6], seg[nseg,6]) as numpy int32 arrays.  Host only."""
+    import numpy as np
+    header = np.zeros(6, dtype=np.int32)
+    lib = load()
+    rc = lib.tuna_plan_phase(P, ranks_per_node, local_radix, global_radix, phase, header.ctypes.data, None, 0)
+    if rc != TUNA_OK:
+        return rc, header, None
+    seg = np.zeros((int(header[4]), 6), dtype=np.int32)
+    rc = lib.tuna_plan_phase(P, ranks_per_node, local_radix, global_radix, phase, header.ctypes.data,
+                             seg.ctypes.data, seg.shape[0])
+    return rc, header, seg
+
+
+def tuna_t_index(o: int, radix: int) -> int:
+    return load().tuna_t_index(o, radix)
+
+
+def tuna_strerror(code: int) -> str:
+    return load().tuna_strerror(code).decode()
+
+
+def tuna_version() -> int:
+    return load().tuna_version()

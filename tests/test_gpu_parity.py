@@ -1,0 +1,271 @@
+"""GPU parity: libtuna.so through its C ABI against the CPU oracle, byte for byte over the whole
+receive allocation (canary bytes between and around the receive regions included), for every
+radix and hierarchy setting.  The result is unique, so the bar is exact equality."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+CANARY = 0xC7
+
+
+@pytest.fixture(scope="module")
+def tuna():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2411_02581_amd as t
+    t.load()
+    return t
+
+
+class Problem:
+    """One alltoallv problem resident on the GPU, with the oracle's expected receive buffer."""
+
+    def __init__(self, lay, send_host):
+        self.lay = lay
+        self.send_host = send_host
+        dev = "cuda:0"
+        self.send = torch.from_numpy(send_host).to(dev)
+        self.sendcounts = torch.from_numpy(lay.sendcounts).to(dev)
+        self.sdispls = torch.from_numpy(lay.sdispls).to(dev)
+        self.recvcounts = torch.from_numpy(lay.recvcounts).to(dev)
+        self.rdispls = torch.from_numpy(lay.rdispls).to(dev)
+        self.recv = torch.empty(lay.recv_bytes, dtype=torch.uint8, device=dev)
+        want = np.full(lay.recv_bytes, CANARY, dtype=np.uint8)
+        assert oracle.alltoallv(send_host, lay.sendcounts, lay.sdispls, want, lay.recvcounts, lay.rdispls) == 0
+        self.want = want
+
+    def args(self):
+        return (self.send, self.sendcounts, self.sdispls, self.recv, self.recvcounts, self.rdispls, self.lay.P)
+
+    def check(self, what):
+        torch.cuda.synchronize()
+        got = self.recv.cpu().numpy()
+        if not np.array_equal(got, self.want):
+            bad = np.flatnonzero(got != self.want)
+            raise AssertionError("%s: %d bytes differ, first at offset %d (got %d, want %d)" %
+                                 (what, bad.size, bad[0], got[bad[0]], self.want[bad[0]]))
+        assert np.array_equal(self.send.cpu().numpy(), self.send_host), what + ": send buffer modified"
+
+    def reset(self):
+        self.recv.fill_(CANARY)
+
+
+def run_flat(tuna, prob, radix, rpn=0):
+    prob.reset()
+    print("case P=%d radix=%d rpn=%d" % (prob.lay.P, radix, rpn), flush=True)
+    rc = tuna.tuna_alltoallv(*prob.args(), radix, rpn)
+    assert rc == 0, tuna.tuna_strerror(rc)
+    prob.check("P=%d radix=%d rpn=%d" % (prob.lay.P, radix, rpn))
+
+
+def run_hier(tuna, prob, Q, rl, rg):
+    prob.reset()
+    print("case P=%d Q=%d rl=%d rg=%d" % (prob.lay.P, Q, rl, rg), flush=True)
+    rc = tuna.tuna_alltoallv_hier(*prob.args(), Q, rl, rg)
+    assert rc == 0, tuna.tuna_strerror(rc)
+    prob.check("P=%d Q=%d rl=%d rg=%d" % (prob.lay.P, Q, rl, rg))
+
+
+def test_config1_traceable_payload(tuna):
+    lay = wl.make_layout(wl.make_counts(1), gap=16)
+    prob = Problem(lay, wl.payload_traceable_int32(lay))
+    run_flat(tuna, prob, 2)
+    st = tuna.tuna_get_stats()
+    assert (st.P, st.w_local, st.K_local, st.B_local) == (16, 4, 4, 11)
+    assert st.total_payload_bytes == lay.payload_bytes and st.max_block_bytes == lay.sendcounts.max()
+    assert st.granularity == 4
+
+
+@pytest.mark.parametrize("P", [1, 2, 3, 5, 8, 13, 16, 31])
+def test_small_every_radix(tuna, P):
+    """Tiny P, byte-granular sizes, gaps and permuted regions, every radix 2..P."""
+    counts = wl.counts_uniform_bytes(P, 77 + P, 300)
+    counts[counts % 5 == 0] = 0
+    lay = wl.make_layout(counts, gap=7, permute_seed=5)
+    prob = Problem(lay, wl.payload_position_hash(P, lay.send_bytes))
+    for r in range(2, max(P, 2) + 1):
+        run_flat(tuna, prob, r)
+    run_flat(tuna, prob, P + 9)       # clamps to P
+
+
+@pytest.mark.parametrize("align,quantum", [(1, 1), (4, 4), (16, 16)])
+def test_granularities(tuna, align, quantum):
+    """The three copy paths: 16-byte, 4-byte and byte granular sizes/displacements."""
+    P = 48
+    counts = (wl.counts_uniform_bytes(P, 5, 3000) // quantum * quantum).astype(np.int32)
+    lay = wl.make_layout(counts, gap=quantum, align=align)
+    prob = Problem(lay, wl.payload_position_hash(3, lay.send_bytes))
+    for r in (2, 7, 48):
+        run_flat(tuna, prob, r)
+        assert tuna.tuna_get_stats().granularity == quantum
+
+
+def test_config2_radix_sweep(tuna):
+    c = wl.CONFIGS[2]
+    lay = wl.make_layout(wl.make_counts(2))
+    prob = Problem(lay, wl.payload_position_hash(c.seed, lay.send_bytes))
+    for r in c.radices:
+        run_flat(tuna, prob, r)
+    st = tuna.tuna_get_stats()
+    assert st.granularity == 1 and st.total_payload_bytes == lay.payload_bytes
+
+
+def test_config3_reduced_hierarchical(tuna):
+    """Zipf sizes (many empty and tiny blocks, rare 16 KiB ones), float32 bit patterns, at
+    P = 256 = 16 ranks/node x 16 nodes; the full-size case is in test_gpu_full_size.py."""
+    P, Q = 256, 16
+    counts = wl.make_counts(3, P)
+    lay = wl.make_layout(counts)
+    prob = Problem(lay, wl.float32_bit_patterns(lay.send_bytes, 33))
+    for rg in (2, 8, 16):
+        run_hier(tuna, prob, Q, 4, rg)
+    run_flat(tuna, prob, 4)
+
+
+def test_config4_reduced(tuna):
+    P = 512
+    lay = wl.make_layout(wl.make_counts(4, P))
+    prob = Problem(lay, wl.payload_position_hash(44, lay.send_bytes))
+    for r in (2, 8, 64, 512):
+        run_flat(tuna, prob, r)
+
+
+def test_config5_reduced_uniform(tuna):
+    """All blocks 256 B: the result is a transpose of 256-byte cells."""
+    P, Q = 256, 32
+    lay = wl.make_layout(wl.counts_constant(P, 256))
+    send = wl.payload_position_hash(55, lay.send_bytes)
+    prob = Problem(lay, send)
+    assert np.array_equal(prob.want.reshape(P, P, 256), send.reshape(P, P, 256).transpose(1, 0, 2))
+    for r in (2, 16, 2048):
+        run_flat(tuna, prob, r, rpn=Q)
+        assert tuna.tuna_get_stats().granularity == 16
+
+
+@pytest.mark.parametrize("Q,N", [(1, 6), (2, 3), (3, 2), (4, 4), (5, 3), (3, 7), (8, 2), (6, 10)])
+def test_hierarchy_shapes(tuna, Q, N):
+    P = Q * N
+    counts = wl.counts_uniform_bytes(P, 900 + P, 700)
+    counts[counts % 3 == 0] = 0
+    lay = wl.make_layout(counts, gap=5, permute_seed=9)
+    prob = Problem(lay, wl.payload_position_hash(P, lay.send_bytes))
+    for rl in sorted({2, 3, max(Q, 2)}):
+        for rg in sorted({2, 3, max(N, 2)}):
+            run_hier(tuna, prob, Q, rl, rg)
+
+
+def test_degenerate_inputs(tuna):
+    # all blocks empty
+    lay = wl.make_layout(np.zeros((9, 9), dtype=np.int32), gap=4)
+    prob = Problem(lay, np.zeros(lay.send_bytes, dtype=np.uint8))
+    run_flat(tuna, prob, 3)
+    # only self blocks
+    counts = np.diag(np.arange(1, 8) * 11).astype(np.int32)
+    lay = wl.make_layout(counts, gap=2)
+    prob = Problem(lay, wl.payload_position_hash(1, lay.send_bytes))
+    run_flat(tuna, prob, 2)
+    # one sender, one huge block among empties (1 MiB + 3 bytes), and ranks that send nothing
+    counts = np.zeros((6, 6), dtype=np.int32)
+    counts[2, 5] = (1 << 20) + 3
+    counts[4, 0] = 17
+    lay = wl.make_layout(counts, gap=1)
+    prob = Problem(lay, wl.payload_position_hash(2, lay.send_bytes))
+    for r in (2, 3, 6):
+        run_flat(tuna, prob, r)
+    run_hier(tuna, prob, 2, 2, 2)
+
+
+def test_many_empty_segments_span_windows(tuna):
+    """More than one LDS window of segments inside a tile: long runs of empty blocks."""
+    P = 700
+    counts = np.zeros((P, P), dtype=np.int32)
+    rng = np.random.default_rng(12)
+    idx = rng.integers(0, P, size=(3000, 2))
+    counts[idx[:, 0], idx[:, 1]] = rng.integers(1, 5000, size=3000)
+    lay = wl.make_layout(counts)
+    prob = Problem(lay, wl.payload_position_hash(6, lay.send_bytes))
+    for r in (2, 700):
+        run_flat(tuna, prob, r)
+
+
+def test_errors(tuna):
+    lay = wl.make_layout(wl.counts_uniform_bytes(8, 1, 64))
+    prob = Problem(lay, wl.payload_position_hash(1, lay.send_bytes))
+    prob.reset()
+    bad = prob.recvcounts.clone()
+    bad[2, 3] += 1
+    a = list(prob.args())
+    a[4] = bad
+    assert tuna.tuna_alltoallv(*a, 2, 0) == tuna.TUNA_ERR_COUNT_MISMATCH
+    neg = prob.sendcounts.clone()
+    neg[1, 1] = -5
+    a = list(prob.args())
+    a[1] = neg
+    assert tuna.tuna_alltoallv(*a, 2, 0) == tuna.TUNA_ERR_NEGATIVE_COUNT
+    assert tuna.tuna_alltoallv(*prob.args(), 1, 0) == tuna.TUNA_ERR_ARG
+    assert tuna.tuna_alltoallv(*prob.args(), 2, 3) == tuna.TUNA_ERR_ARG       # 3 does not divide 8
+    torch.cuda.synchronize()
+    assert (prob.recv.cpu().numpy() == CANARY).all()                          # nothing was moved
+    run_flat(tuna, prob, 2)                                                    # and the library still works
+
+
+def test_stats_phase_bytes(tuna):
+    """Per-phase payload bytes reported by the device equal those of the per-rank model."""
+    from oracle import tuna_model as tm
+    P, r = 12, 3
+    counts = wl.counts_uniform_bytes(P, 4, 40)
+    lay = wl.make_layout(counts)
+    send = wl.payload_position_hash(9, lay.send_bytes)
+    prob = Problem(lay, send)
+    run_flat(tuna, prob, r)
+    st = tuna.tuna_get_stats()
+    S = [[bytes(send[lay.sdispls[i, j]:lay.sdispls[i, j] + counts[i, j]]) for j in range(P)] for i in range(P)]
+    _, ms = tm.simulate_tuna(S, r)
+    assert [st.phase[x].payload_bytes for x in range(st.n_phases)] == [ms["phase_bytes"][x] for x in range(st.n_phases)]
+    assert [st.phase[x].rounds for x in range(st.n_phases)] == [2, 2, 1]
+    assert all(st.phase[x].staged_bytes >= st.phase[x].payload_bytes for x in range(st.n_phases))
+
+
+def test_caller_workspace_and_profiling(tuna):
+    P = 64
+    lay = wl.make_layout(wl.make_counts(4, P))
+    prob = Problem(lay, wl.payload_position_hash(8, lay.send_bytes))
+    rc, need = tuna.tuna_workspace_bytes(prob.sendcounts, P, 0, 4, 4)
+    assert rc == 0 and need > 0
+    ws = torch.empty(need + 256, dtype=torch.uint8, device="cuda:0")
+    base = (ws.data_ptr() + 255) // 256 * 256
+    assert tuna.tuna_set_workspace(base, need) == 0
+    try:
+        run_flat(tuna, prob, 4)
+        assert tuna.tuna_get_stats().workspace_bytes <= need
+        assert tuna.tuna_set_workspace(base, 1024) == 0
+        prob.reset()
+        assert tuna.tuna_alltoallv(*prob.args(), 4, 0) == tuna.TUNA_ERR_WORKSPACE_TOO_SMALL
+    finally:
+        assert tuna.tuna_set_workspace(None, 0) == 0
+    tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 1)
+    try:
+        run_flat(tuna, prob, 4)
+        st = tuna.tuna_get_stats()
+        assert st.ms_total > 0 and all(st.phase[x].ms_pack > 0 for x in range(st.n_phases))
+    finally:
+        tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 0)
+
+
+def test_side_stream(tuna):
+    P = 96
+    lay = wl.make_layout(wl.make_counts(2, P))
+    prob = Problem(lay, wl.payload_position_hash(10, lay.send_bytes))
+    s = torch.cuda.Stream()
+    prob.reset()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        rc = tuna.tuna_alltoallv(*prob.args(), 4, 0, stream=s)
+    assert rc == 0
+    s.synchronize()
+    prob.check("side stream")

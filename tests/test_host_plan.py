@@ -1,0 +1,187 @@
+"""Host logic of the GPU library, checked without a GPU: the C ABI loads and exports every
+symbol the header declares, the schedule (w, K, B, D, T map) agrees with the oracle-side model
+and the paper's printed values, and the per-phase segment tables -- which slot every moving
+block is read from and stored to -- carry every block to its destination when replayed on the
+host with plain Python containers."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2411_02581_amd as tuna
+import workloads as wl
+from oracle import tuna_model as tm
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "tuna.h")).read()
+    declared = set(re.findall(r"^(?:int|const char\*)\s+(tuna_\w+)\s*\(", header, flags=re.M))
+    assert declared == set(tuna.EXPORTS)
+    lib = ctypes.CDLL(tuna.library_path())
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert tuna.tuna_version() >= 100
+    assert "transpose" in tuna.tuna_strerror(tuna.TUNA_ERR_COUNT_MISMATCH)
+
+
+def test_struct_sizes_match_the_header():
+    # 16 int32 + 6 int64 + 4 float + 64 phases of (4 int32 + 3 int64 + 4 float)
+    assert ctypes.sizeof(tuna.tuna_phase_stats_t) == 56
+    assert ctypes.sizeof(tuna.tuna_stats_t) == 64 + 48 + 16 + 64 * 56
+    assert ctypes.sizeof(tuna.tuna_plan_info_t) == 48 + 16
+
+
+def test_plan_matches_printed_values(golden):
+    for P, r, w, K in golden("digits_rounds.txt"):
+        rc, info = tuna.tuna_plan_info(P, 0, r, r)
+        assert rc == 0 and (info.w_local, info.K_local) == (w, K)
+    for P, r, B in golden("temp_slots.txt"):
+        rc, info = tuna.tuna_plan_info(P, 0, r, r)
+        assert rc == 0 and info.B_local == B and info.temp_slots_per_rank == B
+    for P, r, o, t in golden("t_map.txt"):
+        assert tuna.tuna_t_index(o, r) == t
+    for P, N, Q, r, local_steps, coalesced, _ in golden("hier_rounds.txt"):
+        rc, info = tuna.tuna_plan_info(P, Q, r, N)
+        assert rc == 0 and (info.K_local, info.K_global) == (local_steps, coalesced)
+
+
+@pytest.mark.parametrize("P", [1, 2, 3, 5, 8, 9, 16, 27, 30, 64, 100])
+def test_plan_matches_the_model(P):
+    for r in sorted({2, 3, 4, 7, max(P - 1, 2), max(P, 2), P + 5}):
+        rc, info = tuna.tuna_plan_info(P, 0, r, r)
+        assert rc == 0
+        rr = min(r, max(P, 2))
+        assert info.local_radix == rr or P < 2
+        assert info.w_local == tm.num_digits(P, rr)
+        assert info.K_local == tm.num_rounds(P, rr)
+        assert info.B_local == (tm.temp_slots(P, rr) if P > 1 else 0)
+        assert info.blocks_sent_per_rank == tm.blocks_sent_per_rank(P, rr)
+        assert info.n_phases == info.w_local and info.w_global == 0
+        for o in range(1, P):
+            want = -1 if tm.is_direct(o, rr) else tm.t_index(o, rr)
+            assert tuna.tuna_t_index(o, rr) == want
+
+
+def test_configured_schedules():
+    # the schedules of the five benchmark configurations
+    rc, i = tuna.tuna_plan_info(4096, 0, 2, 2)
+    assert (i.w_local, i.K_local, i.B_local) == (12, 12, 4083)
+    rc, i = tuna.tuna_plan_info(4096, 0, 8, 8)
+    assert (i.w_local, i.K_local, i.B_local) == (4, 28, 4067)
+    rc, i = tuna.tuna_plan_info(4096, 0, 64, 64)
+    assert (i.w_local, i.K_local, i.B_local) == (2, 126, 3969)
+    rc, i = tuna.tuna_plan_info(4096, 0, 4096, 4096)
+    assert (i.w_local, i.K_local, i.B_local) == (1, 4095, 0)
+    rc, i = tuna.tuna_plan_info(1024, 16, 4, 8)
+    assert (i.Q, i.N, i.w_local, i.K_local, i.w_global, i.K_global) == (16, 64, 2, 6, 2, 14)
+    rc, i = tuna.tuna_plan_info(2048, 32, 2048, 2048)
+    assert (i.local_radix, i.global_radix, i.K_local, i.K_global) == (32, 64, 31, 63)
+
+
+def test_argument_errors_without_a_gpu():
+    assert tuna.tuna_plan_info(12, 5, 2, 2)[0] == tuna.TUNA_ERR_ARG      # 5 does not divide 12
+    assert tuna.tuna_plan_info(0, 0, 2, 2)[0] == tuna.TUNA_ERR_ARG
+    assert tuna.tuna_plan_info(8, 0, 1, 2)[0] == tuna.TUNA_ERR_ARG
+    assert tuna.tuna_plan_info(1 << 20, 0, 2, 2)[0] == tuna.TUNA_ERR_TOO_LARGE
+    assert tuna.tuna_plan_phase(8, 0, 2, 2, 3)[0] == tuna.TUNA_ERR_ARG    # only 3 phases
+
+
+# ---- replay of the segment tables on the host -------------------------------------------------
+def _replay(counts, Q, rl, rg):
+    """Moves blocks exactly as the tables say: per phase, every rank reads each moving block from
+    the send buffer (source slot -1) or its T slot, the partner at distance z*r^x (downwards, as
+    in Algorithm "TuNA") stores it to the receive buffer (destination slot -1) or its T slot."""
+    P = counts.shape[0]
+    rc, info = tuna.tuna_plan_info(P, Q, rl, rg)
+    assert rc == 0
+    Q, N = info.Q, info.N                               # ranks_per_node 0, 1 or P means flat
+    S = [[bytes([(7 * i + j) & 0xFF]) * int(counts[i, j]) + b"" for j in range(P)] for i in range(P)]
+    R = [[None] * P for _ in range(P)]
+    T = [dict() for _ in range(P)]
+    for p in range(P):
+        R[p][p] = S[p][p]
+    per_phase_bytes = []
+    for ph in range(info.n_phases):
+        rc, hdr, seg = tuna.tuna_plan_phase(P, Q, rl, rg, ph)
+        assert rc == 0
+        dim, x, r, nz, nseg, rx = (int(v) for v in hdr)
+        assert rx == r ** x and nseg == seg.shape[0]
+        # message order: z ascending, then e ascending; e = j*Q + l
+        keys = [(int(s[3]), int(s[0])) for s in seg]
+        assert keys == sorted(keys) and len(set(keys)) == len(keys)
+        assert all(int(s[0]) == int(s[1]) * Q + int(s[2]) for s in seg)
+        assert set(int(s[3]) for s in seg) == set(range(1, nz + 1))
+        moved = []
+        nbytes = 0
+        for p in range(P):
+            n, g = divmod(p, Q)
+            for e, j, l, z, src_slot, dst_slot in seg.tolist():
+                coord = l if dim == 0 else j
+                assert (coord // rx) % r == z
+                if src_slot < 0:
+                    blk = S[p][((n - j) % N) * Q + (g - l) % Q]
+                else:
+                    blk = T[p].pop(src_slot)          # a slot is read exactly once after a store
+                if dim == 0:
+                    q = n * Q + (g - z * rx) % Q
+                else:
+                    q = ((n - z * rx) % N) * Q + g
+                moved.append((q, j, l, dst_slot, blk))
+                nbytes += len(blk)
+        for q, j, l, dst_slot, blk in moved:          # every rank packed before anyone unpacks
+            nq, gq = divmod(q, Q)
+            if dst_slot < 0:
+                src = ((nq + j) % N) * Q + (gq + l) % Q
+                assert R[q][src] is None
+                R[q][src] = blk
+            else:
+                assert 0 <= dst_slot < info.temp_slots_per_rank
+                assert dst_slot not in T[q]           # no live block is overwritten
+                T[q][dst_slot] = blk
+        per_phase_bytes.append(nbytes)
+    assert all(len(t) == 0 for t in T)                # nothing is left behind in T
+    return R, S, per_phase_bytes
+
+
+def _want(S):
+    P = len(S)
+    return [[S[i][j] for i in range(P)] for j in range(P)]
+
+
+@pytest.mark.parametrize("P", list(range(1, 13)) + [16, 17, 25, 33])
+def test_flat_tables_deliver_every_block(P):
+    counts = (wl.make_counts(2, P) % 7).astype(np.int32)
+    radices = range(2, max(P, 2) + 1) if P <= 12 else [2, 3, 4, 5, P - 1, P]
+    for r in radices:
+        R, S, _ = _replay(counts, P, r, r)
+        assert R == _want(S), (P, r)
+
+
+@pytest.mark.parametrize("Q,N", [(1, 5), (2, 2), (2, 3), (3, 2), (4, 4), (5, 3), (3, 7), (8, 2), (4, 9)])
+def test_hier_tables_deliver_every_block(Q, N):
+    P = Q * N
+    counts = (wl.make_counts(3, P) % 5).astype(np.int32)
+    for rl in sorted({2, 3, max(Q, 2)}):
+        for rg in sorted({2, 3, max(N, 2)}):
+            R, S, _ = _replay(counts, Q, rl, rg)
+            assert R == _want(S), (Q, N, rl, rg)
+
+
+def test_phase_bytes_follow_the_model():
+    """Payload bytes per digit phase of the table replay equal those of the per-rank model."""
+    P, r = 12, 3
+    counts = (wl.make_counts(2, P) % 9).astype(np.int32)
+    R, S, per_phase = _replay(counts, P, r, r)
+    _, st = tm.simulate_tuna(S, r)
+    assert per_phase == [st["phase_bytes"][x] for x in range(tm.num_digits(P, r))]
+    Q, N, rl, rg = 4, 3, 2, 2
+    R, S, per_phase = _replay(counts, Q, rl, rg)
+    _, st = tm.simulate_tuna_hier(S, Q, rl, rg)
+    wlc = tm.num_digits(Q, rl)
+    assert per_phase[:wlc] == [st["local_phase_bytes"][x] for x in range(wlc)]
+    assert per_phase[wlc:] == [st["global_phase_bytes"][x] for x in range(tm.num_digits(N, rg))]
