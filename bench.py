@@ -1,0 +1,228 @@
+#!/usr/bin/env python3
+"""Benchmark of the tunable-radix non-uniform all-to-all on one MI355X.
+
+A "step" is one whole tuna_alltoallv call (validation, initial rotation, every digit phase:
+metadata exchange, scan, pack, exchange, unpack) over one synthetic problem whose send and
+receive buffers are already resident in HBM.  Default workload: the P = 4096 flat configuration
+(block sizes normal(1 KiB, 256 B), ~16 GiB payload), radix sweep {2, 8, 64, 4096}.
+
+Prints ONE JSON line: `value` is the effective Alltoallv rate (payload bytes / time per call) of
+the best radix; `per_radix` has every radix; `roofline` is the dominant copy kernel's achieved
+HBM rate (algorithmic bytes = 2 x payload bytes it moves, read + write) against 8 TB/s, timed
+with HIP events on the call's stream; `cpu_baseline` is the plain CPU oracle timed on a bounded
+sample of the same problem on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, help="workload configuration 1..5")
+    ap.add_argument("--ranks", type=int, default=0, help="override P (reduced-size runs)")
+    ap.add_argument("--radices", type=str, default="", help="comma-separated radix sweep")
+    ap.add_argument("--fused", type=int, default=0, help="1: fused single-kernel rounds")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--traffic-json", type=str, default="",
+                    help="optional JSON file {kernel: bytes per launch} from rocprofv3 --pmc runs")
+    return ap.parse_args()
+
+
+def sweep_of(cfg, P):
+    import workloads as wl
+    c = wl.CONFIGS[cfg]
+    if c.global_radices:   # separate local / global radices
+        return [("hier", c.ranks_per_node, c.local_radix, rg) for rg in c.global_radices]
+    return [("single", c.ranks_per_node, min(r, P), min(r, P)) for r in c.radices]
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (all P virtual ranks live in one HBM); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2411_02581_amd as tuna
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    tuna.load()
+    dev = "cuda:0"
+    cfg = wl.CONFIGS[args.config]
+    P = args.ranks or cfg.P
+    t0 = time.time()
+    counts = wl.make_counts(args.config, P)
+    lay = wl.make_layout(counts)
+    Btot = lay.payload_bytes
+    print("[bench] config %d: P=%d payload %.3f GiB, inputs built in %.1f s" %
+          (args.config, P, Btot / 2**30, time.time() - t0), file=sys.stderr, flush=True)
+
+    send = wl.payload_position_hash_torch(cfg.seed, lay.send_bytes, dev)
+    recv = torch.empty(lay.recv_bytes, dtype=torch.uint8, device=dev)
+    d_sc = torch.from_numpy(lay.sendcounts).to(dev)
+    d_sd = torch.from_numpy(lay.sdispls).to(dev)
+    d_rc = torch.from_numpy(lay.recvcounts).to(dev)
+    d_rd = torch.from_numpy(lay.rdispls).to(dev)
+    torch.cuda.synchronize()
+
+    sweep = sweep_of(args.config, P)
+    if args.radices:
+        rs = [int(x) for x in args.radices.split(",")]
+        if cfg.global_radices:
+            sweep = [("hier", cfg.ranks_per_node, cfg.local_radix, r) for r in rs]
+        else:
+            sweep = [("single", cfg.ranks_per_node, min(r, P), min(r, P)) for r in rs]
+    rpn = cfg.ranks_per_node if P % max(cfg.ranks_per_node, 1) == 0 else 0
+
+    def call(kind, rl, rg):
+        if kind == "hier":
+            rc = tuna.tuna_alltoallv_hier(send, d_sc, d_sd, recv, d_rc, d_rd, P, rpn, rl, rg)
+        else:
+            rc = tuna.tuna_alltoallv(send, d_sc, d_sd, recv, d_rc, d_rd, P, rl, rpn)
+        if rc != 0:
+            raise RuntimeError("tuna_alltoallv failed: " + tuna.tuna_strerror(rc))
+
+    tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 1 if args.fused else 0)
+    per_radix = []
+    for kind, _, rl, rg in sweep:
+        label = "r_l=%d,r_g=%d" % (rl, rg) if kind == "hier" else "r=%d" % rl
+        tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 0)
+        for _ in range(args.warmup):
+            call(kind, rl, rg)
+        torch.cuda.synchronize()
+        # ---- timed region: exactly K steps between two synchronisations ----------------------
+        step_ms = []
+        t_start = time.perf_counter()
+        for _ in range(args.steps):
+            t1 = time.perf_counter()
+            call(kind, rl, rg)
+            torch.cuda.synchronize()
+            step_ms.append((time.perf_counter() - t1) * 1e3)
+        torch.cuda.synchronize()
+        total_ms = (time.perf_counter() - t_start) * 1e3
+        ms_per_step = total_ms / args.steps
+        # ---- the same K steps with HIP events around every kernel (roofline figures) ----------
+        tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 1)
+        kern = {"pack": [0.0, 0, 0], "exchange": [0.0, 0, 0], "unpack": [0.0, 0, 0]}   # ms, launches, payload bytes
+        meta_ms = prep_ms = 0.0
+        prof_total = 0.0
+        for _ in range(args.steps):
+            call(kind, rl, rg)
+            st = tuna.tuna_get_stats()
+            prof_total += st.ms_total
+            prep_ms += st.ms_prepare + st.ms_self
+            for x in range(st.n_phases):
+                ph = st.phase[x]
+                meta_ms += ph.ms_metadata
+                for name, ms in (("pack", ph.ms_pack), ("exchange", ph.ms_exchange), ("unpack", ph.ms_unpack)):
+                    kern[name][0] += ms
+                    kern[name][1] += 1
+                    kern[name][2] += ph.payload_bytes
+        tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 0)
+        st = tuna.tuna_get_stats()
+        hop_bytes = sum(st.phase[x].payload_bytes for x in range(st.n_phases))
+        kernels = {}
+        for name, (ms, n, pbytes) in kern.items():
+            if n and ms > 0:
+                kernels[name] = {"avg_ms": ms / n, "launches_per_step": n // args.steps,
+                                 "alg_bytes_per_launch": 2 * pbytes / n,
+                                 "achieved_GBs": 2 * pbytes / (ms * 1e-3) / 1e9}
+        per_radix.append({
+            "radix": label, "ms_per_step": ms_per_step, "median_ms": statistics.median(step_ms),
+            "stdev_ms": statistics.pstdev(step_ms), "effective_GBs": Btot / (ms_per_step * 1e-3) / 1e9,
+            "phases": st.n_phases, "rounds": st.K_local + st.K_global, "hop_bytes": hop_bytes,
+            "temp_bytes": st.temp_bytes, "workspace_bytes": st.workspace_bytes,
+            "profiled_ms_per_step": prof_total / args.steps, "metadata_ms_per_step": meta_ms / args.steps,
+            "prepare_ms_per_step": prep_ms / args.steps, "kernels": kernels, "granularity": st.granularity})
+        print("[bench] %s: %.3f ms/step, %.1f GB/s effective; " % (label, ms_per_step, per_radix[-1]["effective_GBs"]) +
+              ", ".join("%s %.0f GB/s" % (k, v["achieved_GBs"]) for k, v in kernels.items()),
+              file=sys.stderr, flush=True)
+
+    best = max(per_radix, key=lambda r: r["effective_GBs"])
+    # dominant kernel = the copy kernel with the largest total time at the best radix
+    roofline = None
+    if best["kernels"]:
+        dom = max(best["kernels"].items(), key=lambda kv: kv[1]["avg_ms"] * kv[1]["launches_per_step"])
+        traffic = None
+        if args.traffic_json and os.path.exists(args.traffic_json):
+            traffic = json.load(open(args.traffic_json)).get(dom[0])
+        roofline = {"bound": "hbm", "kernel": "k_tile_copy<%s>" % dom[0], "achieved": dom[1]["achieved_GBs"],
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom[1]["achieved_GBs"] / HBM_PEAK_GBS,
+                    "traffic": traffic, "avg_launch_ms": dom[1]["avg_ms"],
+                    "alg_bytes_per_launch": dom[1]["alg_bytes_per_launch"]}
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        cpu_baseline = time_oracle(lay, send, args.cpu_seconds)
+
+    out = {
+        "metric": "effective Alltoallv GB/s (payload bytes / call time) at the best radix; per-radix table and HBM roofline attached",
+        "value": best["effective_GBs"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": best["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "config %d: %s" % (args.config, cfg.description), "P": P,
+                   "payload_bytes": Btot, "best_radix": best["radix"], "fused": bool(args.fused),
+                   "ranks_per_node": rpn},
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "per_radix": per_radix,
+    }
+    print(json.dumps(out))
+
+
+def time_oracle(lay, send_dev, target_seconds):
+    """The CPU oracle (plain transpose, one thread) on a bounded sample: the receive side of the
+    first n receiver ranks of the same problem, n grown until the run takes about target_seconds."""
+    import numpy as np
+
+    import oracle
+    t0 = time.time()
+    send_host = send_dev.cpu().numpy()
+    print("[bench] send buffer to host in %.1f s" % (time.time() - t0), file=sys.stderr, flush=True)
+    P = lay.P
+    recv_host = np.zeros(lay.recv_bytes, dtype=np.uint8)     # pages touched before timing
+    n = max(1, min(P, P // 64))
+    best = None
+    spent = 0.0
+    while True:
+        sel = np.arange(n, dtype=np.int32)
+        nbytes = int(lay.recvcounts[:n].astype(np.int64).sum())
+        t1 = time.perf_counter()
+        rc = oracle.alltoallv_receivers(send_host, lay.sendcounts, lay.sdispls, recv_host, lay.recvcounts,
+                                        lay.rdispls, sel)
+        dt = time.perf_counter() - t1
+        assert rc == 0
+        spent += dt
+        best = (nbytes, dt, n)
+        if n >= P or spent >= target_seconds or dt >= target_seconds / 2:
+            break
+        scale = (target_seconds / 2) / max(dt, 1e-6)
+        n = int(min(P, max(n + 1, n * min(scale, 16))))
+    nbytes, dt, n = best
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count()
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "receive side of the first %d of %d ranks (%.3f GiB of payload), one thread, %.2f s; "
+                      "host has %d usable cores" % (n, P, nbytes / 2**30, dt, cores)}
+
+
+if __name__ == "__main__":
+    main()

@@ -18,7 +18,6 @@ namespace tuna {
 namespace {
 
 constexpr int kVersion = 100;
-constexpr int kWorkgroupsPerCU = 8;
 constexpr size_t kAlign = 256;
 
 struct DevicePlan {
@@ -109,9 +108,9 @@ void carve_layout(Carver& cv, int P, LayoutDev& L) {
     L.pre = cv.take<int>((size_t)P * L.ld);
     L.tot = cv.take<int>(P);
     L.rank_base = cv.take<long long>(P + 1);
-    L.tile_base = cv.take<int>(P + 1);
-    L.n_tiles = cv.take<int>(1);
-    L.tiles = nullptr;
+    L.unit_base = cv.take<int>(P + 1);
+    L.n_units = cv.take<int>(1);
+    L.units = nullptr;
 }
 
 MetaBuffers carve_meta(Carver& cv, int P) {
@@ -124,7 +123,7 @@ MetaBuffers carve_meta(Carver& cv, int P) {
 }
 
 struct DataSizes {
-    size_t tile_cap;        // tiles per layout
+    size_t unit_cap;        // wave units per layout (upper bound)
     size_t stage_chunks;    // chunks per staging buffer
     long long slots;        // T slots per rank
     long long slot_bytes;   // M rounded up to 16
@@ -136,12 +135,12 @@ DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long tot
     DataSizes d{};
     const bool any_phase = !pl.phases.empty() && total_chunks > 0;
     d.stage_chunks = any_phase ? (size_t)total_chunks : 0;
-    d.tile_cap = any_phase ? (size_t)(total_chunks / kTileChunks) + pl.P + 1 : 0;
+    d.unit_cap = any_phase ? (size_t)(total_chunks / kUnitChunks) + pl.P + 1 : 0;
     d.slots = pl.slots;
     d.slot_bytes = (M + 15) / 16 * 16;
     d.t_bytes = any_phase ? (size_t)pl.P * (size_t)d.slots * (size_t)d.slot_bytes : 0;
     const size_t tcopies = fused ? 2 : 1;
-    d.total = 2 * align_up(d.tile_cap * sizeof(int4)) + (fused ? 0 : 2 * align_up(d.stage_chunks * 16)) +
+    d.total = 2 * align_up(d.unit_cap * sizeof(int4)) + (fused ? 0 : 2 * align_up(d.stage_chunks * 16)) +
               tcopies * align_up(d.t_bytes);
     return d;
 }
@@ -205,17 +204,21 @@ void mark(hipStream_t s, int cat, int phase) {
     g.marks.push_back(Mark{g.ev_pool[k], cat, phase});
 }
 
+// One-shot grid over an upper bound of wave units (4 per workgroup); waves past the device-side
+// unit count exit immediately.
 template <int MODE>
-int launch_copy(int gran, const CopyArgs& a, hipStream_t s) {
-    const dim3 grid((unsigned)(g.num_cus * kWorkgroupsPerCU)), block(kCopyThreads);
+int launch_copy(int gran, size_t unit_cap, const CopyArgs& a, hipStream_t s) {
+    const size_t waves = kCopyThreads / kWave;
+    const dim3 grid((unsigned)((unit_cap + waves - 1) / waves)), block(kCopyThreads);
+    if (grid.x == 0) return TUNA_OK;
     if (MODE == kExchange) {
-        hipLaunchKernelGGL((k_tile_copy<MODE, 16>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((k_copy<MODE, 16>), grid, block, 0, s, a);
     } else if (gran == 16) {
-        hipLaunchKernelGGL((k_tile_copy<MODE, 16>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((k_copy<MODE, 16>), grid, block, 0, s, a);
     } else if (gran == 4) {
-        hipLaunchKernelGGL((k_tile_copy<MODE, 4>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((k_copy<MODE, 4>), grid, block, 0, s, a);
     } else {
-        hipLaunchKernelGGL((k_tile_copy<MODE, 1>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((k_copy<MODE, 1>), grid, block, 0, s, a);
     }
     HIPCHK(hipGetLastError());
     return TUNA_OK;
@@ -227,7 +230,7 @@ int build_layout(const int32_t* sizes, const SegInfo* seg, int nseg, int P, cons
     HIPCHK(hipGetLastError());
     hipLaunchKernelGGL(k_layout_base, dim3(1), dim3(1024), 0, s, P, L, phase_chunks);
     HIPCHK(hipGetLastError());
-    hipLaunchKernelGGL(k_layout_tiles, dim3(P), dim3(256), 0, s, nseg, L);
+    hipLaunchKernelGGL(k_layout_units, dim3(P), dim3(256), 0, s, nseg, L);
     HIPCHK(hipGetLastError());
     return TUNA_OK;
 }
@@ -322,10 +325,10 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
     Carver cm(mbase, mbytes);
     MetaBuffers mb = carve_meta(cm, P);
     Carver cd(dbase, ds.total);
-    mb.Ls.tiles = cd.take<int4>(ds.tile_cap);
-    mb.Lr.tiles = cd.take<int4>(ds.tile_cap);
-    uint4* stage_s = cd.take<uint4>(ds.stage_chunks);
-    uint4* stage_r = cd.take<uint4>(ds.stage_chunks);
+    mb.Ls.units = cd.take<int4>(ds.unit_cap);
+    mb.Lr.units = cd.take<int4>(ds.unit_cap);
+    v4u* stage_s = cd.take<v4u>(ds.stage_chunks);
+    v4u* stage_r = cd.take<v4u>(ds.stage_chunks);
     unsigned char* T = cd.take<unsigned char>(ds.t_bytes);
     if (!cm.ok || !cd.ok) return TUNA_ERR_WORKSPACE_TOO_SMALL;
     st.temp_bytes = (int64_t)ds.t_bytes;
@@ -372,17 +375,17 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
         // pack: S / T -> send staging
         a.stage = stage_s; a.L = mb.Ls; a.sizes = cur;
         a.user = (unsigned char*)sendbuf; a.displs = sdispls;
-        rc = launch_copy<kPack>(gran, a, s);
+        rc = launch_copy<kPack>(gran, ds.unit_cap, a, s);
         if (rc != TUNA_OK) return rc;
         mark(s, kCatPack, (int)i);
         // exchange: send staging of the partner -> receive staging
         a.stage = stage_r; a.L = mb.Lr; a.stage_src = stage_s; a.Ls = mb.Ls;
-        rc = launch_copy<kExchange>(gran, a, s);
+        rc = launch_copy<kExchange>(gran, ds.unit_cap, a, s);
         if (rc != TUNA_OK) return rc;
         mark(s, kCatExchange, (int)i);
         // unpack: receive staging -> R / T
         a.sizes = nxt; a.user = (unsigned char*)recvbuf; a.displs = rdispls;
-        rc = launch_copy<kUnpack>(gran, a, s);
+        rc = launch_copy<kUnpack>(gran, ds.unit_cap, a, s);
         if (rc != TUNA_OK) return rc;
         mark(s, kCatUnpack, (int)i);
         std::swap(cur, nxt);

@@ -13,11 +13,12 @@
 
 namespace tuna {
 
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));   // one 16-byte chunk
+
 constexpr int kWave = 64;
-constexpr int kCopyThreads = 256;                        // 4 waves
-constexpr int kChunksPerThread = 4;
-constexpr int kTileChunks = kCopyThreads * kChunksPerThread;   // 1024 chunks = 16 KiB per tile
-constexpr int kWindow = 256;                             // segments resolved per LDS window
+constexpr int kCopyThreads = 256;                        // 4 waves, each an independent work unit
+constexpr int kChunksPerLane = 4;
+constexpr int kUnitChunks = kWave * kChunksPerLane;      // 256 chunks = 4 KiB per wave unit
 constexpr int kScanThreads = 256;
 constexpr int kScanItems = 4;
 
@@ -41,9 +42,9 @@ struct LayoutDev {
     int* pre;                      // [P][ld]: exclusive prefix of chunk counts over the rank's segments; [nseg] = total
     int* tot;                      // [P]: chunks per rank
     long long* rank_base;          // [P+1]: first chunk of each rank in the staging buffer
-    int* tile_base;                // [P+1]: first tile of each rank
-    int4* tiles;                   // {rank, first segment, first chunk (rank-local), chunks in tile}
-    int* n_tiles;                  // total tiles
+    int* unit_base;                // [P+1]: first wave unit of each rank
+    int4* units;                   // {rank, first segment, first chunk (rank-local), chunks in unit}
+    int* n_units;                  // total units
     int ld;                        // row stride of pre (>= P + 1)
 };
 
@@ -265,7 +266,7 @@ __global__ void __launch_bounds__(kScanThreads) k_layout_scan(const int32_t* __r
 
 // ------------------------------------------------------------------------------------------
 // k_layout_base: exclusive scan over the P per-rank totals -> each rank's first chunk in the
-// staging buffer and its first tile.  Single workgroup of 1024 threads, carry across batches.
+// staging buffer and its first wave unit.  Single workgroup of 1024 threads, carry across batches.
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(1024) k_layout_base(int P, LayoutDev L,
                                                       unsigned long long* __restrict__ phase_chunks) {
@@ -277,7 +278,7 @@ __global__ void __launch_bounds__(1024) k_layout_base(int P, LayoutDev L,
     for (int base = 0; base < P; base += 1024) {
         const int p = base + tid;
         const int c = p < P ? L.tot[p] : 0;
-        const int t = (c + kTileChunks - 1) / kTileChunks;
+        const int t = (c + kUnitChunks - 1) / kUnitChunks;
         long long ic = c;
         int it = t;
 #pragma unroll
@@ -297,7 +298,7 @@ __global__ void __launch_bounds__(1024) k_layout_base(int P, LayoutDev L,
         }
         if (p < P) {
             L.rank_base[p] = carry_c + oc + ic - c;
-            L.tile_base[p] = carry_t + ot + it - t;
+            L.unit_base[p] = carry_t + ot + it - t;
         }
         carry_c += totc;
         carry_t += tott;
@@ -305,54 +306,58 @@ __global__ void __launch_bounds__(1024) k_layout_base(int P, LayoutDev L,
     }
     if (tid == 0) {
         L.rank_base[P] = carry_c;
-        L.tile_base[P] = carry_t;
-        *L.n_tiles = carry_t;
+        L.unit_base[P] = carry_t;
+        *L.n_units = carry_t;
         if (phase_chunks) *phase_chunks = (unsigned long long)carry_c;
     }
 }
 
 // ------------------------------------------------------------------------------------------
-// k_layout_tiles: cut every rank's staged chunks into tiles of kTileChunks and record, per tile,
-// the rank and the first segment that overlaps it (binary search in the rank's prefix row).
-// One workgroup per rank.
+// k_layout_units: cut every rank's staged chunks into wave units of kUnitChunks and record, per
+// unit, the rank and the first segment that overlaps it (binary search in the rank's prefix
+// row).  One workgroup per rank.
 // ------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) k_layout_tiles(int nseg, LayoutDev L) {
+__global__ void __launch_bounds__(256) k_layout_units(int nseg, LayoutDev L) {
     const int p = blockIdx.x;
     const int tot = L.tot[p];
-    const int nt = (tot + kTileChunks - 1) / kTileChunks;
+    const int nu = (tot + kUnitChunks - 1) / kUnitChunks;
     const int* pre = L.pre + (size_t)p * L.ld;
-    const int tb = L.tile_base[p];
-    for (int t = threadIdx.x; t < nt; t += blockDim.x) {
-        const int c0 = t * kTileChunks;
+    const int ub = L.unit_base[p];
+    for (int t = threadIdx.x; t < nu; t += blockDim.x) {
+        const int c0 = t * kUnitChunks;
         int lo = 0, hi = nseg;                 // largest s in [0, nseg) with pre[s] <= c0
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
             if (pre[mid] <= c0) lo = mid; else hi = mid;
         }
-        L.tiles[tb + t] = make_int4(p, lo, c0, min(kTileChunks, tot - c0));
+        L.units[ub + t] = make_int4(p, lo, c0, min(kUnitChunks, tot - c0));
     }
 }
 
 // ------------------------------------------------------------------------------------------
-// The copy engine.  pack / exchange / unpack are the same tiled, byte-balanced variable-length
-// copy with a different "other side":
+// The copy engine.  pack / exchange / unpack are the same byte-balanced variable-length copy
+// with a different "other side":
 //   pack     staging(send)  <- S at sdispls, or T slot      (Algorithm "TuNA", line 15, sender side)
 //   exchange staging(recv)  <- staging(send) of the partner (the point-to-point transfer itself)
 //   unpack   staging(recv)  -> R at rdispls, or T slot      (Algorithm "TuNA", lines 16-20)
-// A tile is 1024 consecutive chunks of one rank's staging region; its workgroup loads the chunk
-// prefix of the overlapping segments into LDS (a window of kWindow segments at a time), resolves
-// every segment's other-side address once, and each lane finds the segment of each of its 4
-// chunks by binary search in LDS.  Lanes of a wave touch consecutive 16-byte chunks on the
-// staging side (aligned dwordx4) and consecutive bytes of a block on the other side.
-// Persistent grid: workgroups stride over the tile list, whose length lives in device memory.
+//   fused    S / T of the sender -> R / T' of the receiver  (all three in one hop, no staging)
+// Work unit = one wavefront x 256 consecutive 16-byte chunks (4 KiB) of one rank's staging
+// region.  The wave is self-contained -- no workgroup barrier anywhere: lane i loads the chunk
+// prefix and the table entry of segment s0 + i, the lanes whose segment overlaps the unit
+// resolve its other-side address (T slot arithmetic, or one displacement load), the 64 entries
+// go to the wave's private LDS window, and every lane finds the segment of each of its 4 chunks
+// by a binary search over that window.  Lanes of a wave touch consecutive chunks on the staging
+// side (aligned, non-temporal dwordx4) and consecutive bytes of a block on the other side.
+// One-shot grid: 4 units per workgroup; the host launches an upper bound of units and waves
+// beyond the device-side unit count exit at once.
 // ------------------------------------------------------------------------------------------
 struct CopyArgs {
     // tiled (staging) side
-    uint4* stage;                       // staging buffer being tiled
+    v4u* stage;                         // staging buffer being tiled (unused when fused)
     LayoutDev L;                        // its layout
     const SegInfo* seg;
     int nseg;
-    // other side: caller buffer + T (pack, unpack)
+    // other side: caller buffer + T (pack, unpack, fused source)
     const int32_t* sizes;               // [P][P] block sizes at the tiled side's ranks (cur for pack, nxt for unpack)
     unsigned char* user;                // S (pack) or R (unpack)
     const int64_t* displs;              // sdispls (pack) or rdispls (unpack)
@@ -360,14 +365,18 @@ struct CopyArgs {
     long long slots;
     long long slot_bytes;
     // other side: send staging (exchange)
-    const uint4* stage_src;
+    const v4u* stage_src;
     LayoutDev Ls;
+    // fused: destination side
+    unsigned char* user2;               // R
+    const int64_t* displs2;             // rdispls
+    unsigned char* T2;                  // the copy of T written in this phase
     int P, Q, N, dim, rx;
 };
 
 template <int GRAN>
-__device__ __forceinline__ uint4 load_block_chunk(const unsigned char* src, int nb) {
-    uint4 v = make_uint4(0, 0, 0, 0);
+__device__ __forceinline__ v4u load_block_chunk(const unsigned char* src, int nb) {
+    v4u v = {0u, 0u, 0u, 0u};
     if (GRAN == 16 || nb >= 16) {
         __builtin_memcpy(&v, src, 16);
     } else if (GRAN == 4) {
@@ -380,13 +389,13 @@ __device__ __forceinline__ uint4 load_block_chunk(const unsigned char* src, int 
 #pragma unroll
         for (int b = 0; b < 15; ++b)
             if (b < nb) w[b >> 2] |= (uint32_t)src[b] << (8 * (b & 3));
-        v = make_uint4(w[0], w[1], w[2], w[3]);
+        v.x = w[0]; v.y = w[1]; v.z = w[2]; v.w = w[3];
     }
     return v;
 }
 
 template <int GRAN>
-__device__ __forceinline__ void store_block_chunk(unsigned char* dst, uint4 v, int nb) {
+__device__ __forceinline__ void store_block_chunk(unsigned char* dst, v4u v, int nb) {
     if (GRAN == 16 || nb >= 16) {
         __builtin_memcpy(dst, &v, 16);
     } else if (GRAN == 4) {
@@ -402,107 +411,146 @@ __device__ __forceinline__ void store_block_chunk(unsigned char* dst, uint4 v, i
     }
 }
 
+// Address of the block a table entry describes, on the caller-buffer / T side of rank (n, g).
+// far_is_source = false: the block's destination rank ((n - j) % N, (g - l) % Q) indexes displs
+// (send side); true: its source rank ((n + j) % N, (g + l) % Q) (receive side).
+__device__ __forceinline__ unsigned long long block_address(int slot, bool far_is_source, int p, int n, int g,
+                                                            int j, int l, int P, int Q, int N,
+                                                            unsigned char* user, const int64_t* displs,
+                                                            unsigned char* T, long long slots, long long slot_bytes) {
+    if (slot >= 0) return (unsigned long long)(T + ((long long)p * slots + slot) * slot_bytes);
+    int pn, pg;
+    if (!far_is_source) {
+        pn = n - j; if (pn < 0) pn += N;
+        pg = g - l; if (pg < 0) pg += Q;
+    } else {
+        pn = n + j; if (pn >= N) pn -= N;
+        pg = g + l; if (pg >= Q) pg -= Q;
+    }
+    return (unsigned long long)(user + displs[(size_t)p * P + pn * Q + pg]);
+}
+
 template <int MODE, int GRAN>
-__global__ void __launch_bounds__(kCopyThreads) k_tile_copy(const CopyArgs a) {
-    __shared__ int lpre[kWindow + 1];
-    __shared__ unsigned long long laddr[kWindow];
-    __shared__ int lsize[kWindow];
-    const int tid = threadIdx.x;
-    const int ntiles = *a.L.n_tiles;
-    for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int4 td = a.L.tiles[tile];
-        const int p = td.x, c0 = td.z, cend = td.z + td.w;
-        int sw = td.y;
-        const int n = p / a.Q, g = p - n * a.Q;
-        const int* prow = a.L.pre + (size_t)p * a.L.ld;
-        uint4* stage = a.stage + a.L.rank_base[p];
-        int c[kChunksPerThread];
-        bool pend[kChunksPerThread];
+__global__ void __launch_bounds__(kCopyThreads) k_copy(const CopyArgs a) {
+    __shared__ int s_pre[kCopyThreads / kWave][kWave];
+    __shared__ int s_size[kCopyThreads / kWave][kWave];
+    __shared__ unsigned long long s_addr[kCopyThreads / kWave][kWave];
+    __shared__ unsigned long long s_addr2[MODE == kFused ? kCopyThreads / kWave : 1][kWave];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int unit = blockIdx.x * (kCopyThreads / kWave) + wv;
+    if (unit >= *a.L.n_units) return;            // no barrier below: a wave may leave alone
+    const int4 ud = a.L.units[unit];
+    const int p = __builtin_amdgcn_readfirstlane(ud.x);
+    int sw = __builtin_amdgcn_readfirstlane(ud.y);
+    const int c0 = __builtin_amdgcn_readfirstlane(ud.z);
+    const int cend = c0 + __builtin_amdgcn_readfirstlane(ud.w);
+    const int n = p / a.Q, g = p - n * a.Q;
+    const int* prow = a.L.pre + (size_t)p * a.L.ld;
+    v4u* stage = MODE == kFused ? nullptr : a.stage + a.L.rank_base[p];
+    int* wpre = s_pre[wv];
+    int* wsize = s_size[wv];
+    unsigned long long* waddr = s_addr[wv];
+    unsigned long long* waddr2 = s_addr2[MODE == kFused ? wv : 0];
+
+    int c[kChunksPerLane];
+    bool pend[kChunksPerLane];
 #pragma unroll
-        for (int k = 0; k < kChunksPerThread; ++k) {
-            c[k] = c0 + k * kCopyThreads + tid;
-            pend[k] = c[k] < cend;
+    for (int k = 0; k < kChunksPerLane; ++k) {
+        c[k] = c0 + k * kWave + lane;
+        pend[k] = c[k] < cend;
+    }
+    for (;;) {
+        // ---- window: segments sw .. sw+63, one per lane --------------------------------------
+        const int s = sw + lane;
+        const int pre_i = s <= a.nseg ? prow[s] : INT_MAX;
+        const int pre_n = s + 1 <= a.nseg ? prow[s + 1] : INT_MAX;
+        int4 sa = make_int4(0, 0, -1, -1), sb = make_int4(0, 0, 0, 0);
+        if (s < a.nseg) {
+            const int4* sp = reinterpret_cast<const int4*>(a.seg + s);
+            sa = sp[0];                                   // e, z, src_slot, dst_slot
+            sb = sp[1];                                   // j, l
         }
-        for (;;) {
-            __syncthreads();                         // LDS of the previous window / tile is free
-            for (int t = tid; t <= kWindow; t += kCopyThreads) {
-                const int s = sw + t;
-                lpre[t] = s <= a.nseg ? prow[s] : INT_MAX;
-            }
-            __syncthreads();
-            const int wend = lpre[kWindow];          // chunks below wend are resolved by this window
-            for (int t = tid; t < kWindow; t += kCopyThreads) {
-                const int s = sw + t;
-                if (s < a.nseg && lpre[t] < cend && lpre[t + 1] > lpre[t]) {
-                    const SegInfo si = a.seg[s];
-                    unsigned long long addr;
-                    int size;
-                    if (MODE == kExchange) {
-                        const int ps = partner_up(n, g, a.Q, a.N, a.dim, si.z * a.rx);
-                        addr = (unsigned long long)(a.stage_src + a.Ls.rank_base[ps] +
-                                                    a.Ls.pre[(size_t)ps * a.Ls.ld + s]);
-                        size = (lpre[t + 1] - lpre[t]) << 4;
-                    } else {
-                        size = a.sizes[(size_t)p * a.P + si.e];
-                        const int slot = MODE == kPack ? si.src_slot : si.dst_slot;
-                        if (slot >= 0) {
-                            addr = (unsigned long long)(a.T + ((long long)p * a.slots + slot) * a.slot_bytes);
-                        } else {
-                            int pn, pg;            // the rank at the far end of this block's route
-                            if (MODE == kPack) {   // its destination: ((n - j) % N, (g - l) % Q)
-                                pn = n - si.j; if (pn < 0) pn += a.N;
-                                pg = g - si.l; if (pg < 0) pg += a.Q;
-                            } else {               // its source: ((n + j) % N, (g + l) % Q)
-                                pn = n + si.j; if (pn >= a.N) pn -= a.N;
-                                pg = g + si.l; if (pg >= a.Q) pg -= a.Q;
-                            }
-                            addr = (unsigned long long)(a.user + a.displs[(size_t)p * a.P + pn * a.Q + pg]);
-                        }
-                    }
-                    laddr[t] = addr;
-                    lsize[t] = size;
+        const int wend = __builtin_amdgcn_readlane(pre_n, kWave - 1);   // chunks below wend resolve here
+        const bool need = s < a.nseg && pre_i < cend && pre_n > pre_i && pre_n > c0;
+        unsigned long long addr = 0, addr2 = 0;
+        int size = 0;
+        if (need) {
+            if (MODE == kExchange) {
+                const int ps = partner_up(n, g, a.Q, a.N, a.dim, sa.y * a.rx);
+                addr = (unsigned long long)(a.stage_src + a.Ls.rank_base[ps] + a.Ls.pre[(size_t)ps * a.Ls.ld + s]);
+                size = (pre_n - pre_i) << 4;
+            } else {
+                size = a.sizes[(size_t)p * a.P + sa.x];
+                if (MODE == kPack || MODE == kFused)
+                    addr = block_address(sa.z, false, p, n, g, sb.x, sb.y, a.P, a.Q, a.N, a.user, a.displs, a.T,
+                                         a.slots, a.slot_bytes);
+                if (MODE == kUnpack)
+                    addr = block_address(sa.w, true, p, n, g, sb.x, sb.y, a.P, a.Q, a.N, a.user, a.displs, a.T,
+                                         a.slots, a.slot_bytes);
+                if (MODE == kFused) {                    // the receiver: distance z*r^x downwards
+                    int qn = n, qg = g;
+                    const int dist = sa.y * a.rx;
+                    if (a.dim == 0) { qg -= dist; if (qg < 0) qg += a.Q; }
+                    else { qn -= dist; if (qn < 0) qn += a.N; }
+                    addr2 = block_address(sa.w, true, qn * a.Q + qg, qn, qg, sb.x, sb.y, a.P, a.Q, a.N, a.user2,
+                                          a.displs2, a.T2, a.slots, a.slot_bytes);
                 }
             }
-            __syncthreads();
-            bool act[kChunksPerThread];
-            unsigned long long oa[kChunksPerThread];
-            int nb[kChunksPerThread];
-            uint4 v[kChunksPerThread];
-#pragma unroll
-            for (int k = 0; k < kChunksPerThread; ++k) {
-                act[k] = pend[k] && c[k] < wend;
-                oa[k] = 0; nb[k] = 0;
-                if (act[k]) {
-                    int lo = 0, hi = kWindow;        // lpre[lo] <= c < lpre[hi]
-#pragma unroll
-                    for (int it = 0; it < 8; ++it) {
-                        const int mid = (lo + hi) >> 1;
-                        if (lpre[mid] <= c[k]) lo = mid; else hi = mid;
-                    }
-                    const int off = (c[k] - lpre[lo]) << 4;
-                    oa[k] = laddr[lo] + (unsigned long long)off;
-                    nb[k] = min(16, lsize[lo] - off);
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < kChunksPerThread; ++k) {
-                if (act[k]) {
-                    if (MODE == kUnpack) v[k] = stage[c[k]];
-                    else if (MODE == kExchange) v[k] = *reinterpret_cast<const uint4*>(oa[k]);
-                    else v[k] = load_block_chunk<GRAN>(reinterpret_cast<const unsigned char*>(oa[k]), nb[k]);
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < kChunksPerThread; ++k) {
-                if (act[k]) {
-                    if (MODE == kUnpack) store_block_chunk<GRAN>(reinterpret_cast<unsigned char*>(oa[k]), v[k], nb[k]);
-                    else stage[c[k]] = v[k];
-                    pend[k] = false;
-                }
-            }
-            if (wend >= cend) break;
-            sw += kWindow;
         }
+        wpre[lane] = pre_i;
+        wsize[lane] = size;
+        waddr[lane] = addr;
+        if (MODE == kFused) waddr2[lane] = addr2;
+        // the window is private to this wave; its LDS writes are ordered before the reads below
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        // entries that can hold a chunk of this unit: the leading lanes with pre_i < cend
+        const int nlive = __popcll(__ballot(pre_i < cend));
+        int steps = 0;
+        while ((1 << steps) < nlive) ++steps;
+
+        bool act[kChunksPerLane];
+        unsigned long long oa[kChunksPerLane], oa2[kChunksPerLane];
+        int nb[kChunksPerLane];
+        v4u v[kChunksPerLane];
+#pragma unroll
+        for (int k = 0; k < kChunksPerLane; ++k) {
+            act[k] = pend[k] && c[k] < wend;
+            oa[k] = 0; oa2[k] = 0; nb[k] = 0;
+            if (act[k]) {
+                int lo = 0, hi = nlive;              // wpre[lo] <= c < wpre[hi] (hi == nlive: sentinel)
+                for (int it = 0; it < steps; ++it) {
+                    const int mid = (lo + hi) >> 1;
+                    if (mid > lo) { if (wpre[mid] <= c[k]) lo = mid; else hi = mid; }
+                }
+                const int off = (c[k] - wpre[lo]) << 4;
+                oa[k] = waddr[lo] + (unsigned long long)off;
+                if (MODE == kFused) oa2[k] = waddr2[lo] + (unsigned long long)off;
+                nb[k] = min(16, wsize[lo] - off);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < kChunksPerLane; ++k) {
+            if (act[k]) {
+                if (MODE == kUnpack) v[k] = __builtin_nontemporal_load(stage + c[k]);
+                else if (MODE == kExchange) v[k] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(oa[k]));
+                else v[k] = load_block_chunk<GRAN>(reinterpret_cast<const unsigned char*>(oa[k]), nb[k]);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < kChunksPerLane; ++k) {
+            if (act[k]) {
+                if (MODE == kUnpack) store_block_chunk<GRAN>(reinterpret_cast<unsigned char*>(oa[k]), v[k], nb[k]);
+                else if (MODE == kFused) store_block_chunk<GRAN>(reinterpret_cast<unsigned char*>(oa2[k]), v[k], nb[k]);
+                else __builtin_nontemporal_store(v[k], stage + c[k]);
+                pend[k] = false;
+            }
+        }
+        if (wend >= cend) break;
+        sw += kWave;
+        __builtin_amdgcn_wave_barrier();
     }
 }
 

@@ -13,14 +13,15 @@
 
 namespace tuna {
 
-// One moving block of a phase, in message order (z ascending, then e ascending).  32 bytes.
+// One moving block of a phase, in message order (z ascending, then e ascending).  32 bytes, read
+// by the kernels as two 16-byte halves: {e, z, src_slot, dst_slot} and {j, l, -, -}.
 struct SegInfo {
     int32_t e;         // slot index j*Q + l
-    int32_t j;         // node distance
-    int32_t l;         // local distance
     int32_t z;         // value of the phase's digit (1..r-1): which message, and the partner distance z*r^x
     int32_t src_slot;  // T slot the sender reads it from, or -1: still in the send buffer S
     int32_t dst_slot;  // T slot the receiver stores it to, or -1: final, goes to the receive buffer R
+    int32_t j;         // node distance
+    int32_t l;         // local distance
     int32_t pad0, pad1;
 };
 
