@@ -137,7 +137,7 @@ DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long tot
     d.stage_chunks = any_phase ? (size_t)total_chunks : 0;
     d.unit_cap = any_phase ? (size_t)(total_chunks / kUnitChunks) + pl.P + 1 : 0;
     d.slots = pl.slots;
-    d.slot_bytes = (M + 15) / 16 * 16;
+    d.slot_bytes = (M + 127) / 128 * 128;     // whole 128-byte lines per slot
     d.t_bytes = any_phase ? (size_t)pl.P * (size_t)d.slots * (size_t)d.slot_bytes : 0;
     const size_t tcopies = fused ? 2 : 1;
     d.total = 2 * align_up(d.unit_cap * sizeof(int4)) + (fused ? 0 : 2 * align_up(d.stage_chunks * 16)) +
@@ -375,6 +375,7 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
         // pack: S / T -> send staging
         a.stage = stage_s; a.L = mb.Ls; a.sizes = cur;
         a.user = (unsigned char*)sendbuf; a.displs = sdispls;
+        a.user_limit = (unsigned long long)(uintptr_t)sendbuf + hs.send_extent;
         rc = launch_copy<kPack>(gran, ds.unit_cap, a, s);
         if (rc != TUNA_OK) return rc;
         mark(s, kCatPack, (int)i);

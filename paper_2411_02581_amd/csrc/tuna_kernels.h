@@ -32,7 +32,7 @@ struct Status {
     int pad;
     unsigned long long total_bytes;    // sum of sendcounts
     unsigned long long total_chunks;   // sum of ceil(count / 16)
-    unsigned long long max_rank_chunks;// unused (reserved)
+    unsigned long long send_extent;    // max over non-empty blocks of sdispls + count: bytes of sendbuf that hold blocks
     unsigned long long phase_bytes[64];   // payload bytes moved per phase
     unsigned long long phase_chunks[64];  // staged chunks per phase
 };
@@ -93,7 +93,7 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
     const int tx = threadIdx.x, ty = threadIdx.y;
     unsigned int flags = 0, abits = 0;
     int mx = 0;
-    unsigned long long bytes = 0, chunks = 0;
+    unsigned long long bytes = 0, chunks = 0, extent = 0;
     for (int a = ty; a < 32; a += 8) {
         const int i = bi + a, j = bj + tx;
         int c = 0;
@@ -101,7 +101,11 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
             c = sendcounts[(size_t)i * P + j];
             if (c < 0) { flags |= 1u; c = 0; }
             abits |= (unsigned int)c;
-            if (sdispls) abits |= (unsigned int)sdispls[(size_t)i * P + j] & 15u;
+            if (sdispls) {
+                const int64_t d = sdispls[(size_t)i * P + j];
+                abits |= (unsigned int)d & 15u;
+                if (c > 0 && d >= 0) extent = max(extent, (unsigned long long)d + (unsigned long long)c);
+            }
             mx = max(mx, c);
             bytes += (unsigned long long)c;
             chunks += (unsigned long long)((c + 15) >> 4);
@@ -128,6 +132,7 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
         mx = max(mx, __shfl_xor(mx, d, kWave));
         bytes += __shfl_xor(bytes, d, kWave);
         chunks += __shfl_xor(chunks, d, kWave);
+        extent = max(extent, (unsigned long long)__shfl_xor(extent, d, kWave));
     }
     if (((ty * 32 + tx) & (kWave - 1)) == 0) {
         if (flags) atomicOr(&st->flags, flags);
@@ -135,6 +140,7 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
         if (mx) atomicMax(&st->max_count, mx);
         if (bytes) atomicAdd(&st->total_bytes, bytes);
         if (chunks) atomicAdd(&st->total_chunks, chunks);
+        if (extent) atomicMax(&st->send_extent, extent);
     }
 }
 
@@ -361,6 +367,7 @@ struct CopyArgs {
     const int32_t* sizes;               // [P][P] block sizes at the tiled side's ranks (cur for pack, nxt for unpack)
     unsigned char* user;                // S (pack) or R (unpack)
     const int64_t* displs;              // sdispls (pack) or rdispls (unpack)
+    unsigned long long user_limit;      // pack: address one past the last byte of S that holds a block
     unsigned char* T;                   // temporary buffer: slot s of rank p at ((p*slots + s) * slot_bytes)
     long long slots;
     long long slot_bytes;
@@ -481,13 +488,22 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy(const CopyArgs a) {
                 addr = (unsigned long long)(a.stage_src + a.Ls.rank_base[ps] + a.Ls.pre[(size_t)ps * a.Ls.ld + s]);
                 size = (pre_n - pre_i) << 4;
             } else {
-                size = a.sizes[(size_t)p * a.P + sa.x];
-                if (MODE == kPack || MODE == kFused)
+                // `size` bounds the bytes a chunk access may touch.  T slots and staging are padded
+                // to whole chunks (lines), so only the caller's buffers need care: a store into R
+                // must end exactly with the block; a load from S may run into the bytes that
+                // follow the block as long as it stays inside the part of S that holds blocks.
+                size = (pre_n - pre_i) << 4;
+                if (MODE == kPack || MODE == kFused) {
                     addr = block_address(sa.z, false, p, n, g, sb.x, sb.y, a.P, a.Q, a.N, a.user, a.displs, a.T,
                                          a.slots, a.slot_bytes);
-                if (MODE == kUnpack)
+                    if (sa.z < 0) size = (int)min((unsigned long long)size, a.user_limit - addr);
+                }
+                if (MODE == kUnpack) {
                     addr = block_address(sa.w, true, p, n, g, sb.x, sb.y, a.P, a.Q, a.N, a.user, a.displs, a.T,
                                          a.slots, a.slot_bytes);
+                    if (sa.w < 0) size = a.sizes[(size_t)p * a.P + sa.x];
+                    else size |= 1 << 30;             // T-bound: the tail lane completes the 128-byte line
+                }
                 if (MODE == kFused) {                    // the receiver: distance z*r^x downwards
                     int qn = n, qg = g;
                     const int dist = sa.y * a.rx;
@@ -495,6 +511,8 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy(const CopyArgs a) {
                     else { qn -= dist; if (qn < 0) qn += a.N; }
                     addr2 = block_address(sa.w, true, qn * a.Q + qg, qn, qg, sb.x, sb.y, a.P, a.Q, a.N, a.user2,
                                           a.displs2, a.T2, a.slots, a.slot_bytes);
+                    if (sa.w < 0) size = min(size, a.sizes[(size_t)p * a.P + sa.x]);
+                    else size |= 1 << 30;
                 }
             }
         }
@@ -513,12 +531,12 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy(const CopyArgs a) {
 
         bool act[kChunksPerLane];
         unsigned long long oa[kChunksPerLane], oa2[kChunksPerLane];
-        int nb[kChunksPerLane];
+        int nb[kChunksPerLane], fill[kChunksPerLane];
         v4u v[kChunksPerLane];
 #pragma unroll
         for (int k = 0; k < kChunksPerLane; ++k) {
             act[k] = pend[k] && c[k] < wend;
-            oa[k] = 0; oa2[k] = 0; nb[k] = 0;
+            oa[k] = 0; oa2[k] = 0; nb[k] = 0; fill[k] = 0;
             if (act[k]) {
                 int lo = 0, hi = nlive;              // wpre[lo] <= c < wpre[hi] (hi == nlive: sentinel)
                 for (int it = 0; it < steps; ++it) {
@@ -528,7 +546,10 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy(const CopyArgs a) {
                 const int off = (c[k] - wpre[lo]) << 4;
                 oa[k] = waddr[lo] + (unsigned long long)off;
                 if (MODE == kFused) oa2[k] = waddr2[lo] + (unsigned long long)off;
-                nb[k] = min(16, wsize[lo] - off);
+                const int sz = wsize[lo];
+                nb[k] = min(16, (sz & ~(1 << 30)) - off);
+                // last chunk of a T-bound block: number of further chunks up to the 128-byte line end
+                fill[k] = ((sz >> 30) & 1) && (off + 16 >= (sz & ~(1 << 30))) ? ((128 - ((off + 16) & 127)) & 127) >> 4 : 0;
             }
         }
 #pragma unroll
@@ -542,9 +563,13 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy(const CopyArgs a) {
 #pragma unroll
         for (int k = 0; k < kChunksPerLane; ++k) {
             if (act[k]) {
-                if (MODE == kUnpack) store_block_chunk<GRAN>(reinterpret_cast<unsigned char*>(oa[k]), v[k], nb[k]);
-                else if (MODE == kFused) store_block_chunk<GRAN>(reinterpret_cast<unsigned char*>(oa2[k]), v[k], nb[k]);
-                else __builtin_nontemporal_store(v[k], stage + c[k]);
+                if (MODE == kUnpack || MODE == kFused) {
+                    unsigned char* dst = reinterpret_cast<unsigned char*>(MODE == kFused ? oa2[k] : oa[k]);
+                    store_block_chunk<GRAN>(dst, v[k], nb[k]);
+                    for (int f = 1; f <= fill[k]; ++f) *reinterpret_cast<v4u*>(dst + 16 * f) = v[k];
+                } else {
+                    __builtin_nontemporal_store(v[k], stage + c[k]);
+                }
                 pend[k] = false;
             }
         }
