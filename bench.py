@@ -103,6 +103,22 @@ def main():
         if rc != 0:
             raise RuntimeError("tuna_alltoallv failed: " + tuna.tuna_strerror(rc))
 
+    # ---- practical ceiling: a plain one-chunk-per-thread copy of up to 4 GiB ----------------------
+    nb = min(4 << 30, lay.send_bytes // 16 * 16, lay.recv_bytes // 16 * 16)
+    copy_ceiling = None
+    if nb >= (1 << 20):
+        for _ in range(2):
+            tuna.tuna_plain_copy(send, recv, nb)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            tuna.tuna_plain_copy(send, recv, nb)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 10
+        copy_ceiling = {"GBs": 2 * nb / (ms * 1e-3) / 1e9, "bytes_copied": nb, "ms": ms}
+        print("[bench] plain copy ceiling: %.0f GB/s (read + write)" % copy_ceiling["GBs"], file=sys.stderr, flush=True)
+
     tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 1 if args.fused else 0)
     per_radix = []
     for kind, _, rl, rg in sweep:
@@ -184,7 +200,7 @@ def main():
         "config": {"workload": "config %d: %s" % (args.config, cfg.description), "P": P,
                    "payload_bytes": Btot, "best_radix": best["radix"], "fused": bool(args.fused),
                    "ranks_per_node": rpn},
-        "roofline": roofline, "cpu_baseline": cpu_baseline, "per_radix": per_radix,
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "copy_ceiling": copy_ceiling, "per_radix": per_radix,
     }
     print(json.dumps(out))
 

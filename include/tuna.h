@@ -144,6 +144,14 @@ int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node,
                          int local_radix, int global_radix, size_t* bytes);
 
 /*
+ * Plain device-to-device copy of `bytes` bytes (a multiple of 16; both pointers 16-byte
+ * aligned) with one 16-byte load and store per thread, enqueued on `stream`.  Not part of the
+ * algorithm: it is the measured HBM copy ceiling the benchmark quotes next to the 8 TB/s peak,
+ * and the known-size kernel that hardware byte counters are calibrated against.
+ */
+int tuna_plain_copy(const void* src, void* dst, size_t bytes, void* stream);
+
+/*
  * Optional caller-owned workspace (device memory, 256-byte aligned).  While set, the library
  * allocates nothing and returns TUNA_ERR_WORKSPACE_TOO_SMALL when it does not suffice.
  * tuna_set_workspace(NULL, 0) returns to the library-owned, grow-only workspace.

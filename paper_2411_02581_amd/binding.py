@@ -27,7 +27,7 @@ TUNA_MAX_PHASES = 64
 
 EXPORTS = ("tuna_alltoallv", "tuna_alltoallv_hier", "tuna_workspace_bytes", "tuna_set_workspace",
            "tuna_release", "tuna_set_option", "tuna_get_stats", "tuna_plan_info", "tuna_plan_phase",
-           "tuna_t_index",
+           "tuna_t_index", "tuna_plain_copy",
            "tuna_strerror", "tuna_version")
 
 
@@ -78,9 +78,12 @@ def load() -> ctypes.CDLL:
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.LIB):
-        _build.build_library(force=True)
-    lib = ctypes.CDLL(_build.LIB)
+    path = os.environ.get("TUNA_LIBRARY", "")      # debugging aid: load another build of the library
+    if not path:
+        path = _build.LIB
+        if not os.path.exists(path):
+            _build.build_library(force=True)
+    lib = ctypes.CDLL(path)
     vp, i, i64p = ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p
     lib.tuna_alltoallv.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, vp]
     lib.tuna_alltoallv_hier.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
@@ -92,6 +95,7 @@ def load() -> ctypes.CDLL:
     lib.tuna_plan_info.argtypes = [i, i, i, i, ctypes.POINTER(tuna_plan_info_t)]
     lib.tuna_plan_phase.argtypes = [i, i, i, i, i, vp, vp, i]
     lib.tuna_t_index.argtypes = [i, i]
+    lib.tuna_plain_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.tuna_strerror.argtypes = [i]
     lib.tuna_strerror.restype = ctypes.c_char_p
     lib.tuna_version.argtypes = []
@@ -194,6 +198,10 @@ def tuna_plan_phase(P: int, ranks_per_node: int, local_radix: int, global_radix:
 
 def tuna_t_index(o: int, radix: int) -> int:
     return load().tuna_t_index(o, radix)
+
+
+def tuna_plain_copy(src, dst, nbytes: int, stream=None) -> int:
+    return load().tuna_plain_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream))
 
 
 def tuna_strerror(code: int) -> str:

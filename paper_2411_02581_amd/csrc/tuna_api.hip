@@ -250,8 +250,9 @@ int run_validate(const int32_t* sendcounts, const int32_t* recvcounts, const int
     const int nwords = (int)(sizeof(Status) / 4);
     hipLaunchKernelGGL(k_clear, dim3((nwords + 255) / 256), dim3(256), 0, s, (unsigned int*)g.d_status, nwords);
     HIPCHK(hipGetLastError());
-    const unsigned t = (unsigned)((P + 31) / 32);
-    hipLaunchKernelGGL(k_validate, dim3(t, t), dim3(32, 8), 0, s, sendcounts, recvcounts, sdispls, rdispls, P,
+    const size_t t = (size_t)((P + 31) / 32);
+    const unsigned vgrid = (unsigned)(t * t < (size_t)g.num_cus * 8 ? t * t : (size_t)g.num_cus * 8);
+    hipLaunchKernelGGL(k_validate, dim3(vgrid), dim3(32, 8), 0, s, sendcounts, recvcounts, sdispls, rdispls, P,
                        g.d_status);
     HIPCHK(hipGetLastError());
     HIPCHK(hipMemcpyAsync(g.h_status, g.d_status, 64, hipMemcpyDeviceToHost, s));
@@ -443,6 +444,19 @@ int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node, i
     if (P > 1) pl.phases.resize(1);
     const DataSizes ds = data_sizes_for(pl, g.h_status->max_count, g.h_status->total_chunks, g.opt_fused != 0);
     *bytes = meta_bytes_for(P) + ds.total;
+    return TUNA_OK;
+}
+
+int tuna_plain_copy(const void* src, void* dst, size_t bytes, void* stream) {
+    if (!src || !dst || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return TUNA_ERR_ARG;
+    int rc = ensure_ctx();
+    if (rc != TUNA_OK) return rc;
+    const size_t n = bytes / 16;
+    if (n == 0) return TUNA_OK;
+    if ((n + 255) / 256 > 0x7fffffffull) return TUNA_ERR_TOO_LARGE;
+    hipLaunchKernelGGL(k_plain_copy, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                       (const v4u*)src, (v4u*)dst, n);
+    HIPCHK(hipGetLastError());
     return TUNA_OK;
 }
 

@@ -17,7 +17,10 @@ typedef unsigned int v4u __attribute__((ext_vector_type(4)));   // one 16-byte c
 
 constexpr int kWave = 64;
 constexpr int kCopyThreads = 256;                        // 4 waves, each an independent work unit
-constexpr int kChunksPerLane = 4;
+#ifndef TUNA_CHUNKS_PER_LANE
+#define TUNA_CHUNKS_PER_LANE 4
+#endif
+constexpr int kChunksPerLane = TUNA_CHUNKS_PER_LANE;
 constexpr int kUnitChunks = kWave * kChunksPerLane;      // 256 chunks = 4 KiB per wave unit
 constexpr int kScanThreads = 256;
 constexpr int kScanItems = 4;
@@ -77,11 +80,20 @@ __global__ void k_clear(unsigned int* w, int n) {
 }
 
 // ------------------------------------------------------------------------------------------
+// k_plain_copy: one aligned 16-byte chunk per thread, nothing else.  The practical HBM copy
+// ceiling of the device and the known-size reference that hardware byte counters are scaled by.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_plain_copy(const v4u* __restrict__ src, v4u* __restrict__ dst, size_t n) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+// ------------------------------------------------------------------------------------------
 // k_validate: one pass over the P x P matrices in 32 x 32 tiles.  Finds M (Algorithm "TuNA",
 // line 1: the maximum block size over all ranks, here one device reduction instead of an
 // allreduce), the totals the workspace is sized from, checks counts >= 0 and
 // recvcounts == transpose(sendcounts) through an LDS tile so both matrices are read row-wise.
-// grid (ceil(P/32), ceil(P/32)), block (32, 8).
+// Workgroups of (32, 8) threads stride over the tiles and issue one set of atomics each.
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ sendcounts,
                                                   const int32_t* __restrict__ recvcounts,
@@ -89,42 +101,48 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
                                                   const int64_t* __restrict__ rdispls,
                                                   int P, Status* __restrict__ st) {
     __shared__ int tile[32][33];
-    const int bi = blockIdx.y * 32, bj = blockIdx.x * 32;
+    __shared__ unsigned long long red[4][5];
     const int tx = threadIdx.x, ty = threadIdx.y;
+    const int tpr = (P + 31) / 32;                       // tiles per row
+    const int ntile = tpr * tpr;
     unsigned int flags = 0, abits = 0;
     int mx = 0;
     unsigned long long bytes = 0, chunks = 0, extent = 0;
-    for (int a = ty; a < 32; a += 8) {
-        const int i = bi + a, j = bj + tx;
-        int c = 0;
-        if (i < P && j < P) {
-            c = sendcounts[(size_t)i * P + j];
-            if (c < 0) { flags |= 1u; c = 0; }
-            abits |= (unsigned int)c;
-            if (sdispls) {
-                const int64_t d = sdispls[(size_t)i * P + j];
-                abits |= (unsigned int)d & 15u;
-                if (c > 0 && d >= 0) extent = max(extent, (unsigned long long)d + (unsigned long long)c);
-            }
-            mx = max(mx, c);
-            bytes += (unsigned long long)c;
-            chunks += (unsigned long long)((c + 15) >> 4);
-        }
-        tile[a][tx] = c;
-    }
-    __syncthreads();
-    if (recvcounts) {
+    for (int t = blockIdx.x; t < ntile; t += gridDim.x) {        // a workgroup strides over tiles
+        const int bi = (t / tpr) * 32, bj = (t % tpr) * 32;
         for (int a = ty; a < 32; a += 8) {
-            const int j = bj + a, i = bi + tx;      // recvcounts[j][i] must equal sendcounts[i][j]
+            const int i = bi + a, j = bj + tx;
+            int c = 0;
             if (i < P && j < P) {
-                int rc = recvcounts[(size_t)j * P + i];
-                if (rc < 0) flags |= 1u;
-                else if (rc != tile[tx][a]) flags |= 2u;
-                if (rdispls) abits |= (unsigned int)rdispls[(size_t)j * P + i] & 15u;
+                c = sendcounts[(size_t)i * P + j];
+                if (c < 0) { flags |= 1u; c = 0; }
+                abits |= (unsigned int)c;
+                if (sdispls) {
+                    const int64_t d = sdispls[(size_t)i * P + j];
+                    abits |= (unsigned int)d & 15u;
+                    if (c > 0 && d >= 0) extent = max(extent, (unsigned long long)d + (unsigned long long)c);
+                }
+                mx = max(mx, c);
+                bytes += (unsigned long long)c;
+                chunks += (unsigned long long)((c + 15) >> 4);
+            }
+            tile[a][tx] = c;
+        }
+        __syncthreads();
+        if (recvcounts) {
+            for (int a = ty; a < 32; a += 8) {
+                const int j = bj + a, i = bi + tx;      // recvcounts[j][i] must equal sendcounts[i][j]
+                if (i < P && j < P) {
+                    int rc = recvcounts[(size_t)j * P + i];
+                    if (rc < 0) flags |= 1u;
+                    else if (rc != tile[tx][a]) flags |= 2u;
+                    if (rdispls) abits |= (unsigned int)rdispls[(size_t)j * P + i] & 15u;
+                }
             }
         }
+        __syncthreads();
     }
-    // wave reduction, then one atomic per wave
+    // wave reduction, workgroup reduction through LDS, then one set of atomics per workgroup
 #pragma unroll
     for (int d = kWave / 2; d > 0; d >>= 1) {
         flags |= __shfl_xor(flags, d, kWave);
@@ -134,13 +152,24 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
         chunks += __shfl_xor(chunks, d, kWave);
         extent = max(extent, (unsigned long long)__shfl_xor(extent, d, kWave));
     }
-    if (((ty * 32 + tx) & (kWave - 1)) == 0) {
-        if (flags) atomicOr(&st->flags, flags);
-        if (abits & 15u) atomicOr(&st->align_bits, abits & 15u);
-        if (mx) atomicMax(&st->max_count, mx);
-        if (bytes) atomicAdd(&st->total_bytes, bytes);
-        if (chunks) atomicAdd(&st->total_chunks, chunks);
-        if (extent) atomicMax(&st->send_extent, extent);
+    const int lin = ty * 32 + tx;
+    if ((lin & (kWave - 1)) == 0) {
+        unsigned long long* r = red[lin / kWave];
+        r[0] = ((unsigned long long)flags << 32) | (abits & 15u);
+        r[1] = (unsigned long long)mx; r[2] = bytes; r[3] = chunks; r[4] = extent;
+    }
+    __syncthreads();
+    if (lin == 0) {
+        unsigned long long fa = 0, m = 0, by = 0, ch = 0, ex = 0;
+        for (int w = 0; w < 4; ++w) {
+            fa |= red[w][0]; m = max(m, red[w][1]); by += red[w][2]; ch += red[w][3]; ex = max(ex, red[w][4]);
+        }
+        if (fa >> 32) atomicOr(&st->flags, (unsigned int)(fa >> 32));
+        if (fa & 15u) atomicOr(&st->align_bits, (unsigned int)(fa & 15u));
+        if (m) atomicMax(&st->max_count, (int)m);
+        if (by) atomicAdd(&st->total_bytes, by);
+        if (ch) atomicAdd(&st->total_chunks, ch);
+        if (ex) atomicMax(&st->send_extent, ex);
     }
 }
 

@@ -269,3 +269,13 @@ def test_side_stream(tuna):
     assert rc == 0
     s.synchronize()
     prob.check("side stream")
+
+
+def test_plain_copy(tuna):
+    n = (1 << 20) + 48
+    src = torch.from_numpy(wl.payload_position_hash(21, n)).to("cuda:0")
+    dst = torch.zeros(n, dtype=torch.uint8, device="cuda:0")
+    assert tuna.tuna_plain_copy(src, dst, n - 16) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:n - 16], src[:n - 16]) and int(dst[n - 16:].sum()) == 0
+    assert tuna.tuna_plain_copy(src, dst, 24) == tuna.TUNA_ERR_ARG
