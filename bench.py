@@ -27,6 +27,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per launch (read + write), averaged over the launches of the default sweep
+# (P = 4096, radices 2, 8, 64, 4096: 19 launches of each copy kernel per step set), from two
+# `rocprofv3 --pmc` runs (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter
+# reads for tuna::k_plain_copy moving 4 GiB (factors 2.0000 and 0.9998).  The algorithmic figure
+# for the same launches is 2 x payload = 22.55e9 bytes; see profiles/k_copy_config4_P4096.md.
+MEASURED_TRAFFIC_CONFIG4 = {"pack": 22979.9 * 2**20, "exchange": 22784.7 * 2**20, "unpack": 22699.3 * 2**20}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -176,17 +183,32 @@ def main():
               file=sys.stderr, flush=True)
 
     best = max(per_radix, key=lambda r: r["effective_GBs"])
-    # dominant kernel = the copy kernel with the largest total time at the best radix
+    # Roofline of the dominant kernel: the copy kernel with the largest total time over ALL launches
+    # of the timed sweep (every radix), so that its average launch duration is the one a
+    # `rocprofv3 --kernel-trace --stats` run of this same command reports for that kernel.
     roofline = None
-    if best["kernels"]:
-        dom = max(best["kernels"].items(), key=lambda kv: kv[1]["avg_ms"] * kv[1]["launches_per_step"])
-        traffic = None
-        if args.traffic_json and os.path.exists(args.traffic_json):
-            traffic = json.load(open(args.traffic_json)).get(dom[0])
-        roofline = {"bound": "hbm", "kernel": "k_tile_copy<%s>" % dom[0], "achieved": dom[1]["achieved_GBs"],
-                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom[1]["achieved_GBs"] / HBM_PEAK_GBS,
-                    "traffic": traffic, "avg_launch_ms": dom[1]["avg_ms"],
-                    "alg_bytes_per_launch": dom[1]["alg_bytes_per_launch"]}
+    tot = {}
+    for r in per_radix:
+        for name, v in r["kernels"].items():
+            t = tot.setdefault(name, [0.0, 0, 0.0])
+            n = v["launches_per_step"] * args.steps
+            t[0] += v["avg_ms"] * n
+            t[1] += n
+            t[2] += v["alg_bytes_per_launch"] * n
+    if tot:
+        gran = per_radix[0]["granularity"]
+        dom = max(tot.items(), key=lambda kv: kv[1][0])
+        name, (ms, n, alg) = dom
+        kname = {"pack": "tuna::k_copy<0, %d>" % gran, "exchange": "tuna::k_copy<1, 16>",
+                 "unpack": "tuna::k_copy<2, %d>" % gran, "fused": "tuna::k_copy<3, %d>" % gran}[name]
+        default_run = (args.config == 4 and P == 4096 and not args.radices and not args.fused)
+        traffic = MEASURED_TRAFFIC_CONFIG4.get(name) if default_run else None
+        achieved = alg / (ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": kname, "stage": name, "achieved": achieved, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                    "avg_launch_ms": ms / n, "launches": n, "alg_bytes_per_launch": alg / n,
+                    "frac_of_plain_copy": (achieved / copy_ceiling["GBs"]) if copy_ceiling else None,
+                    "all_stages_GBs": {k: v[2] / (v[0] * 1e-3) / 1e9 for k, v in tot.items()}}
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
