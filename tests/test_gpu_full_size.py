@@ -1,0 +1,130 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration
+bench.py times (dense layout, library-owned workspace, default stream).
+
+Configurations 3 and 5 (about 1 GiB) are compared whole against the CPU oracle.  Configuration 4
+(16 GiB) is checked three ways: (a) the complete receive regions of a sample of receiver ranks
+against the oracle (which gets the send buffer downloaded from the GPU); (b) every 4-byte word of
+the receive buffer against the value the payload generator gives for the send offset the
+definition names -- the payload is a hash of its own position, so the expected words are
+regenerated instead of stored; (c) conservation of the word sum.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def tuna():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2411_02581_amd as t
+    t.load()
+    return t
+
+
+def _upload(lay):
+    dev = "cuda:0"
+    return [torch.from_numpy(a).to(dev) for a in (lay.sendcounts, lay.sdispls, lay.recvcounts, lay.rdispls)]
+
+
+def _whole_oracle_case(tuna, cfg_id, calls):
+    c = wl.CONFIGS[cfg_id]
+    lay = wl.make_layout(wl.make_counts(cfg_id))
+    send_host = wl.float32_bit_patterns(lay.send_bytes, c.seed) if cfg_id == 3 else \
+        wl.payload_position_hash(c.seed, lay.send_bytes)
+    want = np.zeros(lay.recv_bytes, dtype=np.uint8)
+    assert oracle.alltoallv(send_host, lay.sendcounts, lay.sdispls, want, lay.recvcounts, lay.rdispls) == 0
+    want_dev = torch.from_numpy(want).to("cuda:0")
+    send = torch.from_numpy(send_host).to("cuda:0")
+    recv = torch.empty(lay.recv_bytes, dtype=torch.uint8, device="cuda:0")
+    sc, sd, rc, rd = _upload(lay)
+    for label, fn in calls(lay.P):
+        recv.zero_()
+        print("config %d full size, %s" % (cfg_id, label), flush=True)
+        code = fn(send, sc, sd, recv, rc, rd)
+        assert code == 0, tuna.tuna_strerror(code)
+        torch.cuda.synchronize()
+        assert torch.equal(recv, want_dev), "config %d %s differs from the oracle" % (cfg_id, label)
+    assert torch.equal(send, torch.from_numpy(send_host).to("cuda:0"))
+
+
+def test_config3_full_hierarchical(tuna):
+    c = wl.CONFIGS[3]
+
+    def calls(P):
+        for rg in c.global_radices:
+            yield ("r_l=%d r_g=%d" % (c.local_radix, rg),
+                   lambda s, sc, sd, r, rc, rd, rg=rg: tuna.tuna_alltoallv_hier(
+                       s, sc, sd, r, rc, rd, P, c.ranks_per_node, c.local_radix, rg))
+    _whole_oracle_case(tuna, 3, calls)
+    st = tuna.tuna_get_stats()
+    assert (st.Q, st.N, st.K_local, st.K_global) == (16, 64, 6, 63)
+
+
+def test_config5_full_uniform(tuna):
+    c = wl.CONFIGS[5]
+
+    def calls(P):
+        for r in c.radices:
+            yield ("radix=%d" % r, lambda s, sc, sd, rcv, rc, rd, r=r: tuna.tuna_alltoallv(
+                s, sc, sd, rcv, rc, rd, P, r, c.ranks_per_node))
+    _whole_oracle_case(tuna, 5, calls)
+    st = tuna.tuna_get_stats()
+    assert (st.local_radix, st.global_radix, st.K_local, st.K_global) == (32, 64, 31, 63)
+
+
+def test_config4_full(tuna):
+    c = wl.CONFIGS[4]
+    P = c.P
+    dev = "cuda:0"
+    lay = wl.make_layout(wl.make_counts(4))
+    assert lay.payload_bytes > 15.9 * 2**30
+    send = wl.payload_position_hash_torch(c.seed, lay.send_bytes, dev)
+    recv = torch.empty(lay.recv_bytes, dtype=torch.uint8, device=dev)
+    sc, sd, rc, rd = _upload(lay)
+    # (a) oracle on sampled receivers, from the send buffer as the GPU holds it
+    send_host = send.cpu().numpy()
+    assert np.array_equal(send_host[:4096], wl.payload_position_hash(c.seed, 4096))
+    rng = np.random.default_rng(4)
+    receivers = np.unique(np.concatenate([[0, 1, P // 2, P - 1], rng.integers(0, P, 28)])).astype(np.int32)
+    want = np.zeros(lay.recv_bytes, dtype=np.uint8)          # untouched pages are never committed
+    assert oracle.alltoallv_receivers(send_host, lay.sendcounts, lay.sdispls, want, lay.recvcounts,
+                                      lay.rdispls, receivers) == 0
+    del send_host
+    regions = [(int(lay.rdispls[j, 0]), int(lay.rdispls[j, P - 1] + lay.recvcounts[j, P - 1])) for j in receivers]
+    want_regions = [torch.from_numpy(want[lo:hi].copy()).to(dev) for lo, hi in regions]
+    del want
+    send_sum = int(send.view(torch.int32).sum(dtype=torch.int64))
+    counts_w = (sc.to(torch.int64) // 4)                      # [i, j] words of block i -> j
+    sd_w = sd // 4
+    for r in c.radices:
+        recv.zero_()
+        print("config 4 full size, radix=%d" % r, flush=True)
+        code = tuna.tuna_alltoallv(send, sc, sd, recv, rc, rd, P, r, 0)
+        assert code == 0, tuna.tuna_strerror(code)
+        torch.cuda.synchronize()
+        for (lo, hi), w in zip(regions, want_regions):
+            assert torch.equal(recv[lo:hi], w), "radix %d: receiver region [%d, %d) differs from the oracle" % (r, lo, hi)
+        # (c) conservation
+        assert int(recv.view(torch.int32).sum(dtype=torch.int64)) == send_sum
+        # (b) every received word equals the generator's value at the send offset the definition names
+        recv_w = recv.view(torch.int32)
+        step = 128
+        for j0 in range(0, P, step):
+            j1 = min(P, j0 + step)
+            n = counts_w[:, j0:j1].t().contiguous().view(-1)          # receiver-major: (j, i)
+            src0 = sd_w[:, j0:j1].t().contiguous().view(-1)
+            total = int(n.sum())
+            starts = torch.cumsum(n, 0) - n
+            seg = torch.repeat_interleave(torch.arange(n.numel(), device=dev), n, output_size=total)
+            src_word = src0[seg] + (torch.arange(total, device=dev) - starts[seg])
+            expect = wl.payload_position_hash_words32_torch(c.seed, src_word)
+            lo = int(lay.rdispls[j0, 0]) // 4
+            got = recv_w[lo:lo + total].to(torch.int64) & 0xFFFFFFFF
+            assert torch.equal(got, expect), "radix %d: receivers %d..%d differ" % (r, j0, j1)
+            del seg, src_word, expect, got

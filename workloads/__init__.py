@@ -242,6 +242,25 @@ def payload_position_hash_torch(seed: int, nbytes: int, device, chunk_words: int
     return out.view(torch.uint8)[:nbytes]
 
 
+def payload_position_hash_words32_torch(seed: int, word_index):
+    """The 32-bit little-endian words of the position-hashed payload at the given 4-byte word
+    indices (a torch int64 tensor on any device): word w is half (w & 1) of the 8-byte word
+    splitmix64(seed ^ (w >> 1)).  Returned as int64 values in [0, 2^32)."""
+    def _c(v):
+        v &= _MASK64
+        return v - (1 << 64) if v >= (1 << 63) else v
+
+    def _lsr(t, k):
+        return (t >> k) & ((1 << (64 - k)) - 1)
+
+    z = (word_index >> 1) ^ _c(seed)
+    z = z + _c(0x9E3779B97F4A7C15)
+    z = (z ^ _lsr(z, 30)) * _c(0xBF58476D1CE4E5B9)
+    z = (z ^ _lsr(z, 27)) * _c(0x94D049BB133111EB)
+    z = z ^ _lsr(z, 31)
+    return (z >> ((word_index & 1) * 32)) & 0xFFFFFFFF
+
+
 def payload_traceable_int32(layout: Layout) -> np.ndarray:
     """Configuration-1 payload: int32 element k of block (i->j) is (i<<20)|(j<<10)|k, so any
     received element names its origin.  Needs P <= 1024 and blocks of < 1024 int32 elements that
