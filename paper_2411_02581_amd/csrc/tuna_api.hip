@@ -39,7 +39,7 @@ struct Ctx {
     void* meta = nullptr;  size_t meta_bytes = 0;   // library-owned, grow-only
     void* data = nullptr;  size_t data_bytes = 0;
     void* user_ws = nullptr; size_t user_ws_bytes = 0;
-    std::map<std::tuple<int, int, int, int>, DevicePlan> plans;
+    std::map<std::tuple<int, int, int, int, int>, DevicePlan> plans;
     tuna_stats_t stats;
     bool have_stats = false;
     int opt_profile = 0, opt_fused = 0;
@@ -139,13 +139,13 @@ DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long tot
     d.slots = pl.slots;
     d.slot_bytes = (M + 127) / 128 * 128;     // whole 128-byte lines per slot
     d.t_bytes = any_phase ? (size_t)pl.P * (size_t)d.slots * (size_t)d.slot_bytes : 0;
-    const size_t tcopies = fused ? 2 : 1;
+    // pl.slots already counts both copies of T when the plan is a fused one
     d.total = 2 * align_up(d.unit_cap * sizeof(int4)) + (fused ? 0 : 2 * align_up(d.stage_chunks * 16)) +
-              tcopies * align_up(d.t_bytes);
+              align_up(d.t_bytes);
     return d;
 }
 
-int get_plan(int P, int Q, int rl, int rg, DevicePlan** out) {
+int get_plan(int P, int Q, int rl, int rg, bool fused, DevicePlan** out) {
     PlanHost probe;   // clamp radices the same way make_plan does
     const int N = P / Q;
     int crl = rl < 2 ? 2 : rl, crg = rg < 2 ? 2 : rg;
@@ -153,11 +153,11 @@ int get_plan(int P, int Q, int rl, int rg, DevicePlan** out) {
     if (N >= 2 && crg > N) crg = N;
     if (Q < 2) crl = 2;
     if (N < 2) crg = 2;
-    auto key = std::make_tuple(P, Q, crl, crg);
+    auto key = std::make_tuple(P, Q, crl, crg, fused ? 1 : 0);
     auto it = g.plans.find(key);
     if (it == g.plans.end()) {
         DevicePlan dp;
-        dp.host = make_plan(P, Q, crl, crg);
+        dp.host = make_plan(P, Q, crl, crg, fused);
         if ((int)dp.host.phases.size() > TUNA_MAX_PHASES) return TUNA_ERR_TOO_LARGE;
         for (auto& ph : dp.host.phases) {
             SegInfo* ds = nullptr;
@@ -274,7 +274,8 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
     const int N = P / Q;
 
     DevicePlan* dp = nullptr;
-    rc = get_plan(P, Q, rl, rg, &dp);
+    const bool fused = g.opt_fused != 0;
+    rc = get_plan(P, Q, rl, rg, fused, &dp);
     if (rc != TUNA_OK) return rc;
     const PlanHost& pl = dp->host;
 
@@ -287,7 +288,7 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
     st.w_local = pl.w_l; st.w_global = pl.w_g; st.K_local = pl.K_l; st.K_global = pl.K_g;
     st.B_local = pl.B_l; st.B_global = pl.B_g; st.n_phases = (int)pl.phases.size();
     st.temp_slots_per_rank = pl.slots;
-    st.fused = 0;
+    st.fused = fused ? 1 : 0;
     mark(s, -1, -1);
 
     // ---- prepare: validation, M, totals (one read-back) ---------------------------------------
@@ -309,7 +310,7 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
 
     // ---- workspace ---------------------------------------------------------------------------
     const size_t mbytes = meta_bytes_for(P);
-    const DataSizes ds = data_sizes_for(pl, hs.max_count, hs.total_chunks, false);
+    const DataSizes ds = data_sizes_for(pl, hs.max_count, hs.total_chunks, fused);
     void *mbase, *dbase;
     if (g.user_ws) {
         if (mbytes + ds.total > g.user_ws_bytes) return TUNA_ERR_WORKSPACE_TOO_SMALL;
@@ -328,12 +329,12 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
     Carver cd(dbase, ds.total);
     mb.Ls.units = cd.take<int4>(ds.unit_cap);
     mb.Lr.units = cd.take<int4>(ds.unit_cap);
-    v4u* stage_s = cd.take<v4u>(ds.stage_chunks);
-    v4u* stage_r = cd.take<v4u>(ds.stage_chunks);
+    v4u* stage_s = cd.take<v4u>(fused ? 0 : ds.stage_chunks);
+    v4u* stage_r = cd.take<v4u>(fused ? 0 : ds.stage_chunks);
     unsigned char* T = cd.take<unsigned char>(ds.t_bytes);
     if (!cm.ok || !cd.ok) return TUNA_ERR_WORKSPACE_TOO_SMALL;
     st.temp_bytes = (int64_t)ds.t_bytes;
-    st.staging_bytes = (int64_t)(2 * ds.stage_chunks * 16);
+    st.staging_bytes = fused ? 0 : (int64_t)(2 * ds.stage_chunks * 16);
     st.workspace_bytes = (int64_t)(mbytes + ds.total);
 
     // ---- initial rotation (index only) and the own block ----------------------------------------
@@ -363,20 +364,36 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
         hipLaunchKernelGGL(k_meta_exchange, dim3(gP2), dim3(256), 0, s, cur, nxt, dp->d_zt[i], P, Q, N, ph.dim,
                            (int)ph.rx);
         HIPCHK(hipGetLastError());
-        rc = build_layout(cur, seg, ph.nseg, P, mb.Ls, &g.d_status->phase_bytes[i], &g.d_status->phase_chunks[i], s);
-        if (rc != TUNA_OK) return rc;
-        rc = build_layout(nxt, seg, ph.nseg, P, mb.Lr, nullptr, nullptr, s);
-        if (rc != TUNA_OK) return rc;
+        if (fused) {   // only the receive-side layout is needed
+            rc = build_layout(nxt, seg, ph.nseg, P, mb.Lr, &g.d_status->phase_bytes[i], &g.d_status->phase_chunks[i], s);
+            if (rc != TUNA_OK) return rc;
+        } else {
+            rc = build_layout(cur, seg, ph.nseg, P, mb.Ls, &g.d_status->phase_bytes[i], &g.d_status->phase_chunks[i], s);
+            if (rc != TUNA_OK) return rc;
+            rc = build_layout(nxt, seg, ph.nseg, P, mb.Lr, nullptr, nullptr, s);
+            if (rc != TUNA_OK) return rc;
+        }
         mark(s, kCatMeta, (int)i);
 
         CopyArgs a{};
         a.seg = seg; a.nseg = ph.nseg;
         a.T = T; a.slots = ds.slots; a.slot_bytes = ds.slot_bytes;
         a.P = P; a.Q = Q; a.N = N; a.dim = ph.dim; a.rx = (int)ph.rx;
+        a.user_limit = (unsigned long long)(uintptr_t)sendbuf + hs.send_extent;
+        if (fused) {
+            // one hop in one kernel: S / T of the sender -> R / the other copy of T at the receiver
+            a.stage = nullptr; a.L = mb.Lr; a.sizes = nxt;
+            a.user = (unsigned char*)sendbuf; a.displs = sdispls;
+            a.user2 = (unsigned char*)recvbuf; a.displs2 = rdispls; a.T2 = T;
+            rc = launch_copy<kFused>(gran, ds.unit_cap, a, s);
+            if (rc != TUNA_OK) return rc;
+            mark(s, kCatPack, (int)i);
+            std::swap(cur, nxt);
+            continue;
+        }
         // pack: S / T -> send staging
         a.stage = stage_s; a.L = mb.Ls; a.sizes = cur;
         a.user = (unsigned char*)sendbuf; a.displs = sdispls;
-        a.user_limit = (unsigned long long)(uintptr_t)sendbuf + hs.send_extent;
         rc = launch_copy<kPack>(gran, ds.unit_cap, a, s);
         if (rc != TUNA_OK) return rc;
         mark(s, kCatPack, (int)i);
@@ -440,7 +457,7 @@ int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node, i
     pl.P = P; pl.Q = Q; pl.N = N;
     const int Kl = Q > 1 ? num_rounds(Q, rl) : 0, Kg = N > 1 ? num_rounds(N, rg) : 0;
     const int Bl = Q > 1 ? Q - 1 - Kl : 0, Bg = N > 1 ? N - 1 - Kg : 0;
-    pl.slots = (int64_t)Bl + (int64_t)(N - 1) * (Q - 1) + (int64_t)Bg * Q;
+    pl.slots = ((int64_t)Bl + (int64_t)(N - 1) * (Q - 1) + (int64_t)Bg * Q) * (g.opt_fused ? 2 : 1);
     if (P > 1) pl.phases.resize(1);
     const DataSizes ds = data_sizes_for(pl, g.h_status->max_count, g.h_status->total_chunks, g.opt_fused != 0);
     *bytes = meta_bytes_for(P) + ds.total;
@@ -529,7 +546,7 @@ int tuna_plan_info(int P, int ranks_per_node, int local_radix, int global_radix,
     int Q = 0;
     int rc = resolve_hierarchy(P, ranks_per_node, &Q);
     if (rc != TUNA_OK) return rc;
-    const PlanHost pl = make_plan(P, Q, local_radix, global_radix);
+    const PlanHost pl = make_plan(P, Q, local_radix, global_radix, g.opt_fused != 0);
     out->P = P; out->Q = Q; out->N = pl.N;
     out->local_radix = pl.rl; out->global_radix = pl.rg;
     out->w_local = pl.w_l; out->w_global = pl.w_g;
@@ -547,7 +564,7 @@ int tuna_plan_phase(int P, int ranks_per_node, int local_radix, int global_radix
     int Q = 0;
     int rc = resolve_hierarchy(P, ranks_per_node, &Q);
     if (rc != TUNA_OK) return rc;
-    const PlanHost pl = make_plan(P, Q, local_radix, global_radix);
+    const PlanHost pl = make_plan(P, Q, local_radix, global_radix, g.opt_fused != 0);
     if (phase >= (int)pl.phases.size()) return TUNA_ERR_ARG;
     const PhaseHost& ph = pl.phases[phase];
     header[0] = ph.dim; header[1] = ph.x; header[2] = ph.r; header[3] = ph.nz; header[4] = ph.nseg;

@@ -375,7 +375,8 @@ __global__ void __launch_bounds__(256) k_layout_units(int nseg, LayoutDev L) {
 //   pack     staging(send)  <- S at sdispls, or T slot      (Algorithm "TuNA", line 15, sender side)
 //   exchange staging(recv)  <- staging(send) of the partner (the point-to-point transfer itself)
 //   unpack   staging(recv)  -> R at rdispls, or T slot      (Algorithm "TuNA", lines 16-20)
-//   fused    S / T of the sender -> R / T' of the receiver  (all three in one hop, no staging)
+//   fused    S / T of the sender -> R / other copy of T at the receiver, tiled over the receiver's
+//            layout (all three in one hop, no staging)
 // Work unit = one wavefront x 256 consecutive 16-byte chunks (4 KiB) of one rank's staging
 // region.  The wave is self-contained -- no workgroup barrier anywhere: lane i loads the chunk
 // prefix and the table entry of segment s0 + i, the lanes whose segment overlaps the unit
@@ -522,7 +523,7 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy(const CopyArgs a) {
                 // must end exactly with the block; a load from S may run into the bytes that
                 // follow the block as long as it stays inside the part of S that holds blocks.
                 size = (pre_n - pre_i) << 4;
-                if (MODE == kPack || MODE == kFused) {
+                if (MODE == kPack) {
                     addr = block_address(sa.z, false, p, n, g, sb.x, sb.y, a.P, a.Q, a.N, a.user, a.displs, a.T,
                                          a.slots, a.slot_bytes);
                     if (sa.z < 0) size = (int)min((unsigned long long)size, a.user_limit - addr);
@@ -533,13 +534,18 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy(const CopyArgs a) {
                     if (sa.w < 0) size = a.sizes[(size_t)p * a.P + sa.x];
                     else size |= 1 << 30;             // T-bound: the tail lane completes the 128-byte line
                 }
-                if (MODE == kFused) {                    // the receiver: distance z*r^x downwards
-                    int qn = n, qg = g;
+                if (MODE == kFused) {
+                    // tiled over the RECEIVER's layout: its stores into R are consecutive; the loads
+                    // gather from the sender at distance z*r^x upwards (S or its T slot)
+                    int sn = n, sg = g;
                     const int dist = sa.y * a.rx;
-                    if (a.dim == 0) { qg -= dist; if (qg < 0) qg += a.Q; }
-                    else { qn -= dist; if (qn < 0) qn += a.N; }
-                    addr2 = block_address(sa.w, true, qn * a.Q + qg, qn, qg, sb.x, sb.y, a.P, a.Q, a.N, a.user2,
-                                          a.displs2, a.T2, a.slots, a.slot_bytes);
+                    if (a.dim == 0) { sg += dist; if (sg >= a.Q) sg -= a.Q; }
+                    else { sn += dist; if (sn >= a.N) sn -= a.N; }
+                    addr = block_address(sa.z, false, sn * a.Q + sg, sn, sg, sb.x, sb.y, a.P, a.Q, a.N, a.user,
+                                         a.displs, a.T, a.slots, a.slot_bytes);
+                    if (sa.z < 0) size = (int)min((unsigned long long)size, a.user_limit - addr);
+                    addr2 = block_address(sa.w, true, p, n, g, sb.x, sb.y, a.P, a.Q, a.N, a.user2, a.displs2,
+                                          a.T2, a.slots, a.slot_bytes);
                     if (sa.w < 0) size = min(size, a.sizes[(size_t)p * a.P + sa.x]);
                     else size |= 1 << 30;
                 }

@@ -40,7 +40,8 @@ struct PhaseHost {
 struct PlanHost {
     int P = 0, Q = 0, N = 0, rl = 0, rg = 0;
     int w_l = 0, w_g = 0, K_l = 0, K_g = 0, B_l = 0, B_g = 0;
-    int64_t slots = 0;             // T slots per rank
+    int64_t slots = 0;             // T slots per rank (fused: both copies)
+    bool fused = false;
     int64_t blocks_sent = 0;       // per rank, all phases
     std::vector<PhaseHost> phases;
 };
@@ -79,7 +80,11 @@ inline int64_t t_index(int64_t o, int64_t r) {
     return o - 1 - dx * (r - 1) - dz;
 }
 
-inline PlanHost make_plan(int P, int Q, int rl, int rg) {
+// fused = true lays T out twice: a phase then reads every block it forwards from one copy and
+// stores every block it receives into the other, so that one kernel can do both at once.  The
+// copy a block sits in is the parity of the number of hops it has made, which depends on its
+// index only -- it is folded into the slot numbers of the tables.
+inline PlanHost make_plan(int P, int Q, int rl, int rg, bool fused = false) {
     PlanHost pl;
     pl.P = P; pl.Q = Q; pl.N = P / Q;
     const int N = pl.N;
@@ -97,7 +102,18 @@ inline PlanHost make_plan(int P, int Q, int rl, int rg) {
     // for the global phase); then B_g super-slots of Q blocks for the global phase (map t over j).
     const int64_t foreign0 = pl.B_l;
     const int64_t global0 = foreign0 + (int64_t)(N - 1) * (Q - 1);
-    pl.slots = global0 + (int64_t)pl.B_g * Q;
+    const int64_t slots1 = global0 + (int64_t)pl.B_g * Q;
+    pl.slots = fused ? 2 * slots1 : slots1;
+    pl.fused = fused;
+    // hops a block with distance pair (j, l) has made before phase (dim, x): non-zero digits of l
+    // below x (all of l's digits once the global phases run) plus non-zero digits of j below x
+    auto hops_before = [&](int dim, int64_t rx, int j, int l) -> int {
+        int h = 0;
+        int64_t v = dim == 0 ? l % rx : l;
+        for (; v; v /= rl) h += (v % rl) != 0;
+        if (dim == 1) for (v = j % rx; v; v /= rg) h += (v % rg) != 0;
+        return h;
+    };
     auto local_slot = [&](int j, int l) -> int32_t {
         if (j == 0) return (int32_t)t_index(l, rl);
         return (int32_t)(foreign0 + (int64_t)(j - 1) * (Q - 1) + (l - 1));
@@ -142,6 +158,11 @@ inline PlanHost make_plan(int P, int Q, int rl, int rg) {
                         if (j % rx == 0) s.src_slot = (l == 0) ? -1 : local_slot(j, l);
                         else             s.src_slot = global_slot(j, l);
                         s.dst_slot = (j < rx1) ? -1 : global_slot(j, l);
+                    }
+                    if (fused) {
+                        const int h = hops_before(dim, rx, j, l);
+                        if (s.src_slot >= 0) s.src_slot += (int32_t)((h & 1) * slots1);
+                        if (s.dst_slot >= 0) s.dst_slot += (int32_t)(((h + 1) & 1) * slots1);
                     }
                     ph.seg[first[z]++] = s;
                 }

@@ -22,6 +22,15 @@ def tuna():
     return t
 
 
+@pytest.fixture(autouse=True, params=["staged", "fused"])
+def mode(request, tuna):
+    """Every case runs with the three-stage phases (pack, exchange, unpack) and with the fused
+    single-kernel phases."""
+    tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 1 if request.param == "fused" else 0)
+    yield request.param
+    tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+
+
 class Problem:
     """One alltoallv problem resident on the GPU, with the oracle's expected receive buffer."""
 
@@ -71,11 +80,12 @@ def run_hier(tuna, prob, Q, rl, rg):
     prob.check("P=%d Q=%d rl=%d rg=%d" % (prob.lay.P, Q, rl, rg))
 
 
-def test_config1_traceable_payload(tuna):
+def test_config1_traceable_payload(tuna, mode):
     lay = wl.make_layout(wl.make_counts(1), gap=16)
     prob = Problem(lay, wl.payload_traceable_int32(lay))
     run_flat(tuna, prob, 2)
     st = tuna.tuna_get_stats()
+    assert st.fused == (1 if mode == "fused" else 0)
     assert (st.P, st.w_local, st.K_local, st.B_local) == (16, 4, 4, 11)
     assert st.total_payload_bytes == lay.payload_bytes and st.max_block_bytes == lay.sendcounts.max()
     assert st.granularity == 4

@@ -92,7 +92,7 @@ def test_argument_errors_without_a_gpu():
 
 
 # ---- replay of the segment tables on the host -------------------------------------------------
-def _replay(counts, Q, rl, rg):
+def _replay(counts, Q, rl, rg, fused=False):
     """Moves blocks exactly as the tables say: per phase, every rank reads each moving block from
     the send buffer (source slot -1) or its T slot, the partner at distance z*r^x (downwards, as
     in Algorithm "TuNA") stores it to the receive buffer (destination slot -1) or its T slot."""
@@ -118,6 +118,7 @@ def _replay(counts, Q, rl, rg):
         assert set(int(s[3]) for s in seg) == set(range(1, nz + 1))
         moved = []
         nbytes = 0
+        reads = [set() for _ in range(P)]
         for p in range(P):
             n, g = divmod(p, Q)
             for e, j, l, z, src_slot, dst_slot in seg.tolist():
@@ -127,6 +128,7 @@ def _replay(counts, Q, rl, rg):
                     blk = S[p][((n - j) % N) * Q + (g - l) % Q]
                 else:
                     blk = T[p].pop(src_slot)          # a slot is read exactly once after a store
+                    reads[p].add(src_slot)
                 if dim == 0:
                     q = n * Q + (g - z * rx) % Q
                 else:
@@ -142,6 +144,8 @@ def _replay(counts, Q, rl, rg):
             else:
                 assert 0 <= dst_slot < info.temp_slots_per_rank
                 assert dst_slot not in T[q]           # no live block is overwritten
+                if fused:                             # one kernel reads and writes: never the same slot
+                    assert dst_slot not in reads[q]
                 T[q][dst_slot] = blk
         per_phase_bytes.append(nbytes)
     assert all(len(t) == 0 for t in T)                # nothing is left behind in T
@@ -185,3 +189,25 @@ def test_phase_bytes_follow_the_model():
     wlc = tm.num_digits(Q, rl)
     assert per_phase[:wlc] == [st["local_phase_bytes"][x] for x in range(wlc)]
     assert per_phase[wlc:] == [st["global_phase_bytes"][x] for x in range(tm.num_digits(N, rg))]
+
+
+@pytest.mark.parametrize("Q,N", [(9, 1), (16, 1), (27, 1), (2, 3), (4, 4), (5, 3), (3, 7), (4, 9)])
+def test_fused_tables_never_read_and_write_a_slot_in_one_phase(Q, N):
+    """With the fused rounds T is laid out twice and the copy is the parity of the hop count:
+    within a phase no rank's slot is both read (forwarded block) and written (arriving block)."""
+    P = Q * N
+    counts = (wl.make_counts(2, P) % 6).astype(np.int32)
+    assert tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 1) == 0
+    try:
+        for rl in sorted({2, 3, max(Q, 2)}):
+            for rg in sorted({2, 3, max(N, 2)}):
+                rc, fused_info = tuna.tuna_plan_info(P, Q, rl, rg)
+                R, S, _ = _replay(counts, Q, rl, rg, fused=True)
+                assert R == _want(S), (Q, N, rl, rg)
+    finally:
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+    rc, plain = tuna.tuna_plan_info(P, Q, 2, 2)
+    tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 1)
+    rc, fused_info = tuna.tuna_plan_info(P, Q, 2, 2)
+    tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+    assert fused_info.temp_slots_per_rank == 2 * plain.temp_slots_per_rank
