@@ -135,7 +135,9 @@ DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long tot
     DataSizes d{};
     const bool any_phase = !pl.phases.empty() && total_chunks > 0;
     d.stage_chunks = any_phase ? (size_t)total_chunks : 0;
-    d.unit_cap = any_phase ? (size_t)(total_chunks / kUnitChunks) + pl.P + 1 : 0;
+    // fused rounds cut chunks at destination lines: up to one more chunk per moving block
+    const size_t head_chunks = fused ? (size_t)pl.P * pl.P : 0;
+    d.unit_cap = any_phase ? (size_t)((total_chunks + head_chunks) / kUnitChunks) + pl.P + 1 : 0;
     d.slots = pl.slots;
     d.slot_bytes = (M + 127) / 128 * 128;     // whole 128-byte lines per slot
     d.t_bytes = any_phase ? (size_t)pl.P * (size_t)d.slots * (size_t)d.slot_bytes : 0;
@@ -224,9 +226,11 @@ int launch_copy(int gran, size_t unit_cap, const CopyArgs& a, hipStream_t s) {
     return TUNA_OK;
 }
 
-int build_layout(const int32_t* sizes, const SegInfo* seg, int nseg, int P, const LayoutDev& L,
-                 unsigned long long* phase_bytes, unsigned long long* phase_chunks, hipStream_t s) {
-    hipLaunchKernelGGL(k_layout_scan, dim3(P), dim3(kScanThreads), 0, s, sizes, seg, nseg, P, L, phase_bytes);
+int build_layout(const int32_t* sizes, const SegInfo* seg, int nseg, int P, int Q, int N, const LayoutDev& L,
+                 unsigned long long* phase_bytes, unsigned long long* phase_chunks,
+                 const int64_t* head_displs, unsigned int head_base, hipStream_t s) {
+    hipLaunchKernelGGL(k_layout_scan, dim3(P), dim3(kScanThreads), 0, s, sizes, seg, nseg, P, L, phase_bytes,
+                       head_displs, head_base, Q, N);
     HIPCHK(hipGetLastError());
     hipLaunchKernelGGL(k_layout_base, dim3(1), dim3(1024), 0, s, P, L, phase_chunks);
     HIPCHK(hipGetLastError());
@@ -365,12 +369,14 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
                            (int)ph.rx);
         HIPCHK(hipGetLastError());
         if (fused) {   // only the receive-side layout is needed
-            rc = build_layout(nxt, seg, ph.nseg, P, mb.Lr, &g.d_status->phase_bytes[i], &g.d_status->phase_chunks[i], s);
+            rc = build_layout(nxt, seg, ph.nseg, P, Q, N, mb.Lr, &g.d_status->phase_bytes[i],
+                              &g.d_status->phase_chunks[i], rdispls, (unsigned int)((uintptr_t)recvbuf & 15u), s);
             if (rc != TUNA_OK) return rc;
         } else {
-            rc = build_layout(cur, seg, ph.nseg, P, mb.Ls, &g.d_status->phase_bytes[i], &g.d_status->phase_chunks[i], s);
+            rc = build_layout(cur, seg, ph.nseg, P, Q, N, mb.Ls, &g.d_status->phase_bytes[i],
+                              &g.d_status->phase_chunks[i], nullptr, 0u, s);
             if (rc != TUNA_OK) return rc;
-            rc = build_layout(nxt, seg, ph.nseg, P, mb.Lr, nullptr, nullptr, s);
+            rc = build_layout(nxt, seg, ph.nseg, P, Q, N, mb.Lr, nullptr, nullptr, nullptr, 0u, s);
             if (rc != TUNA_OK) return rc;
         }
         mark(s, kCatMeta, (int)i);

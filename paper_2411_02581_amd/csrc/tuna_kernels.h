@@ -26,6 +26,10 @@ constexpr int kScanThreads = 256;
 constexpr int kScanItems = 4;
 
 enum CopyMode { kPack = 0, kExchange = 1, kUnpack = 2, kFused = 3 };
+// per-segment flags in the copy kernel's window: bits 0-3 = bytes of the first chunk that lie
+// before the block (fused rounds), then:
+constexpr int kFlagFill = 16;    // destination is a T slot: the tail lane fills up the 128-byte line
+constexpr int kFlagSrcT = 32;    // source is a T slot: reading past the block's end is always safe
 
 // Device-side status block, cleared at the start of a call and read back once after validation.
 struct Status {
@@ -246,14 +250,19 @@ __global__ void __launch_bounds__(256) k_meta_exchange(const int32_t* __restrict
 // of Algorithm "TuNA", line 15, needs each block's offset inside its message).  One workgroup
 // per rank: gathers the sizes in message order, converts to 16-byte chunks, exclusive scan with
 // wave shuffles + LDS across the 4 waves, a running carry across batches of 1024 segments.
+// With `head_displs` (fused rounds) the chunks of a block bound for R are cut at the 16-byte
+// boundaries of its destination address, so a block that starts `a` bytes into a 16-byte line
+// takes ceil((a + size) / 16) chunks; head_base is the low 4 bits of the receive buffer address.
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kScanThreads) k_layout_scan(const int32_t* __restrict__ sizes,
                                                               const SegInfo* __restrict__ seg, int nseg,
                                                               int P, LayoutDev L,
-                                                              unsigned long long* __restrict__ phase_bytes) {
+                                                              unsigned long long* __restrict__ phase_bytes,
+                                                              const int64_t* __restrict__ head_displs,
+                                                              unsigned int head_base, int Q, int N) {
     __shared__ int wsum[kScanThreads / kWave];
-    __shared__ int carry_s;
     const int p = blockIdx.x;
+    const int pn = p / Q, pg = p - pn * Q;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const int32_t* row = sizes + (size_t)p * P;
     int* pre = L.pre + (size_t)p * L.ld;
@@ -265,10 +274,18 @@ __global__ void __launch_bounds__(kScanThreads) k_layout_scan(const int32_t* __r
 #pragma unroll
         for (int k = 0; k < kScanItems; ++k) {
             const int s = base + tid * kScanItems + k;
-            int sz = 0;
-            if (s < nseg) sz = row[seg[s].e];
+            int sz = 0, head = 0;
+            if (s < nseg) {
+                const SegInfo si = seg[s];
+                sz = row[si.e];
+                if (head_displs && si.dst_slot < 0 && sz > 0) {
+                    int sn = pn + si.j; if (sn >= N) sn -= N;
+                    int sg = pg + si.l; if (sg >= Q) sg -= Q;
+                    head = (int)(((unsigned int)head_displs[(size_t)p * P + sn * Q + sg] + head_base) & 15u);
+                }
+            }
             bytes += (unsigned long long)sz;
-            c[k] = (sz + 15) >> 4;
+            c[k] = (head + sz + 15) >> 4;
             sum += c[k];
         }
         const int incl = wave_incl_scan(sum);
@@ -296,7 +313,6 @@ __global__ void __launch_bounds__(kScanThreads) k_layout_scan(const int32_t* __r
     for (int d = kWave / 2; d > 0; d >>= 1) bytes += __shfl_xor(bytes, d, kWave);
     if (lane == 0 && bytes && phase_bytes) atomicAdd(phase_bytes, bytes);
     if (tid == 0) { pre[nseg] = carry; L.tot[p] = carry; }
-    (void)carry_s;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -467,12 +483,20 @@ __device__ __forceinline__ unsigned long long block_address(int slot, bool far_i
     return (unsigned long long)(user + displs[(size_t)p * P + pn * Q + pg]);
 }
 
+// Waves per SIMD: measured on MI355X, the gathering kernels (pack, exchange) run fastest with at most 6
+// resident waves per SIMD, the scattering unpack with as many as fit.
+#ifndef TUNA_FUSED_MAX_WAVES
+#define TUNA_FUSED_MAX_WAVES 8
+#endif
+constexpr int copy_max_waves(int mode) { return mode == kUnpack ? 8 : (mode == kFused ? TUNA_FUSED_MAX_WAVES : 6); }
 template <int MODE, int GRAN>
-__global__ void __launch_bounds__(kCopyThreads) k_copy(const CopyArgs a) {
+__global__ void __launch_bounds__(kCopyThreads) __attribute__((amdgpu_waves_per_eu(1, copy_max_waves(MODE))))
+k_copy(const CopyArgs a) {
     __shared__ int s_pre[kCopyThreads / kWave][kWave];
     __shared__ int s_size[kCopyThreads / kWave][kWave];
     __shared__ unsigned long long s_addr[kCopyThreads / kWave][kWave];
     __shared__ unsigned long long s_addr2[MODE == kFused ? kCopyThreads / kWave : 1][kWave];
+    __shared__ int s_flag[kCopyThreads / kWave][kWave];
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int unit = blockIdx.x * (kCopyThreads / kWave) + wv;
@@ -489,6 +513,7 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy(const CopyArgs a) {
     int* wsize = s_size[wv];
     unsigned long long* waddr = s_addr[wv];
     unsigned long long* waddr2 = s_addr2[MODE == kFused ? wv : 0];
+    int* wflag = s_flag[wv];
 
     int c[kChunksPerLane];
     bool pend[kChunksPerLane];
@@ -511,28 +536,28 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy(const CopyArgs a) {
         const int wend = __builtin_amdgcn_readlane(pre_n, kWave - 1);   // chunks below wend resolve here
         const bool need = s < a.nseg && pre_i < cend && pre_n > pre_i && pre_n > c0;
         unsigned long long addr = 0, addr2 = 0;
-        int size = 0;
+        int size = 0, flag = 0;
         if (need) {
             if (MODE == kExchange) {
                 const int ps = partner_up(n, g, a.Q, a.N, a.dim, sa.y * a.rx);
                 addr = (unsigned long long)(a.stage_src + a.Ls.rank_base[ps] + a.Ls.pre[(size_t)ps * a.Ls.ld + s]);
                 size = (pre_n - pre_i) << 4;
             } else {
-                // `size` bounds the bytes a chunk access may touch.  T slots and staging are padded
-                // to whole chunks (lines), so only the caller's buffers need care: a store into R
-                // must end exactly with the block; a load from S may run into the bytes that
-                // follow the block as long as it stays inside the part of S that holds blocks.
+                // `size` = bytes of the block the destination may receive.  Staging and T slots are
+                // padded to whole chunks (lines), so they take whole chunks; a store into R must end
+                // exactly with the block.  A load may always run up to 15 bytes past a block's end in
+                // T or staging; in S only while it stays inside the part of S that holds blocks.
                 size = (pre_n - pre_i) << 4;
                 if (MODE == kPack) {
                     addr = block_address(sa.z, false, p, n, g, sb.x, sb.y, a.P, a.Q, a.N, a.user, a.displs, a.T,
                                          a.slots, a.slot_bytes);
-                    if (sa.z < 0) size = (int)min((unsigned long long)size, a.user_limit - addr);
+                    if (sa.z >= 0) flag |= kFlagSrcT;
                 }
                 if (MODE == kUnpack) {
                     addr = block_address(sa.w, true, p, n, g, sb.x, sb.y, a.P, a.Q, a.N, a.user, a.displs, a.T,
                                          a.slots, a.slot_bytes);
                     if (sa.w < 0) size = a.sizes[(size_t)p * a.P + sa.x];
-                    else size |= 1 << 30;             // T-bound: the tail lane completes the 128-byte line
+                    else flag |= kFlagFill;           // T-bound: the tail lane completes the 128-byte line
                 }
                 if (MODE == kFused) {
                     // tiled over the RECEIVER's layout: its stores into R are consecutive; the loads
@@ -543,16 +568,20 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy(const CopyArgs a) {
                     else { sn += dist; if (sn >= a.N) sn -= a.N; }
                     addr = block_address(sa.z, false, sn * a.Q + sg, sn, sg, sb.x, sb.y, a.P, a.Q, a.N, a.user,
                                          a.displs, a.T, a.slots, a.slot_bytes);
-                    if (sa.z < 0) size = (int)min((unsigned long long)size, a.user_limit - addr);
+                    if (sa.z >= 0) flag |= kFlagSrcT;
                     addr2 = block_address(sa.w, true, p, n, g, sb.x, sb.y, a.P, a.Q, a.N, a.user2, a.displs2,
                                           a.T2, a.slots, a.slot_bytes);
-                    if (sa.w < 0) size = min(size, a.sizes[(size_t)p * a.P + sa.x]);
-                    else size |= 1 << 30;
+                    // chunks are cut at the destination's 16-byte boundaries: `head` bytes of the
+                    // first chunk lie before the block (0 for T slots, which are line aligned)
+                    flag |= (int)(addr2 & 15ull);
+                    if (sa.w < 0) size = a.sizes[(size_t)p * a.P + sa.x];
+                    else flag |= kFlagFill;
                 }
             }
         }
         wpre[lane] = pre_i;
         wsize[lane] = size;
+        wflag[lane] = flag;
         waddr[lane] = addr;
         if (MODE == kFused) waddr2[lane] = addr2;
         // the window is private to this wave; its LDS writes are ordered before the reads below
@@ -564,13 +593,14 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy(const CopyArgs a) {
         int steps = 0;
         while ((1 << steps) < nlive) ++steps;
 
-        bool act[kChunksPerLane];
+        bool act[kChunksPerLane], slow[kChunksPerLane];
         unsigned long long oa[kChunksPerLane], oa2[kChunksPerLane];
         int nb[kChunksPerLane], fill[kChunksPerLane];
         v4u v[kChunksPerLane];
 #pragma unroll
         for (int k = 0; k < kChunksPerLane; ++k) {
             act[k] = pend[k] && c[k] < wend;
+            slow[k] = false;
             oa[k] = 0; oa2[k] = 0; nb[k] = 0; fill[k] = 0;
             if (act[k]) {
                 int lo = 0, hi = nlive;              // wpre[lo] <= c < wpre[hi] (hi == nlive: sentinel)
@@ -578,26 +608,38 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy(const CopyArgs a) {
                     const int mid = (lo + hi) >> 1;
                     if (mid > lo) { if (wpre[mid] <= c[k]) lo = mid; else hi = mid; }
                 }
-                const int off = (c[k] - wpre[lo]) << 4;
+                const int lim = wsize[lo];
+                const int fl = wflag[lo];
+                int off = (c[k] - wpre[lo]) << 4;    // first byte of the chunk, relative to the block
+                int end = off + 16;
+                if (MODE == kFused) {                 // chunk grid anchored at the destination line
+                    const int h = fl & 15;
+                    end = off + 16 - h;
+                    off = max(off - h, 0);
+                }
                 oa[k] = waddr[lo] + (unsigned long long)off;
                 if (MODE == kFused) oa2[k] = waddr2[lo] + (unsigned long long)off;
-                const int sz = wsize[lo];
-                nb[k] = min(16, (sz & ~(1 << 30)) - off);
+                nb[k] = min(end, lim) - off;
                 // last chunk of a T-bound block: number of further chunks up to the 128-byte line end
-                fill[k] = ((sz >> 30) & 1) && (off + 16 >= (sz & ~(1 << 30))) ? ((128 - ((off + 16) & 127)) & 127) >> 4 : 0;
+                fill[k] = (fl & kFlagFill) && (end >= lim) ? ((128 - (end & 127)) & 127) >> 4 : 0;
+                // a whole-chunk load from S is safe only inside the part of S that holds blocks
+                if (MODE == kPack || MODE == kFused)
+                    slow[k] = !(fl & kFlagSrcT) && oa[k] + 16 > a.user_limit;
             }
         }
+        // ---- whole-chunk loads, all in flight before the first store --------------------------
 #pragma unroll
         for (int k = 0; k < kChunksPerLane; ++k) {
-            if (act[k]) {
+            if (act[k] && !slow[k]) {
                 if (MODE == kUnpack) v[k] = __builtin_nontemporal_load(stage + c[k]);
                 else if (MODE == kExchange) v[k] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(oa[k]));
-                else v[k] = load_block_chunk<GRAN>(reinterpret_cast<const unsigned char*>(oa[k]), nb[k]);
+                else __builtin_memcpy(&v[k], reinterpret_cast<const unsigned char*>(oa[k]), 16);
             }
         }
+        // ---- stores: whole chunks into staging and T, exact bytes into R -------------------------
 #pragma unroll
         for (int k = 0; k < kChunksPerLane; ++k) {
-            if (act[k]) {
+            if (act[k] && !slow[k]) {
                 if (MODE == kUnpack || MODE == kFused) {
                     unsigned char* dst = reinterpret_cast<unsigned char*>(MODE == kFused ? oa2[k] : oa[k]);
                     store_block_chunk<GRAN>(dst, v[k], nb[k]);
@@ -605,9 +647,27 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy(const CopyArgs a) {
                 } else {
                     __builtin_nontemporal_store(v[k], stage + c[k]);
                 }
-                pend[k] = false;
             }
         }
+        // ---- rare: the last few bytes of S, loaded exactly --------------------------------------------
+        if (MODE == kPack || MODE == kFused) {
+#pragma unroll
+            for (int k = 0; k < kChunksPerLane; ++k) {
+                if (slow[k]) {
+                    const int ns = (int)min((unsigned long long)nb[k], a.user_limit - oa[k]);
+                    const v4u t = load_block_chunk<GRAN>(reinterpret_cast<const unsigned char*>(oa[k]), min(ns, 15));
+                    if (MODE == kPack) {
+                        __builtin_nontemporal_store(t, stage + c[k]);
+                    } else {
+                        unsigned char* dst = reinterpret_cast<unsigned char*>(oa2[k]);
+                        store_block_chunk<GRAN>(dst, t, min(ns, 15));
+                        for (int f = 1; f <= fill[k]; ++f) *reinterpret_cast<v4u*>(dst + 16 * f) = t;
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < kChunksPerLane; ++k) pend[k] = pend[k] && !act[k];
         if (wend >= cend) break;
         sw += kWave;
         __builtin_amdgcn_wave_barrier();
