@@ -22,7 +22,8 @@ constexpr size_t kAlign = 256;
 
 struct DevicePlan {
     PlanHost host;
-    std::vector<SegInfo*> d_seg;
+    std::vector<SegDev> d_seg;
+    std::vector<int32_t*> d_seg_mem;
     std::vector<int32_t*> d_zt;
 };
 
@@ -162,13 +163,21 @@ int get_plan(int P, int Q, int rl, int rg, bool fused, DevicePlan** out) {
         dp.host = make_plan(P, Q, crl, crg, fused);
         if ((int)dp.host.phases.size() > TUNA_MAX_PHASES) return TUNA_ERR_TOO_LARGE;
         for (auto& ph : dp.host.phases) {
-            SegInfo* ds = nullptr;
+            // field-major copy of the table: e[], z[], src[], dst[]
+            const size_t ns = ph.seg.size(), stride = align_up(ns * 4) / 4;
+            std::vector<int32_t> soa(4 * stride, 0);
+            for (size_t k = 0; k < ns; ++k) {
+                soa[k] = ph.seg[k].e; soa[stride + k] = ph.seg[k].z;
+                soa[2 * stride + k] = ph.seg[k].src_slot; soa[3 * stride + k] = ph.seg[k].dst_slot;
+            }
+            int32_t* dm = nullptr;
             int32_t* dz = nullptr;
-            HIPCHK(hipMalloc((void**)&ds, align_up(ph.seg.size() * sizeof(SegInfo))));
+            HIPCHK(hipMalloc((void**)&dm, 4 * stride * 4 + kAlign));
             HIPCHK(hipMalloc((void**)&dz, align_up((size_t)P * 4)));
-            HIPCHK(hipMemcpy(ds, ph.seg.data(), ph.seg.size() * sizeof(SegInfo), hipMemcpyHostToDevice));
+            HIPCHK(hipMemcpy(dm, soa.data(), soa.size() * 4, hipMemcpyHostToDevice));
             HIPCHK(hipMemcpy(dz, ph.zt.data(), (size_t)P * 4, hipMemcpyHostToDevice));
-            dp.d_seg.push_back(ds);
+            dp.d_seg.push_back(SegDev{dm, dm + stride, dm + 2 * stride, dm + 3 * stride});
+            dp.d_seg_mem.push_back(dm);
             dp.d_zt.push_back(dz);
             // the device copies are all the kernels need; drop the host tables
             std::vector<SegInfo>().swap(ph.seg);
@@ -226,7 +235,7 @@ int launch_copy(int gran, size_t unit_cap, const CopyArgs& a, hipStream_t s) {
     return TUNA_OK;
 }
 
-int build_layout(const int32_t* sizes, const SegInfo* seg, int nseg, int P, int Q, int N, const LayoutDev& L,
+int build_layout(const int32_t* sizes, const SegDev& seg, int nseg, int P, int Q, int N, const LayoutDev& L,
                  unsigned long long* phase_bytes, unsigned long long* phase_chunks,
                  const int64_t* head_displs, unsigned int head_base, hipStream_t s) {
     hipLaunchKernelGGL(k_layout_scan, dim3(P), dim3(kScanThreads), 0, s, sizes, seg, nseg, P, L, phase_bytes,
@@ -363,7 +372,7 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
         tuna_phase_stats_t& ps = st.phase[i];
         ps.dim = ph.dim; ps.x = ph.x; ps.radix = ph.r; ps.rounds = ph.nz;
         ps.blocks = (int64_t)ph.nseg * P;
-        const SegInfo* seg = dp->d_seg[i];
+        const SegDev seg = dp->d_seg[i];
         // metadata exchange, then the send-side and receive-side layouts
         hipLaunchKernelGGL(k_meta_exchange, dim3(gP2), dim3(256), 0, s, cur, nxt, dp->d_zt[i], P, Q, N, ph.dim,
                            (int)ph.rx);
@@ -496,7 +505,7 @@ int tuna_release(void) {
     if (g.meta) { HIPCHK(hipFree(g.meta)); g.meta = nullptr; g.meta_bytes = 0; }
     if (g.data) { HIPCHK(hipFree(g.data)); g.data = nullptr; g.data_bytes = 0; }
     for (auto& kv : g.plans) {
-        for (auto* p : kv.second.d_seg) (void)hipFree(p);
+        for (auto* p : kv.second.d_seg_mem) (void)hipFree(p);
         for (auto* p : kv.second.d_zt) (void)hipFree(p);
     }
     g.plans.clear();

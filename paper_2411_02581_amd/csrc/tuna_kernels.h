@@ -44,6 +44,20 @@ struct Status {
     unsigned long long phase_chunks[64];  // staged chunks per phase
 };
 
+// The per-phase table of moving blocks on the device, one array per field (message order).
+struct SegDev {
+    const int32_t* e;      // slot index j*Q + l
+    const int32_t* z;      // digit value: which message, partner distance z*r^x
+    const int32_t* src;    // source T slot or -1 (send buffer)
+    const int32_t* dst;    // destination T slot or -1 (receive buffer)
+};
+
+// Distance pair of a slot index.
+__device__ __forceinline__ void split_slot_index(int e, int Q, int N, int& j, int& l) {
+    if (N == 1) { j = 0; l = e; }
+    else { j = e / Q; l = e - j * Q; }
+}
+
 // One staging layout (send side or receive side) of the current phase.
 struct LayoutDev {
     int* pre;                      // [P][ld]: exclusive prefix of chunk counts over the rank's segments; [nseg] = total
@@ -255,7 +269,7 @@ __global__ void __launch_bounds__(256) k_meta_exchange(const int32_t* __restrict
 // takes ceil((a + size) / 16) chunks; head_base is the low 4 bits of the receive buffer address.
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kScanThreads) k_layout_scan(const int32_t* __restrict__ sizes,
-                                                              const SegInfo* __restrict__ seg, int nseg,
+                                                              const SegDev seg, int nseg,
                                                               int P, LayoutDev L,
                                                               unsigned long long* __restrict__ phase_bytes,
                                                               const int64_t* __restrict__ head_displs,
@@ -276,11 +290,13 @@ __global__ void __launch_bounds__(kScanThreads) k_layout_scan(const int32_t* __r
             const int s = base + tid * kScanItems + k;
             int sz = 0, head = 0;
             if (s < nseg) {
-                const SegInfo si = seg[s];
-                sz = row[si.e];
-                if (head_displs && si.dst_slot < 0 && sz > 0) {
-                    int sn = pn + si.j; if (sn >= N) sn -= N;
-                    int sg = pg + si.l; if (sg >= Q) sg -= Q;
+                const int e = seg.e[s];
+                sz = row[e];
+                if (head_displs && sz > 0 && seg.dst[s] < 0) {
+                    int j, l;
+                    split_slot_index(e, Q, N, j, l);
+                    int sn = pn + j; if (sn >= N) sn -= N;
+                    int sg = pg + l; if (sg >= Q) sg -= Q;
                     head = (int)(((unsigned int)head_displs[(size_t)p * P + sn * Q + sg] + head_base) & 15u);
                 }
             }
@@ -407,7 +423,7 @@ struct CopyArgs {
     // tiled (staging) side
     v4u* stage;                         // staging buffer being tiled (unused when fused)
     LayoutDev L;                        // its layout
-    const SegInfo* seg;
+    SegDev seg;
     int nseg;
     // other side: caller buffer + T (pack, unpack, fused source)
     const int32_t* sizes;               // [P][P] block sizes at the tiled side's ranks (cur for pack, nxt for unpack)
@@ -526,20 +542,24 @@ k_copy(const CopyArgs a) {
         // ---- window: segments sw .. sw+63, one per lane --------------------------------------
         const int s = sw + lane;
         const int pre_i = s <= a.nseg ? prow[s] : INT_MAX;
-        const int pre_n = s + 1 <= a.nseg ? prow[s + 1] : INT_MAX;
-        int4 sa = make_int4(0, 0, -1, -1), sb = make_int4(0, 0, 0, 0);
+        const int pre_w = sw + kWave <= a.nseg ? prow[sw + kWave] : INT_MAX;   // wave-uniform: first prefix of the next window
+        int pre_n = __shfl_down(pre_i, 1, kWave);
+        if (lane == kWave - 1) pre_n = pre_w;
+        // table fields this mode needs, fetched together with the prefix (one round trip)
+        int se = 0, sz_ = 0, ssrc = -1, sdst = -1;
         if (s < a.nseg) {
-            const int4* sp = reinterpret_cast<const int4*>(a.seg + s);
-            sa = sp[0];                                   // e, z, src_slot, dst_slot
-            sb = sp[1];                                   // j, l
+            if (MODE != kExchange) se = a.seg.e[s];
+            if (MODE == kExchange || MODE == kFused) sz_ = a.seg.z[s];
+            if (MODE == kPack || MODE == kFused) ssrc = a.seg.src[s];
+            if (MODE == kUnpack || MODE == kFused) sdst = a.seg.dst[s];
         }
-        const int wend = __builtin_amdgcn_readlane(pre_n, kWave - 1);   // chunks below wend resolve here
+        const int wend = pre_w;                      // chunks below wend resolve in this window
         const bool need = s < a.nseg && pre_i < cend && pre_n > pre_i && pre_n > c0;
         unsigned long long addr = 0, addr2 = 0;
         int size = 0, flag = 0;
         if (need) {
             if (MODE == kExchange) {
-                const int ps = partner_up(n, g, a.Q, a.N, a.dim, sa.y * a.rx);
+                const int ps = partner_up(n, g, a.Q, a.N, a.dim, sz_ * a.rx);
                 addr = (unsigned long long)(a.stage_src + a.Ls.rank_base[ps] + a.Ls.pre[(size_t)ps * a.Ls.ld + s]);
                 size = (pre_n - pre_i) << 4;
             } else {
@@ -548,33 +568,35 @@ k_copy(const CopyArgs a) {
                 // exactly with the block.  A load may always run up to 15 bytes past a block's end in
                 // T or staging; in S only while it stays inside the part of S that holds blocks.
                 size = (pre_n - pre_i) << 4;
+                int bj, bl;
+                split_slot_index(se, a.Q, a.N, bj, bl);
                 if (MODE == kPack) {
-                    addr = block_address(sa.z, false, p, n, g, sb.x, sb.y, a.P, a.Q, a.N, a.user, a.displs, a.T,
+                    addr = block_address(ssrc, false, p, n, g, bj, bl, a.P, a.Q, a.N, a.user, a.displs, a.T,
                                          a.slots, a.slot_bytes);
-                    if (sa.z >= 0) flag |= kFlagSrcT;
+                    if (ssrc >= 0) flag |= kFlagSrcT;
                 }
                 if (MODE == kUnpack) {
-                    addr = block_address(sa.w, true, p, n, g, sb.x, sb.y, a.P, a.Q, a.N, a.user, a.displs, a.T,
+                    addr = block_address(sdst, true, p, n, g, bj, bl, a.P, a.Q, a.N, a.user, a.displs, a.T,
                                          a.slots, a.slot_bytes);
-                    if (sa.w < 0) size = a.sizes[(size_t)p * a.P + sa.x];
+                    if (sdst < 0) size = a.sizes[(size_t)p * a.P + se];
                     else flag |= kFlagFill;           // T-bound: the tail lane completes the 128-byte line
                 }
                 if (MODE == kFused) {
                     // tiled over the RECEIVER's layout: its stores into R are consecutive; the loads
                     // gather from the sender at distance z*r^x upwards (S or its T slot)
                     int sn = n, sg = g;
-                    const int dist = sa.y * a.rx;
+                    const int dist = sz_ * a.rx;
                     if (a.dim == 0) { sg += dist; if (sg >= a.Q) sg -= a.Q; }
                     else { sn += dist; if (sn >= a.N) sn -= a.N; }
-                    addr = block_address(sa.z, false, sn * a.Q + sg, sn, sg, sb.x, sb.y, a.P, a.Q, a.N, a.user,
+                    addr = block_address(ssrc, false, sn * a.Q + sg, sn, sg, bj, bl, a.P, a.Q, a.N, a.user,
                                          a.displs, a.T, a.slots, a.slot_bytes);
-                    if (sa.z >= 0) flag |= kFlagSrcT;
-                    addr2 = block_address(sa.w, true, p, n, g, sb.x, sb.y, a.P, a.Q, a.N, a.user2, a.displs2,
+                    if (ssrc >= 0) flag |= kFlagSrcT;
+                    addr2 = block_address(sdst, true, p, n, g, bj, bl, a.P, a.Q, a.N, a.user2, a.displs2,
                                           a.T2, a.slots, a.slot_bytes);
                     // chunks are cut at the destination's 16-byte boundaries: `head` bytes of the
                     // first chunk lie before the block (0 for T slots, which are line aligned)
                     flag |= (int)(addr2 & 15ull);
-                    if (sa.w < 0) size = a.sizes[(size_t)p * a.P + sa.x];
+                    if (sdst < 0) size = a.sizes[(size_t)p * a.P + se];
                     else flag |= kFlagFill;
                 }
             }
