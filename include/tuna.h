@@ -167,9 +167,14 @@ int tuna_release(void);
  * analysis of coalesced and staggered TuNA_l^g": prepare, metadata, data, replace).
  * TUNA_OPT_FUSED: 1 = move every block of a phase straight from its source (S or T) to its
  * destination (R or the other copy of T) in one kernel instead of pack -> exchange -> unpack.
+ * TUNA_OPT_STAGGERED: 1 = the staggered inter-node schedule of Algorithm "Staggered TuNA_l^g"
+ * for hierarchical calls: after the intra-node phase every one of the Q (N - 1) blocks bound
+ * for another node is its own message and goes straight from where it lies (its T slot, or S)
+ * to R of its destination -- no rearrangement of T, no packing; the global radix is N.
  */
 #define TUNA_OPT_PROFILE 1
 #define TUNA_OPT_FUSED 2
+#define TUNA_OPT_STAGGERED 3
 int tuna_set_option(int option, int value);
 
 /* Statistics of the last tuna_alltoallv* call (host struct).  Synchronises with that call's

@@ -271,10 +271,13 @@ class _HRank:
         assert off == len(data)
 
 
-def simulate_tuna_hier(S: Sequence[Sequence[bytes]], Q: int, rl: int, rg: int):
+def simulate_tuna_hier(S: Sequence[Sequence[bytes]], Q: int, rl: int, rg: int, staggered: bool = False):
     """Coalesced TuNA_l^g over P = len(S) ranks, Q per node.  rg = N gives the paper's inter-node
     schedule (N-1 rounds, Q blocks per message); rg < N runs the same digit rounds over the N
-    node-ranks with super-blocks as the unit.  Returns (R, stats)."""
+    node-ranks with super-blocks as the unit.  staggered = True runs Algorithm "Staggered
+    TuNA_l^g" instead: no rearrangement, Q (N-1) inter-node rounds of one block each, round
+    (gi, gr) carrying block gr of the group for node n - gi to the rank of equal g there.
+    Returns (R, stats)."""
     P = len(S)
     assert P % Q == 0
     N = P // Q
@@ -292,6 +295,23 @@ def simulate_tuna_hier(S: Sequence[Sequence[bytes]], Q: int, rl: int, rg: int):
             ranks[sendrank].local_receive(x, z, metadata, data)
             stats["local_phase_bytes"][x] = stats["local_phase_bytes"].get(x, 0) + len(data)
     stats["after_local_R"] = [list(rk.R) for rk in ranks]
+    if staggered:
+        stats["global_rounds"] = []
+        stats["global_phase_bytes"] = {0: 0}
+        for gi in range(1, N):                              # node distance
+            for gr in range(Q):                             # one block per round
+                msgs = []
+                for rk in ranks:
+                    ndst = (rk.n - gi + N) % N
+                    l = (gr - rk.g) % Q                     # block from source (n, gr) bound for (ndst, g)
+                    blk = rk.S[ndst * Q + rk.g] if l == 0 else rk.T[(ndst, l)]
+                    msgs.append((ndst * Q + rk.g, rk.n * Q + gr, blk))
+                for dst, src, blk in msgs:
+                    assert ranks[dst].R[src] is None
+                    ranks[dst].R[src] = blk
+                    stats["global_phase_bytes"][0] += len(blk)
+                stats["global_rounds"].append((gi, gr))
+        return [rk.R for rk in ranks], stats
     for rk in ranks:
         rk.rearrange()
     for (x, z) in stats["global_rounds"]:

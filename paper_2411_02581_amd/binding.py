@@ -23,6 +23,7 @@ TUNA_ERR_HIP = -6
 TUNA_ERR_TOO_LARGE = -7
 TUNA_OPT_PROFILE = 1
 TUNA_OPT_FUSED = 2
+TUNA_OPT_STAGGERED = 3
 TUNA_MAX_PHASES = 64
 
 EXPORTS = ("tuna_alltoallv", "tuna_alltoallv_hier", "tuna_workspace_bytes", "tuna_set_workspace",

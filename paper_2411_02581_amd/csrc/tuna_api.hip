@@ -43,7 +43,7 @@ struct Ctx {
     std::map<std::tuple<int, int, int, int, int>, DevicePlan> plans;
     tuna_stats_t stats;
     bool have_stats = false;
-    int opt_profile = 0, opt_fused = 0;
+    int opt_profile = 0, opt_fused = 0, opt_staggered = 0;
     std::vector<hipEvent_t> ev_pool;
     std::vector<Mark> marks;
     hipEvent_t ev_end = nullptr;
@@ -132,12 +132,13 @@ struct DataSizes {
     size_t total;
 };
 
-DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long total_chunks, bool fused) {
+DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long total_chunks, bool fused,
+                         bool staggered = false) {
     DataSizes d{};
     const bool any_phase = !pl.phases.empty() && total_chunks > 0;
     d.stage_chunks = any_phase ? (size_t)total_chunks : 0;
     // fused rounds cut chunks at destination lines: up to one more chunk per moving block
-    const size_t head_chunks = fused ? (size_t)pl.P * pl.P : 0;
+    const size_t head_chunks = (fused || staggered) ? (size_t)pl.P * pl.P : 0;
     d.unit_cap = any_phase ? (size_t)((total_chunks + head_chunks) / kUnitChunks) + pl.P + 1 : 0;
     d.slots = pl.slots;
     d.slot_bytes = (M + 127) / 128 * 128;     // whole 128-byte lines per slot
@@ -288,6 +289,9 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
 
     DevicePlan* dp = nullptr;
     const bool fused = g.opt_fused != 0;
+    // staggered inter-node schedule: one block per message, N - 1 node distances, straight from T
+    const bool staggered = g.opt_staggered != 0 && N > 1;
+    if (staggered) rg = N;
     rc = get_plan(P, Q, rl, rg, fused, &dp);
     if (rc != TUNA_OK) return rc;
     const PlanHost& pl = dp->host;
@@ -300,6 +304,7 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
     st.P = P; st.Q = Q; st.N = N; st.local_radix = pl.rl; st.global_radix = pl.rg;
     st.w_local = pl.w_l; st.w_global = pl.w_g; st.K_local = pl.K_l; st.K_global = pl.K_g;
     st.B_local = pl.B_l; st.B_global = pl.B_g; st.n_phases = (int)pl.phases.size();
+    if (staggered) st.K_global = Q * (N - 1);
     st.temp_slots_per_rank = pl.slots;
     st.fused = fused ? 1 : 0;
     mark(s, -1, -1);
@@ -323,7 +328,7 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
 
     // ---- workspace ---------------------------------------------------------------------------
     const size_t mbytes = meta_bytes_for(P);
-    const DataSizes ds = data_sizes_for(pl, hs.max_count, hs.total_chunks, fused);
+    const DataSizes ds = data_sizes_for(pl, hs.max_count, hs.total_chunks, fused, staggered);
     void *mbase, *dbase;
     if (g.user_ws) {
         if (mbytes + ds.total > g.user_ws_bytes) return TUNA_ERR_WORKSPACE_TOO_SMALL;
@@ -371,13 +376,15 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
         const PhaseHost& ph = pl.phases[i];
         tuna_phase_stats_t& ps = st.phase[i];
         ps.dim = ph.dim; ps.x = ph.x; ps.radix = ph.r; ps.rounds = ph.nz;
+        const bool one_kernel = fused || (staggered && ph.dim == 1);
+        if (staggered && ph.dim == 1) ps.rounds = Q * (N - 1);
         ps.blocks = (int64_t)ph.nseg * P;
         const SegDev seg = dp->d_seg[i];
         // metadata exchange, then the send-side and receive-side layouts
         hipLaunchKernelGGL(k_meta_exchange, dim3(gP2), dim3(256), 0, s, cur, nxt, dp->d_zt[i], P, Q, N, ph.dim,
                            (int)ph.rx);
         HIPCHK(hipGetLastError());
-        if (fused) {   // only the receive-side layout is needed
+        if (one_kernel) {   // only the receive-side layout is needed
             rc = build_layout(nxt, seg, ph.nseg, P, Q, N, mb.Lr, &g.d_status->phase_bytes[i],
                               &g.d_status->phase_chunks[i], rdispls, (unsigned int)((uintptr_t)recvbuf & 15u), s);
             if (rc != TUNA_OK) return rc;
@@ -395,7 +402,7 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
         a.T = T; a.slots = ds.slots; a.slot_bytes = ds.slot_bytes;
         a.P = P; a.Q = Q; a.N = N; a.dim = ph.dim; a.rx = (int)ph.rx;
         a.user_limit = (unsigned long long)(uintptr_t)sendbuf + hs.send_extent;
-        if (fused) {
+        if (one_kernel) {
             // one hop in one kernel: S / T of the sender -> R / the other copy of T at the receiver
             a.stage = nullptr; a.L = mb.Lr; a.sizes = nxt;
             a.user = (unsigned char*)sendbuf; a.displs = sdispls;
@@ -466,6 +473,8 @@ int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node, i
     // the schedule's slot count does not need the device tables
     const int N = P / Q;
     int rl = local_radix, rg = global_radix;
+    const bool staggered = g.opt_staggered != 0 && N > 1;
+    if (staggered) rg = N;
     if (Q >= 2 && rl > Q) rl = Q;
     if (N >= 2 && rg > N) rg = N;
     PlanHost pl;
@@ -474,7 +483,7 @@ int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node, i
     const int Bl = Q > 1 ? Q - 1 - Kl : 0, Bg = N > 1 ? N - 1 - Kg : 0;
     pl.slots = ((int64_t)Bl + (int64_t)(N - 1) * (Q - 1) + (int64_t)Bg * Q) * (g.opt_fused ? 2 : 1);
     if (P > 1) pl.phases.resize(1);
-    const DataSizes ds = data_sizes_for(pl, g.h_status->max_count, g.h_status->total_chunks, g.opt_fused != 0);
+    const DataSizes ds = data_sizes_for(pl, g.h_status->max_count, g.h_status->total_chunks, g.opt_fused != 0, staggered);
     *bytes = meta_bytes_for(P) + ds.total;
     return TUNA_OK;
 }
@@ -515,6 +524,7 @@ int tuna_release(void) {
 int tuna_set_option(int option, int value) {
     if (option == TUNA_OPT_PROFILE) { g.opt_profile = value ? 1 : 0; return TUNA_OK; }
     if (option == TUNA_OPT_FUSED) { g.opt_fused = value ? 1 : 0; return TUNA_OK; }
+    if (option == TUNA_OPT_STAGGERED) { g.opt_staggered = value ? 1 : 0; return TUNA_OK; }
     return TUNA_ERR_ARG;
 }
 
@@ -561,11 +571,12 @@ int tuna_plan_info(int P, int ranks_per_node, int local_radix, int global_radix,
     int Q = 0;
     int rc = resolve_hierarchy(P, ranks_per_node, &Q);
     if (rc != TUNA_OK) return rc;
+    if (g.opt_staggered && P / Q > 1) global_radix = P / Q;
     const PlanHost pl = make_plan(P, Q, local_radix, global_radix, g.opt_fused != 0);
     out->P = P; out->Q = Q; out->N = pl.N;
     out->local_radix = pl.rl; out->global_radix = pl.rg;
     out->w_local = pl.w_l; out->w_global = pl.w_g;
-    out->K_local = pl.K_l; out->K_global = pl.K_g;
+    out->K_local = pl.K_l; out->K_global = (g.opt_staggered && pl.N > 1) ? Q * (pl.N - 1) : pl.K_g;
     out->B_local = pl.B_l; out->B_global = pl.B_g;
     out->n_phases = (int)pl.phases.size();
     out->temp_slots_per_rank = pl.slots;

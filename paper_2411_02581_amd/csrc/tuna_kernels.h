@@ -654,7 +654,7 @@ k_copy(const CopyArgs a) {
         for (int k = 0; k < kChunksPerLane; ++k) {
             if (act[k] && !slow[k]) {
                 if (MODE == kUnpack) v[k] = __builtin_nontemporal_load(stage + c[k]);
-                else if (MODE == kExchange) v[k] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(oa[k]));
+                else if (MODE == kExchange) v[k] = *reinterpret_cast<const v4u*>(oa[k]);   // neighbours share its edge lines
                 else __builtin_memcpy(&v[k], reinterpret_cast<const unsigned char*>(oa[k]), 16);
             }
         }

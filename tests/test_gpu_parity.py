@@ -169,6 +169,25 @@ def test_hierarchy_shapes(tuna, Q, N):
             run_hier(tuna, prob, Q, rl, rg)
 
 
+@pytest.mark.parametrize("Q,N", [(2, 3), (4, 4), (5, 3), (16, 8)])
+def test_staggered_inter_node_schedule(tuna, Q, N):
+    """Algorithm "Staggered TuNA_l^g": one block per inter-node message, straight out of T."""
+    P = Q * N
+    counts = wl.make_counts(3, P) if P >= 64 else wl.counts_uniform_bytes(P, 31 + P, 900)
+    lay = wl.make_layout(counts, gap=3)
+    prob = Problem(lay, wl.payload_position_hash(P, lay.send_bytes))
+    tuna.tuna_set_option(tuna.TUNA_OPT_STAGGERED, 1)
+    try:
+        for rl in sorted({2, max(Q, 2)}):
+            run_hier(tuna, prob, Q, rl, 2)
+            st = tuna.tuna_get_stats()
+            assert st.global_radix == N and st.K_global == Q * (N - 1)
+            assert st.phase[st.n_phases - 1].rounds == Q * (N - 1)
+        run_flat(tuna, prob, 3)
+    finally:
+        tuna.tuna_set_option(tuna.TUNA_OPT_STAGGERED, 0)
+
+
 def test_degenerate_inputs(tuna):
     # all blocks empty
     lay = wl.make_layout(np.zeros((9, 9), dtype=np.int32), gap=4)

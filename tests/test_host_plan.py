@@ -211,3 +211,19 @@ def test_fused_tables_never_read_and_write_a_slot_in_one_phase(Q, N):
     rc, fused_info = tuna.tuna_plan_info(P, Q, 2, 2)
     tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
     assert fused_info.temp_slots_per_rank == 2 * plain.temp_slots_per_rank
+
+
+def test_staggered_option_schedule(golden):
+    """Staggered inter-node schedule: Q (N-1) rounds of one block, global radix N; the tables are
+    those of the linear global phase, in which every arrival is final."""
+    tuna.tuna_set_option(tuna.TUNA_OPT_STAGGERED, 1)
+    try:
+        for P, N, Q, r, local_steps, coalesced, staggered in golden("hier_rounds.txt"):
+            rc, info = tuna.tuna_plan_info(P, Q, r, 2)
+            assert rc == 0 and info.global_radix == N and info.K_global == staggered and info.K_local == local_steps
+            rc, hdr, seg = tuna.tuna_plan_phase(P, Q, r, 2, info.n_phases - 1)
+            assert rc == 0 and hdr[0] == 1 and (seg[:, 5] == -1).all()
+        rc, info = tuna.tuna_plan_info(16, 0, 2, 2)      # flat calls are unaffected
+        assert info.K_global == 0 and info.K_local == 4
+    finally:
+        tuna.tuna_set_option(tuna.TUNA_OPT_STAGGERED, 0)

@@ -177,6 +177,22 @@ def test_figure4_round_counts(golden):
                     assert st["after_local_R"][p][s] == S[s][p]
 
 
+def test_staggered_model(golden):
+    """Algorithm "Staggered TuNA_l^g": same result, Q (N-1) inter-node rounds of one block each,
+    and the same inter-node bytes as the coalesced schedule."""
+    for P, N, Q, r, local_steps, coalesced, staggered in golden("hier_rounds.txt"):
+        S = _blocks(P, 45)
+        R, st = tm.simulate_tuna_hier(S, Q, r, N, staggered=True)
+        assert R == _definition(S)
+        assert len(st["global_rounds"]) == staggered == Q * (N - 1)
+        _, co = tm.simulate_tuna_hier(S, Q, r, N)
+        assert st["global_phase_bytes"][0] == sum(co["global_phase_bytes"].values())
+    for Q, N in [(2, 2), (3, 4), (4, 3)]:
+        S = _blocks(Q * N, 46)
+        R, _ = tm.simulate_tuna_hier(S, Q, 2, N, staggered=True)
+        assert R == _definition(S)
+
+
 @pytest.mark.parametrize("Q,N", [(1, 6), (6, 1), (2, 3), (3, 2), (4, 4), (5, 3), (3, 7), (8, 2)])
 def test_hier_model_reaches_the_definition(Q, N):
     P = Q * N
