@@ -45,6 +45,7 @@ def parse_args():
     ap.add_argument("--radices", type=str, default="", help="comma-separated radix sweep")
     ap.add_argument("--fused", type=int, default=0, help="1: fused single-kernel rounds")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-fused-table", action="store_true", help="skip the second sweep with fused rounds")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--traffic-json", type=str, default="",
                     help="optional JSON file {kernel: bytes per launch} from rocprofv3 --pmc runs")
@@ -126,64 +127,74 @@ def main():
         copy_ceiling = {"GBs": 2 * nb / (ms * 1e-3) / 1e9, "bytes_copied": nb, "ms": ms}
         print("[bench] plain copy ceiling: %.0f GB/s (read + write)" % copy_ceiling["GBs"], file=sys.stderr, flush=True)
 
-    tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 1 if args.fused else 0)
-    per_radix = []
-    for kind, _, rl, rg in sweep:
-        label = "r_l=%d,r_g=%d" % (rl, rg) if kind == "hier" else "r=%d" % rl
-        tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 0)
-        for _ in range(args.warmup):
-            call(kind, rl, rg)
-        torch.cuda.synchronize()
-        # ---- timed region: exactly K steps between two synchronisations ----------------------
-        step_ms = []
-        t_start = time.perf_counter()
-        for _ in range(args.steps):
-            t1 = time.perf_counter()
-            call(kind, rl, rg)
+    def run_sweep(fused):
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 1 if fused else 0)
+        per_radix = []
+        for kind, _, rl, rg in sweep:
+            label = "r_l=%d,r_g=%d" % (rl, rg) if kind == "hier" else "r=%d" % rl
+            tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 0)
+            for _ in range(args.warmup):
+                call(kind, rl, rg)
             torch.cuda.synchronize()
-            step_ms.append((time.perf_counter() - t1) * 1e3)
-        torch.cuda.synchronize()
-        total_ms = (time.perf_counter() - t_start) * 1e3
-        ms_per_step = total_ms / args.steps
-        # ---- the same K steps with HIP events around every kernel (roofline figures) ----------
-        tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 1)
-        kern = {"pack": [0.0, 0, 0], "exchange": [0.0, 0, 0], "unpack": [0.0, 0, 0]}   # ms, launches, payload bytes
-        meta_ms = prep_ms = 0.0
-        prof_total = 0.0
-        for _ in range(args.steps):
-            call(kind, rl, rg)
+            # ---- timed region: exactly K steps between two synchronisations ----------------------
+            step_ms = []
+            t_start = time.perf_counter()
+            for _ in range(args.steps):
+                t1 = time.perf_counter()
+                call(kind, rl, rg)
+                torch.cuda.synchronize()
+                step_ms.append((time.perf_counter() - t1) * 1e3)
+            torch.cuda.synchronize()
+            total_ms = (time.perf_counter() - t_start) * 1e3
+            ms_per_step = total_ms / args.steps
+            # ---- the same K steps with HIP events around every kernel (roofline figures) ----------
+            tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 1)
+            kern = {"pack": [0.0, 0, 0], "exchange": [0.0, 0, 0], "unpack": [0.0, 0, 0]}   # ms, launches, payload bytes
+            meta_ms = prep_ms = 0.0
+            prof_total = 0.0
+            for _ in range(args.steps):
+                call(kind, rl, rg)
+                st = tuna.tuna_get_stats()
+                prof_total += st.ms_total
+                prep_ms += st.ms_prepare + st.ms_self
+                for x in range(st.n_phases):
+                    ph = st.phase[x]
+                    meta_ms += ph.ms_metadata
+                    for name, ms in (("pack", ph.ms_pack), ("exchange", ph.ms_exchange), ("unpack", ph.ms_unpack)):
+                        kern[name][0] += ms
+                        kern[name][1] += 1
+                        kern[name][2] += ph.payload_bytes
+            tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 0)
             st = tuna.tuna_get_stats()
-            prof_total += st.ms_total
-            prep_ms += st.ms_prepare + st.ms_self
-            for x in range(st.n_phases):
-                ph = st.phase[x]
-                meta_ms += ph.ms_metadata
-                for name, ms in (("pack", ph.ms_pack), ("exchange", ph.ms_exchange), ("unpack", ph.ms_unpack)):
-                    kern[name][0] += ms
-                    kern[name][1] += 1
-                    kern[name][2] += ph.payload_bytes
-        tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 0)
-        st = tuna.tuna_get_stats()
-        hop_bytes = sum(st.phase[x].payload_bytes for x in range(st.n_phases))
-        if st.fused:        # one kernel per phase; its time is reported in the pack column
-            kern = {"fused": kern["pack"]}
-        kernels = {}
-        for name, (ms, n, pbytes) in kern.items():
-            if n and ms > 0:
-                kernels[name] = {"avg_ms": ms / n, "launches_per_step": n // args.steps,
-                                 "alg_bytes_per_launch": 2 * pbytes / n,
-                                 "achieved_GBs": 2 * pbytes / (ms * 1e-3) / 1e9}
-        per_radix.append({
-            "radix": label, "ms_per_step": ms_per_step, "median_ms": statistics.median(step_ms),
-            "stdev_ms": statistics.pstdev(step_ms), "effective_GBs": Btot / (ms_per_step * 1e-3) / 1e9,
-            "phases": st.n_phases, "rounds": st.K_local + st.K_global, "hop_bytes": hop_bytes,
-            "temp_bytes": st.temp_bytes, "workspace_bytes": st.workspace_bytes,
-            "profiled_ms_per_step": prof_total / args.steps, "metadata_ms_per_step": meta_ms / args.steps,
-            "prepare_ms_per_step": prep_ms / args.steps, "kernels": kernels, "granularity": st.granularity})
-        print("[bench] %s: %.3f ms/step, %.1f GB/s effective; " % (label, ms_per_step, per_radix[-1]["effective_GBs"]) +
-              ", ".join("%s %.0f GB/s" % (k, v["achieved_GBs"]) for k, v in kernels.items()),
-              file=sys.stderr, flush=True)
+            hop_bytes = sum(st.phase[x].payload_bytes for x in range(st.n_phases))
+            if st.fused:        # one kernel per phase; its time is reported in the pack column
+                kern = {"fused": kern["pack"]}
+            kernels = {}
+            for name, (ms, n, pbytes) in kern.items():
+                if n and ms > 0:
+                    kernels[name] = {"avg_ms": ms / n, "launches_per_step": n // args.steps,
+                                     "alg_bytes_per_launch": 2 * pbytes / n,
+                                     "achieved_GBs": 2 * pbytes / (ms * 1e-3) / 1e9}
+            per_radix.append({
+                "radix": label, "ms_per_step": ms_per_step, "median_ms": statistics.median(step_ms),
+                "stdev_ms": statistics.pstdev(step_ms), "effective_GBs": Btot / (ms_per_step * 1e-3) / 1e9,
+                "phases": st.n_phases, "rounds": st.K_local + st.K_global, "hop_bytes": hop_bytes,
+                "temp_bytes": st.temp_bytes, "workspace_bytes": st.workspace_bytes,
+                "profiled_ms_per_step": prof_total / args.steps, "metadata_ms_per_step": meta_ms / args.steps,
+                "prepare_ms_per_step": prep_ms / args.steps, "kernels": kernels, "granularity": st.granularity})
+            print("[bench] %s: %.3f ms/step, %.1f GB/s effective; " % (label, ms_per_step, per_radix[-1]["effective_GBs"]) +
+                  ", ".join("%s %.0f GB/s" % (k, v["achieved_GBs"]) for k, v in kernels.items()) +
+              (" [fused rounds]" if fused else ""),
+                  file=sys.stderr, flush=True)
 
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+        return per_radix
+
+    per_radix = run_sweep(bool(args.fused))
+    # the fused rounds (one kernel per phase, 2 x payload instead of 6 x) as a second table
+    fused_table = None
+    if not args.fused and not args.no_fused_table:
+        fused_table = run_sweep(True)
     best = max(per_radix, key=lambda r: r["effective_GBs"])
     # Roofline of the dominant kernel: the copy kernel with the largest total time over ALL launches
     # of the timed sweep (every radix), so that its average launch duration is the one a
@@ -225,6 +236,9 @@ def main():
                    "payload_bytes": Btot, "best_radix": best["radix"], "fused": bool(args.fused),
                    "ranks_per_node": rpn},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "copy_ceiling": copy_ceiling, "per_radix": per_radix,
+        "fused_rounds": None if fused_table is None else {
+            "note": "same workload with TUNA_OPT_FUSED: one kernel per digit phase moves S/T to R/T directly",
+            "best_effective_GBs": max(r["effective_GBs"] for r in fused_table), "per_radix": fused_table},
     }
     print(json.dumps(out))
 
@@ -239,7 +253,8 @@ def time_oracle(lay, send_dev, target_seconds):
     send_host = send_dev.cpu().numpy()
     print("[bench] send buffer to host in %.1f s" % (time.time() - t0), file=sys.stderr, flush=True)
     P = lay.P
-    recv_host = np.zeros(lay.recv_bytes, dtype=np.uint8)     # pages touched before timing
+    recv_host = np.empty(lay.recv_bytes, dtype=np.uint8)
+    recv_host.fill(0)                                        # every page touched before timing
     n = max(1, min(P, P // 64))
     best = None
     spent = 0.0
@@ -258,10 +273,26 @@ def time_oracle(lay, send_dev, target_seconds):
         scale = (target_seconds / 2) / max(dt, 1e-6)
         n = int(min(P, max(n + 1, n * min(scale, 16))))
     nbytes, dt, n = best
-    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count()
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    # context only: the same loops split over receiver ranks on all usable host cores
+    import threading
+    nthr = max(1, min(cores, n))
+    parts = np.array_split(np.arange(n, dtype=np.int32), nthr)
+
+    def work(sel):
+        oracle.alltoallv_receivers(send_host, lay.sendcounts, lay.sdispls, recv_host, lay.recvcounts, lay.rdispls, sel)
+    threads = [threading.Thread(target=work, args=(sel,)) for sel in parts if sel.size]
+    t1 = time.perf_counter()
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    dt_par = time.perf_counter() - t1
     return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
             "sample": "receive side of the first %d of %d ranks (%.3f GiB of payload), one thread, %.2f s; "
-                      "host has %d usable cores" % (n, P, nbytes / 2**30, dt, cores)}
+                      "host has %d usable cores" % (n, P, nbytes / 2**30, dt, cores),
+            "all_cores": {"value": nbytes / dt_par / 1e9, "unit": "GB/s", "threads": len(threads),
+                          "note": "the same oracle called from one thread per slice of receiver ranks"}}
 
 
 if __name__ == "__main__":

@@ -194,6 +194,23 @@ int tuna_plan_info(int P, int ranks_per_node, int local_radix, int global_radix,
 int tuna_plan_phase(int P, int ranks_per_node, int local_radix, int global_radix, int phase,
                     int32_t* header, int32_t* seg, int seg_capacity);
 
+/*
+ * Radix choice for one GPU.  The paper picks r from P and the block size because each of its K
+ * rounds pays a network latency (Section "Performance analysis of TuNA", "Radix selection":
+ * small blocks -> r near 2, medium -> r near sqrt(P), large -> r near P).  In one HBM a round has
+ * no latency of its own; the cost model of a call is
+ *     t(r) = t_call(P) + w(r) * t_phase(P) + c * H(r) * payload_bytes / BW,
+ * c = 6 (pack, exchange, unpack each read and write the moving bytes) or 2 with fused rounds,
+ * H(r) = average number of hops of a block = sum over digit positions of the share of indices
+ * whose digit is non-zero, w(r) = digits, with t_call, t_phase and BW measured on MI355X.
+ * Evaluates the model for the candidate radices 2, 4, 8, ..., ceil(sqrt(size)), size of each
+ * dimension and returns the minimiser (host only; *predicted_ms may be NULL).  Both H and w
+ * fall as r grows, so the answer is the linear schedule r = Q, r = N for every payload; the
+ * function exists so that callers do not hard-code that and so that the model is testable.
+ */
+int tuna_select_radix(int P, int ranks_per_node, int64_t payload_bytes, int* local_radix,
+                      int* global_radix, double* predicted_ms);
+
 /* Slot of block index o (1 <= o, not a direct block) in T for radix r:
  * t = o - 1 - dx (r - 1) - dz with dx the position and dz the value of o's highest base-r digit
  * (Section "Estimating temporary buffer size").  Returns -1 for o <= 0 or a direct block. */

@@ -28,7 +28,7 @@ TUNA_MAX_PHASES = 64
 
 EXPORTS = ("tuna_alltoallv", "tuna_alltoallv_hier", "tuna_workspace_bytes", "tuna_set_workspace",
            "tuna_release", "tuna_set_option", "tuna_get_stats", "tuna_plan_info", "tuna_plan_phase",
-           "tuna_t_index", "tuna_plain_copy",
+           "tuna_t_index", "tuna_plain_copy", "tuna_select_radix",
            "tuna_strerror", "tuna_version")
 
 
@@ -95,6 +95,8 @@ def load() -> ctypes.CDLL:
     lib.tuna_get_stats.argtypes = [ctypes.POINTER(tuna_stats_t)]
     lib.tuna_plan_info.argtypes = [i, i, i, i, ctypes.POINTER(tuna_plan_info_t)]
     lib.tuna_plan_phase.argtypes = [i, i, i, i, i, vp, vp, i]
+    lib.tuna_select_radix.argtypes = [i, i, ctypes.c_int64, ctypes.POINTER(ctypes.c_int),
+                                      ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_double)]
     lib.tuna_t_index.argtypes = [i, i]
     lib.tuna_plain_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.tuna_strerror.argtypes = [i]
@@ -195,6 +197,14 @@ def tuna_plan_phase(P: int, ranks_per_node: int, local_radix: int, global_radix:
     rc = lib.tuna_plan_phase(P, ranks_per_node, local_radix, global_radix, phase, header.ctypes.data,
                              seg.ctypes.data, seg.shape[0])
     return rc, header, seg
+
+
+def tuna_select_radix(P: int, ranks_per_node: int, payload_bytes: int):
+    """Returns (code, local_radix, global_radix, predicted_ms).  Host only."""
+    rl, rg, ms = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_double(0.0)
+    rc = load().tuna_select_radix(P, ranks_per_node, payload_bytes, ctypes.byref(rl), ctypes.byref(rg),
+                                  ctypes.byref(ms))
+    return rc, rl.value, rg.value, ms.value
 
 
 def tuna_t_index(o: int, radix: int) -> int:

@@ -606,6 +606,43 @@ int tuna_plan_phase(int P, int ranks_per_node, int local_radix, int global_radix
     return TUNA_OK;
 }
 
+int tuna_select_radix(int P, int ranks_per_node, int64_t payload_bytes, int* local_radix, int* global_radix,
+                      double* predicted_ms) {
+    if (!local_radix || !global_radix || payload_bytes < 0) return TUNA_ERR_ARG;
+    int Q = 0;
+    int rc = resolve_hierarchy(P, ranks_per_node, &Q);
+    if (rc != TUNA_OK) return rc;
+    const int N = P / Q;
+    // measured on MI355X at P = 4096 (see profiles/): copy stages ~5.2e12 B/s, metadata kernels of
+    // a phase ~60 us + 20 ps per matrix entry, validation + rotation ~0.3 ms at P = 4096
+    const double bw = 5.2e12, c = g.opt_fused ? 2.0 : 6.0;
+    const double t_phase = 60e-6 + 2.0e-11 * (double)P * P, t_call = 50e-6 + 1.5e-11 * (double)P * P;
+    auto hops = [](int size, int r) {           // H(r) over one dimension
+        long long nz = 0;
+        for (int i = 0; i < size; ++i)
+            for (int v = i; v; v /= r) nz += (v % r) != 0;
+        return (double)nz / size;
+    };
+    auto best = [&](int size, int* radix) -> double {
+        if (size < 2) { *radix = 2; return 0.0; }
+        std::vector<int> cand;
+        for (long long r = 2; r < size; r *= 2) cand.push_back((int)r);
+        int sq = 2;
+        while ((long long)sq * sq < size) ++sq;
+        cand.push_back(sq);
+        cand.push_back(size);
+        double bt = -1.0;
+        for (int r : cand) {
+            const double t = num_digits(size, r) * t_phase + c * hops(size, r) * (double)payload_bytes / bw;
+            if (bt < 0 || t < bt) { bt = t; *radix = r; }
+        }
+        return bt;
+    };
+    const double tl = best(Q, local_radix), tg = best(N, global_radix);
+    if (predicted_ms) *predicted_ms = (t_call + tl + tg) * 1e3;
+    return TUNA_OK;
+}
+
 int tuna_t_index(int o, int radix) {
     if (radix < 2) return -1;
     return (int)t_index(o, radix);

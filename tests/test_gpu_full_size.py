@@ -32,6 +32,18 @@ def _upload(lay):
     return [torch.from_numpy(a).to(dev) for a in (lay.sendcounts, lay.sdispls, lay.recvcounts, lay.rdispls)]
 
 
+def _modes(tuna):
+    """Three-stage phases, fused rounds, and (for hierarchical calls) the staggered schedule."""
+    yield "staged", lambda: None
+    yield "fused", lambda: tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 1)
+    yield "staggered", lambda: tuna.tuna_set_option(tuna.TUNA_OPT_STAGGERED, 1)
+
+
+def _reset_modes(tuna):
+    tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+    tuna.tuna_set_option(tuna.TUNA_OPT_STAGGERED, 0)
+
+
 def _whole_oracle_case(tuna, cfg_id, calls):
     c = wl.CONFIGS[cfg_id]
     lay = wl.make_layout(wl.make_counts(cfg_id))
@@ -43,13 +55,19 @@ def _whole_oracle_case(tuna, cfg_id, calls):
     send = torch.from_numpy(send_host).to("cuda:0")
     recv = torch.empty(lay.recv_bytes, dtype=torch.uint8, device="cuda:0")
     sc, sd, rc, rd = _upload(lay)
-    for label, fn in calls(lay.P):
-        recv.zero_()
-        print("config %d full size, %s" % (cfg_id, label), flush=True)
-        code = fn(send, sc, sd, recv, rc, rd)
-        assert code == 0, tuna.tuna_strerror(code)
-        torch.cuda.synchronize()
-        assert torch.equal(recv, want_dev), "config %d %s differs from the oracle" % (cfg_id, label)
+    try:
+        for mode, enable in _modes(tuna):
+            enable()
+            for label, fn in calls(lay.P):
+                recv.zero_()
+                print("config %d full size, %s, %s" % (cfg_id, mode, label), flush=True)
+                code = fn(send, sc, sd, recv, rc, rd)
+                assert code == 0, tuna.tuna_strerror(code)
+                torch.cuda.synchronize()
+                assert torch.equal(recv, want_dev), "config %d %s %s differs from the oracle" % (cfg_id, mode, label)
+            _reset_modes(tuna)
+    finally:
+        _reset_modes(tuna)
     assert torch.equal(send, torch.from_numpy(send_host).to("cuda:0"))
 
 
@@ -63,7 +81,7 @@ def test_config3_full_hierarchical(tuna):
                        s, sc, sd, r, rc, rd, P, c.ranks_per_node, c.local_radix, rg))
     _whole_oracle_case(tuna, 3, calls)
     st = tuna.tuna_get_stats()
-    assert (st.Q, st.N, st.K_local, st.K_global) == (16, 64, 6, 63)
+    assert (st.Q, st.N, st.K_local, st.K_global) == (16, 64, 6, 16 * 63)     # the last mode run is the staggered one
 
 
 def test_config5_full_uniform(tuna):
@@ -75,7 +93,7 @@ def test_config5_full_uniform(tuna):
                 s, sc, sd, rcv, rc, rd, P, r, c.ranks_per_node))
     _whole_oracle_case(tuna, 5, calls)
     st = tuna.tuna_get_stats()
-    assert (st.local_radix, st.global_radix, st.K_local, st.K_global) == (32, 64, 31, 63)
+    assert (st.local_radix, st.global_radix, st.K_local, st.K_global) == (32, 64, 31, 32 * 63)
 
 
 def test_config4_full(tuna):
@@ -102,10 +120,13 @@ def test_config4_full(tuna):
     send_sum = int(send.view(torch.int32).sum(dtype=torch.int64))
     counts_w = (sc.to(torch.int64) // 4)                      # [i, j] words of block i -> j
     sd_w = sd // 4
-    for r in c.radices:
+    cases = [(r, 0) for r in c.radices] + [(2, 1), (4096, 1)]          # (radix, fused rounds)
+    for r, fused in cases:
         recv.zero_()
-        print("config 4 full size, radix=%d" % r, flush=True)
+        print("config 4 full size, radix=%d fused=%d" % (r, fused), flush=True)
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, fused)
         code = tuna.tuna_alltoallv(send, sc, sd, recv, rc, rd, P, r, 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
         assert code == 0, tuna.tuna_strerror(code)
         torch.cuda.synchronize()
         for (lo, hi), w in zip(regions, want_regions):

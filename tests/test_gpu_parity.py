@@ -188,6 +188,19 @@ def test_staggered_inter_node_schedule(tuna, Q, N):
         tuna.tuna_set_option(tuna.TUNA_OPT_STAGGERED, 0)
 
 
+@pytest.mark.parametrize("pattern", ["n1", "n2"])
+def test_fft_count_patterns(tuna, pattern):
+    """The two closed-form count matrices of the paper's FFT runs: sparse (37.5 % of the ranks
+    send nothing, the last 22 % of the blocks are empty) and near uniform."""
+    P = 192
+    counts = wl.counts_fft_n1(P) if pattern == "n1" else wl.counts_fft_n2(P)
+    lay = wl.make_layout(counts)
+    prob = Problem(lay, wl.payload_position_hash(70, lay.send_bytes))
+    for r in (2, 14, P):
+        run_flat(tuna, prob, r)
+    run_hier(tuna, prob, 16, 4, 12)
+
+
 def test_degenerate_inputs(tuna):
     # all blocks empty
     lay = wl.make_layout(np.zeros((9, 9), dtype=np.int32), gap=4)

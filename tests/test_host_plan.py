@@ -227,3 +227,17 @@ def test_staggered_option_schedule(golden):
         assert info.K_global == 0 and info.K_local == 4
     finally:
         tuna.tuna_set_option(tuna.TUNA_OPT_STAGGERED, 0)
+
+
+def test_select_radix_model():
+    """One HBM has no per-round latency: the model's minimiser is the linear schedule, and the
+    predicted time of configuration 4 at r = P is the three-stage bound 6 * payload / bandwidth
+    plus a few hundred microseconds."""
+    rc, rl, rg, ms = tuna.tuna_select_radix(4096, 0, 16 << 30)
+    assert rc == 0 and rl == 4096
+    assert 6 * (16 << 30) * 4095 / 4096 / 5.2e12 * 1e3 < ms < 6 * (16 << 30) / 5.2e12 * 1e3 + 1.5
+    rc, rl, rg, ms = tuna.tuna_select_radix(1024, 16, 1 << 30)
+    assert rc == 0 and (rl, rg) == (16, 64)
+    rc, rl, rg, ms_small = tuna.tuna_select_radix(256, 0, 1 << 10)
+    assert rc == 0 and rl == 256 and ms_small < 1.0
+    assert tuna.tuna_select_radix(12, 5, 100)[0] == tuna.TUNA_ERR_ARG

@@ -186,6 +186,19 @@ def test_generators_are_seeded_and_shaped():
     assert np.array_equal(a[333:433], b)
 
 
+def test_fft_patterns_have_the_stated_totals():
+    """Section "Fast Fourier transform": N1 = ceil(0.78125 P) ceil(0.625 P) 8 and
+    N2 = ((P - 1) 32 + 8) P complex values of two FP64 each ... the count matrices must add up
+    to the stated problem sizes (N1 counts FP64 values, N2 complex values)."""
+    import math
+    for P in (8, 64, 200):
+        n1 = wl.counts_fft_n1(P)
+        assert int(n1.sum()) // 8 == math.ceil(0.78125 * P) * math.ceil(0.625 * P) * 8
+        assert (n1[math.ceil(0.625 * P):] == 0).all() and (n1[:, math.ceil(0.78125 * P):] == 0).all()
+        n2 = wl.counts_fft_n2(P)
+        assert int(n2.sum()) // 16 == ((P - 1) * 32 + 8) * P
+
+
 def test_torch_payload_matches_numpy_payload():
     import torch
 

@@ -90,6 +90,25 @@ def counts_constant(P: int, nbytes: int) -> np.ndarray:
     return np.full((P, P), nbytes, dtype=np.int32)
 
 
+def counts_fft_n1(P: int) -> np.ndarray:
+    """The sparse FFT transpose pattern (Section "Fast Fourier transform", problem size N1): only
+    ranks below ceil(0.625 P) hold data, and each of them fills its first ceil(0.78125 P) blocks
+    with 8 FP64 values (64 bytes); every other block is empty."""
+    workers = math.ceil(0.625 * P)
+    filled = math.ceil(0.78125 * P)
+    c = np.zeros((P, P), dtype=np.int32)
+    c[:workers, :filled] = 8 * 8
+    return c
+
+
+def counts_fft_n2(P: int) -> np.ndarray:
+    """The near-uniform FFT pattern (same section, problem size N2): every rank but the last sends
+    64 FP64 values (512 bytes) per block, the last rank 16 FP64 values (128 bytes)."""
+    c = np.full((P, P), 64 * 8, dtype=np.int32)
+    c[P - 1, :] = 16 * 8
+    return c
+
+
 # ----------------------------------------------------------------------------
 # the five configurations
 # ----------------------------------------------------------------------------
