@@ -665,9 +665,30 @@ k_copy(const CopyArgs a) {
                 if (MODE == kUnpack || MODE == kFused) {
                     unsigned char* dst = reinterpret_cast<unsigned char*>(MODE == kFused ? oa2[k] : oa[k]);
                     store_block_chunk<GRAN>(dst, v[k], nb[k]);
-                    for (int f = 1; f <= fill[k]; ++f) *reinterpret_cast<v4u*>(dst + 16 * f) = v[k];
                 } else {
                     __builtin_nontemporal_store(v[k], stage + c[k]);
+                }
+            }
+        }
+        // ---- line fill: after the last chunk of a T-bound block the rest of its 128-byte line is
+        // written too (content is don't-care), so that T only ever sees whole-line writes.  One
+        // store instruction per block tail: lanes 0..f-1 write the f missing chunks.
+        if (MODE == kUnpack || MODE == kFused) {
+#pragma unroll
+            for (int k = 0; k < kChunksPerLane; ++k) {
+                const unsigned long long dsta = MODE == kFused ? oa2[k] : oa[k];
+                unsigned long long m = __ballot(act[k] && !slow[k] && fill[k] > 0);
+                while (m) {
+                    const int leader = __ffsll((long long)m) - 1;
+                    m &= m - 1;
+                    const unsigned int lo32 = __builtin_amdgcn_readlane((unsigned int)dsta, leader);
+                    const unsigned int hi32 = __builtin_amdgcn_readlane((unsigned int)(dsta >> 32), leader);
+                    const int f = __builtin_amdgcn_readlane(fill[k], leader);
+                    if (lane < f) {
+                        const v4u zero = {0u, 0u, 0u, 0u};
+                        unsigned char* base = reinterpret_cast<unsigned char*>(((unsigned long long)hi32 << 32) | lo32);
+                        *reinterpret_cast<v4u*>(base + 16 * (lane + 1)) = zero;
+                    }
                 }
             }
         }

@@ -149,3 +149,51 @@ def test_config4_full(tuna):
             got = recv_w[lo:lo + total].to(torch.int64) & 0xFFFFFFFF
             assert torch.equal(got, expect), "radix %d: receivers %d..%d differ" % (r, j0, j1)
             del seg, src_word, expect, got
+
+
+def test_one_block_of_a_gibibyte(tuna):
+    """Maximum block sizes: P = 2 with one block of 1 GiB + 20 bytes (67 million chunks in one
+    segment, many wave units per segment) next to a 3-byte block."""
+    counts = np.array([[5, (1 << 30) + 20], [3, 0]], dtype=np.int32)
+    lay = wl.make_layout(counts, gap=9)
+    send = wl.payload_position_hash_torch(321, lay.send_bytes, "cuda:0")
+    send_host = send.cpu().numpy()
+    want = np.full(lay.recv_bytes, 0x3C, dtype=np.uint8)
+    assert oracle.alltoallv(send_host, lay.sendcounts, lay.sdispls, want, lay.recvcounts, lay.rdispls) == 0
+    want_dev = torch.from_numpy(want).to("cuda:0")
+    sc, sd, rc, rd = _upload(lay)
+    recv = torch.empty(lay.recv_bytes, dtype=torch.uint8, device="cuda:0")
+    for fused in (0, 1):
+        recv.fill_(0x3C)
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, fused)
+        code = tuna.tuna_alltoallv(send, sc, sd, recv, rc, rd, 2, 2, 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+        assert code == 0, tuna.tuna_strerror(code)
+        torch.cuda.synchronize()
+        assert torch.equal(recv, want_dev)
+    assert tuna.tuna_get_stats().max_block_bytes == (1 << 30) + 20
+
+
+def test_many_ranks_small_blocks(tuna):
+    """P = 8192 (67 million blocks of 0..60 bytes, 4-byte granular): flat with radix 2 (13 digit
+    phases) and radix P, and 64 ranks per node x 128 nodes; whole result against the oracle."""
+    P = 8192
+    counts = wl.counts_uniform_elements(P, 8192, 15, 4)
+    lay = wl.make_layout(counts)
+    send_host = wl.payload_position_hash(8192, lay.send_bytes)
+    want = np.zeros(lay.recv_bytes, dtype=np.uint8)
+    assert oracle.alltoallv(send_host, lay.sendcounts, lay.sdispls, want, lay.recvcounts, lay.rdispls) == 0
+    want_dev = torch.from_numpy(want).to("cuda:0")
+    del want
+    send = torch.from_numpy(send_host).to("cuda:0")
+    sc, sd, rc, rd = _upload(lay)
+    recv = torch.empty(lay.recv_bytes, dtype=torch.uint8, device="cuda:0")
+    for radix, rpn in ((2, 0), (P, 0), (8, 64)):
+        recv.zero_()
+        print("P=8192 radix=%d ranks_per_node=%d" % (radix, rpn), flush=True)
+        code = tuna.tuna_alltoallv(send, sc, sd, recv, rc, rd, P, radix, rpn)
+        assert code == 0, tuna.tuna_strerror(code)
+        torch.cuda.synchronize()
+        assert torch.equal(recv, want_dev), (radix, rpn)
+    st = tuna.tuna_get_stats()
+    assert (st.Q, st.N, st.w_local, st.w_global) == (64, 128, 2, 3)
