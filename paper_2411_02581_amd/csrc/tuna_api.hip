@@ -236,15 +236,14 @@ int launch_copy(int gran, size_t unit_cap, const CopyArgs& a, hipStream_t s) {
     return TUNA_OK;
 }
 
-int build_layout(const int32_t* sizes, const SegDev& seg, int nseg, int P, int Q, int N, const LayoutDev& L,
-                 unsigned long long* phase_bytes, unsigned long long* phase_chunks,
-                 const int64_t* head_displs, unsigned int head_base, hipStream_t s) {
-    hipLaunchKernelGGL(k_layout_scan, dim3(P), dim3(kScanThreads), 0, s, sizes, seg, nseg, P, L, phase_bytes,
-                       head_displs, head_base, Q, N);
+// Metadata of one digit phase: sizes exchanged, both staging layouts scanned, wave units cut.
+int phase_metadata(const PhaseLayoutArgs& a, hipStream_t s) {
+    hipLaunchKernelGGL(k_phase_layout, dim3(a.P), dim3(kScanThreads), 0, s, a);
     HIPCHK(hipGetLastError());
-    hipLaunchKernelGGL(k_layout_base, dim3(1), dim3(1024), 0, s, P, L, phase_chunks);
+    hipLaunchKernelGGL(k_layout_base, dim3(a.want_send ? 2 : 1), dim3(kScanThreads), 0, s, a.P, a.Lr, a.Ls,
+                       a.phase_chunks, a.want_send ? 1 : 0);
     HIPCHK(hipGetLastError());
-    hipLaunchKernelGGL(k_layout_units, dim3(P), dim3(256), 0, s, nseg, L);
+    hipLaunchKernelGGL(k_layout_units, dim3(a.P, a.want_send ? 2 : 1), dim3(256), 0, s, a.nseg, a.Lr, a.Ls);
     HIPCHK(hipGetLastError());
     return TUNA_OK;
 }
@@ -380,19 +379,16 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
         if (staggered && ph.dim == 1) ps.rounds = Q * (N - 1);
         ps.blocks = (int64_t)ph.nseg * P;
         const SegDev seg = dp->d_seg[i];
-        // metadata exchange, then the send-side and receive-side layouts
-        hipLaunchKernelGGL(k_meta_exchange, dim3(gP2), dim3(256), 0, s, cur, nxt, dp->d_zt[i], P, Q, N, ph.dim,
-                           (int)ph.rx);
-        HIPCHK(hipGetLastError());
-        if (one_kernel) {   // only the receive-side layout is needed
-            rc = build_layout(nxt, seg, ph.nseg, P, Q, N, mb.Lr, &g.d_status->phase_bytes[i],
-                              &g.d_status->phase_chunks[i], rdispls, (unsigned int)((uintptr_t)recvbuf & 15u), s);
-            if (rc != TUNA_OK) return rc;
-        } else {
-            rc = build_layout(cur, seg, ph.nseg, P, Q, N, mb.Ls, &g.d_status->phase_bytes[i],
-                              &g.d_status->phase_chunks[i], nullptr, 0u, s);
-            if (rc != TUNA_OK) return rc;
-            rc = build_layout(nxt, seg, ph.nseg, P, Q, N, mb.Lr, nullptr, nullptr, nullptr, 0u, s);
+        // metadata exchange and the send-side and receive-side layouts
+        {
+            PhaseLayoutArgs m{};
+            m.cur = cur; m.nxt = nxt; m.zt = dp->d_zt[i]; m.seg = seg; m.nseg = ph.nseg;
+            m.P = P; m.Q = Q; m.N = N; m.dim = ph.dim; m.rx = (int)ph.rx;
+            m.Ls = mb.Ls; m.Lr = mb.Lr; m.want_send = one_kernel ? 0 : 1;
+            m.phase_bytes = &g.d_status->phase_bytes[i]; m.phase_chunks = &g.d_status->phase_chunks[i];
+            m.head_displs = one_kernel ? rdispls : nullptr;
+            m.head_base = (unsigned int)((uintptr_t)recvbuf & 15u);
+            rc = phase_metadata(m, s);
             if (rc != TUNA_OK) return rc;
         }
         mark(s, kCatMeta, (int)i);

@@ -235,156 +235,194 @@ __global__ void __launch_bounds__(256) k_self_copy(const unsigned char* __restri
 }
 
 // ------------------------------------------------------------------------------------------
-// k_meta_exchange: the metadata phase of a digit phase (Section "Two-phase communication";
-// Algorithm "TuNA", line 14).  Every moving block's size travels from the sender's size array to
-// the receiver's: nxt[q][e] = cur[q + z r^x][e] where z = digit of e, and sizes of blocks that
-// stay are carried over.  One thread per (rank, slot).
+// k_phase_layout: all metadata work of one digit phase in one launch, one workgroup per rank.
+//  (1) metadata exchange (Section "Two-phase communication"; Algorithm "TuNA", line 14): the size
+//      of every moving block travels from the sender's size array to the receiver's,
+//      nxt[q][e] = cur[q + z r^x][e] with z the digit of e; sizes of blocks that stay are carried over;
+//  (2) size/displacement scans (the contiguous send buffer of Algorithm "TuNA", line 15, needs each
+//      block's offset inside its message): per rank, the moving blocks' sizes in message order are
+//      converted to 16-byte chunks and exclusive-scanned (wave shuffles + LDS across the 4 waves,
+//      a running carry across batches of 1024 segments) -- once over the sizes the rank receives
+//      (receive-side layout) and once over the sizes it sends (send-side layout);
+// With `head_displs` (one-kernel phases) the chunks of a block bound for R are cut at the 16-byte
+// boundaries of its destination address: a block that starts `a` bytes into a 16-byte line takes
+// ceil((a + size) / 16) chunks; head_base is the low 4 bits of the receive buffer address.
 // ------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) k_meta_exchange(const int32_t* __restrict__ cur,
-                                                       int32_t* __restrict__ nxt,
-                                                       const int32_t* __restrict__ zt,
-                                                       int P, int Q, int N, int dim, int rx) {
-    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (size_t)P * P) return;
-    const int q = (int)(idx / P), e = (int)(idx - (size_t)q * P);
-    const int z = zt[e];
-    int v;
-    if (z == 0) {
-        v = cur[idx];
-    } else {
-        const int n = q / Q, g = q - n * Q;
-        const int s = partner_up(n, g, Q, N, dim, z * rx);
-        v = cur[(size_t)s * P + e];
+struct PhaseLayoutArgs {
+    const int32_t* cur;
+    int32_t* nxt;
+    const int32_t* zt;              // [P] digit value of slot e in this phase (0: stays)
+    SegDev seg;
+    int nseg;
+    int P, Q, N, dim, rx;
+    LayoutDev Ls, Lr;
+    int want_send;                  // 0: only the receive-side layout (one-kernel phases)
+    unsigned long long* phase_bytes;
+    unsigned long long* phase_chunks;
+    const int64_t* head_displs;
+    unsigned int head_base;
+};
+
+// exclusive scan of c[] (kScanItems consecutive items per thread) over the workgroup; returns the
+// thread's running start and adds the batch total to `carry`
+__device__ __forceinline__ int block_scan_batch(const int (&c)[kScanItems], int& carry, int* wsum) {
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    int sum = 0;
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k) sum += c[k];
+    const int incl = wave_incl_scan(sum);
+    __syncthreads();                                  // wsum of the previous batch is consumed
+    if (lane == kWave - 1) wsum[wv] = incl;
+    __syncthreads();
+    int woff = 0, total = 0;
+#pragma unroll
+    for (int k = 0; k < kScanThreads / kWave; ++k) {
+        const int v = wsum[k];
+        if (k < wv) woff += v;
+        total += v;
     }
-    nxt[idx] = v;
+    const int run = carry + woff + incl - sum;
+    carry += total;
+    return run;
 }
 
-// ------------------------------------------------------------------------------------------
-// k_layout_scan: size/displacement scan of one rank's moving blocks (the contiguous send buffer
-// of Algorithm "TuNA", line 15, needs each block's offset inside its message).  One workgroup
-// per rank: gathers the sizes in message order, converts to 16-byte chunks, exclusive scan with
-// wave shuffles + LDS across the 4 waves, a running carry across batches of 1024 segments.
-// With `head_displs` (fused rounds) the chunks of a block bound for R are cut at the 16-byte
-// boundaries of its destination address, so a block that starts `a` bytes into a 16-byte line
-// takes ceil((a + size) / 16) chunks; head_base is the low 4 bits of the receive buffer address.
-// ------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(kScanThreads) k_layout_scan(const int32_t* __restrict__ sizes,
-                                                              const SegDev seg, int nseg,
-                                                              int P, LayoutDev L,
-                                                              unsigned long long* __restrict__ phase_bytes,
-                                                              const int64_t* __restrict__ head_displs,
-                                                              unsigned int head_base, int Q, int N) {
-    __shared__ int wsum[kScanThreads / kWave];
-    const int p = blockIdx.x;
-    const int pn = p / Q, pg = p - pn * Q;
+// exclusive scan over the P per-rank totals of one layout by one workgroup of kScanThreads: every
+// thread sums a contiguous range of ranks, the thread sums are scanned across the workgroup, then
+// every thread writes the bases of its range
+__device__ __forceinline__ void scan_rank_bases(int P, const LayoutDev& L, unsigned long long* phase_chunks,
+                                                long long* wc, int* wt) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
-    const int32_t* row = sizes + (size_t)p * P;
-    int* pre = L.pre + (size_t)p * L.ld;
-    int carry = 0;
-    unsigned long long bytes = 0;
-    for (int base = 0; base < nseg; base += kScanThreads * kScanItems) {
-        int c[kScanItems];
-        int sum = 0;
-#pragma unroll
-        for (int k = 0; k < kScanItems; ++k) {
-            const int s = base + tid * kScanItems + k;
-            int sz = 0, head = 0;
-            if (s < nseg) {
-                const int e = seg.e[s];
-                sz = row[e];
-                if (head_displs && sz > 0 && seg.dst[s] < 0) {
-                    int j, l;
-                    split_slot_index(e, Q, N, j, l);
-                    int sn = pn + j; if (sn >= N) sn -= N;
-                    int sg = pg + l; if (sg >= Q) sg -= Q;
-                    head = (int)(((unsigned int)head_displs[(size_t)p * P + sn * Q + sg] + head_base) & 15u);
-                }
-            }
-            bytes += (unsigned long long)sz;
-            c[k] = (head + sz + 15) >> 4;
-            sum += c[k];
-        }
-        const int incl = wave_incl_scan(sum);
-        if (lane == kWave - 1) wsum[wv] = incl;
-        __syncthreads();
-        int woff = 0, total = 0;
-#pragma unroll
-        for (int k = 0; k < kScanThreads / kWave; ++k) {
-            const int v = wsum[k];
-            if (k < wv) woff += v;
-            total += v;
-        }
-        int run = carry + woff + incl - sum;
-#pragma unroll
-        for (int k = 0; k < kScanItems; ++k) {
-            const int s = base + tid * kScanItems + k;
-            if (s < nseg) pre[s] = run;
-            run += c[k];
-        }
-        carry += total;
-        __syncthreads();
+    const int per = (P + kScanThreads - 1) / kScanThreads;
+    const int p0 = min(P, tid * per), p1 = min(P, p0 + per);
+    long long sc = 0;
+    int st = 0;
+    for (int p = p0; p < p1; ++p) {
+        const int c = L.tot[p];
+        sc += c;
+        st += (c + kUnitChunks - 1) / kUnitChunks;
     }
-    // per-rank totals and payload bytes of the phase
+    long long ic = sc;
+    int it = st;
 #pragma unroll
-    for (int d = kWave / 2; d > 0; d >>= 1) bytes += __shfl_xor(bytes, d, kWave);
-    if (lane == 0 && bytes && phase_bytes) atomicAdd(phase_bytes, bytes);
-    if (tid == 0) { pre[nseg] = carry; L.tot[p] = carry; }
-}
-
-// ------------------------------------------------------------------------------------------
-// k_layout_base: exclusive scan over the P per-rank totals -> each rank's first chunk in the
-// staging buffer and its first wave unit.  Single workgroup of 1024 threads, carry across batches.
-// ------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(1024) k_layout_base(int P, LayoutDev L,
-                                                      unsigned long long* __restrict__ phase_chunks) {
-    __shared__ long long wc[16];
-    __shared__ int wt[16];
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
-    long long carry_c = 0;
-    int carry_t = 0;
-    for (int base = 0; base < P; base += 1024) {
-        const int p = base + tid;
-        const int c = p < P ? L.tot[p] : 0;
-        const int t = (c + kUnitChunks - 1) / kUnitChunks;
-        long long ic = c;
-        int it = t;
+    for (int d = 1; d < kWave; d <<= 1) {
+        long long uc = __shfl_up(ic, d, kWave);
+        int ut = __shfl_up(it, d, kWave);
+        if (lane >= d) { ic += uc; it += ut; }
+    }
+    if (lane == kWave - 1) { wc[wv] = ic; wt[wv] = it; }
+    __syncthreads();
+    long long oc = 0, totc = 0;
+    int ot = 0, tott = 0;
 #pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            long long uc = __shfl_up(ic, d, kWave);
-            int ut = __shfl_up(it, d, kWave);
-            if (lane >= d) { ic += uc; it += ut; }
-        }
-        if (lane == kWave - 1) { wc[wv] = ic; wt[wv] = it; }
-        __syncthreads();
-        long long oc = 0, totc = 0;
-        int ot = 0, tott = 0;
-#pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            if (k < wv) { oc += wc[k]; ot += wt[k]; }
-            totc += wc[k]; tott += wt[k];
-        }
-        if (p < P) {
-            L.rank_base[p] = carry_c + oc + ic - c;
-            L.unit_base[p] = carry_t + ot + it - t;
-        }
-        carry_c += totc;
-        carry_t += tott;
-        __syncthreads();
+    for (int k = 0; k < kScanThreads / kWave; ++k) {
+        if (k < wv) { oc += wc[k]; ot += wt[k]; }
+        totc += wc[k]; tott += wt[k];
+    }
+    long long run_c = oc + ic - sc;
+    int run_t = ot + it - st;
+    for (int p = p0; p < p1; ++p) {
+        const int c = L.tot[p];
+        L.rank_base[p] = run_c;
+        L.unit_base[p] = run_t;
+        run_c += c;
+        run_t += (c + kUnitChunks - 1) / kUnitChunks;
     }
     if (tid == 0) {
-        L.rank_base[P] = carry_c;
-        L.unit_base[P] = carry_t;
-        *L.n_units = carry_t;
-        if (phase_chunks) *phase_chunks = (unsigned long long)carry_c;
+        L.rank_base[P] = totc;
+        L.unit_base[P] = tott;
+        *L.n_units = tott;
+        if (phase_chunks) *phase_chunks = (unsigned long long)totc;
     }
+}
+
+__global__ void __launch_bounds__(kScanThreads) k_phase_layout(const PhaseLayoutArgs a) {
+    __shared__ int wsum[kScanThreads / kWave];
+    const int p = blockIdx.x;
+    const int P = a.P;
+    const int pn = p / a.Q, pg = p - pn * a.Q;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int32_t* crow = a.cur + (size_t)p * P;
+    int32_t* nrow = a.nxt + (size_t)p * P;
+    // (1a) blocks that do not move in this phase keep their size
+    for (int e = tid; e < P; e += kScanThreads)
+        if (a.zt[e] == 0) nrow[e] = crow[e];
+    // (1b) + (2) receive side: sizes arrive from the partner at distance z r^x, then the scan
+    int* pre_r = a.Lr.pre + (size_t)p * a.Lr.ld;
+    int* pre_s = a.Ls.pre + (size_t)p * a.Ls.ld;
+    int carry_r = 0, carry_s = 0;
+    unsigned long long bytes = 0;
+    for (int base = 0; base < a.nseg; base += kScanThreads * kScanItems) {
+        int cr[kScanItems], cs[kScanItems];
+#pragma unroll
+        for (int k = 0; k < kScanItems; ++k) {
+            const int s = base + tid * kScanItems + k;
+            int szr = 0, szs = 0, head = 0;
+            if (s < a.nseg) {
+                const int e = a.seg.e[s];
+                const int ps = partner_up(pn, pg, a.Q, a.N, a.dim, a.seg.z[s] * a.rx);
+                szr = a.cur[(size_t)ps * P + e];
+                nrow[e] = szr;
+                if (a.want_send) szs = crow[e];
+                if (a.head_displs && szr > 0 && a.seg.dst[s] < 0) {
+                    int j, l;
+                    split_slot_index(e, a.Q, a.N, j, l);
+                    int sn = pn + j; if (sn >= a.N) sn -= a.N;
+                    int sg = pg + l; if (sg >= a.Q) sg -= a.Q;
+                    head = (int)(((unsigned int)a.head_displs[(size_t)p * P + sn * a.Q + sg] + a.head_base) & 15u);
+                }
+            }
+            bytes += (unsigned long long)(a.want_send ? szs : szr);
+            cr[k] = (head + szr + 15) >> 4;
+            cs[k] = (szs + 15) >> 4;
+        }
+        int run = block_scan_batch(cr, carry_r, wsum);
+#pragma unroll
+        for (int k = 0; k < kScanItems; ++k) {
+            const int s = base + tid * kScanItems + k;
+            if (s < a.nseg) pre_r[s] = run;
+            run += cr[k];
+        }
+        if (a.want_send) {
+            run = block_scan_batch(cs, carry_s, wsum);
+#pragma unroll
+            for (int k = 0; k < kScanItems; ++k) {
+                const int s = base + tid * kScanItems + k;
+                if (s < a.nseg) pre_s[s] = run;
+                run += cs[k];
+            }
+        }
+    }
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) bytes += __shfl_xor(bytes, d, kWave);
+    if (lane == 0 && bytes && a.phase_bytes) atomicAdd(a.phase_bytes, bytes);
+    if (tid == 0) {
+        pre_r[a.nseg] = carry_r; a.Lr.tot[p] = carry_r;
+        if (a.want_send) { pre_s[a.nseg] = carry_s; a.Ls.tot[p] = carry_s; }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// k_layout_base: exclusive scan over the P per-rank totals of a layout -> each rank's first chunk
+// in its staging buffer and its first wave unit.  One workgroup per layout (x = 0 receive side,
+// 1 send side).  A separate launch rather than a "last workgroup" step inside k_phase_layout:
+// the kernel boundary is the one device-wide release the totals need.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kScanThreads) k_layout_base(int P, LayoutDev Lr, LayoutDev Ls,
+                                                              unsigned long long* __restrict__ phase_chunks,
+                                                              int chunks_from) {
+    __shared__ long long wc[kScanThreads / kWave];
+    __shared__ int wt[kScanThreads / kWave];
+    const int which = blockIdx.x;
+    scan_rank_bases(P, which == 0 ? Lr : Ls, which == chunks_from ? phase_chunks : nullptr, wc, wt);
 }
 
 // ------------------------------------------------------------------------------------------
 // k_layout_units: cut every rank's staged chunks into wave units of kUnitChunks and record, per
 // unit, the rank and the first segment that overlaps it (binary search in the rank's prefix
-// row).  One workgroup per rank.
+// row).  grid (P, layouts): one workgroup per rank and layout (y = 0 receive side, 1 send side).
 // ------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) k_layout_units(int nseg, LayoutDev L) {
+__global__ void __launch_bounds__(256) k_layout_units(int nseg, LayoutDev Lr, LayoutDev Ls) {
+    const LayoutDev& L = blockIdx.y == 0 ? Lr : Ls;
     const int p = blockIdx.x;
     const int tot = L.tot[p];
     const int nu = (tot + kUnitChunks - 1) / kUnitChunks;
