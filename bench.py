@@ -46,6 +46,7 @@ def parse_args():
     ap.add_argument("--fused", type=int, default=0, help="1: fused single-kernel rounds")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fused-table", action="store_true", help="skip the second sweep with fused rounds")
+    ap.add_argument("--no-persistent-table", action="store_true", help="skip the tuna_alltoallv_init / tuna_start sweep")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--traffic-json", type=str, default="",
                     help="optional JSON file {kernel: bytes per launch} from rocprofv3 --pmc runs")
@@ -190,11 +191,59 @@ def main():
         tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
         return per_radix
 
+    def run_persistent(fused):
+        """tuna_alltoallv_init once per radix, then K timed tuna_start calls (no validation, no
+        metadata kernels, no host synchronisation), eagerly and as one captured HIP graph."""
+        rows = []
+        for kind, _, rl, rg in sweep:
+            label = "r_l=%d,r_g=%d" % (rl, rg) if kind == "hier" else "r=%d" % rl
+            tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 1 if fused else 0)
+            rc, plan = tuna.tuna_alltoallv_init(send, d_sc, d_sd, recv, d_rc, d_rd, P, rpn, rl, rg)
+            tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+            if rc != 0:
+                raise RuntimeError("tuna_alltoallv_init failed: " + tuna.tuna_strerror(rc))
+            try:
+                for _ in range(args.warmup):
+                    tuna.tuna_start(plan)
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                for _ in range(args.steps):
+                    tuna.tuna_start(plan)
+                torch.cuda.synchronize()
+                ms_start = (time.perf_counter() - t1) * 1e3 / args.steps
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph):
+                    tuna.tuna_start(plan)
+                graph.replay()
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                for _ in range(args.steps):
+                    graph.replay()
+                torch.cuda.synchronize()
+                ms_graph = (time.perf_counter() - t1) * 1e3 / args.steps
+                del graph
+                st = tuna.tuna_get_stats()
+                rows.append({"radix": label, "ms_per_start": ms_start, "ms_per_graph_replay": ms_graph,
+                             "effective_GBs": Btot / (min(ms_start, ms_graph) * 1e-3) / 1e9,
+                             "plan_bytes": st.workspace_bytes})
+                print("[bench] %s persistent%s: %.3f ms/start, %.3f ms/graph replay, %.1f GB/s effective" %
+                      (label, " fused" if fused else "", ms_start, ms_graph, rows[-1]["effective_GBs"]),
+                      file=sys.stderr, flush=True)
+            finally:
+                tuna.tuna_plan_free(plan)
+        return rows
+
     per_radix = run_sweep(bool(args.fused))
     # the fused rounds (one kernel per phase, 2 x payload instead of 6 x) as a second table
     fused_table = None
     if not args.fused and not args.no_fused_table:
         fused_table = run_sweep(True)
+    persistent = None
+    if not args.no_persistent_table:
+        persistent = {"note": "tuna_alltoallv_init once, then tuna_start per step: payload kernels only",
+                      "staged": run_persistent(bool(args.fused))}
+        if not args.fused and not args.no_fused_table:
+            persistent["fused"] = run_persistent(True)
     best = max(per_radix, key=lambda r: r["effective_GBs"])
     # Roofline of the dominant kernel: the copy kernel with the largest total time over ALL launches
     # of the timed sweep (every radix), so that its average launch duration is the one a
@@ -235,7 +284,7 @@ def main():
         "config": {"workload": "config %d: %s" % (args.config, cfg.description), "P": P,
                    "payload_bytes": Btot, "best_radix": best["radix"], "fused": bool(args.fused),
                    "ranks_per_node": rpn},
-        "roofline": roofline, "cpu_baseline": cpu_baseline, "copy_ceiling": copy_ceiling, "per_radix": per_radix,
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "copy_ceiling": copy_ceiling, "per_radix": per_radix, "persistent": persistent,
         "fused_rounds": None if fused_table is None else {
             "note": "same workload with TUNA_OPT_FUSED: one kernel per digit phase moves S/T to R/T directly",
             "best_effective_GBs": max(r["effective_GBs"] for r in fused_table), "per_radix": fused_table},

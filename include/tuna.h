@@ -24,6 +24,8 @@
  *     the receive regions (MPI_Alltoallv semantics).
  *   - Return value: TUNA_OK (0) or a negative TUNA_ERR_* code.  Nothing throws or aborts.  When
  *     an error is returned no payload byte has been moved.
+ *   - sendbuf and recvbuf must not overlap.  The library uses the HIP device that is current at
+ *     its first call.
  *   - The library keeps one grow-only workspace and the statistics of the last call per process;
  *     calls are not thread-safe against each other, and two calls in flight on different streams
  *     share the workspace and therefore race.
@@ -134,6 +136,27 @@ int tuna_alltoallv(const void* sendbuf, const int32_t* sendcounts, const int64_t
 int tuna_alltoallv_hier(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls,
                         void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls,
                         int P, int ranks_per_node, int local_radix, int global_radix, void* stream);
+
+/*
+ * Persistent form, after MPI's persistent collectives (MPI_Alltoallv_init / MPI_Start): for
+ * callers that repeat an exchange with the same counts, displacements and buffers.
+ * tuna_alltoallv_init does everything that depends only on the counts -- validation, sizing,
+ * every phase's block-size exchange, scans and work lists -- keeps the result in device memory
+ * owned by the plan (it allocates and synchronises), and fixes the options in force
+ * (TUNA_OPT_FUSED, TUNA_OPT_STAGGERED).  tuna_start only enqueues the payload kernels on
+ * `stream`: no allocation, no host synchronisation, no host-visible dependence on device data,
+ * so it may be captured into a HIP graph (unless TUNA_OPT_PROFILE is on) and replayed.  The six
+ * arrays must stay alive and unchanged while the plan exists; the contents of sendbuf may change
+ * between starts.  Two starts of one plan must not overlap in time.  tuna_plan_free waits for
+ * the device and releases the plan's memory.
+ */
+typedef struct tuna_plan_s* tuna_plan_t;
+int tuna_alltoallv_init(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls,
+                        void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls,
+                        int P, int ranks_per_node, int local_radix, int global_radix,
+                        void* stream, tuna_plan_t* plan);
+int tuna_start(tuna_plan_t plan, void* stream);
+int tuna_plan_free(tuna_plan_t plan);
 
 /*
  * Device bytes a call with these counts and parameters needs (Algorithm "TuNA", lines 1-2:

@@ -28,7 +28,7 @@ TUNA_MAX_PHASES = 64
 
 EXPORTS = ("tuna_alltoallv", "tuna_alltoallv_hier", "tuna_workspace_bytes", "tuna_set_workspace",
            "tuna_release", "tuna_set_option", "tuna_get_stats", "tuna_plan_info", "tuna_plan_phase",
-           "tuna_t_index", "tuna_plain_copy", "tuna_select_radix",
+           "tuna_t_index", "tuna_plain_copy", "tuna_select_radix", "tuna_alltoallv_init", "tuna_start", "tuna_plan_free",
            "tuna_strerror", "tuna_version")
 
 
@@ -88,6 +88,9 @@ def load() -> ctypes.CDLL:
     vp, i, i64p = ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p
     lib.tuna_alltoallv.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, vp]
     lib.tuna_alltoallv_hier.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
+    lib.tuna_alltoallv_init.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, ctypes.POINTER(ctypes.c_void_p)]
+    lib.tuna_start.argtypes = [vp, vp]
+    lib.tuna_plan_free.argtypes = [vp]
     lib.tuna_workspace_bytes.argtypes = [vp, i, i, i, i, ctypes.POINTER(ctypes.c_size_t)]
     lib.tuna_set_workspace.argtypes = [vp, ctypes.c_size_t]
     lib.tuna_release.argtypes = []
@@ -147,6 +150,26 @@ def tuna_alltoallv_hier(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdisp
     return load().tuna_alltoallv_hier(_ptr(sendbuf), _ptr(sendcounts, torch.int32), _ptr(sdispls, torch.int64),
                                       _ptr(recvbuf), _ptr(recvcounts, torch.int32), _ptr(rdispls, torch.int64),
                                       P, ranks_per_node, local_radix, global_radix, _stream(stream))
+
+
+def tuna_alltoallv_init(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P: int,
+                        ranks_per_node: int, local_radix: int, global_radix: int, stream=None):
+    """Returns (code, plan handle).  The handle is an opaque integer for tuna_start / tuna_plan_free."""
+    import torch
+    plan = ctypes.c_void_p(None)
+    rc = load().tuna_alltoallv_init(_ptr(sendbuf), _ptr(sendcounts, torch.int32), _ptr(sdispls, torch.int64),
+                                    _ptr(recvbuf), _ptr(recvcounts, torch.int32), _ptr(rdispls, torch.int64),
+                                    P, ranks_per_node, local_radix, global_radix, _stream(stream),
+                                    ctypes.byref(plan))
+    return rc, plan.value
+
+
+def tuna_start(plan, stream=None) -> int:
+    return load().tuna_start(plan, _stream(stream))
+
+
+def tuna_plan_free(plan) -> int:
+    return load().tuna_plan_free(plan)
 
 
 def tuna_workspace_bytes(sendcounts, P: int, ranks_per_node: int, local_radix: int, global_radix: int):

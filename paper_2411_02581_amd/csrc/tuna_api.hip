@@ -4,6 +4,7 @@
 // the ceil(log_r) digit phases.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdio>
 #include <cstring>
 #include <map>
@@ -48,6 +49,7 @@ struct Ctx {
     std::vector<Mark> marks;
     hipEvent_t ev_end = nullptr;
     bool end_recorded = false;
+    const void* stats_plan = nullptr;   // the statistics on file belong to this persistent plan (payload bytes known)
     int last_hip_error = 0;
 };
 
@@ -273,9 +275,56 @@ int run_validate(const int32_t* sendcounts, const int32_t* recvcounts, const int
     return TUNA_OK;
 }
 
-int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
-        const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
-        void* stream) {
+// What the data kernels of a call need, fixed once the counts have been validated and sized.
+struct Prepared {
+    int P = 0, Q = 0, N = 0;
+    DevicePlan* dp = nullptr;
+    bool fused = false, staggered = false;
+    int gran = 1;
+    const void* sendbuf = nullptr;
+    void* recvbuf = nullptr;
+    const int32_t* sendcounts = nullptr;
+    const int32_t* recvcounts = nullptr;
+    const int64_t* sdispls = nullptr;
+    const int64_t* rdispls = nullptr;
+    unsigned long long user_limit = 0;
+    int max_count = 0;
+    DataSizes ds{};
+    v4u* stage_s = nullptr;
+    v4u* stage_r = nullptr;
+    unsigned char* T = nullptr;
+};
+
+bool phase_is_one_kernel(const Prepared& pr, const PhaseHost& ph) {
+    return pr.fused || (pr.staggered && ph.dim == 1);
+}
+
+void fill_stats_header(const Prepared& pr, const Status& hs, tuna_stats_t& st) {
+    const PlanHost& pl = pr.dp->host;
+    std::memset(&st, 0, sizeof(st));
+    st.P = pr.P; st.Q = pr.Q; st.N = pr.N; st.local_radix = pl.rl; st.global_radix = pl.rg;
+    st.w_local = pl.w_l; st.w_global = pl.w_g; st.K_local = pl.K_l; st.K_global = pl.K_g;
+    st.B_local = pl.B_l; st.B_global = pl.B_g; st.n_phases = (int)pl.phases.size();
+    if (pr.staggered) st.K_global = pr.Q * (pr.N - 1);
+    st.temp_slots_per_rank = pl.slots;
+    st.fused = pr.fused ? 1 : 0;
+    st.max_block_bytes = hs.max_count;
+    st.total_payload_bytes = (int64_t)hs.total_bytes;
+    st.granularity = pr.gran;
+    for (size_t i = 0; i < pl.phases.size(); ++i) {
+        const PhaseHost& ph = pl.phases[i];
+        tuna_phase_stats_t& ps = st.phase[i];
+        ps.dim = ph.dim; ps.x = ph.x; ps.radix = ph.r; ps.rounds = ph.nz;
+        if (pr.staggered && ph.dim == 1) ps.rounds = pr.Q * (pr.N - 1);
+        ps.blocks = (int64_t)ph.nseg * pr.P;
+    }
+}
+
+// Argument checks, schedule, validation + sizing pass (one read-back).  On TUNA_OK with
+// *empty == true there is nothing to move.
+int prepare_call(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
+                 const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
+                 hipStream_t s, Prepared& pr, Status& hs, bool* empty) {
     int Q = 0;
     int rc = resolve_hierarchy(P, ranks_per_node, &Q);
     if (rc != TUNA_OK) return rc;
@@ -283,51 +332,121 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
     if (!sendcounts || !recvcounts || !sdispls || !rdispls) return TUNA_ERR_ARG;
     rc = ensure_ctx();
     if (rc != TUNA_OK) return rc;
-    hipStream_t s = (hipStream_t)stream;
     const int N = P / Q;
-
-    DevicePlan* dp = nullptr;
-    const bool fused = g.opt_fused != 0;
+    pr.P = P; pr.Q = Q; pr.N = N;
+    pr.fused = g.opt_fused != 0;
     // staggered inter-node schedule: one block per message, N - 1 node distances, straight from T
-    const bool staggered = g.opt_staggered != 0 && N > 1;
-    if (staggered) rg = N;
-    rc = get_plan(P, Q, rl, rg, fused, &dp);
+    pr.staggered = g.opt_staggered != 0 && N > 1;
+    if (pr.staggered) rg = N;
+    rc = get_plan(P, Q, rl, rg, pr.fused, &pr.dp);
     if (rc != TUNA_OK) return rc;
-    const PlanHost& pl = dp->host;
-
-    g.marks.clear();
-    g.end_recorded = false;
-    g.have_stats = false;
-    tuna_stats_t& st = g.stats;
-    std::memset(&st, 0, sizeof(st));
-    st.P = P; st.Q = Q; st.N = N; st.local_radix = pl.rl; st.global_radix = pl.rg;
-    st.w_local = pl.w_l; st.w_global = pl.w_g; st.K_local = pl.K_l; st.K_global = pl.K_g;
-    st.B_local = pl.B_l; st.B_global = pl.B_g; st.n_phases = (int)pl.phases.size();
-    if (staggered) st.K_global = Q * (N - 1);
-    st.temp_slots_per_rank = pl.slots;
-    st.fused = fused ? 1 : 0;
-    mark(s, -1, -1);
-
-    // ---- prepare: validation, M, totals (one read-back) ---------------------------------------
+    pr.sendbuf = sendbuf; pr.recvbuf = recvbuf; pr.sendcounts = sendcounts; pr.recvcounts = recvcounts;
+    pr.sdispls = sdispls; pr.rdispls = rdispls;
+    // ---- validation, M, totals (one read-back) -------------------------------------------------
     rc = run_validate(sendcounts, recvcounts, sdispls, rdispls, P, s);
     if (rc != TUNA_OK) return rc;
-    const Status hs = *g.h_status;
+    hs = *g.h_status;
     if (hs.flags & 1u) return TUNA_ERR_NEGATIVE_COUNT;
     if (hs.flags & 2u) return TUNA_ERR_COUNT_MISMATCH;
-    st.max_block_bytes = hs.max_count;
-    st.total_payload_bytes = (int64_t)hs.total_bytes;
-    if (hs.total_bytes == 0) { g.have_stats = true; return TUNA_OK; }
+    *empty = hs.total_bytes == 0;
+    if (*empty) return TUNA_OK;
     if (!sendbuf || !recvbuf) return TUNA_ERR_ARG;
     // chunk prefixes are 32-bit per rank
     if ((unsigned long long)P * (unsigned long long)((hs.max_count + 15) / 16) >= (1ull << 31)) return TUNA_ERR_TOO_LARGE;
     const unsigned int abits = hs.align_bits | (unsigned int)((uintptr_t)sendbuf & 15u) |
                                (unsigned int)((uintptr_t)recvbuf & 15u);
-    const int gran = (abits & 15u) == 0 ? 16 : ((abits & 3u) == 0 ? 4 : 1);
-    st.granularity = gran;
+    pr.gran = (abits & 15u) == 0 ? 16 : ((abits & 3u) == 0 ? 4 : 1);
+    pr.max_count = hs.max_count;
+    pr.user_limit = (unsigned long long)(uintptr_t)sendbuf + hs.send_extent;
+    pr.ds = data_sizes_for(pr.dp->host, hs.max_count, hs.total_chunks, pr.fused, pr.staggered);
+    return TUNA_OK;
+}
+
+int launch_phase_metadata(const Prepared& pr, size_t i, const int32_t* cur, int32_t* nxt, const LayoutDev& Ls,
+                          const LayoutDev& Lr, hipStream_t s) {
+    const PhaseHost& ph = pr.dp->host.phases[i];
+    const bool one_kernel = phase_is_one_kernel(pr, ph);
+    PhaseLayoutArgs m{};
+    m.cur = cur; m.nxt = nxt; m.zt = pr.dp->d_zt[i]; m.seg = pr.dp->d_seg[i]; m.nseg = ph.nseg;
+    m.P = pr.P; m.Q = pr.Q; m.N = pr.N; m.dim = ph.dim; m.rx = (int)ph.rx;
+    m.Ls = Ls; m.Lr = Lr; m.want_send = one_kernel ? 0 : 1;
+    m.phase_bytes = &g.d_status->phase_bytes[i]; m.phase_chunks = &g.d_status->phase_chunks[i];
+    m.head_displs = one_kernel ? pr.rdispls : nullptr;
+    m.head_base = (unsigned int)((uintptr_t)pr.recvbuf & 15u);
+    return phase_metadata(m, s);
+}
+
+int launch_self_copy(const Prepared& pr, hipStream_t s) {
+    const int split = pr.max_count > (1 << 16) ? 16 : 1;
+    hipLaunchKernelGGL(k_self_copy, dim3(pr.P, split), dim3(256), 0, s, (const unsigned char*)pr.sendbuf,
+                       pr.sendcounts, pr.sdispls, (unsigned char*)pr.recvbuf, pr.rdispls, pr.P);
+    HIPCHK(hipGetLastError());
+    return TUNA_OK;
+}
+
+// The payload kernels of digit phase i: pack, exchange, unpack -- or the one-kernel hop.
+// unit_cap: number of wave units to launch for (an upper bound is fine).
+int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const LayoutDev& Lr, size_t unit_cap,
+                      hipStream_t s) {
+    const PhaseHost& ph = pr.dp->host.phases[i];
+    CopyArgs a{};
+    a.seg = pr.dp->d_seg[i]; a.nseg = ph.nseg;
+    a.T = pr.T; a.slots = pr.ds.slots; a.slot_bytes = pr.ds.slot_bytes;
+    a.P = pr.P; a.Q = pr.Q; a.N = pr.N; a.dim = ph.dim; a.rx = (int)ph.rx;
+    a.user_limit = pr.user_limit;
+    int rc;
+    if (phase_is_one_kernel(pr, ph)) {
+        // one hop in one kernel: S / T of the sender -> R / the other copy of T at the receiver
+        a.stage = nullptr; a.L = Lr; a.counts = pr.recvcounts;
+        a.user = (unsigned char*)pr.sendbuf; a.displs = pr.sdispls;
+        a.user2 = (unsigned char*)pr.recvbuf; a.displs2 = pr.rdispls; a.T2 = pr.T;
+        rc = launch_copy<kFused>(pr.gran, unit_cap, a, s);
+        if (rc != TUNA_OK) return rc;
+        mark(s, kCatPack, (int)i);
+        return TUNA_OK;
+    }
+    // pack: S / T -> send staging
+    a.stage = pr.stage_s; a.L = Ls;
+    a.user = (unsigned char*)pr.sendbuf; a.displs = pr.sdispls;
+    rc = launch_copy<kPack>(pr.gran, unit_cap, a, s);
+    if (rc != TUNA_OK) return rc;
+    mark(s, kCatPack, (int)i);
+    // exchange: send staging of the partner -> receive staging
+    a.stage = pr.stage_r; a.L = Lr; a.stage_src = pr.stage_s; a.Ls = Ls;
+    rc = launch_copy<kExchange>(pr.gran, unit_cap, a, s);
+    if (rc != TUNA_OK) return rc;
+    mark(s, kCatExchange, (int)i);
+    // unpack: receive staging -> R / T
+    a.counts = pr.recvcounts; a.user = (unsigned char*)pr.recvbuf; a.displs = pr.rdispls;
+    rc = launch_copy<kUnpack>(pr.gran, unit_cap, a, s);
+    if (rc != TUNA_OK) return rc;
+    mark(s, kCatUnpack, (int)i);
+    return TUNA_OK;
+}
+
+int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
+        const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
+        void* stream) {
+    hipStream_t s = (hipStream_t)stream;
+    g.marks.clear();
+    g.end_recorded = false;
+    g.have_stats = false;
+    g.stats_plan = nullptr;
+    if (g.ready) mark(s, -1, -1);
+    Prepared pr;
+    Status hs{};
+    bool empty = false;
+    int rc = prepare_call(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node, rl, rg, s,
+                          pr, hs, &empty);
+    if (rc != TUNA_OK) return rc;
+    tuna_stats_t& st = g.stats;
+    fill_stats_header(pr, hs, st);
+    if (empty) { g.have_stats = true; return TUNA_OK; }
+    const PlanHost& pl = pr.dp->host;
 
     // ---- workspace ---------------------------------------------------------------------------
     const size_t mbytes = meta_bytes_for(P);
-    const DataSizes ds = data_sizes_for(pl, hs.max_count, hs.total_chunks, fused, staggered);
+    const DataSizes& ds = pr.ds;
     void *mbase, *dbase;
     if (g.user_ws) {
         if (mbytes + ds.total > g.user_ws_bytes) return TUNA_ERR_WORKSPACE_TOO_SMALL;
@@ -346,89 +465,162 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
     Carver cd(dbase, ds.total);
     mb.Ls.units = cd.take<int4>(ds.unit_cap);
     mb.Lr.units = cd.take<int4>(ds.unit_cap);
-    v4u* stage_s = cd.take<v4u>(fused ? 0 : ds.stage_chunks);
-    v4u* stage_r = cd.take<v4u>(fused ? 0 : ds.stage_chunks);
-    unsigned char* T = cd.take<unsigned char>(ds.t_bytes);
+    pr.stage_s = cd.take<v4u>(pr.fused ? 0 : ds.stage_chunks);
+    pr.stage_r = cd.take<v4u>(pr.fused ? 0 : ds.stage_chunks);
+    pr.T = cd.take<unsigned char>(ds.t_bytes);
     if (!cm.ok || !cd.ok) return TUNA_ERR_WORKSPACE_TOO_SMALL;
     st.temp_bytes = (int64_t)ds.t_bytes;
-    st.staging_bytes = fused ? 0 : (int64_t)(2 * ds.stage_chunks * 16);
+    st.staging_bytes = pr.fused ? 0 : (int64_t)(2 * ds.stage_chunks * 16);
     st.workspace_bytes = (int64_t)(mbytes + ds.total);
 
     // ---- initial rotation (index only) and the own block ----------------------------------------
     const size_t P2 = (size_t)P * P;
     const unsigned gP2 = (unsigned)((P2 + 255) / 256);
-    hipLaunchKernelGGL(k_rotate_init, dim3(gP2), dim3(256), 0, s, sendcounts, mb.cur, P, Q, N);
+    hipLaunchKernelGGL(k_rotate_init, dim3(gP2), dim3(256), 0, s, sendcounts, mb.cur, P, pr.Q, pr.N);
     HIPCHK(hipGetLastError());
     mark(s, kCatPrepare, -1);
-    {
-        const int split = hs.max_count > (1 << 16) ? 16 : 1;
-        hipLaunchKernelGGL(k_self_copy, dim3(P, split), dim3(256), 0, s, (const unsigned char*)sendbuf, sendcounts,
-                           sdispls, (unsigned char*)recvbuf, rdispls, P);
-        HIPCHK(hipGetLastError());
-    }
+    rc = launch_self_copy(pr, s);
+    if (rc != TUNA_OK) return rc;
     mark(s, kCatSelf, -1);
 
     // ---- digit phases -----------------------------------------------------------------------------
     int32_t* cur = mb.cur;
     int32_t* nxt = mb.nxt;
     for (size_t i = 0; i < pl.phases.size(); ++i) {
-        const PhaseHost& ph = pl.phases[i];
-        tuna_phase_stats_t& ps = st.phase[i];
-        ps.dim = ph.dim; ps.x = ph.x; ps.radix = ph.r; ps.rounds = ph.nz;
-        const bool one_kernel = fused || (staggered && ph.dim == 1);
-        if (staggered && ph.dim == 1) ps.rounds = Q * (N - 1);
-        ps.blocks = (int64_t)ph.nseg * P;
-        const SegDev seg = dp->d_seg[i];
-        // metadata exchange and the send-side and receive-side layouts
-        {
-            PhaseLayoutArgs m{};
-            m.cur = cur; m.nxt = nxt; m.zt = dp->d_zt[i]; m.seg = seg; m.nseg = ph.nseg;
-            m.P = P; m.Q = Q; m.N = N; m.dim = ph.dim; m.rx = (int)ph.rx;
-            m.Ls = mb.Ls; m.Lr = mb.Lr; m.want_send = one_kernel ? 0 : 1;
-            m.phase_bytes = &g.d_status->phase_bytes[i]; m.phase_chunks = &g.d_status->phase_chunks[i];
-            m.head_displs = one_kernel ? rdispls : nullptr;
-            m.head_base = (unsigned int)((uintptr_t)recvbuf & 15u);
-            rc = phase_metadata(m, s);
-            if (rc != TUNA_OK) return rc;
-        }
+        rc = launch_phase_metadata(pr, i, cur, nxt, mb.Ls, mb.Lr, s);
+        if (rc != TUNA_OK) return rc;
         mark(s, kCatMeta, (int)i);
-
-        CopyArgs a{};
-        a.seg = seg; a.nseg = ph.nseg;
-        a.T = T; a.slots = ds.slots; a.slot_bytes = ds.slot_bytes;
-        a.P = P; a.Q = Q; a.N = N; a.dim = ph.dim; a.rx = (int)ph.rx;
-        a.user_limit = (unsigned long long)(uintptr_t)sendbuf + hs.send_extent;
-        if (one_kernel) {
-            // one hop in one kernel: S / T of the sender -> R / the other copy of T at the receiver
-            a.stage = nullptr; a.L = mb.Lr; a.sizes = nxt;
-            a.user = (unsigned char*)sendbuf; a.displs = sdispls;
-            a.user2 = (unsigned char*)recvbuf; a.displs2 = rdispls; a.T2 = T;
-            rc = launch_copy<kFused>(gran, ds.unit_cap, a, s);
-            if (rc != TUNA_OK) return rc;
-            mark(s, kCatPack, (int)i);
-            std::swap(cur, nxt);
-            continue;
-        }
-        // pack: S / T -> send staging
-        a.stage = stage_s; a.L = mb.Ls; a.sizes = cur;
-        a.user = (unsigned char*)sendbuf; a.displs = sdispls;
-        rc = launch_copy<kPack>(gran, ds.unit_cap, a, s);
+        rc = launch_phase_data(pr, i, mb.Ls, mb.Lr, ds.unit_cap, s);
         if (rc != TUNA_OK) return rc;
-        mark(s, kCatPack, (int)i);
-        // exchange: send staging of the partner -> receive staging
-        a.stage = stage_r; a.L = mb.Lr; a.stage_src = stage_s; a.Ls = mb.Ls;
-        rc = launch_copy<kExchange>(gran, ds.unit_cap, a, s);
-        if (rc != TUNA_OK) return rc;
-        mark(s, kCatExchange, (int)i);
-        // unpack: receive staging -> R / T
-        a.sizes = nxt; a.user = (unsigned char*)recvbuf; a.displs = rdispls;
-        rc = launch_copy<kUnpack>(gran, ds.unit_cap, a, s);
-        if (rc != TUNA_OK) return rc;
-        mark(s, kCatUnpack, (int)i);
         std::swap(cur, nxt);
     }
     HIPCHK(hipEventRecord(g.ev_end, s));
     g.end_recorded = true;
+    g.have_stats = true;
+    return TUNA_OK;
+}
+
+// ---- persistent calls ------------------------------------------------------------------------------
+// All metadata of a call (validation, sizing, every phase's size exchange, scans and unit lists) is
+// computed once when the plan is made; starting it only launches the payload kernels.
+struct Plan {
+    Prepared pr;
+    void* mem_meta = nullptr;       // cur / nxt and every phase's two layouts
+    void* mem_data = nullptr;       // staging and T
+    std::vector<LayoutDev> Ls, Lr;  // per phase
+    std::vector<size_t> units;      // per phase: exact number of wave units (max of the two layouts)
+    tuna_stats_t stats;
+    unsigned long long phase_bytes[TUNA_MAX_PHASES];
+    unsigned long long phase_chunks[TUNA_MAX_PHASES];
+    bool empty = false;
+};
+
+size_t layout_bytes_for(int P, size_t unit_cap) {
+    const size_t ld = (size_t)P + 1;
+    return align_up((size_t)P * ld * 4) + align_up((size_t)P * 4) + align_up(((size_t)P + 1) * 8) +
+           align_up(((size_t)P + 1) * 4) + align_up(4) + align_up(unit_cap * sizeof(int4));
+}
+
+void carve_full_layout(Carver& cv, int P, size_t unit_cap, LayoutDev& L) {
+    carve_layout(cv, P, L);
+    L.units = cv.take<int4>(unit_cap);
+}
+
+int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
+                const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
+                hipStream_t s, Plan** out) {
+    Plan* plan = new Plan();
+    Prepared& pr = plan->pr;
+    Status hs{};
+    int rc = prepare_call(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node, rl, rg, s,
+                          pr, hs, &plan->empty);
+    if (rc != TUNA_OK) { delete plan; return rc; }
+    fill_stats_header(pr, hs, plan->stats);
+    if (plan->empty) { *out = plan; return TUNA_OK; }
+    const PlanHost& pl = pr.dp->host;
+    const size_t nph = pl.phases.size();
+    // metadata memory: two size matrices + per phase two complete layouts
+    const size_t P2 = (size_t)P * P;
+    const size_t mbytes = 2 * align_up(P2 * 4) + nph * 2 * layout_bytes_for(P, pr.ds.unit_cap);
+    hipError_t e = hipMalloc(&plan->mem_meta, mbytes ? mbytes : kAlign);
+    if (e != hipSuccess) { (void)hipGetLastError(); g.last_hip_error = (int)e; delete plan; return TUNA_ERR_NOMEM; }
+    Carver cm(plan->mem_meta, mbytes);
+    int32_t* cur = cm.take<int32_t>(P2);
+    int32_t* nxt = cm.take<int32_t>(P2);
+    plan->Ls.resize(nph); plan->Lr.resize(nph); plan->units.assign(nph, 0);
+    for (size_t i = 0; i < nph; ++i) {
+        carve_full_layout(cm, P, pr.ds.unit_cap, plan->Ls[i]);
+        carve_full_layout(cm, P, pr.ds.unit_cap, plan->Lr[i]);
+    }
+    auto fail = [&](int code) { (void)hipFree(plan->mem_meta); if (plan->mem_data) (void)hipFree(plan->mem_data); delete plan; return code; };
+    if (!cm.ok) return fail(TUNA_ERR_NOMEM);
+    const unsigned gP2 = (unsigned)((P2 + 255) / 256);
+    hipLaunchKernelGGL(k_rotate_init, dim3(gP2), dim3(256), 0, s, sendcounts, cur, P, pr.Q, pr.N);
+    if (hipGetLastError() != hipSuccess) return fail(TUNA_ERR_HIP);
+    for (size_t i = 0; i < nph; ++i) {
+        rc = launch_phase_metadata(pr, i, cur, nxt, plan->Ls[i], plan->Lr[i], s);
+        if (rc != TUNA_OK) return fail(rc);
+        std::swap(cur, nxt);
+    }
+    // exact unit counts and staged chunks per phase
+    std::vector<int> nu(2 * nph, 0);
+    for (size_t i = 0; i < nph; ++i) {
+        const bool one = phase_is_one_kernel(pr, pl.phases[i]);
+        if (hipMemcpyAsync(&nu[2 * i], plan->Lr[i].n_units, 4, hipMemcpyDeviceToHost, s) != hipSuccess) return fail(TUNA_ERR_HIP);
+        if (!one && hipMemcpyAsync(&nu[2 * i + 1], plan->Ls[i].n_units, 4, hipMemcpyDeviceToHost, s) != hipSuccess) return fail(TUNA_ERR_HIP);
+    }
+    if (hipMemcpyAsync(g.h_status, g.d_status, sizeof(Status), hipMemcpyDeviceToHost, s) != hipSuccess) return fail(TUNA_ERR_HIP);
+    if (hipStreamSynchronize(s) != hipSuccess) return fail(TUNA_ERR_HIP);
+    unsigned long long max_chunks = 0;
+    for (size_t i = 0; i < nph; ++i) {
+        plan->units[i] = (size_t)std::max(nu[2 * i], nu[2 * i + 1]);
+        plan->phase_bytes[i] = g.h_status->phase_bytes[i];
+        plan->phase_chunks[i] = g.h_status->phase_chunks[i];
+        plan->stats.phase[i].payload_bytes = (int64_t)plan->phase_bytes[i];
+        plan->stats.phase[i].staged_bytes = (int64_t)plan->phase_chunks[i] * 16;
+        if (!phase_is_one_kernel(pr, pl.phases[i])) max_chunks = std::max(max_chunks, plan->phase_chunks[i]);
+    }
+    // payload memory: staging sized by the largest phase, T by M and the slot count
+    const size_t stage_bytes = align_up((size_t)max_chunks * 16);
+    const size_t dbytes = 2 * stage_bytes + align_up(pr.ds.t_bytes);
+    if (dbytes) {
+        e = hipMalloc(&plan->mem_data, dbytes);
+        if (e != hipSuccess) { (void)hipGetLastError(); g.last_hip_error = (int)e; return fail(TUNA_ERR_NOMEM); }
+        Carver cd(plan->mem_data, dbytes);
+        pr.stage_s = cd.take<v4u>(stage_bytes / 16);
+        pr.stage_r = cd.take<v4u>(stage_bytes / 16);
+        pr.T = cd.take<unsigned char>(pr.ds.t_bytes);
+    }
+    plan->stats.temp_bytes = (int64_t)pr.ds.t_bytes;
+    plan->stats.staging_bytes = (int64_t)(2 * stage_bytes);
+    plan->stats.workspace_bytes = (int64_t)(mbytes + dbytes);
+    *out = plan;
+    return TUNA_OK;
+}
+
+int plan_start(Plan* plan, hipStream_t s) {
+    g.marks.clear();
+    g.end_recorded = false;
+    g.have_stats = false;
+    g.stats = plan->stats;
+    g.stats_plan = plan;
+    if (plan->empty) { g.have_stats = true; return TUNA_OK; }
+    mark(s, -1, -1);
+    mark(s, kCatPrepare, -1);
+    const Prepared& pr = plan->pr;
+    int rc = launch_self_copy(pr, s);
+    if (rc != TUNA_OK) return rc;
+    mark(s, kCatSelf, -1);
+    const size_t nph = pr.dp->host.phases.size();
+    for (size_t i = 0; i < nph; ++i) {
+        mark(s, kCatMeta, (int)i);
+        rc = launch_phase_data(pr, i, plan->Ls[i], plan->Lr[i], plan->units[i], s);
+        if (rc != TUNA_OK) return rc;
+    }
+    if (g.opt_profile) {
+        HIPCHK(hipEventRecord(g.ev_end, s));
+        g.end_recorded = true;
+    }
     g.have_stats = true;
     return TUNA_OK;
 }
@@ -453,6 +645,34 @@ int tuna_alltoallv_hier(const void* sendbuf, const int32_t* sendcounts, const in
     if (local_radix < 2 || global_radix < 2) return TUNA_ERR_ARG;
     return run(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node, local_radix,
                global_radix, stream);
+}
+
+int tuna_alltoallv_init(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
+                        const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node,
+                        int local_radix, int global_radix, void* stream, tuna_plan_t* plan) {
+    if (!plan || local_radix < 2 || global_radix < 2) return TUNA_ERR_ARG;
+    *plan = nullptr;
+    Plan* p = nullptr;
+    const int rc = plan_create(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node,
+                               local_radix, global_radix, (hipStream_t)stream, &p);
+    if (rc == TUNA_OK) *plan = reinterpret_cast<tuna_plan_t>(p);
+    return rc;
+}
+
+int tuna_start(tuna_plan_t plan, void* stream) {
+    if (!plan) return TUNA_ERR_ARG;
+    return plan_start(reinterpret_cast<Plan*>(plan), (hipStream_t)stream);
+}
+
+int tuna_plan_free(tuna_plan_t plan) {
+    if (!plan) return TUNA_OK;
+    Plan* p = reinterpret_cast<Plan*>(plan);
+    if (g.stats_plan == p) g.stats_plan = nullptr;
+    HIPCHK(hipDeviceSynchronize());
+    if (p->mem_meta) (void)hipFree(p->mem_meta);
+    if (p->mem_data) (void)hipFree(p->mem_data);
+    delete p;
+    return TUNA_OK;
 }
 
 int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node, int local_radix, int global_radix,
@@ -530,10 +750,12 @@ int tuna_get_stats(tuna_stats_t* out) {
     tuna_stats_t& st = g.stats;
     if (g.end_recorded) {
         HIPCHK(hipEventSynchronize(g.ev_end));
-        HIPCHK(hipMemcpy(g.h_status, g.d_status, sizeof(Status), hipMemcpyDeviceToHost));
-        for (int i = 0; i < st.n_phases; ++i) {
-            st.phase[i].payload_bytes = (int64_t)g.h_status->phase_bytes[i];
-            st.phase[i].staged_bytes = (int64_t)g.h_status->phase_chunks[i] * 16;
+        if (!g.stats_plan) {   // a persistent plan knows its per-phase bytes since it was made
+            HIPCHK(hipMemcpy(g.h_status, g.d_status, sizeof(Status), hipMemcpyDeviceToHost));
+            for (int i = 0; i < st.n_phases; ++i) {
+                st.phase[i].payload_bytes = (int64_t)g.h_status->phase_bytes[i];
+                st.phase[i].staged_bytes = (int64_t)g.h_status->phase_chunks[i] * 16;
+            }
         }
         if (g.marks.size() > 1) {
             st.ms_prepare = st.ms_self = 0.f;

@@ -15,8 +15,11 @@ namespace tuna {
 
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));   // one 16-byte chunk
 
+#ifndef TUNA_COPY_THREADS
+#define TUNA_COPY_THREADS 256
+#endif
 constexpr int kWave = 64;
-constexpr int kCopyThreads = 256;                        // 4 waves, each an independent work unit
+constexpr int kCopyThreads = TUNA_COPY_THREADS;                        // 4 waves, each an independent work unit
 #ifndef TUNA_CHUNKS_PER_LANE
 #define TUNA_CHUNKS_PER_LANE 4
 #endif
@@ -464,7 +467,7 @@ struct CopyArgs {
     SegDev seg;
     int nseg;
     // other side: caller buffer + T (pack, unpack, fused source)
-    const int32_t* sizes;               // [P][P] block sizes at the tiled side's ranks (cur for pack, nxt for unpack)
+    const int32_t* counts;              // recvcounts: exact sizes of the blocks that are final (unpack, fused)
     unsigned char* user;                // S (pack) or R (unpack)
     const int64_t* displs;              // sdispls (pack) or rdispls (unpack)
     unsigned long long user_limit;      // pack: address one past the last byte of S that holds a block
@@ -524,7 +527,8 @@ __device__ __forceinline__ void store_block_chunk(unsigned char* dst, v4u v, int
 __device__ __forceinline__ unsigned long long block_address(int slot, bool far_is_source, int p, int n, int g,
                                                             int j, int l, int P, int Q, int N,
                                                             unsigned char* user, const int64_t* displs,
-                                                            unsigned char* T, long long slots, long long slot_bytes) {
+                                                            unsigned char* T, long long slots, long long slot_bytes,
+                                                            const int32_t* counts = nullptr, int* count = nullptr) {
     if (slot >= 0) return (unsigned long long)(T + ((long long)p * slots + slot) * slot_bytes);
     int pn, pg;
     if (!far_is_source) {
@@ -534,7 +538,9 @@ __device__ __forceinline__ unsigned long long block_address(int slot, bool far_i
         pn = n + j; if (pn >= N) pn -= N;
         pg = g + l; if (pg >= Q) pg -= Q;
     }
-    return (unsigned long long)(user + displs[(size_t)p * P + pn * Q + pg]);
+    const size_t idx = (size_t)p * P + pn * Q + pg;
+    if (counts) *count = counts[idx];          // the caller's count for the same pair (exact size into R)
+    return (unsigned long long)(user + displs[idx]);
 }
 
 // Waves per SIMD: measured on MI355X, the gathering kernels (pack, exchange) run fastest with at most 6
@@ -614,10 +620,11 @@ k_copy(const CopyArgs a) {
                     if (ssrc >= 0) flag |= kFlagSrcT;
                 }
                 if (MODE == kUnpack) {
+                    // a final block's size is the receiver's own recvcounts entry (validated equal to
+                    // the sender's count), read next to its displacement
                     addr = block_address(sdst, true, p, n, g, bj, bl, a.P, a.Q, a.N, a.user, a.displs, a.T,
-                                         a.slots, a.slot_bytes);
-                    if (sdst < 0) size = a.sizes[(size_t)p * a.P + se];
-                    else flag |= kFlagFill;           // T-bound: the tail lane completes the 128-byte line
+                                         a.slots, a.slot_bytes, a.counts, &size);
+                    if (sdst >= 0) flag |= kFlagFill; // T-bound: the tail lane completes the 128-byte line
                 }
                 if (MODE == kFused) {
                     // tiled over the RECEIVER's layout: its stores into R are consecutive; the loads
@@ -630,12 +637,11 @@ k_copy(const CopyArgs a) {
                                          a.displs, a.T, a.slots, a.slot_bytes);
                     if (ssrc >= 0) flag |= kFlagSrcT;
                     addr2 = block_address(sdst, true, p, n, g, bj, bl, a.P, a.Q, a.N, a.user2, a.displs2,
-                                          a.T2, a.slots, a.slot_bytes);
+                                          a.T2, a.slots, a.slot_bytes, a.counts, &size);
                     // chunks are cut at the destination's 16-byte boundaries: `head` bytes of the
                     // first chunk lie before the block (0 for T slots, which are line aligned)
                     flag |= (int)(addr2 & 15ull);
-                    if (sdst < 0) size = a.sizes[(size_t)p * a.P + se];
-                    else flag |= kFlagFill;
+                    if (sdst >= 0) flag |= kFlagFill;
                 }
             }
         }

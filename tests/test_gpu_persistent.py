@@ -1,0 +1,148 @@
+"""GPU parity of the persistent form (tuna_alltoallv_init / tuna_start / tuna_plan_free): the plan is
+made once from the counts, every start moves whatever the send buffer holds at that time, and a
+start can be captured into a HIP graph and replayed.  Every result is compared with the CPU oracle."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+CANARY = 0x6B
+
+
+@pytest.fixture(scope="module")
+def tuna():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2411_02581_amd as t
+    t.load()
+    return t
+
+
+class Resident:
+    def __init__(self, lay):
+        dev = "cuda:0"
+        self.lay = lay
+        self.send = torch.zeros(lay.send_bytes, dtype=torch.uint8, device=dev)
+        self.recv = torch.empty(lay.recv_bytes, dtype=torch.uint8, device=dev)
+        self.sc = torch.from_numpy(lay.sendcounts).to(dev)
+        self.sd = torch.from_numpy(lay.sdispls).to(dev)
+        self.rc = torch.from_numpy(lay.recvcounts).to(dev)
+        self.rd = torch.from_numpy(lay.rdispls).to(dev)
+
+    def load(self, seed):
+        host = wl.payload_position_hash(seed, self.lay.send_bytes)
+        self.send.copy_(torch.from_numpy(host))
+        want = np.full(self.lay.recv_bytes, CANARY, dtype=np.uint8)
+        lay = self.lay
+        assert oracle.alltoallv(host, lay.sendcounts, lay.sdispls, want, lay.recvcounts, lay.rdispls) == 0
+        return want
+
+    def check(self, want, what):
+        torch.cuda.synchronize()
+        got = self.recv.cpu().numpy()
+        assert np.array_equal(got, want), what
+
+
+@pytest.mark.parametrize("fused", [0, 1])
+@pytest.mark.parametrize("P,Q,rl,rg,cfg", [(16, 0, 2, 2, 1), (96, 0, 4, 4, 2), (96, 0, 96, 96, 2),
+                                            (128, 16, 4, 2, 3), (128, 16, 16, 8, 3), (1, 0, 2, 2, 2)])
+def test_start_follows_the_send_buffer(tuna, P, Q, rl, rg, cfg, fused):
+    lay = wl.make_layout(wl.make_counts(cfg, P), gap=4 if cfg != 2 else 5)
+    res = Resident(lay)
+    tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, fused)
+    try:
+        code, plan = tuna.tuna_alltoallv_init(res.send, res.sc, res.sd, res.recv, res.rc, res.rd, P, Q, rl, rg)
+    finally:
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+    assert code == 0, tuna.tuna_strerror(code)
+    try:
+        for seed in (11, 12, 13):                      # same counts, new payload every time
+            want = res.load(seed)
+            res.recv.fill_(CANARY)
+            print("persistent P=%d Q=%d rl=%d rg=%d fused=%d seed=%d" % (P, Q, rl, rg, fused, seed), flush=True)
+            assert tuna.tuna_start(plan) == 0
+            res.check(want, "start %d" % seed)
+        st = tuna.tuna_get_stats()
+        assert st.fused == fused and st.total_payload_bytes == lay.payload_bytes
+        assert sum(st.phase[x].payload_bytes for x in range(st.n_phases)) >= 0
+    finally:
+        assert tuna.tuna_plan_free(plan) == 0
+
+
+def test_staggered_plan_and_stats(tuna):
+    P, Q = 60, 5
+    lay = wl.make_layout(wl.counts_uniform_bytes(P, 3, 900))
+    res = Resident(lay)
+    tuna.tuna_set_option(tuna.TUNA_OPT_STAGGERED, 1)
+    try:
+        code, plan = tuna.tuna_alltoallv_init(res.send, res.sc, res.sd, res.recv, res.rc, res.rd, P, Q, 2, 2)
+    finally:
+        tuna.tuna_set_option(tuna.TUNA_OPT_STAGGERED, 0)
+    assert code == 0
+    try:
+        want = res.load(5)
+        res.recv.fill_(CANARY)
+        assert tuna.tuna_start(plan) == 0
+        res.check(want, "staggered plan")
+        st = tuna.tuna_get_stats()
+        assert st.K_global == Q * (P // Q - 1) and st.global_radix == P // Q
+        # an immediate call in between does not disturb the plan
+        res.recv.fill_(CANARY)
+        assert tuna.tuna_alltoallv(res.send, res.sc, res.sd, res.recv, res.rc, res.rd, P, 3, 0) == 0
+        res.check(want, "immediate call")
+        want = res.load(6)
+        res.recv.fill_(CANARY)
+        assert tuna.tuna_start(plan) == 0
+        res.check(want, "plan after an immediate call")
+    finally:
+        assert tuna.tuna_plan_free(plan) == 0
+
+
+def test_plan_errors(tuna):
+    lay = wl.make_layout(wl.counts_uniform_bytes(8, 1, 64))
+    res = Resident(lay)
+    bad = res.rc.clone()
+    bad[1, 2] += 1
+    code, plan = tuna.tuna_alltoallv_init(res.send, res.sc, res.sd, res.recv, bad, res.rd, 8, 0, 2, 2)
+    assert code == tuna.TUNA_ERR_COUNT_MISMATCH and not plan
+    code, plan = tuna.tuna_alltoallv_init(res.send, res.sc, res.sd, res.recv, res.rc, res.rd, 8, 3, 2, 2)
+    assert code == tuna.TUNA_ERR_ARG and not plan
+    assert tuna.tuna_start(None) == tuna.TUNA_ERR_ARG
+    assert tuna.tuna_plan_free(None) == 0
+
+
+@pytest.mark.parametrize("fused", [0, 1])
+def test_start_captured_in_a_graph(tuna, fused):
+    """tuna_start allocates nothing and never synchronises: captured once, replayed with the
+    program's own eager work and synchronisations between the replays, every replay checked."""
+    P = 64
+    lay = wl.make_layout(wl.make_counts(4, P))
+    res = Resident(lay)
+    tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, fused)
+    try:
+        code, plan = tuna.tuna_alltoallv_init(res.send, res.sc, res.sd, res.recv, res.rc, res.rd, P, 0, 4, 4)
+    finally:
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+    assert code == 0
+    try:
+        want = res.load(1)
+        res.recv.fill_(CANARY)
+        assert tuna.tuna_start(plan) == 0              # eager first
+        res.check(want, "eager")
+        graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph):
+            assert tuna.tuna_start(plan) == 0          # on the capture stream
+        for seed in (2, 3, 4):
+            want = res.load(seed)                      # eager copies and a synchronisation in between
+            res.recv.fill_(CANARY)
+            torch.cuda.synchronize()
+            print("graph replay fused=%d seed=%d" % (fused, seed), flush=True)
+            graph.replay()
+            res.check(want, "replay %d" % seed)
+        del graph
+    finally:
+        assert tuna.tuna_plan_free(plan) == 0
