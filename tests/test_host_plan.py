@@ -241,3 +241,41 @@ def test_select_radix_model():
     rc, rl, rg, ms_small = tuna.tuna_select_radix(256, 0, 1 << 10)
     assert rc == 0 and rl == 256 and ms_small < 1.0
     assert tuna.tuna_select_radix(12, 5, 100)[0] == tuna.TUNA_ERR_ARG
+
+
+def test_random_schedules_deliver_every_block():
+    """Property test over random (Q, N, r_l, r_g): the tables always deliver every block, in both the
+    three-stage and the fused layout of T."""
+    from hypothesis import given, settings, strategies as st
+
+    @settings(max_examples=40, deadline=None)
+    @given(st.integers(1, 7), st.integers(1, 7), st.integers(2, 9), st.integers(2, 9), st.booleans(),
+           st.integers(0, 1000))
+    def prop(Q, N, rl, rg, fused, seed):
+        P = Q * N
+        counts = (wl.counts_uniform_bytes(P, seed, 5)).astype(np.int32)
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 1 if fused else 0)
+        try:
+            R, S, _ = _replay(counts, Q, rl, rg, fused=fused)
+        finally:
+            tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+        assert R == _want(S)
+    prop()
+
+
+def test_compute_entry_points_fail_loudly_without_a_gpu():
+    """No CPU fallback: on a machine without a HIP device every compute entry point returns
+    TUNA_ERR_HIP (the host-only schedule functions keep working)."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    lib = tuna.load()
+    rc = lib.tuna_alltoallv(1, 1, 1, 1, 1, 1, 4, 2, 0, None)           # never dereferenced: no device
+    assert rc == tuna.TUNA_ERR_HIP
+    import ctypes
+    plan = ctypes.c_void_p(None)
+    assert lib.tuna_alltoallv_init(1, 1, 1, 1, 1, 1, 4, 0, 2, 2, None, ctypes.byref(plan)) == tuna.TUNA_ERR_HIP
+    assert lib.tuna_plain_copy(16, 32, 16, None) == tuna.TUNA_ERR_HIP
+    out = ctypes.c_size_t(0)
+    assert lib.tuna_workspace_bytes(1, 4, 0, 2, 2, ctypes.byref(out)) == tuna.TUNA_ERR_HIP
+    assert tuna.tuna_plan_info(4, 0, 2, 2)[0] == 0
