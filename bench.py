@@ -32,7 +32,8 @@ HBM_PEAK_GBS = 8000.0
 # `rocprofv3 --pmc` runs (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter
 # reads for tuna::k_plain_copy moving 4 GiB (factors 2.0000 and 0.9998).  The algorithmic figure
 # for the same launches is 2 x payload = 22.55e9 bytes; see profiles/k_copy_config4_P4096.md.
-MEASURED_TRAFFIC_CONFIG4 = {"pack": 22979.9 * 2**20, "exchange": 22784.7 * 2**20, "unpack": 22699.3 * 2**20}
+MEASURED_TRAFFIC_CONFIG4 = {"pack": 23316.0 * 2**20, "exchange": 22822.0 * 2**20, "unpack": 22663.0 * 2**20,
+                            "fused": 23780.9 * 2**20}
 
 
 def parse_args():
@@ -263,7 +264,7 @@ def main():
         name, (ms, n, alg) = dom
         kname = {"pack": "tuna::k_copy<0, %d>" % gran, "exchange": "tuna::k_copy<1, 16>",
                  "unpack": "tuna::k_copy<2, %d>" % gran, "fused": "tuna::k_copy<3, %d>" % gran}[name]
-        default_run = (args.config == 4 and P == 4096 and not args.radices and not args.fused)
+        default_run = (args.config == 4 and P == 4096 and not args.radices)
         traffic = MEASURED_TRAFFIC_CONFIG4.get(name) if default_run else None
         achieved = alg / (ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": kname, "stage": name, "achieved": achieved, "peak": HBM_PEAK_GBS,
