@@ -181,7 +181,8 @@ int tuna_plain_copy(const void* src, void* dst, size_t bytes, void* stream);
  */
 int tuna_set_workspace(void* workspace, size_t bytes);
 
-/* Frees the library-owned workspace and cached schedules (after the caller has synchronised). */
+/* Frees the library-owned workspace and cached schedules (waits for the device first).  Returns
+ * TUNA_ERR_ARG while persistent plans exist: free them first. */
 int tuna_release(void);
 
 /*

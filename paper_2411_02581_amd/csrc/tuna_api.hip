@@ -49,6 +49,7 @@ struct Ctx {
     std::vector<Mark> marks;
     hipEvent_t ev_end = nullptr;
     bool end_recorded = false;
+    int live_plans = 0;                 // persistent plans not yet freed (they point into `plans`)
     const void* stats_plan = nullptr;   // the statistics on file belong to this persistent plan (payload bytes known)
     int last_hip_error = 0;
 };
@@ -152,8 +153,7 @@ DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long tot
 }
 
 int get_plan(int P, int Q, int rl, int rg, bool fused, DevicePlan** out) {
-    PlanHost probe;   // clamp radices the same way make_plan does
-    const int N = P / Q;
+    const int N = P / Q;                 // radices are clamped the way make_plan clamps them
     int crl = rl < 2 ? 2 : rl, crg = rg < 2 ? 2 : rg;
     if (Q >= 2 && crl > Q) crl = Q;
     if (N >= 2 && crg > N) crg = N;
@@ -189,7 +189,6 @@ int get_plan(int P, int Q, int rl, int rg, bool fused, DevicePlan** out) {
         it = g.plans.emplace(key, std::move(dp)).first;
     }
     *out = &it->second;
-    (void)probe;
     return TUNA_OK;
 }
 
@@ -536,7 +535,7 @@ int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* s
                           pr, hs, &plan->empty);
     if (rc != TUNA_OK) { delete plan; return rc; }
     fill_stats_header(pr, hs, plan->stats);
-    if (plan->empty) { *out = plan; return TUNA_OK; }
+    if (plan->empty) { ++g.live_plans; *out = plan; return TUNA_OK; }
     const PlanHost& pl = pr.dp->host;
     const size_t nph = pl.phases.size();
     // metadata memory: two size matrices + per phase two complete layouts
@@ -594,6 +593,7 @@ int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* s
     plan->stats.temp_bytes = (int64_t)pr.ds.t_bytes;
     plan->stats.staging_bytes = (int64_t)(2 * stage_bytes);
     plan->stats.workspace_bytes = (int64_t)(mbytes + dbytes);
+    ++g.live_plans;
     *out = plan;
     return TUNA_OK;
 }
@@ -672,6 +672,7 @@ int tuna_plan_free(tuna_plan_t plan) {
     if (p->mem_meta) (void)hipFree(p->mem_meta);
     if (p->mem_data) (void)hipFree(p->mem_data);
     delete p;
+    --g.live_plans;
     return TUNA_OK;
 }
 
@@ -726,6 +727,7 @@ int tuna_set_workspace(void* workspace, size_t bytes) {
 
 int tuna_release(void) {
     if (!g.ready) return TUNA_OK;
+    if (g.live_plans > 0) return TUNA_ERR_ARG;      // persistent plans use the cached schedules
     HIPCHK(hipDeviceSynchronize());
     if (g.meta) { HIPCHK(hipFree(g.meta)); g.meta = nullptr; g.meta_bytes = 0; }
     if (g.data) { HIPCHK(hipFree(g.data)); g.data = nullptr; g.data_bytes = 0; }

@@ -15,15 +15,11 @@ namespace tuna {
 
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));   // one 16-byte chunk
 
-#ifndef TUNA_COPY_THREADS
-#define TUNA_COPY_THREADS 256
-#endif
+// Shape of the copy kernels' work, chosen by measurement on MI355X: workgroups of 64, 128, 512 and
+// 1024 threads and 2 or 8 chunks per lane were all slower than 256 threads x 4 chunks.
 constexpr int kWave = 64;
-constexpr int kCopyThreads = TUNA_COPY_THREADS;                        // 4 waves, each an independent work unit
-#ifndef TUNA_CHUNKS_PER_LANE
-#define TUNA_CHUNKS_PER_LANE 4
-#endif
-constexpr int kChunksPerLane = TUNA_CHUNKS_PER_LANE;
+constexpr int kCopyThreads = 256;                        // 4 waves, each an independent work unit
+constexpr int kChunksPerLane = 4;
 constexpr int kUnitChunks = kWave * kChunksPerLane;      // 256 chunks = 4 KiB per wave unit
 constexpr int kScanThreads = 256;
 constexpr int kScanItems = 4;
@@ -39,7 +35,7 @@ struct Status {
     unsigned int flags;            // bit 0: negative count, bit 1: recvcounts != transpose(sendcounts)
     unsigned int align_bits;       // OR of all counts and displacements (low bits decide the granularity)
     int max_count;                 // M
-    int pad;
+    int reserved;
     unsigned long long total_bytes;    // sum of sendcounts
     unsigned long long total_chunks;   // sum of ceil(count / 16)
     unsigned long long send_extent;    // max over non-empty blocks of sdispls + count: bytes of sendbuf that hold blocks
@@ -545,10 +541,7 @@ __device__ __forceinline__ unsigned long long block_address(int slot, bool far_i
 
 // Waves per SIMD: measured on MI355X, the gathering kernels (pack, exchange) run fastest with at most 6
 // resident waves per SIMD, the scattering unpack with as many as fit.
-#ifndef TUNA_FUSED_MAX_WAVES
-#define TUNA_FUSED_MAX_WAVES 8
-#endif
-constexpr int copy_max_waves(int mode) { return mode == kUnpack ? 8 : (mode == kFused ? TUNA_FUSED_MAX_WAVES : 6); }
+constexpr int copy_max_waves(int mode) { return (mode == kUnpack || mode == kFused) ? 8 : 6; }
 template <int MODE, int GRAN>
 __global__ void __launch_bounds__(kCopyThreads) __attribute__((amdgpu_waves_per_eu(1, copy_max_waves(MODE))))
 k_copy(const CopyArgs a) {
