@@ -47,6 +47,7 @@ def parse_args():
     ap.add_argument("--fused", type=int, default=0, help="1: fused single-kernel rounds")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fused-table", action="store_true", help="skip the second sweep with fused rounds")
+    ap.add_argument("--no-secondary", action="store_true", help="skip the P=1024 hierarchical workload")
     ap.add_argument("--no-persistent-table", action="store_true", help="skip the tuna_alltoallv_init / tuna_start sweep")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--traffic-json", type=str, default="",
@@ -277,8 +278,15 @@ def main():
     if not args.no_cpu_baseline:
         cpu_baseline = time_oracle(lay, send, args.cpu_seconds)
 
+    also = None
+    if args.config == 4 and not args.ranks and not args.radices and not args.no_secondary:
+        also = {"config 3: " + wl.CONFIGS[3].description: quick_sweep(tuna, 3, args.steps, args.warmup)}
+
     out = {
-        "metric": "effective Alltoallv GB/s (payload bytes / call time) at the best radix; per-radix table and HBM roofline attached",
+        "metric": "effective Alltoallv GB/s and % of HBM peak vs radix, at P=1024/4096",
+        "metric_note": "value = payload bytes / time per tuna_alltoallv call (three-stage phases) at the best radix of "
+                       "the P=4096 workload; per_radix has every radix, roofline the copy kernels' share of the HBM "
+                       "peak, also_measured the P=1024 hierarchical workload",
         "value": best["effective_GBs"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": best["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u8", "data": "synthetic",
@@ -286,11 +294,73 @@ def main():
                    "payload_bytes": Btot, "best_radix": best["radix"], "fused": bool(args.fused),
                    "ranks_per_node": rpn},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "copy_ceiling": copy_ceiling, "per_radix": per_radix, "persistent": persistent,
+        "also_measured": also,
         "fused_rounds": None if fused_table is None else {
             "note": "same workload with TUNA_OPT_FUSED: one kernel per digit phase moves S/T to R/T directly",
             "best_effective_GBs": max(r["effective_GBs"] for r in fused_table), "per_radix": fused_table},
     }
     print(json.dumps(out))
+
+
+def quick_sweep(tuna, cfg_id, steps, warmup):
+    """Wall-clock sweep of another configuration: immediate calls with three-stage phases and with
+    fused rounds, and starts of a persistent plan with fused rounds."""
+    import torch
+
+    import workloads as wl
+    cfg = wl.CONFIGS[cfg_id]
+    lay = wl.make_layout(wl.make_counts(cfg_id))
+    dev = "cuda:0"
+    send = wl.payload_position_hash_torch(cfg.seed, lay.send_bytes, dev)
+    recv = torch.empty(lay.recv_bytes, dtype=torch.uint8, device=dev)
+    d = [torch.from_numpy(a).to(dev) for a in (lay.sendcounts, lay.sdispls, lay.recvcounts, lay.rdispls)]
+    rows = []
+    for kind, rpn, rl, rg in sweep_of(cfg_id, cfg.P):
+        row = {"radix": "r_l=%d,r_g=%d" % (rl, rg) if kind == "hier" else "r=%d" % rl}
+        for mode, fused in (("staged", 0), ("fused", 1)):
+            tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, fused)
+            try:
+                def call():
+                    if kind == "hier":
+                        rc = tuna.tuna_alltoallv_hier(send, d[0], d[1], recv, d[2], d[3], cfg.P, rpn, rl, rg)
+                    else:
+                        rc = tuna.tuna_alltoallv(send, d[0], d[1], recv, d[2], d[3], cfg.P, rl, rpn)
+                    if rc != 0:
+                        raise RuntimeError(tuna.tuna_strerror(rc))
+                for _ in range(warmup):
+                    call()
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                for _ in range(steps):
+                    call()
+                torch.cuda.synchronize()
+                ms = (time.perf_counter() - t1) * 1e3 / steps
+                row[mode + "_ms"] = ms
+                row[mode + "_GBs"] = lay.payload_bytes / (ms * 1e-3) / 1e9
+                if fused:
+                    rc, plan = tuna.tuna_alltoallv_init(send, d[0], d[1], recv, d[2], d[3], cfg.P, rpn, rl, rg)
+                    if rc != 0:
+                        raise RuntimeError(tuna.tuna_strerror(rc))
+                    try:
+                        for _ in range(warmup):
+                            tuna.tuna_start(plan)
+                        torch.cuda.synchronize()
+                        t1 = time.perf_counter()
+                        for _ in range(steps):
+                            tuna.tuna_start(plan)
+                        torch.cuda.synchronize()
+                        ms = (time.perf_counter() - t1) * 1e3 / steps
+                    finally:
+                        tuna.tuna_plan_free(plan)
+                    row["persistent_fused_ms"] = ms
+                    row["persistent_fused_GBs"] = lay.payload_bytes / (ms * 1e-3) / 1e9
+            finally:
+                tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+        rows.append(row)
+        print("[bench] config %d %s: staged %.3f ms (%.0f GB/s), fused %.3f ms, persistent fused %.3f ms" %
+              (cfg_id, row["radix"], row["staged_ms"], row["staged_GBs"], row["fused_ms"], row["persistent_fused_ms"]),
+              file=sys.stderr, flush=True)
+    return {"P": cfg.P, "payload_bytes": lay.payload_bytes, "per_radix": rows}
 
 
 def time_oracle(lay, send_dev, target_seconds):
