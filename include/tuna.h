@@ -218,6 +218,12 @@ int tuna_plan_info(int P, int ranks_per_node, int local_radix, int global_radix,
 int tuna_plan_phase(int P, int ranks_per_node, int local_radix, int global_radix, int phase,
                     int32_t* header, int32_t* seg, int seg_capacity);
 
+/* The same table as the device holds it (the kernels read tables that k_build_phase_table built
+ * on the GPU with the same index arithmetic): four int32 per moving block in message order,
+ * {e, z, source slot, destination slot}.  Needs a GPU; synchronises.  For verification. */
+int tuna_plan_phase_device(int P, int ranks_per_node, int local_radix, int global_radix, int phase,
+                           int32_t* seg, int seg_capacity);
+
 /*
  * Radix choice for one GPU.  The paper picks r from P and the block size because each of its K
  * rounds pays a network latency (Section "Performance analysis of TuNA", "Radix selection":

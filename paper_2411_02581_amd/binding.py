@@ -28,7 +28,7 @@ TUNA_MAX_PHASES = 64
 
 EXPORTS = ("tuna_alltoallv", "tuna_alltoallv_hier", "tuna_workspace_bytes", "tuna_set_workspace",
            "tuna_release", "tuna_set_option", "tuna_get_stats", "tuna_plan_info", "tuna_plan_phase",
-           "tuna_t_index", "tuna_plain_copy", "tuna_select_radix", "tuna_alltoallv_init", "tuna_start", "tuna_plan_free",
+           "tuna_t_index", "tuna_plan_phase_device", "tuna_plain_copy", "tuna_select_radix", "tuna_alltoallv_init", "tuna_start", "tuna_plan_free",
            "tuna_strerror", "tuna_version")
 
 
@@ -100,6 +100,7 @@ def load() -> ctypes.CDLL:
     lib.tuna_plan_phase.argtypes = [i, i, i, i, i, vp, vp, i]
     lib.tuna_select_radix.argtypes = [i, i, ctypes.c_int64, ctypes.POINTER(ctypes.c_int),
                                       ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_double)]
+    lib.tuna_plan_phase_device.argtypes = [i, i, i, i, i, vp, i]
     lib.tuna_t_index.argtypes = [i, i]
     lib.tuna_plain_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.tuna_strerror.argtypes = [i]
@@ -228,6 +229,14 @@ def tuna_select_radix(P: int, ranks_per_node: int, payload_bytes: int):
     rc = load().tuna_select_radix(P, ranks_per_node, payload_bytes, ctypes.byref(rl), ctypes.byref(rg),
                                   ctypes.byref(ms))
     return rc, rl.value, rg.value, ms.value
+
+
+def tuna_plan_phase_device(P: int, ranks_per_node: int, local_radix: int, global_radix: int, phase: int, nseg: int):
+    """Returns (code, seg[nseg,4]) as the device holds the table: {e, z, src_slot, dst_slot}."""
+    import numpy as np
+    seg = np.zeros((nseg, 4), dtype=np.int32)
+    rc = load().tuna_plan_phase_device(P, ranks_per_node, local_radix, global_radix, phase, seg.ctypes.data, nseg)
+    return rc, seg
 
 
 def tuna_t_index(o: int, radix: int) -> int:

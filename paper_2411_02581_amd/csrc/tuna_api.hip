@@ -25,6 +25,8 @@ struct DevicePlan {
     PlanHost host;
     std::vector<SegDev> d_seg;
     std::vector<int32_t*> d_seg_mem;
+    hipStream_t built_on = nullptr;      // stream the table kernels were enqueued on
+    bool complete = false;               // known to have finished (a later call synchronised)
     std::vector<int32_t*> d_zt;
 };
 
@@ -152,7 +154,10 @@ DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long tot
     return d;
 }
 
-int get_plan(int P, int Q, int rl, int rg, bool fused, DevicePlan** out) {
+// Cached schedule of (P, Q, r_l, r_g, fused).  The host keeps scalars only; the per-phase tables are
+// built on the device by k_build_phase_table, on the caller's stream (the kernels that read them
+// are enqueued behind it).
+int get_plan(int P, int Q, int rl, int rg, bool fused, hipStream_t s, DevicePlan** out) {
     const int N = P / Q;                 // radices are clamped the way make_plan clamps them
     int crl = rl < 2 ? 2 : rl, crg = rg < 2 ? 2 : rg;
     if (Q >= 2 && crl > Q) crl = Q;
@@ -163,30 +168,29 @@ int get_plan(int P, int Q, int rl, int rg, bool fused, DevicePlan** out) {
     auto it = g.plans.find(key);
     if (it == g.plans.end()) {
         DevicePlan dp;
-        dp.host = make_plan(P, Q, crl, crg, fused);
+        dp.host = make_plan(P, Q, crl, crg, fused, /*with_tables=*/false);
         if ((int)dp.host.phases.size() > TUNA_MAX_PHASES) return TUNA_ERR_TOO_LARGE;
         for (auto& ph : dp.host.phases) {
-            // field-major copy of the table: e[], z[], src[], dst[]
-            const size_t ns = ph.seg.size(), stride = align_up(ns * 4) / 4;
-            std::vector<int32_t> soa(4 * stride, 0);
-            for (size_t k = 0; k < ns; ++k) {
-                soa[k] = ph.seg[k].e; soa[stride + k] = ph.seg[k].z;
-                soa[2 * stride + k] = ph.seg[k].src_slot; soa[3 * stride + k] = ph.seg[k].dst_slot;
-            }
+            // field-major table: e[], z[], src[], dst[]
+            const size_t stride = align_up((size_t)ph.nseg * 4) / 4;
             int32_t* dm = nullptr;
             int32_t* dz = nullptr;
             HIPCHK(hipMalloc((void**)&dm, 4 * stride * 4 + kAlign));
             HIPCHK(hipMalloc((void**)&dz, align_up((size_t)P * 4)));
-            HIPCHK(hipMemcpy(dm, soa.data(), soa.size() * 4, hipMemcpyHostToDevice));
-            HIPCHK(hipMemcpy(dz, ph.zt.data(), (size_t)P * 4, hipMemcpyHostToDevice));
+            hipLaunchKernelGGL(k_build_phase_table, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, dp.host.sc,
+                               phase_scalars(ph), dm, dm + stride, dm + 2 * stride, dm + 3 * stride, dz);
+            HIPCHK(hipGetLastError());
             dp.d_seg.push_back(SegDev{dm, dm + stride, dm + 2 * stride, dm + 3 * stride});
             dp.d_seg_mem.push_back(dm);
             dp.d_zt.push_back(dz);
-            // the device copies are all the kernels need; drop the host tables
-            std::vector<SegInfo>().swap(ph.seg);
-            std::vector<int32_t>().swap(ph.zt);
         }
+        dp.built_on = s;
         it = g.plans.emplace(key, std::move(dp)).first;
+    }
+    // a cached schedule built on another stream: make sure its tables are complete
+    if (it->second.built_on != s && !it->second.complete) {
+        HIPCHK(hipStreamSynchronize(it->second.built_on));
+        it->second.complete = true;
     }
     *out = &it->second;
     return TUNA_OK;
@@ -337,7 +341,7 @@ int prepare_call(const void* sendbuf, const int32_t* sendcounts, const int64_t* 
     // staggered inter-node schedule: one block per message, N - 1 node distances, straight from T
     pr.staggered = g.opt_staggered != 0 && N > 1;
     if (pr.staggered) rg = N;
-    rc = get_plan(P, Q, rl, rg, pr.fused, &pr.dp);
+    rc = get_plan(P, Q, rl, rg, pr.fused, s, &pr.dp);
     if (rc != TUNA_OK) return rc;
     pr.sendbuf = sendbuf; pr.recvbuf = recvbuf; pr.sendcounts = sendcounts; pr.recvcounts = recvcounts;
     pr.sdispls = sdispls; pr.rdispls = rdispls;
@@ -345,6 +349,7 @@ int prepare_call(const void* sendbuf, const int32_t* sendcounts, const int64_t* 
     rc = run_validate(sendcounts, recvcounts, sdispls, rdispls, P, s);
     if (rc != TUNA_OK) return rc;
     hs = *g.h_status;
+    if (pr.dp->built_on == s) pr.dp->complete = true;      // run_validate synchronised this stream
     if (hs.flags & 1u) return TUNA_ERR_NEGATIVE_COUNT;
     if (hs.flags & 2u) return TUNA_ERR_COUNT_MISMATCH;
     *empty = hs.total_bytes == 0;
@@ -792,7 +797,7 @@ int tuna_plan_info(int P, int ranks_per_node, int local_radix, int global_radix,
     int rc = resolve_hierarchy(P, ranks_per_node, &Q);
     if (rc != TUNA_OK) return rc;
     if (g.opt_staggered && P / Q > 1) global_radix = P / Q;
-    const PlanHost pl = make_plan(P, Q, local_radix, global_radix, g.opt_fused != 0);
+    const PlanHost pl = make_plan(P, Q, local_radix, global_radix, g.opt_fused != 0, /*with_tables=*/false);
     out->P = P; out->Q = Q; out->N = pl.N;
     out->local_radix = pl.rl; out->global_radix = pl.rg;
     out->w_local = pl.w_l; out->w_global = pl.w_g;
@@ -822,6 +827,32 @@ int tuna_plan_phase(int P, int ranks_per_node, int local_radix, int global_radix
             int32_t* o = seg + (size_t)k * 6;
             o[0] = si.e; o[1] = si.j; o[2] = si.l; o[3] = si.z; o[4] = si.src_slot; o[5] = si.dst_slot;
         }
+    }
+    return TUNA_OK;
+}
+
+int tuna_plan_phase_device(int P, int ranks_per_node, int local_radix, int global_radix, int phase, int32_t* seg,
+                           int seg_capacity) {
+    if (!seg || local_radix < 2 || global_radix < 2 || phase < 0 || seg_capacity < 0) return TUNA_ERR_ARG;
+    int Q = 0;
+    int rc = resolve_hierarchy(P, ranks_per_node, &Q);
+    if (rc != TUNA_OK) return rc;
+    rc = ensure_ctx();
+    if (rc != TUNA_OK) return rc;
+    if (g.opt_staggered && P / Q > 1) global_radix = P / Q;
+    DevicePlan* dp = nullptr;
+    rc = get_plan(P, Q, local_radix, global_radix, g.opt_fused != 0, nullptr, &dp);
+    if (rc != TUNA_OK) return rc;
+    if (phase >= (int)dp->host.phases.size()) return TUNA_ERR_ARG;
+    HIPCHK(hipDeviceSynchronize());
+    dp->complete = true;
+    const int nseg = dp->host.phases[phase].nseg;
+    const int n = seg_capacity < nseg ? seg_capacity : nseg;
+    std::vector<int32_t> f((size_t)n);
+    const int32_t* src[4] = {dp->d_seg[phase].e, dp->d_seg[phase].z, dp->d_seg[phase].src, dp->d_seg[phase].dst};
+    for (int c = 0; c < 4; ++c) {
+        if (n) HIPCHK(hipMemcpy(f.data(), src[c], (size_t)n * 4, hipMemcpyDeviceToHost));
+        for (int k = 0; k < n; ++k) seg[(size_t)k * 4 + c] = f[k];
     }
     return TUNA_OK;
 }

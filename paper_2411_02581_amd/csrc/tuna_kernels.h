@@ -97,6 +97,29 @@ __global__ void k_clear(unsigned int* w, int n) {
 }
 
 // ------------------------------------------------------------------------------------------
+// k_build_phase_table: the rank-independent table of one digit phase, built on the device.  One
+// thread per slot index e: its digit value z in this phase (Algorithm "TuNA", lines 8-11: the
+// blocks whose x-th base-r digit equals z), its position in message order, the T slot it is read
+// from / stored to by the map t = o - 1 - dx (r-1) - dz (Section "Estimating temporary buffer
+// size"), or -1 for the send / receive buffer.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_build_phase_table(const PlanScalars pl, const PhaseScalars ph,
+                                                           int32_t* __restrict__ seg_e, int32_t* __restrict__ seg_z,
+                                                           int32_t* __restrict__ seg_src, int32_t* __restrict__ seg_dst,
+                                                           int32_t* __restrict__ zt) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= pl.P) return;
+    SegInfo s;
+    int pos = 0;
+    if (slot_entry(pl, ph, e, &s, &pos)) {
+        zt[e] = s.z;
+        seg_e[pos] = s.e; seg_z[pos] = s.z; seg_src[pos] = s.src_slot; seg_dst[pos] = s.dst_slot;
+    } else {
+        zt[e] = 0;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // k_plain_copy: one aligned 16-byte chunk per thread, nothing else.  The practical HBM copy
 // ceiling of the device and the known-size reference that hardware byte counters are scaled by.
 // ------------------------------------------------------------------------------------------

@@ -11,6 +11,12 @@
 #include <cstdint>
 #include <vector>
 
+#ifdef __HIPCC__
+#define TUNA_HD __host__ __device__
+#else
+#define TUNA_HD
+#endif
+
 namespace tuna {
 
 // One moving block of a phase, in message order (z ascending, then e ascending).  32 bytes, read
@@ -33,8 +39,23 @@ struct PhaseHost {
     int size;          // Q or N
     int nz;            // valid digit values z = 1..nz (z*rx < size): point-to-point rounds in this phase
     int nseg;          // moving blocks per rank
-    std::vector<SegInfo> seg;     // [nseg]
-    std::vector<int32_t> zt;      // [P]: digit value of slot e in this phase, 0 = does not move
+    std::vector<SegInfo> seg;     // [nseg], only when the plan was made with tables
+    std::vector<int32_t> zt;      // [P]: digit value of slot e in this phase, 0 = does not move (with tables)
+};
+
+// The scalars every table entry is computed from; passed by value to the device.
+struct PlanScalars {
+    int P, Q, N, rl, rg;
+    int B_l, B_g;
+    long long foreign0;   // first T slot of the other nodes' groups
+    long long global0;    // first T slot of the global phase
+    long long slots1;     // slots of one copy of T
+    int fused;
+};
+
+struct PhaseScalars {
+    int dim, x, r, size, nz, nseg;
+    long long rx, rx1;    // r^x, r^(x+1)
 };
 
 struct PlanHost {
@@ -43,48 +64,128 @@ struct PlanHost {
     int64_t slots = 0;             // T slots per rank (fused: both copies)
     bool fused = false;
     int64_t blocks_sent = 0;       // per rank, all phases
+    PlanScalars sc{};
     std::vector<PhaseHost> phases;
 };
 
 // w = ceil(log_r size): smallest w with r^w >= size (Section "Tunable Radix").
-inline int num_digits(int64_t size, int64_t r) {
+TUNA_HD inline int num_digits(long long size, long long r) {
     int w = 0;
-    int64_t v = 1;
+    long long v = 1;
     while (v < size) { v *= r; ++w; }
     return w;
 }
 
 // K: rounds (x, z) with 0 <= x < w, 1 <= z < r and z*r^x < size.
-inline int num_rounds(int64_t size, int64_t r) {
+TUNA_HD inline int num_rounds(long long size, long long r) {
     int K = 0;
-    int64_t rx = 1;
+    long long rx = 1;
     for (int x = 0, w = num_digits(size, r); x < w; ++x, rx *= r) {
-        int64_t nz = (size - 1) / rx;
+        long long nz = (size - 1) / rx;
         K += (int)(nz < r - 1 ? nz : r - 1);
     }
     return K;
 }
 
-inline bool is_direct(int64_t o, int64_t r) {   // exactly one non-zero digit
+TUNA_HD inline bool is_direct(long long o, long long r) {   // exactly one non-zero digit
     if (o <= 0) return false;
     while (o % r == 0) o /= r;
     return o < r;
 }
 
 // t = o - 1 - dx (r-1) - dz (Section "Estimating temporary buffer size"); dx = floor(log_r o).
-inline int64_t t_index(int64_t o, int64_t r) {
+TUNA_HD inline long long t_index(long long o, long long r) {
     if (o <= 0 || is_direct(o, r)) return -1;
-    int64_t dx = 0, v = 1;
+    long long dx = 0, v = 1;
     while (v * r <= o) { v *= r; ++dx; }
-    const int64_t dz = o / v;
+    const long long dz = o / v;
     return o - 1 - dx * (r - 1) - dz;
+}
+
+// Number of coordinates c in [0, size) whose digit x (base r) equals z.
+TUNA_HD inline long long count_with_digit(const PhaseScalars& ph, int z) {
+    const long long full = ph.size / ph.rx1, rem = ph.size % ph.rx1;
+    long long part = rem - (long long)z * ph.rx;
+    part = part < 0 ? 0 : (part > ph.rx ? ph.rx : part);
+    return full * ph.rx + part;
+}
+
+// Number of coordinates whose digit is in 1 .. z-1 (closed form of the sum of count_with_digit).
+TUNA_HD inline long long count_below_digit(const PhaseScalars& ph, int z) {
+    const long long full = ph.size / ph.rx1, rem = ph.size % ph.rx1;
+    const long long a = rem / ph.rx, b = rem % ph.rx;
+    long long whole = (z - 1 < a - 1) ? (z - 1) : (a - 1);
+    if (whole < 0) whole = 0;
+    return (long long)(z - 1) * full * ph.rx + whole * ph.rx + ((a >= 1 && a <= z - 1) ? b : 0);
+}
+
+// Hops a block with distance pair (j, l) has made before phase (dim, x): non-zero digits of l
+// below x (all of l's digits once the global phases run) plus non-zero digits of j below x.
+TUNA_HD inline int hops_before(const PlanScalars& pl, const PhaseScalars& ph, int j, int l) {
+    int h = 0;
+    long long v = ph.dim == 0 ? l % ph.rx : l;
+    for (; v; v /= pl.rl) h += (v % pl.rl) != 0;
+    if (ph.dim == 1) for (v = j % ph.rx; v; v /= pl.rg) h += (v % pl.rg) != 0;
+    return h;
+}
+
+// The table entry of slot index e in a phase: false when the block does not move; else its digit
+// value, its position s in message order (z ascending, then e ascending -- Algorithm "TuNA", the
+// loop that collects the send indices runs over ascending i), where the sender reads it from and
+// where the receiver stores it.  The same function builds the tables on the device and, for the
+// host-only schedule queries, on the host.
+//   never moved (all lower digits zero)      -> source is the send buffer S
+//   final (no higher non-zero digit)         -> destination is the receive buffer R
+//   otherwise a T slot: [0, B_l) own-node blocks by the paper's map t over l; then (N-1)(Q-1)
+//   slots for blocks of the other nodes' groups that moved locally (they wait for the global
+//   phase); then B_g super-slots of Q blocks for the global phase (map t over j).
+TUNA_HD inline bool slot_entry(const PlanScalars& pl, const PhaseScalars& ph, int e, SegInfo* out, int* pos) {
+    const int Q = pl.Q;
+    const int j = e / Q, l = e - j * Q;
+    const int c = ph.dim == 0 ? l : j;
+    const int z = (int)((c / ph.rx) % ph.r);
+    if (z == 0) return false;
+    const long long rc = (c / ph.rx1) * ph.rx + (c % ph.rx);          // rank of c among those with digit z
+    const long long mult = ph.dim == 0 ? pl.N : Q;
+    const long long start = count_below_digit(ph, z) * mult;
+    *pos = (int)(ph.dim == 0 ? start + (long long)j * count_with_digit(ph, z) + rc : start + rc * Q + l);
+    auto local_slot = [&](int jj, int ll) -> int {
+        if (jj == 0) return (int)t_index(ll, pl.rl);
+        return (int)(pl.foreign0 + (long long)(jj - 1) * (Q - 1) + (ll - 1));
+    };
+    auto global_slot = [&](int jj, int ll) -> int { return (int)(pl.global0 + t_index(jj, pl.rg) * Q + ll); };
+    SegInfo s{};
+    s.e = e; s.j = j; s.l = l; s.z = z;
+    if (ph.dim == 0) {
+        s.src_slot = (l % ph.rx == 0) ? -1 : local_slot(j, l);
+        s.dst_slot = (j == 0 && l < ph.rx1) ? -1 : local_slot(j, l);
+    } else {
+        if (j % ph.rx == 0) s.src_slot = (l == 0) ? -1 : local_slot(j, l);
+        else                s.src_slot = global_slot(j, l);
+        s.dst_slot = (j < ph.rx1) ? -1 : global_slot(j, l);
+    }
+    if (pl.fused) {   // the copy of T is the parity of the hop count
+        const int h = hops_before(pl, ph, j, l);
+        if (s.src_slot >= 0) s.src_slot += (int)((h & 1) * pl.slots1);
+        if (s.dst_slot >= 0) s.dst_slot += (int)(((h + 1) & 1) * pl.slots1);
+    }
+    *out = s;
+    return true;
+}
+
+inline PhaseScalars phase_scalars(const PhaseHost& ph) {
+    PhaseScalars s{};
+    s.dim = ph.dim; s.x = ph.x; s.r = ph.r; s.size = ph.size; s.nz = ph.nz; s.nseg = ph.nseg;
+    s.rx = ph.rx; s.rx1 = ph.rx * ph.r;
+    return s;
 }
 
 // fused = true lays T out twice: a phase then reads every block it forwards from one copy and
 // stores every block it receives into the other, so that one kernel can do both at once.  The
 // copy a block sits in is the parity of the number of hops it has made, which depends on its
 // index only -- it is folded into the slot numbers of the tables.
-inline PlanHost make_plan(int P, int Q, int rl, int rg, bool fused = false) {
+// with_tables = false computes the scalars only (the device builds its own tables).
+inline PlanHost make_plan(int P, int Q, int rl, int rg, bool fused = false, bool with_tables = true) {
     PlanHost pl;
     pl.P = P; pl.Q = Q; pl.N = P / Q;
     const int N = pl.N;
@@ -97,30 +198,14 @@ inline PlanHost make_plan(int P, int Q, int rl, int rg, bool fused = false) {
     pl.w_g = num_digits(N, rg);  pl.K_g = num_rounds(N, rg);
     pl.B_l = Q > 1 ? Q - 1 - pl.K_l : 0;      // B = size - (K + 1)
     pl.B_g = N > 1 ? N - 1 - pl.K_g : 0;
-    // T layout per rank: [0, B_l) own-node blocks still travelling (paper's map t over l);
-    // then (N-1)(Q-1) slots for blocks of the other nodes' groups that moved locally (they wait
-    // for the global phase); then B_g super-slots of Q blocks for the global phase (map t over j).
-    const int64_t foreign0 = pl.B_l;
-    const int64_t global0 = foreign0 + (int64_t)(N - 1) * (Q - 1);
-    const int64_t slots1 = global0 + (int64_t)pl.B_g * Q;
-    pl.slots = fused ? 2 * slots1 : slots1;
+    PlanScalars& sc = pl.sc;
+    sc.P = P; sc.Q = Q; sc.N = N; sc.rl = rl; sc.rg = rg; sc.B_l = pl.B_l; sc.B_g = pl.B_g;
+    sc.foreign0 = pl.B_l;
+    sc.global0 = sc.foreign0 + (long long)(N - 1) * (Q - 1);
+    sc.slots1 = sc.global0 + (long long)pl.B_g * Q;
+    sc.fused = fused ? 1 : 0;
+    pl.slots = fused ? 2 * sc.slots1 : sc.slots1;
     pl.fused = fused;
-    // hops a block with distance pair (j, l) has made before phase (dim, x): non-zero digits of l
-    // below x (all of l's digits once the global phases run) plus non-zero digits of j below x
-    auto hops_before = [&](int dim, int64_t rx, int j, int l) -> int {
-        int h = 0;
-        int64_t v = dim == 0 ? l % rx : l;
-        for (; v; v /= rl) h += (v % rl) != 0;
-        if (dim == 1) for (v = j % rx; v; v /= rg) h += (v % rg) != 0;
-        return h;
-    };
-    auto local_slot = [&](int j, int l) -> int32_t {
-        if (j == 0) return (int32_t)t_index(l, rl);
-        return (int32_t)(foreign0 + (int64_t)(j - 1) * (Q - 1) + (l - 1));
-    };
-    auto global_slot = [&](int j, int l) -> int32_t {
-        return (int32_t)(global0 + t_index(j, rg) * Q + l);
-    };
     for (int dim = 0; dim < 2; ++dim) {
         const int size = dim == 0 ? Q : N;
         const int r = dim == 0 ? rl : rg;
@@ -131,41 +216,18 @@ inline PlanHost make_plan(int P, int Q, int rl, int rg, bool fused = false) {
             ph.dim = dim; ph.x = x; ph.r = r; ph.rx = rx; ph.size = size;
             const int64_t nzmax = (size - 1) / rx;
             ph.nz = (int)(nzmax < r - 1 ? nzmax : r - 1);
-            ph.zt.assign(P, 0);
-            const int64_t rx1 = rx * r;
-            // message order: digit value z ascending, then slot index e ascending (Algorithm
-            // "TuNA", the loop that collects the send indices runs over ascending i)
-            std::vector<int32_t> first(ph.nz + 2, 0);
-            for (int j = 0; j < N; ++j)
-                for (int l = 0; l < Q; ++l) {
-                    const int z = (int)(((dim == 0 ? l : j) / rx) % r);
-                    ph.zt[j * Q + l] = z;
-                    if (z) ++first[z + 1];
-                }
-            for (int z = 1; z <= ph.nz; ++z) first[z + 1] += first[z];
-            ph.nseg = first[ph.nz + 1];
-            ph.seg.assign(ph.nseg, SegInfo{});
-            for (int j = 0; j < N; ++j)
-                for (int l = 0; l < Q; ++l) {
-                    const int z = ph.zt[j * Q + l];
-                    if (!z) continue;
+            PhaseScalars ps = phase_scalars(ph);
+            ph.nseg = (int)(count_below_digit(ps, ph.nz + 1) * (dim == 0 ? N : Q));
+            ps.nseg = ph.nseg;
+            if (with_tables) {
+                ph.zt.assign(P, 0);
+                ph.seg.assign(ph.nseg, SegInfo{});
+                for (int e = 0; e < P; ++e) {
                     SegInfo s{};
-                    s.e = j * Q + l; s.j = j; s.l = l; s.z = z;
-                    if (dim == 0) {
-                        s.src_slot = (l % rx == 0) ? -1 : local_slot(j, l);
-                        s.dst_slot = (j == 0 && l < rx1) ? -1 : local_slot(j, l);
-                    } else {
-                        if (j % rx == 0) s.src_slot = (l == 0) ? -1 : local_slot(j, l);
-                        else             s.src_slot = global_slot(j, l);
-                        s.dst_slot = (j < rx1) ? -1 : global_slot(j, l);
-                    }
-                    if (fused) {
-                        const int h = hops_before(dim, rx, j, l);
-                        if (s.src_slot >= 0) s.src_slot += (int32_t)((h & 1) * slots1);
-                        if (s.dst_slot >= 0) s.dst_slot += (int32_t)(((h + 1) & 1) * slots1);
-                    }
-                    ph.seg[first[z]++] = s;
+                    int pos = 0;
+                    if (slot_entry(sc, ps, e, &s, &pos)) { ph.zt[e] = s.z; ph.seg[pos] = s; }
                 }
+            }
             pl.blocks_sent += ph.nseg;
             pl.phases.push_back(std::move(ph));
         }

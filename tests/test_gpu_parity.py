@@ -201,6 +201,21 @@ def test_fft_count_patterns(tuna, pattern):
     run_hier(tuna, prob, 16, 4, 12)
 
 
+@pytest.mark.parametrize("P,Q,rl,rg", [(16, 0, 2, 2), (30, 0, 3, 3), (64, 0, 64, 64), (24, 4, 2, 3), (60, 5, 5, 2),
+                                        (256, 16, 4, 8), (1000, 0, 10, 10)])
+def test_device_built_tables_match_the_host_schedule(tuna, P, Q, rl, rg, mode):
+    """The kernels read tables that k_build_phase_table built on the GPU; they must equal the
+    host-side schedule (which tests/test_host_plan.py replays on the CPU) entry for entry."""
+    rc, info = tuna.tuna_plan_info(P, Q, rl, rg)
+    assert rc == 0
+    for ph in range(info.n_phases):
+        rc, hdr, seg = tuna.tuna_plan_phase(P, Q, rl, rg, ph)
+        assert rc == 0
+        rc, dev = tuna.tuna_plan_phase_device(P, Q, rl, rg, ph, int(hdr[4]))
+        assert rc == 0
+        assert np.array_equal(dev, seg[:, [0, 3, 4, 5]]), (P, Q, rl, rg, ph, mode)
+
+
 def test_degenerate_inputs(tuna):
     # all blocks empty
     lay = wl.make_layout(np.zeros((9, 9), dtype=np.int32), gap=4)
