@@ -336,3 +336,36 @@ def test_plain_copy(tuna):
     torch.cuda.synchronize()
     assert torch.equal(dst[:n - 16], src[:n - 16]) and int(dst[n - 16:].sum()) == 0
     assert tuna.tuna_plain_copy(src, dst, 24) == tuna.TUNA_ERR_ARG
+
+
+def test_random_problems(tuna, mode):
+    """Seeded random problems: rank counts, hierarchy, radices, size distributions (empty rows and
+    columns, tiny and large blocks, every alignment), gaps and region order all vary."""
+    rng = np.random.default_rng(20241102 + (1 if mode == "fused" else 0))
+    for case in range(40):
+        Q = int(rng.integers(1, 9))
+        N = int(rng.integers(1, 9))
+        P = Q * N
+        kind = int(rng.integers(0, 4))
+        if kind == 0:
+            counts = rng.integers(0, 40, size=(P, P))
+        elif kind == 1:
+            counts = (rng.pareto(1.1, size=(P, P)) * 20).astype(np.int64).clip(0, 70000)
+        elif kind == 2:
+            counts = rng.integers(0, 3000, size=(P, P)) * (rng.random((P, P)) < 0.3)
+        else:
+            counts = rng.integers(0, 600, size=(P, P)) // 4 * 4
+        counts = counts.astype(np.int32)
+        if rng.random() < 0.3:
+            counts[rng.integers(0, P)] = 0            # a rank that sends nothing
+        if rng.random() < 0.3:
+            counts[:, rng.integers(0, P)] = 0         # a rank that receives nothing
+        gap = int(rng.integers(0, 20))
+        lay = wl.make_layout(counts, gap=gap, permute_seed=int(rng.integers(0, 1 << 30)) if rng.random() < 0.5 else None,
+                             align=int(rng.choice([1, 1, 4, 16])))
+        prob = Problem(lay, wl.payload_position_hash(case, lay.send_bytes))
+        rl = int(rng.integers(2, max(Q, 2) + 2))
+        rg = int(rng.integers(2, max(N, 2) + 2))
+        run_hier(tuna, prob, Q, rl, rg)
+        if rng.random() < 0.5:
+            run_flat(tuna, prob, int(rng.integers(2, P + 2)))

@@ -146,3 +146,31 @@ def test_start_captured_in_a_graph(tuna, fused):
         del graph
     finally:
         assert tuna.tuna_plan_free(plan) == 0
+
+
+def test_two_plans_on_two_streams(tuna):
+    """Plans own their memory: starts of different plans may overlap on different streams."""
+    lay_a = wl.make_layout(wl.make_counts(4, 96))
+    lay_b = wl.make_layout(wl.make_counts(3, 64))
+    a, b = Resident(lay_a), Resident(lay_b)
+    code, plan_a = tuna.tuna_alltoallv_init(a.send, a.sc, a.sd, a.recv, a.rc, a.rd, 96, 0, 4, 4)
+    assert code == 0
+    code, plan_b = tuna.tuna_alltoallv_init(b.send, b.sc, b.sd, b.recv, b.rc, b.rd, 64, 8, 2, 8)
+    assert code == 0
+    try:
+        want_a, want_b = a.load(1), b.load(2)
+        a.recv.fill_(CANARY)
+        b.recv.fill_(CANARY)
+        torch.cuda.synchronize()
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        for _ in range(3):
+            assert tuna.tuna_start(plan_a, stream=s1) == 0
+            assert tuna.tuna_start(plan_b, stream=s2) == 0
+        s1.synchronize()
+        s2.synchronize()
+        a.check(want_a, "plan a")
+        b.check(want_b, "plan b")
+    finally:
+        assert tuna.tuna_plan_free(plan_a) == 0
+        assert tuna.tuna_plan_free(plan_b) == 0
+    assert tuna.tuna_release() == 0          # no plan left: the cached schedules may go
