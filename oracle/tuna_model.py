@@ -13,7 +13,7 @@ examples of Figures 1, 2 and 4) and per-phase byte counts that the GPU library's
 are compared against.  The pass/fail oracle for payload bytes is the direct transpose in
 alltoallv_oracle.c; this model must itself reproduce that transpose, which is one of its pins.
 
-Readings taken where the printed algorithms are garbled (all listed in the design notes):
+Readings taken where the printed algorithms are garbled:
 half-open loop bounds (0 <= x < w, 1 <= z < r, 0 <= i < P) and rounds with z*r^x >= P skipped;
 "x-th digit is 1" means "equals z"; a received block with index i is final iff i < r^(x+1)
 (it has no higher non-zero digit), which gives the at-most r^x finals per round that

@@ -864,7 +864,7 @@ int tuna_select_radix(int P, int ranks_per_node, int64_t payload_bytes, int* loc
     int rc = resolve_hierarchy(P, ranks_per_node, &Q);
     if (rc != TUNA_OK) return rc;
     const int N = P / Q;
-    // measured on MI355X at P = 4096 (see profiles/): copy stages ~5.2e12 B/s, metadata kernels of
+    // measured on MI355X at P = 4096: copy stages ~5.2e12 B/s, metadata kernels of
     // a phase ~60 us + 20 ps per matrix entry, validation + rotation ~0.3 ms at P = 4096
     const double bw = 5.2e12, c = g.opt_fused ? 2.0 : 6.0;
     const double t_phase = 60e-6 + 2.0e-11 * (double)P * P, t_call = 50e-6 + 1.5e-11 * (double)P * P;
