@@ -132,7 +132,7 @@ struct DataSizes {
     size_t unit_cap;        // wave units per layout (upper bound)
     size_t stage_chunks;    // chunks per staging buffer
     long long slots;        // T slots per rank
-    long long slot_bytes;   // M rounded up to 16
+    long long slot_bytes;   // M rounded up to whole 128-byte lines
     size_t t_bytes;
     size_t total;
 };
