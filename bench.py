@@ -44,6 +44,9 @@ def parse_args():
     ap.add_argument("--config", type=int, default=4, help="workload configuration 1..5")
     ap.add_argument("--ranks", type=int, default=0, help="override P (reduced-size runs)")
     ap.add_argument("--radices", type=str, default="", help="comma-separated radix sweep")
+    ap.add_argument("--uniform-max-bytes", type=int, default=0,
+                    help="replace the configuration's counts by 8 * U{0..S/8} bytes (the paper's uniform [0, S] "
+                         "micro-benchmark with FP64 elements); use with --ranks and --radices")
     ap.add_argument("--fused", type=int, default=0, help="1: fused single-kernel rounds")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fused-table", action="store_true", help="skip the second sweep with fused rounds")
@@ -83,7 +86,10 @@ def main():
     cfg = wl.CONFIGS[args.config]
     P = args.ranks or cfg.P
     t0 = time.time()
-    counts = wl.make_counts(args.config, P)
+    if args.uniform_max_bytes:
+        counts = wl.counts_uniform_elements(P, cfg.seed, args.uniform_max_bytes // 8, 8)
+    else:
+        counts = wl.make_counts(args.config, P)
     lay = wl.make_layout(counts)
     Btot = lay.payload_bytes
     print("[bench] config %d: P=%d payload %.3f GiB, inputs built in %.1f s" %
@@ -290,7 +296,8 @@ def main():
         "value": best["effective_GBs"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": best["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u8", "data": "synthetic",
-        "config": {"workload": "config %d: %s" % (args.config, cfg.description), "P": P,
+        "config": {"workload": ("uniform [0, %d] bytes in FP64 elements, P=%d flat" % (args.uniform_max_bytes, P))
+                               if args.uniform_max_bytes else "config %d: %s" % (args.config, cfg.description), "P": P,
                    "payload_bytes": Btot, "best_radix": best["radix"], "fused": bool(args.fused),
                    "ranks_per_node": rpn},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "copy_ceiling": copy_ceiling, "per_radix": per_radix, "persistent": persistent,
