@@ -355,8 +355,13 @@ int prepare_call(const void* sendbuf, const int32_t* sendcounts, const int64_t* 
     *empty = hs.total_bytes == 0;
     if (*empty) return TUNA_OK;
     if (!sendbuf || !recvbuf) return TUNA_ERR_ARG;
-    // chunk prefixes are 32-bit per rank
-    if ((unsigned long long)P * (unsigned long long)((hs.max_count + 15) / 16) >= (1ull << 31)) return TUNA_ERR_TOO_LARGE;
+    // chunk prefixes are 32-bit per rank: what one rank stages in a phase is bounded both by all
+    // chunks there are and by P blocks of at most M bytes
+    {
+        const unsigned long long by_m = (unsigned long long)P * (unsigned long long)((hs.max_count + 15) / 16 + 1);
+        if ((hs.total_chunks + (unsigned long long)P < by_m ? hs.total_chunks + (unsigned long long)P : by_m) >= (1ull << 31))
+            return TUNA_ERR_TOO_LARGE;
+    }
     const unsigned int abits = hs.align_bits | (unsigned int)((uintptr_t)sendbuf & 15u) |
                                (unsigned int)((uintptr_t)recvbuf & 15u);
     pr.gran = (abits & 15u) == 0 ? 16 : ((abits & 3u) == 0 ? 4 : 1);

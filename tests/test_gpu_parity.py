@@ -369,3 +369,52 @@ def test_random_problems(tuna, mode):
         run_hier(tuna, prob, Q, rl, rg)
         if rng.random() < 0.5:
             run_flat(tuna, prob, int(rng.integers(2, P + 2)))
+
+
+def test_phase_bytes_closed_form(tuna, mode):
+    """Before digit phase x the block at rank p, index i started at rank s = p + (i mod r^x) bound
+    for s - i, so the bytes phase x moves follow from the counts alone:
+    b_x = sum over p and over i with digit_x(i) != 0 of sendcounts[s][(s - i) mod P]."""
+    P = 384
+    counts = wl.make_counts(4, P)
+    lay = wl.make_layout(counts)
+    prob = Problem(lay, wl.payload_position_hash(12, lay.send_bytes))
+    p = np.arange(P)[:, None]
+    i = np.arange(P)[None, :]
+    c64 = counts.astype(np.int64)
+    for r in (2, 5, 20, P):
+        run_flat(tuna, prob, r)
+        st = tuna.tuna_get_stats()
+        for x in range(st.n_phases):
+            rx = r ** x
+            s = (p + i % rx) % P
+            moving = (i // rx) % r != 0
+            b_x = int((c64[s, (s - i) % P] * moving).sum())
+            assert st.phase[x].payload_bytes == b_x, (r, x)
+            assert st.phase[x].blocks == int(moving.sum()) * P
+
+
+def test_temporary_buffer_too_large_is_an_error_not_a_crash(tuna, mode):
+    """T has one M-byte slot per intermediate block: one 512 MiB block among 64 ranks at radix 2
+    asks for terabytes.  The call must return TUNA_ERR_NOMEM, move nothing, and leave the library
+    usable; the same problem runs at radix P, which needs no T."""
+    P = 64
+    counts = np.zeros((P, P), dtype=np.int32)
+    counts[3, 40] = 512 << 20
+    counts[5, 6] = 100
+    lay = wl.make_layout(counts)
+    dev = "cuda:0"
+    send = wl.payload_position_hash_torch(77, lay.send_bytes, dev)
+    recv = torch.zeros(lay.recv_bytes, dtype=torch.uint8, device=dev)
+    d = [torch.from_numpy(a).to(dev) for a in (lay.sendcounts, lay.sdispls, lay.recvcounts, lay.rdispls)]
+    rc = tuna.tuna_alltoallv(send, d[0], d[1], recv, d[2], d[3], P, 2, 0)
+    assert rc == tuna.TUNA_ERR_NOMEM, tuna.tuna_strerror(rc)
+    torch.cuda.synchronize()
+    assert int(recv.count_nonzero()) == 0
+    rc = tuna.tuna_alltoallv(send, d[0], d[1], recv, d[2], d[3], P, P, 0)
+    assert rc == 0, tuna.tuna_strerror(rc)
+    torch.cuda.synchronize()
+    so, ro, n = int(lay.sdispls[3, 40]), int(lay.rdispls[40, 3]), 512 << 20
+    assert torch.equal(recv[ro:ro + n], send[so:so + n])
+    so, ro = int(lay.sdispls[5, 6]), int(lay.rdispls[6, 5])
+    assert torch.equal(recv[ro:ro + 100], send[so:so + 100])
