@@ -80,7 +80,7 @@ typedef struct tuna_stats {
     int32_t granularity;             /* 16, 4 or 1: common divisor of all counts/displacements/base addresses */
     int32_t fused;                   /* 1 when the fused single-kernel rounds were used */
     int32_t last_hip_error;
-    int32_t reserved;
+    int32_t dense_t;                 /* 1 when T is stored in exact size (TUNA_OPT_DENSE_T, persistent plans) */
     int64_t max_block_bytes;         /* M (Algorithm "TuNA", line 1) */
     int64_t total_payload_bytes;     /* sum of sendcounts */
     int64_t temp_slots_per_rank;     /* slots of T actually laid out per rank */
@@ -143,7 +143,7 @@ int tuna_alltoallv_hier(const void* sendbuf, const int32_t* sendcounts, const in
  * tuna_alltoallv_init does everything that depends only on the counts -- validation, sizing,
  * every phase's block-size exchange, scans and work lists -- keeps the result in device memory
  * owned by the plan (it allocates and synchronises), and fixes the options in force
- * (TUNA_OPT_FUSED, TUNA_OPT_STAGGERED).  tuna_start only enqueues the payload kernels on
+ * (TUNA_OPT_FUSED, TUNA_OPT_STAGGERED, TUNA_OPT_DENSE_T).  tuna_start only enqueues the payload kernels on
  * `stream`: no allocation, no host synchronisation, no host-visible dependence on device data,
  * so it may be captured into a HIP graph (unless TUNA_OPT_PROFILE is on) and replayed.  The six
  * arrays must stay alive and unchanged while the plan exists; the contents of sendbuf may change
@@ -195,10 +195,18 @@ int tuna_release(void);
  * for hierarchical calls: after the intra-node phase every one of the Q (N - 1) blocks bound
  * for another node is its own message and goes straight from where it lies (its T slot, or S)
  * to R of its destination -- no rearrangement of T, no packing; the global radix is N.
+ * TUNA_OPT_DENSE_T: 1 = persistent plans store T in exact size.  Section "Estimating temporary
+ * buffer size" bounds T by B slots of M bytes, M the largest block of all; with skewed sizes
+ * nearly all of that is padding.  A plan knows every block size of every round when it is made,
+ * so it lays the blocks a rank stores into T in one phase back to back (padded to 16 bytes) in
+ * an arena of that phase: T then takes the bytes that really wait in it, summed over the
+ * phases, whatever M is.  Calls that are not persistent ignore the option (they size T before
+ * the per-round sizes are known).
  */
 #define TUNA_OPT_PROFILE 1
 #define TUNA_OPT_FUSED 2
 #define TUNA_OPT_STAGGERED 3
+#define TUNA_OPT_DENSE_T 4
 int tuna_set_option(int option, int value);
 
 /* Statistics of the last tuna_alltoallv* call (host struct).  Synchronises with that call's
@@ -217,6 +225,14 @@ int tuna_plan_info(int P, int ranks_per_node, int local_radix, int global_radix,
  * -1 (final: receive buffer)}. */
 int tuna_plan_phase(int P, int ranks_per_node, int local_radix, int global_radix, int phase,
                     int32_t* header, int32_t* seg, int seg_capacity);
+
+/* Host only (on_device = 0) or read back from the device's tables (on_device = 1; needs a GPU,
+ * synchronises): where every moving block of phase `phase` last moved before it -- two int32
+ * per block in message order, {phase in which it arrived in T, its position in that phase's
+ * message order}, or {-1, 0} for a block still in the send buffer.  Exact-size T finds a
+ * block through this pair. */
+int tuna_plan_phase_sources(int P, int ranks_per_node, int local_radix, int global_radix, int phase,
+                            int on_device, int32_t* out, int capacity);
 
 /* The same table as the device holds it (the kernels read tables that k_build_phase_table built
  * on the GPU with the same index arithmetic): four int32 per moving block in message order,

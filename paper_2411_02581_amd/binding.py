@@ -24,11 +24,12 @@ TUNA_ERR_TOO_LARGE = -7
 TUNA_OPT_PROFILE = 1
 TUNA_OPT_FUSED = 2
 TUNA_OPT_STAGGERED = 3
+TUNA_OPT_DENSE_T = 4
 TUNA_MAX_PHASES = 64
 
 EXPORTS = ("tuna_alltoallv", "tuna_alltoallv_hier", "tuna_workspace_bytes", "tuna_set_workspace",
            "tuna_release", "tuna_set_option", "tuna_get_stats", "tuna_plan_info", "tuna_plan_phase",
-           "tuna_t_index", "tuna_plan_phase_device", "tuna_plain_copy", "tuna_select_radix", "tuna_alltoallv_init", "tuna_start", "tuna_plan_free",
+           "tuna_t_index", "tuna_plan_phase_device", "tuna_plan_phase_sources", "tuna_plain_copy", "tuna_select_radix", "tuna_alltoallv_init", "tuna_start", "tuna_plan_free",
            "tuna_strerror", "tuna_version")
 
 
@@ -48,7 +49,7 @@ class tuna_stats_t(ctypes.Structure):
                 ("B_local", ctypes.c_int32), ("B_global", ctypes.c_int32),
                 ("n_phases", ctypes.c_int32), ("granularity", ctypes.c_int32),
                 ("fused", ctypes.c_int32), ("last_hip_error", ctypes.c_int32),
-                ("reserved", ctypes.c_int32),
+                ("dense_t", ctypes.c_int32),
                 ("max_block_bytes", ctypes.c_int64), ("total_payload_bytes", ctypes.c_int64),
                 ("temp_slots_per_rank", ctypes.c_int64), ("temp_bytes", ctypes.c_int64),
                 ("staging_bytes", ctypes.c_int64), ("workspace_bytes", ctypes.c_int64),
@@ -101,6 +102,7 @@ def load() -> ctypes.CDLL:
     lib.tuna_select_radix.argtypes = [i, i, ctypes.c_int64, ctypes.POINTER(ctypes.c_int),
                                       ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_double)]
     lib.tuna_plan_phase_device.argtypes = [i, i, i, i, i, vp, i]
+    lib.tuna_plan_phase_sources.argtypes = [i, i, i, i, i, i, vp, i]
     lib.tuna_t_index.argtypes = [i, i]
     lib.tuna_plain_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.tuna_strerror.argtypes = [i]
@@ -237,6 +239,16 @@ def tuna_plan_phase_device(P: int, ranks_per_node: int, local_radix: int, global
     seg = np.zeros((nseg, 4), dtype=np.int32)
     rc = load().tuna_plan_phase_device(P, ranks_per_node, local_radix, global_radix, phase, seg.ctypes.data, nseg)
     return rc, seg
+
+
+def tuna_plan_phase_sources(P: int, ranks_per_node: int, local_radix: int, global_radix: int, phase: int, nseg: int,
+                            on_device: bool = False):
+    """Returns (code, src[nseg,2]): {phase of the block's previous move or -1, its position there}."""
+    import numpy as np
+    out = np.zeros((nseg, 2), dtype=np.int32)
+    rc = load().tuna_plan_phase_sources(P, ranks_per_node, local_radix, global_radix, phase, 1 if on_device else 0,
+                                        out.ctypes.data, nseg)
+    return rc, out
 
 
 def tuna_t_index(o: int, radix: int) -> int:

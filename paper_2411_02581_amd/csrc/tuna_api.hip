@@ -20,6 +20,9 @@ namespace {
 
 constexpr int kVersion = 100;
 constexpr size_t kAlign = 256;
+// A one-kernel phase cuts chunks at the destination's 16-byte lines, so its last load of a block
+// that lies in T may run up to 15 bytes past the block: T is allocated with this much room behind it.
+constexpr size_t kTailSlack = 256;
 
 struct DevicePlan {
     PlanHost host;
@@ -46,7 +49,7 @@ struct Ctx {
     std::map<std::tuple<int, int, int, int, int>, DevicePlan> plans;
     tuna_stats_t stats;
     bool have_stats = false;
-    int opt_profile = 0, opt_fused = 0, opt_staggered = 0;
+    int opt_profile = 0, opt_fused = 0, opt_staggered = 0, opt_dense_t = 0;
     std::vector<hipEvent_t> ev_pool;
     std::vector<Mark> marks;
     hipEvent_t ev_end = nullptr;
@@ -150,7 +153,7 @@ DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long tot
     d.t_bytes = any_phase ? (size_t)pl.P * (size_t)d.slots * (size_t)d.slot_bytes : 0;
     // pl.slots already counts both copies of T when the plan is a fused one
     d.total = 2 * align_up(d.unit_cap * sizeof(int4)) + (fused ? 0 : 2 * align_up(d.stage_chunks * 16)) +
-              align_up(d.t_bytes);
+              align_up(d.t_bytes + kTailSlack);
     return d;
 }
 
@@ -171,16 +174,17 @@ int get_plan(int P, int Q, int rl, int rg, bool fused, hipStream_t s, DevicePlan
         dp.host = make_plan(P, Q, crl, crg, fused, /*with_tables=*/false);
         if ((int)dp.host.phases.size() > TUNA_MAX_PHASES) return TUNA_ERR_TOO_LARGE;
         for (auto& ph : dp.host.phases) {
-            // field-major table: e[], z[], src[], dst[]
+            // field-major table: e[], z[], src[], dst[], srcph[], srcseg[]
             const size_t stride = align_up((size_t)ph.nseg * 4) / 4;
             int32_t* dm = nullptr;
             int32_t* dz = nullptr;
-            HIPCHK(hipMalloc((void**)&dm, 4 * stride * 4 + kAlign));
+            HIPCHK(hipMalloc((void**)&dm, 6 * stride * 4 + kAlign));
             HIPCHK(hipMalloc((void**)&dz, align_up((size_t)P * 4)));
             hipLaunchKernelGGL(k_build_phase_table, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, dp.host.sc,
-                               phase_scalars(ph), dm, dm + stride, dm + 2 * stride, dm + 3 * stride, dz);
+                               phase_scalars(ph), dm, dm + stride, dm + 2 * stride, dm + 3 * stride, dm + 4 * stride,
+                               dm + 5 * stride, dz);
             HIPCHK(hipGetLastError());
-            dp.d_seg.push_back(SegDev{dm, dm + stride, dm + 2 * stride, dm + 3 * stride});
+            dp.d_seg.push_back(SegDev{dm, dm + stride, dm + 2 * stride, dm + 3 * stride, dm + 4 * stride, dm + 5 * stride});
             dp.d_seg_mem.push_back(dm);
             dp.d_zt.push_back(dz);
         }
@@ -223,29 +227,38 @@ void mark(hipStream_t s, int cat, int phase) {
 
 // One-shot grid over an upper bound of wave units (4 per workgroup); waves past the device-side
 // unit count exit immediately.
-template <int MODE>
-int launch_copy(int gran, size_t unit_cap, const CopyArgs& a, hipStream_t s) {
+template <int MODE, bool DENSE>
+int launch_copy_as(int gran, size_t unit_cap, const CopyArgs& a, hipStream_t s) {
     const size_t waves = kCopyThreads / kWave;
     const dim3 grid((unsigned)((unit_cap + waves - 1) / waves)), block(kCopyThreads);
     if (grid.x == 0) return TUNA_OK;
-    if (MODE == kExchange) {
-        hipLaunchKernelGGL((k_copy<MODE, 16>), grid, block, 0, s, a);
-    } else if (gran == 16) {
-        hipLaunchKernelGGL((k_copy<MODE, 16>), grid, block, 0, s, a);
+    if (MODE == kExchange || gran == 16) {
+        hipLaunchKernelGGL((k_copy<MODE, 16, DENSE>), grid, block, 0, s, a);
     } else if (gran == 4) {
-        hipLaunchKernelGGL((k_copy<MODE, 4>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((k_copy<MODE, 4, DENSE>), grid, block, 0, s, a);
     } else {
-        hipLaunchKernelGGL((k_copy<MODE, 1>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((k_copy<MODE, 1, DENSE>), grid, block, 0, s, a);
     }
     HIPCHK(hipGetLastError());
     return TUNA_OK;
+}
+
+template <int MODE>
+int launch_copy(int gran, size_t unit_cap, const CopyArgs& a, hipStream_t s) {
+    if (MODE != kExchange && a.dense) return launch_copy_as<MODE, true>(gran, unit_cap, a, s);
+    return launch_copy_as<MODE, false>(gran, unit_cap, a, s);
 }
 
 // Metadata of one digit phase: sizes exchanged, both staging layouts scanned, wave units cut.
 int phase_metadata(const PhaseLayoutArgs& a, hipStream_t s) {
     hipLaunchKernelGGL(k_phase_layout, dim3(a.P), dim3(kScanThreads), 0, s, a);
     HIPCHK(hipGetLastError());
-    hipLaunchKernelGGL(k_layout_base, dim3(a.want_send ? 2 : 1), dim3(kScanThreads), 0, s, a.P, a.Lr, a.Ls,
+    // layouts to scan: receive side, then the send side and / or the T-bound blocks where wanted
+    const LayoutDev* list[3] = {&a.Lr, &a.Lr, &a.Lr};
+    int nl = 1;
+    if (a.want_send) list[nl++] = &a.Ls;
+    if (a.want_tbound) list[nl++] = &a.Lt;
+    hipLaunchKernelGGL(k_layout_base, dim3(nl), dim3(kScanThreads), 0, s, a.P, *list[0], *list[1], *list[2],
                        a.phase_chunks, a.want_send ? 1 : 0);
     HIPCHK(hipGetLastError());
     hipLaunchKernelGGL(k_layout_units, dim3(a.P, a.want_send ? 2 : 1), dim3(256), 0, s, a.nseg, a.Lr, a.Ls);
@@ -296,6 +309,7 @@ struct Prepared {
     v4u* stage_s = nullptr;
     v4u* stage_r = nullptr;
     unsigned char* T = nullptr;
+    const DenseT* dense = nullptr;      // exact-size T (persistent plans): per-phase arenas on the device
 };
 
 bool phase_is_one_kernel(const Prepared& pr, const PhaseHost& ph) {
@@ -372,13 +386,14 @@ int prepare_call(const void* sendbuf, const int32_t* sendcounts, const int64_t* 
 }
 
 int launch_phase_metadata(const Prepared& pr, size_t i, const int32_t* cur, int32_t* nxt, const LayoutDev& Ls,
-                          const LayoutDev& Lr, hipStream_t s) {
+                          const LayoutDev& Lr, hipStream_t s, const LayoutDev* Lt = nullptr) {
     const PhaseHost& ph = pr.dp->host.phases[i];
     const bool one_kernel = phase_is_one_kernel(pr, ph);
     PhaseLayoutArgs m{};
     m.cur = cur; m.nxt = nxt; m.zt = pr.dp->d_zt[i]; m.seg = pr.dp->d_seg[i]; m.nseg = ph.nseg;
     m.P = pr.P; m.Q = pr.Q; m.N = pr.N; m.dim = ph.dim; m.rx = (int)ph.rx;
     m.Ls = Ls; m.Lr = Lr; m.want_send = one_kernel ? 0 : 1;
+    if (Lt) { m.Lt = *Lt; m.want_tbound = 1; }
     m.phase_bytes = &g.d_status->phase_bytes[i]; m.phase_chunks = &g.d_status->phase_chunks[i];
     m.head_displs = one_kernel ? pr.rdispls : nullptr;
     m.head_base = (unsigned int)((uintptr_t)pr.recvbuf & 15u);
@@ -403,6 +418,7 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
     a.T = pr.T; a.slots = pr.ds.slots; a.slot_bytes = pr.ds.slot_bytes;
     a.P = pr.P; a.Q = pr.Q; a.N = pr.N; a.dim = ph.dim; a.rx = (int)ph.rx;
     a.user_limit = pr.user_limit;
+    a.dense = pr.dense; a.phase = (int)i;
     int rc;
     if (phase_is_one_kernel(pr, ph)) {
         // one hop in one kernel: S / T of the sender -> R / the other copy of T at the receiver
@@ -476,7 +492,7 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
     mb.Lr.units = cd.take<int4>(ds.unit_cap);
     pr.stage_s = cd.take<v4u>(pr.fused ? 0 : ds.stage_chunks);
     pr.stage_r = cd.take<v4u>(pr.fused ? 0 : ds.stage_chunks);
-    pr.T = cd.take<unsigned char>(ds.t_bytes);
+    pr.T = cd.take<unsigned char>(ds.t_bytes + kTailSlack);
     if (!cm.ok || !cd.ok) return TUNA_ERR_WORKSPACE_TOO_SMALL;
     st.temp_bytes = (int64_t)ds.t_bytes;
     st.staging_bytes = pr.fused ? 0 : (int64_t)(2 * ds.stage_chunks * 16);
@@ -517,6 +533,8 @@ struct Plan {
     void* mem_meta = nullptr;       // cur / nxt and every phase's two layouts
     void* mem_data = nullptr;       // staging and T
     std::vector<LayoutDev> Ls, Lr;  // per phase
+    std::vector<LayoutDev> Lt;      // per phase, exact-size T only: prefix over the T-bound blocks
+    bool dense = false;
     std::vector<size_t> units;      // per phase: exact number of wave units (max of the two layouts)
     tuna_stats_t stats;
     unsigned long long phase_bytes[TUNA_MAX_PHASES];
@@ -535,6 +553,20 @@ void carve_full_layout(Carver& cv, int P, size_t unit_cap, LayoutDev& L) {
     L.units = cv.take<int4>(unit_cap);
 }
 
+// prefix-only layout of the T-bound blocks of one phase (exact-size T)
+size_t tbound_layout_bytes_for(int P) {
+    const size_t ld = (size_t)P + 1;
+    return align_up((size_t)P * ld * 4) + align_up((size_t)P * 4) + align_up(((size_t)P + 1) * 8);
+}
+
+void carve_tbound_layout(Carver& cv, int P, LayoutDev& L) {
+    L.ld = P + 1;
+    L.pre = cv.take<int>((size_t)P * L.ld);
+    L.tot = cv.take<int>(P);
+    L.rank_base = cv.take<long long>(P + 1);
+    L.unit_base = nullptr; L.n_units = nullptr; L.units = nullptr;
+}
+
 int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
                 const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
                 hipStream_t s, Plan** out) {
@@ -550,7 +582,9 @@ int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* s
     const size_t nph = pl.phases.size();
     // metadata memory: two size matrices + per phase two complete layouts
     const size_t P2 = (size_t)P * P;
-    const size_t mbytes = 2 * align_up(P2 * 4) + nph * 2 * layout_bytes_for(P, pr.ds.unit_cap);
+    plan->dense = g.opt_dense_t != 0;
+    const size_t dense_meta = plan->dense ? nph * tbound_layout_bytes_for(P) + align_up(nph * sizeof(DenseT)) : 0;
+    const size_t mbytes = 2 * align_up(P2 * 4) + nph * 2 * layout_bytes_for(P, pr.ds.unit_cap) + dense_meta;
     hipError_t e = hipMalloc(&plan->mem_meta, mbytes ? mbytes : kAlign);
     if (e != hipSuccess) { (void)hipGetLastError(); g.last_hip_error = (int)e; delete plan; return TUNA_ERR_NOMEM; }
     Carver cm(plan->mem_meta, mbytes);
@@ -561,20 +595,28 @@ int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* s
         carve_full_layout(cm, P, pr.ds.unit_cap, plan->Ls[i]);
         carve_full_layout(cm, P, pr.ds.unit_cap, plan->Lr[i]);
     }
+    DenseT* d_dense = nullptr;
+    if (plan->dense) {
+        plan->Lt.resize(nph);
+        for (size_t i = 0; i < nph; ++i) carve_tbound_layout(cm, P, plan->Lt[i]);
+        d_dense = cm.take<DenseT>(nph);
+    }
     auto fail = [&](int code) { (void)hipFree(plan->mem_meta); if (plan->mem_data) (void)hipFree(plan->mem_data); delete plan; return code; };
     if (!cm.ok) return fail(TUNA_ERR_NOMEM);
     const unsigned gP2 = (unsigned)((P2 + 255) / 256);
     hipLaunchKernelGGL(k_rotate_init, dim3(gP2), dim3(256), 0, s, sendcounts, cur, P, pr.Q, pr.N);
     if (hipGetLastError() != hipSuccess) return fail(TUNA_ERR_HIP);
     for (size_t i = 0; i < nph; ++i) {
-        rc = launch_phase_metadata(pr, i, cur, nxt, plan->Ls[i], plan->Lr[i], s);
+        rc = launch_phase_metadata(pr, i, cur, nxt, plan->Ls[i], plan->Lr[i], s, plan->dense ? &plan->Lt[i] : nullptr);
         if (rc != TUNA_OK) return fail(rc);
         std::swap(cur, nxt);
     }
     // exact unit counts and staged chunks per phase
     std::vector<int> nu(2 * nph, 0);
+    std::vector<long long> tchunks(nph, 0);       // exact-size T: chunks every phase stores into T
     for (size_t i = 0; i < nph; ++i) {
         const bool one = phase_is_one_kernel(pr, pl.phases[i]);
+        if (plan->dense && hipMemcpyAsync(&tchunks[i], plan->Lt[i].rank_base + P, 8, hipMemcpyDeviceToHost, s) != hipSuccess) return fail(TUNA_ERR_HIP);
         if (hipMemcpyAsync(&nu[2 * i], plan->Lr[i].n_units, 4, hipMemcpyDeviceToHost, s) != hipSuccess) return fail(TUNA_ERR_HIP);
         if (!one && hipMemcpyAsync(&nu[2 * i + 1], plan->Ls[i].n_units, 4, hipMemcpyDeviceToHost, s) != hipSuccess) return fail(TUNA_ERR_HIP);
     }
@@ -589,17 +631,35 @@ int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* s
         plan->stats.phase[i].staged_bytes = (int64_t)plan->phase_chunks[i] * 16;
         if (!phase_is_one_kernel(pr, pl.phases[i])) max_chunks = std::max(max_chunks, plan->phase_chunks[i]);
     }
-    // payload memory: staging sized by the largest phase, T by M and the slot count
+    // payload memory: staging sized by the largest phase; T by M and the slot count, or -- exact
+    // size -- one arena per phase that holds just the blocks that phase stores into T
     const size_t stage_bytes = align_up((size_t)max_chunks * 16);
-    const size_t dbytes = 2 * stage_bytes + align_up(pr.ds.t_bytes);
+    if (plan->dense) {
+        pr.ds.t_bytes = 0;
+        for (size_t i = 0; i < nph; ++i) pr.ds.t_bytes += align_up((size_t)tchunks[i] * 16);
+        pr.ds.slots = 0;
+        plan->stats.temp_slots_per_rank = 0;
+    }
+    const size_t dbytes = 2 * stage_bytes + (pr.ds.t_bytes ? align_up(pr.ds.t_bytes + kTailSlack) : 0);
     if (dbytes) {
         e = hipMalloc(&plan->mem_data, dbytes);
         if (e != hipSuccess) { (void)hipGetLastError(); g.last_hip_error = (int)e; return fail(TUNA_ERR_NOMEM); }
         Carver cd(plan->mem_data, dbytes);
         pr.stage_s = cd.take<v4u>(stage_bytes / 16);
         pr.stage_r = cd.take<v4u>(stage_bytes / 16);
-        pr.T = cd.take<unsigned char>(pr.ds.t_bytes);
+        pr.T = cd.take<unsigned char>(pr.ds.t_bytes ? pr.ds.t_bytes + kTailSlack : 0);
     }
+    if (plan->dense) {
+        std::vector<DenseT> hd(nph);
+        size_t off = 0;
+        for (size_t i = 0; i < nph; ++i) {
+            hd[i] = DenseT{pr.T ? pr.T + off : nullptr, plan->Lt[i].pre, plan->Lt[i].rank_base, plan->Lt[i].ld, 0};
+            off += align_up((size_t)tchunks[i] * 16);
+        }
+        if (hipMemcpy(d_dense, hd.data(), nph * sizeof(DenseT), hipMemcpyHostToDevice) != hipSuccess) return fail(TUNA_ERR_HIP);
+        pr.dense = d_dense;
+    }
+    plan->stats.dense_t = plan->dense ? 1 : 0;
     plan->stats.temp_bytes = (int64_t)pr.ds.t_bytes;
     plan->stats.staging_bytes = (int64_t)(2 * stage_bytes);
     plan->stats.workspace_bytes = (int64_t)(mbytes + dbytes);
@@ -753,6 +813,7 @@ int tuna_set_option(int option, int value) {
     if (option == TUNA_OPT_PROFILE) { g.opt_profile = value ? 1 : 0; return TUNA_OK; }
     if (option == TUNA_OPT_FUSED) { g.opt_fused = value ? 1 : 0; return TUNA_OK; }
     if (option == TUNA_OPT_STAGGERED) { g.opt_staggered = value ? 1 : 0; return TUNA_OK; }
+    if (option == TUNA_OPT_DENSE_T) { g.opt_dense_t = value ? 1 : 0; return TUNA_OK; }
     return TUNA_ERR_ARG;
 }
 
@@ -858,6 +919,40 @@ int tuna_plan_phase_device(int P, int ranks_per_node, int local_radix, int globa
     for (int c = 0; c < 4; ++c) {
         if (n) HIPCHK(hipMemcpy(f.data(), src[c], (size_t)n * 4, hipMemcpyDeviceToHost));
         for (int k = 0; k < n; ++k) seg[(size_t)k * 4 + c] = f[k];
+    }
+    return TUNA_OK;
+}
+
+int tuna_plan_phase_sources(int P, int ranks_per_node, int local_radix, int global_radix, int phase,
+                            int on_device, int32_t* out, int capacity) {
+    if (!out || local_radix < 2 || global_radix < 2 || phase < 0 || capacity < 0) return TUNA_ERR_ARG;
+    int Q = 0;
+    int rc = resolve_hierarchy(P, ranks_per_node, &Q);
+    if (rc != TUNA_OK) return rc;
+    if (!on_device) {
+        const PlanHost pl = make_plan(P, Q, local_radix, global_radix, g.opt_fused != 0);
+        if (phase >= (int)pl.phases.size()) return TUNA_ERR_ARG;
+        const PhaseHost& ph = pl.phases[phase];
+        const int n = capacity < ph.nseg ? capacity : ph.nseg;
+        for (int k = 0; k < n; ++k) { out[2 * k] = ph.seg[k].src_phase; out[2 * k + 1] = ph.seg[k].src_seg; }
+        return TUNA_OK;
+    }
+    rc = ensure_ctx();
+    if (rc != TUNA_OK) return rc;
+    if (g.opt_staggered && P / Q > 1) global_radix = P / Q;
+    DevicePlan* dp = nullptr;
+    rc = get_plan(P, Q, local_radix, global_radix, g.opt_fused != 0, nullptr, &dp);
+    if (rc != TUNA_OK) return rc;
+    if (phase >= (int)dp->host.phases.size()) return TUNA_ERR_ARG;
+    HIPCHK(hipDeviceSynchronize());
+    dp->complete = true;
+    const int nseg = dp->host.phases[phase].nseg;
+    const int n = capacity < nseg ? capacity : nseg;
+    std::vector<int32_t> f((size_t)n);
+    const int32_t* src[2] = {dp->d_seg[phase].srcph, dp->d_seg[phase].srcseg};
+    for (int c = 0; c < 2; ++c) {
+        if (n) HIPCHK(hipMemcpy(f.data(), src[c], (size_t)n * 4, hipMemcpyDeviceToHost));
+        for (int k = 0; k < n; ++k) out[(size_t)k * 2 + c] = f[k];
     }
     return TUNA_OK;
 }

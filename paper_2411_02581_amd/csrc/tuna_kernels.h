@@ -49,6 +49,18 @@ struct SegDev {
     const int32_t* z;      // digit value: which message, partner distance z*r^x
     const int32_t* src;    // source T slot or -1 (send buffer)
     const int32_t* dst;    // destination T slot or -1 (receive buffer)
+    const int32_t* srcph;  // phase in which the block arrived in T, or -1 (send buffer)
+    const int32_t* srcseg; // its position in that phase's message order
+};
+
+// Exact-size T: the blocks a rank stores into T in one phase lie back to back, in message order,
+// in that phase's arena.  pre / rank_base are the chunk prefix of the T-bound blocks only.
+struct DenseT {
+    unsigned char* arena;
+    const int* pre;                // [P][ld]
+    const long long* rank_base;    // [P+1]
+    int ld;
+    int pad;
 };
 
 // Distance pair of a slot index.
@@ -106,6 +118,7 @@ __global__ void k_clear(unsigned int* w, int n) {
 __global__ void __launch_bounds__(256) k_build_phase_table(const PlanScalars pl, const PhaseScalars ph,
                                                            int32_t* __restrict__ seg_e, int32_t* __restrict__ seg_z,
                                                            int32_t* __restrict__ seg_src, int32_t* __restrict__ seg_dst,
+                                                           int32_t* __restrict__ seg_srcph, int32_t* __restrict__ seg_srcseg,
                                                            int32_t* __restrict__ zt) {
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= pl.P) return;
@@ -114,6 +127,7 @@ __global__ void __launch_bounds__(256) k_build_phase_table(const PlanScalars pl,
     if (slot_entry(pl, ph, e, &s, &pos)) {
         zt[e] = s.z;
         seg_e[pos] = s.e; seg_z[pos] = s.z; seg_src[pos] = s.src_slot; seg_dst[pos] = s.dst_slot;
+        seg_srcph[pos] = s.src_phase; seg_srcseg[pos] = s.src_seg;
     } else {
         zt[e] = 0;
     }
@@ -277,8 +291,9 @@ struct PhaseLayoutArgs {
     SegDev seg;
     int nseg;
     int P, Q, N, dim, rx;
-    LayoutDev Ls, Lr;
+    LayoutDev Ls, Lr, Lt;
     int want_send;                  // 0: only the receive-side layout (one-kernel phases)
+    int want_tbound;                // 1: also the prefix over the T-bound blocks alone (exact-size T)
     unsigned long long* phase_bytes;
     unsigned long long* phase_chunks;
     const int64_t* head_displs;
@@ -345,14 +360,13 @@ __device__ __forceinline__ void scan_rank_bases(int P, const LayoutDev& L, unsig
     for (int p = p0; p < p1; ++p) {
         const int c = L.tot[p];
         L.rank_base[p] = run_c;
-        L.unit_base[p] = run_t;
+        if (L.unit_base) L.unit_base[p] = run_t;
         run_c += c;
         run_t += (c + kUnitChunks - 1) / kUnitChunks;
     }
     if (tid == 0) {
         L.rank_base[P] = totc;
-        L.unit_base[P] = tott;
-        *L.n_units = tott;
+        if (L.unit_base) { L.unit_base[P] = tott; *L.n_units = tott; }
         if (phase_chunks) *phase_chunks = (unsigned long long)totc;
     }
 }
@@ -371,15 +385,18 @@ __global__ void __launch_bounds__(kScanThreads) k_phase_layout(const PhaseLayout
     // (1b) + (2) receive side: sizes arrive from the partner at distance z r^x, then the scan
     int* pre_r = a.Lr.pre + (size_t)p * a.Lr.ld;
     int* pre_s = a.Ls.pre + (size_t)p * a.Ls.ld;
-    int carry_r = 0, carry_s = 0;
+    int* pre_t = a.want_tbound ? a.Lt.pre + (size_t)p * a.Lt.ld : nullptr;
+    int carry_r = 0, carry_s = 0, carry_t = 0;
     unsigned long long bytes = 0;
     for (int base = 0; base < a.nseg; base += kScanThreads * kScanItems) {
-        int cr[kScanItems], cs[kScanItems];
+        int cr[kScanItems], cs[kScanItems], ct[kScanItems];
 #pragma unroll
         for (int k = 0; k < kScanItems; ++k) {
             const int s = base + tid * kScanItems + k;
             int szr = 0, szs = 0, head = 0;
+            bool tbound = false;
             if (s < a.nseg) {
+                tbound = a.want_tbound && a.seg.dst[s] >= 0;
                 const int e = a.seg.e[s];
                 const int ps = partner_up(pn, pg, a.Q, a.N, a.dim, a.seg.z[s] * a.rx);
                 szr = a.cur[(size_t)ps * P + e];
@@ -396,6 +413,7 @@ __global__ void __launch_bounds__(kScanThreads) k_phase_layout(const PhaseLayout
             bytes += (unsigned long long)(a.want_send ? szs : szr);
             cr[k] = (head + szr + 15) >> 4;
             cs[k] = (szs + 15) >> 4;
+            ct[k] = tbound ? (szr + 15) >> 4 : 0;
         }
         int run = block_scan_batch(cr, carry_r, wsum);
 #pragma unroll
@@ -413,6 +431,15 @@ __global__ void __launch_bounds__(kScanThreads) k_phase_layout(const PhaseLayout
                 run += cs[k];
             }
         }
+        if (a.want_tbound) {
+            run = block_scan_batch(ct, carry_t, wsum);
+#pragma unroll
+            for (int k = 0; k < kScanItems; ++k) {
+                const int s = base + tid * kScanItems + k;
+                if (s < a.nseg) pre_t[s] = run;
+                run += ct[k];
+            }
+        }
     }
 #pragma unroll
     for (int d = kWave / 2; d > 0; d >>= 1) bytes += __shfl_xor(bytes, d, kWave);
@@ -420,22 +447,23 @@ __global__ void __launch_bounds__(kScanThreads) k_phase_layout(const PhaseLayout
     if (tid == 0) {
         pre_r[a.nseg] = carry_r; a.Lr.tot[p] = carry_r;
         if (a.want_send) { pre_s[a.nseg] = carry_s; a.Ls.tot[p] = carry_s; }
+        if (a.want_tbound) { pre_t[a.nseg] = carry_t; a.Lt.tot[p] = carry_t; }
     }
 }
 
 // ------------------------------------------------------------------------------------------
 // k_layout_base: exclusive scan over the P per-rank totals of a layout -> each rank's first chunk
-// in its staging buffer and its first wave unit.  One workgroup per layout (x = 0 receive side,
-// 1 send side).  A separate launch rather than a "last workgroup" step inside k_phase_layout:
-// the kernel boundary is the one device-wide release the totals need.
+// in its staging buffer and its first wave unit.  One workgroup per layout the host lists (receive
+// side, send side, T-bound blocks).  A separate launch rather than a "last workgroup" step inside
+// k_phase_layout: the kernel boundary is the one device-wide release the totals need.
 // ------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(kScanThreads) k_layout_base(int P, LayoutDev Lr, LayoutDev Ls,
+__global__ void __launch_bounds__(kScanThreads) k_layout_base(int P, LayoutDev L0, LayoutDev L1, LayoutDev L2,
                                                               unsigned long long* __restrict__ phase_chunks,
                                                               int chunks_from) {
     __shared__ long long wc[kScanThreads / kWave];
     __shared__ int wt[kScanThreads / kWave];
     const int which = blockIdx.x;
-    scan_rank_bases(P, which == 0 ? Lr : Ls, which == chunks_from ? phase_chunks : nullptr, wc, wt);
+    scan_rank_bases(P, which == 0 ? L0 : (which == 1 ? L1 : L2), which == chunks_from ? phase_chunks : nullptr, wc, wt);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -500,6 +528,9 @@ struct CopyArgs {
     unsigned char* user2;               // R
     const int64_t* displs2;             // rdispls
     unsigned char* T2;                  // the copy of T written in this phase
+    // exact-size T (DENSE kernels): one arena per phase instead of slots
+    const DenseT* dense;
+    int phase;                          // index of the phase being run
     int P, Q, N, dim, rx;
 };
 
@@ -562,10 +593,16 @@ __device__ __forceinline__ unsigned long long block_address(int slot, bool far_i
     return (unsigned long long)(user + displs[idx]);
 }
 
+// Address of a block in exact-size T: segment s of rank p in the arena of `phase`.
+__device__ __forceinline__ unsigned long long dense_address(const DenseT* dense, int phase, int p, int s) {
+    const DenseT d = dense[phase];
+    return (unsigned long long)(d.arena + ((d.rank_base[p] + (long long)d.pre[(size_t)p * d.ld + s]) << 4));
+}
+
 // Waves per SIMD: measured on MI355X, the gathering kernels (pack, exchange) run fastest with at most 6
 // resident waves per SIMD, the scattering unpack with as many as fit.
 constexpr int copy_max_waves(int mode) { return (mode == kUnpack || mode == kFused) ? 8 : 6; }
-template <int MODE, int GRAN>
+template <int MODE, int GRAN, bool DENSE>
 __global__ void __launch_bounds__(kCopyThreads) __attribute__((amdgpu_waves_per_eu(1, copy_max_waves(MODE))))
 k_copy(const CopyArgs a) {
     __shared__ int s_pre[kCopyThreads / kWave][kWave];
@@ -606,11 +643,14 @@ k_copy(const CopyArgs a) {
         int pre_n = __shfl_down(pre_i, 1, kWave);
         if (lane == kWave - 1) pre_n = pre_w;
         // table fields this mode needs, fetched together with the prefix (one round trip)
-        int se = 0, sz_ = 0, ssrc = -1, sdst = -1;
+        int se = 0, sz_ = 0, ssrc = -1, sdst = -1, sph = -1, sseg = 0;
         if (s < a.nseg) {
             if (MODE != kExchange) se = a.seg.e[s];
             if (MODE == kExchange || MODE == kFused) sz_ = a.seg.z[s];
-            if (MODE == kPack || MODE == kFused) ssrc = a.seg.src[s];
+            if (MODE == kPack || MODE == kFused) {
+                ssrc = a.seg.src[s];
+                if (DENSE) { sph = a.seg.srcph[s]; sseg = a.seg.srcseg[s]; }
+            }
             if (MODE == kUnpack || MODE == kFused) sdst = a.seg.dst[s];
         }
         const int wend = pre_w;                      // chunks below wend resolve in this window
@@ -631,16 +671,22 @@ k_copy(const CopyArgs a) {
                 int bj, bl;
                 split_slot_index(se, a.Q, a.N, bj, bl);
                 if (MODE == kPack) {
-                    addr = block_address(ssrc, false, p, n, g, bj, bl, a.P, a.Q, a.N, a.user, a.displs, a.T,
-                                         a.slots, a.slot_bytes);
+                    if (DENSE && ssrc >= 0)
+                        addr = dense_address(a.dense, sph, p, sseg);
+                    else
+                        addr = block_address(ssrc, false, p, n, g, bj, bl, a.P, a.Q, a.N, a.user, a.displs, a.T,
+                                             a.slots, a.slot_bytes);
                     if (ssrc >= 0) flag |= kFlagSrcT;
                 }
                 if (MODE == kUnpack) {
                     // a final block's size is the receiver's own recvcounts entry (validated equal to
                     // the sender's count), read next to its displacement
-                    addr = block_address(sdst, true, p, n, g, bj, bl, a.P, a.Q, a.N, a.user, a.displs, a.T,
-                                         a.slots, a.slot_bytes, a.counts, &size);
-                    if (sdst >= 0) flag |= kFlagFill; // T-bound: the tail lane completes the 128-byte line
+                    if (DENSE && sdst >= 0)           // exact-size T: blocks lie back to back, nothing to fill
+                        addr = dense_address(a.dense, a.phase, p, s);
+                    else
+                        addr = block_address(sdst, true, p, n, g, bj, bl, a.P, a.Q, a.N, a.user, a.displs, a.T,
+                                             a.slots, a.slot_bytes, a.counts, &size);
+                    if (!DENSE && sdst >= 0) flag |= kFlagFill; // T-bound: the tail lane completes the 128-byte line
                 }
                 if (MODE == kFused) {
                     // tiled over the RECEIVER's layout: its stores into R are consecutive; the loads
@@ -649,15 +695,21 @@ k_copy(const CopyArgs a) {
                     const int dist = sz_ * a.rx;
                     if (a.dim == 0) { sg += dist; if (sg >= a.Q) sg -= a.Q; }
                     else { sn += dist; if (sn >= a.N) sn -= a.N; }
-                    addr = block_address(ssrc, false, sn * a.Q + sg, sn, sg, bj, bl, a.P, a.Q, a.N, a.user,
-                                         a.displs, a.T, a.slots, a.slot_bytes);
+                    if (DENSE && ssrc >= 0)
+                        addr = dense_address(a.dense, sph, sn * a.Q + sg, sseg);
+                    else
+                        addr = block_address(ssrc, false, sn * a.Q + sg, sn, sg, bj, bl, a.P, a.Q, a.N, a.user,
+                                             a.displs, a.T, a.slots, a.slot_bytes);
                     if (ssrc >= 0) flag |= kFlagSrcT;
-                    addr2 = block_address(sdst, true, p, n, g, bj, bl, a.P, a.Q, a.N, a.user2, a.displs2,
-                                          a.T2, a.slots, a.slot_bytes, a.counts, &size);
+                    if (DENSE && sdst >= 0)
+                        addr2 = dense_address(a.dense, a.phase, p, s);
+                    else
+                        addr2 = block_address(sdst, true, p, n, g, bj, bl, a.P, a.Q, a.N, a.user2, a.displs2,
+                                              a.T2, a.slots, a.slot_bytes, a.counts, &size);
                     // chunks are cut at the destination's 16-byte boundaries: `head` bytes of the
                     // first chunk lie before the block (0 for T slots, which are line aligned)
                     flag |= (int)(addr2 & 15ull);
-                    if (sdst >= 0) flag |= kFlagFill;
+                    if (!DENSE && sdst >= 0) flag |= kFlagFill;
                 }
             }
         }

@@ -28,7 +28,8 @@ struct SegInfo {
     int32_t dst_slot;  // T slot the receiver stores it to, or -1: final, goes to the receive buffer R
     int32_t j;         // node distance
     int32_t l;         // local distance
-    int32_t pad0, pad1;
+    int32_t src_phase; // phase in which the block last moved (it arrived in T then), or -1: still in S
+    int32_t src_seg;   // its position in that phase's message order
 };
 
 struct PhaseHost {
@@ -51,6 +52,7 @@ struct PlanScalars {
     long long global0;    // first T slot of the global phase
     long long slots1;     // slots of one copy of T
     int fused;
+    int w_l;              // number of local phases (they come first in the phase list)
 };
 
 struct PhaseScalars {
@@ -139,16 +141,52 @@ TUNA_HD inline int hops_before(const PlanScalars& pl, const PhaseScalars& ph, in
 //   otherwise a T slot: [0, B_l) own-node blocks by the paper's map t over l; then (N-1)(Q-1)
 //   slots for blocks of the other nodes' groups that moved locally (they wait for the global
 //   phase); then B_g super-slots of Q blocks for the global phase (map t over j).
-TUNA_HD inline bool slot_entry(const PlanScalars& pl, const PhaseScalars& ph, int e, SegInfo* out, int* pos) {
+// Position of slot index e in a phase's message order and its digit value there (0 and -1 when the
+// block does not move in that phase).  Only dim, r, size, rx and rx1 of `ph` are used.
+TUNA_HD inline int slot_position(const PlanScalars& pl, const PhaseScalars& ph, int e, int* z_out) {
     const int Q = pl.Q;
     const int j = e / Q, l = e - j * Q;
     const int c = ph.dim == 0 ? l : j;
     const int z = (int)((c / ph.rx) % ph.r);
-    if (z == 0) return false;
+    *z_out = z;
+    if (z == 0) return -1;
     const long long rc = (c / ph.rx1) * ph.rx + (c % ph.rx);          // rank of c among those with digit z
     const long long mult = ph.dim == 0 ? pl.N : Q;
     const long long start = count_below_digit(ph, z) * mult;
-    *pos = (int)(ph.dim == 0 ? start + (long long)j * count_with_digit(ph, z) + rc : start + rc * Q + l);
+    return (int)(ph.dim == 0 ? start + (long long)j * count_with_digit(ph, z) + rc : start + rc * Q + l);
+}
+
+// The phase in which the block with slot index e moved last before phase `ph`, and its position in
+// that phase's message order: the highest non-zero digit below x of the phase's own coordinate,
+// else (global phases) the highest non-zero digit of l.  false: it has not moved, it is still in S.
+TUNA_HD inline bool previous_move(const PlanScalars& pl, const PhaseScalars& ph, int e, int* phase, int* seg) {
+    const int Q = pl.Q;
+    const int j = e / Q, l = e - j * Q;
+    PhaseScalars q{};
+    long long v = (ph.dim == 0 ? l : j) % ph.rx;
+    q.dim = ph.dim;
+    if (v == 0) {
+        if (ph.dim == 0 || l == 0) return false;
+        v = l;
+        q.dim = 0;
+    }
+    q.r = q.dim == 0 ? pl.rl : pl.rg;
+    q.size = q.dim == 0 ? Q : pl.N;
+    q.x = 0; q.rx = 1;
+    while (q.rx * q.r <= v) { q.rx *= q.r; ++q.x; }
+    q.rx1 = q.rx * q.r;
+    int z = 0;
+    *seg = slot_position(pl, q, e, &z);
+    *phase = q.dim == 0 ? q.x : pl.w_l + q.x;
+    return true;
+}
+
+TUNA_HD inline bool slot_entry(const PlanScalars& pl, const PhaseScalars& ph, int e, SegInfo* out, int* pos) {
+    const int Q = pl.Q;
+    const int j = e / Q, l = e - j * Q;
+    int z = 0;
+    *pos = slot_position(pl, ph, e, &z);
+    if (z == 0) return false;
     auto local_slot = [&](int jj, int ll) -> int {
         if (jj == 0) return (int)t_index(ll, pl.rl);
         return (int)(pl.foreign0 + (long long)(jj - 1) * (Q - 1) + (ll - 1));
@@ -169,6 +207,8 @@ TUNA_HD inline bool slot_entry(const PlanScalars& pl, const PhaseScalars& ph, in
         if (s.src_slot >= 0) s.src_slot += (int)((h & 1) * pl.slots1);
         if (s.dst_slot >= 0) s.dst_slot += (int)(((h + 1) & 1) * pl.slots1);
     }
+    s.src_phase = -1; s.src_seg = 0;
+    if (s.src_slot >= 0) previous_move(pl, ph, e, &s.src_phase, &s.src_seg);
     *out = s;
     return true;
 }
@@ -204,6 +244,7 @@ inline PlanHost make_plan(int P, int Q, int rl, int rg, bool fused = false, bool
     sc.global0 = sc.foreign0 + (long long)(N - 1) * (Q - 1);
     sc.slots1 = sc.global0 + (long long)pl.B_g * Q;
     sc.fused = fused ? 1 : 0;
+    sc.w_l = pl.w_l;
     pl.slots = fused ? 2 * sc.slots1 : sc.slots1;
     pl.fused = fused;
     for (int dim = 0; dim < 2; ++dim) {

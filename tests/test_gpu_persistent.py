@@ -174,3 +174,95 @@ def test_two_plans_on_two_streams(tuna):
         assert tuna.tuna_plan_free(plan_a) == 0
         assert tuna.tuna_plan_free(plan_b) == 0
     assert tuna.tuna_release() == 0          # no plan left: the cached schedules may go
+
+
+# ---- exact-size T (TUNA_OPT_DENSE_T) ------------------------------------------------------------
+def _dense_plan(tuna, res, P, Q, rl, rg, fused=0, staggered=0, dense=1):
+    tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, fused)
+    tuna.tuna_set_option(tuna.TUNA_OPT_STAGGERED, staggered)
+    tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, dense)
+    try:
+        return tuna.tuna_alltoallv_init(res.send, res.sc, res.sd, res.recv, res.rc, res.rd, P, Q, rl, rg)
+    finally:
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_STAGGERED, 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 0)
+
+
+@pytest.mark.parametrize("mode", ["staged", "fused", "staggered"])
+@pytest.mark.parametrize("P,Q,rl,rg,cfg", [(16, 0, 2, 2, 1), (97, 0, 2, 2, 2), (97, 0, 3, 3, 2), (96, 0, 10, 10, 4),
+                                            (96, 0, 96, 96, 2), (128, 16, 2, 2, 3), (120, 8, 3, 4, 2),
+                                            (256, 0, 2, 2, 3), (1, 0, 2, 2, 2), (2, 0, 2, 2, 2)])
+def test_exact_size_t_matches_the_oracle(tuna, P, Q, rl, rg, cfg, mode):
+    if mode == "staggered" and Q == 0:
+        pytest.skip("staggered needs a hierarchy")
+    lay = wl.make_layout(wl.make_counts(cfg, P), gap=4 if cfg != 2 else 5)
+    res = Resident(lay)
+    code, plan = _dense_plan(tuna, res, P, Q, rl, rg, fused=int(mode == "fused"), staggered=int(mode == "staggered"))
+    assert code == 0, tuna.tuna_strerror(code)
+    try:
+        for seed in (21, 22):
+            want = res.load(seed)
+            res.recv.fill_(CANARY)
+            print("exact-size T P=%d Q=%d rl=%d rg=%d %s seed=%d" % (P, Q, rl, rg, mode, seed), flush=True)
+            assert tuna.tuna_start(plan) == 0
+            res.check(want, "start %d" % seed)
+        st = tuna.tuna_get_stats()
+        assert st.dense_t == 1 and st.temp_slots_per_rank == 0
+    finally:
+        assert tuna.tuna_plan_free(plan) == 0
+
+
+def test_exact_size_t_holds_what_waits_in_it(tuna):
+    """T in exact size takes the bytes that are stored into it, summed over the phases (each block
+    padded to 16 bytes, each phase to 256): for every phase but the last that is the phase's
+    payload minus what reaches R.  With r = 2 and P = 2^k, phase x delivers the blocks whose index
+    is below 2^(x+1) among those with bit x set, 2^x of P/2.  Heavy-tailed sizes make the bound
+    of B slots of M bytes many times larger."""
+    P = 256
+    counts = wl.make_counts(3, P)
+    lay = wl.make_layout(counts)
+    res = Resident(lay)
+    code, plan = _dense_plan(tuna, res, P, 0, 2, 2)
+    assert code == 0
+    try:
+        want = res.load(3)
+        res.recv.fill_(CANARY)
+        assert tuna.tuna_start(plan) == 0
+        res.check(want, "exact-size T")
+        st = tuna.tuna_get_stats()
+        dense_bytes = st.temp_bytes
+    finally:
+        assert tuna.tuna_plan_free(plan) == 0
+    # independent count of the chunks each phase stores into T: block (s -> d) has index
+    # i = (s - d) mod P; in phase x it moves when bit x of i is set and stays in T while a higher bit is set
+    idx = (np.arange(P)[:, None] - np.arange(P)[None, :]) % P
+    chunks = (counts.astype(np.int64) + 15) // 16
+    total = 0
+    for x in range(8):
+        stored = ((idx >> x) & 1 == 1) & ((idx >> (x + 1)) != 0)
+        total += -(-int(chunks[stored].sum()) * 16 // 256) * 256
+    assert dense_bytes == total
+    code, plan = _dense_plan(tuna, res, P, 0, 2, 2, dense=0)
+    assert code == 0
+    try:
+        assert tuna.tuna_start(plan) == 0
+        strided = tuna.tuna_get_stats().temp_bytes
+    finally:
+        assert tuna.tuna_plan_free(plan) == 0
+    M = int(counts.max())
+    assert strided == P * (P - 9) * (-(-M // 128) * 128)
+    assert strided > 4 * dense_bytes
+
+
+def test_device_source_tables_match_the_host(tuna):
+    for P, Q, rl, rg in [(64, 0, 2, 2), (100, 0, 3, 3), (96, 8, 2, 3), (60, 5, 5, 12)]:
+        rc, info = tuna.tuna_plan_info(P, Q, rl, rg)
+        assert rc == 0
+        for ph in range(info.n_phases):
+            rc, hdr, seg = tuna.tuna_plan_phase(P, Q, rl, rg, ph)
+            nseg = int(hdr[4])
+            rc, host = tuna.tuna_plan_phase_sources(P, Q, rl, rg, ph, nseg)
+            assert rc == 0
+            rc, dev = tuna.tuna_plan_phase_sources(P, Q, rl, rg, ph, nseg, on_device=True)
+            assert rc == 0 and np.array_equal(host, dev)

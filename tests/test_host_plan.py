@@ -95,7 +95,9 @@ def test_argument_errors_without_a_gpu():
 def _replay(counts, Q, rl, rg, fused=False):
     """Moves blocks exactly as the tables say: per phase, every rank reads each moving block from
     the send buffer (source slot -1) or its T slot, the partner at distance z*r^x (downwards, as
-    in Algorithm "TuNA") stores it to the receive buffer (destination slot -1) or its T slot."""
+    in Algorithm "TuNA") stores it to the receive buffer (destination slot -1) or its T slot.
+    Alongside, the exact-size form of T is replayed: a block stored into T in phase f as that
+    phase's k-th moving block must be what the later phase that forwards it finds under (f, k)."""
     P = counts.shape[0]
     rc, info = tuna.tuna_plan_info(P, Q, rl, rg)
     assert rc == 0
@@ -103,6 +105,7 @@ def _replay(counts, Q, rl, rg, fused=False):
     S = [[bytes([(7 * i + j) & 0xFF]) * int(counts[i, j]) + b"" for j in range(P)] for i in range(P)]
     R = [[None] * P for _ in range(P)]
     T = [dict() for _ in range(P)]
+    arena = [dict() for _ in range(P)]
     for p in range(P):
         R[p][p] = S[p][p]
     per_phase_bytes = []
@@ -111,6 +114,8 @@ def _replay(counts, Q, rl, rg, fused=False):
         assert rc == 0
         dim, x, r, nz, nseg, rx = (int(v) for v in hdr)
         assert rx == r ** x and nseg == seg.shape[0]
+        rc, sources = tuna.tuna_plan_phase_sources(P, Q, rl, rg, ph, nseg)
+        assert rc == 0
         # message order: z ascending, then e ascending; e = j*Q + l
         keys = [(int(s[3]), int(s[0])) for s in seg]
         assert keys == sorted(keys) and len(set(keys)) == len(keys)
@@ -121,21 +126,24 @@ def _replay(counts, Q, rl, rg, fused=False):
         reads = [set() for _ in range(P)]
         for p in range(P):
             n, g = divmod(p, Q)
-            for e, j, l, z, src_slot, dst_slot in seg.tolist():
+            for k, (e, j, l, z, src_slot, dst_slot) in enumerate(seg.tolist()):
                 coord = l if dim == 0 else j
                 assert (coord // rx) % r == z
                 if src_slot < 0:
                     blk = S[p][((n - j) % N) * Q + (g - l) % Q]
+                    assert tuple(sources[k]) == (-1, 0)
                 else:
                     blk = T[p].pop(src_slot)          # a slot is read exactly once after a store
                     reads[p].add(src_slot)
+                    f, kk = (int(v) for v in sources[k])
+                    assert 0 <= f < ph and arena[p].pop((f, kk)) == (e, blk)
                 if dim == 0:
                     q = n * Q + (g - z * rx) % Q
                 else:
                     q = ((n - z * rx) % N) * Q + g
-                moved.append((q, j, l, dst_slot, blk))
+                moved.append((q, j, l, dst_slot, blk, k))
                 nbytes += len(blk)
-        for q, j, l, dst_slot, blk in moved:          # every rank packed before anyone unpacks
+        for q, j, l, dst_slot, blk, k in moved:       # every rank packed before anyone unpacks
             nq, gq = divmod(q, Q)
             if dst_slot < 0:
                 src = ((nq + j) % N) * Q + (gq + l) % Q
@@ -147,8 +155,10 @@ def _replay(counts, Q, rl, rg, fused=False):
                 if fused:                             # one kernel reads and writes: never the same slot
                     assert dst_slot not in reads[q]
                 T[q][dst_slot] = blk
+                arena[q][(ph, k)] = (j * Q + l, blk)
         per_phase_bytes.append(nbytes)
     assert all(len(t) == 0 for t in T)                # nothing is left behind in T
+    assert all(len(t) == 0 for t in arena)
     return R, S, per_phase_bytes
 
 
