@@ -199,15 +199,18 @@ def main():
         tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
         return per_radix
 
-    def run_persistent(fused):
+    def run_persistent(fused, exact_t=False):
         """tuna_alltoallv_init once per radix, then K timed tuna_start calls (no validation, no
-        metadata kernels, no host synchronisation), eagerly and as one captured HIP graph."""
+        metadata kernels, no host synchronisation), eagerly and as one captured HIP graph.
+        exact_t: T stored in exact size (one arena per phase) instead of B slots of M bytes."""
         rows = []
         for kind, _, rl, rg in sweep:
             label = "r_l=%d,r_g=%d" % (rl, rg) if kind == "hier" else "r=%d" % rl
             tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 1 if fused else 0)
+            tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 1 if exact_t else 0)
             rc, plan = tuna.tuna_alltoallv_init(send, d_sc, d_sd, recv, d_rc, d_rd, P, rpn, rl, rg)
             tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+            tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 0)
             if rc != 0:
                 raise RuntimeError("tuna_alltoallv_init failed: " + tuna.tuna_strerror(rc))
             try:
@@ -233,9 +236,10 @@ def main():
                 st = tuna.tuna_get_stats()
                 rows.append({"radix": label, "ms_per_start": ms_start, "ms_per_graph_replay": ms_graph,
                              "effective_GBs": Btot / (min(ms_start, ms_graph) * 1e-3) / 1e9,
-                             "plan_bytes": st.workspace_bytes})
-                print("[bench] %s persistent%s: %.3f ms/start, %.3f ms/graph replay, %.1f GB/s effective" %
-                      (label, " fused" if fused else "", ms_start, ms_graph, rows[-1]["effective_GBs"]),
+                             "plan_bytes": st.workspace_bytes, "temp_bytes": st.temp_bytes})
+                print("[bench] %s persistent%s%s: %.3f ms/start, %.3f ms/graph replay, %.1f GB/s effective, T %.2f GiB" %
+                      (label, " fused" if fused else "", " exact-size T" if exact_t else "", ms_start, ms_graph,
+                       rows[-1]["effective_GBs"], st.temp_bytes / 2 ** 30),
                       file=sys.stderr, flush=True)
             finally:
                 tuna.tuna_plan_free(plan)
@@ -250,8 +254,10 @@ def main():
     if not args.no_persistent_table:
         persistent = {"note": "tuna_alltoallv_init once, then tuna_start per step: payload kernels only",
                       "staged": run_persistent(bool(args.fused))}
+        persistent["staged_exact_t"] = run_persistent(bool(args.fused), exact_t=True)
         if not args.fused and not args.no_fused_table:
             persistent["fused"] = run_persistent(True)
+            persistent["fused_exact_t"] = run_persistent(True, exact_t=True)
     best = max(per_radix, key=lambda r: r["effective_GBs"])
     # Roofline of the dominant kernel: the copy kernel with the largest total time over ALL launches
     # of the timed sweep (every radix), so that its average launch duration is the one a

@@ -310,6 +310,7 @@ struct Prepared {
     v4u* stage_r = nullptr;
     unsigned char* T = nullptr;
     const DenseT* dense = nullptr;      // exact-size T (persistent plans): per-phase arenas on the device
+    std::vector<const SrcRef*> srcref;  // and per phase the resolved source of every table entry
 };
 
 bool phase_is_one_kernel(const Prepared& pr, const PhaseHost& ph) {
@@ -419,6 +420,7 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
     a.P = pr.P; a.Q = pr.Q; a.N = pr.N; a.dim = ph.dim; a.rx = (int)ph.rx;
     a.user_limit = pr.user_limit;
     a.dense = pr.dense; a.phase = (int)i;
+    a.srcref = pr.dense ? pr.srcref[i] : nullptr;
     int rc;
     if (phase_is_one_kernel(pr, ph)) {
         // one hop in one kernel: S / T of the sender -> R / the other copy of T at the receiver
@@ -583,7 +585,11 @@ int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* s
     // metadata memory: two size matrices + per phase two complete layouts
     const size_t P2 = (size_t)P * P;
     plan->dense = g.opt_dense_t != 0;
-    const size_t dense_meta = plan->dense ? nph * tbound_layout_bytes_for(P) + align_up(nph * sizeof(DenseT)) : 0;
+    size_t dense_meta = 0;
+    if (plan->dense) {
+        dense_meta = nph * tbound_layout_bytes_for(P) + align_up(nph * sizeof(DenseT));
+        for (const PhaseHost& ph : pl.phases) dense_meta += align_up((size_t)ph.nseg * sizeof(SrcRef));
+    }
     const size_t mbytes = 2 * align_up(P2 * 4) + nph * 2 * layout_bytes_for(P, pr.ds.unit_cap) + dense_meta;
     hipError_t e = hipMalloc(&plan->mem_meta, mbytes ? mbytes : kAlign);
     if (e != hipSuccess) { (void)hipGetLastError(); g.last_hip_error = (int)e; delete plan; return TUNA_ERR_NOMEM; }
@@ -600,6 +606,7 @@ int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* s
         plan->Lt.resize(nph);
         for (size_t i = 0; i < nph; ++i) carve_tbound_layout(cm, P, plan->Lt[i]);
         d_dense = cm.take<DenseT>(nph);
+        for (size_t i = 0; i < nph; ++i) pr.srcref.push_back(cm.take<SrcRef>((size_t)pl.phases[i].nseg));
     }
     auto fail = [&](int code) { (void)hipFree(plan->mem_meta); if (plan->mem_data) (void)hipFree(plan->mem_data); delete plan; return code; };
     if (!cm.ok) return fail(TUNA_ERR_NOMEM);
@@ -658,6 +665,14 @@ int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* s
         }
         if (hipMemcpy(d_dense, hd.data(), nph * sizeof(DenseT), hipMemcpyHostToDevice) != hipSuccess) return fail(TUNA_ERR_HIP);
         pr.dense = d_dense;
+        for (size_t i = 0; i < nph; ++i) {
+            const int nseg = pl.phases[i].nseg;
+            if (nseg == 0) continue;
+            hipLaunchKernelGGL(k_plan_sources, dim3((unsigned)((nseg + 255) / 256)), dim3(256), 0, s, pr.dp->d_seg[i],
+                               nseg, d_dense, const_cast<SrcRef*>(pr.srcref[i]));
+            if (hipGetLastError() != hipSuccess) return fail(TUNA_ERR_HIP);
+        }
+        if (hipStreamSynchronize(s) != hipSuccess) return fail(TUNA_ERR_HIP);
     }
     plan->stats.dense_t = plan->dense ? 1 : 0;
     plan->stats.temp_bytes = (int64_t)pr.ds.t_bytes;

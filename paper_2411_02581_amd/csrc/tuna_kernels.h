@@ -63,6 +63,16 @@ struct DenseT {
     int pad;
 };
 
+// Where a plan with exact-size T finds the block of one table entry: resolved per segment when the
+// plan is made, so that the copy kernels load it together with the other table fields.
+struct SrcRef {
+    const unsigned char* arena;    // nullptr: the block is still in the send buffer
+    const long long* rank_base;
+    const int* pre_col;            // prefix column of the segment in the phase that stored it: [p * ld]
+    int ld;
+    int pad;
+};
+
 // Distance pair of a slot index.
 __device__ __forceinline__ void split_slot_index(int e, int Q, int N, int& j, int& l) {
     if (N == 1) { j = 0; l = e; }
@@ -131,6 +141,22 @@ __global__ void __launch_bounds__(256) k_build_phase_table(const PlanScalars pl,
     } else {
         zt[e] = 0;
     }
+}
+
+// ------------------------------------------------------------------------------------------
+// k_plan_sources: per-plan source references of one phase for exact-size T.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_plan_sources(SegDev seg, int nseg, const DenseT* __restrict__ dense,
+                                                      SrcRef* __restrict__ out) {
+    const int s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= nseg) return;
+    SrcRef r{};
+    const int ph = seg.srcph[s];
+    if (ph >= 0) {
+        const DenseT d = dense[ph];
+        r.arena = d.arena; r.rank_base = d.rank_base; r.pre_col = d.pre + seg.srcseg[s]; r.ld = d.ld;
+    }
+    out[s] = r;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -530,6 +556,7 @@ struct CopyArgs {
     unsigned char* T2;                  // the copy of T written in this phase
     // exact-size T (DENSE kernels): one arena per phase instead of slots
     const DenseT* dense;
+    const SrcRef* srcref;               // [nseg] of the phase being run
     int phase;                          // index of the phase being run
     int P, Q, N, dim, rx;
 };
@@ -599,6 +626,10 @@ __device__ __forceinline__ unsigned long long dense_address(const DenseT* dense,
     return (unsigned long long)(d.arena + ((d.rank_base[p] + (long long)d.pre[(size_t)p * d.ld + s]) << 4));
 }
 
+__device__ __forceinline__ unsigned long long dense_source(const SrcRef& r, int p) {
+    return (unsigned long long)(r.arena + ((r.rank_base[p] + (long long)r.pre_col[(size_t)p * r.ld]) << 4));
+}
+
 // Waves per SIMD: measured on MI355X, the gathering kernels (pack, exchange) run fastest with at most 6
 // resident waves per SIMD, the scattering unpack with as many as fit.
 constexpr int copy_max_waves(int mode) { return (mode == kUnpack || mode == kFused) ? 8 : 6; }
@@ -643,13 +674,14 @@ k_copy(const CopyArgs a) {
         int pre_n = __shfl_down(pre_i, 1, kWave);
         if (lane == kWave - 1) pre_n = pre_w;
         // table fields this mode needs, fetched together with the prefix (one round trip)
-        int se = 0, sz_ = 0, ssrc = -1, sdst = -1, sph = -1, sseg = 0;
+        int se = 0, sz_ = 0, ssrc = -1, sdst = -1;
+        SrcRef ref{};
         if (s < a.nseg) {
             if (MODE != kExchange) se = a.seg.e[s];
             if (MODE == kExchange || MODE == kFused) sz_ = a.seg.z[s];
             if (MODE == kPack || MODE == kFused) {
                 ssrc = a.seg.src[s];
-                if (DENSE) { sph = a.seg.srcph[s]; sseg = a.seg.srcseg[s]; }
+                if (DENSE) ref = a.srcref[s];
             }
             if (MODE == kUnpack || MODE == kFused) sdst = a.seg.dst[s];
         }
@@ -672,7 +704,7 @@ k_copy(const CopyArgs a) {
                 split_slot_index(se, a.Q, a.N, bj, bl);
                 if (MODE == kPack) {
                     if (DENSE && ssrc >= 0)
-                        addr = dense_address(a.dense, sph, p, sseg);
+                        addr = dense_source(ref, p);
                     else
                         addr = block_address(ssrc, false, p, n, g, bj, bl, a.P, a.Q, a.N, a.user, a.displs, a.T,
                                              a.slots, a.slot_bytes);
@@ -696,7 +728,7 @@ k_copy(const CopyArgs a) {
                     if (a.dim == 0) { sg += dist; if (sg >= a.Q) sg -= a.Q; }
                     else { sn += dist; if (sn >= a.N) sn -= a.N; }
                     if (DENSE && ssrc >= 0)
-                        addr = dense_address(a.dense, sph, sn * a.Q + sg, sseg);
+                        addr = dense_source(ref, sn * a.Q + sg);
                     else
                         addr = block_address(ssrc, false, sn * a.Q + sg, sn, sg, bj, bl, a.P, a.Q, a.N, a.user,
                                              a.displs, a.T, a.slots, a.slot_bytes);
