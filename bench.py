@@ -48,6 +48,7 @@ def parse_args():
                     help="replace the configuration's counts by 8 * U{0..S/8} bytes (the paper's uniform [0, S] "
                          "micro-benchmark with FP64 elements); use with --ranks and --radices")
     ap.add_argument("--fused", type=int, default=0, help="1: fused single-kernel rounds")
+    ap.add_argument("--exact-t", type=int, default=0, help="1: T in exact size (TUNA_OPT_DENSE_T) in the main sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fused-table", action="store_true", help="skip the second sweep with fused rounds")
     ap.add_argument("--no-secondary", action="store_true", help="skip the P=1024 hierarchical workload")
@@ -136,8 +137,9 @@ def main():
         copy_ceiling = {"GBs": 2 * nb / (ms * 1e-3) / 1e9, "bytes_copied": nb, "ms": ms}
         print("[bench] plain copy ceiling: %.0f GB/s (read + write)" % copy_ceiling["GBs"], file=sys.stderr, flush=True)
 
-    def run_sweep(fused):
+    def run_sweep(fused, exact_t=False):
         tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 1 if fused else 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 1 if exact_t else 0)
         per_radix = []
         for kind, _, rl, rg in sweep:
             label = "r_l=%d,r_g=%d" % (rl, rg) if kind == "hier" else "r=%d" % rl
@@ -197,6 +199,7 @@ def main():
                   file=sys.stderr, flush=True)
 
         tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 0)
         return per_radix
 
     def run_persistent(fused, exact_t=False):
@@ -245,11 +248,14 @@ def main():
                 tuna.tuna_plan_free(plan)
         return rows
 
-    per_radix = run_sweep(bool(args.fused))
-    # the fused rounds (one kernel per phase, 2 x payload instead of 6 x) as a second table
-    fused_table = None
-    if not args.fused and not args.no_fused_table:
+    per_radix = run_sweep(bool(args.fused), bool(args.exact_t))
+    # the fused rounds (one kernel per phase, 2 x payload instead of 6 x) as a second table, and both
+    # with T in exact size instead of B slots of M bytes
+    fused_table = exact_table = fused_exact_table = None
+    if not args.fused and not args.exact_t and not args.no_fused_table:
         fused_table = run_sweep(True)
+        exact_table = run_sweep(False, True)
+        fused_exact_table = run_sweep(True, True)
     persistent = None
     if not args.no_persistent_table:
         persistent = {"note": "tuna_alltoallv_init once, then tuna_start per step: payload kernels only",
@@ -275,9 +281,10 @@ def main():
         gran = per_radix[0]["granularity"]
         dom = max(tot.items(), key=lambda kv: kv[1][0])
         name, (ms, n, alg) = dom
-        kname = {"pack": "tuna::k_copy<0, %d>" % gran, "exchange": "tuna::k_copy<1, 16>",
-                 "unpack": "tuna::k_copy<2, %d>" % gran, "fused": "tuna::k_copy<3, %d>" % gran}[name]
-        default_run = (args.config == 4 and P == 4096 and not args.radices)
+        et = "true" if args.exact_t else "false"
+        kname = {"pack": "tuna::k_copy<0, %d, %s>" % (gran, et), "exchange": "tuna::k_copy<1, 16, false>",
+                 "unpack": "tuna::k_copy<2, %d, %s>" % (gran, et), "fused": "tuna::k_copy<3, %d, %s>" % (gran, et)}[name]
+        default_run = (args.config == 4 and P == 4096 and not args.radices and not args.exact_t)
         traffic = MEASURED_TRAFFIC_CONFIG4.get(name) if default_run else None
         achieved = alg / (ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": kname, "stage": name, "achieved": achieved, "peak": HBM_PEAK_GBS,
@@ -305,12 +312,16 @@ def main():
         "config": {"workload": ("uniform [0, %d] bytes in FP64 elements, P=%d flat" % (args.uniform_max_bytes, P))
                                if args.uniform_max_bytes else "config %d: %s" % (args.config, cfg.description), "P": P,
                    "payload_bytes": Btot, "best_radix": best["radix"], "fused": bool(args.fused),
+                   "exact_size_t": bool(args.exact_t),
                    "ranks_per_node": rpn},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "copy_ceiling": copy_ceiling, "per_radix": per_radix, "persistent": persistent,
         "also_measured": also,
         "fused_rounds": None if fused_table is None else {
             "note": "same workload with TUNA_OPT_FUSED: one kernel per digit phase moves S/T to R/T directly",
             "best_effective_GBs": max(r["effective_GBs"] for r in fused_table), "per_radix": fused_table},
+        "exact_size_t": None if exact_table is None else {
+            "note": "same workload with TUNA_OPT_DENSE_T: T holds the waiting blocks back to back instead of B slots of M bytes",
+            "per_radix": exact_table, "fused_per_radix": fused_exact_table},
     }
     print(json.dumps(out))
 

@@ -131,6 +131,32 @@ MetaBuffers carve_meta(Carver& cv, int P) {
     return m;
 }
 
+// prefix-only layout of the T-bound blocks of one phase (exact-size T)
+size_t tbound_layout_bytes_for(int P) {
+    const size_t ld = (size_t)P + 1;
+    return align_up((size_t)P * ld * 4) + align_up((size_t)P * 4) + align_up(((size_t)P + 1) * 8);
+}
+
+void carve_tbound_layout(Carver& cv, int P, LayoutDev& L) {
+    L.ld = P + 1;
+    L.pre = cv.take<int>((size_t)P * L.ld);
+    L.tot = cv.take<int>(P);
+    L.rank_base = cv.take<long long>(P + 1);
+    L.unit_base = nullptr; L.n_units = nullptr; L.units = nullptr;
+}
+
+// metadata of exact-size T: the T-bound prefix in message order (one for the phase being run, or
+// one per phase when a plan keeps them), and per phase the same offsets by slot index, the ranks'
+// bases and the arena's end
+size_t exact_t_meta_bytes_for(const PlanHost& pl, bool keep_all_phases) {
+    const size_t nph = pl.phases.size(), P = (size_t)pl.P;
+    return (keep_all_phases ? nph : 1) * tbound_layout_bytes_for(pl.P) + align_up(nph * P * P * 4) +
+           align_up(nph * P * 8) + align_up(nph * 8);
+}
+
+struct Prepared;
+void carve_exact_t(Carver& cv, const PlanHost& pl, bool keep_all_phases, Prepared& pr);
+
 struct DataSizes {
     size_t unit_cap;        // wave units per layout (upper bound)
     size_t stage_chunks;    // chunks per staging buffer
@@ -141,7 +167,7 @@ struct DataSizes {
 };
 
 DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long total_chunks, bool fused,
-                         bool staggered = false) {
+                         bool staggered = false, bool dense = false, unsigned long long t_chunks = 0) {
     DataSizes d{};
     const bool any_phase = !pl.phases.empty() && total_chunks > 0;
     d.stage_chunks = any_phase ? (size_t)total_chunks : 0;
@@ -151,6 +177,10 @@ DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long tot
     d.slots = pl.slots;
     d.slot_bytes = (M + 127) / 128 * 128;     // whole 128-byte lines per slot
     d.t_bytes = any_phase ? (size_t)pl.P * (size_t)d.slots * (size_t)d.slot_bytes : 0;
+    if (dense) {       // exact size: what is stored into T over all phases, every phase's arena rounded up to 256
+        d.slots = 0;
+        d.t_bytes = any_phase ? (size_t)t_chunks * 16 + pl.phases.size() * kAlign : 0;
+    }
     // pl.slots already counts both copies of T when the plan is a fused one
     d.total = 2 * align_up(d.unit_cap * sizeof(int4)) + (fused ? 0 : 2 * align_up(d.stage_chunks * 16)) +
               align_up(d.t_bytes + kTailSlack);
@@ -245,21 +275,22 @@ int launch_copy_as(int gran, size_t unit_cap, const CopyArgs& a, hipStream_t s) 
 
 template <int MODE>
 int launch_copy(int gran, size_t unit_cap, const CopyArgs& a, hipStream_t s) {
-    if (MODE != kExchange && a.dense) return launch_copy_as<MODE, true>(gran, unit_cap, a, s);
+    if (MODE != kExchange && a.x.tbase) return launch_copy_as<MODE, true>(gran, unit_cap, a, s);
     return launch_copy_as<MODE, false>(gran, unit_cap, a, s);
 }
 
 // Metadata of one digit phase: sizes exchanged, both staging layouts scanned, wave units cut.
-int phase_metadata(const PhaseLayoutArgs& a, hipStream_t s) {
+int phase_metadata(const PhaseLayoutArgs& a, hipStream_t s, const ExactT& x) {
     hipLaunchKernelGGL(k_phase_layout, dim3(a.P), dim3(kScanThreads), 0, s, a);
     HIPCHK(hipGetLastError());
     // layouts to scan: receive side, then the send side and / or the T-bound blocks where wanted
     const LayoutDev* list[3] = {&a.Lr, &a.Lr, &a.Lr};
     int nl = 1;
     if (a.want_send) list[nl++] = &a.Ls;
+    const int tbound_at = a.want_tbound ? nl : -1;
     if (a.want_tbound) list[nl++] = &a.Lt;
     hipLaunchKernelGGL(k_layout_base, dim3(nl), dim3(kScanThreads), 0, s, a.P, *list[0], *list[1], *list[2],
-                       a.phase_chunks, a.want_send ? 1 : 0);
+                       a.phase_chunks, a.want_send ? 1 : 0, tbound_at, x);
     HIPCHK(hipGetLastError());
     hipLaunchKernelGGL(k_layout_units, dim3(a.P, a.want_send ? 2 : 1), dim3(256), 0, s, a.nseg, a.Lr, a.Ls);
     HIPCHK(hipGetLastError());
@@ -277,7 +308,7 @@ int resolve_hierarchy(int P, int ranks_per_node, int* Q) {
 
 // Validation + sizing pass shared by tuna_alltoallv* and tuna_workspace_bytes: fills *g.h_status.
 int run_validate(const int32_t* sendcounts, const int32_t* recvcounts, const int64_t* sdispls,
-                 const int64_t* rdispls, int P, hipStream_t s) {
+                 const int64_t* rdispls, int P, hipStream_t s, const PlanHost* exact_t_for = nullptr) {
     const int nwords = (int)(sizeof(Status) / 4);
     hipLaunchKernelGGL(k_clear, dim3((nwords + 255) / 256), dim3(256), 0, s, (unsigned int*)g.d_status, nwords);
     HIPCHK(hipGetLastError());
@@ -286,6 +317,13 @@ int run_validate(const int32_t* sendcounts, const int32_t* recvcounts, const int
     hipLaunchKernelGGL(k_validate, dim3(vgrid), dim3(32, 8), 0, s, sendcounts, recvcounts, sdispls, rdispls, P,
                        g.d_status);
     HIPCHK(hipGetLastError());
+    if (exact_t_for) {
+        const PlanHost& pl = *exact_t_for;
+        const size_t P2 = (size_t)P * P;
+        const unsigned tgrid = (unsigned)std::min<size_t>((P2 + 255) / 256, (size_t)g.num_cus * 8);
+        hipLaunchKernelGGL(k_t_chunks, dim3(tgrid), dim3(256), 0, s, sendcounts, P, pl.Q, pl.N, pl.rl, pl.rg, g.d_status);
+        HIPCHK(hipGetLastError());
+    }
     HIPCHK(hipMemcpyAsync(g.h_status, g.d_status, 64, hipMemcpyDeviceToHost, s));
     HIPCHK(hipStreamSynchronize(s));
     return TUNA_OK;
@@ -309,9 +347,32 @@ struct Prepared {
     v4u* stage_s = nullptr;
     v4u* stage_r = nullptr;
     unsigned char* T = nullptr;
-    const DenseT* dense = nullptr;      // exact-size T (persistent plans): per-phase arenas on the device
-    std::vector<const SrcRef*> srcref;  // and per phase the resolved source of every table entry
+    // exact-size T: the prefix over the T-bound blocks (per phase, or one reused by every phase) and
+    // the per-phase position tables; the arenas are assigned on the device, phase by phase
+    bool exact_t = false;
+    std::vector<LayoutDev> Lt;
+    ExactT x{};
 };
+
+void carve_exact_t(Carver& cv, const PlanHost& pl, bool keep_all_phases, Prepared& pr) {
+    const size_t nph = pl.phases.size(), P = (size_t)pl.P;
+    pr.Lt.resize(nph);
+    for (size_t i = 0; i < nph; ++i) {
+        if (i == 0 || keep_all_phases) carve_tbound_layout(cv, pl.P, pr.Lt[i]);
+        else pr.Lt[i] = pr.Lt[0];
+    }
+    pr.x.tpos = cv.take<int>(nph * P * P);
+    pr.x.tbase = cv.take<long long>(nph * P);
+    pr.x.arena_end = cv.take<long long>(nph);
+}
+
+// the exact-size T arguments of phase i
+ExactT exact_t_of(const Prepared& pr, size_t i) {
+    ExactT x = pr.x;
+    if (!pr.exact_t) return ExactT{};
+    x.tpre = pr.Lt[i].pre; x.ld = pr.Lt[i].ld; x.phase = (int)i;
+    return x;
+}
 
 bool phase_is_one_kernel(const Prepared& pr, const PhaseHost& ph) {
     return pr.fused || (pr.staggered && ph.dim == 1);
@@ -324,7 +385,8 @@ void fill_stats_header(const Prepared& pr, const Status& hs, tuna_stats_t& st) {
     st.w_local = pl.w_l; st.w_global = pl.w_g; st.K_local = pl.K_l; st.K_global = pl.K_g;
     st.B_local = pl.B_l; st.B_global = pl.B_g; st.n_phases = (int)pl.phases.size();
     if (pr.staggered) st.K_global = pr.Q * (pr.N - 1);
-    st.temp_slots_per_rank = pl.slots;
+    st.temp_slots_per_rank = pr.exact_t ? 0 : pl.slots;
+    st.dense_t = g.opt_dense_t ? 1 : 0;
     st.fused = pr.fused ? 1 : 0;
     st.max_block_bytes = hs.max_count;
     st.total_payload_bytes = (int64_t)hs.total_bytes;
@@ -361,7 +423,8 @@ int prepare_call(const void* sendbuf, const int32_t* sendcounts, const int64_t* 
     pr.sendbuf = sendbuf; pr.recvbuf = recvbuf; pr.sendcounts = sendcounts; pr.recvcounts = recvcounts;
     pr.sdispls = sdispls; pr.rdispls = rdispls;
     // ---- validation, M, totals (one read-back) -------------------------------------------------
-    rc = run_validate(sendcounts, recvcounts, sdispls, rdispls, P, s);
+    pr.exact_t = g.opt_dense_t != 0 && pr.dp->host.slots > 0;      // a schedule without T (r >= P - 1) has nothing to size
+    rc = run_validate(sendcounts, recvcounts, sdispls, rdispls, P, s, pr.exact_t ? &pr.dp->host : nullptr);
     if (rc != TUNA_OK) return rc;
     hs = *g.h_status;
     if (pr.dp->built_on == s) pr.dp->complete = true;      // run_validate synchronised this stream
@@ -382,23 +445,23 @@ int prepare_call(const void* sendbuf, const int32_t* sendcounts, const int64_t* 
     pr.gran = (abits & 15u) == 0 ? 16 : ((abits & 3u) == 0 ? 4 : 1);
     pr.max_count = hs.max_count;
     pr.user_limit = (unsigned long long)(uintptr_t)sendbuf + hs.send_extent;
-    pr.ds = data_sizes_for(pr.dp->host, hs.max_count, hs.total_chunks, pr.fused, pr.staggered);
+    pr.ds = data_sizes_for(pr.dp->host, hs.max_count, hs.total_chunks, pr.fused, pr.staggered, pr.exact_t, hs.t_chunks);
     return TUNA_OK;
 }
 
 int launch_phase_metadata(const Prepared& pr, size_t i, const int32_t* cur, int32_t* nxt, const LayoutDev& Ls,
-                          const LayoutDev& Lr, hipStream_t s, const LayoutDev* Lt = nullptr) {
+                          const LayoutDev& Lr, hipStream_t s) {
     const PhaseHost& ph = pr.dp->host.phases[i];
     const bool one_kernel = phase_is_one_kernel(pr, ph);
     PhaseLayoutArgs m{};
     m.cur = cur; m.nxt = nxt; m.zt = pr.dp->d_zt[i]; m.seg = pr.dp->d_seg[i]; m.nseg = ph.nseg;
     m.P = pr.P; m.Q = pr.Q; m.N = pr.N; m.dim = ph.dim; m.rx = (int)ph.rx;
     m.Ls = Ls; m.Lr = Lr; m.want_send = one_kernel ? 0 : 1;
-    if (Lt) { m.Lt = *Lt; m.want_tbound = 1; }
+    if (pr.exact_t) { m.Lt = pr.Lt[i]; m.want_tbound = 1; m.tpos = pr.x.tpos + i * (size_t)pr.P * pr.P; }
     m.phase_bytes = &g.d_status->phase_bytes[i]; m.phase_chunks = &g.d_status->phase_chunks[i];
     m.head_displs = one_kernel ? pr.rdispls : nullptr;
     m.head_base = (unsigned int)((uintptr_t)pr.recvbuf & 15u);
-    return phase_metadata(m, s);
+    return phase_metadata(m, s, exact_t_of(pr, i));
 }
 
 int launch_self_copy(const Prepared& pr, hipStream_t s) {
@@ -419,8 +482,7 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
     a.T = pr.T; a.slots = pr.ds.slots; a.slot_bytes = pr.ds.slot_bytes;
     a.P = pr.P; a.Q = pr.Q; a.N = pr.N; a.dim = ph.dim; a.rx = (int)ph.rx;
     a.user_limit = pr.user_limit;
-    a.dense = pr.dense; a.phase = (int)i;
-    a.srcref = pr.dense ? pr.srcref[i] : nullptr;
+    a.x = exact_t_of(pr, i);
     int rc;
     if (phase_is_one_kernel(pr, ph)) {
         // one hop in one kernel: S / T of the sender -> R / the other copy of T at the receiver
@@ -472,7 +534,7 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
     const PlanHost& pl = pr.dp->host;
 
     // ---- workspace ---------------------------------------------------------------------------
-    const size_t mbytes = meta_bytes_for(P);
+    const size_t mbytes = meta_bytes_for(P) + (pr.exact_t ? exact_t_meta_bytes_for(pl, false) : 0);
     const DataSizes& ds = pr.ds;
     void *mbase, *dbase;
     if (g.user_ws) {
@@ -489,6 +551,7 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
     }
     Carver cm(mbase, mbytes);
     MetaBuffers mb = carve_meta(cm, P);
+    if (pr.exact_t) carve_exact_t(cm, pl, false, pr);
     Carver cd(dbase, ds.total);
     mb.Ls.units = cd.take<int4>(ds.unit_cap);
     mb.Lr.units = cd.take<int4>(ds.unit_cap);
@@ -535,8 +598,6 @@ struct Plan {
     void* mem_meta = nullptr;       // cur / nxt and every phase's two layouts
     void* mem_data = nullptr;       // staging and T
     std::vector<LayoutDev> Ls, Lr;  // per phase
-    std::vector<LayoutDev> Lt;      // per phase, exact-size T only: prefix over the T-bound blocks
-    bool dense = false;
     std::vector<size_t> units;      // per phase: exact number of wave units (max of the two layouts)
     tuna_stats_t stats;
     unsigned long long phase_bytes[TUNA_MAX_PHASES];
@@ -555,20 +616,6 @@ void carve_full_layout(Carver& cv, int P, size_t unit_cap, LayoutDev& L) {
     L.units = cv.take<int4>(unit_cap);
 }
 
-// prefix-only layout of the T-bound blocks of one phase (exact-size T)
-size_t tbound_layout_bytes_for(int P) {
-    const size_t ld = (size_t)P + 1;
-    return align_up((size_t)P * ld * 4) + align_up((size_t)P * 4) + align_up(((size_t)P + 1) * 8);
-}
-
-void carve_tbound_layout(Carver& cv, int P, LayoutDev& L) {
-    L.ld = P + 1;
-    L.pre = cv.take<int>((size_t)P * L.ld);
-    L.tot = cv.take<int>(P);
-    L.rank_base = cv.take<long long>(P + 1);
-    L.unit_base = nullptr; L.n_units = nullptr; L.units = nullptr;
-}
-
 int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
                 const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
                 hipStream_t s, Plan** out) {
@@ -584,13 +631,8 @@ int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* s
     const size_t nph = pl.phases.size();
     // metadata memory: two size matrices + per phase two complete layouts
     const size_t P2 = (size_t)P * P;
-    plan->dense = g.opt_dense_t != 0;
-    size_t dense_meta = 0;
-    if (plan->dense) {
-        dense_meta = nph * tbound_layout_bytes_for(P) + align_up(nph * sizeof(DenseT));
-        for (const PhaseHost& ph : pl.phases) dense_meta += align_up((size_t)ph.nseg * sizeof(SrcRef));
-    }
-    const size_t mbytes = 2 * align_up(P2 * 4) + nph * 2 * layout_bytes_for(P, pr.ds.unit_cap) + dense_meta;
+    const size_t mbytes = 2 * align_up(P2 * 4) + nph * 2 * layout_bytes_for(P, pr.ds.unit_cap) +
+                          (pr.exact_t ? exact_t_meta_bytes_for(pl, true) : 0);
     hipError_t e = hipMalloc(&plan->mem_meta, mbytes ? mbytes : kAlign);
     if (e != hipSuccess) { (void)hipGetLastError(); g.last_hip_error = (int)e; delete plan; return TUNA_ERR_NOMEM; }
     Carver cm(plan->mem_meta, mbytes);
@@ -601,29 +643,21 @@ int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* s
         carve_full_layout(cm, P, pr.ds.unit_cap, plan->Ls[i]);
         carve_full_layout(cm, P, pr.ds.unit_cap, plan->Lr[i]);
     }
-    DenseT* d_dense = nullptr;
-    if (plan->dense) {
-        plan->Lt.resize(nph);
-        for (size_t i = 0; i < nph; ++i) carve_tbound_layout(cm, P, plan->Lt[i]);
-        d_dense = cm.take<DenseT>(nph);
-        for (size_t i = 0; i < nph; ++i) pr.srcref.push_back(cm.take<SrcRef>((size_t)pl.phases[i].nseg));
-    }
+    if (pr.exact_t) carve_exact_t(cm, pl, true, pr);
     auto fail = [&](int code) { (void)hipFree(plan->mem_meta); if (plan->mem_data) (void)hipFree(plan->mem_data); delete plan; return code; };
     if (!cm.ok) return fail(TUNA_ERR_NOMEM);
     const unsigned gP2 = (unsigned)((P2 + 255) / 256);
     hipLaunchKernelGGL(k_rotate_init, dim3(gP2), dim3(256), 0, s, sendcounts, cur, P, pr.Q, pr.N);
     if (hipGetLastError() != hipSuccess) return fail(TUNA_ERR_HIP);
     for (size_t i = 0; i < nph; ++i) {
-        rc = launch_phase_metadata(pr, i, cur, nxt, plan->Ls[i], plan->Lr[i], s, plan->dense ? &plan->Lt[i] : nullptr);
+        rc = launch_phase_metadata(pr, i, cur, nxt, plan->Ls[i], plan->Lr[i], s);
         if (rc != TUNA_OK) return fail(rc);
         std::swap(cur, nxt);
     }
     // exact unit counts and staged chunks per phase
     std::vector<int> nu(2 * nph, 0);
-    std::vector<long long> tchunks(nph, 0);       // exact-size T: chunks every phase stores into T
     for (size_t i = 0; i < nph; ++i) {
         const bool one = phase_is_one_kernel(pr, pl.phases[i]);
-        if (plan->dense && hipMemcpyAsync(&tchunks[i], plan->Lt[i].rank_base + P, 8, hipMemcpyDeviceToHost, s) != hipSuccess) return fail(TUNA_ERR_HIP);
         if (hipMemcpyAsync(&nu[2 * i], plan->Lr[i].n_units, 4, hipMemcpyDeviceToHost, s) != hipSuccess) return fail(TUNA_ERR_HIP);
         if (!one && hipMemcpyAsync(&nu[2 * i + 1], plan->Ls[i].n_units, 4, hipMemcpyDeviceToHost, s) != hipSuccess) return fail(TUNA_ERR_HIP);
     }
@@ -641,12 +675,6 @@ int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* s
     // payload memory: staging sized by the largest phase; T by M and the slot count, or -- exact
     // size -- one arena per phase that holds just the blocks that phase stores into T
     const size_t stage_bytes = align_up((size_t)max_chunks * 16);
-    if (plan->dense) {
-        pr.ds.t_bytes = 0;
-        for (size_t i = 0; i < nph; ++i) pr.ds.t_bytes += align_up((size_t)tchunks[i] * 16);
-        pr.ds.slots = 0;
-        plan->stats.temp_slots_per_rank = 0;
-    }
     const size_t dbytes = 2 * stage_bytes + (pr.ds.t_bytes ? align_up(pr.ds.t_bytes + kTailSlack) : 0);
     if (dbytes) {
         e = hipMalloc(&plan->mem_data, dbytes);
@@ -656,25 +684,6 @@ int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* s
         pr.stage_r = cd.take<v4u>(stage_bytes / 16);
         pr.T = cd.take<unsigned char>(pr.ds.t_bytes ? pr.ds.t_bytes + kTailSlack : 0);
     }
-    if (plan->dense) {
-        std::vector<DenseT> hd(nph);
-        size_t off = 0;
-        for (size_t i = 0; i < nph; ++i) {
-            hd[i] = DenseT{pr.T ? pr.T + off : nullptr, plan->Lt[i].pre, plan->Lt[i].rank_base, plan->Lt[i].ld, 0};
-            off += align_up((size_t)tchunks[i] * 16);
-        }
-        if (hipMemcpy(d_dense, hd.data(), nph * sizeof(DenseT), hipMemcpyHostToDevice) != hipSuccess) return fail(TUNA_ERR_HIP);
-        pr.dense = d_dense;
-        for (size_t i = 0; i < nph; ++i) {
-            const int nseg = pl.phases[i].nseg;
-            if (nseg == 0) continue;
-            hipLaunchKernelGGL(k_plan_sources, dim3((unsigned)((nseg + 255) / 256)), dim3(256), 0, s, pr.dp->d_seg[i],
-                               nseg, d_dense, const_cast<SrcRef*>(pr.srcref[i]));
-            if (hipGetLastError() != hipSuccess) return fail(TUNA_ERR_HIP);
-        }
-        if (hipStreamSynchronize(s) != hipSuccess) return fail(TUNA_ERR_HIP);
-    }
-    plan->stats.dense_t = plan->dense ? 1 : 0;
     plan->stats.temp_bytes = (int64_t)pr.ds.t_bytes;
     plan->stats.staging_bytes = (int64_t)(2 * stage_bytes);
     plan->stats.workspace_bytes = (int64_t)(mbytes + dbytes);
@@ -769,24 +778,18 @@ int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node, i
     if (rc != TUNA_OK) return rc;
     rc = ensure_ctx();
     if (rc != TUNA_OK) return rc;
-    rc = run_validate(sendcounts, nullptr, nullptr, nullptr, P, nullptr);
+    // the schedule's scalars do not need the device tables
+    const int N = P / Q;
+    const bool staggered = g.opt_staggered != 0 && N > 1;
+    const PlanHost pl = make_plan(P, Q, local_radix, staggered ? N : global_radix, g.opt_fused != 0, /*with_tables=*/false);
+    if ((int)pl.phases.size() > TUNA_MAX_PHASES) return TUNA_ERR_TOO_LARGE;
+    const bool exact_t = g.opt_dense_t != 0 && pl.slots > 0;
+    rc = run_validate(sendcounts, nullptr, nullptr, nullptr, P, nullptr, exact_t ? &pl : nullptr);
     if (rc != TUNA_OK) return rc;
     if (g.h_status->flags & 1u) return TUNA_ERR_NEGATIVE_COUNT;
-    // the schedule's slot count does not need the device tables
-    const int N = P / Q;
-    int rl = local_radix, rg = global_radix;
-    const bool staggered = g.opt_staggered != 0 && N > 1;
-    if (staggered) rg = N;
-    if (Q >= 2 && rl > Q) rl = Q;
-    if (N >= 2 && rg > N) rg = N;
-    PlanHost pl;
-    pl.P = P; pl.Q = Q; pl.N = N;
-    const int Kl = Q > 1 ? num_rounds(Q, rl) : 0, Kg = N > 1 ? num_rounds(N, rg) : 0;
-    const int Bl = Q > 1 ? Q - 1 - Kl : 0, Bg = N > 1 ? N - 1 - Kg : 0;
-    pl.slots = ((int64_t)Bl + (int64_t)(N - 1) * (Q - 1) + (int64_t)Bg * Q) * (g.opt_fused ? 2 : 1);
-    if (P > 1) pl.phases.resize(1);
-    const DataSizes ds = data_sizes_for(pl, g.h_status->max_count, g.h_status->total_chunks, g.opt_fused != 0, staggered);
-    *bytes = meta_bytes_for(P) + ds.total;
+    const DataSizes ds = data_sizes_for(pl, g.h_status->max_count, g.h_status->total_chunks, g.opt_fused != 0, staggered,
+                                        exact_t, g.h_status->t_chunks);
+    *bytes = meta_bytes_for(P) + (exact_t ? exact_t_meta_bytes_for(pl, false) : 0) + ds.total;
     return TUNA_OK;
 }
 

@@ -39,6 +39,7 @@ struct Status {
     unsigned long long total_bytes;    // sum of sendcounts
     unsigned long long total_chunks;   // sum of ceil(count / 16)
     unsigned long long send_extent;    // max over non-empty blocks of sdispls + count: bytes of sendbuf that hold blocks
+    unsigned long long t_chunks;       // exact-size T: chunks stored into T over all phases (k_t_chunks)
     unsigned long long phase_bytes[64];   // payload bytes moved per phase
     unsigned long long phase_chunks[64];  // staged chunks per phase
 };
@@ -54,23 +55,15 @@ struct SegDev {
 };
 
 // Exact-size T: the blocks a rank stores into T in one phase lie back to back, in message order,
-// in that phase's arena.  pre / rank_base are the chunk prefix of the T-bound blocks only.
-struct DenseT {
-    unsigned char* arena;
-    const int* pre;                // [P][ld]
-    const long long* rank_base;    // [P+1]
+// in that phase's arena; the arenas follow each other in T.  All offsets are in 16-byte chunks.
+// A later phase finds a block through the phase that stored it and its slot index e.
+struct ExactT {
+    long long* tbase;      // [phases][P]: first chunk in T of rank p's part of a phase's arena
+    long long* arena_end;  // [phases]: one past the last chunk of a phase's arena, rounded up to 256 bytes
+    int* tpos;             // [phases][P][P]: chunk offset inside that part of the block with slot index e
+    int* tpre;             // [P][ld]: the same offsets for the phase being run, in message order
     int ld;
-    int pad;
-};
-
-// Where a plan with exact-size T finds the block of one table entry: resolved per segment when the
-// plan is made, so that the copy kernels load it together with the other table fields.
-struct SrcRef {
-    const unsigned char* arena;    // nullptr: the block is still in the send buffer
-    const long long* rank_base;
-    const int* pre_col;            // prefix column of the segment in the phase that stored it: [p * ld]
-    int ld;
-    int pad;
+    int phase;             // index of the phase being run
 };
 
 // Distance pair of a slot index.
@@ -141,22 +134,6 @@ __global__ void __launch_bounds__(256) k_build_phase_table(const PlanScalars pl,
     } else {
         zt[e] = 0;
     }
-}
-
-// ------------------------------------------------------------------------------------------
-// k_plan_sources: per-plan source references of one phase for exact-size T.
-// ------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) k_plan_sources(SegDev seg, int nseg, const DenseT* __restrict__ dense,
-                                                      SrcRef* __restrict__ out) {
-    const int s = blockIdx.x * blockDim.x + threadIdx.x;
-    if (s >= nseg) return;
-    SrcRef r{};
-    const int ph = seg.srcph[s];
-    if (ph >= 0) {
-        const DenseT d = dense[ph];
-        r.arena = d.arena; r.rank_base = d.rank_base; r.pre_col = d.pre + seg.srcseg[s]; r.ld = d.ld;
-    }
-    out[s] = r;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -254,6 +231,31 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
 }
 
 // ------------------------------------------------------------------------------------------
+// k_t_chunks: the exact size of T.  A block is stored into T after every hop but its last, and it
+// makes one hop per non-zero digit of its distance pair (l in base r_l, j in base r_g), so T takes
+// sum over blocks of ceil(count / 16) * (hops - 1) chunks over all phases.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_t_chunks(const int32_t* __restrict__ sendcounts, int P, int Q, int N,
+                                                  int rl, int rg, Status* __restrict__ st) {
+    unsigned long long acc = 0;
+    const size_t total = (size_t)P * P;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+        const int c = sendcounts[idx];
+        if (c <= 0) continue;
+        const int i = (int)(idx / P), d = (int)(idx - (size_t)i * P);
+        int l = i % Q - d % Q; if (l < 0) l += Q;
+        int j = i / Q - d / Q; if (j < 0) j += N;
+        int hops = 0;
+        for (; l; l /= rl) hops += (l % rl) != 0;
+        for (; j; j /= rg) hops += (j % rg) != 0;
+        if (hops > 1) acc += (unsigned long long)((c + 15) >> 4) * (unsigned long long)(hops - 1);
+    }
+#pragma unroll
+    for (int dlt = kWave / 2; dlt > 0; dlt >>= 1) acc += __shfl_xor(acc, dlt, kWave);
+    if ((threadIdx.x & (kWave - 1)) == 0 && acc) atomicAdd(&st->t_chunks, acc);
+}
+
+// ------------------------------------------------------------------------------------------
 // k_rotate_init: the index-only initial rotation (Algorithm "TuNA", lines 4-5; Algorithm
 // "Coalesced TuNA_l^g", line 5).  No payload moves: cur[p][j*Q + l] becomes the size of the
 // block rank p = (n, g) holds at distance (j, l), i.e. its block for rank ((n-j)%N, (g-l)%Q).
@@ -320,6 +322,7 @@ struct PhaseLayoutArgs {
     LayoutDev Ls, Lr, Lt;
     int want_send;                  // 0: only the receive-side layout (one-kernel phases)
     int want_tbound;                // 1: also the prefix over the T-bound blocks alone (exact-size T)
+    int* tpos;                      // [P][P]: that prefix again, by slot index, for the phases that forward the blocks
     unsigned long long* phase_bytes;
     unsigned long long* phase_chunks;
     const int64_t* head_displs;
@@ -353,7 +356,7 @@ __device__ __forceinline__ int block_scan_batch(const int (&c)[kScanItems], int&
 // thread sums a contiguous range of ranks, the thread sums are scanned across the workgroup, then
 // every thread writes the bases of its range
 __device__ __forceinline__ void scan_rank_bases(int P, const LayoutDev& L, unsigned long long* phase_chunks,
-                                                long long* wc, int* wt) {
+                                                long long* wc, int* wt, const ExactT* x = nullptr) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const int per = (P + kScanThreads - 1) / kScanThreads;
     const int p0 = min(P, tid * per), p1 = min(P, p0 + per);
@@ -383,9 +386,12 @@ __device__ __forceinline__ void scan_rank_bases(int P, const LayoutDev& L, unsig
     }
     long long run_c = oc + ic - sc;
     int run_t = ot + it - st;
+    // exact-size T: this phase's arena starts where the previous one ends
+    const long long arena0 = (x && x->phase > 0) ? x->arena_end[x->phase - 1] : 0;
     for (int p = p0; p < p1; ++p) {
         const int c = L.tot[p];
         L.rank_base[p] = run_c;
+        if (x) x->tbase[(size_t)x->phase * P + p] = arena0 + run_c;
         if (L.unit_base) L.unit_base[p] = run_t;
         run_c += c;
         run_t += (c + kUnitChunks - 1) / kUnitChunks;
@@ -394,6 +400,7 @@ __device__ __forceinline__ void scan_rank_bases(int P, const LayoutDev& L, unsig
         L.rank_base[P] = totc;
         if (L.unit_base) { L.unit_base[P] = tott; *L.n_units = tott; }
         if (phase_chunks) *phase_chunks = (unsigned long long)totc;
+        if (x) x->arena_end[x->phase] = arena0 + (totc + 15) / 16 * 16;
     }
 }
 
@@ -462,7 +469,10 @@ __global__ void __launch_bounds__(kScanThreads) k_phase_layout(const PhaseLayout
 #pragma unroll
             for (int k = 0; k < kScanItems; ++k) {
                 const int s = base + tid * kScanItems + k;
-                if (s < a.nseg) pre_t[s] = run;
+                if (s < a.nseg) {
+                    pre_t[s] = run;
+                    if (ct[k]) a.tpos[(size_t)p * P + a.seg.e[s]] = run;
+                }
                 run += ct[k];
             }
         }
@@ -485,11 +495,12 @@ __global__ void __launch_bounds__(kScanThreads) k_phase_layout(const PhaseLayout
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kScanThreads) k_layout_base(int P, LayoutDev L0, LayoutDev L1, LayoutDev L2,
                                                               unsigned long long* __restrict__ phase_chunks,
-                                                              int chunks_from) {
+                                                              int chunks_from, int tbound_at, ExactT x) {
     __shared__ long long wc[kScanThreads / kWave];
     __shared__ int wt[kScanThreads / kWave];
     const int which = blockIdx.x;
-    scan_rank_bases(P, which == 0 ? L0 : (which == 1 ? L1 : L2), which == chunks_from ? phase_chunks : nullptr, wc, wt);
+    scan_rank_bases(P, which == 0 ? L0 : (which == 1 ? L1 : L2), which == chunks_from ? phase_chunks : nullptr, wc, wt,
+                    which == tbound_at ? &x : nullptr);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -555,9 +566,7 @@ struct CopyArgs {
     const int64_t* displs2;             // rdispls
     unsigned char* T2;                  // the copy of T written in this phase
     // exact-size T (DENSE kernels): one arena per phase instead of slots
-    const DenseT* dense;
-    const SrcRef* srcref;               // [nseg] of the phase being run
-    int phase;                          // index of the phase being run
+    ExactT x;
     int P, Q, N, dim, rx;
 };
 
@@ -620,14 +629,14 @@ __device__ __forceinline__ unsigned long long block_address(int slot, bool far_i
     return (unsigned long long)(user + displs[idx]);
 }
 
-// Address of a block in exact-size T: segment s of rank p in the arena of `phase`.
-__device__ __forceinline__ unsigned long long dense_address(const DenseT* dense, int phase, int p, int s) {
-    const DenseT d = dense[phase];
-    return (unsigned long long)(d.arena + ((d.rank_base[p] + (long long)d.pre[(size_t)p * d.ld + s]) << 4));
+// Exact-size T: where rank p stores segment s of the phase being run, and where rank p holds the
+// block with slot index e that phase `ph` stored.
+__device__ __forceinline__ unsigned long long exact_t_dst(unsigned char* T, const ExactT& x, int P, int p, int s) {
+    return (unsigned long long)(T + ((x.tbase[(size_t)x.phase * P + p] + (long long)x.tpre[(size_t)p * x.ld + s]) << 4));
 }
-
-__device__ __forceinline__ unsigned long long dense_source(const SrcRef& r, int p) {
-    return (unsigned long long)(r.arena + ((r.rank_base[p] + (long long)r.pre_col[(size_t)p * r.ld]) << 4));
+__device__ __forceinline__ unsigned long long exact_t_src(unsigned char* T, const ExactT& x, int P, int ph, int p, int e) {
+    const size_t row = (size_t)ph * P + p;
+    return (unsigned long long)(T + ((x.tbase[row] + (long long)x.tpos[row * P + e]) << 4));
 }
 
 // Waves per SIMD: measured on MI355X, the gathering kernels (pack, exchange) run fastest with at most 6
@@ -674,14 +683,13 @@ k_copy(const CopyArgs a) {
         int pre_n = __shfl_down(pre_i, 1, kWave);
         if (lane == kWave - 1) pre_n = pre_w;
         // table fields this mode needs, fetched together with the prefix (one round trip)
-        int se = 0, sz_ = 0, ssrc = -1, sdst = -1;
-        SrcRef ref{};
+        int se = 0, sz_ = 0, ssrc = -1, sdst = -1, sph = -1;
         if (s < a.nseg) {
             if (MODE != kExchange) se = a.seg.e[s];
             if (MODE == kExchange || MODE == kFused) sz_ = a.seg.z[s];
             if (MODE == kPack || MODE == kFused) {
                 ssrc = a.seg.src[s];
-                if (DENSE) ref = a.srcref[s];
+                if (DENSE) sph = a.seg.srcph[s];
             }
             if (MODE == kUnpack || MODE == kFused) sdst = a.seg.dst[s];
         }
@@ -704,7 +712,7 @@ k_copy(const CopyArgs a) {
                 split_slot_index(se, a.Q, a.N, bj, bl);
                 if (MODE == kPack) {
                     if (DENSE && ssrc >= 0)
-                        addr = dense_source(ref, p);
+                        addr = exact_t_src(a.T, a.x, a.P, sph, p, se);
                     else
                         addr = block_address(ssrc, false, p, n, g, bj, bl, a.P, a.Q, a.N, a.user, a.displs, a.T,
                                              a.slots, a.slot_bytes);
@@ -714,7 +722,7 @@ k_copy(const CopyArgs a) {
                     // a final block's size is the receiver's own recvcounts entry (validated equal to
                     // the sender's count), read next to its displacement
                     if (DENSE && sdst >= 0)           // exact-size T: blocks lie back to back, nothing to fill
-                        addr = dense_address(a.dense, a.phase, p, s);
+                        addr = exact_t_dst(a.T, a.x, a.P, p, s);
                     else
                         addr = block_address(sdst, true, p, n, g, bj, bl, a.P, a.Q, a.N, a.user, a.displs, a.T,
                                              a.slots, a.slot_bytes, a.counts, &size);
@@ -728,13 +736,13 @@ k_copy(const CopyArgs a) {
                     if (a.dim == 0) { sg += dist; if (sg >= a.Q) sg -= a.Q; }
                     else { sn += dist; if (sn >= a.N) sn -= a.N; }
                     if (DENSE && ssrc >= 0)
-                        addr = dense_source(ref, sn * a.Q + sg);
+                        addr = exact_t_src(a.T, a.x, a.P, sph, sn * a.Q + sg, se);
                     else
                         addr = block_address(ssrc, false, sn * a.Q + sg, sn, sg, bj, bl, a.P, a.Q, a.N, a.user,
                                              a.displs, a.T, a.slots, a.slot_bytes);
                     if (ssrc >= 0) flag |= kFlagSrcT;
                     if (DENSE && sdst >= 0)
-                        addr2 = dense_address(a.dense, a.phase, p, s);
+                        addr2 = exact_t_dst(a.T2, a.x, a.P, p, s);
                     else
                         addr2 = block_address(sdst, true, p, n, g, bj, bl, a.P, a.Q, a.N, a.user2, a.displs2,
                                               a.T2, a.slots, a.slot_bytes, a.counts, &size);

@@ -22,13 +22,15 @@ def tuna():
     return t
 
 
-@pytest.fixture(autouse=True, params=["staged", "fused"])
+@pytest.fixture(autouse=True, params=["staged", "fused", "exact", "fused_exact"])
 def mode(request, tuna):
     """Every case runs with the three-stage phases (pack, exchange, unpack) and with the fused
-    single-kernel phases."""
-    tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 1 if request.param == "fused" else 0)
+    single-kernel phases, each with T in slots of M bytes and with T in exact size."""
+    tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 1 if request.param.startswith("fused") else 0)
+    tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 1 if request.param.endswith("exact") else 0)
     yield request.param
     tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+    tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 0)
 
 
 class Problem:
@@ -85,7 +87,8 @@ def test_config1_traceable_payload(tuna, mode):
     prob = Problem(lay, wl.payload_traceable_int32(lay))
     run_flat(tuna, prob, 2)
     st = tuna.tuna_get_stats()
-    assert st.fused == (1 if mode == "fused" else 0)
+    assert st.fused == (1 if mode.startswith("fused") else 0)
+    assert st.dense_t == (1 if mode.endswith("exact") else 0)
     assert (st.P, st.w_local, st.K_local, st.B_local) == (16, 4, 4, 11)
     assert st.total_payload_bytes == lay.payload_bytes and st.max_block_bytes == lay.sendcounts.max()
     assert st.granularity == 4
@@ -341,7 +344,7 @@ def test_plain_copy(tuna):
 def test_random_problems(tuna, mode):
     """Seeded random problems: rank counts, hierarchy, radices, size distributions (empty rows and
     columns, tiny and large blocks, every alignment), gaps and region order all vary."""
-    rng = np.random.default_rng(20241102 + (1 if mode == "fused" else 0))
+    rng = np.random.default_rng(20241102 + ["staged", "fused", "exact", "fused_exact"].index(mode))
     for case in range(40):
         Q = int(rng.integers(1, 9))
         N = int(rng.integers(1, 9))
@@ -397,7 +400,8 @@ def test_phase_bytes_closed_form(tuna, mode):
 def test_temporary_buffer_too_large_is_an_error_not_a_crash(tuna, mode):
     """T has one M-byte slot per intermediate block: one 512 MiB block among 64 ranks at radix 2
     asks for terabytes.  The call must return TUNA_ERR_NOMEM, move nothing, and leave the library
-    usable; the same problem runs at radix P, which needs no T."""
+    usable; the same problem runs at radix P, which needs no T -- and at radix 2 with T in exact
+    size, which then holds that one block three times (its index 27 has four non-zero bits)."""
     P = 64
     counts = np.zeros((P, P), dtype=np.int32)
     counts[3, 40] = 512 << 20
@@ -408,11 +412,17 @@ def test_temporary_buffer_too_large_is_an_error_not_a_crash(tuna, mode):
     recv = torch.zeros(lay.recv_bytes, dtype=torch.uint8, device=dev)
     d = [torch.from_numpy(a).to(dev) for a in (lay.sendcounts, lay.sdispls, lay.recvcounts, lay.rdispls)]
     rc = tuna.tuna_alltoallv(send, d[0], d[1], recv, d[2], d[3], P, 2, 0)
-    assert rc == tuna.TUNA_ERR_NOMEM, tuna.tuna_strerror(rc)
-    torch.cuda.synchronize()
-    assert int(recv.count_nonzero()) == 0
-    rc = tuna.tuna_alltoallv(send, d[0], d[1], recv, d[2], d[3], P, P, 0)
-    assert rc == 0, tuna.tuna_strerror(rc)
+    if mode.endswith("exact"):
+        assert rc == 0, tuna.tuna_strerror(rc)
+        st = tuna.tuna_get_stats()
+        # the 100-byte block (7 chunks) has index 63: six hops, five stores; six phases of 256 bytes rounding
+        assert st.temp_bytes == 3 * (512 << 20) + 5 * 7 * 16 + 6 * 256
+    else:
+        assert rc == tuna.TUNA_ERR_NOMEM, tuna.tuna_strerror(rc)
+        torch.cuda.synchronize()
+        assert int(recv.count_nonzero()) == 0
+        rc = tuna.tuna_alltoallv(send, d[0], d[1], recv, d[2], d[3], P, P, 0)
+        assert rc == 0, tuna.tuna_strerror(rc)
     torch.cuda.synchronize()
     so, ro, n = int(lay.sdispls[3, 40]), int(lay.rdispls[40, 3]), 512 << 20
     assert torch.equal(recv[ro:ro + n], send[so:so + n])

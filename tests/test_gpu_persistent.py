@@ -215,7 +215,7 @@ def test_exact_size_t_matches_the_oracle(tuna, P, Q, rl, rg, cfg, mode):
 
 def test_exact_size_t_holds_what_waits_in_it(tuna):
     """T in exact size takes the bytes that are stored into it, summed over the phases (each block
-    padded to 16 bytes, each phase to 256): for every phase but the last that is the phase's
+    padded to 16 bytes, plus 256 bytes of rounding per phase): for every phase but the last that is the phase's
     payload minus what reaches R.  With r = 2 and P = 2^k, phase x delivers the blocks whose index
     is below 2^(x+1) among those with bit x set, 2^x of P/2.  Heavy-tailed sizes make the bound
     of B slots of M bytes many times larger."""
@@ -241,8 +241,8 @@ def test_exact_size_t_holds_what_waits_in_it(tuna):
     total = 0
     for x in range(8):
         stored = ((idx >> x) & 1 == 1) & ((idx >> (x + 1)) != 0)
-        total += -(-int(chunks[stored].sum()) * 16 // 256) * 256
-    assert dense_bytes == total
+        total += int(chunks[stored].sum()) * 16
+    assert dense_bytes == total + 8 * 256              # each phase's arena is rounded up to 256 bytes
     code, plan = _dense_plan(tuna, res, P, 0, 2, 2, dense=0)
     assert code == 0
     try:

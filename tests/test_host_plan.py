@@ -289,3 +289,22 @@ def test_compute_entry_points_fail_loudly_without_a_gpu():
     out = ctypes.c_size_t(0)
     assert lib.tuna_workspace_bytes(1, 4, 0, 2, 2, ctypes.byref(out)) == tuna.TUNA_ERR_HIP
     assert tuna.tuna_plan_info(4, 0, 2, 2)[0] == 0
+
+
+@pytest.mark.parametrize("P,Q,rl,rg", [(16, 0, 2, 2), (27, 0, 3, 3), (30, 0, 4, 4), (24, 4, 2, 2), (60, 5, 3, 4),
+                                        (64, 8, 8, 8), (35, 7, 2, 5)])
+def test_exact_size_of_t_counts_hops_minus_one(P, Q, rl, rg):
+    """Exact-size T is allocated from sum over blocks of chunks * (hops - 1), hops = non-zero digits
+    of the distance pair: every slot index must be stored into T in exactly that many phases."""
+    rc, info = tuna.tuna_plan_info(P, Q, rl, rg)
+    assert rc == 0
+    stores = np.zeros(P, dtype=np.int64)
+    for ph in range(info.n_phases):
+        rc, hdr, seg = tuna.tuna_plan_phase(P, Q, rl, rg, ph)
+        assert rc == 0
+        for e, j, l, z, src_slot, dst_slot in seg.tolist():
+            stores[e] += dst_slot >= 0
+    for e in range(P):
+        j, l = divmod(e, info.Q)
+        hops = tm.nonzero_digits(l, info.local_radix) + tm.nonzero_digits(j, info.global_radix)
+        assert stores[e] == max(hops - 1, 0), (e, j, l)
