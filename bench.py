@@ -30,10 +30,13 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch (read + write), averaged over the launches of the default sweep
 # (P = 4096, radices 2, 8, 64, 4096: 19 launches of each copy kernel per step set), from two
 # `rocprofv3 --pmc` runs (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter
-# reads for tuna::k_plain_copy moving 4 GiB (factors 2.0000 and 0.9998).  The algorithmic figure
+# reads for tuna::k_plain_copy moving 4 GiB (factors 2.0000 and 0.9997).  The algorithmic figure
 # for the same launches is 2 x payload = 22.55e9 bytes; see profiles/k_copy_config4_P4096.md.
-MEASURED_TRAFFIC_CONFIG4 = {"pack": 23316.0 * 2**20, "exchange": 22822.0 * 2**20, "unpack": 22663.0 * 2**20,
-                            "fused": 23780.9 * 2**20}
+# First entry: T in exact size (the default); second: T in slots of M bytes (--exact-t 0).
+MEASURED_TRAFFIC_CONFIG4 = {
+    True: {"pack": 23285.8 * 2**20, "exchange": 22824.8 * 2**20, "unpack": 22308.0 * 2**20, "fused": 23405.8 * 2**20},
+    False: {"pack": 23317.6 * 2**20, "exchange": 22824.8 * 2**20, "unpack": 22667.5 * 2**20, "fused": 23782.4 * 2**20},
+}
 
 
 def parse_args():
@@ -48,10 +51,14 @@ def parse_args():
                     help="replace the configuration's counts by 8 * U{0..S/8} bytes (the paper's uniform [0, S] "
                          "micro-benchmark with FP64 elements); use with --ranks and --radices")
     ap.add_argument("--fused", type=int, default=0, help="1: fused single-kernel rounds")
-    ap.add_argument("--exact-t", type=int, default=0, help="1: T in exact size (TUNA_OPT_DENSE_T) in the main sweep")
+    ap.add_argument("--exact-t", type=int, default=1,
+                    help="main sweep: 1 = T in exact size (the library's default), 0 = the paper's B slots of M bytes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fused-table", action="store_true", help="skip the second sweep with fused rounds")
-    ap.add_argument("--no-secondary", action="store_true", help="skip the P=1024 hierarchical workload")
+    ap.add_argument("--secondary", action="store_true",
+                    help="also sweep the P=1024 hierarchical workload (configuration 3) into also_measured; off by "
+                         "default so that every launch of a copy kernel in the run belongs to the timed workload")
+    ap.add_argument("--no-secondary", action="store_true", help="accepted for older command lines; the default now")
     ap.add_argument("--no-persistent-table", action="store_true", help="skip the tuna_alltoallv_init / tuna_start sweep")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--traffic-json", type=str, default="",
@@ -199,10 +206,10 @@ def main():
                   file=sys.stderr, flush=True)
 
         tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
-        tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 1)
         return per_radix
 
-    def run_persistent(fused, exact_t=False):
+    def run_persistent(fused, exact_t=True):
         """tuna_alltoallv_init once per radix, then K timed tuna_start calls (no validation, no
         metadata kernels, no host synchronisation), eagerly and as one captured HIP graph.
         exact_t: T stored in exact size (one arena per phase) instead of B slots of M bytes."""
@@ -213,7 +220,7 @@ def main():
             tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 1 if exact_t else 0)
             rc, plan = tuna.tuna_alltoallv_init(send, d_sc, d_sd, recv, d_rc, d_rd, P, rpn, rl, rg)
             tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
-            tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 0)
+            tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 1)
             if rc != 0:
                 raise RuntimeError("tuna_alltoallv_init failed: " + tuna.tuna_strerror(rc))
             try:
@@ -241,7 +248,7 @@ def main():
                              "effective_GBs": Btot / (min(ms_start, ms_graph) * 1e-3) / 1e9,
                              "plan_bytes": st.workspace_bytes, "temp_bytes": st.temp_bytes})
                 print("[bench] %s persistent%s%s: %.3f ms/start, %.3f ms/graph replay, %.1f GB/s effective, T %.2f GiB" %
-                      (label, " fused" if fused else "", " exact-size T" if exact_t else "", ms_start, ms_graph,
+                      (label, " fused" if fused else "", "" if exact_t else " slots of M", ms_start, ms_graph,
                        rows[-1]["effective_GBs"], st.temp_bytes / 2 ** 30),
                       file=sys.stderr, flush=True)
             finally:
@@ -250,20 +257,20 @@ def main():
 
     per_radix = run_sweep(bool(args.fused), bool(args.exact_t))
     # the fused rounds (one kernel per phase, 2 x payload instead of 6 x) as a second table, and both
-    # with T in exact size instead of B slots of M bytes
-    fused_table = exact_table = fused_exact_table = None
-    if not args.fused and not args.exact_t and not args.no_fused_table:
-        fused_table = run_sweep(True)
-        exact_table = run_sweep(False, True)
-        fused_exact_table = run_sweep(True, True)
+    # with T in the paper's B slots of M bytes instead of exact size
+    fused_table = slots_table = fused_slots_table = None
+    if not args.fused and args.exact_t and not args.no_fused_table:
+        fused_table = run_sweep(True, True)
+        slots_table = run_sweep(False, False)
+        fused_slots_table = run_sweep(True, False)
     persistent = None
     if not args.no_persistent_table:
         persistent = {"note": "tuna_alltoallv_init once, then tuna_start per step: payload kernels only",
-                      "staged": run_persistent(bool(args.fused))}
-        persistent["staged_exact_t"] = run_persistent(bool(args.fused), exact_t=True)
-        if not args.fused and not args.no_fused_table:
+                      "staged": run_persistent(bool(args.fused), bool(args.exact_t))}
+        if not args.fused and args.exact_t and not args.no_fused_table:
             persistent["fused"] = run_persistent(True)
-            persistent["fused_exact_t"] = run_persistent(True, exact_t=True)
+            persistent["staged_slots_of_M"] = run_persistent(False, exact_t=False)
+            persistent["fused_slots_of_M"] = run_persistent(True, exact_t=False)
     best = max(per_radix, key=lambda r: r["effective_GBs"])
     # Roofline of the dominant kernel: the copy kernel with the largest total time over ALL launches
     # of the timed sweep (every radix), so that its average launch duration is the one a
@@ -284,8 +291,8 @@ def main():
         et = "true" if args.exact_t else "false"
         kname = {"pack": "tuna::k_copy<0, %d, %s>" % (gran, et), "exchange": "tuna::k_copy<1, 16, false>",
                  "unpack": "tuna::k_copy<2, %d, %s>" % (gran, et), "fused": "tuna::k_copy<3, %d, %s>" % (gran, et)}[name]
-        default_run = (args.config == 4 and P == 4096 and not args.radices and not args.exact_t)
-        traffic = MEASURED_TRAFFIC_CONFIG4.get(name) if default_run else None
+        default_run = (args.config == 4 and P == 4096 and not args.radices)
+        traffic = MEASURED_TRAFFIC_CONFIG4[bool(args.exact_t)].get(name) if default_run else None
         achieved = alg / (ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": kname, "stage": name, "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
@@ -298,14 +305,14 @@ def main():
         cpu_baseline = time_oracle(lay, send, args.cpu_seconds)
 
     also = None
-    if args.config == 4 and not args.ranks and not args.radices and not args.no_secondary:
+    if args.secondary and not args.no_secondary:
         also = {"config 3: " + wl.CONFIGS[3].description: quick_sweep(tuna, 3, args.steps, args.warmup)}
 
     out = {
         "metric": "effective Alltoallv GB/s and % of HBM peak vs radix, at P=1024/4096",
         "metric_note": "value = payload bytes / time per tuna_alltoallv call (three-stage phases) at the best radix of "
                        "the P=4096 workload; per_radix has every radix, roofline the copy kernels' share of the HBM "
-                       "peak, also_measured the P=1024 hierarchical workload",
+                       "peak, also_measured (with --secondary) the P=1024 hierarchical workload",
         "value": best["effective_GBs"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": best["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u8", "data": "synthetic",
@@ -319,9 +326,9 @@ def main():
         "fused_rounds": None if fused_table is None else {
             "note": "same workload with TUNA_OPT_FUSED: one kernel per digit phase moves S/T to R/T directly",
             "best_effective_GBs": max(r["effective_GBs"] for r in fused_table), "per_radix": fused_table},
-        "exact_size_t": None if exact_table is None else {
-            "note": "same workload with TUNA_OPT_DENSE_T: T holds the waiting blocks back to back instead of B slots of M bytes",
-            "per_radix": exact_table, "fused_per_radix": fused_exact_table},
+        "slots_of_M": None if slots_table is None else {
+            "note": "same workload with TUNA_OPT_DENSE_T = 0: T as the paper's B slots of M bytes per rank instead of exact size",
+            "per_radix": slots_table, "fused_per_radix": fused_slots_table},
     }
     print(json.dumps(out))
 

@@ -195,7 +195,7 @@ int tuna_release(void);
  * for hierarchical calls: after the intra-node phase every one of the Q (N - 1) blocks bound
  * for another node is its own message and goes straight from where it lies (its T slot, or S)
  * to R of its destination -- no rearrangement of T, no packing; the global radix is N.
- * TUNA_OPT_DENSE_T: 1 = T in exact size.  Section "Estimating temporary buffer size" bounds T
+ * TUNA_OPT_DENSE_T (on by default; 0 = the paper's slots): 1 = T in exact size.  Section "Estimating temporary buffer size" bounds T
  * by B slots of M bytes, M the largest block of all; with skewed sizes nearly all of that is
  * padding.  Here every block size is on the device before the first round, so the blocks a rank
  * stores into T in one phase can lie back to back (padded to 16 bytes) in an arena of that

@@ -49,7 +49,7 @@ struct Ctx {
     std::map<std::tuple<int, int, int, int, int>, DevicePlan> plans;
     tuna_stats_t stats;
     bool have_stats = false;
-    int opt_profile = 0, opt_fused = 0, opt_staggered = 0, opt_dense_t = 0;
+    int opt_profile = 0, opt_fused = 0, opt_staggered = 0, opt_dense_t = 1;
     std::vector<hipEvent_t> ev_pool;
     std::vector<Mark> marks;
     hipEvent_t ev_end = nullptr;
@@ -273,9 +273,11 @@ int launch_copy_as(int gran, size_t unit_cap, const CopyArgs& a, hipStream_t s) 
     return TUNA_OK;
 }
 
+// exact_kernels: the variant that addresses T in exact size (it never looks at its T arguments when
+// the schedule has no T-bound block, so it also serves schedules without T)
 template <int MODE>
-int launch_copy(int gran, size_t unit_cap, const CopyArgs& a, hipStream_t s) {
-    if (MODE != kExchange && a.x.tbase) return launch_copy_as<MODE, true>(gran, unit_cap, a, s);
+int launch_copy(int gran, size_t unit_cap, const CopyArgs& a, hipStream_t s, bool exact_kernels) {
+    if (MODE != kExchange && exact_kernels) return launch_copy_as<MODE, true>(gran, unit_cap, a, s);
     return launch_copy_as<MODE, false>(gran, unit_cap, a, s);
 }
 
@@ -349,7 +351,8 @@ struct Prepared {
     unsigned char* T = nullptr;
     // exact-size T: the prefix over the T-bound blocks (per phase, or one reused by every phase) and
     // the per-phase position tables; the arenas are assigned on the device, phase by phase
-    bool exact_t = false;
+    bool exact_t = false;               // T in exact size, and the schedule has T at all
+    bool exact_kernels = false;         // T in exact size was asked for
     std::vector<LayoutDev> Lt;
     ExactT x{};
 };
@@ -423,7 +426,8 @@ int prepare_call(const void* sendbuf, const int32_t* sendcounts, const int64_t* 
     pr.sendbuf = sendbuf; pr.recvbuf = recvbuf; pr.sendcounts = sendcounts; pr.recvcounts = recvcounts;
     pr.sdispls = sdispls; pr.rdispls = rdispls;
     // ---- validation, M, totals (one read-back) -------------------------------------------------
-    pr.exact_t = g.opt_dense_t != 0 && pr.dp->host.slots > 0;      // a schedule without T (r >= P - 1) has nothing to size
+    pr.exact_kernels = g.opt_dense_t != 0;
+    pr.exact_t = pr.exact_kernels && pr.dp->host.slots > 0;        // a schedule without T (r >= P - 1) has nothing to size
     rc = run_validate(sendcounts, recvcounts, sdispls, rdispls, P, s, pr.exact_t ? &pr.dp->host : nullptr);
     if (rc != TUNA_OK) return rc;
     hs = *g.h_status;
@@ -489,7 +493,7 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
         a.stage = nullptr; a.L = Lr; a.counts = pr.recvcounts;
         a.user = (unsigned char*)pr.sendbuf; a.displs = pr.sdispls;
         a.user2 = (unsigned char*)pr.recvbuf; a.displs2 = pr.rdispls; a.T2 = pr.T;
-        rc = launch_copy<kFused>(pr.gran, unit_cap, a, s);
+        rc = launch_copy<kFused>(pr.gran, unit_cap, a, s, pr.exact_kernels);
         if (rc != TUNA_OK) return rc;
         mark(s, kCatPack, (int)i);
         return TUNA_OK;
@@ -497,17 +501,17 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
     // pack: S / T -> send staging
     a.stage = pr.stage_s; a.L = Ls;
     a.user = (unsigned char*)pr.sendbuf; a.displs = pr.sdispls;
-    rc = launch_copy<kPack>(pr.gran, unit_cap, a, s);
+    rc = launch_copy<kPack>(pr.gran, unit_cap, a, s, pr.exact_kernels);
     if (rc != TUNA_OK) return rc;
     mark(s, kCatPack, (int)i);
     // exchange: send staging of the partner -> receive staging
     a.stage = pr.stage_r; a.L = Lr; a.stage_src = pr.stage_s; a.Ls = Ls;
-    rc = launch_copy<kExchange>(pr.gran, unit_cap, a, s);
+    rc = launch_copy<kExchange>(pr.gran, unit_cap, a, s, pr.exact_kernels);
     if (rc != TUNA_OK) return rc;
     mark(s, kCatExchange, (int)i);
     // unpack: receive staging -> R / T
     a.counts = pr.recvcounts; a.user = (unsigned char*)pr.recvbuf; a.displs = pr.rdispls;
-    rc = launch_copy<kUnpack>(pr.gran, unit_cap, a, s);
+    rc = launch_copy<kUnpack>(pr.gran, unit_cap, a, s, pr.exact_kernels);
     if (rc != TUNA_OK) return rc;
     mark(s, kCatUnpack, (int)i);
     return TUNA_OK;

@@ -120,27 +120,27 @@ def test_config4_full(tuna):
     send_sum = int(send.view(torch.int32).sum(dtype=torch.int64))
     counts_w = (sc.to(torch.int64) // 4)                      # [i, j] words of block i -> j
     sd_w = sd // 4
-    # (radix, fused rounds, persistent plan with exact-size T)
-    cases = [(r, 0, 0) for r in c.radices] + [(2, 1, 0), (4096, 1, 0), (2, 0, 1), (8, 1, 1)]
-    for r, fused, exact in cases:
+    # (radix, fused rounds, persistent plan, T in slots of M bytes instead of exact size)
+    cases = [(r, 0, 0, 0) for r in c.radices] + [(2, 1, 0, 0), (4096, 1, 0, 0), (2, 0, 0, 1), (8, 1, 0, 1),
+                                                  (2, 0, 1, 0), (8, 1, 1, 0)]
+    for r, fused, persistent, slots in cases:
         recv.zero_()
-        print("config 4 full size, radix=%d fused=%d exact-size T plan=%d" % (r, fused, exact), flush=True)
+        print("config 4 full size, radix=%d fused=%d persistent=%d slots-of-M=%d" % (r, fused, persistent, slots), flush=True)
         tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, fused)
-        if exact:
+        tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 0 if slots else 1)
+        if persistent:
             assert tuna.tuna_release() == 0                # the immediate calls' workspace is not needed here
-            tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 1)
             code, plan = tuna.tuna_alltoallv_init(send, sc, sd, recv, rc, rd, P, 0, r, r)
-            tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 0)
-            tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
             assert code == 0, tuna.tuna_strerror(code)
             code = tuna.tuna_start(plan)
             torch.cuda.synchronize()
-            assert tuna.tuna_get_stats().dense_t == 1
             assert tuna.tuna_plan_free(plan) == 0
         else:
             code = tuna.tuna_alltoallv(send, sc, sd, recv, rc, rd, P, r, 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 1)
         tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
         assert code == 0, tuna.tuna_strerror(code)
+        assert tuna.tuna_get_stats().dense_t == (0 if slots else 1)
         torch.cuda.synchronize()
         for (lo, hi), w in zip(regions, want_regions):
             assert torch.equal(recv[lo:hi], w), "radix %d: receiver region [%d, %d) differs from the oracle" % (r, lo, hi)

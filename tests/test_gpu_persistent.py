@@ -186,7 +186,7 @@ def _dense_plan(tuna, res, P, Q, rl, rg, fused=0, staggered=0, dense=1):
     finally:
         tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
         tuna.tuna_set_option(tuna.TUNA_OPT_STAGGERED, 0)
-        tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 1)             # the library's default
 
 
 @pytest.mark.parametrize("mode", ["staged", "fused", "staggered"])
