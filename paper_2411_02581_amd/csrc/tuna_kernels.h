@@ -406,8 +406,11 @@ __device__ __forceinline__ void scan_rank_bases(int P, const LayoutDev& L, unsig
 
 __global__ void __launch_bounds__(kScanThreads) k_phase_layout(const PhaseLayoutArgs a) {
     __shared__ int wsum[kScanThreads / kWave];
-    const int p = blockIdx.x;
     const int P = a.P;
+    // Workgroups go to the 8 XCDs round robin.  Give every XCD a contiguous range of ranks: with a
+    // large radix the sizes a rank receives lie on a diagonal of `cur`, and each of its 128-byte
+    // lines is shared by 32 neighbouring ranks -- in one L2 instead of eight.
+    const int p = (P & 7) ? (int)blockIdx.x : (int)(blockIdx.x & 7) * (P >> 3) + (int)(blockIdx.x >> 3);
     const int pn = p / a.Q, pg = p - pn * a.Q;
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int32_t* crow = a.cur + (size_t)p * P;
