@@ -355,6 +355,7 @@ struct Prepared {
     bool exact_kernels = false;         // T in exact size was asked for
     std::vector<LayoutDev> Lt;
     ExactT x{};
+    int64_t* sdispls_t = nullptr;       // one-kernel phases: transposed sdispls
 };
 
 void carve_exact_t(Carver& cv, const PlanHost& pl, bool keep_all_phases, Prepared& pr) {
@@ -468,6 +469,16 @@ int launch_phase_metadata(const Prepared& pr, size_t i, const int32_t* cur, int3
     return phase_metadata(m, s, exact_t_of(pr, i));
 }
 
+bool any_one_kernel_phase(const Prepared& pr) { return pr.fused || pr.staggered; }
+
+int launch_transpose_displs(const Prepared& pr, hipStream_t s) {
+    if (!any_one_kernel_phase(pr)) return TUNA_OK;
+    const unsigned t = (unsigned)((pr.P + 31) / 32);
+    hipLaunchKernelGGL(k_transpose_displs, dim3(t, t), dim3(32, 8), 0, s, pr.sdispls, pr.sdispls_t, pr.P);
+    HIPCHK(hipGetLastError());
+    return TUNA_OK;
+}
+
 int launch_self_copy(const Prepared& pr, hipStream_t s) {
     const int split = pr.max_count > (1 << 16) ? 16 : 1;
     hipLaunchKernelGGL(k_self_copy, dim3(pr.P, split), dim3(256), 0, s, (const unsigned char*)pr.sendbuf,
@@ -491,7 +502,7 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
     if (phase_is_one_kernel(pr, ph)) {
         // one hop in one kernel: S / T of the sender -> R / the other copy of T at the receiver
         a.stage = nullptr; a.L = Lr; a.counts = pr.recvcounts;
-        a.user = (unsigned char*)pr.sendbuf; a.displs = pr.sdispls;
+        a.user = (unsigned char*)pr.sendbuf; a.displs = pr.sdispls_t;
         a.user2 = (unsigned char*)pr.recvbuf; a.displs2 = pr.rdispls; a.T2 = pr.T;
         rc = launch_copy<kFused>(pr.gran, unit_cap, a, s, pr.exact_kernels);
         if (rc != TUNA_OK) return rc;
@@ -538,7 +549,8 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
     const PlanHost& pl = pr.dp->host;
 
     // ---- workspace ---------------------------------------------------------------------------
-    const size_t mbytes = meta_bytes_for(P) + (pr.exact_t ? exact_t_meta_bytes_for(pl, false) : 0);
+    const size_t mbytes = meta_bytes_for(P) + (pr.exact_t ? exact_t_meta_bytes_for(pl, false) : 0) +
+                          (any_one_kernel_phase(pr) ? align_up((size_t)P * P * 8) : 0);
     const DataSizes& ds = pr.ds;
     void *mbase, *dbase;
     if (g.user_ws) {
@@ -556,6 +568,7 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
     Carver cm(mbase, mbytes);
     MetaBuffers mb = carve_meta(cm, P);
     if (pr.exact_t) carve_exact_t(cm, pl, false, pr);
+    if (any_one_kernel_phase(pr)) pr.sdispls_t = cm.take<int64_t>((size_t)P * P);
     Carver cd(dbase, ds.total);
     mb.Ls.units = cd.take<int4>(ds.unit_cap);
     mb.Lr.units = cd.take<int4>(ds.unit_cap);
@@ -572,6 +585,8 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
     const unsigned gP2 = (unsigned)((P2 + 255) / 256);
     hipLaunchKernelGGL(k_rotate_init, dim3(gP2), dim3(256), 0, s, sendcounts, mb.cur, P, pr.Q, pr.N);
     HIPCHK(hipGetLastError());
+    rc = launch_transpose_displs(pr, s);
+    if (rc != TUNA_OK) return rc;
     mark(s, kCatPrepare, -1);
     rc = launch_self_copy(pr, s);
     if (rc != TUNA_OK) return rc;
@@ -636,7 +651,8 @@ int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* s
     // metadata memory: two size matrices + per phase two complete layouts
     const size_t P2 = (size_t)P * P;
     const size_t mbytes = 2 * align_up(P2 * 4) + nph * 2 * layout_bytes_for(P, pr.ds.unit_cap) +
-                          (pr.exact_t ? exact_t_meta_bytes_for(pl, true) : 0);
+                          (pr.exact_t ? exact_t_meta_bytes_for(pl, true) : 0) +
+                          (any_one_kernel_phase(pr) ? align_up(P2 * 8) : 0);
     hipError_t e = hipMalloc(&plan->mem_meta, mbytes ? mbytes : kAlign);
     if (e != hipSuccess) { (void)hipGetLastError(); g.last_hip_error = (int)e; delete plan; return TUNA_ERR_NOMEM; }
     Carver cm(plan->mem_meta, mbytes);
@@ -648,11 +664,14 @@ int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* s
         carve_full_layout(cm, P, pr.ds.unit_cap, plan->Lr[i]);
     }
     if (pr.exact_t) carve_exact_t(cm, pl, true, pr);
+    if (any_one_kernel_phase(pr)) pr.sdispls_t = cm.take<int64_t>(P2);
     auto fail = [&](int code) { (void)hipFree(plan->mem_meta); if (plan->mem_data) (void)hipFree(plan->mem_data); delete plan; return code; };
     if (!cm.ok) return fail(TUNA_ERR_NOMEM);
     const unsigned gP2 = (unsigned)((P2 + 255) / 256);
     hipLaunchKernelGGL(k_rotate_init, dim3(gP2), dim3(256), 0, s, sendcounts, cur, P, pr.Q, pr.N);
     if (hipGetLastError() != hipSuccess) return fail(TUNA_ERR_HIP);
+    rc = launch_transpose_displs(pr, s);
+    if (rc != TUNA_OK) return fail(rc);
     for (size_t i = 0; i < nph; ++i) {
         rc = launch_phase_metadata(pr, i, cur, nxt, plan->Ls[i], plan->Lr[i], s);
         if (rc != TUNA_OK) return fail(rc);
@@ -793,7 +812,8 @@ int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node, i
     if (g.h_status->flags & 1u) return TUNA_ERR_NEGATIVE_COUNT;
     const DataSizes ds = data_sizes_for(pl, g.h_status->max_count, g.h_status->total_chunks, g.opt_fused != 0, staggered,
                                         exact_t, g.h_status->t_chunks);
-    *bytes = meta_bytes_for(P) + (exact_t ? exact_t_meta_bytes_for(pl, false) : 0) + ds.total;
+    *bytes = meta_bytes_for(P) + (exact_t ? exact_t_meta_bytes_for(pl, false) : 0) +
+             ((g.opt_fused || staggered) ? align_up((size_t)P * P * 8) : 0) + ds.total;
     return TUNA_OK;
 }
 

@@ -256,6 +256,26 @@ __global__ void __launch_bounds__(256) k_t_chunks(const int32_t* __restrict__ se
 }
 
 // ------------------------------------------------------------------------------------------
+// k_transpose_displs: out[j][i] = in[i][j] through a 32 x 32 LDS tile, block (32, 8).  A one-kernel
+// phase is tiled over the receiver but reads from the sender's S: with sdispls transposed the
+// displacements of the blocks a rank receives are consecutive instead of a column of the matrix.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_transpose_displs(const int64_t* __restrict__ in, int64_t* __restrict__ out, int P) {
+    __shared__ int64_t tile[32][33];
+    const int tx = threadIdx.x, ty = threadIdx.y;
+    const int bi = blockIdx.y * 32, bj = blockIdx.x * 32;
+    for (int a = ty; a < 32; a += 8) {
+        const int i = bi + a, j = bj + tx;
+        if (i < P && j < P) tile[a][tx] = in[(size_t)i * P + j];
+    }
+    __syncthreads();
+    for (int a = ty; a < 32; a += 8) {
+        const int j = bj + a, i = bi + tx;
+        if (i < P && j < P) out[(size_t)j * P + i] = tile[tx][a];
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // k_rotate_init: the index-only initial rotation (Algorithm "TuNA", lines 4-5; Algorithm
 // "Coalesced TuNA_l^g", line 5).  No payload moves: cur[p][j*Q + l] becomes the size of the
 // block rank p = (n, g) holds at distance (j, l), i.e. its block for rank ((n-j)%N, (g-l)%Q).
@@ -556,7 +576,7 @@ struct CopyArgs {
     // other side: caller buffer + T (pack, unpack, fused source)
     const int32_t* counts;              // recvcounts: exact sizes of the blocks that are final (unpack, fused)
     unsigned char* user;                // S (pack) or R (unpack)
-    const int64_t* displs;              // sdispls (pack) or rdispls (unpack)
+    const int64_t* displs;              // sdispls (pack), rdispls (unpack), transposed sdispls (fused source)
     unsigned long long user_limit;      // pack: address one past the last byte of S that holds a block
     unsigned char* T;                   // temporary buffer: slot s of rank p at ((p*slots + s) * slot_bytes)
     long long slots;
@@ -617,7 +637,8 @@ __device__ __forceinline__ unsigned long long block_address(int slot, bool far_i
                                                             int j, int l, int P, int Q, int N,
                                                             unsigned char* user, const int64_t* displs,
                                                             unsigned char* T, long long slots, long long slot_bytes,
-                                                            const int32_t* counts = nullptr, int* count = nullptr) {
+                                                            const int32_t* counts = nullptr, int* count = nullptr,
+                                                            bool displs_transposed = false) {
     if (slot >= 0) return (unsigned long long)(T + ((long long)p * slots + slot) * slot_bytes);
     int pn, pg;
     if (!far_is_source) {
@@ -629,6 +650,7 @@ __device__ __forceinline__ unsigned long long block_address(int slot, bool far_i
     }
     const size_t idx = (size_t)p * P + pn * Q + pg;
     if (counts) *count = counts[idx];          // the caller's count for the same pair (exact size into R)
+    if (displs_transposed) return (unsigned long long)(user + displs[(size_t)(pn * Q + pg) * P + p]);
     return (unsigned long long)(user + displs[idx]);
 }
 
@@ -742,7 +764,7 @@ k_copy(const CopyArgs a) {
                         addr = exact_t_src(a.T, a.x, a.P, sph, sn * a.Q + sg, se);
                     else
                         addr = block_address(ssrc, false, sn * a.Q + sg, sn, sg, bj, bl, a.P, a.Q, a.N, a.user,
-                                             a.displs, a.T, a.slots, a.slot_bytes);
+                                             a.displs, a.T, a.slots, a.slot_bytes, nullptr, nullptr, true);
                     if (ssrc >= 0) flag |= kFlagSrcT;
                     if (DENSE && sdst >= 0)
                         addr2 = exact_t_dst(a.T2, a.x, a.P, p, s);
