@@ -303,6 +303,9 @@ def main():
     cpu_baseline = None
     if not args.no_cpu_baseline:
         cpu_baseline = time_oracle(lay, send, args.cpu_seconds)
+        # context, not a target: the GPU call at its best radix against the oracle's plain transpose
+        cpu_baseline["gpu_over_cpu"] = {"one_core": best["effective_GBs"] / cpu_baseline["value"],
+                                        "all_cores": best["effective_GBs"] / cpu_baseline["all_cores"]["value"]}
 
     also = None
     if args.secondary and not args.no_secondary:
@@ -448,7 +451,16 @@ def time_oracle(lay, send_dev, target_seconds):
     for t in threads:
         t.join()
     dt_par = time.perf_counter() - t1
-    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle", "cpu_model": model,
             "sample": "receive side of the first %d of %d ranks (%.3f GiB of payload), one thread, %.2f s per pass, "
                       "mean of %d passes; host has %d usable cores" % (n, P, nbytes / 2**30, dt, reps, cores),
             "all_cores": {"value": nbytes / dt_par / 1e9, "unit": "GB/s", "threads": len(threads),
