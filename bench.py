@@ -53,6 +53,8 @@ def parse_args():
     ap.add_argument("--fused", type=int, default=0, help="1: fused single-kernel rounds")
     ap.add_argument("--exact-t", type=int, default=1,
                     help="main sweep: 1 = T in exact size (the library's default), 0 = the paper's B slots of M bytes")
+    ap.add_argument("--block-count", type=int, default=0,
+                    help="TUNA_OPT_BLOCK_COUNT: rounds per batch of launches (0: all rounds of a phase at once)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fused-table", action="store_true", help="skip the second sweep with fused rounds")
     ap.add_argument("--secondary", action="store_true",
@@ -111,6 +113,8 @@ def main():
     d_rd = torch.from_numpy(lay.rdispls).to(dev)
     torch.cuda.synchronize()
 
+    if args.block_count:
+        tuna.tuna_set_option(tuna.TUNA_OPT_BLOCK_COUNT, args.block_count)
     sweep = sweep_of(args.config, P)
     if args.radices:
         rs = [int(x) for x in args.radices.split(",")]
@@ -322,7 +326,7 @@ def main():
         "config": {"workload": ("uniform [0, %d] bytes in FP64 elements, P=%d flat" % (args.uniform_max_bytes, P))
                                if args.uniform_max_bytes else "config %d: %s" % (args.config, cfg.description), "P": P,
                    "payload_bytes": Btot, "best_radix": best["radix"], "fused": bool(args.fused),
-                   "exact_size_t": bool(args.exact_t),
+                   "exact_size_t": bool(args.exact_t), "block_count": args.block_count,
                    "ranks_per_node": rpn},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "copy_ceiling": copy_ceiling, "per_radix": per_radix, "persistent": persistent,
         "also_measured": also,

@@ -201,11 +201,21 @@ int tuna_release(void);
  * stores into T in one phase can lie back to back (padded to 16 bytes) in an arena of that
  * phase: T then takes sum over blocks of ceil(size / 16) * 16 * (hops - 1) bytes, whatever M is
  * (a block makes one hop per non-zero digit of its rank distance and waits in T between hops).
+ * TUNA_OPT_BLOCK_COUNT: k > 0 = at most k rounds of a digit phase are moved per set of kernel
+ * launches, in ascending round order; 0 (default) = all rounds of a phase at once.  This is the
+ * block_count of Algorithms "Staggered TuNA_l^g" and "Coalesced TuNA_l^g" (the number of
+ * point-to-point rounds in flight between two waits; Section "Performance analysis of coalesced
+ * and staggered TuNA_l^g": 1 .. N - 1 for the coalesced schedule, 1 .. (N - 1) Q for the
+ * staggered one, where a round carries one block -- there k is rounded down to whole node
+ * distances of Q rounds each, at least one).  With the linear schedule r = P it gives the
+ * scattered algorithm of Section "Background".  On a network it bounds congestion; in one HBM
+ * it moves the same bytes with more launches.
  */
 #define TUNA_OPT_PROFILE 1
 #define TUNA_OPT_FUSED 2
 #define TUNA_OPT_STAGGERED 3
 #define TUNA_OPT_DENSE_T 4
+#define TUNA_OPT_BLOCK_COUNT 5
 int tuna_set_option(int option, int value);
 
 /* Statistics of the last tuna_alltoallv* call (host struct).  Synchronises with that call's

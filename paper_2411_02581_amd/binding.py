@@ -25,6 +25,7 @@ TUNA_OPT_PROFILE = 1
 TUNA_OPT_FUSED = 2
 TUNA_OPT_STAGGERED = 3
 TUNA_OPT_DENSE_T = 4
+TUNA_OPT_BLOCK_COUNT = 5
 TUNA_MAX_PHASES = 64
 
 EXPORTS = ("tuna_alltoallv", "tuna_alltoallv_hier", "tuna_workspace_bytes", "tuna_set_workspace",

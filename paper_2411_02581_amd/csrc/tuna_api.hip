@@ -49,7 +49,7 @@ struct Ctx {
     std::map<std::tuple<int, int, int, int, int>, DevicePlan> plans;
     tuna_stats_t stats;
     bool have_stats = false;
-    int opt_profile = 0, opt_fused = 0, opt_staggered = 0, opt_dense_t = 1;
+    int opt_profile = 0, opt_fused = 0, opt_staggered = 0, opt_dense_t = 1, opt_block_count = 0;
     std::vector<hipEvent_t> ev_pool;
     std::vector<Mark> marks;
     hipEvent_t ev_end = nullptr;
@@ -356,6 +356,7 @@ struct Prepared {
     std::vector<LayoutDev> Lt;
     ExactT x{};
     int64_t* sdispls_t = nullptr;       // one-kernel phases: transposed sdispls
+    int block_count = 0;                // rounds per batch of launches (0: all rounds of a phase at once)
 };
 
 void carve_exact_t(Carver& cv, const PlanHost& pl, bool keep_all_phases, Prepared& pr) {
@@ -427,6 +428,7 @@ int prepare_call(const void* sendbuf, const int32_t* sendcounts, const int64_t* 
     pr.sendbuf = sendbuf; pr.recvbuf = recvbuf; pr.sendcounts = sendcounts; pr.recvcounts = recvcounts;
     pr.sdispls = sdispls; pr.rdispls = rdispls;
     // ---- validation, M, totals (one read-back) -------------------------------------------------
+    pr.block_count = g.opt_block_count;
     pr.exact_kernels = g.opt_dense_t != 0;
     pr.exact_t = pr.exact_kernels && pr.dp->host.slots > 0;        // a schedule without T (r >= P - 1) has nothing to size
     rc = run_validate(sendcounts, recvcounts, sdispls, rdispls, P, s, pr.exact_t ? &pr.dp->host : nullptr);
@@ -498,33 +500,45 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
     a.P = pr.P; a.Q = pr.Q; a.N = pr.N; a.dim = ph.dim; a.rx = (int)ph.rx;
     a.user_limit = pr.user_limit;
     a.x = exact_t_of(pr, i);
-    int rc;
-    if (phase_is_one_kernel(pr, ph)) {
-        // one hop in one kernel: S / T of the sender -> R / the other copy of T at the receiver
-        a.stage = nullptr; a.L = Lr; a.counts = pr.recvcounts;
-        a.user = (unsigned char*)pr.sendbuf; a.displs = pr.sdispls_t;
-        a.user2 = (unsigned char*)pr.recvbuf; a.displs2 = pr.rdispls; a.T2 = pr.T;
-        rc = launch_copy<kFused>(pr.gran, unit_cap, a, s, pr.exact_kernels);
+    // batches of rounds (Algorithm "Coalesced TuNA_l^g": block_count rounds are in flight at a time): the
+    // rounds z0 .. z1-1 of a phase are the segments [below(z0), below(z1)) of every rank's message order
+    const PhaseScalars ps = phase_scalars(ph);
+    const long long mult = ph.dim == 0 ? pr.N : pr.Q;
+    int per_batch = pr.block_count;                  // the staggered schedule counts single-block rounds: Q per node distance
+    if (per_batch > 0 && pr.staggered && ph.dim == 1) per_batch = std::max(1, per_batch / pr.Q);
+    const int step = (per_batch > 0 && per_batch < ph.nz) ? per_batch : ph.nz;
+    for (int z0 = 1; z0 <= ph.nz; z0 += step) {
+        const int z1 = std::min(z0 + step, ph.nz + 1);
+        a.seg_lo = (int)(count_below_digit(ps, z0) * mult);
+        a.seg_hi = (int)(count_below_digit(ps, z1) * mult);
+        int rc;
+        if (phase_is_one_kernel(pr, ph)) {
+            // one hop in one kernel: S / T of the sender -> R / the other copy of T at the receiver
+            a.stage = nullptr; a.L = Lr; a.counts = pr.recvcounts;
+            a.user = (unsigned char*)pr.sendbuf; a.displs = pr.sdispls_t;
+            a.user2 = (unsigned char*)pr.recvbuf; a.displs2 = pr.rdispls; a.T2 = pr.T;
+            rc = launch_copy<kFused>(pr.gran, unit_cap, a, s, pr.exact_kernels);
+            if (rc != TUNA_OK) return rc;
+            mark(s, kCatPack, (int)i);
+            continue;
+        }
+        // pack: S / T -> send staging
+        a.stage = pr.stage_s; a.L = Ls; a.counts = nullptr;
+        a.user = (unsigned char*)pr.sendbuf; a.displs = pr.sdispls;
+        rc = launch_copy<kPack>(pr.gran, unit_cap, a, s, pr.exact_kernels);
         if (rc != TUNA_OK) return rc;
         mark(s, kCatPack, (int)i);
-        return TUNA_OK;
+        // exchange: send staging of the partner -> receive staging
+        a.stage = pr.stage_r; a.L = Lr; a.stage_src = pr.stage_s; a.Ls = Ls;
+        rc = launch_copy<kExchange>(pr.gran, unit_cap, a, s, pr.exact_kernels);
+        if (rc != TUNA_OK) return rc;
+        mark(s, kCatExchange, (int)i);
+        // unpack: receive staging -> R / T
+        a.counts = pr.recvcounts; a.user = (unsigned char*)pr.recvbuf; a.displs = pr.rdispls;
+        rc = launch_copy<kUnpack>(pr.gran, unit_cap, a, s, pr.exact_kernels);
+        if (rc != TUNA_OK) return rc;
+        mark(s, kCatUnpack, (int)i);
     }
-    // pack: S / T -> send staging
-    a.stage = pr.stage_s; a.L = Ls;
-    a.user = (unsigned char*)pr.sendbuf; a.displs = pr.sdispls;
-    rc = launch_copy<kPack>(pr.gran, unit_cap, a, s, pr.exact_kernels);
-    if (rc != TUNA_OK) return rc;
-    mark(s, kCatPack, (int)i);
-    // exchange: send staging of the partner -> receive staging
-    a.stage = pr.stage_r; a.L = Lr; a.stage_src = pr.stage_s; a.Ls = Ls;
-    rc = launch_copy<kExchange>(pr.gran, unit_cap, a, s, pr.exact_kernels);
-    if (rc != TUNA_OK) return rc;
-    mark(s, kCatExchange, (int)i);
-    // unpack: receive staging -> R / T
-    a.counts = pr.recvcounts; a.user = (unsigned char*)pr.recvbuf; a.displs = pr.rdispls;
-    rc = launch_copy<kUnpack>(pr.gran, unit_cap, a, s, pr.exact_kernels);
-    if (rc != TUNA_OK) return rc;
-    mark(s, kCatUnpack, (int)i);
     return TUNA_OK;
 }
 
@@ -856,6 +870,7 @@ int tuna_set_option(int option, int value) {
     if (option == TUNA_OPT_FUSED) { g.opt_fused = value ? 1 : 0; return TUNA_OK; }
     if (option == TUNA_OPT_STAGGERED) { g.opt_staggered = value ? 1 : 0; return TUNA_OK; }
     if (option == TUNA_OPT_DENSE_T) { g.opt_dense_t = value ? 1 : 0; return TUNA_OK; }
+    if (option == TUNA_OPT_BLOCK_COUNT) { if (value < 0) return TUNA_ERR_ARG; g.opt_block_count = value; return TUNA_OK; }
     return TUNA_ERR_ARG;
 }
 

@@ -590,6 +590,8 @@ struct CopyArgs {
     unsigned char* T2;                  // the copy of T written in this phase
     // exact-size T (DENSE kernels): one arena per phase instead of slots
     ExactT x;
+    // a launch may cover only the rounds of one batch: the segments [seg_lo, seg_hi) of every rank
+    int seg_lo, seg_hi;
     int P, Q, N, dim, rx;
 };
 
@@ -693,12 +695,19 @@ k_copy(const CopyArgs a) {
     unsigned long long* waddr2 = s_addr2[MODE == kFused ? wv : 0];
     int* wflag = s_flag[wv];
 
+    // batch of rounds: the rank's chunks [blo, bhi) belong to this launch
+    int blo = 0, bhi = INT_MAX;
+    if (a.seg_hi - a.seg_lo < a.nseg) {
+        blo = prow[a.seg_lo];
+        bhi = prow[a.seg_hi];
+        if (c0 >= bhi || cend <= blo) return;
+    }
     int c[kChunksPerLane];
     bool pend[kChunksPerLane];
 #pragma unroll
     for (int k = 0; k < kChunksPerLane; ++k) {
         c[k] = c0 + k * kWave + lane;
-        pend[k] = c[k] < cend;
+        pend[k] = c[k] < cend && c[k] >= blo && c[k] < bhi;
     }
     for (;;) {
         // ---- window: segments sw .. sw+63, one per lane --------------------------------------

@@ -428,3 +428,27 @@ def test_temporary_buffer_too_large_is_an_error_not_a_crash(tuna, mode):
     assert torch.equal(recv[ro:ro + n], send[so:so + n])
     so, ro = int(lay.sdispls[5, 6]), int(lay.rdispls[6, 5])
     assert torch.equal(recv[ro:ro + 100], send[so:so + 100])
+
+
+@pytest.mark.parametrize("P,Q,rl,rg,cfg,k", [(64, 0, 64, 64, 2, 1), (64, 0, 64, 64, 2, 7), (100, 0, 10, 10, 4, 3),
+                                              (96, 8, 8, 12, 3, 2), (96, 8, 3, 12, 2, 100), (30, 0, 2, 2, 2, 1)])
+def test_block_count_batches_move_the_same_bytes(tuna, P, Q, rl, rg, cfg, k, mode):
+    """Rounds moved in batches of k (block_count; with r = P the scattered linear algorithm): the
+    result is the same as with all rounds of a phase at once."""
+    lay = wl.make_layout(wl.make_counts(cfg, P), gap=5 if cfg == 2 else 4)
+    prob = Problem(lay, wl.payload_position_hash(500 + k, lay.send_bytes))
+    assert tuna.tuna_set_option(tuna.TUNA_OPT_BLOCK_COUNT, k) == 0
+    try:
+        prob.reset()
+        print("block_count=%d P=%d Q=%d rl=%d rg=%d %s" % (k, P, Q, rl, rg, mode), flush=True)
+        assert tuna.tuna_alltoallv_hier(*prob.args(), Q, rl, rg) == 0
+        prob.check("block_count %d" % k)
+        if Q:
+            tuna.tuna_set_option(tuna.TUNA_OPT_STAGGERED, 1)
+            prob.reset()
+            assert tuna.tuna_alltoallv_hier(*prob.args(), Q, rl, rg) == 0
+            prob.check("staggered, block_count %d" % k)
+    finally:
+        tuna.tuna_set_option(tuna.TUNA_OPT_STAGGERED, 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_BLOCK_COUNT, 0)
+    assert tuna.tuna_set_option(tuna.TUNA_OPT_BLOCK_COUNT, -1) == tuna.TUNA_ERR_ARG
