@@ -210,3 +210,36 @@ def test_many_ranks_small_blocks(tuna):
         assert torch.equal(recv, want_dev), (radix, rpn)
     st = tuna.tuna_get_stats()
     assert (st.Q, st.N, st.w_local, st.w_global) == (64, 128, 2, 3)
+
+
+def test_sixteen_thousand_ranks(tuna):
+    """P = 16384 (268 million blocks of 0..28 bytes): table rows, T positions and prefix rows are
+    indexed beyond 2^32 entries.  Flat radix 2 (14 digit phases, T in exact size) and radix 128 with
+    one-kernel phases; whole result against the oracle."""
+    P = 16384
+    print("P=16384: counts", flush=True)
+    counts = wl.counts_uniform_elements(P, 16384, 7, 4)
+    print("P=16384: layout", flush=True)
+    lay = wl.make_layout(counts)
+    send_host = wl.payload_position_hash(16384, lay.send_bytes)
+    want = np.zeros(lay.recv_bytes, dtype=np.uint8)
+    print("P=16384: oracle", flush=True)
+    assert oracle.alltoallv(send_host, lay.sendcounts, lay.sdispls, want, lay.recvcounts, lay.rdispls) == 0
+    want_dev = torch.from_numpy(want).to("cuda:0")
+    del want
+    send = torch.from_numpy(send_host).to("cuda:0")
+    sc, sd, rc, rd = _upload(lay)
+    recv = torch.empty(lay.recv_bytes, dtype=torch.uint8, device="cuda:0")
+    assert tuna.tuna_release() == 0
+    for radix, fused in ((2, 0), (128, 1)):
+        recv.zero_()
+        print("P=16384 radix=%d fused=%d" % (radix, fused), flush=True)
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, fused)
+        code = tuna.tuna_alltoallv(send, sc, sd, recv, rc, rd, P, radix, 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+        assert code == 0, tuna.tuna_strerror(code)
+        torch.cuda.synchronize()
+        assert torch.equal(recv, want_dev), (radix, fused)
+    st = tuna.tuna_get_stats()
+    assert (st.P, st.w_local, st.dense_t) == (P, 2, 1)
+    assert tuna.tuna_release() == 0
