@@ -31,6 +31,7 @@ struct DevicePlan {
     hipStream_t built_on = nullptr;      // stream the table kernels were enqueued on
     bool complete = false;               // known to have finished (a later call synchronised)
     std::vector<int32_t*> d_zt;
+    int32_t* d_hm1 = nullptr;            // [P]: hops - 1 of every slot index (how often the block is stored into T)
 };
 
 enum Category { kCatPrepare = 0, kCatSelf, kCatMeta, kCatPack, kCatExchange, kCatUnpack };
@@ -218,6 +219,9 @@ int get_plan(int P, int Q, int rl, int rg, bool fused, hipStream_t s, DevicePlan
             dp.d_seg_mem.push_back(dm);
             dp.d_zt.push_back(dz);
         }
+        HIPCHK(hipMalloc((void**)&dp.d_hm1, align_up((size_t)P * 4)));
+        hipLaunchKernelGGL(k_build_hops, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, dp.host.sc, dp.d_hm1);
+        HIPCHK(hipGetLastError());
         dp.built_on = s;
         it = g.plans.emplace(key, std::move(dp)).first;
     }
@@ -294,7 +298,9 @@ int phase_metadata(const PhaseLayoutArgs& a, hipStream_t s, const ExactT& x) {
     hipLaunchKernelGGL(k_layout_base, dim3(nl), dim3(kScanThreads), 0, s, a.P, *list[0], *list[1], *list[2],
                        a.phase_chunks, a.want_send ? 1 : 0, tbound_at, x);
     HIPCHK(hipGetLastError());
-    hipLaunchKernelGGL(k_layout_units, dim3(a.P, a.want_send ? 2 : 1), dim3(256), 0, s, a.nseg, a.Lr, a.Ls);
+    const int lds_ints = a.nseg + 1 <= kUnitsLdsMaxInts ? a.nseg + 1 : 0;
+    hipLaunchKernelGGL(k_layout_units, dim3(a.P, a.want_send ? 2 : 1), dim3(256), (size_t)lds_ints * 4, s, a.nseg, a.Lr,
+                       a.Ls, lds_ints);
     HIPCHK(hipGetLastError());
     return TUNA_OK;
 }
@@ -310,22 +316,16 @@ int resolve_hierarchy(int P, int ranks_per_node, int* Q) {
 
 // Validation + sizing pass shared by tuna_alltoallv* and tuna_workspace_bytes: fills *g.h_status.
 int run_validate(const int32_t* sendcounts, const int32_t* recvcounts, const int64_t* sdispls,
-                 const int64_t* rdispls, int P, hipStream_t s, const PlanHost* exact_t_for = nullptr) {
+                 const int64_t* rdispls, int P, hipStream_t s, const DevicePlan* exact_t_for = nullptr) {
     const int nwords = (int)(sizeof(Status) / 4);
     hipLaunchKernelGGL(k_clear, dim3((nwords + 255) / 256), dim3(256), 0, s, (unsigned int*)g.d_status, nwords);
     HIPCHK(hipGetLastError());
-    const size_t t = (size_t)((P + 31) / 32);
+    const size_t t = (size_t)((P + kValTile - 1) / kValTile);
     const unsigned vgrid = (unsigned)(t * t < (size_t)g.num_cus * 8 ? t * t : (size_t)g.num_cus * 8);
-    hipLaunchKernelGGL(k_validate, dim3(vgrid), dim3(32, 8), 0, s, sendcounts, recvcounts, sdispls, rdispls, P,
-                       g.d_status);
+    hipLaunchKernelGGL(k_validate, dim3(vgrid), dim3(kValTile, 4), 0, s, sendcounts, recvcounts, sdispls, rdispls, P,
+                       g.d_status, exact_t_for ? exact_t_for->d_hm1 : nullptr, exact_t_for ? exact_t_for->host.Q : 1,
+                       exact_t_for ? exact_t_for->host.N : 1);
     HIPCHK(hipGetLastError());
-    if (exact_t_for) {
-        const PlanHost& pl = *exact_t_for;
-        const size_t P2 = (size_t)P * P;
-        const unsigned tgrid = (unsigned)std::min<size_t>((P2 + 255) / 256, (size_t)g.num_cus * 8);
-        hipLaunchKernelGGL(k_t_chunks, dim3(tgrid), dim3(256), 0, s, sendcounts, P, pl.Q, pl.N, pl.rl, pl.rg, g.d_status);
-        HIPCHK(hipGetLastError());
-    }
     HIPCHK(hipMemcpyAsync(g.h_status, g.d_status, 64, hipMemcpyDeviceToHost, s));
     HIPCHK(hipStreamSynchronize(s));
     return TUNA_OK;
@@ -431,7 +431,7 @@ int prepare_call(const void* sendbuf, const int32_t* sendcounts, const int64_t* 
     pr.block_count = g.opt_block_count;
     pr.exact_kernels = g.opt_dense_t != 0;
     pr.exact_t = pr.exact_kernels && pr.dp->host.slots > 0;        // a schedule without T (r >= P - 1) has nothing to size
-    rc = run_validate(sendcounts, recvcounts, sdispls, rdispls, P, s, pr.exact_t ? &pr.dp->host : nullptr);
+    rc = run_validate(sendcounts, recvcounts, sdispls, rdispls, P, s, pr.exact_t ? pr.dp : nullptr);
     if (rc != TUNA_OK) return rc;
     hs = *g.h_status;
     if (pr.dp->built_on == s) pr.dp->complete = true;      // run_validate synchronised this stream
@@ -815,14 +815,16 @@ int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node, i
     if (rc != TUNA_OK) return rc;
     rc = ensure_ctx();
     if (rc != TUNA_OK) return rc;
-    // the schedule's scalars do not need the device tables
     const int N = P / Q;
     const bool staggered = g.opt_staggered != 0 && N > 1;
-    const PlanHost pl = make_plan(P, Q, local_radix, staggered ? N : global_radix, g.opt_fused != 0, /*with_tables=*/false);
-    if ((int)pl.phases.size() > TUNA_MAX_PHASES) return TUNA_ERR_TOO_LARGE;
-    const bool exact_t = g.opt_dense_t != 0 && pl.slots > 0;
-    rc = run_validate(sendcounts, nullptr, nullptr, nullptr, P, nullptr, exact_t ? &pl : nullptr);
+    DevicePlan* dp = nullptr;
+    rc = get_plan(P, Q, local_radix, staggered ? N : global_radix, g.opt_fused != 0, nullptr, &dp);
     if (rc != TUNA_OK) return rc;
+    const PlanHost& pl = dp->host;
+    const bool exact_t = g.opt_dense_t != 0 && pl.slots > 0;
+    rc = run_validate(sendcounts, nullptr, nullptr, nullptr, P, nullptr, exact_t ? dp : nullptr);
+    if (rc != TUNA_OK) return rc;
+    dp->complete = true;                                  // run_validate synchronised the stream the tables were built on
     if (g.h_status->flags & 1u) return TUNA_ERR_NEGATIVE_COUNT;
     const DataSizes ds = data_sizes_for(pl, g.h_status->max_count, g.h_status->total_chunks, g.opt_fused != 0, staggered,
                                         exact_t, g.h_status->t_chunks);
@@ -860,6 +862,7 @@ int tuna_release(void) {
     for (auto& kv : g.plans) {
         for (auto* p : kv.second.d_seg_mem) (void)hipFree(p);
         for (auto* p : kv.second.d_zt) (void)hipFree(p);
+        if (kv.second.d_hm1) (void)hipFree(kv.second.d_hm1);
     }
     g.plans.clear();
     return TUNA_OK;

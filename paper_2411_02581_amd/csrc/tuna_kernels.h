@@ -39,7 +39,7 @@ struct Status {
     unsigned long long total_bytes;    // sum of sendcounts
     unsigned long long total_chunks;   // sum of ceil(count / 16)
     unsigned long long send_extent;    // max over non-empty blocks of sdispls + count: bytes of sendbuf that hold blocks
-    unsigned long long t_chunks;       // exact-size T: chunks stored into T over all phases (k_t_chunks)
+    unsigned long long t_chunks;       // exact-size T: chunks stored into T over all phases
     unsigned long long phase_bytes[64];   // payload bytes moved per phase
     unsigned long long phase_chunks[64];  // staged chunks per phase
 };
@@ -146,29 +146,49 @@ __global__ void __launch_bounds__(256) k_plain_copy(const v4u* __restrict__ src,
 }
 
 // ------------------------------------------------------------------------------------------
-// k_validate: one pass over the P x P matrices in 32 x 32 tiles.  Finds M (Algorithm "TuNA",
+// k_build_hops: hm1[e] = (hops of the block with slot index e) - 1, at least 0.  A block makes one
+// hop per non-zero digit of its distance pair (l in base r_l, j in base r_g) and is stored into T
+// after every hop but its last -- hm1[e] times.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_build_hops(const PlanScalars pl, int32_t* __restrict__ hm1) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= pl.P) return;
+    int j = e / pl.Q, l = e - j * pl.Q, hops = 0;
+    for (; l; l /= pl.rl) hops += (l % pl.rl) != 0;
+    for (; j; j /= pl.rg) hops += (j % pl.rg) != 0;
+    hm1[e] = hops > 1 ? hops - 1 : 0;
+}
+
+// ------------------------------------------------------------------------------------------
+// k_validate: one pass over the P x P matrices in 64 x 64 tiles.  Finds M (Algorithm "TuNA",
 // line 1: the maximum block size over all ranks, here one device reduction instead of an
 // allreduce), the totals the workspace is sized from, checks counts >= 0 and
-// recvcounts == transpose(sendcounts) through an LDS tile so both matrices are read row-wise.
-// Workgroups of (32, 8) threads stride over the tiles and issue one set of atomics each.
+// recvcounts == transpose(sendcounts) through an LDS tile so both matrices are read row-wise
+// (a wave reads 64 consecutive entries of one row).  With `hm1` it also sums the exact size of T:
+// ceil(count / 16) * hm1[slot index of the block] chunks over all blocks.
+// Workgroups of (64, 4) threads stride over the tiles and issue one set of atomics each.
 // ------------------------------------------------------------------------------------------
+constexpr int kValTile = 64;
 __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ sendcounts,
                                                   const int32_t* __restrict__ recvcounts,
                                                   const int64_t* __restrict__ sdispls,
                                                   const int64_t* __restrict__ rdispls,
-                                                  int P, Status* __restrict__ st) {
-    __shared__ int tile[32][33];
-    __shared__ unsigned long long red[4][5];
+                                                  int P, Status* __restrict__ st,
+                                                  const int32_t* __restrict__ hm1, int Q, int N) {
+    __shared__ int tile[kValTile][kValTile + 1];
+    __shared__ unsigned long long red[4][6];
     const int tx = threadIdx.x, ty = threadIdx.y;
-    const int tpr = (P + 31) / 32;                       // tiles per row
+    const int tpr = (P + kValTile - 1) / kValTile;       // tiles per row
     const int ntile = tpr * tpr;
     unsigned int flags = 0, abits = 0;
     int mx = 0;
-    unsigned long long bytes = 0, chunks = 0, extent = 0;
+    unsigned long long bytes = 0, chunks = 0, extent = 0, tchunks = 0;
     for (int t = blockIdx.x; t < ntile; t += gridDim.x) {        // a workgroup strides over tiles
-        const int bi = (t / tpr) * 32, bj = (t % tpr) * 32;
-        for (int a = ty; a < 32; a += 8) {
-            const int i = bi + a, j = bj + tx;
+        const int bi = (t / tpr) * kValTile, bj = (t % tpr) * kValTile;
+        const int j = bj + tx;
+        const int jn = hm1 ? j / Q : 0, jg = hm1 ? j - jn * Q : 0;   // the destination's node and local id
+        for (int a = ty; a < kValTile; a += 4) {
+            const int i = bi + a;
             int c = 0;
             if (i < P && j < P) {
                 c = sendcounts[(size_t)i * P + j];
@@ -181,19 +201,26 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
                 }
                 mx = max(mx, c);
                 bytes += (unsigned long long)c;
-                chunks += (unsigned long long)((c + 15) >> 4);
+                const unsigned long long ch = (unsigned long long)((c + 15) >> 4);
+                chunks += ch;
+                if (hm1 && c > 0) {
+                    const int in = i / Q, ig = i - in * Q;
+                    int dn = in - jn; if (dn < 0) dn += N;
+                    int dg = ig - jg; if (dg < 0) dg += Q;
+                    tchunks += ch * (unsigned long long)hm1[dn * Q + dg];
+                }
             }
             tile[a][tx] = c;
         }
         __syncthreads();
         if (recvcounts) {
-            for (int a = ty; a < 32; a += 8) {
-                const int j = bj + a, i = bi + tx;      // recvcounts[j][i] must equal sendcounts[i][j]
-                if (i < P && j < P) {
-                    int rc = recvcounts[(size_t)j * P + i];
+            for (int a = ty; a < kValTile; a += 4) {
+                const int jr = bj + a, i = bi + tx;     // recvcounts[jr][i] must equal sendcounts[i][jr]
+                if (i < P && jr < P) {
+                    int rc = recvcounts[(size_t)jr * P + i];
                     if (rc < 0) flags |= 1u;
                     else if (rc != tile[tx][a]) flags |= 2u;
-                    if (rdispls) abits |= (unsigned int)rdispls[(size_t)j * P + i] & 15u;
+                    if (rdispls) abits |= (unsigned int)rdispls[(size_t)jr * P + i] & 15u;
                 }
             }
         }
@@ -207,19 +234,20 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
         mx = max(mx, __shfl_xor(mx, d, kWave));
         bytes += __shfl_xor(bytes, d, kWave);
         chunks += __shfl_xor(chunks, d, kWave);
+        tchunks += __shfl_xor(tchunks, d, kWave);
         extent = max(extent, (unsigned long long)__shfl_xor(extent, d, kWave));
     }
-    const int lin = ty * 32 + tx;
-    if ((lin & (kWave - 1)) == 0) {
-        unsigned long long* r = red[lin / kWave];
+    if (tx == 0) {                                       // one wave per value of ty
+        unsigned long long* r = red[ty];
         r[0] = ((unsigned long long)flags << 32) | (abits & 15u);
-        r[1] = (unsigned long long)mx; r[2] = bytes; r[3] = chunks; r[4] = extent;
+        r[1] = (unsigned long long)mx; r[2] = bytes; r[3] = chunks; r[4] = extent; r[5] = tchunks;
     }
     __syncthreads();
-    if (lin == 0) {
-        unsigned long long fa = 0, m = 0, by = 0, ch = 0, ex = 0;
+    if (tx == 0 && ty == 0) {
+        unsigned long long fa = 0, m = 0, by = 0, ch = 0, ex = 0, tc = 0;
         for (int w = 0; w < 4; ++w) {
             fa |= red[w][0]; m = max(m, red[w][1]); by += red[w][2]; ch += red[w][3]; ex = max(ex, red[w][4]);
+            tc += red[w][5];
         }
         if (fa >> 32) atomicOr(&st->flags, (unsigned int)(fa >> 32));
         if (fa & 15u) atomicOr(&st->align_bits, (unsigned int)(fa & 15u));
@@ -227,32 +255,8 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
         if (by) atomicAdd(&st->total_bytes, by);
         if (ch) atomicAdd(&st->total_chunks, ch);
         if (ex) atomicMax(&st->send_extent, ex);
+        if (tc) atomicAdd(&st->t_chunks, tc);
     }
-}
-
-// ------------------------------------------------------------------------------------------
-// k_t_chunks: the exact size of T.  A block is stored into T after every hop but its last, and it
-// makes one hop per non-zero digit of its distance pair (l in base r_l, j in base r_g), so T takes
-// sum over blocks of ceil(count / 16) * (hops - 1) chunks over all phases.
-// ------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) k_t_chunks(const int32_t* __restrict__ sendcounts, int P, int Q, int N,
-                                                  int rl, int rg, Status* __restrict__ st) {
-    unsigned long long acc = 0;
-    const size_t total = (size_t)P * P;
-    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
-        const int c = sendcounts[idx];
-        if (c <= 0) continue;
-        const int i = (int)(idx / P), d = (int)(idx - (size_t)i * P);
-        int l = i % Q - d % Q; if (l < 0) l += Q;
-        int j = i / Q - d / Q; if (j < 0) j += N;
-        int hops = 0;
-        for (; l; l /= rl) hops += (l % rl) != 0;
-        for (; j; j /= rg) hops += (j % rg) != 0;
-        if (hops > 1) acc += (unsigned long long)((c + 15) >> 4) * (unsigned long long)(hops - 1);
-    }
-#pragma unroll
-    for (int dlt = kWave / 2; dlt > 0; dlt >>= 1) acc += __shfl_xor(acc, dlt, kWave);
-    if ((threadIdx.x & (kWave - 1)) == 0 && acc) atomicAdd(&st->t_chunks, acc);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -529,14 +533,24 @@ __global__ void __launch_bounds__(kScanThreads) k_layout_base(int P, LayoutDev L
 // ------------------------------------------------------------------------------------------
 // k_layout_units: cut every rank's staged chunks into wave units of kUnitChunks and record, per
 // unit, the rank and the first segment that overlaps it (binary search in the rank's prefix
-// row).  grid (P, layouts): one workgroup per rank and layout (y = 0 receive side, 1 send side).
+// row, which is staged in LDS when it fits: lds_ints = nseg + 1, else 0 and the search reads
+// global memory).  grid (P, layouts): one workgroup per rank and layout (y = 0 receive side,
+// 1 send side).
 // ------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) k_layout_units(int nseg, LayoutDev Lr, LayoutDev Ls) {
+constexpr int kUnitsLdsMaxInts = 12288;     // 48 KiB of the workgroup's LDS
+__global__ void __launch_bounds__(256) k_layout_units(int nseg, LayoutDev Lr, LayoutDev Ls, int lds_ints) {
+    extern __shared__ int s_row[];
     const LayoutDev& L = blockIdx.y == 0 ? Lr : Ls;
     const int p = blockIdx.x;
     const int tot = L.tot[p];
     const int nu = (tot + kUnitChunks - 1) / kUnitChunks;
+    if (nu == 0) return;                       // uniform over the workgroup
     const int* pre = L.pre + (size_t)p * L.ld;
+    if (lds_ints) {
+        for (int i = threadIdx.x; i < lds_ints; i += blockDim.x) s_row[i] = pre[i];
+        __syncthreads();
+        pre = s_row;
+    }
     const int ub = L.unit_base[p];
     for (int t = threadIdx.x; t < nu; t += blockDim.x) {
         const int c0 = t * kUnitChunks;

@@ -266,3 +266,32 @@ def test_device_source_tables_match_the_host(tuna):
             assert rc == 0
             rc, dev = tuna.tuna_plan_phase_sources(P, Q, rl, rg, ph, nseg, on_device=True)
             assert rc == 0 and np.array_equal(host, dev)
+
+
+@pytest.mark.parametrize("P,Q,rl,rg", [(96, 8, 3, 4), (120, 5, 2, 5), (64, 0, 4, 4)])
+def test_exact_size_t_bytes_hierarchical(tuna, P, Q, rl, rg):
+    """The bytes of T the library reports are sum over blocks of 16 ceil(size / 16) (hops - 1) plus 256
+    per phase, hops = non-zero digits of the block's local distance in base r_l and of its node
+    distance in base r_g (counted here with the model's digit function)."""
+    from oracle import tuna_model as tm
+    counts = wl.make_counts(2, P)
+    lay = wl.make_layout(counts)
+    res = Resident(lay)
+    code, plan = _dense_plan(tuna, res, P, Q, rl, rg)
+    assert code == 0
+    try:
+        want = res.load(9)
+        res.recv.fill_(CANARY)
+        assert tuna.tuna_start(plan) == 0
+        res.check(want, "exact-size T, hierarchical")
+        st = tuna.tuna_get_stats()
+    finally:
+        assert tuna.tuna_plan_free(plan) == 0
+    Qe = Q if Q else P
+    N = P // Qe
+    total = 0
+    for i in range(P):
+        for d in range(P):
+            hops = tm.nonzero_digits((i % Qe - d % Qe) % Qe, rl) + tm.nonzero_digits((i // Qe - d // Qe) % N, rg)
+            total += (int(counts[i, d]) + 15) // 16 * 16 * max(hops - 1, 0)
+    assert st.temp_bytes == total + 256 * st.n_phases
