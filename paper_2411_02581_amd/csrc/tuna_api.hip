@@ -44,6 +44,7 @@ struct Ctx {
     int num_cus = 256;
     Status* d_status = nullptr;       // device status block (one-time small allocation)
     Status* h_status = nullptr;       // pinned host mirror
+    unsigned long long* d_vpart = nullptr;   // partial results of the validation pass, one row per workgroup
     void* meta = nullptr;  size_t meta_bytes = 0;   // library-owned, grow-only
     void* data = nullptr;  size_t data_bytes = 0;
     void* user_ws = nullptr; size_t user_ws_bytes = 0;
@@ -81,6 +82,7 @@ int ensure_ctx() {
     g.num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     HIPCHK(hipMalloc((void**)&g.d_status, align_up(sizeof(Status))));
     HIPCHK(hipHostMalloc((void**)&g.h_status, sizeof(Status), hipHostMallocDefault));
+    HIPCHK(hipMalloc((void**)&g.d_vpart, align_up((size_t)g.num_cus * 8 * kValPartial * 8)));
     HIPCHK(hipEventCreate(&g.ev_end));
     std::memset(&g.stats, 0, sizeof(g.stats));
     g.ready = true;
@@ -103,6 +105,7 @@ struct Carver {
 struct MetaBuffers {
     int32_t *cur, *nxt;
     LayoutDev Ls, Lr;
+    unsigned long long* rank_bytes;
 };
 
 size_t meta_bytes_for(int P) {
@@ -110,6 +113,7 @@ size_t meta_bytes_for(int P) {
     size_t b = 0;
     b += 2 * align_up(P2 * 4);
     b += 2 * (align_up(P * ld * 4) + align_up(P * 4) + align_up((P + 1) * 8) + align_up((P + 1) * 4) + align_up(4));
+    b += align_up((size_t)P * 8);          // payload bytes per rank of the phase being laid out
     return b;
 }
 
@@ -129,6 +133,7 @@ MetaBuffers carve_meta(Carver& cv, int P) {
     m.nxt = cv.take<int32_t>((size_t)P * P);
     carve_layout(cv, P, m.Ls);
     carve_layout(cv, P, m.Lr);
+    m.rank_bytes = cv.take<unsigned long long>(P);
     return m;
 }
 
@@ -286,7 +291,11 @@ int launch_copy(int gran, size_t unit_cap, const CopyArgs& a, hipStream_t s, boo
 }
 
 // Metadata of one digit phase: sizes exchanged, both staging layouts scanned, wave units cut.
-int phase_metadata(const PhaseLayoutArgs& a, hipStream_t s, const ExactT& x) {
+int phase_metadata(const PhaseLayoutArgs& a, int32_t* nxt, hipStream_t s, const ExactT& x) {
+    hipLaunchKernelGGL(k_size_exchange, dim3((unsigned)((a.P + 255) / 256), (unsigned)((a.P + kExchangeRanks - 1) / kExchangeRanks)),
+                       dim3(256), 0, s, a.cur, nxt,
+                       a.zt, a.P, a.Q, a.N, a.dim, a.rx);
+    HIPCHK(hipGetLastError());
     hipLaunchKernelGGL(k_phase_layout, dim3(a.P), dim3(kScanThreads), 0, s, a);
     HIPCHK(hipGetLastError());
     // layouts to scan: receive side, then the send side and / or the T-bound blocks where wanted
@@ -296,7 +305,7 @@ int phase_metadata(const PhaseLayoutArgs& a, hipStream_t s, const ExactT& x) {
     const int tbound_at = a.want_tbound ? nl : -1;
     if (a.want_tbound) list[nl++] = &a.Lt;
     hipLaunchKernelGGL(k_layout_base, dim3(nl), dim3(kScanThreads), 0, s, a.P, *list[0], *list[1], *list[2],
-                       a.phase_chunks, a.want_send ? 1 : 0, tbound_at, x);
+                       a.phase_chunks, a.want_send ? 1 : 0, tbound_at, x, a.rank_bytes, a.phase_bytes);
     HIPCHK(hipGetLastError());
     const int lds_ints = a.nseg + 1 <= kUnitsLdsMaxInts ? a.nseg + 1 : 0;
     hipLaunchKernelGGL(k_layout_units, dim3(a.P, a.want_send ? 2 : 1), dim3(256), (size_t)lds_ints * 4, s, a.nseg, a.Lr,
@@ -323,8 +332,10 @@ int run_validate(const int32_t* sendcounts, const int32_t* recvcounts, const int
     const size_t t = (size_t)((P + kValTile - 1) / kValTile);
     const unsigned vgrid = (unsigned)(t * t < (size_t)g.num_cus * 8 ? t * t : (size_t)g.num_cus * 8);
     hipLaunchKernelGGL(k_validate, dim3(vgrid), dim3(kValTile, 4), 0, s, sendcounts, recvcounts, sdispls, rdispls, P,
-                       g.d_status, exact_t_for ? exact_t_for->d_hm1 : nullptr, exact_t_for ? exact_t_for->host.Q : 1,
+                       g.d_vpart, exact_t_for ? exact_t_for->d_hm1 : nullptr, exact_t_for ? exact_t_for->host.Q : 1,
                        exact_t_for ? exact_t_for->host.N : 1);
+    HIPCHK(hipGetLastError());
+    hipLaunchKernelGGL(k_validate_finish, dim3(1), dim3(256), 0, s, g.d_vpart, (int)vgrid, g.d_status);
     HIPCHK(hipGetLastError());
     HIPCHK(hipMemcpyAsync(g.h_status, g.d_status, 64, hipMemcpyDeviceToHost, s));
     HIPCHK(hipStreamSynchronize(s));
@@ -357,6 +368,7 @@ struct Prepared {
     ExactT x{};
     int64_t* sdispls_t = nullptr;       // one-kernel phases: transposed sdispls
     int block_count = 0;                // rounds per batch of launches (0: all rounds of a phase at once)
+    unsigned long long* rank_bytes = nullptr;   // [P] scratch of the metadata kernels
 };
 
 void carve_exact_t(Carver& cv, const PlanHost& pl, bool keep_all_phases, Prepared& pr) {
@@ -465,10 +477,11 @@ int launch_phase_metadata(const Prepared& pr, size_t i, const int32_t* cur, int3
     m.P = pr.P; m.Q = pr.Q; m.N = pr.N; m.dim = ph.dim; m.rx = (int)ph.rx;
     m.Ls = Ls; m.Lr = Lr; m.want_send = one_kernel ? 0 : 1;
     if (pr.exact_t) { m.Lt = pr.Lt[i]; m.want_tbound = 1; m.tpos = pr.x.tpos + i * (size_t)pr.P * pr.P; }
+    m.rank_bytes = pr.rank_bytes;
     m.phase_bytes = &g.d_status->phase_bytes[i]; m.phase_chunks = &g.d_status->phase_chunks[i];
     m.head_displs = one_kernel ? pr.rdispls : nullptr;
     m.head_base = (unsigned int)((uintptr_t)pr.recvbuf & 15u);
-    return phase_metadata(m, s, exact_t_of(pr, i));
+    return phase_metadata(m, nxt, s, exact_t_of(pr, i));
 }
 
 bool any_one_kernel_phase(const Prepared& pr) { return pr.fused || pr.staggered; }
@@ -581,6 +594,7 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
     }
     Carver cm(mbase, mbytes);
     MetaBuffers mb = carve_meta(cm, P);
+    pr.rank_bytes = mb.rank_bytes;
     if (pr.exact_t) carve_exact_t(cm, pl, false, pr);
     if (any_one_kernel_phase(pr)) pr.sdispls_t = cm.take<int64_t>((size_t)P * P);
     Carver cd(dbase, ds.total);
@@ -664,7 +678,7 @@ int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* s
     const size_t nph = pl.phases.size();
     // metadata memory: two size matrices + per phase two complete layouts
     const size_t P2 = (size_t)P * P;
-    const size_t mbytes = 2 * align_up(P2 * 4) + nph * 2 * layout_bytes_for(P, pr.ds.unit_cap) +
+    const size_t mbytes = 2 * align_up(P2 * 4) + align_up((size_t)P * 8) + nph * 2 * layout_bytes_for(P, pr.ds.unit_cap) +
                           (pr.exact_t ? exact_t_meta_bytes_for(pl, true) : 0) +
                           (any_one_kernel_phase(pr) ? align_up(P2 * 8) : 0);
     hipError_t e = hipMalloc(&plan->mem_meta, mbytes ? mbytes : kAlign);
@@ -672,6 +686,7 @@ int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* s
     Carver cm(plan->mem_meta, mbytes);
     int32_t* cur = cm.take<int32_t>(P2);
     int32_t* nxt = cm.take<int32_t>(P2);
+    pr.rank_bytes = cm.take<unsigned long long>(P);
     plan->Ls.resize(nph); plan->Lr.resize(nph); plan->units.assign(nph, 0);
     for (size_t i = 0; i < nph; ++i) {
         carve_full_layout(cm, P, pr.ds.unit_cap, plan->Ls[i]);
@@ -1024,10 +1039,10 @@ int tuna_select_radix(int P, int ranks_per_node, int64_t payload_bytes, int* loc
     int rc = resolve_hierarchy(P, ranks_per_node, &Q);
     if (rc != TUNA_OK) return rc;
     const int N = P / Q;
-    // measured on MI355X at P = 4096: copy stages ~5.2e12 B/s, metadata kernels of
-    // a phase ~60 us + 20 ps per matrix entry, validation + rotation ~0.3 ms at P = 4096
-    const double bw = 5.2e12, c = g.opt_fused ? 2.0 : 6.0;
-    const double t_phase = 60e-6 + 2.0e-11 * (double)P * P, t_call = 50e-6 + 1.5e-11 * (double)P * P;
+    // measured on MI355X at P = 4096: copy stages ~5.5e12 B/s, metadata kernels of
+    // a phase ~40 us + 10 ps per matrix entry, validation + rotation ~0.25 ms at P = 4096
+    const double bw = 5.5e12, c = g.opt_fused ? 2.0 : 6.0;
+    const double t_phase = 40e-6 + 1.0e-11 * (double)P * P, t_call = 40e-6 + 1.3e-11 * (double)P * P;
     auto hops = [](int size, int r) {           // H(r) over one dimension
         long long nz = 0;
         for (int i = 0; i < size; ++i)

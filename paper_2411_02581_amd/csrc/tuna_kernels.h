@@ -169,11 +169,12 @@ __global__ void __launch_bounds__(256) k_build_hops(const PlanScalars pl, int32_
 // Workgroups of (64, 4) threads stride over the tiles and issue one set of atomics each.
 // ------------------------------------------------------------------------------------------
 constexpr int kValTile = 64;
+constexpr int kValPartial = 8;              // 64-bit words per workgroup in the partial-result array
 __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ sendcounts,
                                                   const int32_t* __restrict__ recvcounts,
                                                   const int64_t* __restrict__ sdispls,
                                                   const int64_t* __restrict__ rdispls,
-                                                  int P, Status* __restrict__ st,
+                                                  int P, unsigned long long* __restrict__ partial,
                                                   const int32_t* __restrict__ hm1, int Q, int N) {
     __shared__ int tile[kValTile][kValTile + 1];
     __shared__ unsigned long long red[4][6];
@@ -249,13 +250,47 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
             fa |= red[w][0]; m = max(m, red[w][1]); by += red[w][2]; ch += red[w][3]; ex = max(ex, red[w][4]);
             tc += red[w][5];
         }
-        if (fa >> 32) atomicOr(&st->flags, (unsigned int)(fa >> 32));
-        if (fa & 15u) atomicOr(&st->align_bits, (unsigned int)(fa & 15u));
-        if (m) atomicMax(&st->max_count, (int)m);
-        if (by) atomicAdd(&st->total_bytes, by);
-        if (ch) atomicAdd(&st->total_chunks, ch);
-        if (ex) atomicMax(&st->send_extent, ex);
-        if (tc) atomicAdd(&st->t_chunks, tc);
+        // one row of partial results per workgroup, folded by k_validate_finish: thousands of atomics
+        // on the same few addresses would take longer than reading the matrices
+        unsigned long long* o = partial + (size_t)blockIdx.x * kValPartial;
+        o[0] = fa; o[1] = m; o[2] = by; o[3] = ch; o[4] = ex; o[5] = tc;
+    }
+}
+
+// k_validate_finish: folds the workgroups' partial results into the status block (one workgroup).
+__global__ void __launch_bounds__(256) k_validate_finish(const unsigned long long* __restrict__ partial, int n,
+                                                         Status* __restrict__ st) {
+    __shared__ unsigned long long red[4][6];
+    unsigned long long fa = 0, m = 0, by = 0, ch = 0, ex = 0, tc = 0;
+    for (int i = threadIdx.x; i < n; i += blockDim.x) {
+        const unsigned long long* o = partial + (size_t)i * kValPartial;
+        fa |= o[0]; m = max(m, o[1]); by += o[2]; ch += o[3]; ex = max(ex, o[4]); tc += o[5];
+    }
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) {
+        fa |= __shfl_xor(fa, d, kWave);
+        m = max(m, (unsigned long long)__shfl_xor(m, d, kWave));
+        by += __shfl_xor(by, d, kWave);
+        ch += __shfl_xor(ch, d, kWave);
+        ex = max(ex, (unsigned long long)__shfl_xor(ex, d, kWave));
+        tc += __shfl_xor(tc, d, kWave);
+    }
+    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
+    if (lane == 0) { red[wv][0] = fa; red[wv][1] = m; red[wv][2] = by; red[wv][3] = ch; red[wv][4] = ex; red[wv][5] = tc; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        fa = m = by = ch = ex = tc = 0;
+        for (int w = 0; w < 4; ++w) {
+            fa |= red[w][0]; m = max(m, red[w][1]); by += red[w][2]; ch += red[w][3]; ex = max(ex, red[w][4]);
+            tc += red[w][5];
+        }
+        st->flags = (unsigned int)(fa >> 32);
+        st->align_bits = (unsigned int)(fa & 15u);
+        st->max_count = (int)m;
+        st->total_bytes = by;
+        st->total_chunks = ch;
+        st->send_extent = ex;
+        st->t_chunks = tc;
     }
 }
 
@@ -323,22 +358,53 @@ __global__ void __launch_bounds__(256) k_self_copy(const unsigned char* __restri
 }
 
 // ------------------------------------------------------------------------------------------
-// k_phase_layout: all metadata work of one digit phase in one launch, one workgroup per rank.
-//  (1) metadata exchange (Section "Two-phase communication"; Algorithm "TuNA", line 14): the size
-//      of every moving block travels from the sender's size array to the receiver's,
-//      nxt[q][e] = cur[q + z r^x][e] with z the digit of e; sizes of blocks that stay are carried over;
-//  (2) size/displacement scans (the contiguous send buffer of Algorithm "TuNA", line 15, needs each
-//      block's offset inside its message): per rank, the moving blocks' sizes in message order are
-//      converted to 16-byte chunks and exclusive-scanned (wave shuffles + LDS across the 4 waves,
-//      a running carry across batches of 1024 segments) -- once over the sizes the rank receives
-//      (receive-side layout) and once over the sizes it sends (send-side layout);
+// k_size_exchange: the metadata exchange of one digit phase (Section "Two-phase communication";
+// Algorithm "TuNA", line 14): the size of every moving block travels from the sender's size array
+// to the receiver's, nxt[q][e] = cur[q + z r^x][e] with z the digit of e; sizes of blocks that stay
+// are carried over.  One thread per (rank, slot index): both rows are read and written along e.
+// ------------------------------------------------------------------------------------------
+constexpr int kExchangeRanks = 8;           // ranks per thread of k_size_exchange
+__global__ void __launch_bounds__(256) k_size_exchange(const int32_t* __restrict__ cur, int32_t* __restrict__ nxt,
+                                                       const int32_t* __restrict__ zt, int P, int Q, int N, int dim,
+                                                       int rx) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= P) return;
+    const int dist = zt[e] * rx;                      // 0: the block stays
+    const int q0 = blockIdx.y * kExchangeRanks;
+    int v[kExchangeRanks];
+#pragma unroll
+    for (int k = 0; k < kExchangeRanks; ++k) {        // all loads of a thread are in flight together
+        const int q = q0 + k;
+        v[k] = 0;
+        if (q < P) {
+            int src = q;
+            if (dist) {
+                const int qn = q / Q;
+                src = partner_up(qn, q - qn * Q, Q, N, dim, dist);
+            }
+            v[k] = cur[(size_t)src * P + e];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < kExchangeRanks; ++k)
+        if (q0 + k < P) nxt[(size_t)(q0 + k) * P + e] = v[k];
+}
+
+// ------------------------------------------------------------------------------------------
+// k_phase_layout: the size/displacement scans of one digit phase, one workgroup per rank, from the
+// sizes the rank holds before the phase (`cur`) and after it (`nxt`, see k_size_exchange):
+//  size/displacement scans (the contiguous send buffer of Algorithm "TuNA", line 15, needs each
+//  block's offset inside its message): per rank, the moving blocks' sizes in message order are
+//  converted to 16-byte chunks and exclusive-scanned (wave shuffles + LDS across the 4 waves,
+//  a running carry across batches of 1024 segments) -- once over the sizes the rank receives
+//  (receive-side layout) and once over the sizes it sends (send-side layout);
 // With `head_displs` (one-kernel phases) the chunks of a block bound for R are cut at the 16-byte
 // boundaries of its destination address: a block that starts `a` bytes into a 16-byte line takes
 // ceil((a + size) / 16) chunks; head_base is the low 4 bits of the receive buffer address.
 // ------------------------------------------------------------------------------------------
 struct PhaseLayoutArgs {
-    const int32_t* cur;
-    int32_t* nxt;
+    const int32_t* cur;             // [P][P] sizes before the phase
+    const int32_t* nxt;             // [P][P] sizes after it
     const int32_t* zt;              // [P] digit value of slot e in this phase (0: stays)
     SegDev seg;
     int nseg;
@@ -347,22 +413,34 @@ struct PhaseLayoutArgs {
     int want_send;                  // 0: only the receive-side layout (one-kernel phases)
     int want_tbound;                // 1: also the prefix over the T-bound blocks alone (exact-size T)
     int* tpos;                      // [P][P]: that prefix again, by slot index, for the phases that forward the blocks
+    unsigned long long* rank_bytes; // [P]: payload bytes every rank moves in this phase
     unsigned long long* phase_bytes;
     unsigned long long* phase_chunks;
     const int64_t* head_displs;
     unsigned int head_base;
 };
 
-// exclusive scan of c[] (kScanItems consecutive items per thread) over the workgroup; returns the
-// thread's running start and adds the batch total to `carry`
-__device__ __forceinline__ int block_scan_batch(const int (&c)[kScanItems], int& carry, int* wsum) {
+// Item k of a thread in a batch of kScanThreads * kScanItems segments: every wave owns
+// kScanItems * 64 consecutive segments and lane i takes the ones at i, i + 64, ...: one load
+// instruction of a wave reads 64 consecutive table entries.
+__device__ __forceinline__ int scan_item_index(int k) {
+    const int tid = threadIdx.x;
+    return (tid / kWave) * (kWave * kScanItems) + k * kWave + (tid & (kWave - 1));
+}
+
+// exclusive scan of the batch in that order; run[k] = start of item k, `carry` grows by the batch total
+__device__ __forceinline__ void block_scan_batch(const int (&c)[kScanItems], int (&run)[kScanItems], int& carry,
+                                                 int* wsum) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
-    int sum = 0;
+    int wtotal = 0;
 #pragma unroll
-    for (int k = 0; k < kScanItems; ++k) sum += c[k];
-    const int incl = wave_incl_scan(sum);
+    for (int k = 0; k < kScanItems; ++k) {
+        const int incl = wave_incl_scan(c[k]);
+        run[k] = wtotal + incl - c[k];
+        wtotal += __shfl(incl, kWave - 1, kWave);
+    }
     __syncthreads();                                  // wsum of the previous batch is consumed
-    if (lane == kWave - 1) wsum[wv] = incl;
+    if (lane == 0) wsum[wv] = wtotal;
     __syncthreads();
     int woff = 0, total = 0;
 #pragma unroll
@@ -371,16 +449,18 @@ __device__ __forceinline__ int block_scan_batch(const int (&c)[kScanItems], int&
         if (k < wv) woff += v;
         total += v;
     }
-    const int run = carry + woff + incl - sum;
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k) run[k] += carry + woff;
     carry += total;
-    return run;
 }
 
 // exclusive scan over the P per-rank totals of one layout by one workgroup of kScanThreads: every
 // thread sums a contiguous range of ranks, the thread sums are scanned across the workgroup, then
 // every thread writes the bases of its range
 __device__ __forceinline__ void scan_rank_bases(int P, const LayoutDev& L, unsigned long long* phase_chunks,
-                                                long long* wc, int* wt, const ExactT* x = nullptr) {
+                                                long long* wc, int* wt, const ExactT* x = nullptr,
+                                                const unsigned long long* rank_bytes = nullptr,
+                                                unsigned long long* phase_bytes = nullptr) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const int per = (P + kScanThreads - 1) / kScanThreads;
     const int p0 = min(P, tid * per), p1 = min(P, p0 + per);
@@ -426,23 +506,32 @@ __device__ __forceinline__ void scan_rank_bases(int P, const LayoutDev& L, unsig
         if (phase_chunks) *phase_chunks = (unsigned long long)totc;
         if (x) x->arena_end[x->phase] = arena0 + (totc + 15) / 16 * 16;
     }
+    if (phase_bytes) {                                // payload bytes of the phase = sum of the ranks' sums
+        unsigned long long b = 0;
+        for (int p = p0; p < p1; ++p) b += rank_bytes[p];
+#pragma unroll
+        for (int d = kWave / 2; d > 0; d >>= 1) b += __shfl_xor(b, d, kWave);
+        __syncthreads();                              // wc is reused
+        if (lane == 0) wc[wv] = (long long)b;
+        __syncthreads();
+        if (tid == 0) {
+            unsigned long long t = 0;
+#pragma unroll
+            for (int k = 0; k < kScanThreads / kWave; ++k) t += (unsigned long long)wc[k];
+            *phase_bytes = t;
+        }
+    }
 }
 
 __global__ void __launch_bounds__(kScanThreads) k_phase_layout(const PhaseLayoutArgs a) {
     __shared__ int wsum[kScanThreads / kWave];
+    __shared__ unsigned long long wbytes[kScanThreads / kWave];
     const int P = a.P;
-    // Workgroups go to the 8 XCDs round robin.  Give every XCD a contiguous range of ranks: with a
-    // large radix the sizes a rank receives lie on a diagonal of `cur`, and each of its 128-byte
-    // lines is shared by 32 neighbouring ranks -- in one L2 instead of eight.
-    const int p = (P & 7) ? (int)blockIdx.x : (int)(blockIdx.x & 7) * (P >> 3) + (int)(blockIdx.x >> 3);
+    const int p = blockIdx.x;
     const int pn = p / a.Q, pg = p - pn * a.Q;
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int32_t* crow = a.cur + (size_t)p * P;
-    int32_t* nrow = a.nxt + (size_t)p * P;
-    // (1a) blocks that do not move in this phase keep their size
-    for (int e = tid; e < P; e += kScanThreads)
-        if (a.zt[e] == 0) nrow[e] = crow[e];
-    // (1b) + (2) receive side: sizes arrive from the partner at distance z r^x, then the scan
+    const int32_t* nrow = a.nxt + (size_t)p * P;
     int* pre_r = a.Lr.pre + (size_t)p * a.Lr.ld;
     int* pre_s = a.Ls.pre + (size_t)p * a.Ls.ld;
     int* pre_t = a.want_tbound ? a.Lt.pre + (size_t)p * a.Lt.ld : nullptr;
@@ -452,15 +541,13 @@ __global__ void __launch_bounds__(kScanThreads) k_phase_layout(const PhaseLayout
         int cr[kScanItems], cs[kScanItems], ct[kScanItems];
 #pragma unroll
         for (int k = 0; k < kScanItems; ++k) {
-            const int s = base + tid * kScanItems + k;
+            const int s = base + scan_item_index(k);
             int szr = 0, szs = 0, head = 0;
             bool tbound = false;
             if (s < a.nseg) {
                 tbound = a.want_tbound && a.seg.dst[s] >= 0;
                 const int e = a.seg.e[s];
-                const int ps = partner_up(pn, pg, a.Q, a.N, a.dim, a.seg.z[s] * a.rx);
-                szr = a.cur[(size_t)ps * P + e];
-                nrow[e] = szr;
+                szr = nrow[e];
                 if (a.want_send) szs = crow[e];
                 if (a.head_displs && szr > 0 && a.seg.dst[s] < 0) {
                     int j, l;
@@ -475,38 +562,46 @@ __global__ void __launch_bounds__(kScanThreads) k_phase_layout(const PhaseLayout
             cs[k] = (szs + 15) >> 4;
             ct[k] = tbound ? (szr + 15) >> 4 : 0;
         }
-        int run = block_scan_batch(cr, carry_r, wsum);
+        int run[kScanItems];
+        block_scan_batch(cr, run, carry_r, wsum);
 #pragma unroll
         for (int k = 0; k < kScanItems; ++k) {
-            const int s = base + tid * kScanItems + k;
-            if (s < a.nseg) pre_r[s] = run;
-            run += cr[k];
+            const int s = base + scan_item_index(k);
+            if (s < a.nseg) pre_r[s] = run[k];
         }
         if (a.want_send) {
-            run = block_scan_batch(cs, carry_s, wsum);
+            block_scan_batch(cs, run, carry_s, wsum);
 #pragma unroll
             for (int k = 0; k < kScanItems; ++k) {
-                const int s = base + tid * kScanItems + k;
-                if (s < a.nseg) pre_s[s] = run;
-                run += cs[k];
+                const int s = base + scan_item_index(k);
+                if (s < a.nseg) pre_s[s] = run[k];
             }
         }
         if (a.want_tbound) {
-            run = block_scan_batch(ct, carry_t, wsum);
+            block_scan_batch(ct, run, carry_t, wsum);
 #pragma unroll
             for (int k = 0; k < kScanItems; ++k) {
-                const int s = base + tid * kScanItems + k;
+                const int s = base + scan_item_index(k);
                 if (s < a.nseg) {
-                    pre_t[s] = run;
-                    if (ct[k]) a.tpos[(size_t)p * P + a.seg.e[s]] = run;
+                    pre_t[s] = run[k];
+                    if (ct[k]) a.tpos[(size_t)p * P + a.seg.e[s]] = run[k];
                 }
-                run += ct[k];
             }
         }
     }
 #pragma unroll
     for (int d = kWave / 2; d > 0; d >>= 1) bytes += __shfl_xor(bytes, d, kWave);
-    if (lane == 0 && bytes && a.phase_bytes) atomicAdd(a.phase_bytes, bytes);
+    // one sum per rank, added up by k_layout_base: thousands of atomics on one address would take
+    // longer than the scans
+    __syncthreads();
+    if (lane == 0) wbytes[tid / kWave] = bytes;
+    __syncthreads();
+    if (tid == 0) {
+        unsigned long long t = 0;
+#pragma unroll
+        for (int k = 0; k < kScanThreads / kWave; ++k) t += wbytes[k];
+        a.rank_bytes[p] = t;
+    }
     if (tid == 0) {
         pre_r[a.nseg] = carry_r; a.Lr.tot[p] = carry_r;
         if (a.want_send) { pre_s[a.nseg] = carry_s; a.Ls.tot[p] = carry_s; }
@@ -522,12 +617,14 @@ __global__ void __launch_bounds__(kScanThreads) k_phase_layout(const PhaseLayout
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kScanThreads) k_layout_base(int P, LayoutDev L0, LayoutDev L1, LayoutDev L2,
                                                               unsigned long long* __restrict__ phase_chunks,
-                                                              int chunks_from, int tbound_at, ExactT x) {
+                                                              int chunks_from, int tbound_at, ExactT x,
+                                                              const unsigned long long* __restrict__ rank_bytes,
+                                                              unsigned long long* __restrict__ phase_bytes) {
     __shared__ long long wc[kScanThreads / kWave];
     __shared__ int wt[kScanThreads / kWave];
     const int which = blockIdx.x;
     scan_rank_bases(P, which == 0 ? L0 : (which == 1 ? L1 : L2), which == chunks_from ? phase_chunks : nullptr, wc, wt,
-                    which == tbound_at ? &x : nullptr);
+                    which == tbound_at ? &x : nullptr, rank_bytes, which == chunks_from ? phase_bytes : nullptr);
 }
 
 // ------------------------------------------------------------------------------------------
