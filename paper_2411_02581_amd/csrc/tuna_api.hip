@@ -610,8 +610,8 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
 
     // ---- initial rotation (index only) and the own block ----------------------------------------
     const size_t P2 = (size_t)P * P;
-    const unsigned gP2 = (unsigned)((P2 + 255) / 256);
-    hipLaunchKernelGGL(k_rotate_init, dim3(gP2), dim3(256), 0, s, sendcounts, mb.cur, P, pr.Q, pr.N);
+    const dim3 grot((unsigned)((P + 255) / 256), (unsigned)((P + kExchangeRanks - 1) / kExchangeRanks));
+    hipLaunchKernelGGL(k_rotate_init, grot, dim3(256), 0, s, sendcounts, mb.cur, P, pr.Q, pr.N);
     HIPCHK(hipGetLastError());
     rc = launch_transpose_displs(pr, s);
     if (rc != TUNA_OK) return rc;
@@ -696,8 +696,8 @@ int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* s
     if (any_one_kernel_phase(pr)) pr.sdispls_t = cm.take<int64_t>(P2);
     auto fail = [&](int code) { (void)hipFree(plan->mem_meta); if (plan->mem_data) (void)hipFree(plan->mem_data); delete plan; return code; };
     if (!cm.ok) return fail(TUNA_ERR_NOMEM);
-    const unsigned gP2 = (unsigned)((P2 + 255) / 256);
-    hipLaunchKernelGGL(k_rotate_init, dim3(gP2), dim3(256), 0, s, sendcounts, cur, P, pr.Q, pr.N);
+    const dim3 grot((unsigned)((P + 255) / 256), (unsigned)((P + kExchangeRanks - 1) / kExchangeRanks));
+    hipLaunchKernelGGL(k_rotate_init, grot, dim3(256), 0, s, sendcounts, cur, P, pr.Q, pr.N);
     if (hipGetLastError() != hipSuccess) return fail(TUNA_ERR_HIP);
     rc = launch_transpose_displs(pr, s);
     if (rc != TUNA_OK) return fail(rc);

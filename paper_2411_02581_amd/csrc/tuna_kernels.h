@@ -23,6 +23,7 @@ constexpr int kChunksPerLane = 4;
 constexpr int kUnitChunks = kWave * kChunksPerLane;      // 256 chunks = 4 KiB per wave unit
 constexpr int kScanThreads = 256;
 constexpr int kScanItems = 4;
+constexpr int kExchangeRanks = 8;                        // ranks per thread of the elementwise size kernels
 
 enum CopyMode { kPack = 0, kExchange = 1, kUnpack = 2, kFused = 3 };
 // per-segment flags in the copy kernel's window: bits 0-3 = bytes of the first chunk that lie
@@ -321,14 +322,25 @@ __global__ void __launch_bounds__(256) k_transpose_displs(const int64_t* __restr
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) k_rotate_init(const int32_t* __restrict__ sendcounts,
                                                      int32_t* __restrict__ cur, int P, int Q, int N) {
-    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (size_t)P * P) return;
-    const int p = (int)(idx / P), e = (int)(idx - (size_t)p * P);
-    const int n = p / Q, g = p - n * Q;
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;      // grid (ceil(P / 256), ceil(P / kExchangeRanks))
+    if (e >= P) return;
     const int j = e / Q, l = e - j * Q;
-    int dn = n - j; if (dn < 0) dn += N;
-    int dg = g - l; if (dg < 0) dg += Q;
-    cur[idx] = sendcounts[(size_t)p * P + dn * Q + dg];
+    const int p0 = blockIdx.y * kExchangeRanks;
+    int v[kExchangeRanks];
+#pragma unroll
+    for (int k = 0; k < kExchangeRanks; ++k) {
+        const int p = p0 + k;
+        v[k] = 0;
+        if (p < P) {
+            const int n = p / Q, g = p - n * Q;
+            int dn = n - j; if (dn < 0) dn += N;
+            int dg = g - l; if (dg < 0) dg += Q;
+            v[k] = sendcounts[(size_t)p * P + dn * Q + dg];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < kExchangeRanks; ++k)
+        if (p0 + k < P) cur[(size_t)(p0 + k) * P + e] = v[k];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -363,7 +375,6 @@ __global__ void __launch_bounds__(256) k_self_copy(const unsigned char* __restri
 // to the receiver's, nxt[q][e] = cur[q + z r^x][e] with z the digit of e; sizes of blocks that stay
 // are carried over.  One thread per (rank, slot index): both rows are read and written along e.
 // ------------------------------------------------------------------------------------------
-constexpr int kExchangeRanks = 8;           // ranks per thread of k_size_exchange
 __global__ void __launch_bounds__(256) k_size_exchange(const int32_t* __restrict__ cur, int32_t* __restrict__ nxt,
                                                        const int32_t* __restrict__ zt, int P, int Q, int N, int dim,
                                                        int rx) {
