@@ -51,8 +51,9 @@ def parse_args():
                     help="replace the configuration's counts by 8 * U{0..S/8} bytes (the paper's uniform [0, S] "
                          "micro-benchmark with FP64 elements); use with --ranks and --radices")
     ap.add_argument("--fused", type=int, default=0, help="1: fused single-kernel rounds")
-    ap.add_argument("--exact-t", type=int, default=1,
-                    help="main sweep: 1 = T in exact size (the library's default), 0 = the paper's B slots of M bytes")
+    ap.add_argument("--exact-t", type=int, default=2,
+                    help="main sweep, TUNA_OPT_DENSE_T: 2 = the library's default (T in exact size unless the paper's slots "
+                         "would be 90 %% full), 1 = exact size, 0 = the paper's B slots of M bytes")
     ap.add_argument("--block-count", type=int, default=0,
                     help="TUNA_OPT_BLOCK_COUNT: rounds per batch of launches (0: all rounds of a phase at once)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -148,9 +149,9 @@ def main():
         copy_ceiling = {"GBs": 2 * nb / (ms * 1e-3) / 1e9, "bytes_copied": nb, "ms": ms}
         print("[bench] plain copy ceiling: %.0f GB/s (read + write)" % copy_ceiling["GBs"], file=sys.stderr, flush=True)
 
-    def run_sweep(fused, exact_t=False):
+    def run_sweep(fused, exact_t=2):
         tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 1 if fused else 0)
-        tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 1 if exact_t else 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, int(exact_t))
         per_radix = []
         for kind, _, rl, rg in sweep:
             label = "r_l=%d,r_g=%d" % (rl, rg) if kind == "hier" else "r=%d" % rl
@@ -201,7 +202,7 @@ def main():
                 "radix": label, "ms_per_step": ms_per_step, "median_ms": statistics.median(step_ms),
                 "stdev_ms": statistics.pstdev(step_ms), "effective_GBs": Btot / (ms_per_step * 1e-3) / 1e9,
                 "phases": st.n_phases, "rounds": st.K_local + st.K_global, "hop_bytes": hop_bytes,
-                "temp_bytes": st.temp_bytes, "workspace_bytes": st.workspace_bytes,
+                "temp_bytes": st.temp_bytes, "workspace_bytes": st.workspace_bytes, "exact_size_t": st.dense_t,
                 "profiled_ms_per_step": prof_total / args.steps, "metadata_ms_per_step": meta_ms / args.steps,
                 "prepare_ms_per_step": prep_ms / args.steps, "kernels": kernels, "granularity": st.granularity})
             print("[bench] %s: %.3f ms/step, %.1f GB/s effective; " % (label, ms_per_step, per_radix[-1]["effective_GBs"]) +
@@ -210,10 +211,10 @@ def main():
                   file=sys.stderr, flush=True)
 
         tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
-        tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 1)
+        tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 2)
         return per_radix
 
-    def run_persistent(fused, exact_t=True):
+    def run_persistent(fused, exact_t=2):
         """tuna_alltoallv_init once per radix, then K timed tuna_start calls (no validation, no
         metadata kernels, no host synchronisation), eagerly and as one captured HIP graph.
         exact_t: T stored in exact size (one arena per phase) instead of B slots of M bytes."""
@@ -221,10 +222,10 @@ def main():
         for kind, _, rl, rg in sweep:
             label = "r_l=%d,r_g=%d" % (rl, rg) if kind == "hier" else "r=%d" % rl
             tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 1 if fused else 0)
-            tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 1 if exact_t else 0)
+            tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, int(exact_t))
             rc, plan = tuna.tuna_alltoallv_init(send, d_sc, d_sd, recv, d_rc, d_rd, P, rpn, rl, rg)
             tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
-            tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 1)
+            tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 2)
             if rc != 0:
                 raise RuntimeError("tuna_alltoallv_init failed: " + tuna.tuna_strerror(rc))
             try:
@@ -252,29 +253,29 @@ def main():
                              "effective_GBs": Btot / (min(ms_start, ms_graph) * 1e-3) / 1e9,
                              "plan_bytes": st.workspace_bytes, "temp_bytes": st.temp_bytes})
                 print("[bench] %s persistent%s%s: %.3f ms/start, %.3f ms/graph replay, %.1f GB/s effective, T %.2f GiB" %
-                      (label, " fused" if fused else "", "" if exact_t else " slots of M", ms_start, ms_graph,
+                      (label, " fused" if fused else "", "" if st.dense_t else " slots of M", ms_start, ms_graph,
                        rows[-1]["effective_GBs"], st.temp_bytes / 2 ** 30),
                       file=sys.stderr, flush=True)
             finally:
                 tuna.tuna_plan_free(plan)
         return rows
 
-    per_radix = run_sweep(bool(args.fused), bool(args.exact_t))
+    per_radix = run_sweep(bool(args.fused), args.exact_t)
     # the fused rounds (one kernel per phase, 2 x payload instead of 6 x) as a second table, and both
     # with T in the paper's B slots of M bytes instead of exact size
     fused_table = slots_table = fused_slots_table = None
     if not args.fused and args.exact_t and not args.no_fused_table:
-        fused_table = run_sweep(True, True)
-        slots_table = run_sweep(False, False)
-        fused_slots_table = run_sweep(True, False)
+        fused_table = run_sweep(True, args.exact_t)
+        slots_table = run_sweep(False, 0)
+        fused_slots_table = run_sweep(True, 0)
     persistent = None
     if not args.no_persistent_table:
         persistent = {"note": "tuna_alltoallv_init once, then tuna_start per step: payload kernels only",
-                      "staged": run_persistent(bool(args.fused), bool(args.exact_t))}
+                      "staged": run_persistent(bool(args.fused), args.exact_t)}
         if not args.fused and args.exact_t and not args.no_fused_table:
-            persistent["fused"] = run_persistent(True)
-            persistent["staged_slots_of_M"] = run_persistent(False, exact_t=False)
-            persistent["fused_slots_of_M"] = run_persistent(True, exact_t=False)
+            persistent["fused"] = run_persistent(True, args.exact_t)
+            persistent["staged_slots_of_M"] = run_persistent(False, exact_t=0)
+            persistent["fused_slots_of_M"] = run_persistent(True, exact_t=0)
     best = max(per_radix, key=lambda r: r["effective_GBs"])
     # Roofline of the dominant kernel: the copy kernel with the largest total time over ALL launches
     # of the timed sweep (every radix), so that its average launch duration is the one a
@@ -292,11 +293,12 @@ def main():
         gran = per_radix[0]["granularity"]
         dom = max(tot.items(), key=lambda kv: kv[1][0])
         name, (ms, n, alg) = dom
-        et = "true" if args.exact_t else "false"
+        exact_used = bool(per_radix[0]["exact_size_t"])
+        et = "true" if exact_used else "false"
         kname = {"pack": "tuna::k_copy<0, %d, %s>" % (gran, et), "exchange": "tuna::k_copy<1, 16, false>",
                  "unpack": "tuna::k_copy<2, %d, %s>" % (gran, et), "fused": "tuna::k_copy<3, %d, %s>" % (gran, et)}[name]
         default_run = (args.config == 4 and P == 4096 and not args.radices)
-        traffic = MEASURED_TRAFFIC_CONFIG4[bool(args.exact_t)].get(name) if default_run else None
+        traffic = MEASURED_TRAFFIC_CONFIG4[exact_used].get(name) if default_run else None
         achieved = alg / (ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": kname, "stage": name, "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
@@ -326,7 +328,7 @@ def main():
         "config": {"workload": ("uniform [0, %d] bytes in FP64 elements, P=%d flat" % (args.uniform_max_bytes, P))
                                if args.uniform_max_bytes else "config %d: %s" % (args.config, cfg.description), "P": P,
                    "payload_bytes": Btot, "best_radix": best["radix"], "fused": bool(args.fused),
-                   "exact_size_t": bool(args.exact_t), "block_count": args.block_count,
+                   "exact_size_t": bool(per_radix[0]["exact_size_t"]), "t_layout_option": args.exact_t, "block_count": args.block_count,
                    "ranks_per_node": rpn},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "copy_ceiling": copy_ceiling, "per_radix": per_radix, "persistent": persistent,
         "also_measured": also,

@@ -80,7 +80,7 @@ typedef struct tuna_stats {
     int32_t granularity;             /* 16, 4 or 1: common divisor of all counts/displacements/base addresses */
     int32_t fused;                   /* 1 when the fused single-kernel rounds were used */
     int32_t last_hip_error;
-    int32_t dense_t;                 /* 1 when T is stored in exact size (TUNA_OPT_DENSE_T) */
+    int32_t dense_t;                 /* 1 when T was addressed in exact size, 0 in slots of M bytes (TUNA_OPT_DENSE_T) */
     int64_t max_block_bytes;         /* M (Algorithm "TuNA", line 1) */
     int64_t total_payload_bytes;     /* sum of sendcounts */
     int64_t temp_slots_per_rank;     /* slots of T actually laid out per rank */
@@ -195,7 +195,9 @@ int tuna_release(void);
  * for hierarchical calls: after the intra-node phase every one of the Q (N - 1) blocks bound
  * for another node is its own message and goes straight from where it lies (its T slot, or S)
  * to R of its destination -- no rearrangement of T, no packing; the global radix is N.
- * TUNA_OPT_DENSE_T (on by default; 0 = the paper's slots): 1 = T in exact size.  Section "Estimating temporary buffer size" bounds T
+ * TUNA_OPT_DENSE_T: 1 = T in exact size, 0 = T in the paper's slots, 2 (default) = exact size
+ * unless the slots would be at least 90 % full (blocks of nearly one size), where the slot
+ * arithmetic is just as dense and cheaper to address.  Exact size: Section "Estimating temporary buffer size" bounds T
  * by B slots of M bytes, M the largest block of all; with skewed sizes nearly all of that is
  * padding.  Here every block size is on the device before the first round, so the blocks a rank
  * stores into T in one phase can lie back to back (padded to 16 bytes) in an arena of that

@@ -51,7 +51,7 @@ struct Ctx {
     std::map<std::tuple<int, int, int, int, int>, DevicePlan> plans;
     tuna_stats_t stats;
     bool have_stats = false;
-    int opt_profile = 0, opt_fused = 0, opt_staggered = 0, opt_dense_t = 1, opt_block_count = 0;
+    int opt_profile = 0, opt_fused = 0, opt_staggered = 0, opt_dense_t = 2, opt_block_count = 0;
     std::vector<hipEvent_t> ev_pool;
     std::vector<Mark> marks;
     hipEvent_t ev_end = nullptr;
@@ -391,6 +391,15 @@ ExactT exact_t_of(const Prepared& pr, size_t i) {
     return x;
 }
 
+// T in exact size or in the paper's slots of M bytes.  Left to the library (option value 2), slots
+// are kept only when they would be at least 90 % full -- blocks of (nearly) one size, where the
+// slot arithmetic is as dense as the arenas and cheaper to address.
+bool choose_exact_t(int option, int P, const Status& hs) {
+    if (option != 2) return option != 0;
+    const double slot_bytes = (double)((hs.max_count + 127) / 128 * 128);
+    return (double)hs.total_bytes < 0.9 * (double)P * (double)P * slot_bytes;
+}
+
 bool phase_is_one_kernel(const Prepared& pr, const PhaseHost& ph) {
     return pr.fused || (pr.staggered && ph.dim == 1);
 }
@@ -403,7 +412,7 @@ void fill_stats_header(const Prepared& pr, const Status& hs, tuna_stats_t& st) {
     st.B_local = pl.B_l; st.B_global = pl.B_g; st.n_phases = (int)pl.phases.size();
     if (pr.staggered) st.K_global = pr.Q * (pr.N - 1);
     st.temp_slots_per_rank = pr.exact_t ? 0 : pl.slots;
-    st.dense_t = g.opt_dense_t ? 1 : 0;
+    st.dense_t = pr.exact_kernels ? 1 : 0;
     st.fused = pr.fused ? 1 : 0;
     st.max_block_bytes = hs.max_count;
     st.total_payload_bytes = (int64_t)hs.total_bytes;
@@ -441,11 +450,12 @@ int prepare_call(const void* sendbuf, const int32_t* sendcounts, const int64_t* 
     pr.sdispls = sdispls; pr.rdispls = rdispls;
     // ---- validation, M, totals (one read-back) -------------------------------------------------
     pr.block_count = g.opt_block_count;
-    pr.exact_kernels = g.opt_dense_t != 0;
-    pr.exact_t = pr.exact_kernels && pr.dp->host.slots > 0;        // a schedule without T (r >= P - 1) has nothing to size
-    rc = run_validate(sendcounts, recvcounts, sdispls, rdispls, P, s, pr.exact_t ? pr.dp : nullptr);
+    const bool has_t = pr.dp->host.slots > 0;              // a schedule without T (r >= P - 1) has nothing to size
+    rc = run_validate(sendcounts, recvcounts, sdispls, rdispls, P, s, (g.opt_dense_t != 0 && has_t) ? pr.dp : nullptr);
     if (rc != TUNA_OK) return rc;
     hs = *g.h_status;
+    pr.exact_kernels = choose_exact_t(g.opt_dense_t, P, hs);
+    pr.exact_t = pr.exact_kernels && has_t;
     if (pr.dp->built_on == s) pr.dp->complete = true;      // run_validate synchronised this stream
     if (hs.flags & 1u) return TUNA_ERR_NEGATIVE_COUNT;
     if (hs.flags & 2u) return TUNA_ERR_COUNT_MISMATCH;
@@ -836,9 +846,9 @@ int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node, i
     rc = get_plan(P, Q, local_radix, staggered ? N : global_radix, g.opt_fused != 0, nullptr, &dp);
     if (rc != TUNA_OK) return rc;
     const PlanHost& pl = dp->host;
-    const bool exact_t = g.opt_dense_t != 0 && pl.slots > 0;
-    rc = run_validate(sendcounts, nullptr, nullptr, nullptr, P, nullptr, exact_t ? dp : nullptr);
+    rc = run_validate(sendcounts, nullptr, nullptr, nullptr, P, nullptr, (g.opt_dense_t != 0 && pl.slots > 0) ? dp : nullptr);
     if (rc != TUNA_OK) return rc;
+    const bool exact_t = choose_exact_t(g.opt_dense_t, P, *g.h_status) && pl.slots > 0;
     dp->complete = true;                                  // run_validate synchronised the stream the tables were built on
     if (g.h_status->flags & 1u) return TUNA_ERR_NEGATIVE_COUNT;
     const DataSizes ds = data_sizes_for(pl, g.h_status->max_count, g.h_status->total_chunks, g.opt_fused != 0, staggered,
@@ -887,7 +897,7 @@ int tuna_set_option(int option, int value) {
     if (option == TUNA_OPT_PROFILE) { g.opt_profile = value ? 1 : 0; return TUNA_OK; }
     if (option == TUNA_OPT_FUSED) { g.opt_fused = value ? 1 : 0; return TUNA_OK; }
     if (option == TUNA_OPT_STAGGERED) { g.opt_staggered = value ? 1 : 0; return TUNA_OK; }
-    if (option == TUNA_OPT_DENSE_T) { g.opt_dense_t = value ? 1 : 0; return TUNA_OK; }
+    if (option == TUNA_OPT_DENSE_T) { if (value < 0 || value > 2) return TUNA_ERR_ARG; g.opt_dense_t = value; return TUNA_OK; }
     if (option == TUNA_OPT_BLOCK_COUNT) { if (value < 0) return TUNA_ERR_ARG; g.opt_block_count = value; return TUNA_OK; }
     return TUNA_ERR_ARG;
 }

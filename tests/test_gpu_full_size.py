@@ -137,7 +137,7 @@ def test_config4_full(tuna):
             assert tuna.tuna_plan_free(plan) == 0
         else:
             code = tuna.tuna_alltoallv(send, sc, sd, recv, rc, rd, P, r, 0)
-        tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 1)
+        tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 2)
         tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
         assert code == 0, tuna.tuna_strerror(code)
         assert tuna.tuna_get_stats().dense_t == (0 if slots else 1)

@@ -30,7 +30,7 @@ def mode(request, tuna):
     tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 1 if request.param.endswith("exact") else 0)
     yield request.param
     tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
-    tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 1)                 # the library's default
+    tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 2)                 # the library's default
 
 
 class Problem:

@@ -186,7 +186,7 @@ def _dense_plan(tuna, res, P, Q, rl, rg, fused=0, staggered=0, dense=1):
     finally:
         tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
         tuna.tuna_set_option(tuna.TUNA_OPT_STAGGERED, 0)
-        tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 1)             # the library's default
+        tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 2)             # the library's default
 
 
 @pytest.mark.parametrize("mode", ["staged", "fused", "staggered"])
@@ -295,3 +295,19 @@ def test_exact_size_t_bytes_hierarchical(tuna, P, Q, rl, rg):
             hops = tm.nonzero_digits((i % Qe - d % Qe) % Qe, rl) + tm.nonzero_digits((i // Qe - d // Qe) % N, rg)
             total += (int(counts[i, d]) + 15) // 16 * 16 * max(hops - 1, 0)
     assert st.temp_bytes == total + 256 * st.n_phases
+
+
+def test_t_layout_left_to_the_library(tuna):
+    """Option value 2 (the default): blocks of one size keep the paper's slots (they are full),
+    blocks of mixed sizes get T in exact size; both match the oracle."""
+    P = 64
+    assert tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 2) == 0
+    for counts, want_exact in ((wl.counts_constant(P, 256), 0), (wl.make_counts(4, P), 1)):
+        lay = wl.make_layout(counts)
+        res = Resident(lay)
+        want = res.load(31)
+        res.recv.fill_(CANARY)
+        assert tuna.tuna_alltoallv(res.send, res.sc, res.sd, res.recv, res.rc, res.rd, P, 4, 0) == 0
+        res.check(want, "automatic T layout")
+        assert tuna.tuna_get_stats().dense_t == want_exact
+    assert tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 3) == tuna.TUNA_ERR_ARG
