@@ -326,9 +326,7 @@ int resolve_hierarchy(int P, int ranks_per_node, int* Q) {
 // Validation + sizing pass shared by tuna_alltoallv* and tuna_workspace_bytes: fills *g.h_status.
 int run_validate(const int32_t* sendcounts, const int32_t* recvcounts, const int64_t* sdispls,
                  const int64_t* rdispls, int P, hipStream_t s, const DevicePlan* exact_t_for = nullptr) {
-    const int nwords = (int)(sizeof(Status) / 4);
-    hipLaunchKernelGGL(k_clear, dim3((nwords + 255) / 256), dim3(256), 0, s, (unsigned int*)g.d_status, nwords);
-    HIPCHK(hipGetLastError());
+    // every field of the status block a call reads is written by the call's own kernels: no clearing
     const size_t t = (size_t)((P + kValTile - 1) / kValTile);
     const unsigned vgrid = (unsigned)(t * t < (size_t)g.num_cus * 8 ? t * t : (size_t)g.num_cus * 8);
     hipLaunchKernelGGL(k_validate, dim3(vgrid), dim3(kValTile, 4), 0, s, sendcounts, recvcounts, sdispls, rdispls, P,

@@ -31,7 +31,8 @@ enum CopyMode { kPack = 0, kExchange = 1, kUnpack = 2, kFused = 3 };
 constexpr int kFlagFill = 16;    // destination is a T slot: the tail lane fills up the 128-byte line
 constexpr int kFlagSrcT = 32;    // source is a T slot: reading past the block's end is always safe
 
-// Device-side status block, cleared at the start of a call and read back once after validation.
+// Device-side status block: the validation pass writes the head, every phase its own two counters;
+// the head is read back once after validation.
 struct Status {
     unsigned int flags;            // bit 0: negative count, bit 1: recvcounts != transpose(sendcounts)
     unsigned int align_bits;       // OR of all counts and displacements (low bits decide the granularity)
@@ -102,14 +103,6 @@ __device__ __forceinline__ int wave_incl_scan(int v) {
 __device__ __forceinline__ int partner_up(int n, int g, int Q, int N, int dim, int dist) {
     if (dim == 0) { int gg = g + dist; if (gg >= Q) gg -= Q; return n * Q + gg; }
     int nn = n + dist; if (nn >= N) nn -= N; return nn * Q + g;
-}
-
-// ------------------------------------------------------------------------------------------
-// k_clear: zero a small word array (instead of a memset node, so a caller may capture the stream)
-// ------------------------------------------------------------------------------------------
-__global__ void k_clear(unsigned int* w, int n) {
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) w[i] = 0u;
 }
 
 // ------------------------------------------------------------------------------------------
