@@ -176,7 +176,9 @@ DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long tot
                          bool staggered = false, bool dense = false, unsigned long long t_chunks = 0) {
     DataSizes d{};
     const bool any_phase = !pl.phases.empty() && total_chunks > 0;
-    d.stage_chunks = any_phase ? (size_t)total_chunks : 0;
+    // every rank's region of a staging buffer (and of an arena of T) is rounded up to a 128-byte line
+    const size_t rank_pad = (size_t)pl.P * kRankAlignChunks;
+    d.stage_chunks = any_phase ? (size_t)total_chunks + rank_pad : 0;
     // fused rounds cut chunks at destination lines: up to one more chunk per moving block
     const size_t head_chunks = (fused || staggered) ? (size_t)pl.P * pl.P : 0;
     d.unit_cap = any_phase ? (size_t)((total_chunks + head_chunks) / kUnitChunks) + pl.P + 1 : 0;
@@ -185,7 +187,7 @@ DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long tot
     d.t_bytes = any_phase ? (size_t)pl.P * (size_t)d.slots * (size_t)d.slot_bytes : 0;
     if (dense) {       // exact size: what is stored into T over all phases, every phase's arena rounded up to 256
         d.slots = 0;
-        d.t_bytes = any_phase ? (size_t)t_chunks * 16 + pl.phases.size() * kAlign : 0;
+        d.t_bytes = any_phase ? (size_t)t_chunks * 16 + pl.phases.size() * (kAlign + rank_pad * 16) : 0;
     }
     // pl.slots already counts both copies of T when the plan is a fused one
     d.total = 2 * align_up(d.unit_cap * sizeof(int4)) + (fused ? 0 : 2 * align_up(d.stage_chunks * 16)) +

@@ -21,6 +21,7 @@ constexpr int kWave = 64;
 constexpr int kCopyThreads = 256;                        // 4 waves, each an independent work unit
 constexpr int kChunksPerLane = 4;
 constexpr int kUnitChunks = kWave * kChunksPerLane;      // 256 chunks = 4 KiB per wave unit
+constexpr int kRankAlignChunks = 8;                      // every rank's region of a staging buffer or arena starts on a 128-byte line
 constexpr int kScanThreads = 256;
 constexpr int kScanItems = 4;
 constexpr int kExchangeRanks = 8;                        // ranks per thread of the elementwise size kernels
@@ -468,11 +469,15 @@ __device__ __forceinline__ void scan_rank_bases(int P, const LayoutDev& L, unsig
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const int per = (P + kScanThreads - 1) / kScanThreads;
     const int p0 = min(P, tid * per), p1 = min(P, p0 + per);
+    const int ralign = kRankAlignChunks;
     long long sc = 0;
     int st = 0;
+    // a rank's region is rounded up to whole 128-byte lines: units, which are cut every 4 KiB from
+    // the region's start, then begin and end on line boundaries and their streaming stores are never
+    // split into partial-line writes
     for (int p = p0; p < p1; ++p) {
         const int c = L.tot[p];
-        sc += c;
+        sc += (c + ralign - 1) / ralign * ralign;
         st += (c + kUnitChunks - 1) / kUnitChunks;
     }
     long long ic = sc;
@@ -501,7 +506,7 @@ __device__ __forceinline__ void scan_rank_bases(int P, const LayoutDev& L, unsig
         L.rank_base[p] = run_c;
         if (x) x->tbase[(size_t)x->phase * P + p] = arena0 + run_c;
         if (L.unit_base) L.unit_base[p] = run_t;
-        run_c += c;
+        run_c += (c + ralign - 1) / ralign * ralign;
         run_t += (c + kUnitChunks - 1) / kUnitChunks;
     }
     if (tid == 0) {

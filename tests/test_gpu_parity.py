@@ -415,8 +415,9 @@ def test_temporary_buffer_too_large_is_an_error_not_a_crash(tuna, mode):
     if mode.endswith("exact"):
         assert rc == 0, tuna.tuna_strerror(rc)
         st = tuna.tuna_get_stats()
-        # the 100-byte block (7 chunks) has index 63: six hops, five stores; six phases of 256 bytes rounding
-        assert st.temp_bytes == 3 * (512 << 20) + 5 * 7 * 16 + 6 * 256
+        # the 100-byte block (7 chunks) has index 63: six hops, five stores; per phase 256 bytes of
+        # rounding and one 128-byte line per rank
+        assert st.temp_bytes == 3 * (512 << 20) + 5 * 7 * 16 + 6 * (256 + P * 128)
     else:
         assert rc == tuna.TUNA_ERR_NOMEM, tuna.tuna_strerror(rc)
         torch.cuda.synchronize()

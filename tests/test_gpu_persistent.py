@@ -215,7 +215,7 @@ def test_exact_size_t_matches_the_oracle(tuna, P, Q, rl, rg, cfg, mode):
 
 def test_exact_size_t_holds_what_waits_in_it(tuna):
     """T in exact size takes the bytes that are stored into it, summed over the phases (each block
-    padded to 16 bytes, plus 256 bytes of rounding per phase): for every phase but the last that is the phase's
+    padded to 16 bytes, plus 256 bytes of rounding per phase and a 128-byte line per rank and phase): for every phase but the last that is the phase's
     payload minus what reaches R.  With r = 2 and P = 2^k, phase x delivers the blocks whose index
     is below 2^(x+1) among those with bit x set, 2^x of P/2.  Heavy-tailed sizes make the bound
     of B slots of M bytes many times larger."""
@@ -242,7 +242,7 @@ def test_exact_size_t_holds_what_waits_in_it(tuna):
     for x in range(8):
         stored = ((idx >> x) & 1 == 1) & ((idx >> (x + 1)) != 0)
         total += int(chunks[stored].sum()) * 16
-    assert dense_bytes == total + 8 * 256              # each phase's arena is rounded up to 256 bytes
+    assert dense_bytes == total + 8 * (256 + P * 128)  # per phase: 256 bytes of rounding and one 128-byte line per rank
     code, plan = _dense_plan(tuna, res, P, 0, 2, 2, dense=0)
     assert code == 0
     try:
@@ -270,8 +270,8 @@ def test_device_source_tables_match_the_host(tuna):
 
 @pytest.mark.parametrize("P,Q,rl,rg", [(96, 8, 3, 4), (120, 5, 2, 5), (64, 0, 4, 4)])
 def test_exact_size_t_bytes_hierarchical(tuna, P, Q, rl, rg):
-    """The bytes of T the library reports are sum over blocks of 16 ceil(size / 16) (hops - 1) plus 256
-    per phase, hops = non-zero digits of the block's local distance in base r_l and of its node
+    """The bytes of T the library reports are sum over blocks of 16 ceil(size / 16) (hops - 1) plus 256 and
+    a 128-byte line per rank per phase, hops = non-zero digits of the block's local distance in base r_l and of its node
     distance in base r_g (counted here with the model's digit function)."""
     from oracle import tuna_model as tm
     counts = wl.make_counts(2, P)
@@ -294,7 +294,7 @@ def test_exact_size_t_bytes_hierarchical(tuna, P, Q, rl, rg):
         for d in range(P):
             hops = tm.nonzero_digits((i % Qe - d % Qe) % Qe, rl) + tm.nonzero_digits((i // Qe - d // Qe) % N, rg)
             total += (int(counts[i, d]) + 15) // 16 * 16 * max(hops - 1, 0)
-    assert st.temp_bytes == total + 256 * st.n_phases
+    assert st.temp_bytes == total + (256 + P * 128) * st.n_phases
 
 
 def test_t_layout_left_to_the_library(tuna):
