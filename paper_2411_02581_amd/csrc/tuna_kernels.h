@@ -409,7 +409,8 @@ __global__ void __launch_bounds__(256) k_size_exchange(const int32_t* __restrict
 // ------------------------------------------------------------------------------------------
 struct PhaseLayoutArgs {
     const int32_t* cur;             // [P][P] sizes before the phase
-    const int32_t* nxt;             // [P][P] sizes after it
+    int32_t* nxt;                   // [P][P] sizes after it
+    int inline_exchange;            // 1: this kernel also does the size exchange (few ranks: one launch less)
     const int32_t* zt;              // [P] digit value of slot e in this phase (0: stays)
     SegDev seg;
     int nseg;
@@ -540,7 +541,13 @@ __global__ void __launch_bounds__(kScanThreads) k_phase_layout(const PhaseLayout
     const int pn = p / a.Q, pg = p - pn * a.Q;
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int32_t* crow = a.cur + (size_t)p * P;
-    const int32_t* nrow = a.nxt + (size_t)p * P;
+    int32_t* nrow = a.nxt + (size_t)p * P;
+    if (a.inline_exchange) {
+        // the metadata exchange (see k_size_exchange), here by the receiving rank's own workgroup:
+        // blocks that do not move keep their size, the others arrive with the scan's gather below
+        for (int e = tid; e < P; e += kScanThreads)
+            if (a.zt[e] == 0) nrow[e] = crow[e];
+    }
     int* pre_r = a.Lr.pre + (size_t)p * a.Lr.ld;
     int* pre_s = a.Ls.pre + (size_t)p * a.Ls.ld;
     int* pre_t = a.want_tbound ? a.Lt.pre + (size_t)p * a.Lt.ld : nullptr;
@@ -556,7 +563,13 @@ __global__ void __launch_bounds__(kScanThreads) k_phase_layout(const PhaseLayout
             if (s < a.nseg) {
                 tbound = a.want_tbound && a.seg.dst[s] >= 0;
                 const int e = a.seg.e[s];
-                szr = nrow[e];
+                if (a.inline_exchange) {
+                    const int ps = partner_up(pn, pg, a.Q, a.N, a.dim, a.seg.z[s] * a.rx);
+                    szr = a.cur[(size_t)ps * P + e];
+                    nrow[e] = szr;
+                } else {
+                    szr = nrow[e];
+                }
                 if (a.want_send) szs = crow[e];
                 if (a.head_displs && szr > 0 && a.seg.dst[s] < 0) {
                     int j, l;
