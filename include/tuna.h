@@ -159,9 +159,10 @@ int tuna_start(tuna_plan_t plan, void* stream);
 int tuna_plan_free(tuna_plan_t plan);
 
 /*
- * Device bytes a call with these counts and parameters needs (Algorithm "TuNA", lines 1-2:
- * maximum block size M by a reduction over all ranks, T sized from it).  The reduction runs on
- * the device; the call synchronises.  *bytes is a host pointer.
+ * Device bytes a call with these counts and parameters needs under the options in force
+ * (Algorithm "TuNA", lines 1-2: maximum block size M by a reduction over all ranks, T sized from
+ * it -- or from the blocks' sizes and hop counts when T is kept in exact size).  The reduction
+ * runs on the device; the call synchronises.  *bytes is a host pointer.
  */
 int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node,
                          int local_radix, int global_radix, size_t* bytes);
@@ -190,19 +191,21 @@ int tuna_release(void);
  * that tuna_get_stats reports per-phase times (the breakdown categories of Section "Performance
  * analysis of coalesced and staggered TuNA_l^g": prepare, metadata, data, replace).
  * TUNA_OPT_FUSED: 1 = move every block of a phase straight from its source (S or T) to its
- * destination (R or the other copy of T) in one kernel instead of pack -> exchange -> unpack.
+ * destination (R or T; with T in slots, the other of two copies of T) in one kernel instead of
+ * pack -> exchange -> unpack.
  * TUNA_OPT_STAGGERED: 1 = the staggered inter-node schedule of Algorithm "Staggered TuNA_l^g"
  * for hierarchical calls: after the intra-node phase every one of the Q (N - 1) blocks bound
  * for another node is its own message and goes straight from where it lies (its T slot, or S)
  * to R of its destination -- no rearrangement of T, no packing; the global radix is N.
  * TUNA_OPT_DENSE_T: 1 = T in exact size, 0 = T in the paper's slots, 2 (default) = exact size
  * unless the slots would be at least 90 % full (blocks of nearly one size), where the slot
- * arithmetic is just as dense and cheaper to address.  Exact size: Section "Estimating temporary buffer size" bounds T
- * by B slots of M bytes, M the largest block of all; with skewed sizes nearly all of that is
- * padding.  Here every block size is on the device before the first round, so the blocks a rank
- * stores into T in one phase can lie back to back (padded to 16 bytes) in an arena of that
- * phase: T then takes sum over blocks of ceil(size / 16) * 16 * (hops - 1) bytes, whatever M is
- * (a block makes one hop per non-zero digit of its rank distance and waits in T between hops).
+ * arithmetic is just as dense and cheaper to address.  Exact size: Section "Estimating
+ * temporary buffer size" bounds T by B slots of M bytes, M the largest block of all; with skewed
+ * sizes nearly all of that is padding.  Here every block size is on the device before the first
+ * round, so the blocks a rank stores into T in one phase can lie back to back (padded to 16
+ * bytes) in an arena of that phase: T then takes sum over blocks of ceil(size / 16) * 16 *
+ * (hops - 1) bytes plus 256 + 128 P bytes of rounding per phase, whatever M is (a block makes
+ * one hop per non-zero digit of its rank distance and waits in T between hops).
  * TUNA_OPT_BLOCK_COUNT: k > 0 = at most k rounds of a digit phase are moved per set of kernel
  * launches, in ascending round order; 0 (default) = all rounds of a phase at once.  This is the
  * block_count of Algorithms "Staggered TuNA_l^g" and "Coalesced TuNA_l^g" (the number of
