@@ -570,6 +570,16 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
     return TUNA_OK;
 }
 
+int run_two_pass(const Prepared& prepared, hipStream_t s);
+size_t plan_meta_bytes(const Prepared& pr);
+
+// Immediate calls take the two-pass form (see run_two_pass) from this many staged chunks on (64 MiB),
+// when the schedule has at least two phases.
+constexpr unsigned long long kTwoPassMinChunks = 1ull << 22;
+bool use_two_pass(const PlanHost& pl, const Status& hs) {
+    return pl.phases.size() >= 2 && hs.total_chunks >= kTwoPassMinChunks;
+}
+
 int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
         const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
         void* stream) {
@@ -589,6 +599,7 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
     fill_stats_header(pr, hs, st);
     if (empty) { g.have_stats = true; return TUNA_OK; }
     const PlanHost& pl = pr.dp->host;
+    if (use_two_pass(pl, hs)) return run_two_pass(pr, s);
 
     // ---- workspace ---------------------------------------------------------------------------
     const size_t mbytes = meta_bytes_for(P) + (pr.exact_t ? exact_t_meta_bytes_for(pl, false) : 0) +
@@ -678,27 +689,25 @@ void carve_full_layout(Carver& cv, int P, size_t unit_cap, LayoutDev& L) {
     L.units = cv.take<int4>(unit_cap);
 }
 
-int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
-                const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
-                hipStream_t s, Plan** out) {
-    Plan* plan = new Plan();
+// Metadata memory of a plan: two size matrices, the per-rank byte sums, per phase two complete layouts.
+size_t plan_meta_bytes(const Prepared& pr) {
+    const PlanHost& pl = pr.dp->host;
+    const size_t P2 = (size_t)pr.P * pr.P;
+    return 2 * align_up(P2 * 4) + align_up((size_t)pr.P * 8) + pl.phases.size() * 2 * layout_bytes_for(pr.P, pr.ds.unit_cap) +
+           (pr.exact_t ? exact_t_meta_bytes_for(pl, true) : 0) + (any_one_kernel_phase(pr) ? align_up(P2 * 8) : 0);
+}
+
+// Every phase's metadata in `meta` (plan_meta_bytes of it), then one read-back: exact unit counts,
+// per-phase bytes and chunks, and from them the payload memory the plan needs (*dbytes).
+// with_marks: record the profiling marks of an immediate call.
+int plan_build_metadata(Plan* plan, void* meta, size_t mbytes, hipStream_t s, bool with_marks, size_t* stage_bytes,
+                        size_t* dbytes) {
     Prepared& pr = plan->pr;
-    Status hs{};
-    int rc = prepare_call(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node, rl, rg, s,
-                          pr, hs, &plan->empty);
-    if (rc != TUNA_OK) { delete plan; return rc; }
-    fill_stats_header(pr, hs, plan->stats);
-    if (plan->empty) { ++g.live_plans; *out = plan; return TUNA_OK; }
     const PlanHost& pl = pr.dp->host;
     const size_t nph = pl.phases.size();
-    // metadata memory: two size matrices + per phase two complete layouts
+    const int P = pr.P;
     const size_t P2 = (size_t)P * P;
-    const size_t mbytes = 2 * align_up(P2 * 4) + align_up((size_t)P * 8) + nph * 2 * layout_bytes_for(P, pr.ds.unit_cap) +
-                          (pr.exact_t ? exact_t_meta_bytes_for(pl, true) : 0) +
-                          (any_one_kernel_phase(pr) ? align_up(P2 * 8) : 0);
-    hipError_t e = hipMalloc(&plan->mem_meta, mbytes ? mbytes : kAlign);
-    if (e != hipSuccess) { (void)hipGetLastError(); g.last_hip_error = (int)e; delete plan; return TUNA_ERR_NOMEM; }
-    Carver cm(plan->mem_meta, mbytes);
+    Carver cm(meta, mbytes);
     int32_t* cur = cm.take<int32_t>(P2);
     int32_t* nxt = cm.take<int32_t>(P2);
     pr.rank_bytes = cm.take<unsigned long long>(P);
@@ -709,27 +718,28 @@ int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* s
     }
     if (pr.exact_t) carve_exact_t(cm, pl, true, pr);
     if (any_one_kernel_phase(pr)) pr.sdispls_t = cm.take<int64_t>(P2);
-    auto fail = [&](int code) { (void)hipFree(plan->mem_meta); if (plan->mem_data) (void)hipFree(plan->mem_data); delete plan; return code; };
-    if (!cm.ok) return fail(TUNA_ERR_NOMEM);
+    if (!cm.ok) return TUNA_ERR_WORKSPACE_TOO_SMALL;
     const dim3 grot((unsigned)((P + 255) / 256), (unsigned)((P + kExchangeRanks - 1) / kExchangeRanks));
-    hipLaunchKernelGGL(k_rotate_init, grot, dim3(256), 0, s, sendcounts, cur, P, pr.Q, pr.N);
-    if (hipGetLastError() != hipSuccess) return fail(TUNA_ERR_HIP);
-    rc = launch_transpose_displs(pr, s);
-    if (rc != TUNA_OK) return fail(rc);
+    hipLaunchKernelGGL(k_rotate_init, grot, dim3(256), 0, s, pr.sendcounts, cur, P, pr.Q, pr.N);
+    HIPCHK(hipGetLastError());
+    int rc = launch_transpose_displs(pr, s);
+    if (rc != TUNA_OK) return rc;
+    if (with_marks) mark(s, kCatPrepare, -1);
     for (size_t i = 0; i < nph; ++i) {
         rc = launch_phase_metadata(pr, i, cur, nxt, plan->Ls[i], plan->Lr[i], s);
-        if (rc != TUNA_OK) return fail(rc);
+        if (rc != TUNA_OK) return rc;
+        if (with_marks) mark(s, kCatMeta, (int)i);
         std::swap(cur, nxt);
     }
     // exact unit counts and staged chunks per phase
     std::vector<int> nu(2 * nph, 0);
     for (size_t i = 0; i < nph; ++i) {
         const bool one = phase_is_one_kernel(pr, pl.phases[i]);
-        if (hipMemcpyAsync(&nu[2 * i], plan->Lr[i].n_units, 4, hipMemcpyDeviceToHost, s) != hipSuccess) return fail(TUNA_ERR_HIP);
-        if (!one && hipMemcpyAsync(&nu[2 * i + 1], plan->Ls[i].n_units, 4, hipMemcpyDeviceToHost, s) != hipSuccess) return fail(TUNA_ERR_HIP);
+        HIPCHK(hipMemcpyAsync(&nu[2 * i], plan->Lr[i].n_units, 4, hipMemcpyDeviceToHost, s));
+        if (!one) HIPCHK(hipMemcpyAsync(&nu[2 * i + 1], plan->Ls[i].n_units, 4, hipMemcpyDeviceToHost, s));
     }
-    if (hipMemcpyAsync(g.h_status, g.d_status, sizeof(Status), hipMemcpyDeviceToHost, s) != hipSuccess) return fail(TUNA_ERR_HIP);
-    if (hipStreamSynchronize(s) != hipSuccess) return fail(TUNA_ERR_HIP);
+    HIPCHK(hipMemcpyAsync(g.h_status, g.d_status, sizeof(Status), hipMemcpyDeviceToHost, s));
+    HIPCHK(hipStreamSynchronize(s));
     unsigned long long max_chunks = 0;
     for (size_t i = 0; i < nph; ++i) {
         plan->units[i] = (size_t)std::max(nu[2 * i], nu[2 * i + 1]);
@@ -741,19 +751,61 @@ int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* s
     }
     // payload memory: staging sized by the largest phase; T by M and the slot count, or -- exact
     // size -- one arena per phase that holds just the blocks that phase stores into T
-    const size_t stage_bytes = align_up((size_t)max_chunks * 16);
-    const size_t dbytes = 2 * stage_bytes + (pr.ds.t_bytes ? align_up(pr.ds.t_bytes + kTailSlack) : 0);
+    // (phase_chunks is the send side's total; the receive side holds the same blocks, but every rank's
+    // region is rounded up to a line on its own, so its total may be up to one line per rank larger)
+    *stage_bytes = max_chunks ? align_up(((size_t)max_chunks + (size_t)P * kRankAlignChunks) * 16) : 0;
+    *dbytes = 2 * *stage_bytes + (pr.ds.t_bytes ? align_up(pr.ds.t_bytes + kTailSlack) : 0);
+    plan->stats.temp_bytes = (int64_t)pr.ds.t_bytes;
+    plan->stats.staging_bytes = (int64_t)(2 * *stage_bytes);
+    plan->stats.workspace_bytes = (int64_t)(mbytes + *dbytes);
+    return TUNA_OK;
+}
+
+void plan_carve_data(Plan* plan, void* data, size_t stage_bytes, size_t dbytes) {
+    Prepared& pr = plan->pr;
+    Carver cd(data, dbytes);
+    pr.stage_s = cd.take<v4u>(stage_bytes / 16);
+    pr.stage_r = cd.take<v4u>(stage_bytes / 16);
+    pr.T = cd.take<unsigned char>(pr.ds.t_bytes ? pr.ds.t_bytes + kTailSlack : 0);
+}
+
+// The payload kernels of every phase, with exact grids.
+int plan_launch_data(const Plan* plan, hipStream_t s) {
+    const Prepared& pr = plan->pr;
+    int rc = launch_self_copy(pr, s);
+    if (rc != TUNA_OK) return rc;
+    mark(s, kCatSelf, -1);
+    const size_t nph = pr.dp->host.phases.size();
+    for (size_t i = 0; i < nph; ++i) {
+        rc = launch_phase_data(pr, i, plan->Ls[i], plan->Lr[i], plan->units[i], s);
+        if (rc != TUNA_OK) return rc;
+    }
+    return TUNA_OK;
+}
+
+int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
+                const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
+                hipStream_t s, Plan** out) {
+    Plan* plan = new Plan();
+    Prepared& pr = plan->pr;
+    Status hs{};
+    int rc = prepare_call(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node, rl, rg, s,
+                          pr, hs, &plan->empty);
+    if (rc != TUNA_OK) { delete plan; return rc; }
+    fill_stats_header(pr, hs, plan->stats);
+    if (plan->empty) { ++g.live_plans; *out = plan; return TUNA_OK; }
+    const size_t mbytes = plan_meta_bytes(pr);
+    hipError_t e = hipMalloc(&plan->mem_meta, mbytes ? mbytes : kAlign);
+    if (e != hipSuccess) { (void)hipGetLastError(); g.last_hip_error = (int)e; delete plan; return TUNA_ERR_NOMEM; }
+    auto fail = [&](int code) { (void)hipFree(plan->mem_meta); if (plan->mem_data) (void)hipFree(plan->mem_data); delete plan; return code; };
+    size_t stage_bytes = 0, dbytes = 0;
+    rc = plan_build_metadata(plan, plan->mem_meta, mbytes, s, /*with_marks=*/false, &stage_bytes, &dbytes);
+    if (rc != TUNA_OK) return fail(rc == TUNA_ERR_WORKSPACE_TOO_SMALL ? TUNA_ERR_NOMEM : rc);
     if (dbytes) {
         e = hipMalloc(&plan->mem_data, dbytes);
         if (e != hipSuccess) { (void)hipGetLastError(); g.last_hip_error = (int)e; return fail(TUNA_ERR_NOMEM); }
-        Carver cd(plan->mem_data, dbytes);
-        pr.stage_s = cd.take<v4u>(stage_bytes / 16);
-        pr.stage_r = cd.take<v4u>(stage_bytes / 16);
-        pr.T = cd.take<unsigned char>(pr.ds.t_bytes ? pr.ds.t_bytes + kTailSlack : 0);
+        plan_carve_data(plan, plan->mem_data, stage_bytes, dbytes);
     }
-    plan->stats.temp_bytes = (int64_t)pr.ds.t_bytes;
-    plan->stats.staging_bytes = (int64_t)(2 * stage_bytes);
-    plan->stats.workspace_bytes = (int64_t)(mbytes + dbytes);
     ++g.live_plans;
     *out = plan;
     return TUNA_OK;
@@ -768,20 +820,55 @@ int plan_start(Plan* plan, hipStream_t s) {
     if (plan->empty) { g.have_stats = true; return TUNA_OK; }
     mark(s, -1, -1);
     mark(s, kCatPrepare, -1);
-    const Prepared& pr = plan->pr;
-    int rc = launch_self_copy(pr, s);
+    int rc = plan_launch_data(plan, s);
     if (rc != TUNA_OK) return rc;
-    mark(s, kCatSelf, -1);
-    const size_t nph = pr.dp->host.phases.size();
-    for (size_t i = 0; i < nph; ++i) {
-        mark(s, kCatMeta, (int)i);
-        rc = launch_phase_data(pr, i, plan->Ls[i], plan->Lr[i], plan->units[i], s);
-        if (rc != TUNA_OK) return rc;
-    }
     if (g.opt_profile) {
         HIPCHK(hipEventRecord(g.ev_end, s));
         g.end_recorded = true;
     }
+    g.have_stats = true;
+    return TUNA_OK;
+}
+
+// An immediate call in two passes: every phase's metadata first, one more read-back, then the
+// payload kernels with exact grids and staging sized by the largest phase -- a transient plan in
+// the library's (or the caller's) workspace.  Worth the second synchronisation when the payload
+// is large and the schedule has several phases: the one-pass form launches every copy kernel for
+// an upper bound of units, most of which are empty at small radices.
+int run_two_pass(const Prepared& prepared, hipStream_t s) {
+    Plan plan;
+    plan.pr = prepared;
+    plan.stats = g.stats;
+    const size_t mbytes = plan_meta_bytes(plan.pr);
+    void* mbase = nullptr;
+    int rc;
+    if (g.user_ws) {
+        if (mbytes > g.user_ws_bytes) return TUNA_ERR_WORKSPACE_TOO_SMALL;
+        mbase = g.user_ws;
+    } else {
+        rc = grow(&g.meta, &g.meta_bytes, mbytes);
+        if (rc != TUNA_OK) return rc;
+        mbase = g.meta;
+    }
+    size_t stage_bytes = 0, dbytes = 0;
+    rc = plan_build_metadata(&plan, mbase, mbytes, s, /*with_marks=*/true, &stage_bytes, &dbytes);
+    if (rc != TUNA_OK) return rc;
+    void* dbase = nullptr;
+    if (g.user_ws) {
+        if (mbytes + dbytes > g.user_ws_bytes) return TUNA_ERR_WORKSPACE_TOO_SMALL;
+        dbase = (char*)g.user_ws + mbytes;
+    } else if (dbytes) {
+        rc = grow(&g.data, &g.data_bytes, dbytes);
+        if (rc != TUNA_OK) return rc;
+        dbase = g.data;
+    }
+    if (dbytes) plan_carve_data(&plan, dbase, stage_bytes, dbytes);
+    g.stats = plan.stats;
+    mark(s, kCatPrepare, -1);                     // the read-back between the passes counts as preparation
+    rc = plan_launch_data(&plan, s);
+    if (rc != TUNA_OK) return rc;
+    HIPCHK(hipEventRecord(g.ev_end, s));
+    g.end_recorded = true;
     g.have_stats = true;
     return TUNA_OK;
 }
@@ -860,6 +947,14 @@ int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node, i
                                         exact_t, g.h_status->t_chunks);
     *bytes = meta_bytes_for(P) + (exact_t ? exact_t_meta_bytes_for(pl, false) : 0) +
              ((g.opt_fused || staggered) ? align_up((size_t)P * P * 8) : 0) + ds.total;
+    if (use_two_pass(pl, *g.h_status)) {
+        // the two-pass form keeps every phase's layouts; its staging is at most the one-pass form's
+        Prepared pr;
+        pr.P = P; pr.Q = Q; pr.N = N; pr.dp = dp; pr.ds = ds; pr.exact_t = exact_t;
+        pr.fused = g.opt_fused != 0; pr.staggered = staggered;
+        *bytes = plan_meta_bytes(pr) + (pr.fused ? 0 : 2 * align_up(ds.stage_chunks * 16)) +
+                 (ds.t_bytes ? align_up(ds.t_bytes + kTailSlack) : 0);
+    }
     return TUNA_OK;
 }
 

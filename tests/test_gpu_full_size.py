@@ -84,6 +84,67 @@ def test_config3_full_hierarchical(tuna):
     assert (st.Q, st.N, st.K_local, st.K_global) == (16, 64, 6, 16 * 63)     # the last mode run is the staggered one
 
 
+def test_config3_caller_workspace_and_phase_times(tuna):
+    """A call of this size is made in two passes (all metadata, a second read-back, then the payload
+    kernels with exact grids).  Here it runs in a caller-owned workspace of tuna_workspace_bytes bytes,
+    with per-kernel timing on: same bytes as the oracle, every stage of every phase timed, and the
+    workspace it reports fits the one that was asked for."""
+    c = wl.CONFIGS[3]
+    P = c.P
+    lay = wl.make_layout(wl.make_counts(3))
+    send_host = wl.float32_bit_patterns(lay.send_bytes, c.seed)
+    want = np.zeros(lay.recv_bytes, dtype=np.uint8)
+    assert oracle.alltoallv(send_host, lay.sendcounts, lay.sdispls, want, lay.recvcounts, lay.rdispls) == 0
+    want_dev = torch.from_numpy(want).to("cuda:0")
+    send = torch.from_numpy(send_host).to("cuda:0")
+    recv = torch.empty(lay.recv_bytes, dtype=torch.uint8, device="cuda:0")
+    sc, sd, rc, rd = _upload(lay)
+    for fused in (0, 1):
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, fused)
+        code, need = tuna.tuna_workspace_bytes(sc, P, c.ranks_per_node, c.local_radix, 8)
+        assert code == 0 and need > 0
+        ws = torch.empty(need + 256, dtype=torch.uint8, device="cuda:0")
+        base = (ws.data_ptr() + 255) // 256 * 256
+        assert tuna.tuna_set_workspace(base, need) == 0
+        tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 1)
+        try:
+            recv.zero_()
+            print("config 3, caller workspace of %d bytes, fused=%d" % (need, fused), flush=True)
+            code = tuna.tuna_alltoallv_hier(send, sc, sd, recv, rc, rd, P, c.ranks_per_node, c.local_radix, 8)
+            assert code == 0, tuna.tuna_strerror(code)
+            st = tuna.tuna_get_stats()
+            torch.cuda.synchronize()
+            assert torch.equal(recv, want_dev)
+            assert 0 < st.workspace_bytes <= need
+            assert st.n_phases == 4 and st.ms_total > 0
+            for x in range(st.n_phases):
+                ph = st.phase[x]
+                assert ph.ms_metadata > 0 and ph.ms_pack > 0
+                assert (ph.ms_exchange > 0 and ph.ms_unpack > 0) or fused
+            # the same exchange as a persistent plan (its staging is sized by the largest phase)
+            tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 0)
+            assert tuna.tuna_set_workspace(None, 0) == 0
+            code, plan = tuna.tuna_alltoallv_init(send, sc, sd, recv, rc, rd, P, c.ranks_per_node, c.local_radix, 2)
+            assert code == 0, tuna.tuna_strerror(code)
+            recv.zero_()
+            assert tuna.tuna_start(plan) == 0
+            torch.cuda.synchronize()
+            assert torch.equal(recv, want_dev), "persistent plan, fused=%d" % fused
+            assert tuna.tuna_plan_free(plan) == 0
+            # a workspace that is too small is refused before anything moves
+            assert tuna.tuna_set_workspace(base, need // 8) == 0
+            recv.zero_()
+            code = tuna.tuna_alltoallv_hier(send, sc, sd, recv, rc, rd, P, c.ranks_per_node, c.local_radix, 8)
+            assert code == tuna.TUNA_ERR_WORKSPACE_TOO_SMALL
+            torch.cuda.synchronize()
+            assert int(recv.count_nonzero()) == 0
+        finally:
+            tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 0)
+            tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+            tuna.tuna_set_workspace(None, 0)
+        del ws
+
+
 def test_config5_full_uniform(tuna):
     c = wl.CONFIGS[5]
 
