@@ -120,7 +120,10 @@ typedef struct tuna_plan_info {
  *                   with local radix min(radix, Q) and global radix min(radix, N), N = P / Q.
  * The call validates the counts on the device, reads a few integers back (one stream
  * synchronisation), sizes or grows the workspace, then enqueues all phases on `stream` and
- * returns without waiting for them.
+ * returns without waiting for them.  Payloads of 64 MiB and more with at least two digit phases
+ * are done in two passes -- the block-size exchange and the scans of every phase first, a second
+ * read-back of the phases' exact work-list lengths, then the payload kernels -- which costs one
+ * more synchronisation and saves launching every copy kernel for an upper bound of work.
  */
 int tuna_alltoallv(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls,
                    void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls,

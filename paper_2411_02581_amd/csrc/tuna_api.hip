@@ -308,7 +308,7 @@ int phase_metadata(const PhaseLayoutArgs& a, hipStream_t s, const ExactT& x) {
     const int tbound_at = a.want_tbound ? nl : -1;
     if (a.want_tbound) list[nl++] = &a.Lt;
     hipLaunchKernelGGL(k_layout_base, dim3(nl), dim3(kScanThreads), 0, s, a.P, *list[0], *list[1], *list[2],
-                       a.phase_chunks, a.want_send ? 1 : 0, tbound_at, x, a.rank_bytes, a.phase_bytes);
+                       a.phase_chunks, a.want_send ? 1 : 0, tbound_at, x, a.rank_bytes, a.phase_bytes, a.phase_units);
     HIPCHK(hipGetLastError());
     const int lds_ints = a.nseg + 1 <= kUnitsLdsMaxInts ? a.nseg + 1 : 0;
     hipLaunchKernelGGL(k_layout_units, dim3(a.P, a.want_send ? 2 : 1), dim3(256), (size_t)lds_ints * 4, s, a.nseg, a.Lr,
@@ -490,6 +490,7 @@ int launch_phase_metadata(const Prepared& pr, size_t i, const int32_t* cur, int3
     if (pr.exact_t) { m.Lt = pr.Lt[i]; m.want_tbound = 1; m.tpos = pr.x.tpos + i * (size_t)pr.P * pr.P; }
     m.rank_bytes = pr.rank_bytes;
     m.phase_bytes = &g.d_status->phase_bytes[i]; m.phase_chunks = &g.d_status->phase_chunks[i];
+    m.phase_units = g.d_status->phase_units[i];
     m.head_displs = one_kernel ? pr.rdispls : nullptr;
     m.head_base = (unsigned int)((uintptr_t)pr.recvbuf & 15u);
     // with few ranks a launch costs more than the kernel (measured: 19 us per call at P = 16, nothing at
@@ -731,18 +732,13 @@ int plan_build_metadata(Plan* plan, void* meta, size_t mbytes, hipStream_t s, bo
         if (with_marks) mark(s, kCatMeta, (int)i);
         std::swap(cur, nxt);
     }
-    // exact unit counts and staged chunks per phase
-    std::vector<int> nu(2 * nph, 0);
-    for (size_t i = 0; i < nph; ++i) {
-        const bool one = phase_is_one_kernel(pr, pl.phases[i]);
-        HIPCHK(hipMemcpyAsync(&nu[2 * i], plan->Lr[i].n_units, 4, hipMemcpyDeviceToHost, s));
-        if (!one) HIPCHK(hipMemcpyAsync(&nu[2 * i + 1], plan->Ls[i].n_units, 4, hipMemcpyDeviceToHost, s));
-    }
+    // exact unit counts, bytes and staged chunks per phase: one read-back of the status block
     HIPCHK(hipMemcpyAsync(g.h_status, g.d_status, sizeof(Status), hipMemcpyDeviceToHost, s));
     HIPCHK(hipStreamSynchronize(s));
     unsigned long long max_chunks = 0;
     for (size_t i = 0; i < nph; ++i) {
-        plan->units[i] = (size_t)std::max(nu[2 * i], nu[2 * i + 1]);
+        const bool one = phase_is_one_kernel(pr, pl.phases[i]);
+        plan->units[i] = (size_t)std::max(g.h_status->phase_units[i][0], one ? 0u : g.h_status->phase_units[i][1]);
         plan->phase_bytes[i] = g.h_status->phase_bytes[i];
         plan->phase_chunks[i] = g.h_status->phase_chunks[i];
         plan->stats.phase[i].payload_bytes = (int64_t)plan->phase_bytes[i];

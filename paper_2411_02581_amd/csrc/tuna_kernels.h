@@ -45,6 +45,7 @@ struct Status {
     unsigned long long t_chunks;       // exact-size T: chunks stored into T over all phases
     unsigned long long phase_bytes[64];   // payload bytes moved per phase
     unsigned long long phase_chunks[64];  // staged chunks per phase
+    unsigned int phase_units[64][2];      // wave units per phase: [0] receive-side layout, [1] send-side layout
 };
 
 // The per-phase table of moving blocks on the device, one array per field (message order).
@@ -422,6 +423,7 @@ struct PhaseLayoutArgs {
     unsigned long long* rank_bytes; // [P]: payload bytes every rank moves in this phase
     unsigned long long* phase_bytes;
     unsigned long long* phase_chunks;
+    unsigned int* phase_units;      // [2]: wave units of the receive-side and of the send-side layout
     const int64_t* head_displs;
     unsigned int head_base;
 };
@@ -466,7 +468,8 @@ __device__ __forceinline__ void block_scan_batch(const int (&c)[kScanItems], int
 __device__ __forceinline__ void scan_rank_bases(int P, const LayoutDev& L, unsigned long long* phase_chunks,
                                                 long long* wc, int* wt, const ExactT* x = nullptr,
                                                 const unsigned long long* rank_bytes = nullptr,
-                                                unsigned long long* phase_bytes = nullptr) {
+                                                unsigned long long* phase_bytes = nullptr,
+                                                unsigned int* units_out = nullptr) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const int per = (P + kScanThreads - 1) / kScanThreads;
     const int p0 = min(P, tid * per), p1 = min(P, p0 + per);
@@ -513,6 +516,7 @@ __device__ __forceinline__ void scan_rank_bases(int P, const LayoutDev& L, unsig
     if (tid == 0) {
         L.rank_base[P] = totc;
         if (L.unit_base) { L.unit_base[P] = tott; *L.n_units = tott; }
+        if (units_out) *units_out = (unsigned int)tott;
         if (phase_chunks) *phase_chunks = (unsigned long long)totc;
         if (x) x->arena_end[x->phase] = arena0 + (totc + 15) / 16 * 16;
     }
@@ -641,12 +645,14 @@ __global__ void __launch_bounds__(kScanThreads) k_layout_base(int P, LayoutDev L
                                                               unsigned long long* __restrict__ phase_chunks,
                                                               int chunks_from, int tbound_at, ExactT x,
                                                               const unsigned long long* __restrict__ rank_bytes,
-                                                              unsigned long long* __restrict__ phase_bytes) {
+                                                              unsigned long long* __restrict__ phase_bytes,
+                                                              unsigned int* __restrict__ phase_units) {
     __shared__ long long wc[kScanThreads / kWave];
     __shared__ int wt[kScanThreads / kWave];
     const int which = blockIdx.x;
     scan_rank_bases(P, which == 0 ? L0 : (which == 1 ? L1 : L2), which == chunks_from ? phase_chunks : nullptr, wc, wt,
-                    which == tbound_at ? &x : nullptr, rank_bytes, which == chunks_from ? phase_bytes : nullptr);
+                    which == tbound_at ? &x : nullptr, rank_bytes, which == chunks_from ? phase_bytes : nullptr,
+                    which == tbound_at ? nullptr : phase_units + which);       // layout 0 is the receive side, 1 the send side
 }
 
 // ------------------------------------------------------------------------------------------
