@@ -15,7 +15,8 @@
  *   - Count and displacement matrices are row-major P x P, row = owning virtual rank:
  *       sendcounts[i*P + j], sdispls[i*P + j] : the block rank i sends to rank j
  *       recvcounts[j*P + i], rdispls[j*P + i] : where rank j receives the block from rank i
- *     Counts are BYTES (int32, >= 0); displacements are BYTES (int64) from `sendbuf` / `recvbuf`,
+ *     Counts are BYTES (int32, >= 0); displacements are BYTES (int64, >= 0 for every non-empty
+ *     block) from `sendbuf` / `recvbuf`,
  *     one allocation each holding all P ranks' buffers; regions may come in any order, with gaps.
  *     Receive regions must not overlap each other.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
@@ -25,7 +26,7 @@
  *   - Return value: TUNA_OK (0) or a negative TUNA_ERR_* code.  Nothing throws or aborts.  When
  *     an error is returned no payload byte has been moved.
  *   - sendbuf and recvbuf must not overlap.  The library uses the HIP device that is current at
- *     its first call.
+ *     its first call; a compute call made while another device is current returns TUNA_ERR_ARG.
  *   - The library keeps one grow-only workspace and the statistics of the last call per process;
  *     calls are not thread-safe against each other, and two calls in flight on different streams
  *     share the workspace and therefore race.
@@ -43,7 +44,8 @@ extern "C" {
 #endif
 
 #define TUNA_OK 0
-#define TUNA_ERR_ARG -1              /* null pointer, P < 1, radix < 2, ranks_per_node does not divide P */
+#define TUNA_ERR_ARG -1              /* null pointer, P < 1, radix < 2, ranks_per_node does not divide P,
+                                        a non-empty block at a negative displacement */
 #define TUNA_ERR_COUNT_MISMATCH -2   /* recvcounts[j][i] != sendcounts[i][j] for some i, j */
 #define TUNA_ERR_NEGATIVE_COUNT -3   /* a negative count */
 #define TUNA_ERR_NOMEM -4            /* the library could not allocate its workspace */

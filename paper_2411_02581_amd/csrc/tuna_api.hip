@@ -72,7 +72,13 @@ Ctx g;
 inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
 
 int ensure_ctx() {
-    if (g.ready) return TUNA_OK;
+    if (g.ready) {
+        // the workspace, the schedules and the status block live on the first call's device: refuse to
+        // launch kernels on them from another one
+        int dev = -1;
+        HIPCHK(hipGetDevice(&dev));
+        return dev == g.device ? TUNA_OK : TUNA_ERR_ARG;
+    }
     int ndev = 0;
     HIPCHK(hipGetDeviceCount(&ndev));
     if (ndev < 1) { g.last_hip_error = (int)hipErrorNoDevice; return TUNA_ERR_HIP; }
@@ -195,6 +201,13 @@ DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long tot
     return d;
 }
 
+void free_device_plan(DevicePlan& dp) {
+    for (auto* p : dp.d_seg_mem) (void)hipFree(p);
+    for (auto* p : dp.d_zt) (void)hipFree(p);
+    if (dp.d_hm1) (void)hipFree(dp.d_hm1);
+    dp.d_seg_mem.clear(); dp.d_zt.clear(); dp.d_seg.clear(); dp.d_hm1 = nullptr;
+}
+
 // Cached schedule of (P, Q, r_l, r_g, fused).  The host keeps scalars only; the per-phase tables are
 // built on the device by k_build_phase_table, on the caller's stream (the kernels that read them
 // are enqueued behind it).
@@ -211,25 +224,31 @@ int get_plan(int P, int Q, int rl, int rg, bool fused, hipStream_t s, DevicePlan
         DevicePlan dp;
         dp.host = make_plan(P, Q, crl, crg, fused, /*with_tables=*/false);
         if ((int)dp.host.phases.size() > TUNA_MAX_PHASES) return TUNA_ERR_TOO_LARGE;
+        // a schedule that cannot be completed leaves nothing behind (its kernels may be in flight: wait)
+        struct Guard {
+            DevicePlan* dp; hipStream_t s;
+            ~Guard() { if (dp) { (void)hipStreamSynchronize(s); free_device_plan(*dp); } }
+        } guard{&dp, s};
         for (auto& ph : dp.host.phases) {
             // field-major table: e[], z[], src[], dst[], srcph[], srcseg[]
             const size_t stride = align_up((size_t)ph.nseg * 4) / 4;
             int32_t* dm = nullptr;
             int32_t* dz = nullptr;
             HIPCHK(hipMalloc((void**)&dm, 6 * stride * 4 + kAlign));
+            dp.d_seg_mem.push_back(dm);
             HIPCHK(hipMalloc((void**)&dz, align_up((size_t)P * 4)));
+            dp.d_zt.push_back(dz);
             hipLaunchKernelGGL(k_build_phase_table, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, dp.host.sc,
                                phase_scalars(ph), dm, dm + stride, dm + 2 * stride, dm + 3 * stride, dm + 4 * stride,
                                dm + 5 * stride, dz);
             HIPCHK(hipGetLastError());
             dp.d_seg.push_back(SegDev{dm, dm + stride, dm + 2 * stride, dm + 3 * stride, dm + 4 * stride, dm + 5 * stride});
-            dp.d_seg_mem.push_back(dm);
-            dp.d_zt.push_back(dz);
         }
         HIPCHK(hipMalloc((void**)&dp.d_hm1, align_up((size_t)P * 4)));
         hipLaunchKernelGGL(k_build_hops, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, dp.host.sc, dp.d_hm1);
         HIPCHK(hipGetLastError());
         dp.built_on = s;
+        guard.dp = nullptr;
         it = g.plans.emplace(key, std::move(dp)).first;
     }
     // a cached schedule built on another stream: make sure its tables are complete
@@ -460,6 +479,7 @@ int prepare_call(const void* sendbuf, const int32_t* sendcounts, const int64_t* 
     if (pr.dp->built_on == s) pr.dp->complete = true;      // run_validate synchronised this stream
     if (hs.flags & 1u) return TUNA_ERR_NEGATIVE_COUNT;
     if (hs.flags & 2u) return TUNA_ERR_COUNT_MISMATCH;
+    if (hs.flags & 4u) return TUNA_ERR_ARG;                 // a non-empty block at a negative displacement
     *empty = hs.total_bytes == 0;
     if (*empty) return TUNA_OK;
     if (!sendbuf || !recvbuf) return TUNA_ERR_ARG;
@@ -905,6 +925,8 @@ int tuna_alltoallv_init(const void* sendbuf, const int32_t* sendcounts, const in
 
 int tuna_start(tuna_plan_t plan, void* stream) {
     if (!plan) return TUNA_ERR_ARG;
+    const int rc = ensure_ctx();           // the plan's memory lives on the library's device
+    if (rc != TUNA_OK) return rc;
     return plan_start(reinterpret_cast<Plan*>(plan), (hipStream_t)stream);
 }
 
@@ -980,11 +1002,7 @@ int tuna_release(void) {
     HIPCHK(hipDeviceSynchronize());
     if (g.meta) { HIPCHK(hipFree(g.meta)); g.meta = nullptr; g.meta_bytes = 0; }
     if (g.data) { HIPCHK(hipFree(g.data)); g.data = nullptr; g.data_bytes = 0; }
-    for (auto& kv : g.plans) {
-        for (auto* p : kv.second.d_seg_mem) (void)hipFree(p);
-        for (auto* p : kv.second.d_zt) (void)hipFree(p);
-        if (kv.second.d_hm1) (void)hipFree(kv.second.d_hm1);
-    }
+    for (auto& kv : g.plans) free_device_plan(kv.second);
     g.plans.clear();
     return TUNA_OK;
 }

@@ -32,10 +32,11 @@ enum CopyMode { kPack = 0, kExchange = 1, kUnpack = 2, kFused = 3 };
 constexpr int kFlagFill = 16;    // destination is a T slot: the tail lane fills up the 128-byte line
 constexpr int kFlagSrcT = 32;    // source is a T slot: reading past the block's end is always safe
 
-// Device-side status block: the validation pass writes the head, every phase its own two counters;
-// the head is read back once after validation.
+// Device-side status block: the validation pass writes the head, every phase its own entries of the
+// three arrays; the head is read back once after validation.
 struct Status {
-    unsigned int flags;            // bit 0: negative count, bit 1: recvcounts != transpose(sendcounts)
+    unsigned int flags;            // bit 0: negative count, bit 1: recvcounts != transpose(sendcounts),
+                                   // bit 2: negative displacement of a non-empty block
     unsigned int align_bits;       // OR of all counts and displacements (low bits decide the granularity)
     int max_count;                 // M
     int reserved;
@@ -162,7 +163,8 @@ __global__ void __launch_bounds__(256) k_build_hops(const PlanScalars pl, int32_
 // recvcounts == transpose(sendcounts) through an LDS tile so both matrices are read row-wise
 // (a wave reads 64 consecutive entries of one row).  With `hm1` it also sums the exact size of T:
 // ceil(count / 16) * hm1[slot index of the block] chunks over all blocks.
-// Workgroups of (64, 4) threads stride over the tiles and issue one set of atomics each.
+// A non-empty block with a negative displacement is flagged too.  Workgroups of (64, 4) threads
+// stride over the tiles and write one row of partial results each.
 // ------------------------------------------------------------------------------------------
 constexpr int kValTile = 64;
 constexpr int kValPartial = 8;              // 64-bit words per workgroup in the partial-result array
@@ -194,7 +196,10 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
                 if (sdispls) {
                     const int64_t d = sdispls[(size_t)i * P + j];
                     abits |= (unsigned int)d & 15u;
-                    if (c > 0 && d >= 0) extent = max(extent, (unsigned long long)d + (unsigned long long)c);
+                    if (c > 0) {
+                        if (d >= 0) extent = max(extent, (unsigned long long)d + (unsigned long long)c);
+                        else flags |= 4u;
+                    }
                 }
                 mx = max(mx, c);
                 bytes += (unsigned long long)c;
@@ -217,13 +222,17 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
                     int rc = recvcounts[(size_t)jr * P + i];
                     if (rc < 0) flags |= 1u;
                     else if (rc != tile[tx][a]) flags |= 2u;
-                    if (rdispls) abits |= (unsigned int)rdispls[(size_t)jr * P + i] & 15u;
+                    if (rdispls) {
+                        const int64_t d = rdispls[(size_t)jr * P + i];
+                        abits |= (unsigned int)d & 15u;
+                        if (rc > 0 && d < 0) flags |= 4u;
+                    }
                 }
             }
         }
         __syncthreads();
     }
-    // wave reduction, workgroup reduction through LDS, then one set of atomics per workgroup
+    // wave reduction, workgroup reduction through LDS, then one row of partial results per workgroup
 #pragma unroll
     for (int d = kWave / 2; d > 0; d >>= 1) {
         flags |= __shfl_xor(flags, d, kWave);

@@ -269,9 +269,27 @@ def test_errors(tuna):
     assert tuna.tuna_alltoallv(*a, 2, 0) == tuna.TUNA_ERR_NEGATIVE_COUNT
     assert tuna.tuna_alltoallv(*prob.args(), 1, 0) == tuna.TUNA_ERR_ARG
     assert tuna.tuna_alltoallv(*prob.args(), 2, 3) == tuna.TUNA_ERR_ARG       # 3 does not divide 8
+    for which in (2, 5):                                                      # sdispls, rdispls
+        cnt = prob.sendcounts if which == 2 else prob.recvcounts
+        nz = torch.nonzero(cnt)[0]
+        a = list(prob.args())
+        a[which] = a[which].clone()
+        a[which][nz[0], nz[1]] = -16                                          # a non-empty block in front of the buffer
+        assert tuna.tuna_alltoallv(*a, 2, 0) == tuna.TUNA_ERR_ARG
     torch.cuda.synchronize()
     assert (prob.recv.cpu().numpy() == CANARY).all()                          # nothing was moved
     run_flat(tuna, prob, 2)                                                    # and the library still works
+    for which in (2, 5):                                                      # an empty block may sit anywhere
+        cnt = prob.sendcounts if which == 2 else prob.recvcounts
+        z = torch.nonzero(cnt == 0)
+        if len(z) == 0:
+            continue
+        a = list(prob.args())
+        a[which] = a[which].clone()
+        a[which][z[0][0], z[0][1]] = -16
+        prob.reset()
+        assert tuna.tuna_alltoallv(*a, 2, 0) == tuna.TUNA_OK
+        prob.check("empty block at a negative displacement")
 
 
 def test_stats_phase_bytes(tuna):
