@@ -290,7 +290,8 @@ void mark(hipStream_t s, int cat, int phase) {
 template <int MODE, bool DENSE>
 int launch_copy_as(int gran, size_t unit_cap, const CopyArgs& a, hipStream_t s) {
     const size_t waves = kCopyThreads / kWave;
-    const dim3 grid((unsigned)((unit_cap + waves - 1) / waves)), block(kCopyThreads);
+    // unit_cap counts the units of the whole launch, or of one rank's row when the launch has a row per rank
+    const dim3 grid((unsigned)((unit_cap + waves - 1) / waves), a.batch_rows ? (unsigned)a.P : 1u), block(kCopyThreads);
     if (grid.x == 0) return TUNA_OK;
     if (MODE == kExchange || gran == 16) {
         hipLaunchKernelGGL((k_copy<MODE, 16, DENSE>), grid, block, 0, s, a);
@@ -560,13 +561,23 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
         const int z1 = std::min(z0 + step, ph.nz + 1);
         a.seg_lo = (int)(count_below_digit(ps, z0) * mult);
         a.seg_hi = (int)(count_below_digit(ps, z1) * mult);
+        // a batch touches few units of every rank: at most its blocks times the chunks of the largest
+        // block (one more per block when chunks are cut at destination lines), and the unit it starts
+        // in.  One grid row per rank of that width, unless the whole unit list is shorter.
+        size_t launch_units = unit_cap;
+        a.batch_rows = 0;
+        if (step < ph.nz) {
+            const size_t cmax = (size_t)(pr.max_count + 15) / 16 + 1;
+            const size_t row_units = ((size_t)(a.seg_hi - a.seg_lo) * cmax + kUnitChunks - 1) / kUnitChunks + 1;
+            if (row_units * (size_t)pr.P < unit_cap) { launch_units = row_units; a.batch_rows = 1; }
+        }
         int rc;
         if (phase_is_one_kernel(pr, ph)) {
             // one hop in one kernel: S / T of the sender -> R / the other copy of T at the receiver
             a.stage = nullptr; a.L = Lr; a.counts = pr.recvcounts;
             a.user = (unsigned char*)pr.sendbuf; a.displs = pr.sdispls_t;
             a.user2 = (unsigned char*)pr.recvbuf; a.displs2 = pr.rdispls; a.T2 = pr.T;
-            rc = launch_copy<kFused>(pr.gran, unit_cap, a, s, pr.exact_kernels);
+            rc = launch_copy<kFused>(pr.gran, launch_units, a, s, pr.exact_kernels);
             if (rc != TUNA_OK) return rc;
             mark(s, kCatPack, (int)i);
             continue;
@@ -574,17 +585,17 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
         // pack: S / T -> send staging
         a.stage = pr.stage_s; a.L = Ls; a.counts = nullptr;
         a.user = (unsigned char*)pr.sendbuf; a.displs = pr.sdispls;
-        rc = launch_copy<kPack>(pr.gran, unit_cap, a, s, pr.exact_kernels);
+        rc = launch_copy<kPack>(pr.gran, launch_units, a, s, pr.exact_kernels);
         if (rc != TUNA_OK) return rc;
         mark(s, kCatPack, (int)i);
         // exchange: send staging of the partner -> receive staging
         a.stage = pr.stage_r; a.L = Lr; a.stage_src = pr.stage_s; a.Ls = Ls;
-        rc = launch_copy<kExchange>(pr.gran, unit_cap, a, s, pr.exact_kernels);
+        rc = launch_copy<kExchange>(pr.gran, launch_units, a, s, pr.exact_kernels);
         if (rc != TUNA_OK) return rc;
         mark(s, kCatExchange, (int)i);
         // unpack: receive staging -> R / T
         a.counts = pr.recvcounts; a.user = (unsigned char*)pr.recvbuf; a.displs = pr.rdispls;
-        rc = launch_copy<kUnpack>(pr.gran, unit_cap, a, s, pr.exact_kernels);
+        rc = launch_copy<kUnpack>(pr.gran, launch_units, a, s, pr.exact_kernels);
         if (rc != TUNA_OK) return rc;
         mark(s, kCatUnpack, (int)i);
     }

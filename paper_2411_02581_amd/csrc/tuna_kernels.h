@@ -713,7 +713,8 @@ __global__ void __launch_bounds__(256) k_layout_units(int nseg, LayoutDev Lr, La
 // by a binary search over that window.  Lanes of a wave touch consecutive chunks on the staging
 // side (aligned, non-temporal dwordx4) and consecutive bytes of a block on the other side.
 // One-shot grid: 4 units per workgroup; the host launches an upper bound of units and waves
-// beyond the device-side unit count exit at once.
+// beyond the device-side unit count exit at once.  A launch for a batch of rounds may instead use
+// one grid row per rank, as wide as the units a rank can have in the batch.
 // ------------------------------------------------------------------------------------------
 struct CopyArgs {
     // tiled (staging) side
@@ -740,6 +741,9 @@ struct CopyArgs {
     ExactT x;
     // a launch may cover only the rounds of one batch: the segments [seg_lo, seg_hi) of every rank
     int seg_lo, seg_hi;
+    // 1: such a launch has a grid of (units a rank can have in the batch / 4, P) -- row y covers the units
+    // of rank y that overlap the batch; 0: one-dimensional grid over all units
+    int batch_rows;
     int P, Q, N, dim, rx;
 };
 
@@ -827,8 +831,17 @@ k_copy(const CopyArgs a) {
     __shared__ int s_flag[kCopyThreads / kWave][kWave];
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const int unit = blockIdx.x * (kCopyThreads / kWave) + wv;
-    if (unit >= *a.L.n_units) return;            // no barrier below: a wave may leave alone
+    int unit = blockIdx.x * (kCopyThreads / kWave) + wv;
+    if (a.batch_rows) {
+        // the batch's chunks [lo, hi) of rank blockIdx.y lie in its units lo / 256 .. (hi - 1) / 256
+        const int* brow = a.L.pre + (size_t)blockIdx.y * a.L.ld;
+        const int lo = brow[a.seg_lo], hi = brow[a.seg_hi];
+        const int u = lo / kUnitChunks + unit;
+        if (hi <= lo || (long long)u * kUnitChunks >= hi) return;
+        unit = a.L.unit_base[blockIdx.y] + u;
+    } else if (unit >= *a.L.n_units) {
+        return;                                  // no barrier below: a wave may leave alone
+    }
     const int4 ud = a.L.units[unit];
     const int p = __builtin_amdgcn_readfirstlane(ud.x);
     int sw = __builtin_amdgcn_readfirstlane(ud.y);

@@ -181,13 +181,15 @@ def test_config4_full(tuna):
     send_sum = int(send.view(torch.int32).sum(dtype=torch.int64))
     counts_w = (sc.to(torch.int64) // 4)                      # [i, j] words of block i -> j
     sd_w = sd // 4
-    # (radix, fused rounds, persistent plan, T in slots of M bytes instead of exact size)
-    cases = [(r, 0, 0, 0) for r in c.radices] + [(2, 1, 0, 0), (4096, 1, 0, 0), (2, 0, 0, 1), (8, 1, 0, 1),
-                                                  (2, 0, 1, 0), (8, 1, 1, 0)]
-    for r, fused, persistent, slots in cases:
+    # (radix, fused rounds, persistent plan, T in slots of M bytes instead of exact size, rounds per batch)
+    cases = [(r, 0, 0, 0, 0) for r in c.radices] + [(2, 1, 0, 0, 0), (4096, 1, 0, 0, 0), (2, 0, 0, 1, 0), (8, 1, 0, 1, 0),
+                                                     (2, 0, 1, 0, 0), (8, 1, 1, 0, 0), (4096, 0, 0, 0, 300), (64, 1, 1, 0, 5)]
+    for r, fused, persistent, slots, batch in cases:
         recv.zero_()
-        print("config 4 full size, radix=%d fused=%d persistent=%d slots-of-M=%d" % (r, fused, persistent, slots), flush=True)
+        print("config 4 full size, radix=%d fused=%d persistent=%d slots-of-M=%d block_count=%d" %
+              (r, fused, persistent, slots, batch), flush=True)
         tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, fused)
+        tuna.tuna_set_option(tuna.TUNA_OPT_BLOCK_COUNT, batch)
         tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 0 if slots else 1)
         if persistent:
             assert tuna.tuna_release() == 0                # the immediate calls' workspace is not needed here
@@ -200,6 +202,7 @@ def test_config4_full(tuna):
             code = tuna.tuna_alltoallv(send, sc, sd, recv, rc, rd, P, r, 0)
         tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 2)
         tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_BLOCK_COUNT, 0)
         assert code == 0, tuna.tuna_strerror(code)
         assert tuna.tuna_get_stats().dense_t == (0 if slots else 1)
         torch.cuda.synchronize()
