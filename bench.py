@@ -47,6 +47,9 @@ def parse_args():
     ap.add_argument("--config", type=int, default=4, help="workload configuration 1..5")
     ap.add_argument("--ranks", type=int, default=0, help="override P (reduced-size runs)")
     ap.add_argument("--radices", type=str, default="", help="comma-separated radix sweep")
+    ap.add_argument("--element-bytes", type=int, default=8,
+                    help="element size of --uniform-max-bytes (8 = the paper's FP64; 16 makes every count and "
+                         "displacement a multiple of the 16-byte chunk)")
     ap.add_argument("--uniform-max-bytes", type=int, default=0,
                     help="replace the configuration's counts by 8 * U{0..S/8} bytes (the paper's uniform [0, S] "
                          "micro-benchmark with FP64 elements); use with --ranks and --radices")
@@ -98,7 +101,7 @@ def main():
     P = args.ranks or cfg.P
     t0 = time.time()
     if args.uniform_max_bytes:
-        counts = wl.counts_uniform_elements(P, cfg.seed, args.uniform_max_bytes // 8, 8)
+        counts = wl.counts_uniform_elements(P, cfg.seed, args.uniform_max_bytes // args.element_bytes, args.element_bytes)
     else:
         counts = wl.make_counts(args.config, P)
     lay = wl.make_layout(counts)
@@ -296,7 +299,7 @@ def main():
         exact_used = bool(per_radix[0]["exact_size_t"])
         et = "true" if exact_used else "false"
         kname = {"pack": "tuna::k_copy<0, %d, %s>" % (gran, et), "exchange": "tuna::k_copy<1, 16, false>",
-                 "unpack": "tuna::k_copy<2, %d, %s>" % (gran, et), "fused": "tuna::k_copy<3, %d, %s>" % (gran, et)}[name]
+                 "unpack": "tuna::k_copy<2, %d, %s>" % (min(gran, 16), et), "fused": "tuna::k_copy<3, %d, %s>" % (gran, et)}[name]
         default_run = (args.config == 4 and P == 4096 and not args.radices)
         traffic = MEASURED_TRAFFIC_CONFIG4[exact_used].get(name) if default_run else None
         achieved = alg / (ms * 1e-3) / 1e9
@@ -325,7 +328,7 @@ def main():
         "value": best["effective_GBs"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": best["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u8", "data": "synthetic",
-        "config": {"workload": ("uniform [0, %d] bytes in FP64 elements, P=%d flat" % (args.uniform_max_bytes, P))
+        "config": {"workload": ("uniform [0, %d] bytes in %d-byte elements, P=%d flat" % (args.uniform_max_bytes, args.element_bytes, P))
                                if args.uniform_max_bytes else "config %d: %s" % (args.config, cfg.description), "P": P,
                    "payload_bytes": Btot, "best_radix": best["radix"], "fused": bool(args.fused),
                    "exact_size_t": bool(per_radix[0]["exact_size_t"]), "t_layout_option": args.exact_t, "block_count": args.block_count,

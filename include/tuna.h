@@ -79,7 +79,7 @@ typedef struct tuna_stats {
     int32_t K_local, K_global;       /* point-to-point rounds */
     int32_t B_local, B_global;       /* T slots of the paper's bound, B = size - (K + 1), per dimension */
     int32_t n_phases;
-    int32_t granularity;             /* 16, 4 or 1: common divisor of all counts/displacements/base addresses */
+    int32_t granularity;             /* 128, 16, 4 or 1: common divisor of all counts/displacements/base addresses */
     int32_t fused;                   /* 1 when the fused single-kernel rounds were used */
     int32_t last_hip_error;
     int32_t dense_t;                 /* 1 when T was addressed in exact size, 0 in slots of M bytes (TUNA_OPT_DENSE_T) */

@@ -293,7 +293,9 @@ int launch_copy_as(int gran, size_t unit_cap, const CopyArgs& a, hipStream_t s) 
     // unit_cap counts the units of the whole launch, or of one rank's row when the launch has a row per rank
     const dim3 grid((unsigned)((unit_cap + waves - 1) / waves), a.batch_rows ? (unsigned)a.P : 1u), block(kCopyThreads);
     if (grid.x == 0) return TUNA_OK;
-    if (MODE == kExchange || gran == 16) {
+    if ((MODE == kPack || MODE == kFused) && gran == 128) {
+        hipLaunchKernelGGL((k_copy<MODE, 128, DENSE>), grid, block, 0, s, a);      // sources are whole lines
+    } else if (MODE == kExchange || gran >= 16) {
         hipLaunchKernelGGL((k_copy<MODE, 16, DENSE>), grid, block, 0, s, a);
     } else if (gran == 4) {
         hipLaunchKernelGGL((k_copy<MODE, 4, DENSE>), grid, block, 0, s, a);
@@ -491,9 +493,9 @@ int prepare_call(const void* sendbuf, const int32_t* sendcounts, const int64_t* 
         if ((hs.total_chunks + (unsigned long long)P < by_m ? hs.total_chunks + (unsigned long long)P : by_m) >= (1ull << 31))
             return TUNA_ERR_TOO_LARGE;
     }
-    const unsigned int abits = hs.align_bits | (unsigned int)((uintptr_t)sendbuf & 15u) |
-                               (unsigned int)((uintptr_t)recvbuf & 15u);
-    pr.gran = (abits & 15u) == 0 ? 16 : ((abits & 3u) == 0 ? 4 : 1);
+    const unsigned int abits = hs.align_bits | (unsigned int)((uintptr_t)sendbuf & 127u) |
+                               (unsigned int)((uintptr_t)recvbuf & 127u);
+    pr.gran = (abits & 127u) == 0 ? 128 : ((abits & 15u) == 0 ? 16 : ((abits & 3u) == 0 ? 4 : 1));
     pr.max_count = hs.max_count;
     pr.user_limit = (unsigned long long)(uintptr_t)sendbuf + hs.send_extent;
     pr.ds = data_sizes_for(pr.dp->host, hs.max_count, hs.total_chunks, pr.fused, pr.staggered, pr.exact_t, hs.t_chunks);

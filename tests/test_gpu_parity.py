@@ -106,9 +106,9 @@ def test_small_every_radix(tuna, P):
     run_flat(tuna, prob, P + 9)       # clamps to P
 
 
-@pytest.mark.parametrize("align,quantum", [(1, 1), (4, 4), (16, 16)])
+@pytest.mark.parametrize("align,quantum", [(1, 1), (4, 4), (16, 16), (128, 128)])
 def test_granularities(tuna, align, quantum):
-    """The three copy paths: 16-byte, 4-byte and byte granular sizes/displacements."""
+    """The copy paths: whole-line, 16-byte, 4-byte and byte granular sizes/displacements."""
     P = 48
     counts = (wl.counts_uniform_bytes(P, 5, 3000) // quantum * quantum).astype(np.int32)
     lay = wl.make_layout(counts, gap=quantum, align=align)
@@ -157,7 +157,7 @@ def test_config5_reduced_uniform(tuna):
     assert np.array_equal(prob.want.reshape(P, P, 256), send.reshape(P, P, 256).transpose(1, 0, 2))
     for r in (2, 16, 2048):
         run_flat(tuna, prob, r, rpn=Q)
-        assert tuna.tuna_get_stats().granularity == 16
+        assert tuna.tuna_get_stats().granularity == 128
 
 
 @pytest.mark.parametrize("Q,N", [(1, 6), (2, 3), (3, 2), (4, 4), (5, 3), (3, 7), (8, 2), (6, 10)])
