@@ -287,20 +287,43 @@ void mark(hipStream_t s, int cat, int phase) {
 
 // One-shot grid over an upper bound of wave units (4 per workgroup); waves past the device-side
 // unit count exit immediately.
+// Dynamic LDS that leaves room for `resident` workgroups of a copy kernel per compute unit (one wave
+// per SIMD each; 8 is the kernels' own limit).  Nothing uses the memory: it only caps the occupancy.
+// static_lds: the kernel's own LDS bytes.
+size_t occupancy_padding(int resident, size_t static_lds) {
+    constexpr size_t kLdsPerCu = 160 * 1024;
+    if (resident >= 8) return 0;
+    // more than 1 / (resident + 1) of the LDS each, rounded up to 1 KiB: resident + 1 workgroups no longer fit
+    const size_t want = (kLdsPerCu / (size_t)(resident + 1) / 1024 + 1) * 1024;
+    return want > static_lds ? want - static_lds : 0;
+}
+
+template <class K>
+size_t static_lds_of(K kernel) {
+    hipFuncAttributes at{};
+    if (hipFuncGetAttributes(&at, reinterpret_cast<const void*>(kernel)) != hipSuccess) { (void)hipGetLastError(); return 0; }
+    return at.sharedSizeBytes;
+}
+
+// resident: workgroups per compute unit the launch may keep resident (see occupancy_padding)
 template <int MODE, bool DENSE>
-int launch_copy_as(int gran, size_t unit_cap, const CopyArgs& a, hipStream_t s) {
+int launch_copy_as(int gran, size_t unit_cap, const CopyArgs& a, hipStream_t s, int resident) {
     const size_t waves = kCopyThreads / kWave;
     // unit_cap counts the units of the whole launch, or of one rank's row when the launch has a row per rank
     const dim3 grid((unsigned)((unit_cap + waves - 1) / waves), a.batch_rows ? (unsigned)a.P : 1u), block(kCopyThreads);
     if (grid.x == 0) return TUNA_OK;
     if ((MODE == kPack || MODE == kFused) && gran == 128) {
-        hipLaunchKernelGGL((k_copy<MODE, 128, DENSE>), grid, block, 0, s, a);      // sources are whole lines
+        static const size_t lds = static_lds_of(k_copy<MODE, 128, DENSE>);
+        hipLaunchKernelGGL((k_copy<MODE, 128, DENSE>), grid, block, occupancy_padding(resident, lds), s, a);   // sources are whole lines
     } else if (MODE == kExchange || gran >= 16) {
-        hipLaunchKernelGGL((k_copy<MODE, 16, DENSE>), grid, block, 0, s, a);
+        static const size_t lds = static_lds_of(k_copy<MODE, 16, DENSE>);
+        hipLaunchKernelGGL((k_copy<MODE, 16, DENSE>), grid, block, occupancy_padding(resident, lds), s, a);
     } else if (gran == 4) {
-        hipLaunchKernelGGL((k_copy<MODE, 4, DENSE>), grid, block, 0, s, a);
+        static const size_t lds = static_lds_of(k_copy<MODE, 4, DENSE>);
+        hipLaunchKernelGGL((k_copy<MODE, 4, DENSE>), grid, block, occupancy_padding(resident, lds), s, a);
     } else {
-        hipLaunchKernelGGL((k_copy<MODE, 1, DENSE>), grid, block, 0, s, a);
+        static const size_t lds = static_lds_of(k_copy<MODE, 1, DENSE>);
+        hipLaunchKernelGGL((k_copy<MODE, 1, DENSE>), grid, block, occupancy_padding(resident, lds), s, a);
     }
     HIPCHK(hipGetLastError());
     return TUNA_OK;
@@ -309,9 +332,9 @@ int launch_copy_as(int gran, size_t unit_cap, const CopyArgs& a, hipStream_t s) 
 // exact_kernels: the variant that addresses T in exact size (it never looks at its T arguments when
 // the schedule has no T-bound block, so it also serves schedules without T)
 template <int MODE>
-int launch_copy(int gran, size_t unit_cap, const CopyArgs& a, hipStream_t s, bool exact_kernels) {
-    if (MODE != kExchange && exact_kernels) return launch_copy_as<MODE, true>(gran, unit_cap, a, s);
-    return launch_copy_as<MODE, false>(gran, unit_cap, a, s);
+int launch_copy(int gran, size_t unit_cap, const CopyArgs& a, hipStream_t s, bool exact_kernels, int resident = 8) {
+    if (MODE != kExchange && exact_kernels) return launch_copy_as<MODE, true>(gran, unit_cap, a, s, resident);
+    return launch_copy_as<MODE, false>(gran, unit_cap, a, s, resident);
 }
 
 // Metadata of one digit phase: sizes exchanged, both staging layouts scanned, wave units cut.
@@ -379,6 +402,7 @@ struct Prepared {
     const int64_t* rdispls = nullptr;
     unsigned long long user_limit = 0;
     int max_count = 0;
+    unsigned long long total_bytes = 0;
     DataSizes ds{};
     v4u* stage_s = nullptr;
     v4u* stage_r = nullptr;
@@ -497,6 +521,7 @@ int prepare_call(const void* sendbuf, const int32_t* sendcounts, const int64_t* 
                                (unsigned int)((uintptr_t)recvbuf & 127u);
     pr.gran = (abits & 127u) == 0 ? 128 : ((abits & 15u) == 0 ? 16 : ((abits & 3u) == 0 ? 4 : 1));
     pr.max_count = hs.max_count;
+    pr.total_bytes = hs.total_bytes;
     pr.user_limit = (unsigned long long)(uintptr_t)sendbuf + hs.send_extent;
     pr.ds = data_sizes_for(pr.dp->host, hs.max_count, hs.total_chunks, pr.fused, pr.staggered, pr.exact_t, hs.t_chunks);
     return TUNA_OK;
@@ -556,6 +581,19 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
     // rounds z0 .. z1-1 of a phase are the segments [below(z0), below(z1)) of every rank's message order
     const PhaseScalars ps = phase_scalars(ph);
     const long long mult = ph.dim == 0 ? pr.N : pr.Q;
+    // Resident workgroups per compute unit of the three-stage kernels, measured on MI355X: launches that
+    // move little (under 2 GiB) or short pieces (under 2 KiB) are fastest with all 8 -- 3 to 5 % over 6
+    // -- and long launches over long pieces with 6 (8 loses 4 % in pack, up to 9 % in the exchange and
+    // up to 14 % in unpack).  A piece is a block for pack and unpack and a message for the exchange;
+    // sizes are estimated from the mean block.  The one-kernel phases hold 7 by their registers and
+    // are indifferent between 6 and 8.
+    const double mean_block = (double)pr.total_bytes / ((double)pr.P * (double)pr.P);
+    const bool short_launch = mean_block * (double)ph.nseg * (double)pr.P < 2.0 * 1024 * 1024 * 1024;
+    const int block_resident = (short_launch || mean_block < 2048.0) ? 8 : 6;
+    // pack also prefers 6 when it reads from slots of M bytes that are mostly empty (1 KiB blocks in 2.4 KiB slots: 7 %)
+    const bool sparse_slots = !pr.exact_t && pr.ds.slots > 0 && mean_block < 0.9 * (double)pr.ds.slot_bytes;
+    const int pack_resident = (!short_launch && sparse_slots) ? 6 : block_resident;
+    const int exchange_resident = (short_launch || mean_block * (double)ph.nseg / (double)ph.nz < 2048.0) ? 8 : 6;
     int per_batch = pr.block_count;                  // the staggered schedule counts single-block rounds: Q per node distance
     if (per_batch > 0 && pr.staggered && ph.dim == 1) per_batch = std::max(1, per_batch / pr.Q);
     const int step = (per_batch > 0 && per_batch < ph.nz) ? per_batch : ph.nz;
@@ -587,17 +625,17 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
         // pack: S / T -> send staging
         a.stage = pr.stage_s; a.L = Ls; a.counts = nullptr;
         a.user = (unsigned char*)pr.sendbuf; a.displs = pr.sdispls;
-        rc = launch_copy<kPack>(pr.gran, launch_units, a, s, pr.exact_kernels);
+        rc = launch_copy<kPack>(pr.gran, launch_units, a, s, pr.exact_kernels, pack_resident);
         if (rc != TUNA_OK) return rc;
         mark(s, kCatPack, (int)i);
         // exchange: send staging of the partner -> receive staging
         a.stage = pr.stage_r; a.L = Lr; a.stage_src = pr.stage_s; a.Ls = Ls;
-        rc = launch_copy<kExchange>(pr.gran, launch_units, a, s, pr.exact_kernels);
+        rc = launch_copy<kExchange>(pr.gran, launch_units, a, s, pr.exact_kernels, exchange_resident);
         if (rc != TUNA_OK) return rc;
         mark(s, kCatExchange, (int)i);
         // unpack: receive staging -> R / T
         a.counts = pr.recvcounts; a.user = (unsigned char*)pr.recvbuf; a.displs = pr.rdispls;
-        rc = launch_copy<kUnpack>(pr.gran, launch_units, a, s, pr.exact_kernels);
+        rc = launch_copy<kUnpack>(pr.gran, launch_units, a, s, pr.exact_kernels, block_resident);
         if (rc != TUNA_OK) return rc;
         mark(s, kCatUnpack, (int)i);
     }

@@ -818,12 +818,10 @@ __device__ __forceinline__ unsigned long long exact_t_src(unsigned char* T, cons
     return (unsigned long long)(T + ((x.tbase[row] + (long long)x.tpos[row * P + e]) << 4));
 }
 
-// Waves per SIMD, measured on MI355X: pack, unpack and the one-kernel phases run fastest with as many
-// resident waves as fit; the exchange, which gathers long runs from other ranks' staging, loses
-// 3 to 8 % at small radices with 8 waves and 2 % at r = P with 6.
-constexpr int copy_max_waves(int mode) { return mode == kExchange ? 7 : 8; }
+// Compiled for 8 waves per SIMD (a workgroup is one wave per SIMD).  The host lowers the number of
+// resident workgroups per launch where fewer are faster by asking for unused dynamic LDS.
 template <int MODE, int GRAN, bool DENSE>
-__global__ void __launch_bounds__(kCopyThreads) __attribute__((amdgpu_waves_per_eu(1, copy_max_waves(MODE))))
+__global__ void __launch_bounds__(kCopyThreads) __attribute__((amdgpu_waves_per_eu(1, 8)))
 k_copy(const CopyArgs a) {
     __shared__ int s_pre[kCopyThreads / kWave][kWave];
     __shared__ int s_size[kCopyThreads / kWave][kWave];
