@@ -819,9 +819,11 @@ __device__ __forceinline__ unsigned long long exact_t_src(unsigned char* T, cons
 }
 
 // Compiled for 8 waves per SIMD (a workgroup is one wave per SIMD).  The host lowers the number of
-// resident workgroups per launch where fewer are faster by asking for unused dynamic LDS.
+// resident workgroups per launch where fewer are faster by asking for unused dynamic LDS.  Unpack
+// keeps its payload in registers across the address resolution; left alone the compiler then takes
+// 84 registers (5 waves), held to 8 waves it needs 56 and spills nothing (byte-granular calls excepted).
 template <int MODE, int GRAN, bool DENSE>
-__global__ void __launch_bounds__(kCopyThreads) __attribute__((amdgpu_waves_per_eu(1, 8)))
+__global__ void __launch_bounds__(kCopyThreads) __attribute__((amdgpu_waves_per_eu((MODE == kUnpack && GRAN >= 4) ? 8 : 1, 8)))
 k_copy(const CopyArgs a) {
     __shared__ int s_pre[kCopyThreads / kWave][kWave];
     __shared__ int s_size[kCopyThreads / kWave][kWave];
@@ -888,6 +890,15 @@ k_copy(const CopyArgs a) {
             if (MODE == kUnpack || MODE == kFused) sdst = a.seg.dst[s];
         }
         const int wend = pre_w;                      // chunks below wend resolve in this window
+        // unpack reads its own staging region: the payload loads of this window need only its bounds and
+        // go out before the addresses are resolved, so the two latencies overlap
+        bool act[kChunksPerLane];
+        v4u v[kChunksPerLane];
+#pragma unroll
+        for (int k = 0; k < kChunksPerLane; ++k) {
+            act[k] = pend[k] && c[k] < wend;
+            if (MODE == kUnpack && act[k]) v[k] = __builtin_nontemporal_load(stage + c[k]);
+        }
         const bool need = s < a.nseg && pre_i < cend && pre_n > pre_i && pre_n > c0;
         unsigned long long addr = 0, addr2 = 0;
         int size = 0, flag = 0;
@@ -961,13 +972,11 @@ k_copy(const CopyArgs a) {
         int steps = 0;
         while ((1 << steps) < nlive) ++steps;
 
-        bool act[kChunksPerLane], slow[kChunksPerLane];
+        bool slow[kChunksPerLane];
         unsigned long long oa[kChunksPerLane], oa2[kChunksPerLane];
         int nb[kChunksPerLane], fill[kChunksPerLane];
-        v4u v[kChunksPerLane];
 #pragma unroll
         for (int k = 0; k < kChunksPerLane; ++k) {
-            act[k] = pend[k] && c[k] < wend;
             slow[k] = false;
             oa[k] = 0; oa2[k] = 0; nb[k] = 0; fill[k] = 0;
             if (act[k]) {
@@ -998,9 +1007,8 @@ k_copy(const CopyArgs a) {
         // ---- whole-chunk loads, all in flight before the first store --------------------------
 #pragma unroll
         for (int k = 0; k < kChunksPerLane; ++k) {
-            if (act[k] && !slow[k]) {
-                if (MODE == kUnpack) v[k] = __builtin_nontemporal_load(stage + c[k]);
-                else if (MODE == kExchange) v[k] = *reinterpret_cast<const v4u*>(oa[k]);   // neighbours share its edge lines
+            if (MODE != kUnpack && act[k] && !slow[k]) {
+                if (MODE == kExchange) v[k] = *reinterpret_cast<const v4u*>(oa[k]);   // neighbours share its edge lines
                 // blocks that are whole 128-byte lines share no line with a neighbour: streaming loads
                 // (measured on 256-byte blocks: pack +7 to +19 %, one-kernel phases +3 to +6 %; with blocks
                 // that share their edge lines they lose up to 15 %)
