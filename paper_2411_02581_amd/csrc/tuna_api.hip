@@ -581,21 +581,19 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
     // rounds z0 .. z1-1 of a phase are the segments [below(z0), below(z1)) of every rank's message order
     const PhaseScalars ps = phase_scalars(ph);
     const long long mult = ph.dim == 0 ? pr.N : pr.Q;
-    // Resident workgroups per compute unit of the three-stage kernels, measured on MI355X.  The two
-    // gathering kernels: launches that move little (under 2 GiB) or short pieces (under 2 KiB) are fastest
-    // with all 8 -- 3 to 5 % over 6 -- and long launches over long pieces with 6 (8 loses 4 % in pack and
-    // up to 9 % in the exchange).  A piece is a block for pack and a message for the exchange; sizes are
-    // estimated from the mean block.  Unpack, whose payload loads go out ahead of the address loads, has
-    // more bytes in flight per wave: 6 for long launches (10 % over 8), 7 for short ones.  The one-kernel
-    // phases hold 7 by their registers and are indifferent between 6 and 8.
+    // Resident workgroups per compute unit of the three-stage kernels, measured on MI355X.  The kernels
+    // keep many loads in flight per wave, and beyond some number of waves more of them only queue up in
+    // the memory system.  Launches that move 2 GiB and more are fastest with 6 resident workgroups of 8
+    // (blocks under 2 KiB: 2 to 4 % over 8 in pack, up to 7 % in the exchange, 10 % in unpack) or with 5
+    // (larger blocks: another 3 to 8 %); short launches, where the ramp and the tail count, with 8 in pack
+    // and 7 in the exchange and unpack.  Sizes are estimated from the mean block.  The one-kernel phases
+    // hold 6 by their registers.
     const double mean_block = (double)pr.total_bytes / ((double)pr.P * (double)pr.P);
     const bool short_launch = mean_block * (double)ph.nseg * (double)pr.P < 2.0 * 1024 * 1024 * 1024;
-    const int block_resident = (short_launch || mean_block < 2048.0) ? 8 : 6;
-    // pack also prefers 6 when it reads from slots of M bytes that are mostly empty (1 KiB blocks in 2.4 KiB slots: 7 %)
-    const bool sparse_slots = !pr.exact_t && pr.ds.slots > 0 && mean_block < 0.9 * (double)pr.ds.slot_bytes;
-    const int pack_resident = (!short_launch && sparse_slots) ? 6 : block_resident;
-    const int unpack_resident = short_launch ? 7 : 6;
-    const int exchange_resident = (short_launch || mean_block * (double)ph.nseg / (double)ph.nz < 2048.0) ? 8 : 6;
+    const int long_resident = mean_block < 2048.0 ? 6 : 5;
+    const int pack_resident = short_launch ? 8 : long_resident;
+    const int exchange_resident = short_launch ? 7 : long_resident;
+    const int unpack_resident = short_launch ? 7 : long_resident;
     int per_batch = pr.block_count;                  // the staggered schedule counts single-block rounds: Q per node distance
     if (per_batch > 0 && pr.staggered && ph.dim == 1) per_batch = std::max(1, per_batch / pr.Q);
     const int step = (per_batch > 0 && per_batch < ph.nz) ? per_batch : ph.nz;
