@@ -34,8 +34,8 @@ HBM_PEAK_GBS = 8000.0
 # for the same launches is 2 x payload = 22.55e9 bytes; see profiles/k_copy_config4_P4096.md.
 # First entry: T in exact size (the default); second: T in slots of M bytes (--exact-t 0).
 MEASURED_TRAFFIC_CONFIG4 = {
-    True: {"pack": 22818.3 * 2**20, "exchange": 22308.8 * 2**20, "unpack": 22436.7 * 2**20, "fused": 23709.0 * 2**20},
-    False: {"pack": 22848.8 * 2**20, "exchange": 22308.8 * 2**20, "unpack": 22485.4 * 2**20, "fused": 23664.3 * 2**20},
+    True: {"pack": 22816.4 * 2**20, "exchange": 22307.3 * 2**20, "unpack": 22496.0 * 2**20, "fused": 23689.2 * 2**20},
+    False: {"pack": 22847.3 * 2**20, "exchange": 22307.3 * 2**20, "unpack": 22486.3 * 2**20, "fused": 23695.8 * 2**20},
 }
 
 
