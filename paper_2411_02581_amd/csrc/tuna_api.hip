@@ -1214,9 +1214,9 @@ int tuna_select_radix(int P, int ranks_per_node, int64_t payload_bytes, int* loc
     int rc = resolve_hierarchy(P, ranks_per_node, &Q);
     if (rc != TUNA_OK) return rc;
     const int N = P / Q;
-    // measured on MI355X at P = 4096: copy stages ~5.5e12 B/s, metadata kernels of
-    // a phase ~40 us + 10 ps per matrix entry, validation + rotation ~0.25 ms at P = 4096
-    const double bw = 5.5e12, c = g.opt_fused ? 2.0 : 6.0;
+    // measured on MI355X at P = 4096: the three copy stages ~6.0e12 B/s, the one-kernel phases ~5.0e12;
+    // metadata kernels of a phase ~40 us + 10 ps per matrix entry, validation + rotation ~0.25 ms at P = 4096
+    const double bw = g.opt_fused ? 5.0e12 : 6.0e12, c = g.opt_fused ? 2.0 : 6.0;
     const double t_phase = 40e-6 + 1.0e-11 * (double)P * P, t_call = 40e-6 + 1.3e-11 * (double)P * P;
     auto hops = [](int size, int r) {           // H(r) over one dimension
         long long nz = 0;

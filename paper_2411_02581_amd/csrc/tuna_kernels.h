@@ -708,7 +708,8 @@ __global__ void __launch_bounds__(256) k_layout_units(int nseg, LayoutDev Lr, La
 // Work unit = one wavefront x 256 consecutive 16-byte chunks (4 KiB) of one rank's staging
 // region.  The wave is self-contained -- no workgroup barrier anywhere: lane i loads the chunk
 // prefix and the table entry of segment s0 + i, the lanes whose segment overlaps the unit
-// resolve its other-side address (T slot arithmetic, or one displacement load), the 64 entries
+// resolve its other-side address (T slot arithmetic, a position in exact-size T, or one
+// displacement load), the 64 entries
 // go to the wave's private LDS window, and every lane finds the segment of each of its 4 chunks
 // by a binary search over that window.  Lanes of a wave touch consecutive chunks on the staging
 // side (aligned, non-temporal dwordx4) and consecutive bytes of a block on the other side.

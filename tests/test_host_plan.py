@@ -245,7 +245,7 @@ def test_select_radix_model():
     plus a few hundred microseconds."""
     rc, rl, rg, ms = tuna.tuna_select_radix(4096, 0, 16 << 30)
     assert rc == 0 and rl == 4096
-    assert 6 * (16 << 30) * 4095 / 4096 / 5.5e12 * 1e3 < ms < 6 * (16 << 30) / 5.5e12 * 1e3 + 1.5
+    assert 6 * (16 << 30) * 4095 / 4096 / 6.0e12 * 1e3 < ms < 6 * (16 << 30) / 6.0e12 * 1e3 + 1.5
     rc, rl, rg, ms = tuna.tuna_select_radix(1024, 16, 1 << 30)
     assert rc == 0 and (rl, rg) == (16, 64)
     rc, rl, rg, ms_small = tuna.tuna_select_radix(256, 0, 1 << 10)
