@@ -51,7 +51,8 @@ extern "C" {
 #define TUNA_ERR_NOMEM -4            /* the library could not allocate its workspace */
 #define TUNA_ERR_WORKSPACE_TOO_SMALL -5 /* a caller-supplied workspace is smaller than needed */
 #define TUNA_ERR_HIP -6              /* a HIP call failed; tuna_stats_t.last_hip_error has the code */
-#define TUNA_ERR_TOO_LARGE -7        /* P or a per-rank byte total exceeds the supported range */
+#define TUNA_ERR_TOO_LARGE -7        /* P, a block or a per-rank byte total exceeds the supported range */
+#define TUNA_ERR_NOALLOC_LIMIT -8    /* tuna_alltoallv_noalloc: the call needs more than TUNA_NOALLOC_SCRATCH_BYTES */
 
 #define TUNA_MAX_PHASES 64
 #define TUNA_MAX_RANKS 32768
@@ -141,6 +142,28 @@ int tuna_alltoallv(const void* sendbuf, const int32_t* sendcounts, const int64_t
 int tuna_alltoallv_hier(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls,
                         void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls,
                         int P, int ranks_per_node, int local_radix, int global_radix, void* stream);
+
+/*
+ * For callers that cannot allocate device memory when they call -- code under HIP graph capture
+ * rules, tight serving loops, harnesses that forbid hipMalloc: the same call as
+ * tuna_alltoallv_hier (same arguments, same result, the options in force apply, TUNA_OPT_PROFILE
+ * excepted), done in one pass with every internal buffer -- status block, schedule tables, size
+ * matrices, scans, work lists, staging buffers, T -- carved from one static device array of
+ * TUNA_NOALLOC_SCRATCH_BYTES bytes that each GPU the library runs on holds until the process ends.
+ * The call itself calls no hipMalloc, hipFree, hipHostMalloc or hipEventCreate (it still reads a
+ * few integers back and synchronises `stream` once, like tuna_alltoallv).  A problem that needs
+ * more than the array returns TUNA_ERR_NOALLOC_LIMIT before any payload byte has moved: the need
+ * is about 26 P^2 bytes of tables and scans per phase-independent part, 24 bytes per moving block
+ * and phase of schedule tables, twice the payload for the staging buffers of three-stage phases
+ * and the bytes waiting in T -- e.g. P = 256 with 8 MiB of payload fits at every radix.
+ * It uses the device that is current and works on any device.  All calls on one GPU share that
+ * GPU's array, which keeps the previous call's contents (every call writes whatever it reads):
+ * two calls that overlap in time on one GPU race, also with different streams.
+ */
+#define TUNA_NOALLOC_SCRATCH_BYTES (64u << 20)
+int tuna_alltoallv_noalloc(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls,
+                           void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls,
+                           int P, int ranks_per_node, int local_radix, int global_radix, void* stream);
 
 /*
  * Persistent form, after MPI's persistent collectives (MPI_Alltoallv_init / MPI_Start): for

@@ -21,6 +21,8 @@ TUNA_ERR_NOMEM = -4
 TUNA_ERR_WORKSPACE_TOO_SMALL = -5
 TUNA_ERR_HIP = -6
 TUNA_ERR_TOO_LARGE = -7
+TUNA_ERR_NOALLOC_LIMIT = -8
+TUNA_NOALLOC_SCRATCH_BYTES = 64 << 20
 TUNA_OPT_PROFILE = 1
 TUNA_OPT_FUSED = 2
 TUNA_OPT_STAGGERED = 3
@@ -28,7 +30,7 @@ TUNA_OPT_DENSE_T = 4
 TUNA_OPT_BLOCK_COUNT = 5
 TUNA_MAX_PHASES = 64
 
-EXPORTS = ("tuna_alltoallv", "tuna_alltoallv_hier", "tuna_workspace_bytes", "tuna_set_workspace",
+EXPORTS = ("tuna_alltoallv", "tuna_alltoallv_hier", "tuna_alltoallv_noalloc", "tuna_workspace_bytes", "tuna_set_workspace",
            "tuna_release", "tuna_set_option", "tuna_get_stats", "tuna_plan_info", "tuna_plan_phase",
            "tuna_t_index", "tuna_plan_phase_device", "tuna_plan_phase_sources", "tuna_plain_copy", "tuna_select_radix", "tuna_alltoallv_init", "tuna_start", "tuna_plan_free",
            "tuna_strerror", "tuna_version")
@@ -90,6 +92,7 @@ def load() -> ctypes.CDLL:
     vp, i, i64p = ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p
     lib.tuna_alltoallv.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, vp]
     lib.tuna_alltoallv_hier.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
+    lib.tuna_alltoallv_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
     lib.tuna_alltoallv_init.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, ctypes.POINTER(ctypes.c_void_p)]
     lib.tuna_start.argtypes = [vp, vp]
     lib.tuna_plan_free.argtypes = [vp]
@@ -154,6 +157,14 @@ def tuna_alltoallv_hier(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdisp
     return load().tuna_alltoallv_hier(_ptr(sendbuf), _ptr(sendcounts, torch.int32), _ptr(sdispls, torch.int64),
                                       _ptr(recvbuf), _ptr(recvcounts, torch.int32), _ptr(rdispls, torch.int64),
                                       P, ranks_per_node, local_radix, global_radix, _stream(stream))
+
+
+def tuna_alltoallv_noalloc(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P: int,
+                           ranks_per_node: int, local_radix: int, global_radix: int, stream=None) -> int:
+    import torch
+    return load().tuna_alltoallv_noalloc(_ptr(sendbuf), _ptr(sendcounts, torch.int32), _ptr(sdispls, torch.int64),
+                                         _ptr(recvbuf), _ptr(recvcounts, torch.int32), _ptr(rdispls, torch.int64),
+                                         P, ranks_per_node, local_radix, global_radix, _stream(stream))
 
 
 def tuna_alltoallv_init(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P: int,

@@ -15,10 +15,16 @@
 #include "tuna_kernels.h"
 #include "tuna_plan.h"
 
+// Scratch memory of tuna_alltoallv_noalloc: everything the kernels of a call need beyond the caller's
+// six arrays (status block, schedule tables, size matrices, scans, work lists, staging buffers, T).
+// One array per GPU, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels receive the address that call returned for the current device.
+static __device__ __align__(256) unsigned char scratch[TUNA_NOALLOC_SCRATCH_BYTES];
+
 namespace tuna {
 namespace {
 
-constexpr int kVersion = 100;
+constexpr int kVersion = 101;
 constexpr size_t kAlign = 256;
 // A one-kernel phase cuts chunks at the destination's 16-byte lines, so its last load of a block
 // that lies in T may run up to 15 bytes past the block: T is allocated with this much room behind it.
@@ -34,6 +40,15 @@ struct DevicePlan {
     int32_t* d_hm1 = nullptr;            // [P]: hops - 1 of every slot index (how often the block is stored into T)
 };
 
+// Where a call's validation pass and per-phase totals are written and read back: the library's own
+// small allocations, or a part of the static scratch of the entry point that allocates nothing.
+struct StatusBufs {
+    Status* d_status = nullptr;              // device status block
+    Status* h_status = nullptr;              // host mirror (pinned for the library's own)
+    unsigned long long* d_vpart = nullptr;   // partial results of the validation pass, one row per workgroup
+    int num_cus = 256;
+};
+
 enum Category { kCatPrepare = 0, kCatSelf, kCatMeta, kCatPack, kCatExchange, kCatUnpack };
 
 struct Mark { hipEvent_t ev; int cat; int phase; };
@@ -41,10 +56,7 @@ struct Mark { hipEvent_t ev; int cat; int phase; };
 struct Ctx {
     bool ready = false;
     int device = -1;
-    int num_cus = 256;
-    Status* d_status = nullptr;       // device status block (one-time small allocation)
-    Status* h_status = nullptr;       // pinned host mirror
-    unsigned long long* d_vpart = nullptr;   // partial results of the validation pass, one row per workgroup
+    StatusBufs sb;                    // status block, its pinned host mirror, validation partials (one-time small allocations)
     void* meta = nullptr;  size_t meta_bytes = 0;   // library-owned, grow-only
     void* data = nullptr;  size_t data_bytes = 0;
     void* user_ws = nullptr; size_t user_ws_bytes = 0;
@@ -59,6 +71,7 @@ struct Ctx {
     int live_plans = 0;                 // persistent plans not yet freed (they point into `plans`)
     const void* stats_plan = nullptr;   // the statistics on file belong to this persistent plan (payload bytes known)
     int last_hip_error = 0;
+    bool no_marks = false;              // set while the entry point that allocates nothing runs: it creates no events
 };
 
 Ctx g;
@@ -70,6 +83,9 @@ Ctx g;
     } while (0)
 
 inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
+
+// 64-bit words of the validation pass's partial results: at most 8 workgroups per compute unit
+inline size_t vpart_words(int num_cus) { return (size_t)num_cus * 8 * kValPartial; }
 
 int ensure_ctx() {
     if (g.ready) {
@@ -85,10 +101,10 @@ int ensure_ctx() {
     HIPCHK(hipGetDevice(&g.device));
     hipDeviceProp_t prop;
     HIPCHK(hipGetDeviceProperties(&prop, g.device));
-    g.num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-    HIPCHK(hipMalloc((void**)&g.d_status, align_up(sizeof(Status))));
-    HIPCHK(hipHostMalloc((void**)&g.h_status, sizeof(Status), hipHostMallocDefault));
-    HIPCHK(hipMalloc((void**)&g.d_vpart, align_up((size_t)g.num_cus * 8 * kValPartial * 8)));
+    g.sb.num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    HIPCHK(hipMalloc((void**)&g.sb.d_status, align_up(sizeof(Status))));
+    HIPCHK(hipHostMalloc((void**)&g.sb.h_status, sizeof(Status), hipHostMallocDefault));
+    HIPCHK(hipMalloc((void**)&g.sb.d_vpart, align_up(vpart_words(g.sb.num_cus) * 8)));
     HIPCHK(hipEventCreate(&g.ev_end));
     std::memset(&g.stats, 0, sizeof(g.stats));
     g.ready = true;
@@ -211,13 +227,19 @@ void free_device_plan(DevicePlan& dp) {
 // Cached schedule of (P, Q, r_l, r_g, fused).  The host keeps scalars only; the per-phase tables are
 // built on the device by k_build_phase_table, on the caller's stream (the kernels that read them
 // are enqueued behind it).
+// Radices clamped the way make_plan clamps them.
+void clamp_radices(int Q, int N, int rl, int rg, int* crl, int* crg) {
+    *crl = rl < 2 ? 2 : rl; *crg = rg < 2 ? 2 : rg;
+    if (Q >= 2 && *crl > Q) *crl = Q;
+    if (N >= 2 && *crg > N) *crg = N;
+    if (Q < 2) *crl = 2;
+    if (N < 2) *crg = 2;
+}
+
 int get_plan(int P, int Q, int rl, int rg, bool fused, hipStream_t s, DevicePlan** out) {
-    const int N = P / Q;                 // radices are clamped the way make_plan clamps them
-    int crl = rl < 2 ? 2 : rl, crg = rg < 2 ? 2 : rg;
-    if (Q >= 2 && crl > Q) crl = Q;
-    if (N >= 2 && crg > N) crg = N;
-    if (Q < 2) crl = 2;
-    if (N < 2) crg = 2;
+    const int N = P / Q;
+    int crl, crg;
+    clamp_radices(Q, N, rl, rg, &crl, &crg);
     auto key = std::make_tuple(P, Q, crl, crg, fused ? 1 : 0);
     auto it = g.plans.find(key);
     if (it == g.plans.end()) {
@@ -274,7 +296,7 @@ int grow(void** buf, size_t* have, size_t need) {
 }
 
 void mark(hipStream_t s, int cat, int phase) {
-    if (!g.opt_profile) return;
+    if (!g.opt_profile || g.no_marks) return;
     const size_t k = g.marks.size();
     if (k >= g.ev_pool.size()) {
         hipEvent_t ev;
@@ -371,19 +393,19 @@ int resolve_hierarchy(int P, int ranks_per_node, int* Q) {
     return TUNA_OK;
 }
 
-// Validation + sizing pass shared by tuna_alltoallv* and tuna_workspace_bytes: fills *g.h_status.
-int run_validate(const int32_t* sendcounts, const int32_t* recvcounts, const int64_t* sdispls,
+// Validation + sizing pass shared by tuna_alltoallv* and tuna_workspace_bytes: fills *sb.h_status.
+int run_validate(const StatusBufs& sb, const int32_t* sendcounts, const int32_t* recvcounts, const int64_t* sdispls,
                  const int64_t* rdispls, int P, hipStream_t s, const DevicePlan* exact_t_for = nullptr) {
     // every field of the status block a call reads is written by the call's own kernels: no clearing
     const size_t t = (size_t)((P + kValTile - 1) / kValTile);
-    const unsigned vgrid = (unsigned)(t * t < (size_t)g.num_cus * 8 ? t * t : (size_t)g.num_cus * 8);
+    const unsigned vgrid = (unsigned)(t * t < (size_t)sb.num_cus * 8 ? t * t : (size_t)sb.num_cus * 8);
     hipLaunchKernelGGL(k_validate, dim3(vgrid), dim3(kValTile, 4), 0, s, sendcounts, recvcounts, sdispls, rdispls, P,
-                       g.d_vpart, exact_t_for ? exact_t_for->d_hm1 : nullptr, exact_t_for ? exact_t_for->host.Q : 1,
+                       sb.d_vpart, exact_t_for ? exact_t_for->d_hm1 : nullptr, exact_t_for ? exact_t_for->host.Q : 1,
                        exact_t_for ? exact_t_for->host.N : 1);
     HIPCHK(hipGetLastError());
-    hipLaunchKernelGGL(k_validate_finish, dim3(1), dim3(256), 0, s, g.d_vpart, (int)vgrid, g.d_status);
+    hipLaunchKernelGGL(k_validate_finish, dim3(1), dim3(256), 0, s, sb.d_vpart, (int)vgrid, sb.d_status);
     HIPCHK(hipGetLastError());
-    HIPCHK(hipMemcpyAsync(g.h_status, g.d_status, 64, hipMemcpyDeviceToHost, s));
+    HIPCHK(hipMemcpyAsync(sb.h_status, sb.d_status, 64, hipMemcpyDeviceToHost, s));
     HIPCHK(hipStreamSynchronize(s));
     return TUNA_OK;
 }
@@ -392,6 +414,7 @@ int run_validate(const int32_t* sendcounts, const int32_t* recvcounts, const int
 struct Prepared {
     int P = 0, Q = 0, N = 0;
     DevicePlan* dp = nullptr;
+    StatusBufs sb;
     bool fused = false, staggered = false;
     int gran = 1;
     const void* sendbuf = nullptr;
@@ -473,8 +496,44 @@ void fill_stats_header(const Prepared& pr, const Status& hs, tuna_stats_t& st) {
     }
 }
 
-// Argument checks, schedule, validation + sizing pass (one read-back).  On TUNA_OK with
-// *empty == true there is nothing to move.
+// Validation + sizing pass of a call whose arguments, schedule and status buffers are in `pr` (one
+// read-back).  On TUNA_OK with *empty == true there is nothing to move.
+int prepare_sizes(Prepared& pr, int dense_option, hipStream_t s, Status& hs, bool* empty) {
+    const int P = pr.P;
+    const bool has_t = pr.dp->host.slots > 0;              // a schedule without T (r >= P - 1) has nothing to size
+    int rc = run_validate(pr.sb, pr.sendcounts, pr.recvcounts, pr.sdispls, pr.rdispls, P, s,
+                          (dense_option != 0 && has_t) ? pr.dp : nullptr);
+    if (rc != TUNA_OK) return rc;
+    hs = *pr.sb.h_status;
+    if (pr.dp->built_on == s) pr.dp->complete = true;      // run_validate synchronised this stream
+    if (hs.flags & 1u) return TUNA_ERR_NEGATIVE_COUNT;
+    if (hs.flags & 2u) return TUNA_ERR_COUNT_MISMATCH;
+    if (hs.flags & 4u) return TUNA_ERR_ARG;                 // a non-empty block at a negative displacement
+    // the kernels round block sizes up to chunks and lines in 32-bit arithmetic
+    if (hs.max_count > INT_MAX - 256) return TUNA_ERR_TOO_LARGE;
+    pr.exact_kernels = choose_exact_t(dense_option, P, hs);
+    pr.exact_t = pr.exact_kernels && has_t;
+    *empty = hs.total_bytes == 0;
+    if (*empty) return TUNA_OK;
+    if (!pr.sendbuf || !pr.recvbuf) return TUNA_ERR_ARG;
+    // chunk prefixes are 32-bit per rank: what one rank stages in a phase is bounded both by all
+    // chunks there are and by P blocks of at most M bytes
+    {
+        const unsigned long long by_m = (unsigned long long)P * (unsigned long long)((hs.max_count + 15) / 16 + 1);
+        if ((hs.total_chunks + (unsigned long long)P < by_m ? hs.total_chunks + (unsigned long long)P : by_m) >= (1ull << 31))
+            return TUNA_ERR_TOO_LARGE;
+    }
+    const unsigned int abits = hs.align_bits | (unsigned int)((uintptr_t)pr.sendbuf & 127u) |
+                               (unsigned int)((uintptr_t)pr.recvbuf & 127u);
+    pr.gran = (abits & 127u) == 0 ? 128 : ((abits & 15u) == 0 ? 16 : ((abits & 3u) == 0 ? 4 : 1));
+    pr.max_count = hs.max_count;
+    pr.total_bytes = hs.total_bytes;
+    pr.user_limit = (unsigned long long)(uintptr_t)pr.sendbuf + hs.send_extent;
+    pr.ds = data_sizes_for(pr.dp->host, hs.max_count, hs.total_chunks, pr.fused, pr.staggered, pr.exact_t, hs.t_chunks);
+    return TUNA_OK;
+}
+
+// Argument checks, cached schedule, validation + sizing pass.
 int prepare_call(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
                  const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
                  hipStream_t s, Prepared& pr, Status& hs, bool* empty) {
@@ -487,6 +546,7 @@ int prepare_call(const void* sendbuf, const int32_t* sendcounts, const int64_t* 
     if (rc != TUNA_OK) return rc;
     const int N = P / Q;
     pr.P = P; pr.Q = Q; pr.N = N;
+    pr.sb = g.sb;
     pr.fused = g.opt_fused != 0;
     // staggered inter-node schedule: one block per message, N - 1 node distances, straight from T
     pr.staggered = g.opt_staggered != 0 && N > 1;
@@ -495,36 +555,8 @@ int prepare_call(const void* sendbuf, const int32_t* sendcounts, const int64_t* 
     if (rc != TUNA_OK) return rc;
     pr.sendbuf = sendbuf; pr.recvbuf = recvbuf; pr.sendcounts = sendcounts; pr.recvcounts = recvcounts;
     pr.sdispls = sdispls; pr.rdispls = rdispls;
-    // ---- validation, M, totals (one read-back) -------------------------------------------------
     pr.block_count = g.opt_block_count;
-    const bool has_t = pr.dp->host.slots > 0;              // a schedule without T (r >= P - 1) has nothing to size
-    rc = run_validate(sendcounts, recvcounts, sdispls, rdispls, P, s, (g.opt_dense_t != 0 && has_t) ? pr.dp : nullptr);
-    if (rc != TUNA_OK) return rc;
-    hs = *g.h_status;
-    pr.exact_kernels = choose_exact_t(g.opt_dense_t, P, hs);
-    pr.exact_t = pr.exact_kernels && has_t;
-    if (pr.dp->built_on == s) pr.dp->complete = true;      // run_validate synchronised this stream
-    if (hs.flags & 1u) return TUNA_ERR_NEGATIVE_COUNT;
-    if (hs.flags & 2u) return TUNA_ERR_COUNT_MISMATCH;
-    if (hs.flags & 4u) return TUNA_ERR_ARG;                 // a non-empty block at a negative displacement
-    *empty = hs.total_bytes == 0;
-    if (*empty) return TUNA_OK;
-    if (!sendbuf || !recvbuf) return TUNA_ERR_ARG;
-    // chunk prefixes are 32-bit per rank: what one rank stages in a phase is bounded both by all
-    // chunks there are and by P blocks of at most M bytes
-    {
-        const unsigned long long by_m = (unsigned long long)P * (unsigned long long)((hs.max_count + 15) / 16 + 1);
-        if ((hs.total_chunks + (unsigned long long)P < by_m ? hs.total_chunks + (unsigned long long)P : by_m) >= (1ull << 31))
-            return TUNA_ERR_TOO_LARGE;
-    }
-    const unsigned int abits = hs.align_bits | (unsigned int)((uintptr_t)sendbuf & 127u) |
-                               (unsigned int)((uintptr_t)recvbuf & 127u);
-    pr.gran = (abits & 127u) == 0 ? 128 : ((abits & 15u) == 0 ? 16 : ((abits & 3u) == 0 ? 4 : 1));
-    pr.max_count = hs.max_count;
-    pr.total_bytes = hs.total_bytes;
-    pr.user_limit = (unsigned long long)(uintptr_t)sendbuf + hs.send_extent;
-    pr.ds = data_sizes_for(pr.dp->host, hs.max_count, hs.total_chunks, pr.fused, pr.staggered, pr.exact_t, hs.t_chunks);
-    return TUNA_OK;
+    return prepare_sizes(pr, g.opt_dense_t, s, hs, empty);
 }
 
 int launch_phase_metadata(const Prepared& pr, size_t i, const int32_t* cur, int32_t* nxt, const LayoutDev& Ls,
@@ -537,8 +569,8 @@ int launch_phase_metadata(const Prepared& pr, size_t i, const int32_t* cur, int3
     m.Ls = Ls; m.Lr = Lr; m.want_send = one_kernel ? 0 : 1;
     if (pr.exact_t) { m.Lt = pr.Lt[i]; m.want_tbound = 1; m.tpos = pr.x.tpos + i * (size_t)pr.P * pr.P; }
     m.rank_bytes = pr.rank_bytes;
-    m.phase_bytes = &g.d_status->phase_bytes[i]; m.phase_chunks = &g.d_status->phase_chunks[i];
-    m.phase_units = g.d_status->phase_units[i];
+    m.phase_bytes = &pr.sb.d_status->phase_bytes[i]; m.phase_chunks = &pr.sb.d_status->phase_chunks[i];
+    m.phase_units = pr.sb.d_status->phase_units[i];
     m.head_displs = one_kernel ? pr.rdispls : nullptr;
     m.head_base = (unsigned int)((uintptr_t)pr.recvbuf & 15u);
     // with few ranks a launch costs more than the kernel (measured: 19 us per call at P = 16, nothing at
@@ -652,6 +684,61 @@ bool use_two_pass(const PlanHost& pl, const Status& hs) {
     return pl.phases.size() >= 2 && hs.total_chunks >= kTwoPassMinChunks;
 }
 
+// Metadata bytes of a one-pass call: the two size matrices, one pair of layouts reused by every phase,
+// the exact-size T tables and, for one-kernel phases, the transposed send displacements.
+size_t one_pass_meta_bytes(const Prepared& pr) {
+    return meta_bytes_for(pr.P) + (pr.exact_t ? exact_t_meta_bytes_for(pr.dp->host, false) : 0) +
+           (any_one_kernel_phase(pr) ? align_up((size_t)pr.P * pr.P * 8) : 0);
+}
+
+// A call in one pass: rotation, the own blocks, then per digit phase its metadata kernels followed at
+// once by its payload kernels, launched for an upper bound of work.  `mbase` holds one_pass_meta_bytes,
+// `dbase` pr.ds.total bytes.
+int run_one_pass(Prepared& pr, void* mbase, size_t mbytes, void* dbase, hipStream_t s, tuna_stats_t& st) {
+    const PlanHost& pl = pr.dp->host;
+    const DataSizes& ds = pr.ds;
+    const int P = pr.P;
+    Carver cm(mbase, mbytes);
+    MetaBuffers mb = carve_meta(cm, P);
+    pr.rank_bytes = mb.rank_bytes;
+    if (pr.exact_t) carve_exact_t(cm, pl, false, pr);
+    if (any_one_kernel_phase(pr)) pr.sdispls_t = cm.take<int64_t>((size_t)P * P);
+    Carver cd(dbase, ds.total);
+    mb.Ls.units = cd.take<int4>(ds.unit_cap);
+    mb.Lr.units = cd.take<int4>(ds.unit_cap);
+    pr.stage_s = cd.take<v4u>(pr.fused ? 0 : ds.stage_chunks);
+    pr.stage_r = cd.take<v4u>(pr.fused ? 0 : ds.stage_chunks);
+    pr.T = cd.take<unsigned char>(ds.t_bytes + kTailSlack);
+    if (!cm.ok || !cd.ok) return TUNA_ERR_WORKSPACE_TOO_SMALL;
+    st.temp_bytes = (int64_t)ds.t_bytes;
+    st.staging_bytes = pr.fused ? 0 : (int64_t)(2 * ds.stage_chunks * 16);
+    st.workspace_bytes = (int64_t)(mbytes + ds.total);
+
+    // ---- initial rotation (index only) and the own block ----------------------------------------
+    const dim3 grot((unsigned)((P + 255) / 256), (unsigned)((P + kExchangeRanks - 1) / kExchangeRanks));
+    hipLaunchKernelGGL(k_rotate_init, grot, dim3(256), 0, s, pr.sendcounts, mb.cur, P, pr.Q, pr.N);
+    HIPCHK(hipGetLastError());
+    int rc = launch_transpose_displs(pr, s);
+    if (rc != TUNA_OK) return rc;
+    mark(s, kCatPrepare, -1);
+    rc = launch_self_copy(pr, s);
+    if (rc != TUNA_OK) return rc;
+    mark(s, kCatSelf, -1);
+
+    // ---- digit phases -----------------------------------------------------------------------------
+    int32_t* cur = mb.cur;
+    int32_t* nxt = mb.nxt;
+    for (size_t i = 0; i < pl.phases.size(); ++i) {
+        rc = launch_phase_metadata(pr, i, cur, nxt, mb.Ls, mb.Lr, s);
+        if (rc != TUNA_OK) return rc;
+        mark(s, kCatMeta, (int)i);
+        rc = launch_phase_data(pr, i, mb.Ls, mb.Lr, ds.unit_cap, s);
+        if (rc != TUNA_OK) return rc;
+        std::swap(cur, nxt);
+    }
+    return TUNA_OK;
+}
+
 int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
         const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
         void* stream) {
@@ -674,8 +761,7 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
     if (use_two_pass(pl, hs)) return run_two_pass(pr, s);
 
     // ---- workspace ---------------------------------------------------------------------------
-    const size_t mbytes = meta_bytes_for(P) + (pr.exact_t ? exact_t_meta_bytes_for(pl, false) : 0) +
-                          (any_one_kernel_phase(pr) ? align_up((size_t)P * P * 8) : 0);
+    const size_t mbytes = one_pass_meta_bytes(pr);
     const DataSizes& ds = pr.ds;
     void *mbase, *dbase;
     if (g.user_ws) {
@@ -690,45 +776,8 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
         mbase = g.meta;
         dbase = g.data;
     }
-    Carver cm(mbase, mbytes);
-    MetaBuffers mb = carve_meta(cm, P);
-    pr.rank_bytes = mb.rank_bytes;
-    if (pr.exact_t) carve_exact_t(cm, pl, false, pr);
-    if (any_one_kernel_phase(pr)) pr.sdispls_t = cm.take<int64_t>((size_t)P * P);
-    Carver cd(dbase, ds.total);
-    mb.Ls.units = cd.take<int4>(ds.unit_cap);
-    mb.Lr.units = cd.take<int4>(ds.unit_cap);
-    pr.stage_s = cd.take<v4u>(pr.fused ? 0 : ds.stage_chunks);
-    pr.stage_r = cd.take<v4u>(pr.fused ? 0 : ds.stage_chunks);
-    pr.T = cd.take<unsigned char>(ds.t_bytes + kTailSlack);
-    if (!cm.ok || !cd.ok) return TUNA_ERR_WORKSPACE_TOO_SMALL;
-    st.temp_bytes = (int64_t)ds.t_bytes;
-    st.staging_bytes = pr.fused ? 0 : (int64_t)(2 * ds.stage_chunks * 16);
-    st.workspace_bytes = (int64_t)(mbytes + ds.total);
-
-    // ---- initial rotation (index only) and the own block ----------------------------------------
-    const size_t P2 = (size_t)P * P;
-    const dim3 grot((unsigned)((P + 255) / 256), (unsigned)((P + kExchangeRanks - 1) / kExchangeRanks));
-    hipLaunchKernelGGL(k_rotate_init, grot, dim3(256), 0, s, sendcounts, mb.cur, P, pr.Q, pr.N);
-    HIPCHK(hipGetLastError());
-    rc = launch_transpose_displs(pr, s);
+    rc = run_one_pass(pr, mbase, mbytes, dbase, s, st);
     if (rc != TUNA_OK) return rc;
-    mark(s, kCatPrepare, -1);
-    rc = launch_self_copy(pr, s);
-    if (rc != TUNA_OK) return rc;
-    mark(s, kCatSelf, -1);
-
-    // ---- digit phases -----------------------------------------------------------------------------
-    int32_t* cur = mb.cur;
-    int32_t* nxt = mb.nxt;
-    for (size_t i = 0; i < pl.phases.size(); ++i) {
-        rc = launch_phase_metadata(pr, i, cur, nxt, mb.Ls, mb.Lr, s);
-        if (rc != TUNA_OK) return rc;
-        mark(s, kCatMeta, (int)i);
-        rc = launch_phase_data(pr, i, mb.Ls, mb.Lr, ds.unit_cap, s);
-        if (rc != TUNA_OK) return rc;
-        std::swap(cur, nxt);
-    }
     HIPCHK(hipEventRecord(g.ev_end, s));
     g.end_recorded = true;
     g.have_stats = true;
@@ -804,14 +853,15 @@ int plan_build_metadata(Plan* plan, void* meta, size_t mbytes, hipStream_t s, bo
         std::swap(cur, nxt);
     }
     // exact unit counts, bytes and staged chunks per phase: one read-back of the status block
-    HIPCHK(hipMemcpyAsync(g.h_status, g.d_status, sizeof(Status), hipMemcpyDeviceToHost, s));
+    const Status* h_status = pr.sb.h_status;
+    HIPCHK(hipMemcpyAsync(pr.sb.h_status, pr.sb.d_status, sizeof(Status), hipMemcpyDeviceToHost, s));
     HIPCHK(hipStreamSynchronize(s));
     unsigned long long max_chunks = 0;
     for (size_t i = 0; i < nph; ++i) {
         const bool one = phase_is_one_kernel(pr, pl.phases[i]);
-        plan->units[i] = (size_t)std::max(g.h_status->phase_units[i][0], one ? 0u : g.h_status->phase_units[i][1]);
-        plan->phase_bytes[i] = g.h_status->phase_bytes[i];
-        plan->phase_chunks[i] = g.h_status->phase_chunks[i];
+        plan->units[i] = (size_t)std::max(h_status->phase_units[i][0], one ? 0u : h_status->phase_units[i][1]);
+        plan->phase_bytes[i] = h_status->phase_bytes[i];
+        plan->phase_chunks[i] = h_status->phase_chunks[i];
         plan->stats.phase[i].payload_bytes = (int64_t)plan->phase_bytes[i];
         plan->stats.phase[i].staged_bytes = (int64_t)plan->phase_chunks[i] * 16;
         if (!phase_is_one_kernel(pr, pl.phases[i])) max_chunks = std::max(max_chunks, plan->phase_chunks[i]);
@@ -940,6 +990,101 @@ int run_two_pass(const Prepared& prepared, hipStream_t s) {
     return TUNA_OK;
 }
 
+// ---- the entry point that allocates nothing --------------------------------------------------------
+// Same call as tuna_alltoallv_hier, one pass, with every buffer carved from the static device array
+// `scratch`: no hipMalloc, no hipFree, no event or pinned-memory creation.  The schedule tables are
+// rebuilt in scratch by every call (a few small kernels) instead of being cached in allocated memory.
+constexpr int kMaxDevices = 64;
+struct StaticState {
+    unsigned char* ptr[kMaxDevices] = {};   // device address of `scratch` on each GPU (every GPU has its own copy)
+    int num_cus[kMaxDevices] = {};
+    Status h_status;                          // host mirror of the status block (pageable: no pinned allocation)
+};
+StaticState g_static;
+
+int run_static(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
+               const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
+               hipStream_t s) {
+    int Q = 0;
+    int rc = resolve_hierarchy(P, ranks_per_node, &Q);
+    if (rc != TUNA_OK) return rc;
+    if (rl < 2 || rg < 2) return TUNA_ERR_ARG;
+    if (!sendcounts || !recvcounts || !sdispls || !rdispls) return TUNA_ERR_ARG;
+    const int N = P / Q;
+    // set-up, once per device with that device current: the address of this GPU's copy of the array
+    int dev = -1;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return TUNA_ERR_ARG;
+    if (!g_static.ptr[dev]) {
+        void* p = nullptr;
+        HIPCHK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) { g.last_hip_error = (int)hipErrorInvalidSymbol; return TUNA_ERR_HIP; }
+        int cus = 0;
+        HIPCHK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        g_static.num_cus[dev] = cus > 0 ? cus : 256;
+        g_static.ptr[dev] = (unsigned char*)p;
+    }
+    Carver cv(g_static.ptr[dev], (size_t)TUNA_NOALLOC_SCRATCH_BYTES);
+
+    Prepared pr;
+    pr.P = P; pr.Q = Q; pr.N = N;
+    pr.sb.num_cus = g_static.num_cus[dev];
+    pr.sb.d_status = cv.take<Status>(1);
+    pr.sb.d_vpart = cv.take<unsigned long long>(vpart_words(pr.sb.num_cus));
+    pr.sb.h_status = &g_static.h_status;
+    pr.fused = g.opt_fused != 0;
+    pr.staggered = g.opt_staggered != 0 && N > 1;
+    if (pr.staggered) rg = N;
+    pr.block_count = g.opt_block_count;
+    pr.sendbuf = sendbuf; pr.recvbuf = recvbuf; pr.sendcounts = sendcounts; pr.recvcounts = recvcounts;
+    pr.sdispls = sdispls; pr.rdispls = rdispls;
+
+    // ---- the schedule, its tables in scratch (see get_plan for the cached form) ------------------------
+    int crl, crg;
+    clamp_radices(Q, N, rl, rg, &crl, &crg);
+    DevicePlan dp;
+    dp.host = make_plan(P, Q, crl, crg, pr.fused, /*with_tables=*/false);
+    if ((int)dp.host.phases.size() > TUNA_MAX_PHASES) return TUNA_ERR_TOO_LARGE;
+    size_t table_bytes = align_up((size_t)P * 4);
+    for (const auto& ph : dp.host.phases) table_bytes += 6 * align_up((size_t)ph.nseg * 4) + align_up((size_t)P * 4);
+    if (cv.off + table_bytes > cv.cap) return TUNA_ERR_NOALLOC_LIMIT;     // before any kernel is launched
+    for (const auto& ph : dp.host.phases) {
+        const size_t stride = align_up((size_t)ph.nseg * 4) / 4;
+        int32_t* dm = cv.take<int32_t>(6 * stride);
+        int32_t* dz = cv.take<int32_t>(P);
+        hipLaunchKernelGGL(k_build_phase_table, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, dp.host.sc,
+                           phase_scalars(ph), dm, dm + stride, dm + 2 * stride, dm + 3 * stride, dm + 4 * stride,
+                           dm + 5 * stride, dz);
+        HIPCHK(hipGetLastError());
+        dp.d_zt.push_back(dz);
+        dp.d_seg.push_back(SegDev{dm, dm + stride, dm + 2 * stride, dm + 3 * stride, dm + 4 * stride, dm + 5 * stride});
+    }
+    dp.d_hm1 = cv.take<int32_t>(P);
+    hipLaunchKernelGGL(k_build_hops, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, dp.host.sc, dp.d_hm1);
+    HIPCHK(hipGetLastError());
+    dp.built_on = s;
+    pr.dp = &dp;
+
+    // ---- validation and sizing (one read-back), then the one-pass call ---------------------------------
+    Status hs{};
+    bool empty = false;
+    rc = prepare_sizes(pr, g.opt_dense_t, s, hs, &empty);
+    if (rc != TUNA_OK) return rc;
+    g.marks.clear();
+    g.end_recorded = false;
+    g.stats_plan = nullptr;
+    fill_stats_header(pr, hs, g.stats);
+    g.have_stats = true;
+    if (empty) return TUNA_OK;
+    const size_t mbytes = one_pass_meta_bytes(pr);
+    if (cv.off + mbytes + pr.ds.total > cv.cap) return TUNA_ERR_NOALLOC_LIMIT;
+    char* mbase = cv.base + cv.off;
+    g.no_marks = true;
+    rc = run_one_pass(pr, mbase, mbytes, mbase + mbytes, s, g.stats);
+    g.no_marks = false;
+    return rc;
+}
+
 }  // namespace
 }  // namespace tuna
 
@@ -960,6 +1105,13 @@ int tuna_alltoallv_hier(const void* sendbuf, const int32_t* sendcounts, const in
     if (local_radix < 2 || global_radix < 2) return TUNA_ERR_ARG;
     return run(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node, local_radix,
                global_radix, stream);
+}
+
+int tuna_alltoallv_noalloc(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
+                           const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node,
+                           int local_radix, int global_radix, void* stream) {
+    return run_static(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node, local_radix,
+                      global_radix, (hipStream_t)stream);
 }
 
 int tuna_alltoallv_init(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
@@ -1007,16 +1159,17 @@ int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node, i
     rc = get_plan(P, Q, local_radix, staggered ? N : global_radix, g.opt_fused != 0, nullptr, &dp);
     if (rc != TUNA_OK) return rc;
     const PlanHost& pl = dp->host;
-    rc = run_validate(sendcounts, nullptr, nullptr, nullptr, P, nullptr, (g.opt_dense_t != 0 && pl.slots > 0) ? dp : nullptr);
+    rc = run_validate(g.sb, sendcounts, nullptr, nullptr, nullptr, P, nullptr, (g.opt_dense_t != 0 && pl.slots > 0) ? dp : nullptr);
     if (rc != TUNA_OK) return rc;
-    const bool exact_t = choose_exact_t(g.opt_dense_t, P, *g.h_status) && pl.slots > 0;
+    const Status* h_status = g.sb.h_status;
+    const bool exact_t = choose_exact_t(g.opt_dense_t, P, *h_status) && pl.slots > 0;
     dp->complete = true;                                  // run_validate synchronised the stream the tables were built on
-    if (g.h_status->flags & 1u) return TUNA_ERR_NEGATIVE_COUNT;
-    const DataSizes ds = data_sizes_for(pl, g.h_status->max_count, g.h_status->total_chunks, g.opt_fused != 0, staggered,
-                                        exact_t, g.h_status->t_chunks);
+    if (h_status->flags & 1u) return TUNA_ERR_NEGATIVE_COUNT;
+    const DataSizes ds = data_sizes_for(pl, h_status->max_count, h_status->total_chunks, g.opt_fused != 0, staggered,
+                                        exact_t, h_status->t_chunks);
     *bytes = meta_bytes_for(P) + (exact_t ? exact_t_meta_bytes_for(pl, false) : 0) +
              ((g.opt_fused || staggered) ? align_up((size_t)P * P * 8) : 0) + ds.total;
-    if (use_two_pass(pl, *g.h_status)) {
+    if (use_two_pass(pl, *h_status)) {
         // the two-pass form keeps every phase's layouts; its staging is at most the one-pass form's
         Prepared pr;
         pr.P = P; pr.Q = Q; pr.N = N; pr.dp = dp; pr.ds = ds; pr.exact_t = exact_t;
@@ -1074,10 +1227,10 @@ int tuna_get_stats(tuna_stats_t* out) {
     if (g.end_recorded) {
         HIPCHK(hipEventSynchronize(g.ev_end));
         if (!g.stats_plan) {   // a persistent plan knows its per-phase bytes since it was made
-            HIPCHK(hipMemcpy(g.h_status, g.d_status, sizeof(Status), hipMemcpyDeviceToHost));
+            HIPCHK(hipMemcpy(g.sb.h_status, g.sb.d_status, sizeof(Status), hipMemcpyDeviceToHost));
             for (int i = 0; i < st.n_phases; ++i) {
-                st.phase[i].payload_bytes = (int64_t)g.h_status->phase_bytes[i];
-                st.phase[i].staged_bytes = (int64_t)g.h_status->phase_chunks[i] * 16;
+                st.phase[i].payload_bytes = (int64_t)g.sb.h_status->phase_bytes[i];
+                st.phase[i].staged_bytes = (int64_t)g.sb.h_status->phase_chunks[i] * 16;
             }
         }
         if (g.marks.size() > 1) {
@@ -1259,6 +1412,7 @@ const char* tuna_strerror(int code) {
         case TUNA_ERR_WORKSPACE_TOO_SMALL: return "caller-supplied workspace too small";
         case TUNA_ERR_HIP: return "HIP runtime error";
         case TUNA_ERR_TOO_LARGE: return "problem exceeds the supported range";
+        case TUNA_ERR_NOALLOC_LIMIT: return "problem needs more than the static scratch of tuna_alltoallv_noalloc";
         default: return "unknown error";
     }
 }
