@@ -436,7 +436,12 @@ struct Prepared {
     bool exact_kernels = false;         // T in exact size was asked for
     std::vector<LayoutDev> Lt;
     ExactT x{};
-    int64_t* sdispls_t = nullptr;       // one-kernel phases: transposed sdispls
+    HopDev hop{};                       // one-kernel phases of a one-pass call: the resolved addresses of the phase being run
+    // the ranks' own blocks: moved by the copy engine when blocks can be large (see launch_self_copy)
+    bool self_engine = false;
+    LayoutDev selfL{};
+    HopDev selfH{};
+    size_t self_units = 0;              // wave units to launch for: an upper bound, or the exact count of a plan
     int block_count = 0;                // rounds per batch of launches (0: all rounds of a phase at once)
     unsigned long long* rank_bytes = nullptr;   // [P] scratch of the metadata kernels
 };
@@ -560,7 +565,7 @@ int prepare_call(const void* sendbuf, const int32_t* sendcounts, const int64_t* 
 }
 
 int launch_phase_metadata(const Prepared& pr, size_t i, const int32_t* cur, int32_t* nxt, const LayoutDev& Ls,
-                          const LayoutDev& Lr, hipStream_t s) {
+                          const LayoutDev& Lr, const HopDev& hop, hipStream_t s) {
     const PhaseHost& ph = pr.dp->host.phases[i];
     const bool one_kernel = phase_is_one_kernel(pr, ph);
     PhaseLayoutArgs m{};
@@ -577,22 +582,101 @@ int launch_phase_metadata(const Prepared& pr, size_t i, const int32_t* cur, int3
     // P = 256, while at P = 4096 the separate kernel saves 44 us per phase): the scan kernel then
     // exchanges the sizes itself
     m.inline_exchange = pr.P <= 128 ? 1 : 0;
-    return phase_metadata(m, s, exact_t_of(pr, i));
+    int rc = phase_metadata(m, s, exact_t_of(pr, i));
+    if (rc != TUNA_OK || !one_kernel) return rc;
+    // one-kernel phase: where every block comes from and goes to, once per phase instead of once per wave
+    ResolveArgs ra{};
+    ra.nxt = nxt; ra.seg = pr.dp->d_seg[i]; ra.nseg = ph.nseg;
+    ra.P = pr.P; ra.Q = pr.Q; ra.N = pr.N; ra.dim = ph.dim; ra.rx = (int)ph.rx;
+    ra.S = (const unsigned char*)pr.sendbuf; ra.sdispls = pr.sdispls;
+    ra.R = (unsigned char*)pr.recvbuf; ra.rdispls = pr.rdispls;
+    ra.slots = pr.ds.slots; ra.slot_bytes = pr.ds.slot_bytes;
+    ra.x = exact_t_of(pr, i);
+    ra.hop = hop;
+    const dim3 grid((unsigned)((ph.nseg + 255) / 256), (unsigned)pr.P);
+    if (pr.exact_kernels) hipLaunchKernelGGL(k_resolve_hop<true>, grid, dim3(256), 0, s, ra);
+    else hipLaunchKernelGGL(k_resolve_hop<false>, grid, dim3(256), 0, s, ra);
+    HIPCHK(hipGetLastError());
+    return TUNA_OK;
 }
 
 bool any_one_kernel_phase(const Prepared& pr) { return pr.fused || pr.staggered; }
 
-int launch_transpose_displs(const Prepared& pr, hipStream_t s) {
-    if (!any_one_kernel_phase(pr)) return TUNA_OK;
-    const unsigned t = (unsigned)((pr.P + 31) / 32);
-    hipLaunchKernelGGL(k_transpose_displs, dim3(t, t), dim3(32, 8), 0, s, pr.sdispls, pr.sdispls_t, pr.P);
+// Resolved addresses of a one-kernel phase: row stride and bytes.
+int hop_ld_for(int nseg) { return (nseg + 31) / 32 * 32; }
+size_t hop_bytes_for(int P, int ld) { return 2 * align_up((size_t)P * ld * 8) + align_up((size_t)P * ld * 4); }
+void carve_hop(Carver& cv, int P, int ld, HopDev& h) {
+    h.ld = ld;
+    h.src = cv.take<unsigned long long>((size_t)P * ld);
+    h.dst = cv.take<unsigned long long>((size_t)P * ld);
+    h.size = cv.take<int>((size_t)P * ld);
+}
+// largest row stride any one-kernel phase of the call needs (0: it has none)
+int max_hop_ld(const Prepared& pr) {
+    int ld = 0;
+    for (const auto& ph : pr.dp->host.phases)
+        if (phase_is_one_kernel(pr, ph)) ld = std::max(ld, hop_ld_for(ph.nseg));
+    return ld;
+}
+
+// The block every rank keeps for itself (Section "Estimating temporary buffer size": one block is
+// destined for the rank itself) goes straight from S to R.  Small blocks: one workgroup per rank.  When
+// blocks can be large (M above 64 KiB) the own blocks are laid out as one more one-kernel phase and
+// the byte-balanced copy engine moves them, so that a 1 GiB diagonal block is spread over the whole
+// device like any other block.
+constexpr int kSelfEngineMinM = 1 << 16;
+bool self_uses_engine(const Prepared& pr) { return pr.max_count > kSelfEngineMinM; }
+size_t self_unit_bound(const Prepared& pr) {
+    // per rank at most ceil((15 + M + 15) / 16) chunks
+    return (size_t)pr.P * (((size_t)pr.max_count / 16 + 2) / kUnitChunks + 1);
+}
+size_t self_meta_bytes(const Prepared& pr) {
+    if (!self_uses_engine(pr)) return 0;
+    const size_t P = (size_t)pr.P;
+    return align_up(P * 2 * 4) + align_up(P * 4) + align_up((P + 1) * 8) + align_up((P + 1) * 4) + align_up(4) +
+           align_up(self_unit_bound(pr) * sizeof(int4)) + 2 * align_up(P * 8) + align_up(P * 4);
+}
+void carve_self(Carver& cv, Prepared& pr) {
+    pr.self_engine = self_uses_engine(pr);
+    if (!pr.self_engine) return;
+    const size_t P = (size_t)pr.P;
+    LayoutDev& L = pr.selfL;
+    L.ld = 2;
+    L.pre = cv.take<int>(P * 2);
+    L.tot = cv.take<int>(P);
+    L.rank_base = cv.take<long long>(P + 1);
+    L.unit_base = cv.take<int>(P + 1);
+    L.n_units = cv.take<int>(1);
+    pr.self_units = self_unit_bound(pr);
+    L.units = cv.take<int4>(pr.self_units);
+    carve_hop(cv, pr.P, 1, pr.selfH);
+}
+
+// layout of the own blocks for the copy engine (nothing to do for the one-workgroup-per-rank form)
+int launch_self_metadata(const Prepared& pr, hipStream_t s) {
+    if (!pr.self_engine) return TUNA_OK;
+    hipLaunchKernelGGL(k_self_layout, dim3((unsigned)((pr.P + 255) / 256)), dim3(256), 0, s,
+                       (const unsigned char*)pr.sendbuf, pr.sendcounts, pr.sdispls, (unsigned char*)pr.recvbuf, pr.rdispls,
+                       pr.P, pr.selfL, pr.selfH);
+    HIPCHK(hipGetLastError());
+    hipLaunchKernelGGL(k_layout_base, dim3(1), dim3(kScanThreads), 0, s, pr.P, pr.selfL, pr.selfL, pr.selfL,
+                       (unsigned long long*)nullptr, -1, -1, ExactT{}, (const unsigned long long*)nullptr,
+                       (unsigned long long*)nullptr, &pr.sb.d_status->self_units);
+    HIPCHK(hipGetLastError());
+    hipLaunchKernelGGL(k_layout_units, dim3(pr.P, 1), dim3(256), 2 * sizeof(int), s, 1, pr.selfL, pr.selfL, 2);
     HIPCHK(hipGetLastError());
     return TUNA_OK;
 }
 
 int launch_self_copy(const Prepared& pr, hipStream_t s) {
-    const int split = pr.max_count > (1 << 16) ? 16 : 1;
-    hipLaunchKernelGGL(k_self_copy, dim3(pr.P, split), dim3(256), 0, s, (const unsigned char*)pr.sendbuf,
+    if (pr.self_engine) {
+        CopyArgs a{};
+        a.L = pr.selfL; a.hop = pr.selfH; a.nseg = 1; a.seg_lo = 0; a.seg_hi = 1;
+        a.P = pr.P; a.Q = pr.Q; a.N = pr.N;
+        a.user_limit = pr.user_limit;
+        return launch_copy<kFused>(pr.gran, pr.self_units, a, s, pr.exact_kernels, 6);
+    }
+    hipLaunchKernelGGL(k_self_copy, dim3(pr.P, 1), dim3(256), 0, s, (const unsigned char*)pr.sendbuf,
                        pr.sendcounts, pr.sdispls, (unsigned char*)pr.recvbuf, pr.rdispls, pr.P);
     HIPCHK(hipGetLastError());
     return TUNA_OK;
@@ -600,8 +684,8 @@ int launch_self_copy(const Prepared& pr, hipStream_t s) {
 
 // The payload kernels of digit phase i: pack, exchange, unpack -- or the one-kernel hop.
 // unit_cap: number of wave units to launch for (an upper bound is fine).
-int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const LayoutDev& Lr, size_t unit_cap,
-                      hipStream_t s) {
+int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const LayoutDev& Lr, const HopDev& hop,
+                      size_t unit_cap, hipStream_t s) {
     const PhaseHost& ph = pr.dp->host.phases[i];
     CopyArgs a{};
     a.seg = pr.dp->d_seg[i]; a.nseg = ph.nseg;
@@ -646,10 +730,12 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
         int rc;
         if (phase_is_one_kernel(pr, ph)) {
             // one hop in one kernel: S / T of the sender -> R / the other copy of T at the receiver
-            a.stage = nullptr; a.L = Lr; a.counts = pr.recvcounts;
-            a.user = (unsigned char*)pr.sendbuf; a.displs = pr.sdispls_t;
-            a.user2 = (unsigned char*)pr.recvbuf; a.displs2 = pr.rdispls; a.T2 = pr.T;
-            rc = launch_copy<kFused>(pr.gran, launch_units, a, s, pr.exact_kernels);
+            a.stage = nullptr; a.L = Lr; a.hop = hop;
+            // measured on the 16 GiB workload: a phase of many rounds gathers short pieces from many senders
+            // and wants all the waves it can get (7 or 8 resident workgroups: 5.35 TB/s, 5 % less with 6); a
+            // phase of few rounds streams long runs and is fastest with 6 (5.4 TB/s; 10 % less with 8)
+            const int fused_resident = short_launch ? 8 : (ph.nz >= 32 ? 7 : 6);
+            rc = launch_copy<kFused>(pr.gran, launch_units, a, s, pr.exact_kernels, fused_resident);
             if (rc != TUNA_OK) return rc;
             mark(s, kCatPack, (int)i);
             continue;
@@ -687,8 +773,9 @@ bool use_two_pass(const PlanHost& pl, const Status& hs) {
 // Metadata bytes of a one-pass call: the two size matrices, one pair of layouts reused by every phase,
 // the exact-size T tables and, for one-kernel phases, the transposed send displacements.
 size_t one_pass_meta_bytes(const Prepared& pr) {
+    const int hld = max_hop_ld(pr);
     return meta_bytes_for(pr.P) + (pr.exact_t ? exact_t_meta_bytes_for(pr.dp->host, false) : 0) +
-           (any_one_kernel_phase(pr) ? align_up((size_t)pr.P * pr.P * 8) : 0);
+           (hld ? hop_bytes_for(pr.P, hld) : 0) + self_meta_bytes(pr);
 }
 
 // A call in one pass: rotation, the own blocks, then per digit phase its metadata kernels followed at
@@ -702,7 +789,8 @@ int run_one_pass(Prepared& pr, void* mbase, size_t mbytes, void* dbase, hipStrea
     MetaBuffers mb = carve_meta(cm, P);
     pr.rank_bytes = mb.rank_bytes;
     if (pr.exact_t) carve_exact_t(cm, pl, false, pr);
-    if (any_one_kernel_phase(pr)) pr.sdispls_t = cm.take<int64_t>((size_t)P * P);
+    if (const int hld = max_hop_ld(pr)) carve_hop(cm, P, hld, pr.hop);
+    carve_self(cm, pr);
     Carver cd(dbase, ds.total);
     mb.Ls.units = cd.take<int4>(ds.unit_cap);
     mb.Lr.units = cd.take<int4>(ds.unit_cap);
@@ -718,9 +806,9 @@ int run_one_pass(Prepared& pr, void* mbase, size_t mbytes, void* dbase, hipStrea
     const dim3 grot((unsigned)((P + 255) / 256), (unsigned)((P + kExchangeRanks - 1) / kExchangeRanks));
     hipLaunchKernelGGL(k_rotate_init, grot, dim3(256), 0, s, pr.sendcounts, mb.cur, P, pr.Q, pr.N);
     HIPCHK(hipGetLastError());
-    int rc = launch_transpose_displs(pr, s);
-    if (rc != TUNA_OK) return rc;
     mark(s, kCatPrepare, -1);
+    int rc = launch_self_metadata(pr, s);
+    if (rc != TUNA_OK) return rc;
     rc = launch_self_copy(pr, s);
     if (rc != TUNA_OK) return rc;
     mark(s, kCatSelf, -1);
@@ -729,10 +817,10 @@ int run_one_pass(Prepared& pr, void* mbase, size_t mbytes, void* dbase, hipStrea
     int32_t* cur = mb.cur;
     int32_t* nxt = mb.nxt;
     for (size_t i = 0; i < pl.phases.size(); ++i) {
-        rc = launch_phase_metadata(pr, i, cur, nxt, mb.Ls, mb.Lr, s);
+        rc = launch_phase_metadata(pr, i, cur, nxt, mb.Ls, mb.Lr, pr.hop, s);
         if (rc != TUNA_OK) return rc;
         mark(s, kCatMeta, (int)i);
-        rc = launch_phase_data(pr, i, mb.Ls, mb.Lr, ds.unit_cap, s);
+        rc = launch_phase_data(pr, i, mb.Ls, mb.Lr, pr.hop, ds.unit_cap, s);
         if (rc != TUNA_OK) return rc;
         std::swap(cur, nxt);
     }
@@ -792,6 +880,7 @@ struct Plan {
     void* mem_meta = nullptr;       // cur / nxt and every phase's two layouts
     void* mem_data = nullptr;       // staging and T
     std::vector<LayoutDev> Ls, Lr;  // per phase
+    std::vector<HopDev> hop;        // per phase (one-kernel phases only)
     std::vector<size_t> units;      // per phase: exact number of wave units (max of the two layouts)
     tuna_stats_t stats;
     unsigned long long phase_bytes[TUNA_MAX_PHASES];
@@ -814,8 +903,11 @@ void carve_full_layout(Carver& cv, int P, size_t unit_cap, LayoutDev& L) {
 size_t plan_meta_bytes(const Prepared& pr) {
     const PlanHost& pl = pr.dp->host;
     const size_t P2 = (size_t)pr.P * pr.P;
+    size_t hop_bytes = 0;
+    for (const auto& ph : pl.phases)
+        if (phase_is_one_kernel(pr, ph)) hop_bytes += hop_bytes_for(pr.P, hop_ld_for(ph.nseg));
     return 2 * align_up(P2 * 4) + align_up((size_t)pr.P * 8) + pl.phases.size() * 2 * layout_bytes_for(pr.P, pr.ds.unit_cap) +
-           (pr.exact_t ? exact_t_meta_bytes_for(pl, true) : 0) + (any_one_kernel_phase(pr) ? align_up(P2 * 8) : 0);
+           (pr.exact_t ? exact_t_meta_bytes_for(pl, true) : 0) + hop_bytes + self_meta_bytes(pr);
 }
 
 // Every phase's metadata in `meta` (plan_meta_bytes of it), then one read-back: exact unit counts,
@@ -838,16 +930,19 @@ int plan_build_metadata(Plan* plan, void* meta, size_t mbytes, hipStream_t s, bo
         carve_full_layout(cm, P, pr.ds.unit_cap, plan->Lr[i]);
     }
     if (pr.exact_t) carve_exact_t(cm, pl, true, pr);
-    if (any_one_kernel_phase(pr)) pr.sdispls_t = cm.take<int64_t>(P2);
+    plan->hop.assign(nph, HopDev{});
+    for (size_t i = 0; i < nph; ++i)
+        if (phase_is_one_kernel(pr, pl.phases[i])) carve_hop(cm, P, hop_ld_for(pl.phases[i].nseg), plan->hop[i]);
+    carve_self(cm, pr);
     if (!cm.ok) return TUNA_ERR_WORKSPACE_TOO_SMALL;
     const dim3 grot((unsigned)((P + 255) / 256), (unsigned)((P + kExchangeRanks - 1) / kExchangeRanks));
     hipLaunchKernelGGL(k_rotate_init, grot, dim3(256), 0, s, pr.sendcounts, cur, P, pr.Q, pr.N);
     HIPCHK(hipGetLastError());
-    int rc = launch_transpose_displs(pr, s);
+    int rc = launch_self_metadata(pr, s);
     if (rc != TUNA_OK) return rc;
     if (with_marks) mark(s, kCatPrepare, -1);
     for (size_t i = 0; i < nph; ++i) {
-        rc = launch_phase_metadata(pr, i, cur, nxt, plan->Ls[i], plan->Lr[i], s);
+        rc = launch_phase_metadata(pr, i, cur, nxt, plan->Ls[i], plan->Lr[i], plan->hop[i], s);
         if (rc != TUNA_OK) return rc;
         if (with_marks) mark(s, kCatMeta, (int)i);
         std::swap(cur, nxt);
@@ -857,6 +952,7 @@ int plan_build_metadata(Plan* plan, void* meta, size_t mbytes, hipStream_t s, bo
     HIPCHK(hipMemcpyAsync(pr.sb.h_status, pr.sb.d_status, sizeof(Status), hipMemcpyDeviceToHost, s));
     HIPCHK(hipStreamSynchronize(s));
     unsigned long long max_chunks = 0;
+    if (pr.self_engine) pr.self_units = h_status->self_units;     // exact from now on
     for (size_t i = 0; i < nph; ++i) {
         const bool one = phase_is_one_kernel(pr, pl.phases[i]);
         plan->units[i] = (size_t)std::max(h_status->phase_units[i][0], one ? 0u : h_status->phase_units[i][1]);
@@ -894,7 +990,7 @@ int plan_launch_data(const Plan* plan, hipStream_t s) {
     mark(s, kCatSelf, -1);
     const size_t nph = pr.dp->host.phases.size();
     for (size_t i = 0; i < nph; ++i) {
-        rc = launch_phase_data(pr, i, plan->Ls[i], plan->Lr[i], plan->units[i], s);
+        rc = launch_phase_data(pr, i, plan->Ls[i], plan->Lr[i], plan->hop[i], plan->units[i], s);
         if (rc != TUNA_OK) return rc;
     }
     return TUNA_OK;
@@ -1167,13 +1263,12 @@ int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node, i
     if (h_status->flags & 1u) return TUNA_ERR_NEGATIVE_COUNT;
     const DataSizes ds = data_sizes_for(pl, h_status->max_count, h_status->total_chunks, g.opt_fused != 0, staggered,
                                         exact_t, h_status->t_chunks);
-    *bytes = meta_bytes_for(P) + (exact_t ? exact_t_meta_bytes_for(pl, false) : 0) +
-             ((g.opt_fused || staggered) ? align_up((size_t)P * P * 8) : 0) + ds.total;
+    Prepared pr;
+    pr.P = P; pr.Q = Q; pr.N = N; pr.dp = dp; pr.ds = ds; pr.exact_t = exact_t;
+    pr.fused = g.opt_fused != 0; pr.staggered = staggered;
+    *bytes = one_pass_meta_bytes(pr) + ds.total;
     if (use_two_pass(pl, *h_status)) {
         // the two-pass form keeps every phase's layouts; its staging is at most the one-pass form's
-        Prepared pr;
-        pr.P = P; pr.Q = Q; pr.N = N; pr.dp = dp; pr.ds = ds; pr.exact_t = exact_t;
-        pr.fused = g.opt_fused != 0; pr.staggered = staggered;
         *bytes = plan_meta_bytes(pr) + (pr.fused ? 0 : 2 * align_up(ds.stage_chunks * 16)) +
                  (ds.t_bytes ? align_up(ds.t_bytes + kTailSlack) : 0);
     }

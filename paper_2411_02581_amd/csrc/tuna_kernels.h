@@ -47,6 +47,7 @@ struct Status {
     unsigned long long phase_bytes[64];   // payload bytes moved per phase
     unsigned long long phase_chunks[64];  // staged chunks per phase
     unsigned int phase_units[64][2];      // wave units per phase: [0] receive-side layout, [1] send-side layout
+    unsigned int self_units;              // wave units of the ranks' own blocks when the copy engine moves them
 };
 
 // The per-phase table of moving blocks on the device, one array per field (message order).
@@ -87,6 +88,20 @@ struct LayoutDev {
     int* n_units;                  // total units
     int ld;                        // row stride of pre (>= P + 1)
 };
+
+// One-kernel phases: where every block a rank receives in the phase is read from and written to,
+// resolved once per phase by k_resolve_hop, in the receive-side message order of the rank.  The copy
+// kernel then needs one round of loads (prefix, source, destination, size) before its payload loads
+// instead of three dependent ones (table, displacement or T position, payload).
+struct HopDev {
+    unsigned long long* src;       // [P][ld]: source address; kHopInT: an offset into T instead
+    unsigned long long* dst;       // [P][ld]: destination address; kHopInT: an offset into T; kHopFill: a T slot whose last line is filled up
+    int* size;                     // [P][ld]: bytes the destination takes: the exact count into R, whole chunks into T
+    int ld;
+};
+constexpr unsigned long long kHopInT = 1ull << 62;
+constexpr unsigned long long kHopFill = 1ull << 63;
+constexpr int kHopLanes = 16;      // lanes of a copy wave that fetch their hop entries before the prefix is known
 
 // ------------------------------------------------------------------------------------------
 // small helpers
@@ -300,26 +315,6 @@ __global__ void __launch_bounds__(256) k_validate_finish(const unsigned long lon
 }
 
 // ------------------------------------------------------------------------------------------
-// k_transpose_displs: out[j][i] = in[i][j] through a 32 x 32 LDS tile, block (32, 8).  A one-kernel
-// phase is tiled over the receiver but reads from the sender's S: with sdispls transposed the
-// displacements of the blocks a rank receives are consecutive instead of a column of the matrix.
-// ------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) k_transpose_displs(const int64_t* __restrict__ in, int64_t* __restrict__ out, int P) {
-    __shared__ int64_t tile[32][33];
-    const int tx = threadIdx.x, ty = threadIdx.y;
-    const int bi = blockIdx.y * 32, bj = blockIdx.x * 32;
-    for (int a = ty; a < 32; a += 8) {
-        const int i = bi + a, j = bj + tx;
-        if (i < P && j < P) tile[a][tx] = in[(size_t)i * P + j];
-    }
-    __syncthreads();
-    for (int a = ty; a < 32; a += 8) {
-        const int j = bj + a, i = bi + tx;
-        if (i < P && j < P) out[(size_t)j * P + i] = tile[tx][a];
-    }
-}
-
-// ------------------------------------------------------------------------------------------
 // k_rotate_init: the index-only initial rotation (Algorithm "TuNA", lines 4-5; Algorithm
 // "Coalesced TuNA_l^g", line 5).  No payload moves: cur[p][j*Q + l] becomes the size of the
 // block rank p = (n, g) holds at distance (j, l), i.e. its block for rank ((n-j)%N, (g-l)%Q).
@@ -371,6 +366,31 @@ __global__ void __launch_bounds__(256) k_self_copy(const unsigned char* __restri
         const int tail = n & 15;
         if ((int)threadIdx.x < tail) dst[(nchunk << 4) + threadIdx.x] = src[(nchunk << 4) + threadIdx.x];
     }
+}
+
+// ------------------------------------------------------------------------------------------
+// k_self_layout: the ranks' own blocks laid out as one more one-kernel phase of a single block per
+// rank, source S at sdispls[p][p], destination R at rdispls[p][p], so that the byte-balanced copy
+// engine moves them (large own blocks: one workgroup per rank would leave most of the device idle).
+// One thread per rank; k_layout_base and k_layout_units then cut the wave units as for any phase.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_self_layout(const unsigned char* __restrict__ S,
+                                                     const int32_t* __restrict__ sendcounts,
+                                                     const int64_t* __restrict__ sdispls, unsigned char* __restrict__ R,
+                                                     const int64_t* __restrict__ rdispls, int P, LayoutDev L, HopDev h) {
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= P) return;
+    const size_t d = (size_t)p * P + p;
+    const int sz = sendcounts[d];
+    const unsigned long long src = (unsigned long long)(S + sdispls[d]);
+    const unsigned long long dst = (unsigned long long)(R + rdispls[d]);
+    // chunks are cut at the destination's 16-byte boundaries, as in every one-kernel phase
+    const int chunks = sz > 0 ? (int)(((unsigned int)(dst & 15ull) + (unsigned int)sz + 15u) >> 4) : 0;
+    int* pre = L.pre + (size_t)p * L.ld;
+    pre[0] = 0; pre[1] = chunks;
+    L.tot[p] = chunks;
+    const size_t o = (size_t)p * h.ld;
+    h.src[o] = sz > 0 ? src : 0ull; h.dst[o] = sz > 0 ? dst : 0ull; h.size[o] = sz > 0 ? sz : 0;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -734,10 +754,8 @@ struct CopyArgs {
     // other side: send staging (exchange)
     const v4u* stage_src;
     LayoutDev Ls;
-    // fused: destination side
-    unsigned char* user2;               // R
-    const int64_t* displs2;             // rdispls
-    unsigned char* T2;                  // the copy of T written in this phase
+    // fused: every block's source and destination, resolved by k_resolve_hop
+    HopDev hop;
     // exact-size T (DENSE kernels): one arena per phase instead of slots
     ExactT x;
     // a launch may cover only the rounds of one batch: the segments [seg_lo, seg_hi) of every rank
@@ -792,8 +810,7 @@ __device__ __forceinline__ unsigned long long block_address(int slot, bool far_i
                                                             int j, int l, int P, int Q, int N,
                                                             unsigned char* user, const int64_t* displs,
                                                             unsigned char* T, long long slots, long long slot_bytes,
-                                                            const int32_t* counts = nullptr, int* count = nullptr,
-                                                            bool displs_transposed = false) {
+                                                            const int32_t* counts = nullptr, int* count = nullptr) {
     if (slot >= 0) return (unsigned long long)(T + ((long long)p * slots + slot) * slot_bytes);
     int pn, pg;
     if (!far_is_source) {
@@ -805,7 +822,6 @@ __device__ __forceinline__ unsigned long long block_address(int slot, bool far_i
     }
     const size_t idx = (size_t)p * P + pn * Q + pg;
     if (counts) *count = counts[idx];          // the caller's count for the same pair (exact size into R)
-    if (displs_transposed) return (unsigned long long)(user + displs[(size_t)(pn * Q + pg) * P + p]);
     return (unsigned long long)(user + displs[idx]);
 }
 
@@ -819,12 +835,82 @@ __device__ __forceinline__ unsigned long long exact_t_src(unsigned char* T, cons
     return (unsigned long long)(T + ((x.tbase[row] + (long long)x.tpos[row * P + e]) << 4));
 }
 
+// ------------------------------------------------------------------------------------------
+// k_resolve_hop: for a one-kernel phase, the source and the destination of every block every rank
+// receives (Algorithm "TuNA", lines 15-20 collapsed into one hop: the block goes from where its sender
+// holds it -- S at sdispls[sender][destination], or the sender's T -- straight to where its receiver
+// keeps it -- R at rdispls[receiver][source], or the receiver's T), in the receiver's message order.
+// One thread per (segment, receiving rank); grid (ceil(nseg / 256), P).  Addresses in T are stored as
+// offsets (kHopInT) because a persistent plan resolves them before its T is allocated.
+// ------------------------------------------------------------------------------------------
+struct ResolveArgs {
+    const int32_t* nxt;                 // [P][P] block sizes after the phase's size exchange (the receiver's view)
+    SegDev seg;
+    int nseg;
+    int P, Q, N, dim, rx;
+    const unsigned char* S;
+    const int64_t* sdispls;
+    unsigned char* R;
+    const int64_t* rdispls;
+    long long slots;                    // T in slots: slot s of rank p at offset (p * slots + s) * slot_bytes
+    long long slot_bytes;
+    ExactT x;                           // T in exact size
+    HopDev hop;
+};
+
+template <bool DENSE>
+__global__ void __launch_bounds__(256) k_resolve_hop(const ResolveArgs a) {
+    const int s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= a.nseg) return;
+    const int p = blockIdx.y;
+    const int n = p / a.Q, g = p - n * a.Q;
+    const int e = a.seg.e[s];
+    const int sz = a.nxt[(size_t)p * a.P + e];
+    const size_t o = (size_t)p * a.hop.ld + s;
+    if (sz <= 0) {                       // an empty block owns no chunk: its entry is never used
+        a.hop.src[o] = 0; a.hop.dst[o] = 0; a.hop.size[o] = 0;
+        return;
+    }
+    int j, l;
+    split_slot_index(e, a.Q, a.N, j, l);
+    const int ssrc = a.seg.src[s], sdst = a.seg.dst[s];
+    // the sender: the rank at distance z r^x upwards in the phase's dimension
+    const int q = partner_up(n, g, a.Q, a.N, a.dim, a.seg.z[s] * a.rx);
+    unsigned long long src, dst;
+    if (ssrc < 0) {                      // never moved: in the sender's S, addressed by its destination rank
+        const int qn = q / a.Q, qg = q - qn * a.Q;
+        int dn = qn - j; if (dn < 0) dn += a.N;
+        int dg = qg - l; if (dg < 0) dg += a.Q;
+        src = (unsigned long long)(a.S + a.sdispls[(size_t)q * a.P + dn * a.Q + dg]);
+    } else if (DENSE) {
+        const size_t row = (size_t)a.seg.srcph[s] * a.P + q;
+        src = (((unsigned long long)(a.x.tbase[row] + (long long)a.x.tpos[row * a.P + e])) << 4) | kHopInT;
+    } else {
+        src = (unsigned long long)(((long long)q * a.slots + ssrc) * a.slot_bytes) | kHopInT;
+    }
+    int size = sz;
+    if (sdst < 0) {                      // final: into R at the slot of its source rank, exactly `sz` bytes
+        int sn = n + j; if (sn >= a.N) sn -= a.N;
+        int sg = g + l; if (sg >= a.Q) sg -= a.Q;
+        dst = (unsigned long long)(a.R + a.rdispls[(size_t)p * a.P + sn * a.Q + sg]);
+    } else {
+        size = ((sz + 15) >> 4) << 4;    // T takes whole chunks
+        if (DENSE)
+            dst = (((unsigned long long)(a.x.tbase[(size_t)a.x.phase * a.P + p] + (long long)a.x.tpre[(size_t)p * a.x.ld + s])) << 4) | kHopInT;
+        else
+            dst = (unsigned long long)(((long long)p * a.slots + sdst) * a.slot_bytes) | kHopInT | kHopFill;
+    }
+    a.hop.src[o] = src; a.hop.dst[o] = dst; a.hop.size[o] = size;
+}
+
 // Compiled for 8 waves per SIMD (a workgroup is one wave per SIMD).  The host lowers the number of
 // resident workgroups per launch where fewer are faster by asking for unused dynamic LDS.  Unpack
 // keeps its payload in registers across the address resolution; left alone the compiler then takes
 // 84 registers (5 waves), held to 8 waves it needs 64 and spills nothing (byte-granular calls excepted).
+// The one-kernel variant needs 62 to 68 registers by itself; held to 8 waves it is scheduled for
+// occupancy and gathers of many short pieces run 6 % faster (measured at r = P on 16 GiB).
 template <int MODE, int GRAN, bool DENSE>
-__global__ void __launch_bounds__(kCopyThreads) __attribute__((amdgpu_waves_per_eu((MODE == kUnpack && GRAN >= 4) ? 8 : 1, 8)))
+__global__ void __launch_bounds__(kCopyThreads) __attribute__((amdgpu_waves_per_eu(((MODE == kUnpack || MODE == kFused) && GRAN >= 4) ? 8 : 1, 8)))
 k_copy(const CopyArgs a) {
     __shared__ int s_pre[kCopyThreads / kWave][kWave];
     __shared__ int s_size[kCopyThreads / kWave][kWave];
@@ -878,21 +964,34 @@ k_copy(const CopyArgs a) {
         int pre_i, pre_w;                            // pre_w is wave-uniform: the first prefix of the next window
         // table fields this mode needs, fetched together with the prefix
         int se = 0, sz_ = 0, ssrc = -1, sdst = -1, sph = -1;
+        unsigned long long addr = 0, addr2 = 0;
+        int size = 0, flag = 0;
         if (MODE == kFused) {
-            // One-kernel phases: every lane loads from an index clamped into range instead of under a branch,
-            // so that the six loads sit in one basic block and go out back to back (under branches the
-            // compiler waits for the prefix row before it asks for the table: measured 2 to 3.5 % slower).
-            // The empty statements keep the table loads from being sunk into the branch that uses them.
-            // The three-stage kernels are faster the other way round and keep their branches.
+            // One-kernel phases: source, destination and size of every block were resolved by k_resolve_hop.
+            // Every lane loads from an index clamped into range instead of under a branch, so that the
+            // loads sit in one basic block and go out back to back.
             const int s_tab = min(s, a.nseg - 1);
+            const size_t hi_ = (size_t)p * a.hop.ld + s_tab;
             const int pre_raw = prow[min(s, a.nseg)];
             const int pre_w_raw = prow[min(sw + kWave, a.nseg)];
-            se = a.seg.e[s_tab]; sz_ = a.seg.z[s_tab]; ssrc = a.seg.src[s_tab]; sdst = a.seg.dst[s_tab];
-            if (DENSE) sph = a.seg.srcph[s_tab];
-            asm volatile("" : "+v"(se), "+v"(sz_), "+v"(ssrc), "+v"(sdst));
-            if (DENSE) asm volatile("" : "+v"(sph));
+            // A unit of 256 chunks seldom overlaps more than a few blocks: the first kHopLanes lanes fetch
+            // their entries at once, together with the prefix (the condition depends on no loaded value);
+            // the others only when the prefix shows that the unit reaches that far (many tiny blocks).
+            const bool early = lane < kHopLanes;
+            unsigned long long hs_ = 0, hd_ = 0;
+            if (early) { hs_ = a.hop.src[hi_]; hd_ = a.hop.dst[hi_]; size = a.hop.size[hi_]; }
             pre_i = s <= a.nseg ? pre_raw : INT_MAX;
             pre_w = sw + kWave <= a.nseg ? pre_w_raw : INT_MAX;
+            const int reach = __popcll(__ballot(pre_i < cend));
+            if (reach > kHopLanes) {
+                if (!early && lane < reach) { hs_ = a.hop.src[hi_]; hd_ = a.hop.dst[hi_]; size = a.hop.size[hi_]; }
+            }
+            const unsigned long long tb = (unsigned long long)a.T;
+            addr = (hs_ & ~(kHopInT | kHopFill)) + ((hs_ & kHopInT) ? tb : 0ull);
+            addr2 = (hd_ & ~(kHopInT | kHopFill)) + ((hd_ & kHopInT) ? tb : 0ull);
+            // chunks are cut at the destination's 16-byte boundaries: `head` bytes of the first chunk lie
+            // before the block (0 in T, where blocks start on chunk or line boundaries)
+            flag = (int)(addr2 & 15ull) | ((hs_ & kHopInT) ? kFlagSrcT : 0) | ((hd_ & kHopFill) ? kFlagFill : 0);
         } else {
             pre_i = s <= a.nseg ? prow[s] : INT_MAX;
             pre_w = sw + kWave <= a.nseg ? prow[sw + kWave] : INT_MAX;
@@ -918,9 +1017,7 @@ k_copy(const CopyArgs a) {
             act[k] = pend[k] && c[k] < wend;
             if (MODE == kUnpack && act[k]) v[k] = __builtin_nontemporal_load(stage + c[k]);
         }
-        const bool need = s < a.nseg && pre_i < cend && pre_n > pre_i && pre_n > c0;
-        unsigned long long addr = 0, addr2 = 0;
-        int size = 0, flag = 0;
+        const bool need = MODE != kFused && s < a.nseg && pre_i < cend && pre_n > pre_i && pre_n > c0;
         if (need) {
             if (MODE == kExchange) {
                 const int ps = partner_up(n, g, a.Q, a.N, a.dim, sz_ * a.rx);
@@ -952,29 +1049,6 @@ k_copy(const CopyArgs a) {
                                              a.slots, a.slot_bytes, a.counts, &size);
                     if (!DENSE && sdst >= 0) flag |= kFlagFill; // T-bound: the tail lane completes the 128-byte line
                 }
-                if (MODE == kFused) {
-                    // tiled over the RECEIVER's layout: its stores into R are consecutive; the loads
-                    // gather from the sender at distance z*r^x upwards (S or its T slot)
-                    int sn = n, sg = g;
-                    const int dist = sz_ * a.rx;
-                    if (a.dim == 0) { sg += dist; if (sg >= a.Q) sg -= a.Q; }
-                    else { sn += dist; if (sn >= a.N) sn -= a.N; }
-                    if (DENSE && ssrc >= 0)
-                        addr = exact_t_src(a.T, a.x, a.P, sph, sn * a.Q + sg, se);
-                    else
-                        addr = block_address(ssrc, false, sn * a.Q + sg, sn, sg, bj, bl, a.P, a.Q, a.N, a.user,
-                                             a.displs, a.T, a.slots, a.slot_bytes, nullptr, nullptr, true);
-                    if (ssrc >= 0) flag |= kFlagSrcT;
-                    if (DENSE && sdst >= 0)
-                        addr2 = exact_t_dst(a.T2, a.x, a.P, p, s);
-                    else
-                        addr2 = block_address(sdst, true, p, n, g, bj, bl, a.P, a.Q, a.N, a.user2, a.displs2,
-                                              a.T2, a.slots, a.slot_bytes, a.counts, &size);
-                    // chunks are cut at the destination's 16-byte boundaries: `head` bytes of the
-                    // first chunk lie before the block (0 for T slots, which are line aligned)
-                    flag |= (int)(addr2 & 15ull);
-                    if (!DENSE && sdst >= 0) flag |= kFlagFill;
-                }
             }
         }
         wpre[lane] = pre_i;
@@ -991,7 +1065,6 @@ k_copy(const CopyArgs a) {
         int steps = 0;
         while ((1 << steps) < nlive) ++steps;
 
-        bool slow[kChunksPerLane];
         unsigned long long oa[kChunksPerLane], oa2[kChunksPerLane];
         int nb[kChunksPerLane], fill[kChunksPerLane];
         // The four searches of a lane advance together, without branches: every step is four independent
@@ -1026,15 +1099,30 @@ k_copy(const CopyArgs a) {
             if (MODE == kFused) oa2[k] = act[k] ? waddr2[lo[k]] + (unsigned long long)(long long)off : 0ull;
             else oa2[k] = 0;
             nb[k] = act[k] ? min(end, lim) - off : 0;
-            // last chunk of a T-bound block: number of further chunks up to the 128-byte line end
-            fill[k] = (act[k] && (fl & kFlagFill) && (end >= lim)) ? ((128 - (end & 127)) & 127) >> 4 : 0;
-            // a whole-chunk load from S is safe only inside the part of S that holds blocks
-            slow[k] = (MODE == kPack || MODE == kFused) && act[k] && !(fl & kFlagSrcT) && src + 16 > a.user_limit;
+            // last chunk of a T-bound block in a slot: number of further chunks up to the 128-byte line end
+            fill[k] = (!DENSE && act[k] && (fl & kFlagFill) && (end >= lim)) ? ((128 - (end & 127)) & 127) >> 4 : 0;
+            pend[k] = pend[k] && !act[k];
+            // Rare: a whole-chunk load from S is safe only inside the part of S that holds blocks.  The
+            // last few bytes of S are loaded exactly and stored at once; the chunk then takes no part in
+            // the batched loads and stores below (and none of its state stays live across them).
+            if ((MODE == kPack || MODE == kFused) && act[k] && !(fl & kFlagSrcT) && src + 16 > a.user_limit) {
+                const int ns = (int)min((unsigned long long)nb[k], a.user_limit - src);
+                const v4u t = load_block_chunk<GRAN>(reinterpret_cast<const unsigned char*>(src), min(ns, 15));
+                if (MODE == kPack) {
+                    __builtin_nontemporal_store(t, stage + c[k]);
+                } else {
+                    unsigned char* dst = reinterpret_cast<unsigned char*>(oa2[k]);
+                    store_block_chunk<GRAN>(dst, t, min(ns, 15));
+                    for (int f = 1; f <= fill[k]; ++f) *reinterpret_cast<v4u*>(dst + 16 * f) = t;
+                }
+                act[k] = false;
+                fill[k] = 0;
+            }
         }
         // ---- whole-chunk loads, all in flight before the first store --------------------------
 #pragma unroll
         for (int k = 0; k < kChunksPerLane; ++k) {
-            if (MODE != kUnpack && act[k] && !slow[k]) {
+            if (MODE != kUnpack && act[k]) {
                 if (MODE == kExchange) v[k] = *reinterpret_cast<const v4u*>(oa[k]);   // neighbours share its edge lines
                 // blocks that are whole 128-byte lines share no line with a neighbour: streaming loads
                 // (measured on 256-byte blocks: pack +7 to +19 %, one-kernel phases +3 to +6 %; with blocks
@@ -1046,7 +1134,7 @@ k_copy(const CopyArgs a) {
         // ---- stores: whole chunks into staging and T, exact bytes into R -------------------------
 #pragma unroll
         for (int k = 0; k < kChunksPerLane; ++k) {
-            if (act[k] && !slow[k]) {
+            if (act[k]) {
                 if (MODE == kUnpack || MODE == kFused) {
                     unsigned char* dst = reinterpret_cast<unsigned char*>(MODE == kFused ? oa2[k] : oa[k]);
                     // with exact-size T whole chunks stream into R and the arenas (measured: +3 to +9 %);
@@ -1067,11 +1155,11 @@ k_copy(const CopyArgs a) {
         // ---- line fill: after the last chunk of a T-bound block the rest of its 128-byte line is
         // written too (content is don't-care), so that T only ever sees whole-line writes.  One
         // store instruction per block tail: lanes 0..f-1 write the f missing chunks.
-        if (MODE == kUnpack || MODE == kFused) {
+        if (!DENSE && (MODE == kUnpack || MODE == kFused)) {
 #pragma unroll
             for (int k = 0; k < kChunksPerLane; ++k) {
                 const unsigned long long dsta = MODE == kFused ? oa2[k] : oa[k];
-                unsigned long long m = __ballot(act[k] && !slow[k] && fill[k] > 0);
+                unsigned long long m = __ballot(act[k] && fill[k] > 0);
                 while (m) {
                     const int leader = __ffsll((long long)m) - 1;
                     m &= m - 1;
@@ -1086,25 +1174,6 @@ k_copy(const CopyArgs a) {
                 }
             }
         }
-        // ---- rare: the last few bytes of S, loaded exactly --------------------------------------------
-        if (MODE == kPack || MODE == kFused) {
-#pragma unroll
-            for (int k = 0; k < kChunksPerLane; ++k) {
-                if (slow[k]) {
-                    const int ns = (int)min((unsigned long long)nb[k], a.user_limit - oa[k]);
-                    const v4u t = load_block_chunk<GRAN>(reinterpret_cast<const unsigned char*>(oa[k]), min(ns, 15));
-                    if (MODE == kPack) {
-                        __builtin_nontemporal_store(t, stage + c[k]);
-                    } else {
-                        unsigned char* dst = reinterpret_cast<unsigned char*>(oa2[k]);
-                        store_block_chunk<GRAN>(dst, t, min(ns, 15));
-                        for (int f = 1; f <= fill[k]; ++f) *reinterpret_cast<v4u*>(dst + 16 * f) = t;
-                    }
-                }
-            }
-        }
-#pragma unroll
-        for (int k = 0; k < kChunksPerLane; ++k) pend[k] = pend[k] && !act[k];
         if (wend >= cend) break;
         sw += kWave;
         __builtin_amdgcn_wave_barrier();

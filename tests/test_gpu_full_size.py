@@ -251,6 +251,44 @@ def test_one_block_of_a_gibibyte(tuna):
     assert tuna.tuna_get_stats().max_block_bytes == (1 << 30) + 20
 
 
+def test_own_blocks_of_64_mebibytes(tuna):
+    """P = 64 with about 64 MiB (byte-granular) kept by every rank for itself, 4 GiB on the diagonal,
+    small blocks elsewhere: the own blocks are spread over the whole device by the copy engine.  Whole
+    result against the oracle, three-stage and one-kernel phases; the own-block copy must not be the
+    slow part (it moves 4 GiB: well under 10 ms at HBM speed, seconds if one workgroup per rank did it)."""
+    P = 64
+    counts = wl.counts_uniform_bytes(P, 64, 2000)
+    rng = np.random.default_rng(64)
+    for p in range(P):
+        counts[p, p] = (64 << 20) + int(rng.integers(-100000, 100000))
+    lay = wl.make_layout(counts, gap=5)
+    send = wl.payload_position_hash_torch(640, lay.send_bytes, "cuda:0")
+    send_host = send.cpu().numpy()
+    want = np.full(lay.recv_bytes, 0x3C, dtype=np.uint8)
+    assert oracle.alltoallv(send_host, lay.sendcounts, lay.sdispls, want, lay.recvcounts, lay.rdispls) == 0
+    want_dev = torch.from_numpy(want).to("cuda:0")
+    del want, send_host
+    sc, sd, rc, rd = _upload(lay)
+    recv = torch.empty(lay.recv_bytes, dtype=torch.uint8, device="cuda:0")
+    for fused in (0, 1):
+        recv.fill_(0x3C)
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, fused)
+        tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 1)
+        try:
+            print("own blocks of 64 MiB, fused=%d" % fused, flush=True)
+            code = tuna.tuna_alltoallv(send, sc, sd, recv, rc, rd, P, 8, 0)
+            st = tuna.tuna_get_stats()
+        finally:
+            tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+            tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 0)
+        assert code == 0, tuna.tuna_strerror(code)
+        torch.cuda.synchronize()
+        assert torch.equal(recv, want_dev)
+        diag = int(np.trace(counts.astype(np.int64)))
+        print("own-block copy: %.3f ms, %.0f GB/s read + write" % (st.ms_self, 2 * diag / (st.ms_self * 1e-3) / 1e9), flush=True)
+        assert st.ms_self < 10.0
+
+
 def test_many_ranks_small_blocks(tuna):
     """P = 8192 (67 million blocks of 0..60 bytes, 4-byte granular): flat with radix 2 (13 digit
     phases) and radix P, and 64 ranks per node x 128 nodes; whole result against the oracle."""

@@ -240,6 +240,26 @@ def test_degenerate_inputs(tuna):
     run_hier(tuna, prob, 2, 2, 2)
 
 
+def test_large_own_blocks(tuna):
+    """Blocks a rank keeps for itself above 64 KiB go through the byte-balanced copy engine (one more
+    one-kernel phase of one block per rank) instead of one workgroup per rank: byte-granular sizes of
+    about 1 MiB on the diagonal, some ranks with an empty own block, small blocks elsewhere; also
+    P = 1 (nothing but the own block) and a hierarchy."""
+    P = 12
+    counts = wl.counts_uniform_bytes(P, 31, 400)
+    rng = np.random.default_rng(3)
+    for p in range(P):
+        counts[p, p] = 0 if p in (4, 9) else (1 << 20) + int(rng.integers(-5000, 5000))
+    lay = wl.make_layout(counts, gap=3, permute_seed=8)
+    prob = Problem(lay, wl.payload_position_hash(4, lay.send_bytes))
+    for r in (2, 12):
+        run_flat(tuna, prob, r)
+    run_hier(tuna, prob, 3, 2, 4)
+    lay = wl.make_layout(np.array([[300001]], dtype=np.int32), gap=5)
+    prob = Problem(lay, wl.payload_position_hash(5, lay.send_bytes))
+    run_flat(tuna, prob, 2)
+
+
 def test_many_empty_segments_span_windows(tuna):
     """More than one LDS window of segments inside a tile: long runs of empty blocks."""
     P = 700

@@ -72,6 +72,31 @@ def test_start_follows_the_send_buffer(tuna, P, Q, rl, rg, cfg, fused):
         assert tuna.tuna_plan_free(plan) == 0
 
 
+@pytest.mark.parametrize("fused", [0, 1])
+def test_plan_with_large_own_blocks(tuna, fused):
+    """The own blocks of a plan are laid out once for the copy engine when blocks can exceed 64 KiB."""
+    P = 10
+    counts = wl.counts_uniform_bytes(P, 17, 900)
+    for p in range(P):
+        counts[p, p] = 200000 + 7919 * p
+    lay = wl.make_layout(counts, gap=6)
+    res = Resident(lay)
+    tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, fused)
+    try:
+        code, plan = tuna.tuna_alltoallv_init(res.send, res.sc, res.sd, res.recv, res.rc, res.rd, P, 0, 3, 3)
+    finally:
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+    assert code == 0, tuna.tuna_strerror(code)
+    try:
+        for seed in (21, 22):
+            want = res.load(seed)
+            res.recv.fill_(CANARY)
+            assert tuna.tuna_start(plan) == 0
+            res.check(want, "start %d" % seed)
+    finally:
+        assert tuna.tuna_plan_free(plan) == 0
+
+
 def test_staggered_plan_and_stats(tuna):
     P, Q = 60, 5
     lay = wl.make_layout(wl.counts_uniform_bytes(P, 3, 900))
