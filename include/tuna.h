@@ -27,9 +27,13 @@
  *     an error is returned no payload byte has been moved.
  *   - sendbuf and recvbuf must not overlap.  The library uses the HIP device that is current at
  *     its first call; a compute call made while another device is current returns TUNA_ERR_ARG.
- *   - The library keeps one grow-only workspace and the statistics of the last call per process;
- *     calls are not thread-safe against each other, and two calls in flight on different streams
- *     share the workspace and therefore race.
+ *   - A context (tuna_ctx_t) holds what an immediate call uses besides the caller's arrays: a grow-only
+ *     workspace, a small status block and the statistics of its last call.  The entry points without a
+ *     context argument use the process's default context.  Calls on one context share its workspace:
+ *     a call issued on another stream than the context's previous call makes its stream wait for that
+ *     call first, so they do not race (and do not overlap).  Calls on different contexts share nothing
+ *     but the read-only cached schedules and may overlap.  A context is not thread-safe: one host
+ *     thread at a time per context; the process-wide defaults (tuna_set_option) are plain variables.
  *   - There is no CPU fallback: without a HIP device every compute entry point returns
  *     TUNA_ERR_HIP.
  */
@@ -53,6 +57,8 @@ extern "C" {
 #define TUNA_ERR_HIP -6              /* a HIP call failed; tuna_stats_t.last_hip_error has the code */
 #define TUNA_ERR_TOO_LARGE -7        /* P, a block or a per-rank byte total exceeds the supported range */
 #define TUNA_ERR_NOALLOC_LIMIT -8    /* tuna_alltoallv_noalloc: the call needs more than TUNA_NOALLOC_SCRATCH_BYTES */
+
+#define TUNA_RADIX_AUTO 0            /* as a radix argument: left to the library (the linear schedule, see tuna_select) */
 
 #define TUNA_MAX_PHASES 64
 #define TUNA_MAX_RANKS 32768
@@ -144,6 +150,50 @@ int tuna_alltoallv_hier(const void* sendbuf, const int32_t* sendcounts, const in
                         int P, int ranks_per_node, int local_radix, int global_radix, void* stream);
 
 /*
+ * Options of one call or plan.  tuna_opts_init fills the struct with the process-wide defaults (as
+ * tuna_set_option left them) and its size; a caller then changes what it wants and passes the struct
+ * to tuna_alltoallv_ex / tuna_alltoallv_init_ex.  A NULL options pointer means the defaults.
+ *   mode         TUNA_MODE_AUTO (default): left to the library, which takes the one-kernel hops --
+ *                with all ranks in one memory a hop needs no message, and moving a block straight from
+ *                where its sender holds it to where its receiver keeps it reads and writes it once
+ *                instead of three times.  TUNA_MODE_STAGED: pack -> exchange -> unpack, the paper's
+ *                three steps as three kernels.  TUNA_MODE_FUSED: the one-kernel hops.
+ *   staggered, t_layout, block_count, profile: as TUNA_OPT_STAGGERED, TUNA_OPT_DENSE_T,
+ *                TUNA_OPT_BLOCK_COUNT, TUNA_OPT_PROFILE below.
+ */
+#define TUNA_MODE_AUTO 0
+#define TUNA_MODE_STAGED 1
+#define TUNA_MODE_FUSED 2
+#define TUNA_T_SLOTS 0
+#define TUNA_T_EXACT 1
+#define TUNA_T_AUTO 2
+typedef struct tuna_opts {
+    int32_t struct_size;    /* sizeof(tuna_opts_t), set by tuna_opts_init */
+    int32_t mode;
+    int32_t staggered;
+    int32_t t_layout;
+    int32_t block_count;
+    int32_t profile;
+    int32_t reserved[2];
+} tuna_opts_t;
+int tuna_opts_init(tuna_opts_t* opts);
+
+/* A context of its own: workspace, status block, statistics.  tuna_ctx_create allocates a few hundred
+ * KiB and an event; tuna_ctx_destroy waits for the device and frees everything the context owns.
+ * NULL stands for the default context wherever a tuna_ctx_t is taken. */
+typedef struct tuna_ctx_s* tuna_ctx_t;
+int tuna_ctx_create(tuna_ctx_t* ctx);
+int tuna_ctx_destroy(tuna_ctx_t ctx);
+int tuna_ctx_get_stats(tuna_ctx_t ctx, tuna_stats_t* out);
+
+/* tuna_alltoallv_hier on a given context with given options (Section "Hierarchical TuNA"; the radices
+ * may be TUNA_RADIX_AUTO). */
+int tuna_alltoallv_ex(tuna_ctx_t ctx, const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls,
+                      void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls,
+                      int P, int ranks_per_node, int local_radix, int global_radix,
+                      const tuna_opts_t* opts, void* stream);
+
+/*
  * For callers that cannot allocate device memory when they call -- code under HIP graph capture
  * rules, tight serving loops, harnesses that forbid hipMalloc: the same call as
  * tuna_alltoallv_hier (same arguments, same result, the options in force apply, TUNA_OPT_PROFILE
@@ -183,6 +233,12 @@ int tuna_alltoallv_init(const void* sendbuf, const int32_t* sendcounts, const in
                         void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls,
                         int P, int ranks_per_node, int local_radix, int global_radix,
                         void* stream, tuna_plan_t* plan);
+/* The same with options and a context (which receives the plan's statistics and profiling events; the
+ * plan's device memory is its own either way). */
+int tuna_alltoallv_init_ex(tuna_ctx_t ctx, const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls,
+                           void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls,
+                           int P, int ranks_per_node, int local_radix, int global_radix,
+                           const tuna_opts_t* opts, void* stream, tuna_plan_t* plan);
 int tuna_start(tuna_plan_t plan, void* stream);
 int tuna_plan_free(tuna_plan_t plan);
 
@@ -204,8 +260,9 @@ int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node,
 int tuna_plain_copy(const void* src, void* dst, size_t bytes, void* stream);
 
 /*
- * Optional caller-owned workspace (device memory, 256-byte aligned).  While set, the library
- * allocates nothing and returns TUNA_ERR_WORKSPACE_TOO_SMALL when it does not suffice.
+ * Optional caller-owned workspace of the default context (device memory, 256-byte aligned).  While
+ * set, calls on that context allocate nothing and return TUNA_ERR_WORKSPACE_TOO_SMALL when it does
+ * not suffice.
  * tuna_set_workspace(NULL, 0) returns to the library-owned, grow-only workspace.
  */
 int tuna_set_workspace(void* workspace, size_t bytes);
@@ -220,7 +277,7 @@ int tuna_release(void);
  * analysis of coalesced and staggered TuNA_l^g": prepare, metadata, data, replace).
  * TUNA_OPT_FUSED: 1 = move every block of a phase straight from its source (S or T) to its
  * destination (R or T; with T in slots, the other of two copies of T) in one kernel instead of
- * pack -> exchange -> unpack.
+ * pack -> exchange -> unpack; 0 = the three kernels; 2 (default) = left to the library (tuna_opts_t.mode).
  * TUNA_OPT_STAGGERED: 1 = the staggered inter-node schedule of Algorithm "Staggered TuNA_l^g"
  * for hierarchical calls: after the intra-node phase every one of the Q (N - 1) blocks bound
  * for another node is its own message and goes straight from where it lies (its T slot, or S)
@@ -251,8 +308,8 @@ int tuna_release(void);
 #define TUNA_OPT_BLOCK_COUNT 5
 int tuna_set_option(int option, int value);
 
-/* Statistics of the last tuna_alltoallv* call (host struct).  Synchronises with that call's
- * stream work when profiling is on. */
+/* Statistics of the last tuna_alltoallv* call on the default context (host struct).  Synchronises
+ * with that call's stream work. */
 int tuna_get_stats(tuna_stats_t* out);
 
 /* Schedule description, host only. */
@@ -283,21 +340,44 @@ int tuna_plan_phase_device(int P, int ranks_per_node, int local_radix, int globa
                            int32_t* seg, int seg_capacity);
 
 /*
- * Radix choice for one GPU.  The paper picks r from P and the block size because each of its K
- * rounds pays a network latency (Section "Performance analysis of TuNA", "Radix selection":
- * small blocks -> r near 2, medium -> r near sqrt(P), large -> r near P).  In one HBM a round has
- * no latency of its own; the cost model of a call is
- *     t(r) = t_call(P) + w(r) * t_phase(P) + c * H(r) * payload_bytes / BW,
- * c = 6 (pack, exchange, unpack each read and write the moving bytes) or 2 with fused rounds,
- * H(r) = average number of hops of a block = sum over digit positions of the share of indices
- * whose digit is non-zero, w(r) = digits, with t_call, t_phase and BW measured on MI355X.
- * Evaluates the model for the candidate radices 2, 4, 8, ..., ceil(sqrt(size)), size of each
- * dimension and returns the minimiser (host only; *predicted_ms may be NULL).  Both H and w
- * fall as r grows, so the answer is the linear schedule r = Q, r = N for every payload; the
- * function exists so that callers do not hard-code that and so that the model is testable.
+ * Radix, mode and T layout for one GPU, from a cost model fitted to timed calls.  The paper picks r
+ * from P and the block size because each of its K rounds pays a network latency (Section "Performance
+ * analysis of TuNA", "Radix selection": small blocks -> r near 2, medium -> r near sqrt(P), large -> r
+ * near P).  In one HBM a round has no latency of its own; the model of an immediate call is
+ *     ms = c0 + c1 * phases + c2 * P^2 / 1e6 + c3 * hop bytes / 1e9 + c4 * moving blocks / 1e6,
+ * phases = digits of the two radices, hop bytes = payload bytes times the average number of hops of a
+ * block (the share of rank distances whose digit is non-zero, summed over the digit positions), moving
+ * blocks = the same count in blocks; one set of constants for three-stage phases and one for one-kernel
+ * hops; T in the paper's slots adds to the byte term by how empty the slots are (mean block / M).
+ *   tuna_calibrate   times about forty immediate calls of dense synthetic problems on the current
+ *                    device (a few hundred milliseconds; allocates up to about 8 GiB and frees it;
+ *                    synchronises) and fits the constants to them.  Without it the constants are the
+ *                    built-in ones, fitted the same way on an MI355X.
+ *   tuna_predict_ms  the model's time for one setting.  max_block_bytes = 0: unknown (slots taken as full).
+ *                    granularity: the largest of 1, 4, 16, 128 that divides every count, displacement
+ *                    and both buffer addresses (tuna_stats_t.granularity), 0 = unknown (taken as 4);
+ *                    byte-granular problems run kernel variants whose byte term costs a fitted factor more.
+ *   tuna_select      evaluates the model for the radices 2, 4, 8, ..., ceil(sqrt(size)), size of each
+ *                    dimension, both modes and both T layouts and returns the minimiser.  Every term
+ *                    falls as r grows and one-kernel hops move a third of the bytes, so the answer on
+ *                    one GPU is the linear schedule (r = Q, r = N) with one-kernel hops for every
+ *                    payload; the function exists so that callers do not hard-code that, and so that
+ *                    the model can be checked against measurements (the GPU tests do).
+ * All three are host functions; only tuna_calibrate touches the GPU.
  */
-int tuna_select_radix(int P, int ranks_per_node, int64_t payload_bytes, int* local_radix,
-                      int* global_radix, double* predicted_ms);
+typedef struct tuna_choice {
+    int32_t local_radix, global_radix;
+    int32_t mode;            /* TUNA_MODE_STAGED or TUNA_MODE_FUSED */
+    int32_t t_layout;        /* TUNA_T_EXACT or TUNA_T_SLOTS */
+    int32_t calibrated;      /* 1: constants fitted by tuna_calibrate in this process; 0: the built-in ones */
+    int32_t reserved;
+    double predicted_ms;     /* of one immediate call with this setting */
+} tuna_choice_t;
+int tuna_calibrate(void* stream);
+int tuna_predict_ms(int P, int ranks_per_node, int local_radix, int global_radix, int mode, int t_layout,
+                    int64_t payload_bytes, int64_t max_block_bytes, int granularity, double* ms);
+int tuna_select(int P, int ranks_per_node, int64_t payload_bytes, int64_t max_block_bytes, int granularity,
+                tuna_choice_t* out);
 
 /* Slot of block index o (1 <= o, not a direct block) in T for radix r:
  * t = o - 1 - dx (r - 1) - dz with dx the position and dz the value of o's highest base-r digit
@@ -306,6 +386,8 @@ int tuna_t_index(int o, int radix);
 
 const char* tuna_strerror(int code);
 int tuna_version(void);
+/* Hash of the sources this library was built from (set by the build script; "unknown" otherwise). */
+const char* tuna_build_id(void);
 
 #ifdef __cplusplus
 }

@@ -29,10 +29,14 @@ TUNA_OPT_STAGGERED = 3
 TUNA_OPT_DENSE_T = 4
 TUNA_OPT_BLOCK_COUNT = 5
 TUNA_MAX_PHASES = 64
+TUNA_RADIX_AUTO = 0
+TUNA_MODE_AUTO, TUNA_MODE_STAGED, TUNA_MODE_FUSED = 0, 1, 2
+TUNA_T_SLOTS, TUNA_T_EXACT, TUNA_T_AUTO = 0, 1, 2
 
-EXPORTS = ("tuna_alltoallv", "tuna_alltoallv_hier", "tuna_alltoallv_noalloc", "tuna_workspace_bytes", "tuna_set_workspace",
+EXPORTS = ("tuna_alltoallv", "tuna_alltoallv_hier", "tuna_alltoallv_noalloc", "tuna_alltoallv_ex", "tuna_alltoallv_init_ex",
+           "tuna_opts_init", "tuna_ctx_create", "tuna_ctx_destroy", "tuna_ctx_get_stats", "tuna_build_id", "tuna_workspace_bytes", "tuna_set_workspace",
            "tuna_release", "tuna_set_option", "tuna_get_stats", "tuna_plan_info", "tuna_plan_phase",
-           "tuna_t_index", "tuna_plan_phase_device", "tuna_plan_phase_sources", "tuna_plain_copy", "tuna_select_radix", "tuna_alltoallv_init", "tuna_start", "tuna_plan_free",
+           "tuna_t_index", "tuna_plan_phase_device", "tuna_plan_phase_sources", "tuna_plain_copy", "tuna_select", "tuna_predict_ms", "tuna_calibrate", "tuna_alltoallv_init", "tuna_start", "tuna_plan_free",
            "tuna_strerror", "tuna_version")
 
 
@@ -61,6 +65,18 @@ class tuna_stats_t(ctypes.Structure):
                 ("phase", tuna_phase_stats_t * TUNA_MAX_PHASES)]
 
 
+class tuna_opts_t(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_int32), ("mode", ctypes.c_int32), ("staggered", ctypes.c_int32),
+                ("t_layout", ctypes.c_int32), ("block_count", ctypes.c_int32), ("profile", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 2)]
+
+
+class tuna_choice_t(ctypes.Structure):
+    _fields_ = [("local_radix", ctypes.c_int32), ("global_radix", ctypes.c_int32), ("mode", ctypes.c_int32),
+                ("t_layout", ctypes.c_int32), ("calibrated", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("predicted_ms", ctypes.c_double)]
+
+
 class tuna_plan_info_t(ctypes.Structure):
     _fields_ = [("P", ctypes.c_int32), ("Q", ctypes.c_int32), ("N", ctypes.c_int32),
                 ("local_radix", ctypes.c_int32), ("global_radix", ctypes.c_int32),
@@ -79,20 +95,31 @@ def library_path() -> str:
 
 
 def load() -> ctypes.CDLL:
-    """Load libtuna.so (building it first only when no built library exists)."""
+    """Load libtuna.so.  The library carries a hash of the sources it was built from: when that differs
+    from the sources next to it (or no library exists) it is rebuilt first, so that tests and benchmarks
+    never report on code that is not the code in the tree."""
     global _lib
     if _lib is not None:
         return _lib
     path = os.environ.get("TUNA_LIBRARY", "")      # debugging aid: load another build of the library
     if not path:
         path = _build.LIB
-        if not os.path.exists(path):
+        if not os.path.exists(path) or _built_from(path) != _build.source_hash():
             _build.build_library(force=True)
     lib = ctypes.CDLL(path)
     vp, i, i64p = ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p
     lib.tuna_alltoallv.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, vp]
     lib.tuna_alltoallv_hier.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
     lib.tuna_alltoallv_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
+    lib.tuna_alltoallv_ex.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, ctypes.POINTER(tuna_opts_t), vp]
+    lib.tuna_alltoallv_init_ex.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, ctypes.POINTER(tuna_opts_t), vp,
+                                           ctypes.POINTER(ctypes.c_void_p)]
+    lib.tuna_opts_init.argtypes = [ctypes.POINTER(tuna_opts_t)]
+    lib.tuna_ctx_create.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    lib.tuna_ctx_destroy.argtypes = [vp]
+    lib.tuna_ctx_get_stats.argtypes = [vp, ctypes.POINTER(tuna_stats_t)]
+    lib.tuna_build_id.argtypes = []
+    lib.tuna_build_id.restype = ctypes.c_char_p
     lib.tuna_alltoallv_init.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, ctypes.POINTER(ctypes.c_void_p)]
     lib.tuna_start.argtypes = [vp, vp]
     lib.tuna_plan_free.argtypes = [vp]
@@ -103,8 +130,9 @@ def load() -> ctypes.CDLL:
     lib.tuna_get_stats.argtypes = [ctypes.POINTER(tuna_stats_t)]
     lib.tuna_plan_info.argtypes = [i, i, i, i, ctypes.POINTER(tuna_plan_info_t)]
     lib.tuna_plan_phase.argtypes = [i, i, i, i, i, vp, vp, i]
-    lib.tuna_select_radix.argtypes = [i, i, ctypes.c_int64, ctypes.POINTER(ctypes.c_int),
-                                      ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_double)]
+    lib.tuna_select.argtypes = [i, i, ctypes.c_int64, ctypes.c_int64, i, ctypes.POINTER(tuna_choice_t)]
+    lib.tuna_predict_ms.argtypes = [i, i, i, i, i, i, ctypes.c_int64, ctypes.c_int64, i, ctypes.POINTER(ctypes.c_double)]
+    lib.tuna_calibrate.argtypes = [vp]
     lib.tuna_plan_phase_device.argtypes = [i, i, i, i, i, vp, i]
     lib.tuna_plan_phase_sources.argtypes = [i, i, i, i, i, i, vp, i]
     lib.tuna_t_index.argtypes = [i, i]
@@ -113,10 +141,23 @@ def load() -> ctypes.CDLL:
     lib.tuna_strerror.restype = ctypes.c_char_p
     lib.tuna_version.argtypes = []
     for name in EXPORTS:
-        if name != "tuna_strerror":
+        if name not in ("tuna_strerror", "tuna_build_id"):
             getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
+
+
+def _built_from(path: str) -> str:
+    """tuna_build_id of the library file at `path`, read from the file (the library is not loaded: a
+    stale one could not be unloaded again)."""
+    marker = b"tuna-build-id:"
+    try:
+        with open(path, "rb") as f:
+            data = f.read()
+    except OSError:
+        return ""
+    k = data.find(marker)
+    return data[k + len(marker):k + len(marker) + 16].decode("ascii", "replace") if k >= 0 else ""
 
 
 def _ptr(a: Any, dtype=None) -> Optional[int]:
@@ -157,6 +198,61 @@ def tuna_alltoallv_hier(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdisp
     return load().tuna_alltoallv_hier(_ptr(sendbuf), _ptr(sendcounts, torch.int32), _ptr(sdispls, torch.int64),
                                       _ptr(recvbuf), _ptr(recvcounts, torch.int32), _ptr(rdispls, torch.int64),
                                       P, ranks_per_node, local_radix, global_radix, _stream(stream))
+
+
+def tuna_opts_init() -> tuna_opts_t:
+    """A tuna_opts_t holding the process-wide defaults."""
+    o = tuna_opts_t()
+    rc = load().tuna_opts_init(ctypes.byref(o))
+    if rc != TUNA_OK:
+        raise RuntimeError("tuna_opts_init: " + tuna_strerror(rc))
+    return o
+
+
+def tuna_ctx_create():
+    """Returns (code, context handle)."""
+    ctx = ctypes.c_void_p(None)
+    rc = load().tuna_ctx_create(ctypes.byref(ctx))
+    return rc, ctx.value
+
+
+def tuna_ctx_destroy(ctx) -> int:
+    return load().tuna_ctx_destroy(ctx)
+
+
+def tuna_ctx_get_stats(ctx) -> tuna_stats_t:
+    st = tuna_stats_t()
+    rc = load().tuna_ctx_get_stats(ctx, ctypes.byref(st))
+    if rc != TUNA_OK:
+        raise RuntimeError("tuna_ctx_get_stats: " + tuna_strerror(rc))
+    return st
+
+
+def tuna_alltoallv_ex(ctx, sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P: int, ranks_per_node: int,
+                      local_radix: int, global_radix: int, opts: Optional[tuna_opts_t] = None, stream=None) -> int:
+    import torch
+    return load().tuna_alltoallv_ex(ctx, _ptr(sendbuf), _ptr(sendcounts, torch.int32), _ptr(sdispls, torch.int64),
+                                    _ptr(recvbuf), _ptr(recvcounts, torch.int32), _ptr(rdispls, torch.int64),
+                                    P, ranks_per_node, local_radix, global_radix,
+                                    ctypes.byref(opts) if opts is not None else None, _stream(stream))
+
+
+def tuna_alltoallv_init_ex(ctx, sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P: int,
+                           ranks_per_node: int, local_radix: int, global_radix: int,
+                           opts: Optional[tuna_opts_t] = None, stream=None):
+    """Returns (code, plan handle)."""
+    import torch
+    plan = ctypes.c_void_p(None)
+    rc = load().tuna_alltoallv_init_ex(ctx, _ptr(sendbuf), _ptr(sendcounts, torch.int32), _ptr(sdispls, torch.int64),
+                                       _ptr(recvbuf), _ptr(recvcounts, torch.int32), _ptr(rdispls, torch.int64),
+                                       P, ranks_per_node, local_radix, global_radix,
+                                       ctypes.byref(opts) if opts is not None else None, _stream(stream),
+                                       ctypes.byref(plan))
+    return rc, plan.value
+
+
+def tuna_build_id() -> str:
+    return load().tuna_build_id().decode()
 
 
 def tuna_alltoallv_noalloc(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P: int,
@@ -237,12 +333,24 @@ def tuna_plan_phase(P: int, ranks_per_node: int, local_radix: int, global_radix:
     return rc, header, seg
 
 
-def tuna_select_radix(P: int, ranks_per_node: int, payload_bytes: int):
-    """Returns (code, local_radix, global_radix, predicted_ms).  Host only."""
-    rl, rg, ms = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_double(0.0)
-    rc = load().tuna_select_radix(P, ranks_per_node, payload_bytes, ctypes.byref(rl), ctypes.byref(rg),
-                                  ctypes.byref(ms))
-    return rc, rl.value, rg.value, ms.value
+def tuna_select(P: int, ranks_per_node: int, payload_bytes: int, max_block_bytes: int = 0, granularity: int = 0):
+    """Returns (code, tuna_choice_t).  Host only."""
+    ch = tuna_choice_t()
+    rc = load().tuna_select(P, ranks_per_node, payload_bytes, max_block_bytes, granularity, ctypes.byref(ch))
+    return rc, ch
+
+
+def tuna_predict_ms(P: int, ranks_per_node: int, local_radix: int, global_radix: int, mode: int, t_layout: int,
+                    payload_bytes: int, max_block_bytes: int = 0, granularity: int = 0):
+    """Returns (code, predicted milliseconds of one immediate call).  Host only."""
+    ms = ctypes.c_double(0.0)
+    rc = load().tuna_predict_ms(P, ranks_per_node, local_radix, global_radix, mode, t_layout, payload_bytes,
+                                max_block_bytes, granularity, ctypes.byref(ms))
+    return rc, ms.value
+
+
+def tuna_calibrate(stream=None) -> int:
+    return load().tuna_calibrate(_stream(stream))
 
 
 def tuna_plan_phase_device(P: int, ranks_per_node: int, local_radix: int, global_radix: int, phase: int, nseg: int):

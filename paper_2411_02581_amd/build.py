@@ -1,6 +1,7 @@
 """Builds libtuna.so (the HIP kernels + the C ABI) in-tree for gfx950 with hipcc."""
 from __future__ import annotations
 
+import hashlib
 import os
 import subprocess
 import sys
@@ -13,9 +14,20 @@ HEADERS = [os.path.join(CSRC, "tuna_kernels.h"), os.path.join(CSRC, "tuna_plan.h
            os.path.join(os.path.dirname(HERE), "include", "tuna.h")]
 
 
+def source_hash() -> str:
+    """Hash of every source and header the library is built from; compiled into the library
+    (tuna_build_id) so that a loaded library can be told from one built from other sources."""
+    h = hashlib.sha256()
+    for f in SOURCES + HEADERS:
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
 def hipcc_command(out: str) -> list:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     return [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
+            "-DTUNA_BUILD_ID=\"%s\"" % source_hash(),
             # packed-FP32 instructions are not wanted in any code object of this library
             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
             "-Wall", "-Wno-unused-function", "-Wno-unused-command-line-argument",

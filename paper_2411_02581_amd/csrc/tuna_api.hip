@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <chrono>
+#include <cmath>
 #include <cstdio>
 #include <cstring>
 #include <map>
@@ -53,33 +55,55 @@ enum Category { kCatPrepare = 0, kCatSelf, kCatMeta, kCatPack, kCatExchange, kCa
 
 struct Mark { hipEvent_t ev; int cat; int phase; };
 
-struct Ctx {
+// Options of one call or plan (tuna_opts_t, or the process-wide defaults that tuna_set_option edits).
+struct Options {
+    int profile = 0;
+    int mode = TUNA_MODE_AUTO;
+    int staggered = 0;
+    int t_layout = TUNA_T_AUTO;
+    int block_count = 0;
+};
+
+// Process-wide state: the device, the cached schedules (read-only once built), the default options.
+struct Shared {
     bool ready = false;
     int device = -1;
+    int num_cus = 256;
+    std::map<std::tuple<int, int, int, int, int>, DevicePlan> plans;
+    int live_plans = 0;                 // persistent plans not yet freed (they point into `plans`)
+    int live_contexts = 0;              // contexts made by tuna_ctx_create and not yet destroyed
+    int last_hip_error = 0;
+    Options defaults;
+};
+
+Shared sh;
+
+// Everything one immediate call writes besides the caller's receive buffer: the workspace, the status
+// block, the statistics and the profiling events.  Calls that share a context share these; calls on
+// different contexts share nothing and may overlap in time.
+struct Ctx {
+    bool ready = false;
     StatusBufs sb;                    // status block, its pinned host mirror, validation partials (one-time small allocations)
     void* meta = nullptr;  size_t meta_bytes = 0;   // library-owned, grow-only
     void* data = nullptr;  size_t data_bytes = 0;
     void* user_ws = nullptr; size_t user_ws_bytes = 0;
-    std::map<std::tuple<int, int, int, int, int>, DevicePlan> plans;
     tuna_stats_t stats;
     bool have_stats = false;
-    int opt_profile = 0, opt_fused = 0, opt_staggered = 0, opt_dense_t = 2, opt_block_count = 0;
+    bool profile = false;               // the call being issued records events
     std::vector<hipEvent_t> ev_pool;
     std::vector<Mark> marks;
     hipEvent_t ev_end = nullptr;
     bool end_recorded = false;
-    int live_plans = 0;                 // persistent plans not yet freed (they point into `plans`)
+    hipStream_t last_stream = nullptr;  // stream of the last immediate call (its end is ev_end when end_recorded)
     const void* stats_plan = nullptr;   // the statistics on file belong to this persistent plan (payload bytes known)
-    int last_hip_error = 0;
-    bool no_marks = false;              // set while the entry point that allocates nothing runs: it creates no events
 };
 
-Ctx g;
+Ctx g;                                  // the default context
 
 #define HIPCHK(expr)                                                       \
     do {                                                                   \
         hipError_t _e = (expr);                                            \
-        if (_e != hipSuccess) { g.last_hip_error = (int)_e; g.stats.last_hip_error = (int)_e; return TUNA_ERR_HIP; } \
+        if (_e != hipSuccess) { sh.last_hip_error = (int)_e; return TUNA_ERR_HIP; } \
     } while (0)
 
 inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
@@ -87,28 +111,48 @@ inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a
 // 64-bit words of the validation pass's partial results: at most 8 workgroups per compute unit
 inline size_t vpart_words(int num_cus) { return (size_t)num_cus * 8 * kValPartial; }
 
-int ensure_ctx() {
-    if (g.ready) {
-        // the workspace, the schedules and the status block live on the first call's device: refuse to
-        // launch kernels on them from another one
+// The library runs on the HIP device that is current at its first call.
+int ensure_device() {
+    if (sh.ready) {
+        // the workspaces, the schedules and the status blocks live on the first call's device: refuse
+        // to launch kernels on them from another one
         int dev = -1;
         HIPCHK(hipGetDevice(&dev));
-        return dev == g.device ? TUNA_OK : TUNA_ERR_ARG;
+        return dev == sh.device ? TUNA_OK : TUNA_ERR_ARG;
     }
     int ndev = 0;
     HIPCHK(hipGetDeviceCount(&ndev));
-    if (ndev < 1) { g.last_hip_error = (int)hipErrorNoDevice; return TUNA_ERR_HIP; }
-    HIPCHK(hipGetDevice(&g.device));
+    if (ndev < 1) { sh.last_hip_error = (int)hipErrorNoDevice; return TUNA_ERR_HIP; }
+    HIPCHK(hipGetDevice(&sh.device));
     hipDeviceProp_t prop;
-    HIPCHK(hipGetDeviceProperties(&prop, g.device));
-    g.sb.num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-    HIPCHK(hipMalloc((void**)&g.sb.d_status, align_up(sizeof(Status))));
-    HIPCHK(hipHostMalloc((void**)&g.sb.h_status, sizeof(Status), hipHostMallocDefault));
-    HIPCHK(hipMalloc((void**)&g.sb.d_vpart, align_up(vpart_words(g.sb.num_cus) * 8)));
-    HIPCHK(hipEventCreate(&g.ev_end));
-    std::memset(&g.stats, 0, sizeof(g.stats));
-    g.ready = true;
+    HIPCHK(hipGetDeviceProperties(&prop, sh.device));
+    sh.num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    sh.ready = true;
     return TUNA_OK;
+}
+
+int ensure_ctx(Ctx& c) {
+    const int rc = ensure_device();
+    if (rc != TUNA_OK || c.ready) return rc;
+    c.sb.num_cus = sh.num_cus;
+    HIPCHK(hipMalloc((void**)&c.sb.d_status, align_up(sizeof(Status))));
+    HIPCHK(hipHostMalloc((void**)&c.sb.h_status, sizeof(Status), hipHostMallocDefault));
+    HIPCHK(hipMalloc((void**)&c.sb.d_vpart, align_up(vpart_words(c.sb.num_cus) * 8)));
+    HIPCHK(hipEventCreate(&c.ev_end));
+    std::memset(&c.stats, 0, sizeof(c.stats));
+    c.ready = true;
+    return TUNA_OK;
+}
+
+void free_ctx(Ctx& c) {
+    if (c.sb.d_status) (void)hipFree(c.sb.d_status);
+    if (c.sb.h_status) (void)hipHostFree(c.sb.h_status);
+    if (c.sb.d_vpart) (void)hipFree(c.sb.d_vpart);
+    if (c.meta) (void)hipFree(c.meta);
+    if (c.data) (void)hipFree(c.data);
+    if (c.ev_end) (void)hipEventDestroy(c.ev_end);
+    for (hipEvent_t e : c.ev_pool) (void)hipEventDestroy(e);
+    c = Ctx{};
 }
 
 // Bump allocator over one device range.
@@ -241,8 +285,8 @@ int get_plan(int P, int Q, int rl, int rg, bool fused, hipStream_t s, DevicePlan
     int crl, crg;
     clamp_radices(Q, N, rl, rg, &crl, &crg);
     auto key = std::make_tuple(P, Q, crl, crg, fused ? 1 : 0);
-    auto it = g.plans.find(key);
-    if (it == g.plans.end()) {
+    auto it = sh.plans.find(key);
+    if (it == sh.plans.end()) {
         DevicePlan dp;
         dp.host = make_plan(P, Q, crl, crg, fused, /*with_tables=*/false);
         if ((int)dp.host.phases.size() > TUNA_MAX_PHASES) return TUNA_ERR_TOO_LARGE;
@@ -271,7 +315,7 @@ int get_plan(int P, int Q, int rl, int rg, bool fused, hipStream_t s, DevicePlan
         HIPCHK(hipGetLastError());
         dp.built_on = s;
         guard.dp = nullptr;
-        it = g.plans.emplace(key, std::move(dp)).first;
+        it = sh.plans.emplace(key, std::move(dp)).first;
     }
     // a cached schedule built on another stream: make sure its tables are complete
     if (it->second.built_on != s && !it->second.complete) {
@@ -290,21 +334,21 @@ int grow(void** buf, size_t* have, size_t need) {
         *buf = nullptr; *have = 0;
     }
     hipError_t e = hipMalloc(buf, need);
-    if (e != hipSuccess) { (void)hipGetLastError(); g.last_hip_error = (int)e; *buf = nullptr; return TUNA_ERR_NOMEM; }
+    if (e != hipSuccess) { (void)hipGetLastError(); sh.last_hip_error = (int)e; *buf = nullptr; return TUNA_ERR_NOMEM; }
     *have = need;
     return TUNA_OK;
 }
 
-void mark(hipStream_t s, int cat, int phase) {
-    if (!g.opt_profile || g.no_marks) return;
-    const size_t k = g.marks.size();
-    if (k >= g.ev_pool.size()) {
+void mark(Ctx* c, hipStream_t s, int cat, int phase) {
+    if (!c || !c->profile) return;
+    const size_t k = c->marks.size();
+    if (k >= c->ev_pool.size()) {
         hipEvent_t ev;
         if (hipEventCreate(&ev) != hipSuccess) return;
-        g.ev_pool.push_back(ev);
+        c->ev_pool.push_back(ev);
     }
-    if (hipEventRecord(g.ev_pool[k], s) != hipSuccess) return;
-    g.marks.push_back(Mark{g.ev_pool[k], cat, phase});
+    if (hipEventRecord(c->ev_pool[k], s) != hipSuccess) return;
+    c->marks.push_back(Mark{c->ev_pool[k], cat, phase});
 }
 
 // One-shot grid over an upper bound of wave units (4 per workgroup); waves past the device-side
@@ -415,6 +459,8 @@ struct Prepared {
     int P = 0, Q = 0, N = 0;
     DevicePlan* dp = nullptr;
     StatusBufs sb;
+    Ctx* ctx = nullptr;                 // where profiling marks go (none for the entry point that allocates nothing)
+    Options opt;
     bool fused = false, staggered = false;
     int gran = 1;
     const void* sendbuf = nullptr;
@@ -467,12 +513,21 @@ ExactT exact_t_of(const Prepared& pr, size_t i) {
 }
 
 // T in exact size or in the paper's slots of M bytes.  Left to the library (option value 2), slots
-// are kept only when they would be at least 90 % full -- blocks of (nearly) one size, where the
-// slot arithmetic is as dense as the arenas and cheaper to address.
-bool choose_exact_t(int option, int P, const Status& hs) {
+// are kept when they would be at least 90 % full -- blocks of (nearly) one size, where the slot
+// arithmetic is as dense as the arenas and cheaper to address.  Otherwise both footprints are known
+// from the validation pass: exact size is taken when it is not the larger one, or when it still fits
+// into half of the device memory that is free (it is the faster layout: dense writes and reads);
+// else the paper's slots.
+bool choose_exact_t(int option, const PlanHost& pl, const Status& hs) {
     if (option != 2) return option != 0;
     const double slot_bytes = (double)((hs.max_count + 127) / 128 * 128);
-    return (double)hs.total_bytes < 0.9 * (double)P * (double)P * slot_bytes;
+    if ((double)hs.total_bytes >= 0.9 * (double)pl.P * (double)pl.P * slot_bytes) return false;
+    const double slots_t = (double)pl.P * (double)pl.slots * slot_bytes;
+    const double exact_t = (double)hs.t_chunks * 16.0 + (double)pl.phases.size() * (double)pl.P * (double)pl.P * 4.0;
+    if (exact_t <= slots_t) return true;
+    size_t free_b = 0, total_b = 0;
+    if (hipMemGetInfo(&free_b, &total_b) != hipSuccess) { (void)hipGetLastError(); return false; }
+    return exact_t <= 0.5 * (double)free_b;
 }
 
 bool phase_is_one_kernel(const Prepared& pr, const PhaseHost& ph) {
@@ -516,7 +571,7 @@ int prepare_sizes(Prepared& pr, int dense_option, hipStream_t s, Status& hs, boo
     if (hs.flags & 4u) return TUNA_ERR_ARG;                 // a non-empty block at a negative displacement
     // the kernels round block sizes up to chunks and lines in 32-bit arithmetic
     if (hs.max_count > INT_MAX - 256) return TUNA_ERR_TOO_LARGE;
-    pr.exact_kernels = choose_exact_t(dense_option, P, hs);
+    pr.exact_kernels = choose_exact_t(dense_option, pr.dp->host, hs);
     pr.exact_t = pr.exact_kernels && has_t;
     *empty = hs.total_bytes == 0;
     if (*empty) return TUNA_OK;
@@ -539,29 +594,37 @@ int prepare_sizes(Prepared& pr, int dense_option, hipStream_t s, Status& hs, boo
 }
 
 // Argument checks, cached schedule, validation + sizing pass.
-int prepare_call(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
-                 const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
-                 hipStream_t s, Prepared& pr, Status& hs, bool* empty) {
+// One-kernel hops or the three stages.  Left to the library (TUNA_MODE_AUTO) it is the one-kernel hop:
+// with every rank's buffers in one memory a hop needs no message, and moving a block straight from where
+// its sender holds it to where its receiver keeps it reads and writes it once instead of three times
+// (measured on every workload of the benchmark: 2.0 to 2.6 times faster per call, less memory).
+bool mode_is_fused(const Options& o) { return o.mode != TUNA_MODE_STAGED; }
+
+int prepare_call(Ctx& c, const Options& opt, const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls,
+                 void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl,
+                 int rg, hipStream_t s, Prepared& pr, Status& hs, bool* empty) {
     int Q = 0;
     int rc = resolve_hierarchy(P, ranks_per_node, &Q);
     if (rc != TUNA_OK) return rc;
     if (rl < 2 || rg < 2) return TUNA_ERR_ARG;
     if (!sendcounts || !recvcounts || !sdispls || !rdispls) return TUNA_ERR_ARG;
-    rc = ensure_ctx();
+    rc = ensure_ctx(c);
     if (rc != TUNA_OK) return rc;
     const int N = P / Q;
     pr.P = P; pr.Q = Q; pr.N = N;
-    pr.sb = g.sb;
-    pr.fused = g.opt_fused != 0;
+    pr.sb = c.sb;
+    pr.ctx = &c;
+    pr.opt = opt;
+    pr.fused = mode_is_fused(opt);
     // staggered inter-node schedule: one block per message, N - 1 node distances, straight from T
-    pr.staggered = g.opt_staggered != 0 && N > 1;
+    pr.staggered = opt.staggered != 0 && N > 1;
     if (pr.staggered) rg = N;
     rc = get_plan(P, Q, rl, rg, pr.fused, s, &pr.dp);
     if (rc != TUNA_OK) return rc;
     pr.sendbuf = sendbuf; pr.recvbuf = recvbuf; pr.sendcounts = sendcounts; pr.recvcounts = recvcounts;
     pr.sdispls = sdispls; pr.rdispls = rdispls;
-    pr.block_count = g.opt_block_count;
-    return prepare_sizes(pr, g.opt_dense_t, s, hs, empty);
+    pr.block_count = opt.block_count;
+    return prepare_sizes(pr, opt.t_layout, s, hs, empty);
 }
 
 int launch_phase_metadata(const Prepared& pr, size_t i, const int32_t* cur, int32_t* nxt, const LayoutDev& Ls,
@@ -737,7 +800,7 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
             const int fused_resident = short_launch ? 8 : (ph.nz >= 32 ? 7 : 6);
             rc = launch_copy<kFused>(pr.gran, launch_units, a, s, pr.exact_kernels, fused_resident);
             if (rc != TUNA_OK) return rc;
-            mark(s, kCatPack, (int)i);
+            mark(pr.ctx, s, kCatPack, (int)i);
             continue;
         }
         // pack: S / T -> send staging
@@ -745,22 +808,22 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
         a.user = (unsigned char*)pr.sendbuf; a.displs = pr.sdispls;
         rc = launch_copy<kPack>(pr.gran, launch_units, a, s, pr.exact_kernels, pack_resident);
         if (rc != TUNA_OK) return rc;
-        mark(s, kCatPack, (int)i);
+        mark(pr.ctx, s, kCatPack, (int)i);
         // exchange: send staging of the partner -> receive staging
         a.stage = pr.stage_r; a.L = Lr; a.stage_src = pr.stage_s; a.Ls = Ls;
         rc = launch_copy<kExchange>(pr.gran, launch_units, a, s, pr.exact_kernels, exchange_resident);
         if (rc != TUNA_OK) return rc;
-        mark(s, kCatExchange, (int)i);
+        mark(pr.ctx, s, kCatExchange, (int)i);
         // unpack: receive staging -> R / T
         a.counts = pr.recvcounts; a.user = (unsigned char*)pr.recvbuf; a.displs = pr.rdispls;
         rc = launch_copy<kUnpack>(pr.gran, launch_units, a, s, pr.exact_kernels, unpack_resident);
         if (rc != TUNA_OK) return rc;
-        mark(s, kCatUnpack, (int)i);
+        mark(pr.ctx, s, kCatUnpack, (int)i);
     }
     return TUNA_OK;
 }
 
-int run_two_pass(const Prepared& prepared, hipStream_t s);
+int run_two_pass(Ctx& c, const Prepared& prepared, hipStream_t s);
 size_t plan_meta_bytes(const Prepared& pr);
 
 // Immediate calls take the two-pass form (see run_two_pass) from this many staged chunks on (64 MiB),
@@ -806,12 +869,12 @@ int run_one_pass(Prepared& pr, void* mbase, size_t mbytes, void* dbase, hipStrea
     const dim3 grot((unsigned)((P + 255) / 256), (unsigned)((P + kExchangeRanks - 1) / kExchangeRanks));
     hipLaunchKernelGGL(k_rotate_init, grot, dim3(256), 0, s, pr.sendcounts, mb.cur, P, pr.Q, pr.N);
     HIPCHK(hipGetLastError());
-    mark(s, kCatPrepare, -1);
+    mark(pr.ctx, s, kCatPrepare, -1);
     int rc = launch_self_metadata(pr, s);
     if (rc != TUNA_OK) return rc;
     rc = launch_self_copy(pr, s);
     if (rc != TUNA_OK) return rc;
-    mark(s, kCatSelf, -1);
+    mark(pr.ctx, s, kCatSelf, -1);
 
     // ---- digit phases -----------------------------------------------------------------------------
     int32_t* cur = mb.cur;
@@ -819,7 +882,7 @@ int run_one_pass(Prepared& pr, void* mbase, size_t mbytes, void* dbase, hipStrea
     for (size_t i = 0; i < pl.phases.size(); ++i) {
         rc = launch_phase_metadata(pr, i, cur, nxt, mb.Ls, mb.Lr, pr.hop, s);
         if (rc != TUNA_OK) return rc;
-        mark(s, kCatMeta, (int)i);
+        mark(pr.ctx, s, kCatMeta, (int)i);
         rc = launch_phase_data(pr, i, mb.Ls, mb.Lr, pr.hop, ds.unit_cap, s);
         if (rc != TUNA_OK) return rc;
         std::swap(cur, nxt);
@@ -827,48 +890,73 @@ int run_one_pass(Prepared& pr, void* mbase, size_t mbytes, void* dbase, hipStrea
     return TUNA_OK;
 }
 
-int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
-        const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
+int run_once(Ctx& c, const Options& opt, const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls,
+             void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
+             void* stream);
+
+// An immediate call.  When the T layout was left to the library and exact-size T could not be
+// allocated, the call is made again with the paper's slots before it gives up (nothing has moved yet).
+int run(Ctx& c, const Options& opt, const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls,
+        void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
+        void* stream) {
+    int rc = run_once(c, opt, sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node, rl, rg, stream);
+    if (rc == TUNA_ERR_NOMEM && opt.t_layout == TUNA_T_AUTO && c.stats.dense_t) {
+        Options o = opt;
+        o.t_layout = TUNA_T_SLOTS;
+        rc = run_once(c, o, sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node, rl, rg, stream);
+    }
+    return rc;
+}
+
+// An immediate call on context `c`.  Calls on one context share its workspace and status block: a call
+// issued on another stream than the previous one first makes its stream wait for that call's end.
+int run_once(Ctx& c, const Options& opt, const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls,
+        void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
         void* stream) {
     hipStream_t s = (hipStream_t)stream;
-    g.marks.clear();
-    g.end_recorded = false;
-    g.have_stats = false;
-    g.stats_plan = nullptr;
-    if (g.ready) mark(s, -1, -1);
+    if (c.ready && c.end_recorded && c.last_stream != s) HIPCHK(hipStreamWaitEvent(s, c.ev_end, 0));
+    c.marks.clear();
+    c.end_recorded = false;
+    c.have_stats = false;
+    c.stats_plan = nullptr;
+    c.profile = opt.profile != 0;
+    if (c.ready) mark(&c, s, -1, -1);
     Prepared pr;
     Status hs{};
     bool empty = false;
-    int rc = prepare_call(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node, rl, rg, s,
-                          pr, hs, &empty);
+    int rc = prepare_call(c, opt, sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node, rl, rg,
+                          s, pr, hs, &empty);
     if (rc != TUNA_OK) return rc;
-    tuna_stats_t& st = g.stats;
+    tuna_stats_t& st = c.stats;
     fill_stats_header(pr, hs, st);
-    if (empty) { g.have_stats = true; return TUNA_OK; }
+    if (empty) { c.have_stats = true; return TUNA_OK; }
     const PlanHost& pl = pr.dp->host;
-    if (use_two_pass(pl, hs)) return run_two_pass(pr, s);
-
-    // ---- workspace ---------------------------------------------------------------------------
-    const size_t mbytes = one_pass_meta_bytes(pr);
-    const DataSizes& ds = pr.ds;
-    void *mbase, *dbase;
-    if (g.user_ws) {
-        if (mbytes + ds.total > g.user_ws_bytes) return TUNA_ERR_WORKSPACE_TOO_SMALL;
-        mbase = g.user_ws;
-        dbase = (char*)g.user_ws + mbytes;
+    if (use_two_pass(pl, hs)) {
+        rc = run_two_pass(c, pr, s);
     } else {
-        rc = grow(&g.meta, &g.meta_bytes, mbytes);
-        if (rc != TUNA_OK) return rc;
-        rc = grow(&g.data, &g.data_bytes, ds.total);
-        if (rc != TUNA_OK) return rc;
-        mbase = g.meta;
-        dbase = g.data;
+        // ---- workspace ---------------------------------------------------------------------------
+        const size_t mbytes = one_pass_meta_bytes(pr);
+        const DataSizes& ds = pr.ds;
+        void *mbase, *dbase;
+        if (c.user_ws) {
+            if (mbytes + ds.total > c.user_ws_bytes) return TUNA_ERR_WORKSPACE_TOO_SMALL;
+            mbase = c.user_ws;
+            dbase = (char*)c.user_ws + mbytes;
+        } else {
+            rc = grow(&c.meta, &c.meta_bytes, mbytes);
+            if (rc != TUNA_OK) return rc;
+            rc = grow(&c.data, &c.data_bytes, ds.total);
+            if (rc != TUNA_OK) return rc;
+            mbase = c.meta;
+            dbase = c.data;
+        }
+        rc = run_one_pass(pr, mbase, mbytes, dbase, s, st);
     }
-    rc = run_one_pass(pr, mbase, mbytes, dbase, s, st);
     if (rc != TUNA_OK) return rc;
-    HIPCHK(hipEventRecord(g.ev_end, s));
-    g.end_recorded = true;
-    g.have_stats = true;
+    HIPCHK(hipEventRecord(c.ev_end, s));
+    c.end_recorded = true;
+    c.last_stream = s;
+    c.have_stats = true;
     return TUNA_OK;
 }
 
@@ -877,6 +965,7 @@ int run(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, 
 // computed once when the plan is made; starting it only launches the payload kernels.
 struct Plan {
     Prepared pr;
+    Ctx* ctx = nullptr;             // its statistics and profiling marks go here
     void* mem_meta = nullptr;       // cur / nxt and every phase's two layouts
     void* mem_data = nullptr;       // staging and T
     std::vector<LayoutDev> Ls, Lr;  // per phase
@@ -940,11 +1029,11 @@ int plan_build_metadata(Plan* plan, void* meta, size_t mbytes, hipStream_t s, bo
     HIPCHK(hipGetLastError());
     int rc = launch_self_metadata(pr, s);
     if (rc != TUNA_OK) return rc;
-    if (with_marks) mark(s, kCatPrepare, -1);
+    if (with_marks) mark(pr.ctx, s, kCatPrepare, -1);
     for (size_t i = 0; i < nph; ++i) {
         rc = launch_phase_metadata(pr, i, cur, nxt, plan->Ls[i], plan->Lr[i], plan->hop[i], s);
         if (rc != TUNA_OK) return rc;
-        if (with_marks) mark(s, kCatMeta, (int)i);
+        if (with_marks) mark(pr.ctx, s, kCatMeta, (int)i);
         std::swap(cur, nxt);
     }
     // exact unit counts, bytes and staged chunks per phase: one read-back of the status block
@@ -987,7 +1076,7 @@ int plan_launch_data(const Plan* plan, hipStream_t s) {
     const Prepared& pr = plan->pr;
     int rc = launch_self_copy(pr, s);
     if (rc != TUNA_OK) return rc;
-    mark(s, kCatSelf, -1);
+    mark(pr.ctx, s, kCatSelf, -1);
     const size_t nph = pr.dp->host.phases.size();
     for (size_t i = 0; i < nph; ++i) {
         rc = launch_phase_data(pr, i, plan->Ls[i], plan->Lr[i], plan->hop[i], plan->units[i], s);
@@ -996,50 +1085,56 @@ int plan_launch_data(const Plan* plan, hipStream_t s) {
     return TUNA_OK;
 }
 
-int plan_create(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
-                const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
+int plan_create(Ctx& c, const Options& opt, const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls,
+                void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
                 hipStream_t s, Plan** out) {
     Plan* plan = new Plan();
+    plan->ctx = &c;
     Prepared& pr = plan->pr;
     Status hs{};
-    int rc = prepare_call(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node, rl, rg, s,
+    c.profile = false;
+    int rc = prepare_call(c, opt, sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node, rl, rg, s,
                           pr, hs, &plan->empty);
     if (rc != TUNA_OK) { delete plan; return rc; }
     fill_stats_header(pr, hs, plan->stats);
-    if (plan->empty) { ++g.live_plans; *out = plan; return TUNA_OK; }
+    if (plan->empty) { ++sh.live_plans; *out = plan; return TUNA_OK; }
     const size_t mbytes = plan_meta_bytes(pr);
     hipError_t e = hipMalloc(&plan->mem_meta, mbytes ? mbytes : kAlign);
-    if (e != hipSuccess) { (void)hipGetLastError(); g.last_hip_error = (int)e; delete plan; return TUNA_ERR_NOMEM; }
+    if (e != hipSuccess) { (void)hipGetLastError(); sh.last_hip_error = (int)e; delete plan; return TUNA_ERR_NOMEM; }
     auto fail = [&](int code) { (void)hipFree(plan->mem_meta); if (plan->mem_data) (void)hipFree(plan->mem_data); delete plan; return code; };
     size_t stage_bytes = 0, dbytes = 0;
     rc = plan_build_metadata(plan, plan->mem_meta, mbytes, s, /*with_marks=*/false, &stage_bytes, &dbytes);
     if (rc != TUNA_OK) return fail(rc == TUNA_ERR_WORKSPACE_TOO_SMALL ? TUNA_ERR_NOMEM : rc);
     if (dbytes) {
         e = hipMalloc(&plan->mem_data, dbytes);
-        if (e != hipSuccess) { (void)hipGetLastError(); g.last_hip_error = (int)e; return fail(TUNA_ERR_NOMEM); }
+        if (e != hipSuccess) { (void)hipGetLastError(); sh.last_hip_error = (int)e; return fail(TUNA_ERR_NOMEM); }
         plan_carve_data(plan, plan->mem_data, stage_bytes, dbytes);
     }
-    ++g.live_plans;
+    ++sh.live_plans;
     *out = plan;
     return TUNA_OK;
 }
 
+// Starts of different plans share nothing but their context's statistics and profiling marks (the
+// last start wins there); the plan's own memory holds everything its kernels touch.
 int plan_start(Plan* plan, hipStream_t s) {
-    g.marks.clear();
-    g.end_recorded = false;
-    g.have_stats = false;
-    g.stats = plan->stats;
-    g.stats_plan = plan;
-    if (plan->empty) { g.have_stats = true; return TUNA_OK; }
-    mark(s, -1, -1);
-    mark(s, kCatPrepare, -1);
+    Ctx& c = *plan->ctx;
+    c.marks.clear();
+    c.have_stats = false;
+    c.stats = plan->stats;
+    c.stats_plan = plan;
+    c.profile = plan->pr.opt.profile != 0 || sh.defaults.profile != 0;
+    if (plan->empty) { c.end_recorded = false; c.have_stats = true; return TUNA_OK; }
+    mark(&c, s, -1, -1);
+    mark(&c, s, kCatPrepare, -1);
     int rc = plan_launch_data(plan, s);
     if (rc != TUNA_OK) return rc;
-    if (g.opt_profile) {
-        HIPCHK(hipEventRecord(g.ev_end, s));
-        g.end_recorded = true;
+    if (c.profile) {
+        HIPCHK(hipEventRecord(c.ev_end, s));
+        c.end_recorded = true;
+        c.last_stream = s;
     }
-    g.have_stats = true;
+    c.have_stats = true;
     return TUNA_OK;
 }
 
@@ -1048,43 +1143,45 @@ int plan_start(Plan* plan, hipStream_t s) {
 // the library's (or the caller's) workspace.  Worth the second synchronisation when the payload
 // is large and the schedule has several phases: the one-pass form launches every copy kernel for
 // an upper bound of units, most of which are empty at small radices.
-int run_two_pass(const Prepared& prepared, hipStream_t s) {
+int run_two_pass(Ctx& c, const Prepared& prepared, hipStream_t s) {
     Plan plan;
     plan.pr = prepared;
-    plan.stats = g.stats;
+    plan.ctx = &c;
+    plan.stats = c.stats;
     const size_t mbytes = plan_meta_bytes(plan.pr);
     void* mbase = nullptr;
     int rc;
-    if (g.user_ws) {
-        if (mbytes > g.user_ws_bytes) return TUNA_ERR_WORKSPACE_TOO_SMALL;
-        mbase = g.user_ws;
+    if (c.user_ws) {
+        if (mbytes > c.user_ws_bytes) return TUNA_ERR_WORKSPACE_TOO_SMALL;
+        mbase = c.user_ws;
     } else {
-        rc = grow(&g.meta, &g.meta_bytes, mbytes);
+        rc = grow(&c.meta, &c.meta_bytes, mbytes);
         if (rc != TUNA_OK) return rc;
-        mbase = g.meta;
+        mbase = c.meta;
     }
     size_t stage_bytes = 0, dbytes = 0;
     rc = plan_build_metadata(&plan, mbase, mbytes, s, /*with_marks=*/true, &stage_bytes, &dbytes);
     if (rc != TUNA_OK) return rc;
     void* dbase = nullptr;
-    if (g.user_ws) {
-        if (mbytes + dbytes > g.user_ws_bytes) return TUNA_ERR_WORKSPACE_TOO_SMALL;
-        dbase = (char*)g.user_ws + mbytes;
+    if (c.user_ws) {
+        if (mbytes + dbytes > c.user_ws_bytes) return TUNA_ERR_WORKSPACE_TOO_SMALL;
+        dbase = (char*)c.user_ws + mbytes;
     } else if (dbytes) {
-        rc = grow(&g.data, &g.data_bytes, dbytes);
+        rc = grow(&c.data, &c.data_bytes, dbytes);
         if (rc != TUNA_OK) return rc;
-        dbase = g.data;
+        dbase = c.data;
     }
     if (dbytes) plan_carve_data(&plan, dbase, stage_bytes, dbytes);
-    g.stats = plan.stats;
-    mark(s, kCatPrepare, -1);                     // the read-back between the passes counts as preparation
-    rc = plan_launch_data(&plan, s);
-    if (rc != TUNA_OK) return rc;
-    HIPCHK(hipEventRecord(g.ev_end, s));
-    g.end_recorded = true;
-    g.have_stats = true;
-    return TUNA_OK;
+    c.stats = plan.stats;
+    mark(&c, s, kCatPrepare, -1);                 // the read-back between the passes counts as preparation
+    return plan_launch_data(&plan, s);
 }
+
+}  // namespace
+}  // namespace tuna
+
+namespace tuna {
+namespace {
 
 // ---- the entry point that allocates nothing --------------------------------------------------------
 // Same call as tuna_alltoallv_hier, one pass, with every buffer carved from the static device array
@@ -1114,7 +1211,7 @@ int run_static(const void* sendbuf, const int32_t* sendcounts, const int64_t* sd
     if (!g_static.ptr[dev]) {
         void* p = nullptr;
         HIPCHK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
-        if (!p) { g.last_hip_error = (int)hipErrorInvalidSymbol; return TUNA_ERR_HIP; }
+        if (!p) { sh.last_hip_error = (int)hipErrorInvalidSymbol; return TUNA_ERR_HIP; }
         int cus = 0;
         HIPCHK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
         g_static.num_cus[dev] = cus > 0 ? cus : 256;
@@ -1128,10 +1225,12 @@ int run_static(const void* sendbuf, const int32_t* sendcounts, const int64_t* sd
     pr.sb.d_status = cv.take<Status>(1);
     pr.sb.d_vpart = cv.take<unsigned long long>(vpart_words(pr.sb.num_cus));
     pr.sb.h_status = &g_static.h_status;
-    pr.fused = g.opt_fused != 0;
-    pr.staggered = g.opt_staggered != 0 && N > 1;
+    pr.opt = sh.defaults;
+    pr.opt.profile = 0;                       // no events are created here
+    pr.fused = mode_is_fused(pr.opt);
+    pr.staggered = pr.opt.staggered != 0 && N > 1;
     if (pr.staggered) rg = N;
-    pr.block_count = g.opt_block_count;
+    pr.block_count = pr.opt.block_count;
     pr.sendbuf = sendbuf; pr.recvbuf = recvbuf; pr.sendcounts = sendcounts; pr.recvcounts = recvcounts;
     pr.sdispls = sdispls; pr.rdispls = rdispls;
 
@@ -1164,8 +1263,9 @@ int run_static(const void* sendbuf, const int32_t* sendcounts, const int64_t* sd
     // ---- validation and sizing (one read-back), then the one-pass call ---------------------------------
     Status hs{};
     bool empty = false;
-    rc = prepare_sizes(pr, g.opt_dense_t, s, hs, &empty);
+    rc = prepare_sizes(pr, pr.opt.t_layout, s, hs, &empty);
     if (rc != TUNA_OK) return rc;
+    // the statistics on file (header only: nothing here is timed) are the default context's
     g.marks.clear();
     g.end_recorded = false;
     g.stats_plan = nullptr;
@@ -1175,10 +1275,217 @@ int run_static(const void* sendbuf, const int32_t* sendcounts, const int64_t* sd
     const size_t mbytes = one_pass_meta_bytes(pr);
     if (cv.off + mbytes + pr.ds.total > cv.cap) return TUNA_ERR_NOALLOC_LIMIT;
     char* mbase = cv.base + cv.off;
-    g.no_marks = true;
-    rc = run_one_pass(pr, mbase, mbytes, mbase + mbytes, s, g.stats);
-    g.no_marks = false;
-    return rc;
+    return run_one_pass(pr, mbase, mbytes, mbase + mbytes, s, g.stats);
+}
+
+// ---- cost model of a call and its calibration ----------------------------------------------------------
+// The paper chooses the radix from P and the block size because each of its K rounds pays a network
+// latency (Section "Performance analysis of TuNA", "Radix selection").  In one HBM a round has no latency
+// of its own; what a call costs is a fixed part, a part per digit phase (its launches), a part per entry
+// of the P x P matrices (validation, rotation), the bytes its hops move and a part per moving block
+// (metadata; the whole cost when blocks are tiny):
+//     ms = c0 + c1 * phases + c2 * P^2 / 1e6 + c3 * hop bytes / 1e9 + c4 * moving blocks / 1e6
+// with hop bytes = sum over phases of the payload bytes that move, moving blocks likewise.  One set of
+// constants per mode (three-stage, one-kernel).  The built-in constants were fitted to immediate calls
+// on MI355X (the five benchmark configurations and uniform [0, S] sizes at P = 2048, S = 16 B .. 8 KiB:
+// worst relative error 15 %); tuna_calibrate replaces them by a fit to calls timed on the device at hand.
+struct Model {
+    double c[5];
+};
+struct ModelSet {
+    Model m[2] = {{{0.05969, 0.03001, 0.00676, 0.96579, 0.05007}},     // [0] three stages
+                  {{0.05776, 0.02737, 0.00586, 0.37560, 0.03834}}};    // [1] one-kernel hops
+    // T in the paper's slots of M bytes: the bytes that pass through T cost more the emptier the slots are
+    // (sparse writes and reads): their share of the byte term is scaled by 1 + k * (1 - mean / M)
+    double slot_penalty[2] = {0.25, 0.45};
+    // byte-granular problems (some count, displacement or buffer address is not a multiple of 4) run the
+    // kernel variants that load and store single bytes at block edges: their byte term is scaled by this
+    double byte_granular[2] = {2.2, 3.0};
+    bool calibrated = false;
+};
+ModelSet g_model;
+
+struct Features {
+    double phases, p2, hop_gb, mblocks, t_share;    // t_share: share of the hop bytes that is written to or read from T
+};
+
+Features features_of(const PlanHost& pl, double payload_bytes) {
+    Features f{};
+    const double P = (double)pl.P;
+    f.phases = (double)pl.phases.size();
+    f.p2 = P * P / 1e6;
+    double moving = 0.0;
+    for (const auto& ph : pl.phases) moving += (double)ph.nseg * P;
+    f.mblocks = moving / 1e6;
+    // sizes are taken to be independent of the rank distance: every slot index carries payload / P^2
+    f.hop_gb = P > 0 ? payload_bytes * (moving / (P * P)) / 1e9 : 0.0;
+    // a block of h hops passes through T h - 1 times: it is written there h - 1 times and read h - 1 times,
+    // of 2 h accesses in all
+    const double hops = P > 0 ? moving / P : 0.0;                    // sum over slot indices of their hops
+    const double through_t = hops - (P - 1.0);                       // sum of (h - 1) over the P - 1 moving indices
+    f.t_share = hops > 0 ? (through_t > 0 ? through_t / hops : 0.0) : 0.0;
+    return f;
+}
+
+double model_ms(const Model& m, const Features& f) {
+    return m.c[0] + m.c[1] * f.phases + m.c[2] * f.p2 + m.c[3] * f.hop_gb + m.c[4] * f.mblocks;
+}
+
+double predict_ms(int P, int Q, int rl, int rg, bool fused, int t_layout, int64_t payload_bytes, int64_t max_block,
+                  int granularity) {
+    const PlanHost pl = make_plan(P, Q, rl, rg, false, /*with_tables=*/false);
+    Features f = features_of(pl, (double)payload_bytes);
+    const Model& m = g_model.m[fused ? 1 : 0];
+    double ms = model_ms(m, f);
+    if (granularity > 0 && granularity < 4) ms += m.c[3] * f.hop_gb * (g_model.byte_granular[fused ? 1 : 0] - 1.0);
+    if (t_layout == TUNA_T_SLOTS && max_block > 0 && pl.slots > 0) {
+        const double mean = (double)payload_bytes / ((double)P * (double)P);
+        const double m128 = (double)((max_block + 127) / 128 * 128);
+        const double empty = 1.0 - std::min(1.0, mean / m128);
+        ms += m.c[3] * f.hop_gb * f.t_share * g_model.slot_penalty[fused ? 1 : 0] * empty;
+    }
+    return ms;
+}
+
+// Least squares for the five constants from timed calls, weighted for relative error; a constant that
+// comes out negative is set to zero and the others are fitted again.
+bool fit_model(const std::vector<Features>& X, const std::vector<double>& y, Model* out) {
+    const int n = 5;
+    bool fixed[n] = {false, false, false, false, false};
+    for (int round = 0; round < n; ++round) {
+        double A[n][n + 1] = {};
+        for (size_t k = 0; k < X.size(); ++k) {
+            const double w = 1.0 / (y[k] * y[k]);
+            const double row[n] = {1.0, X[k].phases, X[k].p2, X[k].hop_gb, X[k].mblocks};
+            for (int i = 0; i < n; ++i) {
+                if (fixed[i]) continue;
+                for (int j = 0; j < n; ++j)
+                    if (!fixed[j]) A[i][j] += w * row[i] * row[j];
+                A[i][n] += w * row[i] * y[k];
+            }
+        }
+        for (int i = 0; i < n; ++i)
+            if (fixed[i]) A[i][i] = 1.0;              // x_i = 0
+        // Gaussian elimination with partial pivoting
+        int perm[n];
+        for (int i = 0; i < n; ++i) perm[i] = i;
+        for (int col = 0; col < n; ++col) {
+            int piv = col;
+            for (int r = col + 1; r < n; ++r)
+                if (std::fabs(A[perm[r]][col]) > std::fabs(A[perm[piv]][col])) piv = r;
+            std::swap(perm[col], perm[piv]);
+            const double d = A[perm[col]][col];
+            if (std::fabs(d) < 1e-300) return false;
+            for (int r = col + 1; r < n; ++r) {
+                const double fct = A[perm[r]][col] / d;
+                for (int c2 = col; c2 <= n; ++c2) A[perm[r]][c2] -= fct * A[perm[col]][c2];
+            }
+        }
+        double x[n];
+        for (int i = n - 1; i >= 0; --i) {
+            double v = A[perm[i]][n];
+            for (int j = i + 1; j < n; ++j) v -= A[perm[i]][j] * x[j];
+            x[i] = v / A[perm[i]][i];
+        }
+        int worst = -1;
+        for (int i = 0; i < n; ++i)
+            if (!fixed[i] && x[i] < 0 && (worst < 0 || x[i] < x[worst])) worst = i;
+        if (worst < 0) {
+            for (int i = 0; i < n; ++i) out->c[i] = fixed[i] ? 0.0 : x[i];
+            return true;
+        }
+        fixed[worst] = true;
+    }
+    return false;
+}
+
+// Times immediate calls of dense problems with equal blocks (P x P blocks of S bytes) on a context of
+// their own and fits the model to them.  Allocates the problems' buffers (up to about 2.3 GiB, plus
+// the calls' workspaces) and frees them again; synchronises.
+int calibrate(hipStream_t s) {
+    int rc = ensure_device();
+    if (rc != TUNA_OK) return rc;
+    struct Problem { int P, S; int radices[3]; };
+    const Problem odd = {256, 515, {2, 16, 256}};        // byte-granular: fitted after the others, as a factor on the byte term
+    // tiny (fixed costs), many tiny blocks (per-block and per-entry costs), large blocks beyond the caches
+    // (bytes), and a mix; S is 4 bytes off a multiple of 16, the usual alignment of float payloads
+    const Problem problems[] = {{32, 68, {2, 6, 32}}, {1024, 20, {2, 32, 1024}}, {2048, 36, {8, 2048, 0}},
+                                {512, 4100, {2, 23, 512}}, {2048, 260, {8, 2048, 0}}};
+    size_t max_entries = 0, max_bytes = 0;
+    for (const Problem& pb : problems) {
+        max_entries = std::max(max_entries, (size_t)pb.P * pb.P);
+        max_bytes = std::max(max_bytes, (size_t)pb.P * pb.P * pb.S);
+    }
+    max_bytes = std::max(max_bytes, (size_t)odd.P * odd.P * odd.S);
+    int32_t *sc = nullptr, *rc_ = nullptr;
+    int64_t *sd = nullptr, *rd = nullptr;
+    unsigned char *send = nullptr, *recv = nullptr;
+    Ctx* c = new Ctx();
+    auto cleanup = [&]() {
+        (void)hipDeviceSynchronize();
+        for (void* ptr : {(void*)sc, (void*)rc_, (void*)sd, (void*)rd, (void*)send, (void*)recv})
+            if (ptr) (void)hipFree(ptr);
+        free_ctx(*c);
+        delete c;
+    };
+    auto alloc = [&](void** ptr, size_t bytes) {
+        const hipError_t e = hipMalloc(ptr, bytes);
+        if (e != hipSuccess) { (void)hipGetLastError(); sh.last_hip_error = (int)e; *ptr = nullptr; return false; }
+        return true;
+    };
+    if (!alloc((void**)&sc, max_entries * 4) || !alloc((void**)&rc_, max_entries * 4) || !alloc((void**)&sd, max_entries * 8) ||
+        !alloc((void**)&rd, max_entries * 8) || !alloc((void**)&send, max_bytes + 256) || !alloc((void**)&recv, max_bytes + 256)) {
+        cleanup();
+        return TUNA_ERR_NOMEM;
+    }
+    if (hipMemsetAsync(send, 0x5a, max_bytes + 256, s) != hipSuccess) { (void)hipGetLastError(); cleanup(); return TUNA_ERR_HIP; }
+    std::vector<Features> X[2], Xo[2];
+    std::vector<double> y[2], yo[2];
+    std::vector<Problem> all(std::begin(problems), std::end(problems));
+    all.push_back(odd);
+    for (const Problem& pb : all) {
+        const bool is_odd = (pb.S & 3) != 0;
+        const size_t entries = (size_t)pb.P * pb.P;
+        hipLaunchKernelGGL(k_fill_uniform, dim3((unsigned)((entries + 255) / 256)), dim3(256), 0, s, sc, sd, rc_, rd, pb.P, pb.S);
+        if (hipGetLastError() != hipSuccess || hipStreamSynchronize(s) != hipSuccess) { cleanup(); return TUNA_ERR_HIP; }
+        for (int r : pb.radices) {
+            if (r < 2) continue;
+            for (int fused = 0; fused < 2; ++fused) {
+                Options o;
+                o.mode = fused ? TUNA_MODE_FUSED : TUNA_MODE_STAGED;
+                o.t_layout = TUNA_T_EXACT;
+                double t[4];
+                for (int it = 0; it < 4; ++it) {         // the first call warms up (allocations, schedule tables)
+                    const auto t0 = std::chrono::steady_clock::now();
+                    rc = run(*c, o, send, sc, sd, recv, rc_, rd, pb.P, 0, r, r, s);
+                    if (rc == TUNA_OK && hipStreamSynchronize(s) != hipSuccess) rc = TUNA_ERR_HIP;
+                    if (rc != TUNA_OK) { cleanup(); return rc; }
+                    t[it] = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+                }
+                std::sort(t + 1, t + 4);
+                const PlanHost pl = make_plan(pb.P, pb.P, r, r, false, false);
+                (is_odd ? Xo : X)[fused].push_back(features_of(pl, (double)entries * pb.S));
+                (is_odd ? yo : y)[fused].push_back(t[2]);                // median of the three timed calls
+            }
+        }
+    }
+    cleanup();
+    ModelSet fitted = g_model;
+    for (int fused = 0; fused < 2; ++fused) {
+        if (!fit_model(X[fused], y[fused], &fitted.m[fused])) return TUNA_ERR_HIP;
+        // the factor on the byte term that explains the byte-granular calls best (least squares)
+        double num = 0.0, den = 0.0;
+        for (size_t k = 0; k < Xo[fused].size(); ++k) {
+            const double bytes_ms = fitted.m[fused].c[3] * Xo[fused][k].hop_gb;
+            const double rest = model_ms(fitted.m[fused], Xo[fused][k]) - bytes_ms;
+            num += (yo[fused][k] - rest) * bytes_ms;
+            den += bytes_ms * bytes_ms;
+        }
+        if (den > 0) fitted.byte_granular[fused] = std::max(1.0, num / den);
+    }
+    fitted.calibrated = true;
+    g_model = fitted;
+    return TUNA_OK;
 }
 
 }  // namespace
@@ -1188,43 +1495,97 @@ using namespace tuna;
 
 extern "C" {
 
+// Options of a call: the caller's struct where given (checked), else the process-wide defaults.
+static int options_from(const tuna_opts_t* o, Options* out) {
+    *out = sh.defaults;
+    if (!o) return TUNA_OK;
+    if (o->struct_size != (int32_t)sizeof(tuna_opts_t)) return TUNA_ERR_ARG;
+    if (o->mode < TUNA_MODE_AUTO || o->mode > TUNA_MODE_FUSED || o->t_layout < TUNA_T_SLOTS || o->t_layout > TUNA_T_AUTO ||
+        o->block_count < 0)
+        return TUNA_ERR_ARG;
+    out->profile = o->profile ? 1 : 0; out->mode = o->mode; out->staggered = o->staggered ? 1 : 0;
+    out->t_layout = o->t_layout; out->block_count = o->block_count;
+    return TUNA_OK;
+}
+
+// The schedule queries describe the tables of the one-kernel hops (T in slots laid out twice) only when
+// that mode was asked for by name; left to the library they describe the paper's single T.
+static bool query_fused() { return sh.defaults.mode == TUNA_MODE_FUSED; }
+
+static Ctx* ctx_of(tuna_ctx_t ctx) { return ctx ? reinterpret_cast<Ctx*>(ctx) : &g; }
+
+// radix 0 = left to the library: the linear schedule in both dimensions (see tuna_select)
+static int auto_radix(int radix, int P) { return radix == TUNA_RADIX_AUTO ? (P > 2 ? P : 2) : radix; }
+
 int tuna_alltoallv(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
                    const int32_t* recvcounts, const int64_t* rdispls, int P, int radix, int ranks_per_node,
                    void* stream) {
+    radix = auto_radix(radix, P);
     if (radix < 2) return TUNA_ERR_ARG;
-    return run(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node, radix, radix, stream);
+    return run(g, sh.defaults, sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node, radix,
+               radix, stream);
 }
 
 int tuna_alltoallv_hier(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
                         const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node,
                         int local_radix, int global_radix, void* stream) {
+    local_radix = auto_radix(local_radix, P); global_radix = auto_radix(global_radix, P);
     if (local_radix < 2 || global_radix < 2) return TUNA_ERR_ARG;
-    return run(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node, local_radix,
-               global_radix, stream);
+    return run(g, sh.defaults, sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node,
+               local_radix, global_radix, stream);
+}
+
+int tuna_alltoallv_ex(tuna_ctx_t ctx, const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls,
+                      void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node,
+                      int local_radix, int global_radix, const tuna_opts_t* opts, void* stream) {
+    Options o;
+    const int rc = options_from(opts, &o);
+    if (rc != TUNA_OK) return rc;
+    local_radix = auto_radix(local_radix, P); global_radix = auto_radix(global_radix, P);
+    if (local_radix < 2 || global_radix < 2) return TUNA_ERR_ARG;
+    return run(*ctx_of(ctx), o, sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node,
+               local_radix, global_radix, stream);
 }
 
 int tuna_alltoallv_noalloc(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
                            const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node,
                            int local_radix, int global_radix, void* stream) {
-    return run_static(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node, local_radix,
-                      global_radix, (hipStream_t)stream);
+    return run_static(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node,
+                      auto_radix(local_radix, P), auto_radix(global_radix, P), (hipStream_t)stream);
+}
+
+int tuna_alltoallv_init_ex(tuna_ctx_t ctx, const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls,
+                           void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node,
+                           int local_radix, int global_radix, const tuna_opts_t* opts, void* stream, tuna_plan_t* plan) {
+    if (!plan) return TUNA_ERR_ARG;
+    *plan = nullptr;
+    Options o;
+    int rc = options_from(opts, &o);
+    if (rc != TUNA_OK) return rc;
+    local_radix = auto_radix(local_radix, P); global_radix = auto_radix(global_radix, P);
+    if (local_radix < 2 || global_radix < 2) return TUNA_ERR_ARG;
+    Plan* p = nullptr;
+    rc = plan_create(*ctx_of(ctx), o, sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node,
+                     local_radix, global_radix, (hipStream_t)stream, &p);
+    if (rc == TUNA_ERR_NOMEM && o.t_layout == TUNA_T_AUTO) {     // exact-size T did not fit: the paper's slots may
+        o.t_layout = TUNA_T_SLOTS;
+        rc = plan_create(*ctx_of(ctx), o, sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node,
+                         local_radix, global_radix, (hipStream_t)stream, &p);
+    }
+    if (rc == TUNA_OK) *plan = reinterpret_cast<tuna_plan_t>(p);
+    return rc;
 }
 
 int tuna_alltoallv_init(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
                         const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node,
                         int local_radix, int global_radix, void* stream, tuna_plan_t* plan) {
-    if (!plan || local_radix < 2 || global_radix < 2) return TUNA_ERR_ARG;
-    *plan = nullptr;
-    Plan* p = nullptr;
-    const int rc = plan_create(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node,
-                               local_radix, global_radix, (hipStream_t)stream, &p);
-    if (rc == TUNA_OK) *plan = reinterpret_cast<tuna_plan_t>(p);
-    return rc;
+    return tuna_alltoallv_init_ex(nullptr, sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node,
+                                  local_radix, global_radix, nullptr, stream, plan);
 }
 
 int tuna_start(tuna_plan_t plan, void* stream) {
     if (!plan) return TUNA_ERR_ARG;
-    const int rc = ensure_ctx();           // the plan's memory lives on the library's device
+    const int rc = ensure_device();        // the plan's memory lives on the library's device
     if (rc != TUNA_OK) return rc;
     return plan_start(reinterpret_cast<Plan*>(plan), (hipStream_t)stream);
 }
@@ -1232,12 +1593,46 @@ int tuna_start(tuna_plan_t plan, void* stream) {
 int tuna_plan_free(tuna_plan_t plan) {
     if (!plan) return TUNA_OK;
     Plan* p = reinterpret_cast<Plan*>(plan);
-    if (g.stats_plan == p) g.stats_plan = nullptr;
-    HIPCHK(hipDeviceSynchronize());
+    if (p->ctx && p->ctx->stats_plan == p) p->ctx->stats_plan = nullptr;
+    // the plan goes away whatever the wait for the device says: its memory is released and the count of
+    // live plans drops, then the error (if any) is reported
+    const hipError_t e = hipDeviceSynchronize();
     if (p->mem_meta) (void)hipFree(p->mem_meta);
     if (p->mem_data) (void)hipFree(p->mem_data);
     delete p;
-    --g.live_plans;
+    --sh.live_plans;
+    if (e != hipSuccess) { sh.last_hip_error = (int)e; return TUNA_ERR_HIP; }
+    return TUNA_OK;
+}
+
+int tuna_ctx_create(tuna_ctx_t* ctx) {
+    if (!ctx) return TUNA_ERR_ARG;
+    *ctx = nullptr;
+    Ctx* c = new Ctx();
+    const int rc = ensure_ctx(*c);
+    if (rc != TUNA_OK) { free_ctx(*c); delete c; return rc; }
+    ++sh.live_contexts;
+    *ctx = reinterpret_cast<tuna_ctx_t>(c);
+    return TUNA_OK;
+}
+
+int tuna_ctx_destroy(tuna_ctx_t ctx) {
+    if (!ctx) return TUNA_OK;
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    const hipError_t e = hipDeviceSynchronize();
+    free_ctx(*c);
+    delete c;
+    --sh.live_contexts;
+    if (e != hipSuccess) { sh.last_hip_error = (int)e; return TUNA_ERR_HIP; }
+    return TUNA_OK;
+}
+
+int tuna_opts_init(tuna_opts_t* opts) {
+    if (!opts) return TUNA_ERR_ARG;
+    std::memset(opts, 0, sizeof(*opts));
+    opts->struct_size = (int32_t)sizeof(tuna_opts_t);
+    opts->mode = sh.defaults.mode; opts->staggered = sh.defaults.staggered; opts->t_layout = sh.defaults.t_layout;
+    opts->block_count = sh.defaults.block_count; opts->profile = sh.defaults.profile;
     return TUNA_OK;
 }
 
@@ -1247,25 +1642,27 @@ int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node, i
     int Q = 0;
     int rc = resolve_hierarchy(P, ranks_per_node, &Q);
     if (rc != TUNA_OK) return rc;
-    rc = ensure_ctx();
+    rc = ensure_ctx(g);
     if (rc != TUNA_OK) return rc;
     const int N = P / Q;
-    const bool staggered = g.opt_staggered != 0 && N > 1;
+    const Options& o = sh.defaults;
+    const bool fused = mode_is_fused(o);
+    const bool staggered = o.staggered != 0 && N > 1;
     DevicePlan* dp = nullptr;
-    rc = get_plan(P, Q, local_radix, staggered ? N : global_radix, g.opt_fused != 0, nullptr, &dp);
+    rc = get_plan(P, Q, local_radix, staggered ? N : global_radix, fused, nullptr, &dp);
     if (rc != TUNA_OK) return rc;
     const PlanHost& pl = dp->host;
-    rc = run_validate(g.sb, sendcounts, nullptr, nullptr, nullptr, P, nullptr, (g.opt_dense_t != 0 && pl.slots > 0) ? dp : nullptr);
+    rc = run_validate(g.sb, sendcounts, nullptr, nullptr, nullptr, P, nullptr, (o.t_layout != 0 && pl.slots > 0) ? dp : nullptr);
     if (rc != TUNA_OK) return rc;
     const Status* h_status = g.sb.h_status;
-    const bool exact_t = choose_exact_t(g.opt_dense_t, P, *h_status) && pl.slots > 0;
+    const bool exact_t = choose_exact_t(o.t_layout, pl, *h_status) && pl.slots > 0;
     dp->complete = true;                                  // run_validate synchronised the stream the tables were built on
     if (h_status->flags & 1u) return TUNA_ERR_NEGATIVE_COUNT;
-    const DataSizes ds = data_sizes_for(pl, h_status->max_count, h_status->total_chunks, g.opt_fused != 0, staggered,
+    const DataSizes ds = data_sizes_for(pl, h_status->max_count, h_status->total_chunks, fused, staggered,
                                         exact_t, h_status->t_chunks);
     Prepared pr;
     pr.P = P; pr.Q = Q; pr.N = N; pr.dp = dp; pr.ds = ds; pr.exact_t = exact_t;
-    pr.fused = g.opt_fused != 0; pr.staggered = staggered;
+    pr.fused = fused; pr.staggered = staggered; pr.max_count = h_status->max_count;
     *bytes = one_pass_meta_bytes(pr) + ds.total;
     if (use_two_pass(pl, *h_status)) {
         // the two-pass form keeps every phase's layouts; its staging is at most the one-pass form's
@@ -1277,7 +1674,7 @@ int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node, i
 
 int tuna_plain_copy(const void* src, void* dst, size_t bytes, void* stream) {
     if (!src || !dst || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return TUNA_ERR_ARG;
-    int rc = ensure_ctx();
+    int rc = ensure_device();
     if (rc != TUNA_OK) return rc;
     const size_t n = bytes / 16;
     if (n == 0) return TUNA_OK;
@@ -1296,28 +1693,36 @@ int tuna_set_workspace(void* workspace, size_t bytes) {
 }
 
 int tuna_release(void) {
-    if (!g.ready) return TUNA_OK;
-    if (g.live_plans > 0) return TUNA_ERR_ARG;      // persistent plans use the cached schedules
+    if (!sh.ready) return TUNA_OK;
+    if (sh.live_plans > 0) return TUNA_ERR_ARG;      // persistent plans use the cached schedules
     HIPCHK(hipDeviceSynchronize());
     if (g.meta) { HIPCHK(hipFree(g.meta)); g.meta = nullptr; g.meta_bytes = 0; }
     if (g.data) { HIPCHK(hipFree(g.data)); g.data = nullptr; g.data_bytes = 0; }
-    for (auto& kv : g.plans) free_device_plan(kv.second);
-    g.plans.clear();
+    for (auto& kv : sh.plans) free_device_plan(kv.second);
+    sh.plans.clear();
     return TUNA_OK;
 }
 
 int tuna_set_option(int option, int value) {
-    if (option == TUNA_OPT_PROFILE) { g.opt_profile = value ? 1 : 0; return TUNA_OK; }
-    if (option == TUNA_OPT_FUSED) { g.opt_fused = value ? 1 : 0; return TUNA_OK; }
-    if (option == TUNA_OPT_STAGGERED) { g.opt_staggered = value ? 1 : 0; return TUNA_OK; }
-    if (option == TUNA_OPT_DENSE_T) { if (value < 0 || value > 2) return TUNA_ERR_ARG; g.opt_dense_t = value; return TUNA_OK; }
-    if (option == TUNA_OPT_BLOCK_COUNT) { if (value < 0) return TUNA_ERR_ARG; g.opt_block_count = value; return TUNA_OK; }
+    Options& d = sh.defaults;
+    if (option == TUNA_OPT_PROFILE) { d.profile = value ? 1 : 0; return TUNA_OK; }
+    if (option == TUNA_OPT_FUSED) {      // 0: three stages, 1: one-kernel hops, 2: left to the library
+        if (value < 0 || value > 2) return TUNA_ERR_ARG;
+        d.mode = value == 0 ? TUNA_MODE_STAGED : (value == 1 ? TUNA_MODE_FUSED : TUNA_MODE_AUTO);
+        return TUNA_OK;
+    }
+    if (option == TUNA_OPT_STAGGERED) { d.staggered = value ? 1 : 0; return TUNA_OK; }
+    if (option == TUNA_OPT_DENSE_T) { if (value < 0 || value > 2) return TUNA_ERR_ARG; d.t_layout = value; return TUNA_OK; }
+    if (option == TUNA_OPT_BLOCK_COUNT) { if (value < 0) return TUNA_ERR_ARG; d.block_count = value; return TUNA_OK; }
     return TUNA_ERR_ARG;
 }
 
-int tuna_get_stats(tuna_stats_t* out) {
+int tuna_get_stats(tuna_stats_t* out) { return tuna_ctx_get_stats(nullptr, out); }
+
+int tuna_ctx_get_stats(tuna_ctx_t ctx, tuna_stats_t* out) {
+    Ctx& g = *ctx_of(ctx);               // the context whose statistics are asked for
     if (!out) return TUNA_ERR_ARG;
-    if (!g.have_stats) { std::memset(out, 0, sizeof(*out)); out->last_hip_error = g.last_hip_error; return TUNA_OK; }
+    if (!g.have_stats) { std::memset(out, 0, sizeof(*out)); out->last_hip_error = sh.last_hip_error; return TUNA_OK; }
     tuna_stats_t& st = g.stats;
     if (g.end_recorded) {
         HIPCHK(hipEventSynchronize(g.ev_end));
@@ -1352,6 +1757,7 @@ int tuna_get_stats(tuna_stats_t* out) {
         }
     }
     *out = st;
+    out->last_hip_error = sh.last_hip_error;
     return TUNA_OK;
 }
 
@@ -1360,12 +1766,12 @@ int tuna_plan_info(int P, int ranks_per_node, int local_radix, int global_radix,
     int Q = 0;
     int rc = resolve_hierarchy(P, ranks_per_node, &Q);
     if (rc != TUNA_OK) return rc;
-    if (g.opt_staggered && P / Q > 1) global_radix = P / Q;
-    const PlanHost pl = make_plan(P, Q, local_radix, global_radix, g.opt_fused != 0, /*with_tables=*/false);
+    if (sh.defaults.staggered && P / Q > 1) global_radix = P / Q;
+    const PlanHost pl = make_plan(P, Q, local_radix, global_radix, query_fused(), /*with_tables=*/false);
     out->P = P; out->Q = Q; out->N = pl.N;
     out->local_radix = pl.rl; out->global_radix = pl.rg;
     out->w_local = pl.w_l; out->w_global = pl.w_g;
-    out->K_local = pl.K_l; out->K_global = (g.opt_staggered && pl.N > 1) ? Q * (pl.N - 1) : pl.K_g;
+    out->K_local = pl.K_l; out->K_global = (sh.defaults.staggered && pl.N > 1) ? Q * (pl.N - 1) : pl.K_g;
     out->B_local = pl.B_l; out->B_global = pl.B_g;
     out->n_phases = (int)pl.phases.size();
     out->temp_slots_per_rank = pl.slots;
@@ -1379,7 +1785,7 @@ int tuna_plan_phase(int P, int ranks_per_node, int local_radix, int global_radix
     int Q = 0;
     int rc = resolve_hierarchy(P, ranks_per_node, &Q);
     if (rc != TUNA_OK) return rc;
-    const PlanHost pl = make_plan(P, Q, local_radix, global_radix, g.opt_fused != 0);
+    const PlanHost pl = make_plan(P, Q, local_radix, global_radix, query_fused());
     if (phase >= (int)pl.phases.size()) return TUNA_ERR_ARG;
     const PhaseHost& ph = pl.phases[phase];
     header[0] = ph.dim; header[1] = ph.x; header[2] = ph.r; header[3] = ph.nz; header[4] = ph.nseg;
@@ -1401,11 +1807,11 @@ int tuna_plan_phase_device(int P, int ranks_per_node, int local_radix, int globa
     int Q = 0;
     int rc = resolve_hierarchy(P, ranks_per_node, &Q);
     if (rc != TUNA_OK) return rc;
-    rc = ensure_ctx();
+    rc = ensure_device();
     if (rc != TUNA_OK) return rc;
-    if (g.opt_staggered && P / Q > 1) global_radix = P / Q;
+    if (sh.defaults.staggered && P / Q > 1) global_radix = P / Q;
     DevicePlan* dp = nullptr;
-    rc = get_plan(P, Q, local_radix, global_radix, g.opt_fused != 0, nullptr, &dp);
+    rc = get_plan(P, Q, local_radix, global_radix, query_fused(), nullptr, &dp);
     if (rc != TUNA_OK) return rc;
     if (phase >= (int)dp->host.phases.size()) return TUNA_ERR_ARG;
     HIPCHK(hipDeviceSynchronize());
@@ -1428,18 +1834,18 @@ int tuna_plan_phase_sources(int P, int ranks_per_node, int local_radix, int glob
     int rc = resolve_hierarchy(P, ranks_per_node, &Q);
     if (rc != TUNA_OK) return rc;
     if (!on_device) {
-        const PlanHost pl = make_plan(P, Q, local_radix, global_radix, g.opt_fused != 0);
+        const PlanHost pl = make_plan(P, Q, local_radix, global_radix, query_fused());
         if (phase >= (int)pl.phases.size()) return TUNA_ERR_ARG;
         const PhaseHost& ph = pl.phases[phase];
         const int n = capacity < ph.nseg ? capacity : ph.nseg;
         for (int k = 0; k < n; ++k) { out[2 * k] = ph.seg[k].src_phase; out[2 * k + 1] = ph.seg[k].src_seg; }
         return TUNA_OK;
     }
-    rc = ensure_ctx();
+    rc = ensure_device();
     if (rc != TUNA_OK) return rc;
-    if (g.opt_staggered && P / Q > 1) global_radix = P / Q;
+    if (sh.defaults.staggered && P / Q > 1) global_radix = P / Q;
     DevicePlan* dp = nullptr;
-    rc = get_plan(P, Q, local_radix, global_radix, g.opt_fused != 0, nullptr, &dp);
+    rc = get_plan(P, Q, local_radix, global_radix, query_fused(), nullptr, &dp);
     if (rc != TUNA_OK) return rc;
     if (phase >= (int)dp->host.phases.size()) return TUNA_ERR_ARG;
     HIPCHK(hipDeviceSynchronize());
@@ -1455,42 +1861,57 @@ int tuna_plan_phase_sources(int P, int ranks_per_node, int local_radix, int glob
     return TUNA_OK;
 }
 
-int tuna_select_radix(int P, int ranks_per_node, int64_t payload_bytes, int* local_radix, int* global_radix,
-                      double* predicted_ms) {
-    if (!local_radix || !global_radix || payload_bytes < 0) return TUNA_ERR_ARG;
+int tuna_predict_ms(int P, int ranks_per_node, int local_radix, int global_radix, int mode, int t_layout,
+                    int64_t payload_bytes, int64_t max_block_bytes, int granularity, double* ms) {
+    if (!ms || payload_bytes < 0 || max_block_bytes < 0 || granularity < 0 || mode < TUNA_MODE_AUTO || mode > TUNA_MODE_FUSED ||
+        t_layout < TUNA_T_SLOTS || t_layout > TUNA_T_AUTO)
+        return TUNA_ERR_ARG;
     int Q = 0;
-    int rc = resolve_hierarchy(P, ranks_per_node, &Q);
+    const int rc = resolve_hierarchy(P, ranks_per_node, &Q);
     if (rc != TUNA_OK) return rc;
-    const int N = P / Q;
-    // measured on MI355X at P = 4096: the three copy stages ~6.0e12 B/s, the one-kernel phases ~5.0e12;
-    // metadata kernels of a phase ~40 us + 10 ps per matrix entry, validation + rotation ~0.25 ms at P = 4096
-    const double bw = g.opt_fused ? 5.0e12 : 6.0e12, c = g.opt_fused ? 2.0 : 6.0;
-    const double t_phase = 40e-6 + 1.0e-11 * (double)P * P, t_call = 40e-6 + 1.3e-11 * (double)P * P;
-    auto hops = [](int size, int r) {           // H(r) over one dimension
-        long long nz = 0;
-        for (int i = 0; i < size; ++i)
-            for (int v = i; v; v /= r) nz += (v % r) != 0;
-        return (double)nz / size;
-    };
-    auto best = [&](int size, int* radix) -> double {
-        if (size < 2) { *radix = 2; return 0.0; }
-        std::vector<int> cand;
-        for (long long r = 2; r < size; r *= 2) cand.push_back((int)r);
-        int sq = 2;
-        while ((long long)sq * sq < size) ++sq;
-        cand.push_back(sq);
-        cand.push_back(size);
-        double bt = -1.0;
-        for (int r : cand) {
-            const double t = num_digits(size, r) * t_phase + c * hops(size, r) * (double)payload_bytes / bw;
-            if (bt < 0 || t < bt) { bt = t; *radix = r; }
-        }
-        return bt;
-    };
-    const double tl = best(Q, local_radix), tg = best(N, global_radix);
-    if (predicted_ms) *predicted_ms = (t_call + tl + tg) * 1e3;
+    local_radix = auto_radix(local_radix, P); global_radix = auto_radix(global_radix, P);
+    if (local_radix < 2 || global_radix < 2) return TUNA_ERR_ARG;
+    *ms = predict_ms(P, Q, local_radix, global_radix, mode != TUNA_MODE_STAGED, t_layout, payload_bytes, max_block_bytes,
+                     granularity);
     return TUNA_OK;
 }
+
+int tuna_select(int P, int ranks_per_node, int64_t payload_bytes, int64_t max_block_bytes, int granularity,
+                tuna_choice_t* out) {
+    if (!out || payload_bytes < 0 || max_block_bytes < 0 || granularity < 0) return TUNA_ERR_ARG;
+    int Q = 0;
+    const int rc = resolve_hierarchy(P, ranks_per_node, &Q);
+    if (rc != TUNA_OK) return rc;
+    const int N = P / Q;
+    auto candidates = [](int size) {
+        std::vector<int> c;
+        if (size < 2) { c.push_back(2); return c; }
+        for (long long r = 2; r < size; r *= 2) c.push_back((int)r);
+        int sq = 2;
+        while ((long long)sq * sq < size) ++sq;
+        c.push_back(sq);
+        c.push_back(size);
+        return c;
+    };
+    std::memset(out, 0, sizeof(*out));
+    double best = -1.0;
+    for (int rl : candidates(Q))
+        for (int rg : candidates(N))
+            for (int fused = 1; fused >= 0; --fused)
+                for (int tl = TUNA_T_EXACT; tl >= TUNA_T_SLOTS; --tl) {
+                    const double t = predict_ms(P, Q, rl, rg, fused != 0, tl, payload_bytes, max_block_bytes, granularity);
+                    if (best < 0 || t < best * (1.0 - 1e-9)) {
+                        best = t;
+                        out->local_radix = rl; out->global_radix = rg;
+                        out->mode = fused ? TUNA_MODE_FUSED : TUNA_MODE_STAGED; out->t_layout = tl;
+                    }
+                }
+    out->predicted_ms = best;
+    out->calibrated = g_model.calibrated ? 1 : 0;
+    return TUNA_OK;
+}
+
+int tuna_calibrate(void* stream) { return calibrate((hipStream_t)stream); }
 
 int tuna_t_index(int o, int radix) {
     if (radix < 2) return -1;
@@ -1513,5 +1934,12 @@ const char* tuna_strerror(int code) {
 }
 
 int tuna_version(void) { return kVersion; }
+
+#ifndef TUNA_BUILD_ID
+#define TUNA_BUILD_ID "unknown"
+#endif
+// the prefix lets the build id be read from the library file without loading it
+static const char kBuildId[] = "tuna-build-id:" TUNA_BUILD_ID;
+const char* tuna_build_id(void) { return kBuildId + sizeof("tuna-build-id:") - 1; }
 
 }  // extern "C"

@@ -158,6 +158,19 @@ __global__ void __launch_bounds__(256) k_plain_copy(const v4u* __restrict__ src,
 }
 
 // ------------------------------------------------------------------------------------------
+// k_fill_uniform: the count and displacement matrices of a dense problem whose blocks all have
+// `bytes` bytes (the calibration problems of the cost model); one thread per matrix entry.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_fill_uniform(int32_t* __restrict__ sendcounts, int64_t* __restrict__ sdispls,
+                                                      int32_t* __restrict__ recvcounts, int64_t* __restrict__ rdispls,
+                                                      int P, int bytes) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)P * P) return;
+    sendcounts[i] = bytes; recvcounts[i] = bytes;
+    sdispls[i] = (int64_t)i * bytes; rdispls[i] = (int64_t)i * bytes;
+}
+
+// ------------------------------------------------------------------------------------------
 // k_build_hops: hm1[e] = (hops of the block with slot index e) - 1, at least 0.  A block makes one
 // hop per non-zero digit of its distance pair (l in base r_l, j in base r_g) and is stored into T
 // after every hop but its last -- hm1[e] times.
@@ -907,10 +920,11 @@ __global__ void __launch_bounds__(256) k_resolve_hop(const ResolveArgs a) {
 // resident workgroups per launch where fewer are faster by asking for unused dynamic LDS.  Unpack
 // keeps its payload in registers across the address resolution; left alone the compiler then takes
 // 84 registers (5 waves), held to 8 waves it needs 64 and spills nothing (byte-granular calls excepted).
-// The one-kernel variant needs 62 to 68 registers by itself; held to 8 waves it is scheduled for
-// occupancy and gathers of many short pieces run 6 % faster (measured at r = P on 16 GiB).
+// The one-kernel variant needs 62 to 72 registers by itself.  Where it fits into 64 without spilling
+// (4-byte granular, exact-size T) it is held to 8 waves too: scheduled for occupancy, gathers of many
+// short pieces run 6 % faster (measured at r = P on 16 GiB); the variants that would spill are left alone.
 template <int MODE, int GRAN, bool DENSE>
-__global__ void __launch_bounds__(kCopyThreads) __attribute__((amdgpu_waves_per_eu(((MODE == kUnpack || MODE == kFused) && GRAN >= 4) ? 8 : 1, 8)))
+__global__ void __launch_bounds__(kCopyThreads) __attribute__((amdgpu_waves_per_eu(((MODE == kUnpack && GRAN >= 4) || (MODE == kFused && GRAN == 4 && DENSE)) ? 8 : 1, 8)))
 k_copy(const CopyArgs a) {
     __shared__ int s_pre[kCopyThreads / kWave][kWave];
     __shared__ int s_size[kCopyThreads / kWave][kWave];

@@ -40,7 +40,7 @@ def _modes(tuna):
 
 
 def _reset_modes(tuna):
-    tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+    tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 2)
     tuna.tuna_set_option(tuna.TUNA_OPT_STAGGERED, 0)
 
 
@@ -140,7 +140,7 @@ def test_config3_caller_workspace_and_phase_times(tuna):
             assert int(recv.count_nonzero()) == 0
         finally:
             tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 0)
-            tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+            tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 2)
             tuna.tuna_set_workspace(None, 0)
         del ws
 
@@ -201,7 +201,7 @@ def test_config4_full(tuna):
         else:
             code = tuna.tuna_alltoallv(send, sc, sd, recv, rc, rd, P, r, 0)
         tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 2)
-        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 2)
         tuna.tuna_set_option(tuna.TUNA_OPT_BLOCK_COUNT, 0)
         assert code == 0, tuna.tuna_strerror(code)
         assert tuna.tuna_get_stats().dense_t == (0 if slots else 1)
@@ -244,7 +244,7 @@ def test_one_block_of_a_gibibyte(tuna):
         recv.fill_(0x3C)
         tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, fused)
         code = tuna.tuna_alltoallv(send, sc, sd, recv, rc, rd, 2, 2, 0)
-        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 2)
         assert code == 0, tuna.tuna_strerror(code)
         torch.cuda.synchronize()
         assert torch.equal(recv, want_dev)
@@ -279,7 +279,7 @@ def test_own_blocks_of_64_mebibytes(tuna):
             code = tuna.tuna_alltoallv(send, sc, sd, recv, rc, rd, P, 8, 0)
             st = tuna.tuna_get_stats()
         finally:
-            tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+            tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 2)
             tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 0)
         assert code == 0, tuna.tuna_strerror(code)
         torch.cuda.synchronize()
@@ -338,7 +338,7 @@ def test_sixteen_thousand_ranks(tuna):
         print("P=16384 radix=%d fused=%d" % (radix, fused), flush=True)
         tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, fused)
         code = tuna.tuna_alltoallv(send, sc, sd, recv, rc, rd, P, radix, 0)
-        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 2)
         assert code == 0, tuna.tuna_strerror(code)
         torch.cuda.synchronize()
         assert torch.equal(recv, want_dev), (radix, fused)

@@ -29,7 +29,7 @@ def mode(request, tuna):
     tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 1 if request.param.startswith("fused") else 0)
     tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 1 if request.param.endswith("exact") else 0)
     yield request.param
-    tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+    tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 2)
     tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 2)                 # the library's default
 
 

@@ -56,7 +56,7 @@ def test_start_follows_the_send_buffer(tuna, P, Q, rl, rg, cfg, fused):
     try:
         code, plan = tuna.tuna_alltoallv_init(res.send, res.sc, res.sd, res.recv, res.rc, res.rd, P, Q, rl, rg)
     finally:
-        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 2)
     assert code == 0, tuna.tuna_strerror(code)
     try:
         for seed in (11, 12, 13):                      # same counts, new payload every time
@@ -85,7 +85,7 @@ def test_plan_with_large_own_blocks(tuna, fused):
     try:
         code, plan = tuna.tuna_alltoallv_init(res.send, res.sc, res.sd, res.recv, res.rc, res.rd, P, 0, 3, 3)
     finally:
-        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 2)
     assert code == 0, tuna.tuna_strerror(code)
     try:
         for seed in (21, 22):
@@ -150,7 +150,7 @@ def test_start_captured_in_a_graph(tuna, fused):
     try:
         code, plan = tuna.tuna_alltoallv_init(res.send, res.sc, res.sd, res.recv, res.rc, res.rd, P, 0, 4, 4)
     finally:
-        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 2)
     assert code == 0
     try:
         want = res.load(1)
@@ -209,7 +209,7 @@ def _dense_plan(tuna, res, P, Q, rl, rg, fused=0, staggered=0, dense=1):
     try:
         return tuna.tuna_alltoallv_init(res.send, res.sc, res.sd, res.recv, res.rc, res.rd, P, Q, rl, rg)
     finally:
-        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 2)
         tuna.tuna_set_option(tuna.TUNA_OPT_STAGGERED, 0)
         tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 2)             # the library's default
 

@@ -1,0 +1,112 @@
+"""The fitted cost model behind tuna_select against timed calls on the device (Section "Performance
+analysis of TuNA", "Radix selection": the paper's choice of r depends on P and the block size through the
+network latency of a round; in one HBM the same question is answered by a model fitted to measurements).
+
+tuna_calibrate fits the constants to about forty timed calls of dense equal-block problems; the tests
+then time immediate calls of OTHER problems -- the benchmark configurations 2 to 5 and the paper's
+uniform [0, S] sizes at P = 2048 for S = 16 B, 512 B, 8 KiB -- over their radix sweeps, in both modes,
+and check two things: the predicted time of every setting lies within PREDICT_TOL of the measured one,
+and the setting tuna_select picks is within CHOICE_TOL of the best measured setting of the sweep."""
+import statistics
+import time
+
+import numpy as np
+import pytest
+
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+PREDICT_TOL = 0.20      # |predicted - measured| / measured
+CHOICE_TOL = 0.05       # measured time of the chosen setting over the best measured time, minus one
+
+
+@pytest.fixture(scope="module")
+def tuna():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2411_02581_amd as t
+    t.load()
+    rc = t.tuna_calibrate()
+    assert rc == 0, t.tuna_strerror(rc)
+    torch.cuda.synchronize()
+    return t
+
+
+def _time_sweep(tuna, counts, Q, sweep, modes):
+    """{(rl, rg, mode): (measured ms, predicted ms)} for immediate calls of the problem `counts`."""
+    P = counts.shape[0]
+    lay = wl.make_layout(counts)
+    dev = "cuda:0"
+    send = wl.payload_position_hash_torch(5, lay.send_bytes, dev)
+    recv = torch.empty(lay.recv_bytes, dtype=torch.uint8, device=dev)
+    d = [torch.from_numpy(a).to(dev) for a in (lay.sendcounts, lay.sdispls, lay.recvcounts, lay.rdispls)]
+    M = int(counts.max())
+    out = {}
+    for rl, rg in sweep:
+        for mode in modes:
+            o = tuna.tuna_opts_init()
+            o.mode = mode
+
+            # device addresses resolved once: the timed region holds one foreign call and the synchronisation
+            ptrs = [t.data_ptr() for t in (send, d[0], d[1], recv, d[2], d[3])]
+            stream = torch.cuda.current_stream().cuda_stream
+
+            def call():
+                rc = tuna.tuna_alltoallv_ex(None, *ptrs, P, Q, rl, rg, o, stream)
+                assert rc == 0, tuna.tuna_strerror(rc)
+                torch.cuda.synchronize()
+            call()
+            call()
+            ts = []
+            for _ in range(7):
+                t0 = time.perf_counter()
+                call()
+                ts.append((time.perf_counter() - t0) * 1e3)
+            st = tuna.tuna_get_stats()
+            rc, pred = tuna.tuna_predict_ms(P, Q, rl, rg, mode, tuna.TUNA_T_EXACT if st.dense_t else tuna.TUNA_T_SLOTS,
+                                            lay.payload_bytes, M, st.granularity)
+            assert rc == 0
+            gran = st.granularity
+            out[(rl, rg, mode)] = (statistics.median(ts), pred)
+    del send, recv, d
+    tuna.tuna_release()
+    torch.cuda.empty_cache()
+    return out, lay.payload_bytes, M, gran
+
+
+WORKLOADS = {
+    "config2": lambda: (wl.make_counts(2), 0, [(r, r) for r in (2, 4, 16, 256)]),
+    "config3": lambda: (wl.make_counts(3), 16, [(4, 2), (4, 8), (4, 64), (16, 64)]),
+    "config4": lambda: (wl.make_counts(4), 0, [(r, r) for r in (2, 8, 64, 4096)]),
+    "config5": lambda: (wl.make_counts(5), 32, [(2, 2), (16, 16), (32, 64)]),
+    "uniform16": lambda: (wl.counts_uniform_elements(2048, 99, 2, 8), 0, [(r, r) for r in (2, 8, 46, 2048)]),
+    "uniform512": lambda: (wl.counts_uniform_elements(2048, 99, 64, 8), 0, [(r, r) for r in (2, 8, 46, 2048)]),
+    "uniform8192": lambda: (wl.counts_uniform_elements(2048, 99, 1024, 8), 0, [(r, r) for r in (2, 8, 46, 2048)]),
+}
+
+
+@pytest.mark.parametrize("name", sorted(WORKLOADS))
+def test_prediction_and_choice(tuna, name):
+    counts, Q, sweep = WORKLOADS[name]()
+    P = counts.shape[0]
+    modes = (tuna.TUNA_MODE_FUSED, tuna.TUNA_MODE_STAGED)
+    res, payload, M, gran = _time_sweep(tuna, counts, Q, sweep, modes)
+    worst = 0.0
+    for (rl, rg, mode), (meas, pred) in sorted(res.items()):
+        err = (pred - meas) / meas
+        worst = max(worst, abs(err))
+        print("%-12s r_l=%-5d r_g=%-5d %-6s measured %9.3f ms  predicted %9.3f ms  %+5.1f %%" %
+              (name, rl, rg, "fused" if mode == tuna.TUNA_MODE_FUSED else "staged", meas, pred, 100 * err), flush=True)
+    assert worst <= PREDICT_TOL, "%s: worst prediction error %.1f %%" % (name, 100 * worst)
+    rc, ch = tuna.tuna_select(P, Q, payload, M, gran)
+    assert rc == 0 and ch.calibrated == 1
+    # a flat problem has no global phases: its sweep names one radix
+    key = (ch.local_radix, ch.global_radix if Q else ch.local_radix, ch.mode)
+    assert key in res, "%s: the selector chose %s, which the sweep does not hold" % (name, key)
+    best = min(v[0] for v in res.values())
+    print("%-12s chosen r_l=%d r_g=%d mode=%d: %.3f ms, best of the sweep %.3f ms" %
+          (name, key[0], key[1], key[2], res[key][0], best), flush=True)
+    assert res[key][0] <= best * (1 + CHOICE_TOL)

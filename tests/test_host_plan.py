@@ -215,11 +215,11 @@ def test_fused_tables_never_read_and_write_a_slot_in_one_phase(Q, N):
                 R, S, _ = _replay(counts, Q, rl, rg, fused=True)
                 assert R == _want(S), (Q, N, rl, rg)
     finally:
-        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 2)
     rc, plain = tuna.tuna_plan_info(P, Q, 2, 2)
     tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 1)
     rc, fused_info = tuna.tuna_plan_info(P, Q, 2, 2)
-    tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+    tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 2)
     assert fused_info.temp_slots_per_rank == 2 * plain.temp_slots_per_rank
 
 
@@ -239,18 +239,35 @@ def test_staggered_option_schedule(golden):
         tuna.tuna_set_option(tuna.TUNA_OPT_STAGGERED, 0)
 
 
-def test_select_radix_model():
-    """One HBM has no per-round latency: the model's minimiser is the linear schedule, and the
-    predicted time of configuration 4 at r = P is the three-stage bound 6 * payload / bandwidth
-    plus a few hundred microseconds."""
-    rc, rl, rg, ms = tuna.tuna_select_radix(4096, 0, 16 << 30)
-    assert rc == 0 and rl == 4096
-    assert 6 * (16 << 30) * 4095 / 4096 / 6.0e12 * 1e3 < ms < 6 * (16 << 30) / 6.0e12 * 1e3 + 1.5
-    rc, rl, rg, ms = tuna.tuna_select_radix(1024, 16, 1 << 30)
-    assert rc == 0 and (rl, rg) == (16, 64)
-    rc, rl, rg, ms_small = tuna.tuna_select_radix(256, 0, 1 << 10)
-    assert rc == 0 and rl == 256 and ms_small < 1.0
-    assert tuna.tuna_select_radix(12, 5, 100)[0] == tuna.TUNA_ERR_ARG
+def test_select_model():
+    """One HBM has no per-round latency: with the built-in constants (no GPU here) the model's minimiser
+    is the linear schedule with one-kernel hops for every payload, the predicted time of configuration 4
+    at r = P is what its bytes cost at about 5.3 TB/s plus under a millisecond, three stages cost three
+    times the bytes, and emptier slots cost more than exact-size T."""
+    big = 16 << 30
+    rc, ch = tuna.tuna_select(4096, 0, big, 2412)
+    assert rc == 0 and (ch.local_radix, ch.mode, ch.t_layout, ch.calibrated) == (4096, tuna.TUNA_MODE_FUSED, tuna.TUNA_T_EXACT, 0)
+    assert 2 * big * 4095 / 4096 / 5.5e12 * 1e3 < ch.predicted_ms < 2 * big / 5.0e12 * 1e3 + 1.0
+    rc, ms_staged = tuna.tuna_predict_ms(4096, 0, 4096, 4096, tuna.TUNA_MODE_STAGED, tuna.TUNA_T_EXACT, big, 2412)
+    assert rc == 0 and 2.0 < ms_staged / ch.predicted_ms < 3.0
+    rc, ms_r2 = tuna.tuna_predict_ms(4096, 0, 2, 2, tuna.TUNA_MODE_FUSED, tuna.TUNA_T_EXACT, big, 2412)
+    rc, ms_r2_slots = tuna.tuna_predict_ms(4096, 0, 2, 2, tuna.TUNA_MODE_FUSED, tuna.TUNA_T_SLOTS, big, 2412)
+    assert ms_r2 > 4 * ch.predicted_ms and 1.05 < ms_r2_slots / ms_r2 < 1.6
+    rc, ms_full_slots = tuna.tuna_predict_ms(2048, 32, 2, 2, tuna.TUNA_MODE_FUSED, tuna.TUNA_T_SLOTS, 1 << 30, 256)
+    rc, ms_full_exact = tuna.tuna_predict_ms(2048, 32, 2, 2, tuna.TUNA_MODE_FUSED, tuna.TUNA_T_EXACT, 1 << 30, 256)
+    assert ms_full_slots == ms_full_exact                      # full slots are as dense as exact size
+    rc, ch = tuna.tuna_select(1024, 16, 1 << 30, 16384)
+    assert rc == 0 and (ch.local_radix, ch.global_radix, ch.mode) == (16, 64, tuna.TUNA_MODE_FUSED)
+    rc, small = tuna.tuna_select(256, 0, 1 << 10)
+    assert rc == 0 and small.local_radix == 256 and small.predicted_ms < 0.2
+    rc, auto = tuna.tuna_predict_ms(256, 0, tuna.TUNA_RADIX_AUTO, tuna.TUNA_RADIX_AUTO, tuna.TUNA_MODE_AUTO, tuna.TUNA_T_AUTO, 1 << 10)
+    assert rc == 0 and auto == small.predicted_ms
+    assert tuna.tuna_select(12, 5, 100)[0] == tuna.TUNA_ERR_ARG
+    assert tuna.tuna_predict_ms(12, 0, 1, 2, 0, 0, 100)[0] == tuna.TUNA_ERR_ARG
+    rc, odd = tuna.tuna_predict_ms(256, 0, 256, 256, tuna.TUNA_MODE_FUSED, tuna.TUNA_T_EXACT, 32 << 20, 1024, 1)
+    rc, even = tuna.tuna_predict_ms(256, 0, 256, 256, tuna.TUNA_MODE_FUSED, tuna.TUNA_T_EXACT, 32 << 20, 1024, 4)
+    assert odd > even                                          # byte-granular kernels cost more per byte
+    assert tuna.tuna_predict_ms(12, 0, 2, 2, 5, 0, 100)[0] == tuna.TUNA_ERR_ARG
 
 
 def test_random_schedules_deliver_every_block():
@@ -268,7 +285,7 @@ def test_random_schedules_deliver_every_block():
         try:
             R, S, _ = _replay(counts, Q, rl, rg, fused=fused)
         finally:
-            tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+            tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 2)
         assert R == _want(S)
     prop()
 

@@ -70,22 +70,30 @@ def test_two_calls_in_a_row_match_the_allocating_entry_point(tuna, fused, dense)
             assert np.array_equal(got, case.want), name + ": differs from the oracle"
             assert np.array_equal(case.send.cpu().numpy(), case.send_host), name + ": send buffer modified"
     finally:
-        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 2)
         tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 2)
 
 
 def test_a_problem_beyond_the_static_scratch_is_refused(tuna):
-    """32 MiB of payload needs two staging buffers of that size: more than the array holds.  The call
-    says so and moves nothing; a small call right after it works."""
+    """32 MiB of payload in three-stage phases needs two staging buffers of that size: more than the
+    array holds.  The call says so and moves nothing; a small call right after it works; and the same
+    problem with one-kernel hops (no staging) fits and is right."""
     case = Case(wl.make_counts(2), seed=9, gap=0, Q=0, rl=16, rg=16)
     assert 2 * case.lay.payload_bytes > tuna.TUNA_NOALLOC_SCRATCH_BYTES
-    rc, got = case.run(tuna.tuna_alltoallv_noalloc)
+    tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
+    try:
+        rc, got = case.run(tuna.tuna_alltoallv_noalloc)
+    finally:
+        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 2)
     assert rc == tuna.TUNA_ERR_NOALLOC_LIMIT, tuna.tuna_strerror(rc)
     assert (got == CANARY).all()
     assert "static scratch" in tuna.tuna_strerror(rc)
     small = small_case()
     rc, got = small.run(tuna.tuna_alltoallv_noalloc)
     assert rc == 0 and np.array_equal(got, small.want)
+    rc, got = case.run(tuna.tuna_alltoallv_noalloc)
+    assert rc == 0, tuna.tuna_strerror(rc)
+    assert np.array_equal(got, case.want)
 
 
 def test_argument_errors(tuna):
