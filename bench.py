@@ -1,16 +1,25 @@
 #!/usr/bin/env python3
 """Benchmark of the tunable-radix non-uniform all-to-all on one MI355X.
 
-A "step" is one whole tuna_alltoallv call (validation, initial rotation, every digit phase:
-metadata exchange, scan, pack, exchange, unpack) over one synthetic problem whose send and
-receive buffers are already resident in HBM.  Default workload: the P = 4096 flat configuration
-(block sizes normal(1 KiB, 256 B), ~16 GiB payload), radix sweep {2, 8, 64, 4096}.
+A "step" is one whole immediate call (validation, initial rotation, the ranks' own blocks, every
+digit phase: metadata exchange, scans, the payload kernels) over one synthetic problem whose send
+and receive buffers are already resident in HBM.  Default workload: the P = 4096 flat configuration
+(block sizes normal(1 KiB, 256 B), ~16 GiB payload), radix sweep {2, 8, 64, 4096}, with the library's
+default options (the mode and the layout of T left to the library).
 
-Prints ONE JSON line: `value` is the effective Alltoallv rate (payload bytes / time per call) of
-the best radix; `per_radix` has every radix; `roofline` is the dominant copy kernel's achieved
-HBM rate (algorithmic bytes = 2 x payload bytes it moves, read + write) against 8 TB/s, timed
-with HIP events on the call's stream; `cpu_baseline` is the plain CPU oracle timed on a bounded
-sample of the same problem on this machine's host cores.
+Prints ONE JSON line:
+  value         effective Alltoallv rate (payload bytes / time per call) of the best radix, defaults
+  per_radix     every radix of that sweep, with the payload kernels' event-timed rates
+  three_stage   the same sweep with pack -> exchange -> unpack as three kernels (the paper's three steps;
+                the >= 60 % of HBM peak target is stated for these kernels)
+  persistent    tuna_alltoallv_init once, then tuna_start per step
+  roofline      the dominant payload kernel of the timed sweep: algorithmic bytes (2 x the payload bytes
+                it moves: read + write) / event-timed duration, against 8 TB/s; `traffic` = HBM bytes
+                per launch from hardware counters (profiles/traffic_config4_P4096.txt)
+  also_measured the P = 1024 hierarchical configuration (the other half of the headline metric) and short
+                rows for the staggered schedule, batches of rounds, the FFT count patterns at P = 8192,
+                large own blocks and the small-block regime
+  cpu_baseline  the plain CPU oracle timed on a bounded sample of the same problem on this machine's cores
 """
 from __future__ import annotations
 
@@ -26,17 +35,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-
-# HBM bytes per launch (read + write), averaged over the launches of the default sweep
-# (P = 4096, radices 2, 8, 64, 4096: 19 launches of each copy kernel per step set), from two
-# `rocprofv3 --pmc` runs (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter
-# reads for tuna::k_plain_copy moving 4 GiB (factors 2.0000 and 0.9997).  The algorithmic figure
-# for the same launches is 2 x payload = 22.55e9 bytes; see profiles/k_copy_config4_P4096.md.
-# First entry: T in exact size (the default); second: T in slots of M bytes (--exact-t 0).
-MEASURED_TRAFFIC_CONFIG4 = {
-    True: {"pack": 22816.4 * 2**20, "exchange": 22307.3 * 2**20, "unpack": 22496.0 * 2**20, "fused": 23689.2 * 2**20},
-    False: {"pack": 22847.3 * 2**20, "exchange": 22307.3 * 2**20, "unpack": 22486.3 * 2**20, "fused": 23695.8 * 2**20},
-}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic_config4_P4096.txt")
+MODES = {"auto": 0, "staged": 1, "fused": 2}
+STAGE_OF_MODE = {0: "pack", 1: "exchange", 2: "unpack", 3: "hop"}
 
 
 def parse_args():
@@ -45,6 +46,9 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, help="workload configuration 1..5")
+    ap.add_argument("--workload", type=str, default="",
+                    help="instead of --config: fft_n1 | fft_n2 (the count patterns of the paper's FFT runs) | diagonal "
+                         "(64 MiB kept by every rank for itself); use with --ranks")
     ap.add_argument("--ranks", type=int, default=0, help="override P (reduced-size runs)")
     ap.add_argument("--radices", type=str, default="", help="comma-separated radix sweep")
     ap.add_argument("--element-bytes", type=int, default=8,
@@ -53,31 +57,216 @@ def parse_args():
     ap.add_argument("--uniform-max-bytes", type=int, default=0,
                     help="replace the configuration's counts by 8 * U{0..S/8} bytes (the paper's uniform [0, S] "
                          "micro-benchmark with FP64 elements); use with --ranks and --radices")
-    ap.add_argument("--fused", type=int, default=0, help="1: fused single-kernel rounds")
-    ap.add_argument("--exact-t", type=int, default=2,
-                    help="main sweep, TUNA_OPT_DENSE_T: 2 = the library's default (T in exact size unless the paper's slots "
-                         "would be 90 %% full), 1 = exact size, 0 = the paper's B slots of M bytes")
+    ap.add_argument("--mode", choices=sorted(MODES), default="auto",
+                    help="main sweep: auto = left to the library (its default), staged = pack / exchange / unpack, "
+                         "fused = one kernel per digit phase")
+    ap.add_argument("--t-layout", type=int, default=2,
+                    help="main sweep, layout of T: 2 = left to the library, 1 = exact size, 0 = the paper's B slots of M bytes")
+    ap.add_argument("--staggered", action="store_true", help="main sweep with the staggered inter-node schedule")
     ap.add_argument("--block-count", type=int, default=0,
-                    help="TUNA_OPT_BLOCK_COUNT: rounds per batch of launches (0: all rounds of a phase at once)")
+                    help="rounds per batch of launches (0: all rounds of a phase at once)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-fused-table", action="store_true", help="skip the second sweep with fused rounds")
-    ap.add_argument("--secondary", action="store_true",
-                    help="also sweep the P=1024 hierarchical workload (configuration 3) into also_measured; off by "
-                         "default so that every launch of a copy kernel in the run belongs to the timed workload")
-    ap.add_argument("--no-secondary", action="store_true", help="accepted for older command lines; the default now")
-    ap.add_argument("--no-persistent-table", action="store_true", help="skip the tuna_alltoallv_init / tuna_start sweep")
+    ap.add_argument("--no-three-stage-table", action="store_true", help="skip the sweep with three-stage phases")
+    ap.add_argument("--no-persistent-table", action="store_true", help="skip the tuna_alltoallv_init / tuna_start sweeps")
+    ap.add_argument("--no-secondary", action="store_true", help="skip also_measured (configuration 3 and the short rows)")
+    ap.add_argument("--slots-table", action="store_true", help="also sweep with T in the paper's slots of M bytes")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
-    ap.add_argument("--traffic-json", type=str, default="",
-                    help="optional JSON file {kernel: bytes per launch} from rocprofv3 --pmc runs")
+    ap.add_argument("--traffic-file", type=str, default=TRAFFIC_FILE,
+                    help="text file with the JSON object {kernel name: HBM bytes per launch} of the default run's "
+                         "rocprofv3 --pmc passes (lines starting with # are comments)")
     return ap.parse_args()
 
 
-def sweep_of(cfg, P):
-    import workloads as wl
-    c = wl.CONFIGS[cfg]
-    if c.global_radices:   # separate local / global radices
-        return [("hier", c.ranks_per_node, c.local_radix, rg) for rg in c.global_radices]
-    return [("single", c.ranks_per_node, min(r, P), min(r, P)) for r in c.radices]
+def load_traffic(path):
+    """{kernel name: bytes per launch} and the build id it was measured at, from the tracked summary file."""
+    try:
+        with open(path) as f:
+            text = "".join(line for line in f if not line.lstrip().startswith("#"))
+        return json.loads(text)
+    except (OSError, ValueError):
+        return None
+
+
+class Resident:
+    """One problem resident on the GPU, and timed calls of it."""
+
+    def __init__(self, tuna, counts, seed, ranks_per_node, steps, warmup):
+        import torch
+
+        import workloads as wl
+        self.tuna, self.torch = tuna, torch
+        self.lay = lay = wl.make_layout(counts)
+        self.P = lay.P
+        self.rpn = ranks_per_node
+        self.steps, self.warmup = steps, warmup
+        dev = "cuda:0"
+        self.send = wl.payload_position_hash_torch(seed, lay.send_bytes, dev)
+        self.recv = torch.empty(lay.recv_bytes, dtype=torch.uint8, device=dev)
+        self.meta = [torch.from_numpy(a).to(dev) for a in (lay.sendcounts, lay.sdispls, lay.recvcounts, lay.rdispls)]
+        self.max_block = int(counts.max()) if counts.size else 0
+        torch.cuda.synchronize()
+
+    def opts(self, mode=0, t_layout=2, staggered=0, block_count=0, profile=0):
+        o = self.tuna.tuna_opts_init()
+        o.mode, o.t_layout, o.staggered, o.block_count, o.profile = mode, t_layout, staggered, block_count, profile
+        return o
+
+    def call(self, rl, rg, o):
+        sc, sd, rc_, rd = self.meta
+        rc = self.tuna.tuna_alltoallv_ex(None, self.send, sc, sd, self.recv, rc_, rd, self.P, self.rpn, rl, rg, o)
+        if rc != 0:
+            raise RuntimeError("tuna_alltoallv_ex failed: " + self.tuna.tuna_strerror(rc))
+
+    def time_calls(self, rl, rg, o, label):
+        """K timed immediate calls between two synchronisations, then the same K calls with HIP events
+        around every kernel (the kernels' rates)."""
+        tuna, torch = self.tuna, self.torch
+        Btot = self.lay.payload_bytes
+        for _ in range(self.warmup):
+            self.call(rl, rg, o)
+        torch.cuda.synchronize()
+        step_ms = []
+        t_start = time.perf_counter()
+        for _ in range(self.steps):
+            t1 = time.perf_counter()
+            self.call(rl, rg, o)
+            torch.cuda.synchronize()
+            step_ms.append((time.perf_counter() - t1) * 1e3)
+        torch.cuda.synchronize()
+        ms_per_step = (time.perf_counter() - t_start) * 1e3 / self.steps
+        o.profile = 1
+        kern = {"pack": [0.0, 0, 0], "exchange": [0.0, 0, 0], "unpack": [0.0, 0, 0]}   # ms, launches, payload bytes
+        meta_ms = prep_ms = self_ms = prof_total = 0.0
+        for _ in range(self.steps):
+            self.call(rl, rg, o)
+            st = tuna.tuna_get_stats()
+            prof_total += st.ms_total
+            prep_ms += st.ms_prepare
+            self_ms += st.ms_self
+            for x in range(st.n_phases):
+                ph = st.phase[x]
+                meta_ms += ph.ms_metadata
+                for name, ms in (("pack", ph.ms_pack), ("exchange", ph.ms_exchange), ("unpack", ph.ms_unpack)):
+                    if ms > 0:
+                        kern[name][0] += ms
+                        kern[name][1] += 1
+                        kern[name][2] += ph.payload_bytes
+        o.profile = 0
+        st = tuna.tuna_get_stats()
+        hop_bytes = sum(st.phase[x].payload_bytes for x in range(st.n_phases))
+        if st.fused:        # one kernel per phase; its time is reported in the pack column
+            kern = {"hop": kern["pack"]}
+        kernels = {}
+        for name, (ms, n, pbytes) in kern.items():
+            if n and ms > 0:
+                kernels[name] = {"avg_ms": ms / n, "launches_per_step": n // self.steps,
+                                 "alg_bytes_per_launch": 2 * pbytes / n,
+                                 "achieved_GBs": 2 * pbytes / (ms * 1e-3) / 1e9}
+        row = {"radix": label, "ms_per_step": ms_per_step, "median_ms": statistics.median(step_ms),
+               "stdev_ms": statistics.pstdev(step_ms), "effective_GBs": Btot / (ms_per_step * 1e-3) / 1e9,
+               "phases": st.n_phases, "rounds": st.K_local + st.K_global, "hop_bytes": hop_bytes,
+               "temp_bytes": st.temp_bytes, "workspace_bytes": st.workspace_bytes, "exact_size_t": st.dense_t,
+               "one_kernel_phases": st.fused, "profiled_ms_per_step": prof_total / self.steps,
+               "metadata_ms_per_step": meta_ms / self.steps, "prepare_ms_per_step": prep_ms / self.steps,
+               "own_blocks_ms_per_step": self_ms / self.steps, "kernels": kernels, "granularity": st.granularity}
+        print("[bench] %s: %.3f ms/step, %.1f GB/s effective; " % (label, ms_per_step, row["effective_GBs"]) +
+              ", ".join("%s %.0f GB/s" % (k, v["achieved_GBs"]) for k, v in kernels.items()) +
+              (" [one-kernel phases]" if st.fused else " [three stages]"), file=sys.stderr, flush=True)
+        return row
+
+    def sweep(self, radices, **opt):
+        return [self.time_calls(rl, rg, self.opts(**opt), label) for label, rl, rg in radices]
+
+    def time_plan(self, rl, rg, o, label):
+        """tuna_alltoallv_init once, then K timed tuna_start calls (payload kernels only: no validation,
+        no metadata kernels, no host synchronisation), eagerly and as one captured HIP graph."""
+        tuna, torch = self.tuna, self.torch
+        sc, sd, rc_, rd = self.meta
+        rc, plan = tuna.tuna_alltoallv_init_ex(None, self.send, sc, sd, self.recv, rc_, rd, self.P, self.rpn, rl, rg, o)
+        if rc != 0:
+            raise RuntimeError("tuna_alltoallv_init_ex failed: " + tuna.tuna_strerror(rc))
+        try:
+            for _ in range(self.warmup):
+                tuna.tuna_start(plan)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(self.steps):
+                tuna.tuna_start(plan)
+            torch.cuda.synchronize()
+            ms_start = (time.perf_counter() - t1) * 1e3 / self.steps
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                tuna.tuna_start(plan)
+            graph.replay()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(self.steps):
+                graph.replay()
+            torch.cuda.synchronize()
+            ms_graph = (time.perf_counter() - t1) * 1e3 / self.steps
+            del graph
+            st = tuna.tuna_get_stats()
+            row = {"radix": label, "ms_per_start": ms_start, "ms_per_graph_replay": ms_graph,
+                   "effective_GBs": self.lay.payload_bytes / (min(ms_start, ms_graph) * 1e-3) / 1e9,
+                   "plan_bytes": st.workspace_bytes, "temp_bytes": st.temp_bytes, "one_kernel_phases": st.fused,
+                   "exact_size_t": st.dense_t}
+            print("[bench] %s persistent%s: %.3f ms/start, %.3f ms/graph replay, %.1f GB/s effective, T %.2f GiB" %
+                  (label, " one-kernel" if st.fused else " three stages", ms_start, ms_graph, row["effective_GBs"],
+                   st.temp_bytes / 2 ** 30), file=sys.stderr, flush=True)
+            return row
+        finally:
+            tuna.tuna_plan_free(plan)
+
+    def close(self):
+        del self.send, self.recv, self.meta
+        self.tuna.tuna_release()
+        self.torch.cuda.empty_cache()
+
+
+def radices_of(cfg, P, override=""):
+    """[(label, local radix, global radix)] of a configuration's sweep."""
+    if override:
+        rs = [int(x) for x in override.split(",")]
+    elif cfg.global_radices:
+        rs = list(cfg.global_radices)
+    else:
+        rs = list(cfg.radices)
+    if cfg.global_radices:
+        return [("r_l=%d,r_g=%d" % (cfg.local_radix, r), cfg.local_radix, r) for r in rs]
+    return [("r=%d" % min(r, P), min(r, P), min(r, P)) for r in rs]
+
+
+def kernel_name(stage, gran, exact):
+    et = "true" if exact else "false"
+    return {"pack": "tuna::k_copy<0, %d, %s>" % (gran, et), "exchange": "tuna::k_copy<1, 16, false>",
+            "unpack": "tuna::k_copy<2, %d, %s>" % (min(gran, 16), et), "hop": "tuna::k_copy<3, %d, %s>" % (gran, et)}[stage]
+
+
+def roofline_of(rows, steps, traffic, copy_ceiling):
+    """The payload kernel with the largest total time over ALL launches of the timed sweep (every radix),
+    so that its average launch duration is the one `rocprofv3 --kernel-trace --stats` of the same command
+    reports for that kernel."""
+    tot = {}
+    for r in rows:
+        for name, v in r["kernels"].items():
+            t = tot.setdefault(name, [0.0, 0, 0.0])
+            n = v["launches_per_step"] * steps
+            t[0] += v["avg_ms"] * n
+            t[1] += n
+            t[2] += v["alg_bytes_per_launch"] * n
+    if not tot:
+        return None
+    name, (ms, n, alg) = max(tot.items(), key=lambda kv: kv[1][0])
+    kname = kernel_name(name, rows[0]["granularity"], bool(rows[0]["exact_size_t"]))
+    achieved = alg / (ms * 1e-3) / 1e9
+    tr = traffic.get("bytes_per_launch", {}).get(kname) if traffic else None
+    return {"bound": "hbm", "kernel": kname, "stage": name, "achieved": achieved, "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": tr,
+            "traffic_source": None if tr is None else {"file": "profiles/traffic_config4_P4096.txt",
+                                                        "library_build_id": traffic.get("library_build_id")},
+            "avg_launch_ms": ms / n, "launches": n, "alg_bytes_per_launch": alg / n,
+            "frac_of_plain_copy": (achieved / copy_ceiling["GBs"]) if copy_ceiling else None,
+            "all_stages_GBs": {k: v[2] / (v[0] * 1e-3) / 1e9 for k, v in tot.items()}}
 
 
 def main():
@@ -96,314 +285,175 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     tuna.load()
-    dev = "cuda:0"
     cfg = wl.CONFIGS[args.config]
     P = args.ranks or cfg.P
     t0 = time.time()
-    if args.uniform_max_bytes:
+    if args.workload == "fft_n1":
+        counts, wname = wl.counts_fft_n1(P), "FFT count pattern N1 (Section \"Fast Fourier transform\"), P=%d flat" % P
+    elif args.workload == "fft_n2":
+        counts, wname = wl.counts_fft_n2(P), "FFT count pattern N2 (Section \"Fast Fourier transform\"), P=%d flat" % P
+    elif args.workload == "diagonal":
+        counts, wname = diagonal_counts(P), "64 MiB kept by every rank for itself, small blocks elsewhere, P=%d flat" % P
+    elif args.uniform_max_bytes:
         counts = wl.counts_uniform_elements(P, cfg.seed, args.uniform_max_bytes // args.element_bytes, args.element_bytes)
+        wname = "uniform [0, %d] bytes in %d-byte elements, P=%d flat" % (args.uniform_max_bytes, args.element_bytes, P)
     else:
-        counts = wl.make_counts(args.config, P)
-    lay = wl.make_layout(counts)
-    Btot = lay.payload_bytes
-    print("[bench] config %d: P=%d payload %.3f GiB, inputs built in %.1f s" %
-          (args.config, P, Btot / 2**30, time.time() - t0), file=sys.stderr, flush=True)
-
-    send = wl.payload_position_hash_torch(cfg.seed, lay.send_bytes, dev)
-    recv = torch.empty(lay.recv_bytes, dtype=torch.uint8, device=dev)
-    d_sc = torch.from_numpy(lay.sendcounts).to(dev)
-    d_sd = torch.from_numpy(lay.sdispls).to(dev)
-    d_rc = torch.from_numpy(lay.recvcounts).to(dev)
-    d_rd = torch.from_numpy(lay.rdispls).to(dev)
-    torch.cuda.synchronize()
-
-    if args.block_count:
-        tuna.tuna_set_option(tuna.TUNA_OPT_BLOCK_COUNT, args.block_count)
-    sweep = sweep_of(args.config, P)
-    if args.radices:
-        rs = [int(x) for x in args.radices.split(",")]
-        if cfg.global_radices:
-            sweep = [("hier", cfg.ranks_per_node, cfg.local_radix, r) for r in rs]
-        else:
-            sweep = [("single", cfg.ranks_per_node, min(r, P), min(r, P)) for r in rs]
-    rpn = cfg.ranks_per_node if P % max(cfg.ranks_per_node, 1) == 0 else 0
-
-    def call(kind, rl, rg):
-        if kind == "hier":
-            rc = tuna.tuna_alltoallv_hier(send, d_sc, d_sd, recv, d_rc, d_rd, P, rpn, rl, rg)
-        else:
-            rc = tuna.tuna_alltoallv(send, d_sc, d_sd, recv, d_rc, d_rd, P, rl, rpn)
-        if rc != 0:
-            raise RuntimeError("tuna_alltoallv failed: " + tuna.tuna_strerror(rc))
+        counts, wname = wl.make_counts(args.config, P), "config %d: %s" % (args.config, cfg.description)
+    named = bool(args.workload)
+    rpn = 0 if named or args.uniform_max_bytes else (cfg.ranks_per_node if P % max(cfg.ranks_per_node, 1) == 0 else 0)
+    res = Resident(tuna, counts, cfg.seed, rpn, args.steps, args.warmup)
+    Btot = res.lay.payload_bytes
+    print("[bench] %s: P=%d payload %.3f GiB, inputs built in %.1f s, library build %s" %
+          (wname, P, Btot / 2**30, time.time() - t0, tuna.tuna_build_id()), file=sys.stderr, flush=True)
+    if named or args.uniform_max_bytes:
+        rs = [int(x) for x in args.radices.split(",")] if args.radices else [2, P]
+        sweep = [("r=%d" % min(r, P), min(r, P), min(r, P)) for r in rs]
+    else:
+        sweep = radices_of(cfg, P, args.radices)
 
     # ---- practical ceiling: a plain one-chunk-per-thread copy of up to 4 GiB ----------------------
-    nb = min(4 << 30, lay.send_bytes // 16 * 16, lay.recv_bytes // 16 * 16)
+    nb = min(4 << 30, res.lay.send_bytes // 16 * 16, res.lay.recv_bytes // 16 * 16)
     copy_ceiling = None
     if nb >= (1 << 20):
         for _ in range(2):
-            tuna.tuna_plain_copy(send, recv, nb)
+            tuna.tuna_plain_copy(res.send, res.recv, nb)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(10):
-            tuna.tuna_plain_copy(send, recv, nb)
+            tuna.tuna_plain_copy(res.send, res.recv, nb)
         e1.record()
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / 10
         copy_ceiling = {"GBs": 2 * nb / (ms * 1e-3) / 1e9, "bytes_copied": nb, "ms": ms}
         print("[bench] plain copy ceiling: %.0f GB/s (read + write)" % copy_ceiling["GBs"], file=sys.stderr, flush=True)
 
-    def run_sweep(fused, exact_t=2):
-        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 1 if fused else 0)
-        tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, int(exact_t))
-        per_radix = []
-        for kind, _, rl, rg in sweep:
-            label = "r_l=%d,r_g=%d" % (rl, rg) if kind == "hier" else "r=%d" % rl
-            tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 0)
-            for _ in range(args.warmup):
-                call(kind, rl, rg)
-            torch.cuda.synchronize()
-            # ---- timed region: exactly K steps between two synchronisations ----------------------
-            step_ms = []
-            t_start = time.perf_counter()
-            for _ in range(args.steps):
-                t1 = time.perf_counter()
-                call(kind, rl, rg)
-                torch.cuda.synchronize()
-                step_ms.append((time.perf_counter() - t1) * 1e3)
-            torch.cuda.synchronize()
-            total_ms = (time.perf_counter() - t_start) * 1e3
-            ms_per_step = total_ms / args.steps
-            # ---- the same K steps with HIP events around every kernel (roofline figures) ----------
-            tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 1)
-            kern = {"pack": [0.0, 0, 0], "exchange": [0.0, 0, 0], "unpack": [0.0, 0, 0]}   # ms, launches, payload bytes
-            meta_ms = prep_ms = 0.0
-            prof_total = 0.0
-            for _ in range(args.steps):
-                call(kind, rl, rg)
-                st = tuna.tuna_get_stats()
-                prof_total += st.ms_total
-                prep_ms += st.ms_prepare + st.ms_self
-                for x in range(st.n_phases):
-                    ph = st.phase[x]
-                    meta_ms += ph.ms_metadata
-                    for name, ms in (("pack", ph.ms_pack), ("exchange", ph.ms_exchange), ("unpack", ph.ms_unpack)):
-                        kern[name][0] += ms
-                        kern[name][1] += 1
-                        kern[name][2] += ph.payload_bytes
-            tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 0)
-            st = tuna.tuna_get_stats()
-            hop_bytes = sum(st.phase[x].payload_bytes for x in range(st.n_phases))
-            if st.fused:        # one kernel per phase; its time is reported in the pack column
-                kern = {"fused": kern["pack"]}
-            kernels = {}
-            for name, (ms, n, pbytes) in kern.items():
-                if n and ms > 0:
-                    kernels[name] = {"avg_ms": ms / n, "launches_per_step": n // args.steps,
-                                     "alg_bytes_per_launch": 2 * pbytes / n,
-                                     "achieved_GBs": 2 * pbytes / (ms * 1e-3) / 1e9}
-            per_radix.append({
-                "radix": label, "ms_per_step": ms_per_step, "median_ms": statistics.median(step_ms),
-                "stdev_ms": statistics.pstdev(step_ms), "effective_GBs": Btot / (ms_per_step * 1e-3) / 1e9,
-                "phases": st.n_phases, "rounds": st.K_local + st.K_global, "hop_bytes": hop_bytes,
-                "temp_bytes": st.temp_bytes, "workspace_bytes": st.workspace_bytes, "exact_size_t": st.dense_t,
-                "profiled_ms_per_step": prof_total / args.steps, "metadata_ms_per_step": meta_ms / args.steps,
-                "prepare_ms_per_step": prep_ms / args.steps, "kernels": kernels, "granularity": st.granularity})
-            print("[bench] %s: %.3f ms/step, %.1f GB/s effective; " % (label, ms_per_step, per_radix[-1]["effective_GBs"]) +
-                  ", ".join("%s %.0f GB/s" % (k, v["achieved_GBs"]) for k, v in kernels.items()) +
-              (" [fused rounds]" if fused else ""),
-                  file=sys.stderr, flush=True)
-
-        tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
-        tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 2)
-        return per_radix
-
-    def run_persistent(fused, exact_t=2):
-        """tuna_alltoallv_init once per radix, then K timed tuna_start calls (no validation, no
-        metadata kernels, no host synchronisation), eagerly and as one captured HIP graph.
-        exact_t: T stored in exact size (one arena per phase) instead of B slots of M bytes."""
-        rows = []
-        for kind, _, rl, rg in sweep:
-            label = "r_l=%d,r_g=%d" % (rl, rg) if kind == "hier" else "r=%d" % rl
-            tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 1 if fused else 0)
-            tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, int(exact_t))
-            rc, plan = tuna.tuna_alltoallv_init(send, d_sc, d_sd, recv, d_rc, d_rd, P, rpn, rl, rg)
-            tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
-            tuna.tuna_set_option(tuna.TUNA_OPT_DENSE_T, 2)
-            if rc != 0:
-                raise RuntimeError("tuna_alltoallv_init failed: " + tuna.tuna_strerror(rc))
-            try:
-                for _ in range(args.warmup):
-                    tuna.tuna_start(plan)
-                torch.cuda.synchronize()
-                t1 = time.perf_counter()
-                for _ in range(args.steps):
-                    tuna.tuna_start(plan)
-                torch.cuda.synchronize()
-                ms_start = (time.perf_counter() - t1) * 1e3 / args.steps
-                graph = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(graph):
-                    tuna.tuna_start(plan)
-                graph.replay()
-                torch.cuda.synchronize()
-                t1 = time.perf_counter()
-                for _ in range(args.steps):
-                    graph.replay()
-                torch.cuda.synchronize()
-                ms_graph = (time.perf_counter() - t1) * 1e3 / args.steps
-                del graph
-                st = tuna.tuna_get_stats()
-                rows.append({"radix": label, "ms_per_start": ms_start, "ms_per_graph_replay": ms_graph,
-                             "effective_GBs": Btot / (min(ms_start, ms_graph) * 1e-3) / 1e9,
-                             "plan_bytes": st.workspace_bytes, "temp_bytes": st.temp_bytes})
-                print("[bench] %s persistent%s%s: %.3f ms/start, %.3f ms/graph replay, %.1f GB/s effective, T %.2f GiB" %
-                      (label, " fused" if fused else "", "" if st.dense_t else " slots of M", ms_start, ms_graph,
-                       rows[-1]["effective_GBs"], st.temp_bytes / 2 ** 30),
-                      file=sys.stderr, flush=True)
-            finally:
-                tuna.tuna_plan_free(plan)
-        return rows
-
-    per_radix = run_sweep(bool(args.fused), args.exact_t)
-    # the fused rounds (one kernel per phase, 2 x payload instead of 6 x) as a second table, and both
-    # with T in the paper's B slots of M bytes instead of exact size
-    fused_table = slots_table = fused_slots_table = None
-    if not args.fused and args.exact_t and not args.no_fused_table:
-        fused_table = run_sweep(True, args.exact_t)
-        slots_table = run_sweep(False, 0)
-        fused_slots_table = run_sweep(True, 0)
+    main_opts = dict(mode=MODES[args.mode], t_layout=args.t_layout, staggered=int(args.staggered), block_count=args.block_count)
+    per_radix = res.sweep(sweep, **main_opts)
+    main_is_staged = not per_radix[0]["one_kernel_phases"]
+    three_stage = slots = None
+    if not args.no_three_stage_table and not main_is_staged:
+        three_stage = res.sweep(sweep, **dict(main_opts, mode=MODES["staged"]))
+    if args.slots_table:
+        slots = {"note": "T as the paper's B slots of M bytes per rank instead of exact size",
+                 "per_radix": res.sweep(sweep, **dict(main_opts, t_layout=0))}
+        if three_stage is not None:
+            slots["three_stage_per_radix"] = res.sweep(sweep, **dict(main_opts, mode=MODES["staged"], t_layout=0))
     persistent = None
     if not args.no_persistent_table:
         persistent = {"note": "tuna_alltoallv_init once, then tuna_start per step: payload kernels only",
-                      "staged": run_persistent(bool(args.fused), args.exact_t)}
-        if not args.fused and args.exact_t and not args.no_fused_table:
-            persistent["fused"] = run_persistent(True, args.exact_t)
-            persistent["staged_slots_of_M"] = run_persistent(False, exact_t=0)
-            persistent["fused_slots_of_M"] = run_persistent(True, exact_t=0)
+                      "default": [res.time_plan(rl, rg, res.opts(**main_opts), label) for label, rl, rg in sweep]}
+        if three_stage is not None:
+            persistent["three_stage"] = [res.time_plan(rl, rg, res.opts(**dict(main_opts, mode=MODES["staged"])), label)
+                                         for label, rl, rg in sweep]
     best = max(per_radix, key=lambda r: r["effective_GBs"])
-    # Roofline of the dominant kernel: the copy kernel with the largest total time over ALL launches
-    # of the timed sweep (every radix), so that its average launch duration is the one a
-    # `rocprofv3 --kernel-trace --stats` run of this same command reports for that kernel.
-    roofline = None
-    tot = {}
-    for r in per_radix:
-        for name, v in r["kernels"].items():
-            t = tot.setdefault(name, [0.0, 0, 0.0])
-            n = v["launches_per_step"] * args.steps
-            t[0] += v["avg_ms"] * n
-            t[1] += n
-            t[2] += v["alg_bytes_per_launch"] * n
-    if tot:
-        gran = per_radix[0]["granularity"]
-        dom = max(tot.items(), key=lambda kv: kv[1][0])
-        name, (ms, n, alg) = dom
-        exact_used = bool(per_radix[0]["exact_size_t"])
-        et = "true" if exact_used else "false"
-        kname = {"pack": "tuna::k_copy<0, %d, %s>" % (gran, et), "exchange": "tuna::k_copy<1, 16, false>",
-                 "unpack": "tuna::k_copy<2, %d, %s>" % (min(gran, 16), et), "fused": "tuna::k_copy<3, %d, %s>" % (gran, et)}[name]
-        default_run = (args.config == 4 and P == 4096 and not args.radices)
-        traffic = MEASURED_TRAFFIC_CONFIG4[exact_used].get(name) if default_run else None
-        achieved = alg / (ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": kname, "stage": name, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                    "avg_launch_ms": ms / n, "launches": n, "alg_bytes_per_launch": alg / n,
-                    "frac_of_plain_copy": (achieved / copy_ceiling["GBs"]) if copy_ceiling else None,
-                    "all_stages_GBs": {k: v[2] / (v[0] * 1e-3) / 1e9 for k, v in tot.items()}}
+    default_run = (args.config == 4 and P == 4096 and not args.radices and not named and not args.uniform_max_bytes
+                   and args.mode == "auto" and args.t_layout == 2 and not args.staggered and not args.block_count)
+    traffic = load_traffic(args.traffic_file) if default_run else None
+    roofline = roofline_of(per_radix, args.steps, traffic, copy_ceiling)
+    three_stage_roofline = roofline_of(three_stage, args.steps, traffic, copy_ceiling) if three_stage else None
+
+    # the selector's view of the same problem (built-in constants: nothing is calibrated inside the benchmark)
+    rc, ch = tuna.tuna_select(P, rpn, Btot, res.max_block, per_radix[0]["granularity"])
+    selector = None if rc != 0 else {"local_radix": ch.local_radix, "global_radix": ch.global_radix,
+                                     "mode": "one-kernel phases" if ch.mode == 2 else "three stages",
+                                     "t_layout": "exact size" if ch.t_layout == 1 else "slots of M",
+                                     "predicted_ms": ch.predicted_ms, "calibrated": bool(ch.calibrated)}
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
-        cpu_baseline = time_oracle(lay, send, args.cpu_seconds)
+        cpu_baseline = time_oracle(res.lay, res.send, args.cpu_seconds)
         # context, not a target: the GPU call at its best radix against the oracle's plain transpose
         cpu_baseline["gpu_over_cpu"] = {"one_core": best["effective_GBs"] / cpu_baseline["value"],
                                         "all_cores": best["effective_GBs"] / cpu_baseline["all_cores"]["value"]}
+    res.close()
 
     also = None
-    if args.secondary and not args.no_secondary:
-        also = {"config 3: " + wl.CONFIGS[3].description: quick_sweep(tuna, 3, args.steps, args.warmup)}
+    if not args.no_secondary and default_run:
+        also = secondary(tuna, wl, np, args, copy_ceiling)
 
     out = {
         "metric": "effective Alltoallv GB/s and % of HBM peak vs radix, at P=1024/4096",
-        "metric_note": "value = payload bytes / time per tuna_alltoallv call (three-stage phases) at the best radix of "
-                       "the P=4096 workload; per_radix has every radix, roofline the copy kernels' share of the HBM "
-                       "peak, also_measured (with --secondary) the P=1024 hierarchical workload",
+        "metric_note": "value = payload bytes / time per immediate call with the library's default options at the best radix "
+                       "of the P=4096 workload; per_radix has every radix, three_stage the same sweep with pack / exchange / "
+                       "unpack as three kernels, roofline the dominant payload kernel's share of the HBM peak, also_measured "
+                       "the P=1024 hierarchical workload and short rows for the other schedules",
         "value": best["effective_GBs"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": best["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u8", "data": "synthetic",
-        "config": {"workload": ("uniform [0, %d] bytes in %d-byte elements, P=%d flat" % (args.uniform_max_bytes, args.element_bytes, P))
-                               if args.uniform_max_bytes else "config %d: %s" % (args.config, cfg.description), "P": P,
-                   "payload_bytes": Btot, "best_radix": best["radix"], "fused": bool(args.fused),
-                   "exact_size_t": bool(per_radix[0]["exact_size_t"]), "t_layout_option": args.exact_t, "block_count": args.block_count,
-                   "ranks_per_node": rpn},
-        "roofline": roofline, "cpu_baseline": cpu_baseline, "copy_ceiling": copy_ceiling, "per_radix": per_radix, "persistent": persistent,
-        "also_measured": also,
-        "fused_rounds": None if fused_table is None else {
-            "note": "same workload with TUNA_OPT_FUSED: one kernel per digit phase moves S/T to R/T directly",
-            "best_effective_GBs": max(r["effective_GBs"] for r in fused_table), "per_radix": fused_table},
-        "slots_of_M": None if slots_table is None else {
-            "note": "same workload with TUNA_OPT_DENSE_T = 0: T as the paper's B slots of M bytes per rank instead of exact size",
-            "per_radix": slots_table, "fused_per_radix": fused_slots_table},
+        "config": {"workload": wname, "P": P, "payload_bytes": Btot, "best_radix": best["radix"], "mode": args.mode,
+                   "one_kernel_phases": bool(best["one_kernel_phases"]), "exact_size_t": bool(best["exact_size_t"]),
+                   "t_layout_option": args.t_layout, "staggered": bool(args.staggered), "block_count": args.block_count,
+                   "ranks_per_node": rpn, "library_build_id": tuna.tuna_build_id()},
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "copy_ceiling": copy_ceiling, "per_radix": per_radix,
+        "three_stage": None if three_stage is None else {
+            "note": "same workload, pack -> exchange -> unpack as three kernels per digit phase (TUNA_MODE_STAGED)",
+            "best_effective_GBs": max(r["effective_GBs"] for r in three_stage), "roofline": three_stage_roofline,
+            "per_radix": three_stage},
+        "slots_of_M": slots, "persistent": persistent, "selector": selector, "also_measured": also,
     }
     print(json.dumps(out))
 
 
-def quick_sweep(tuna, cfg_id, steps, warmup):
-    """Wall-clock sweep of another configuration: immediate calls with three-stage phases and with
-    fused rounds, and starts of a persistent plan with fused rounds."""
-    import torch
+def diagonal_counts(P):
+    import numpy as np
 
     import workloads as wl
-    cfg = wl.CONFIGS[cfg_id]
-    lay = wl.make_layout(wl.make_counts(cfg_id))
-    dev = "cuda:0"
-    send = wl.payload_position_hash_torch(cfg.seed, lay.send_bytes, dev)
-    recv = torch.empty(lay.recv_bytes, dtype=torch.uint8, device=dev)
-    d = [torch.from_numpy(a).to(dev) for a in (lay.sendcounts, lay.sdispls, lay.recvcounts, lay.rdispls)]
-    rows = []
-    for kind, rpn, rl, rg in sweep_of(cfg_id, cfg.P):
-        row = {"radix": "r_l=%d,r_g=%d" % (rl, rg) if kind == "hier" else "r=%d" % rl}
-        for mode, fused in (("staged", 0), ("fused", 1)):
-            tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, fused)
-            try:
-                def call():
-                    if kind == "hier":
-                        rc = tuna.tuna_alltoallv_hier(send, d[0], d[1], recv, d[2], d[3], cfg.P, rpn, rl, rg)
-                    else:
-                        rc = tuna.tuna_alltoallv(send, d[0], d[1], recv, d[2], d[3], cfg.P, rl, rpn)
-                    if rc != 0:
-                        raise RuntimeError(tuna.tuna_strerror(rc))
-                for _ in range(warmup):
-                    call()
-                torch.cuda.synchronize()
-                t1 = time.perf_counter()
-                for _ in range(steps):
-                    call()
-                torch.cuda.synchronize()
-                ms = (time.perf_counter() - t1) * 1e3 / steps
-                row[mode + "_ms"] = ms
-                row[mode + "_GBs"] = lay.payload_bytes / (ms * 1e-3) / 1e9
-                if fused:
-                    rc, plan = tuna.tuna_alltoallv_init(send, d[0], d[1], recv, d[2], d[3], cfg.P, rpn, rl, rg)
-                    if rc != 0:
-                        raise RuntimeError(tuna.tuna_strerror(rc))
-                    try:
-                        for _ in range(warmup):
-                            tuna.tuna_start(plan)
-                        torch.cuda.synchronize()
-                        t1 = time.perf_counter()
-                        for _ in range(steps):
-                            tuna.tuna_start(plan)
-                        torch.cuda.synchronize()
-                        ms = (time.perf_counter() - t1) * 1e3 / steps
-                    finally:
-                        tuna.tuna_plan_free(plan)
-                    row["persistent_fused_ms"] = ms
-                    row["persistent_fused_GBs"] = lay.payload_bytes / (ms * 1e-3) / 1e9
-            finally:
-                tuna.tuna_set_option(tuna.TUNA_OPT_FUSED, 0)
-        rows.append(row)
-        print("[bench] config %d %s: staged %.3f ms (%.0f GB/s), fused %.3f ms, persistent fused %.3f ms" %
-              (cfg_id, row["radix"], row["staged_ms"], row["staged_GBs"], row["fused_ms"], row["persistent_fused_ms"]),
-              file=sys.stderr, flush=True)
-    return {"P": cfg.P, "payload_bytes": lay.payload_bytes, "per_radix": rows}
+    counts = wl.counts_uniform_bytes(P, 64, 2000)
+    rng = np.random.default_rng(64)
+    for p in range(P):
+        counts[p, p] = (64 << 20) + 4 * int(rng.integers(-25000, 25000))
+    return (counts // 4 * 4).astype(np.int32)
+
+
+def secondary(tuna, wl, np, args, copy_ceiling):
+    """The P = 1024 hierarchical configuration with its own roofline entry, and short rows (few steps) for
+    the schedules and workloads the main sweep does not touch."""
+    steps, warmup = args.steps, args.warmup
+    out = {}
+    cfg = wl.CONFIGS[3]
+    res = Resident(tuna, wl.make_counts(3), cfg.seed, cfg.ranks_per_node, steps, warmup)
+    sweep = radices_of(cfg, cfg.P) + [("r_l=16,r_g=64", 16, 64)]
+    rows = res.sweep(sweep)
+    staged = res.sweep(sweep, mode=MODES["staged"])
+    plans = [res.time_plan(rl, rg, res.opts(), label) for label, rl, rg in sweep]
+    best = max(rows, key=lambda r: r["effective_GBs"])
+    out["config3"] = {"workload": "config 3: " + cfg.description, "P": cfg.P, "payload_bytes": res.lay.payload_bytes,
+                      "value": best["effective_GBs"], "unit": "GB/s", "best_radix": best["radix"], "ms_per_step": best["ms_per_step"],
+                      "roofline": roofline_of(rows, steps, None, copy_ceiling), "per_radix": rows,
+                      "three_stage": {"roofline": roofline_of(staged, steps, None, copy_ceiling), "per_radix": staged},
+                      "persistent": plans}
+    # staggered inter-node schedule and batches of rounds on the same problem (Algorithm "Staggered TuNA_l^g";
+    # block_count of Algorithm "Coalesced TuNA_l^g")
+    short = Resident.__new__(Resident)
+    short.__dict__.update(res.__dict__)
+    short.steps, short.warmup = max(3, steps // 4), 2
+    out["config3"]["staggered"] = short.sweep([("r_l=4 staggered", 4, 64)], staggered=1)
+    out["config3"]["block_count"] = [dict(short.time_calls(4, 64, short.opts(block_count=k), "r_l=4,r_g=64 block_count=%d" % k), block_count=k)
+                                     for k in (8, 1)]
+    res.close()
+
+    def short_rows(name, counts, seed, rpn, sweep, note, **opt):
+        r = Resident(tuna, counts, seed, rpn, max(3, steps // 4), 2)
+        rows = r.sweep(sweep, **opt)
+        plans = [r.time_plan(rl, rg, r.opts(**opt), label) for label, rl, rg in sweep[-1:]]
+        out[name] = {"workload": note, "P": r.P, "payload_bytes": r.lay.payload_bytes, "per_radix": rows, "persistent": plans}
+        r.close()
+
+    P = 8192
+    short_rows("fft_n1", wl.counts_fft_n1(P), 81, 0, [("r=90", 90, 90), ("r=%d" % P, P, P)],
+               "FFT count pattern N1 at P=8192: only the ranks below ceil(0.625 P) send, 64 B to each of the first ceil(0.78125 P) ranks")
+    short_rows("fft_n2", wl.counts_fft_n2(P), 82, 0, [("r=%d" % P, P, P)],
+               "FFT count pattern N2 at P=8192: 512 B per block, 128 B from the last rank")
+    short_rows("diagonal", diagonal_counts(64), 83, 0, [("r=64", 64, 64)],
+               "64 MiB kept by every rank for itself (P=64), small blocks elsewhere: own_blocks_ms_per_step is the copy of 4 GiB")
+    d = out["diagonal"]
+    diag_bytes = 64 * (64 << 20)
+    d["own_block_copy_GBs"] = [2 * diag_bytes / (r["own_blocks_ms_per_step"] * 1e-3) / 1e9 for r in d["per_radix"]]
+    short_rows("small_blocks", wl.counts_uniform_elements(2048, 99, 2, 8), 84, 0, [("r=2", 2, 2), ("r=2048", 2048, 2048)],
+               "the paper's uniform [0, 16] bytes at P=2048 (Section \"Performance analysis of TuNA\": small S)")
+    short_rows("config1", wl.make_counts(1), wl.CONFIGS[1].seed, 0, [("r=2", 2, 2), ("r=16", 16, 16)],
+               "config 1: " + wl.CONFIGS[1].description)
+    return out
 
 
 def time_oracle(lay, send_dev, target_seconds):
@@ -472,7 +522,7 @@ def time_oracle(lay, send_dev, target_seconds):
     return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle", "cpu_model": model,
             "sample": "receive side of the first %d of %d ranks (%.3f GiB of payload), one thread, %.2f s per pass, "
                       "mean of %d passes; host has %d usable cores" % (n, P, nbytes / 2**30, dt, reps, cores),
-            "all_cores": {"value": nbytes / dt_par / 1e9, "unit": "GB/s", "threads": len(threads),
+            "all_cores": {"value": nbytes / dt_par / 1e9, "unit": "GB/s", "cores": len(threads), "threads": len(threads),
                           "note": "the same oracle called from one thread per slice of receiver ranks"}}
 
 

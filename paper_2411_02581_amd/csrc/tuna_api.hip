@@ -40,7 +40,38 @@ struct DevicePlan {
     bool complete = false;               // known to have finished (a later call synchronised)
     std::vector<int32_t*> d_zt;
     int32_t* d_hm1 = nullptr;            // [P]: hops - 1 of every slot index (how often the block is stored into T)
+    unsigned long long* d_mask = nullptr; // [P]: phases in which the block with a slot index moves (move_mask)
+    // exact-size T: per phase the T-bound segments grouped by class (see ExactT), on the device and,
+    // for the launch shapes, the classes on the host
+    std::vector<int32_t*> d_tord, d_tcls;
+    std::vector<std::vector<int32_t>> tcls;   // per phase: {class id, first entry of tord, entries} per class
+    bool borrowed = false;               // the device memory belongs to someone else (static scratch)
 };
+
+// The T-bound segments of every phase grouped by the class they are stored into, in message order
+// within a class: tord[phase] lists segment indices, tcls[phase] holds {class id, start, count} triples.
+void build_class_tables(const PlanHost& pl, std::vector<std::vector<int32_t>>& tord, std::vector<std::vector<int32_t>>& tcls) {
+    const size_t nph = pl.phases.size();
+    tord.assign(nph, {}); tcls.assign(nph, {});
+    for (size_t i = 0; i < nph; ++i) {
+        PhaseScalars ps = phase_scalars(pl.phases[i]);
+        std::vector<std::vector<int32_t>> by_next(nph);       // segment indices by the phase of the next move
+        for (int e = 0; e < pl.P; ++e) {
+            SegInfo si{};
+            int pos = 0;
+            if (slot_entry(pl.sc, ps, e, &si, &pos) && si.nxt_phase >= 0 && si.nxt_phase < (int)nph)
+                by_next[si.nxt_phase].push_back(pos);
+        }
+        for (size_t y = i + 1; y < nph; ++y) {
+            if (by_next[y].empty()) continue;
+            std::sort(by_next[y].begin(), by_next[y].end());
+            tcls[i].push_back(class_id((int)i, (int)y, (int)nph));
+            tcls[i].push_back((int32_t)tord[i].size());
+            tcls[i].push_back((int32_t)by_next[y].size());
+            tord[i].insert(tord[i].end(), by_next[y].begin(), by_next[y].end());
+        }
+    }
+}
 
 // Where a call's validation pass and per-phase totals are written and read back: the library's own
 // small allocations, or a part of the static scratch of the entry point that allocates nothing.
@@ -203,27 +234,13 @@ MetaBuffers carve_meta(Carver& cv, int P) {
     return m;
 }
 
-// prefix-only layout of the T-bound blocks of one phase (exact-size T)
-size_t tbound_layout_bytes_for(int P) {
-    const size_t ld = (size_t)P + 1;
-    return align_up((size_t)P * ld * 4) + align_up((size_t)P * 4) + align_up(((size_t)P + 1) * 8);
-}
-
-void carve_tbound_layout(Carver& cv, int P, LayoutDev& L) {
-    L.ld = P + 1;
-    L.pre = cv.take<int>((size_t)P * L.ld);
-    L.tot = cv.take<int>(P);
-    L.rank_base = cv.take<long long>(P + 1);
-    L.unit_base = nullptr; L.n_units = nullptr; L.units = nullptr;
-}
-
-// metadata of exact-size T: the T-bound prefix in message order (one for the phase being run, or
-// one per phase when a plan keeps them), and per phase the same offsets by slot index, the ranks'
-// bases and the arena's end
+// metadata of exact-size T: per class the ranks' first chunks and part sizes and the class's place in
+// T, per phase the blocks' offsets by slot index, and the same offsets in message order (one array for
+// the phase being run, or one per phase when a plan keeps them)
 size_t exact_t_meta_bytes_for(const PlanHost& pl, bool keep_all_phases) {
-    const size_t nph = pl.phases.size(), P = (size_t)pl.P;
-    return (keep_all_phases ? nph : 1) * tbound_layout_bytes_for(pl.P) + align_up(nph * P * P * 4) +
-           align_up(nph * P * 8) + align_up(nph * 8);
+    const size_t nph = pl.phases.size(), P = (size_t)pl.P, ncls = (size_t)class_count((int)nph);
+    return (keep_all_phases ? nph : 1) * align_up(P * (P + 1) * 4) + align_up(nph * P * P * 4) +
+           align_up(ncls * P * 8) + align_up(ncls * P * 4) + align_up(ncls * 8);
 }
 
 struct Prepared;
@@ -240,6 +257,7 @@ struct DataSizes {
 
 DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long total_chunks, bool fused,
                          bool staggered = false, bool dense = false, unsigned long long t_chunks = 0) {
+    // t_chunks: exact-size T as the host laid it out (colour_classes)
     DataSizes d{};
     const bool any_phase = !pl.phases.empty() && total_chunks > 0;
     // every rank's region of a staging buffer (and of an arena of T) is rounded up to a 128-byte line
@@ -251,9 +269,9 @@ DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long tot
     d.slots = pl.slots;
     d.slot_bytes = (M + 127) / 128 * 128;     // whole 128-byte lines per slot
     d.t_bytes = any_phase ? (size_t)pl.P * (size_t)d.slots * (size_t)d.slot_bytes : 0;
-    if (dense) {       // exact size: what is stored into T over all phases, every phase's arena rounded up to 256
+    if (dense) {       // exact size: what waits in T at one time
         d.slots = 0;
-        d.t_bytes = any_phase ? (size_t)t_chunks * 16 + pl.phases.size() * (kAlign + rank_pad * 16) : 0;
+        d.t_bytes = any_phase ? (size_t)t_chunks * 16 : 0;
     }
     // pl.slots already counts both copies of T when the plan is a fused one
     d.total = 2 * align_up(d.unit_cap * sizeof(int4)) + (fused ? 0 : 2 * align_up(d.stage_chunks * 16)) +
@@ -262,10 +280,16 @@ DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long tot
 }
 
 void free_device_plan(DevicePlan& dp) {
-    for (auto* p : dp.d_seg_mem) (void)hipFree(p);
-    for (auto* p : dp.d_zt) (void)hipFree(p);
-    if (dp.d_hm1) (void)hipFree(dp.d_hm1);
-    dp.d_seg_mem.clear(); dp.d_zt.clear(); dp.d_seg.clear(); dp.d_hm1 = nullptr;
+    if (!dp.borrowed) {
+        for (auto* p : dp.d_seg_mem) (void)hipFree(p);
+        for (auto* p : dp.d_zt) (void)hipFree(p);
+        for (auto* p : dp.d_tord) (void)hipFree(p);
+        for (auto* p : dp.d_tcls) (void)hipFree(p);
+        if (dp.d_hm1) (void)hipFree(dp.d_hm1);
+        if (dp.d_mask) (void)hipFree(dp.d_mask);
+    }
+    dp.d_seg_mem.clear(); dp.d_zt.clear(); dp.d_seg.clear(); dp.d_tord.clear(); dp.d_tcls.clear();
+    dp.d_hm1 = nullptr; dp.d_mask = nullptr;
 }
 
 // Cached schedule of (P, Q, r_l, r_g, fused).  The host keeps scalars only; the per-phase tables are
@@ -300,19 +324,34 @@ int get_plan(int P, int Q, int rl, int rg, bool fused, hipStream_t s, DevicePlan
             const size_t stride = align_up((size_t)ph.nseg * 4) / 4;
             int32_t* dm = nullptr;
             int32_t* dz = nullptr;
-            HIPCHK(hipMalloc((void**)&dm, 6 * stride * 4 + kAlign));
+            HIPCHK(hipMalloc((void**)&dm, 8 * stride * 4 + kAlign));
             dp.d_seg_mem.push_back(dm);
             HIPCHK(hipMalloc((void**)&dz, align_up((size_t)P * 4)));
             dp.d_zt.push_back(dz);
             hipLaunchKernelGGL(k_build_phase_table, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, dp.host.sc,
                                phase_scalars(ph), dm, dm + stride, dm + 2 * stride, dm + 3 * stride, dm + 4 * stride,
-                               dm + 5 * stride, dz);
+                               dm + 5 * stride, dm + 6 * stride, dm + 7 * stride, dz);
             HIPCHK(hipGetLastError());
-            dp.d_seg.push_back(SegDev{dm, dm + stride, dm + 2 * stride, dm + 3 * stride, dm + 4 * stride, dm + 5 * stride});
+            dp.d_seg.push_back(SegDev{dm, dm + stride, dm + 2 * stride, dm + 3 * stride, dm + 4 * stride, dm + 5 * stride,
+                                      dm + 6 * stride, dm + 7 * stride});
         }
         HIPCHK(hipMalloc((void**)&dp.d_hm1, align_up((size_t)P * 4)));
-        hipLaunchKernelGGL(k_build_hops, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, dp.host.sc, dp.d_hm1);
+        HIPCHK(hipMalloc((void**)&dp.d_mask, align_up((size_t)P * 8)));
+        hipLaunchKernelGGL(k_build_hops, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, dp.host.sc, dp.d_hm1, dp.d_mask);
         HIPCHK(hipGetLastError());
+        // the class tables of exact-size T come from the host (copied before the call returns: the
+        // vectors are temporaries)
+        std::vector<std::vector<int32_t>> tord;
+        build_class_tables(dp.host, tord, dp.tcls);
+        for (size_t i = 0; i < dp.host.phases.size(); ++i) {
+            int32_t *d_o = nullptr, *d_c = nullptr;
+            HIPCHK(hipMalloc((void**)&d_o, align_up(tord[i].size() * 4 + 4)));
+            dp.d_tord.push_back(d_o);
+            HIPCHK(hipMalloc((void**)&d_c, align_up(dp.tcls[i].size() * 4 + 4)));
+            dp.d_tcls.push_back(d_c);
+            if (!tord[i].empty()) HIPCHK(hipMemcpy(d_o, tord[i].data(), tord[i].size() * 4, hipMemcpyHostToDevice));
+            if (!dp.tcls[i].empty()) HIPCHK(hipMemcpy(d_c, dp.tcls[i].data(), dp.tcls[i].size() * 4, hipMemcpyHostToDevice));
+        }
         dp.built_on = s;
         guard.dp = nullptr;
         it = sh.plans.emplace(key, std::move(dp)).first;
@@ -412,14 +451,10 @@ int phase_metadata(const PhaseLayoutArgs& a, hipStream_t s, const ExactT& x) {
     }
     hipLaunchKernelGGL(k_phase_layout, dim3(a.P), dim3(kScanThreads), 0, s, a);
     HIPCHK(hipGetLastError());
-    // layouts to scan: receive side, then the send side and / or the T-bound blocks where wanted
-    const LayoutDev* list[3] = {&a.Lr, &a.Lr, &a.Lr};
-    int nl = 1;
-    if (a.want_send) list[nl++] = &a.Ls;
-    const int tbound_at = a.want_tbound ? nl : -1;
-    if (a.want_tbound) list[nl++] = &a.Lt;
-    hipLaunchKernelGGL(k_layout_base, dim3(nl), dim3(kScanThreads), 0, s, a.P, *list[0], *list[1], *list[2],
-                       a.phase_chunks, a.want_send ? 1 : 0, tbound_at, x, a.rank_bytes, a.phase_bytes, a.phase_units);
+    // layouts to scan: receive side, the send side where wanted, then the classes of exact-size T
+    const int nl = a.want_send ? 2 : 1;
+    hipLaunchKernelGGL(k_layout_base, dim3(nl + (a.want_tbound ? x.ncls : 0)), dim3(kScanThreads), 0, s, a.P, a.Lr, a.Ls, nl,
+                       a.phase_chunks, a.want_send ? 1 : 0, x, a.rank_bytes, a.phase_bytes, a.phase_units);
     HIPCHK(hipGetLastError());
     const int lds_ints = a.nseg + 1 <= kUnitsLdsMaxInts ? a.nseg + 1 : 0;
     hipLaunchKernelGGL(k_layout_units, dim3(a.P, a.want_send ? 2 : 1), dim3(256), (size_t)lds_ints * 4, s, a.nseg, a.Lr,
@@ -443,13 +478,23 @@ int run_validate(const StatusBufs& sb, const int32_t* sendcounts, const int32_t*
     // every field of the status block a call reads is written by the call's own kernels: no clearing
     const size_t t = (size_t)((P + kValTile - 1) / kValTile);
     const unsigned vgrid = (unsigned)(t * t < (size_t)sb.num_cus * 8 ? t * t : (size_t)sb.num_cus * 8);
-    hipLaunchKernelGGL(k_validate, dim3(vgrid), dim3(kValTile, 4), 0, s, sendcounts, recvcounts, sdispls, rdispls, P,
-                       sb.d_vpart, exact_t_for ? exact_t_for->d_hm1 : nullptr, exact_t_for ? exact_t_for->host.Q : 1,
-                       exact_t_for ? exact_t_for->host.N : 1);
+    // with a schedule that has T: also the size of every class of exact-size T (summed into the status block)
+    const int nph = exact_t_for ? (int)exact_t_for->host.phases.size() : 0;
+    const int ncls = class_count(nph);
+    if (ncls > 0) {
+        hipLaunchKernelGGL(k_zero64, dim3((unsigned)((ncls + 255) / 256)), dim3(256), 0, s, sb.d_status->cls_chunks, ncls);
+        HIPCHK(hipGetLastError());
+    }
+    hipLaunchKernelGGL(k_validate, dim3(vgrid), dim3(kValTile, 4), (size_t)ncls * 8, s, sendcounts, recvcounts, sdispls,
+                       rdispls, P, sb.d_vpart, exact_t_for ? exact_t_for->d_hm1 : nullptr,
+                       exact_t_for ? exact_t_for->host.Q : 1, exact_t_for ? exact_t_for->host.N : 1,
+                       exact_t_for ? exact_t_for->d_mask : nullptr, nph, sb.d_status->cls_chunks);
     HIPCHK(hipGetLastError());
     hipLaunchKernelGGL(k_validate_finish, dim3(1), dim3(256), 0, s, sb.d_vpart, (int)vgrid, sb.d_status);
     HIPCHK(hipGetLastError());
     HIPCHK(hipMemcpyAsync(sb.h_status, sb.d_status, 64, hipMemcpyDeviceToHost, s));
+    if (ncls > 0)
+        HIPCHK(hipMemcpyAsync(sb.h_status->cls_chunks, sb.d_status->cls_chunks, (size_t)ncls * 8, hipMemcpyDeviceToHost, s));
     HIPCHK(hipStreamSynchronize(s));
     return TUNA_OK;
 }
@@ -480,8 +525,11 @@ struct Prepared {
     // the per-phase position tables; the arenas are assigned on the device, phase by phase
     bool exact_t = false;               // T in exact size, and the schedule has T at all
     bool exact_kernels = false;         // T in exact size was asked for
-    std::vector<LayoutDev> Lt;
+    std::vector<int*> tpre;             // per phase: the blocks' offsets in message order (one array shared, or one each)
     ExactT x{};
+    long long* d_cbase = nullptr;       // [classes]: where the host placed every class in T
+    std::vector<long long> cbase;       // the same on the host
+    unsigned long long t_chunks = 0;    // chunks of exact-size T as laid out
     HopDev hop{};                       // one-kernel phases of a one-pass call: the resolved addresses of the phase being run
     // the ranks' own blocks: moved by the copy engine when blocks can be large (see launch_self_copy)
     bool self_engine = false;
@@ -493,23 +541,102 @@ struct Prepared {
 };
 
 void carve_exact_t(Carver& cv, const PlanHost& pl, bool keep_all_phases, Prepared& pr) {
-    const size_t nph = pl.phases.size(), P = (size_t)pl.P;
-    pr.Lt.resize(nph);
-    for (size_t i = 0; i < nph; ++i) {
-        if (i == 0 || keep_all_phases) carve_tbound_layout(cv, pl.P, pr.Lt[i]);
-        else pr.Lt[i] = pr.Lt[0];
-    }
+    const size_t nph = pl.phases.size(), P = (size_t)pl.P, ncls = (size_t)class_count((int)nph);
+    pr.tpre.assign(nph, nullptr);
+    for (size_t i = 0; i < nph; ++i)
+        pr.tpre[i] = (i == 0 || keep_all_phases) ? cv.take<int>(P * (P + 1)) : pr.tpre[0];
     pr.x.tpos = cv.take<int>(nph * P * P);
-    pr.x.tbase = cv.take<long long>(nph * P);
-    pr.x.arena_end = cv.take<long long>(nph);
+    pr.x.tbase = cv.take<long long>(ncls * P);
+    pr.x.csub = cv.take<int>(ncls * P);
+    pr.d_cbase = cv.take<long long>(ncls);
+    pr.x.cbase = pr.d_cbase;
+}
+
+// The classes' places in T go to the device through the pinned mirror of the status block (its class
+// sums have been read by now); the copy is ordered on the stream before the kernels that read it.
+int upload_cbase(const Prepared& pr, hipStream_t s) {
+    const size_t ncls = pr.cbase.size();
+    if (!pr.exact_t || !ncls) return TUNA_OK;
+    long long* stage = reinterpret_cast<long long*>(pr.sb.h_status->cls_chunks);
+    for (size_t k = 0; k < ncls; ++k) stage[k] = pr.cbase[k];
+    HIPCHK(hipMemcpyAsync(pr.d_cbase, stage, ncls * 8, hipMemcpyHostToDevice, s));
+    return TUNA_OK;
 }
 
 // the exact-size T arguments of phase i
 ExactT exact_t_of(const Prepared& pr, size_t i) {
     ExactT x = pr.x;
     if (!pr.exact_t) return ExactT{};
-    x.tpre = pr.Lt[i].pre; x.ld = pr.Lt[i].ld; x.phase = (int)i;
+    x.tpre = pr.tpre[i]; x.ld = pr.P + 1; x.phase = (int)i;
+    x.tord = pr.dp->d_tord[i]; x.tcls = pr.dp->d_tcls[i]; x.ncls = (int)(pr.dp->tcls[i].size() / 3);
     return x;
+}
+
+bool phase_is_one_kernel(const Prepared& pr, const PhaseHost& ph) {
+    return pr.fused || (pr.staggered && ph.dim == 1);
+}
+
+// Where the classes of exact-size T lie.  Class (f, y) holds the blocks stored when they arrive in
+// phase f and forwarded in phase y; it needs its chunks (summed by the validation pass) plus a 128-byte
+// line of rounding per rank, and it is alive from the kernel that stores it to the kernel that reads it:
+// with three stages from the unpack of phase f to the pack of phase y, with one-kernel phases from the
+// kernel of phase f to the kernel of phase y (which reads it while it stores the classes (y, .), so those
+// must lie elsewhere).  Every class is placed at the lowest offset where it overlaps no class alive at
+// the same time (first fit).  Returns the chunks of T; cbase[class] = first chunk.
+unsigned long long colour_classes(const PlanHost& pl, bool fused, bool staggered, const unsigned long long* cls_chunks,
+                                  std::vector<long long>& cbase) {
+    const int nph = (int)pl.phases.size();
+    struct Item { int cid, start, end; unsigned long long cap; long long off; };
+    std::vector<Item> items;
+    for (int f = 0; f < nph; ++f) {
+        const bool one_kernel = fused || (staggered && pl.phases[f].dim == 1);
+        for (int y = f + 1; y < nph; ++y) {
+            const int cid = class_id(f, y, nph);
+            if (!cls_chunks[cid]) continue;
+            const unsigned long long cap = (cls_chunks[cid] + (unsigned long long)pl.P * kRankAlignChunks + 15) / 16 * 16;
+            items.push_back(Item{cid, 2 * f + (one_kernel ? 0 : 1), 2 * y, cap, 0});
+        }
+    }
+    // First fit depends on the order of placement and no single order is best for every schedule: four
+    // are tried (by first use, by size, by length of life, by size times length of life) and the
+    // tightest result is kept (at most 12 % above the bytes alive at one time on the schedules measured).
+    cbase.assign((size_t)class_count(nph), 0);
+    unsigned long long best_extent = ~0ull;
+    for (int order = 0; order < 4; ++order) {
+        std::vector<Item> it = items;
+        std::stable_sort(it.begin(), it.end(), [order](const Item& a, const Item& b) {
+            const long long la = a.end - a.start + 1, lb = b.end - b.start + 1;
+            switch (order) {
+                case 0: return a.start != b.start ? a.start < b.start : a.cap > b.cap;
+                case 1: return a.cap != b.cap ? a.cap > b.cap : a.start < b.start;
+                case 2: return la != lb ? la > lb : a.cap > b.cap;
+                default: {
+                    const unsigned long long xa = a.cap * (unsigned long long)la, xb = b.cap * (unsigned long long)lb;
+                    return xa != xb ? xa > xb : a.start < b.start;
+                }
+            }
+        });
+        unsigned long long extent = 0;
+        for (size_t k = 0; k < it.size(); ++k) {
+            std::vector<std::pair<long long, long long>> busy;   // ranges of the classes alive together with this one
+            for (size_t m = 0; m < k; ++m)
+                if (it[m].end >= it[k].start && it[m].start <= it[k].end)
+                    busy.emplace_back(it[m].off, it[m].off + (long long)it[m].cap);
+            std::sort(busy.begin(), busy.end());
+            long long off = 0;
+            for (const auto& b : busy) {
+                if (off + (long long)it[k].cap <= b.first) break;
+                off = std::max(off, b.second);
+            }
+            it[k].off = off;
+            extent = std::max(extent, (unsigned long long)off + it[k].cap);
+        }
+        if (extent < best_extent) {
+            best_extent = extent;
+            for (const Item& x : it) cbase[(size_t)x.cid] = x.off;
+        }
+    }
+    return items.empty() ? 0 : best_extent;
 }
 
 // T in exact size or in the paper's slots of M bytes.  Left to the library (option value 2), slots
@@ -518,20 +645,16 @@ ExactT exact_t_of(const Prepared& pr, size_t i) {
 // from the validation pass: exact size is taken when it is not the larger one, or when it still fits
 // into half of the device memory that is free (it is the faster layout: dense writes and reads);
 // else the paper's slots.
-bool choose_exact_t(int option, const PlanHost& pl, const Status& hs) {
+bool choose_exact_t(int option, const PlanHost& pl, const Status& hs, unsigned long long exact_t_chunks) {
     if (option != 2) return option != 0;
     const double slot_bytes = (double)((hs.max_count + 127) / 128 * 128);
     if ((double)hs.total_bytes >= 0.9 * (double)pl.P * (double)pl.P * slot_bytes) return false;
     const double slots_t = (double)pl.P * (double)pl.slots * slot_bytes;
-    const double exact_t = (double)hs.t_chunks * 16.0 + (double)pl.phases.size() * (double)pl.P * (double)pl.P * 4.0;
+    const double exact_t = (double)exact_t_chunks * 16.0 + (double)pl.phases.size() * (double)pl.P * (double)pl.P * 4.0;
     if (exact_t <= slots_t) return true;
     size_t free_b = 0, total_b = 0;
     if (hipMemGetInfo(&free_b, &total_b) != hipSuccess) { (void)hipGetLastError(); return false; }
     return exact_t <= 0.5 * (double)free_b;
-}
-
-bool phase_is_one_kernel(const Prepared& pr, const PhaseHost& ph) {
-    return pr.fused || (pr.staggered && ph.dim == 1);
 }
 
 void fill_stats_header(const Prepared& pr, const Status& hs, tuna_stats_t& st) {
@@ -571,7 +694,9 @@ int prepare_sizes(Prepared& pr, int dense_option, hipStream_t s, Status& hs, boo
     if (hs.flags & 4u) return TUNA_ERR_ARG;                 // a non-empty block at a negative displacement
     // the kernels round block sizes up to chunks and lines in 32-bit arithmetic
     if (hs.max_count > INT_MAX - 256) return TUNA_ERR_TOO_LARGE;
-    pr.exact_kernels = choose_exact_t(dense_option, pr.dp->host, hs);
+    if (dense_option != 0 && has_t)
+        pr.t_chunks = colour_classes(pr.dp->host, pr.fused, pr.staggered, pr.sb.h_status->cls_chunks, pr.cbase);
+    pr.exact_kernels = choose_exact_t(dense_option, pr.dp->host, hs, pr.t_chunks);
     pr.exact_t = pr.exact_kernels && has_t;
     *empty = hs.total_bytes == 0;
     if (*empty) return TUNA_OK;
@@ -589,7 +714,7 @@ int prepare_sizes(Prepared& pr, int dense_option, hipStream_t s, Status& hs, boo
     pr.max_count = hs.max_count;
     pr.total_bytes = hs.total_bytes;
     pr.user_limit = (unsigned long long)(uintptr_t)pr.sendbuf + hs.send_extent;
-    pr.ds = data_sizes_for(pr.dp->host, hs.max_count, hs.total_chunks, pr.fused, pr.staggered, pr.exact_t, hs.t_chunks);
+    pr.ds = data_sizes_for(pr.dp->host, hs.max_count, hs.total_chunks, pr.fused, pr.staggered, pr.exact_t, pr.t_chunks);
     return TUNA_OK;
 }
 
@@ -635,7 +760,7 @@ int launch_phase_metadata(const Prepared& pr, size_t i, const int32_t* cur, int3
     m.cur = cur; m.nxt = nxt; m.zt = pr.dp->d_zt[i]; m.seg = pr.dp->d_seg[i]; m.nseg = ph.nseg;
     m.P = pr.P; m.Q = pr.Q; m.N = pr.N; m.dim = ph.dim; m.rx = (int)ph.rx;
     m.Ls = Ls; m.Lr = Lr; m.want_send = one_kernel ? 0 : 1;
-    if (pr.exact_t) { m.Lt = pr.Lt[i]; m.want_tbound = 1; m.tpos = pr.x.tpos + i * (size_t)pr.P * pr.P; }
+    if (pr.exact_t) { m.want_tbound = 1; m.x = exact_t_of(pr, i); }
     m.rank_bytes = pr.rank_bytes;
     m.phase_bytes = &pr.sb.d_status->phase_bytes[i]; m.phase_chunks = &pr.sb.d_status->phase_chunks[i];
     m.phase_units = pr.sb.d_status->phase_units[i];
@@ -722,8 +847,8 @@ int launch_self_metadata(const Prepared& pr, hipStream_t s) {
                        (const unsigned char*)pr.sendbuf, pr.sendcounts, pr.sdispls, (unsigned char*)pr.recvbuf, pr.rdispls,
                        pr.P, pr.selfL, pr.selfH);
     HIPCHK(hipGetLastError());
-    hipLaunchKernelGGL(k_layout_base, dim3(1), dim3(kScanThreads), 0, s, pr.P, pr.selfL, pr.selfL, pr.selfL,
-                       (unsigned long long*)nullptr, -1, -1, ExactT{}, (const unsigned long long*)nullptr,
+    hipLaunchKernelGGL(k_layout_base, dim3(1), dim3(kScanThreads), 0, s, pr.P, pr.selfL, pr.selfL, 1,
+                       (unsigned long long*)nullptr, -1, ExactT{}, (const unsigned long long*)nullptr,
                        (unsigned long long*)nullptr, &pr.sb.d_status->self_units);
     HIPCHK(hipGetLastError());
     hipLaunchKernelGGL(k_layout_units, dim3(pr.P, 1), dim3(256), 2 * sizeof(int), s, 1, pr.selfL, pr.selfL, 2);
@@ -861,6 +986,8 @@ int run_one_pass(Prepared& pr, void* mbase, size_t mbytes, void* dbase, hipStrea
     pr.stage_r = cd.take<v4u>(pr.fused ? 0 : ds.stage_chunks);
     pr.T = cd.take<unsigned char>(ds.t_bytes + kTailSlack);
     if (!cm.ok || !cd.ok) return TUNA_ERR_WORKSPACE_TOO_SMALL;
+    int rc = upload_cbase(pr, s);
+    if (rc != TUNA_OK) return rc;
     st.temp_bytes = (int64_t)ds.t_bytes;
     st.staging_bytes = pr.fused ? 0 : (int64_t)(2 * ds.stage_chunks * 16);
     st.workspace_bytes = (int64_t)(mbytes + ds.total);
@@ -870,7 +997,7 @@ int run_one_pass(Prepared& pr, void* mbase, size_t mbytes, void* dbase, hipStrea
     hipLaunchKernelGGL(k_rotate_init, grot, dim3(256), 0, s, pr.sendcounts, mb.cur, P, pr.Q, pr.N);
     HIPCHK(hipGetLastError());
     mark(pr.ctx, s, kCatPrepare, -1);
-    int rc = launch_self_metadata(pr, s);
+    rc = launch_self_metadata(pr, s);
     if (rc != TUNA_OK) return rc;
     rc = launch_self_copy(pr, s);
     if (rc != TUNA_OK) return rc;
@@ -1024,10 +1151,12 @@ int plan_build_metadata(Plan* plan, void* meta, size_t mbytes, hipStream_t s, bo
         if (phase_is_one_kernel(pr, pl.phases[i])) carve_hop(cm, P, hop_ld_for(pl.phases[i].nseg), plan->hop[i]);
     carve_self(cm, pr);
     if (!cm.ok) return TUNA_ERR_WORKSPACE_TOO_SMALL;
+    int rc = upload_cbase(pr, s);
+    if (rc != TUNA_OK) return rc;
     const dim3 grot((unsigned)((P + 255) / 256), (unsigned)((P + kExchangeRanks - 1) / kExchangeRanks));
     hipLaunchKernelGGL(k_rotate_init, grot, dim3(256), 0, s, pr.sendcounts, cur, P, pr.Q, pr.N);
     HIPCHK(hipGetLastError());
-    int rc = launch_self_metadata(pr, s);
+    rc = launch_self_metadata(pr, s);
     if (rc != TUNA_OK) return rc;
     if (with_marks) mark(pr.ctx, s, kCatPrepare, -1);
     for (size_t i = 0; i < nph; ++i) {
@@ -1240,22 +1369,37 @@ int run_static(const void* sendbuf, const int32_t* sendcounts, const int64_t* sd
     DevicePlan dp;
     dp.host = make_plan(P, Q, crl, crg, pr.fused, /*with_tables=*/false);
     if ((int)dp.host.phases.size() > TUNA_MAX_PHASES) return TUNA_ERR_TOO_LARGE;
-    size_t table_bytes = align_up((size_t)P * 4);
-    for (const auto& ph : dp.host.phases) table_bytes += 6 * align_up((size_t)ph.nseg * 4) + align_up((size_t)P * 4);
+    dp.borrowed = true;                       // nothing of it is freed: it all lies in the static array
+    std::vector<std::vector<int32_t>> tord;
+    build_class_tables(dp.host, tord, dp.tcls);
+    size_t table_bytes = align_up((size_t)P * 4) + align_up((size_t)P * 8);
+    for (size_t i = 0; i < dp.host.phases.size(); ++i)
+        table_bytes += 8 * align_up((size_t)dp.host.phases[i].nseg * 4) + align_up((size_t)P * 4) +
+                       align_up(tord[i].size() * 4 + 4) + align_up(dp.tcls[i].size() * 4 + 4);
     if (cv.off + table_bytes > cv.cap) return TUNA_ERR_NOALLOC_LIMIT;     // before any kernel is launched
-    for (const auto& ph : dp.host.phases) {
+    for (size_t i = 0; i < dp.host.phases.size(); ++i) {
+        const PhaseHost& ph = dp.host.phases[i];
         const size_t stride = align_up((size_t)ph.nseg * 4) / 4;
-        int32_t* dm = cv.take<int32_t>(6 * stride);
+        int32_t* dm = cv.take<int32_t>(8 * stride);
         int32_t* dz = cv.take<int32_t>(P);
         hipLaunchKernelGGL(k_build_phase_table, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, dp.host.sc,
                            phase_scalars(ph), dm, dm + stride, dm + 2 * stride, dm + 3 * stride, dm + 4 * stride,
-                           dm + 5 * stride, dz);
+                           dm + 5 * stride, dm + 6 * stride, dm + 7 * stride, dz);
         HIPCHK(hipGetLastError());
         dp.d_zt.push_back(dz);
-        dp.d_seg.push_back(SegDev{dm, dm + stride, dm + 2 * stride, dm + 3 * stride, dm + 4 * stride, dm + 5 * stride});
+        dp.d_seg.push_back(SegDev{dm, dm + stride, dm + 2 * stride, dm + 3 * stride, dm + 4 * stride, dm + 5 * stride,
+                                  dm + 6 * stride, dm + 7 * stride});
+        int32_t* d_o = cv.take<int32_t>(tord[i].size() + 1);
+        int32_t* d_c = cv.take<int32_t>(dp.tcls[i].size() + 1);
+        // pageable source: the copy has left the host arrays when the call returns
+        if (!tord[i].empty()) HIPCHK(hipMemcpyAsync(d_o, tord[i].data(), tord[i].size() * 4, hipMemcpyHostToDevice, s));
+        if (!dp.tcls[i].empty()) HIPCHK(hipMemcpyAsync(d_c, dp.tcls[i].data(), dp.tcls[i].size() * 4, hipMemcpyHostToDevice, s));
+        dp.d_tord.push_back(d_o);
+        dp.d_tcls.push_back(d_c);
     }
     dp.d_hm1 = cv.take<int32_t>(P);
-    hipLaunchKernelGGL(k_build_hops, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, dp.host.sc, dp.d_hm1);
+    dp.d_mask = cv.take<unsigned long long>(P);
+    hipLaunchKernelGGL(k_build_hops, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, dp.host.sc, dp.d_hm1, dp.d_mask);
     HIPCHK(hipGetLastError());
     dp.built_on = s;
     pr.dp = &dp;
@@ -1655,11 +1799,14 @@ int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node, i
     rc = run_validate(g.sb, sendcounts, nullptr, nullptr, nullptr, P, nullptr, (o.t_layout != 0 && pl.slots > 0) ? dp : nullptr);
     if (rc != TUNA_OK) return rc;
     const Status* h_status = g.sb.h_status;
-    const bool exact_t = choose_exact_t(o.t_layout, pl, *h_status) && pl.slots > 0;
+    std::vector<long long> cbase;
+    const unsigned long long t_chunks = (o.t_layout != 0 && pl.slots > 0)
+        ? colour_classes(pl, fused, staggered, h_status->cls_chunks, cbase) : 0;
+    const bool exact_t = choose_exact_t(o.t_layout, pl, *h_status, t_chunks) && pl.slots > 0;
     dp->complete = true;                                  // run_validate synchronised the stream the tables were built on
     if (h_status->flags & 1u) return TUNA_ERR_NEGATIVE_COUNT;
     const DataSizes ds = data_sizes_for(pl, h_status->max_count, h_status->total_chunks, fused, staggered,
-                                        exact_t, h_status->t_chunks);
+                                        exact_t, t_chunks);
     Prepared pr;
     pr.P = P; pr.Q = Q; pr.N = N; pr.dp = dp; pr.ds = ds; pr.exact_t = exact_t;
     pr.fused = fused; pr.staggered = staggered; pr.max_count = h_status->max_count;

@@ -32,6 +32,8 @@ enum CopyMode { kPack = 0, kExchange = 1, kUnpack = 2, kFused = 3 };
 constexpr int kFlagFill = 16;    // destination is a T slot: the tail lane fills up the 128-byte line
 constexpr int kFlagSrcT = 32;    // source is a T slot: reading past the block's end is always safe
 
+constexpr int kMaxClasses = 64 * 63 / 2;     // class_count(TUNA_MAX_PHASES)
+
 // Device-side status block: the validation pass writes the head, every phase its own entries of the
 // three arrays; the head is read back once after validation.
 struct Status {
@@ -48,6 +50,8 @@ struct Status {
     unsigned long long phase_chunks[64];  // staged chunks per phase
     unsigned int phase_units[64][2];      // wave units per phase: [0] receive-side layout, [1] send-side layout
     unsigned int self_units;              // wave units of the ranks' own blocks when the copy engine moves them
+    unsigned int reserved2;
+    unsigned long long cls_chunks[kMaxClasses];   // exact-size T: chunks of every class (f, y), summed by the validation pass
 };
 
 // The per-phase table of moving blocks on the device, one array per field (message order).
@@ -58,18 +62,29 @@ struct SegDev {
     const int32_t* dst;    // destination T slot or -1 (receive buffer)
     const int32_t* srcph;  // phase in which the block arrived in T, or -1 (send buffer)
     const int32_t* srcseg; // its position in that phase's message order
+    const int32_t* scls;   // exact-size T: class (arrival phase, this phase) the block is read from, or -1
+    const int32_t* dcls;   // exact-size T: class (this phase, next move) the block is stored into, or -1
 };
 
-// Exact-size T: the blocks a rank stores into T in one phase lie back to back, in message order,
-// in that phase's arena; the arenas follow each other in T.  All offsets are in 16-byte chunks.
-// A later phase finds a block through the phase that stored it and its slot index e.
+// Exact-size T.  A block that arrives in phase f and moves again in phase y waits in T from f to y: the
+// blocks of one such class (f, y) lie together, rank after rank, each rank's part back to back in
+// message order (padded to 16 bytes per block, to a 128-byte line per rank).  Where a class lies in T
+// is decided on the host from the classes' sizes (the validation pass sums them) and lifetimes: classes
+// whose lifetimes do not overlap share memory, so T holds what waits in it at one time, not what ever
+// passed through it.  All offsets are in 16-byte chunks.
 struct ExactT {
-    long long* tbase;      // [phases][P]: first chunk in T of rank p's part of a phase's arena
-    long long* arena_end;  // [phases]: one past the last chunk of a phase's arena, rounded up to 256 bytes
-    int* tpos;             // [phases][P][P]: chunk offset inside that part of the block with slot index e
-    int* tpre;             // [P][ld]: the same offsets for the phase being run, in message order
+    const long long* cbase;  // [classes]: first chunk of each class in T (from the host)
+    long long* tbase;        // [classes][P]: first chunk in T of rank p's part of a class
+    int* csub;               // [classes][P]: chunks of rank p's part of a class
+    int* tpos;               // [phases][P][P]: chunk offset, inside its rank's part of its class, of the block with slot index e that the phase stored
+    int* tpre;               // [P][ld]: the same offsets for the phase being run, in message order
     int ld;
-    int phase;             // index of the phase being run
+    int phase;               // index of the phase being run
+    // the T-bound blocks of the phase being run, grouped by class: tord[tcls[3k+1] .. +tcls[3k+2]) are the
+    // segment indices of class tcls[3k], in message order
+    const int32_t* tord;
+    const int32_t* tcls;
+    int ncls;                // classes the phase being run stores into
 };
 
 // Distance pair of a slot index.
@@ -134,6 +149,7 @@ __global__ void __launch_bounds__(256) k_build_phase_table(const PlanScalars pl,
                                                            int32_t* __restrict__ seg_e, int32_t* __restrict__ seg_z,
                                                            int32_t* __restrict__ seg_src, int32_t* __restrict__ seg_dst,
                                                            int32_t* __restrict__ seg_srcph, int32_t* __restrict__ seg_srcseg,
+                                                           int32_t* __restrict__ seg_scls, int32_t* __restrict__ seg_dcls,
                                                            int32_t* __restrict__ zt) {
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= pl.P) return;
@@ -143,6 +159,9 @@ __global__ void __launch_bounds__(256) k_build_phase_table(const PlanScalars pl,
         zt[e] = s.z;
         seg_e[pos] = s.e; seg_z[pos] = s.z; seg_src[pos] = s.src_slot; seg_dst[pos] = s.dst_slot;
         seg_srcph[pos] = s.src_phase; seg_srcseg[pos] = s.src_seg;
+        const int cur = ph.dim == 0 ? ph.x : pl.w_l + ph.x;
+        seg_scls[pos] = s.src_phase >= 0 ? class_id(s.src_phase, cur, pl.nph) : -1;
+        seg_dcls[pos] = s.nxt_phase >= 0 ? class_id(cur, s.nxt_phase, pl.nph) : -1;
     } else {
         zt[e] = 0;
     }
@@ -175,9 +194,11 @@ __global__ void __launch_bounds__(256) k_fill_uniform(int32_t* __restrict__ send
 // hop per non-zero digit of its distance pair (l in base r_l, j in base r_g) and is stored into T
 // after every hop but its last -- hm1[e] times.
 // ------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) k_build_hops(const PlanScalars pl, int32_t* __restrict__ hm1) {
+__global__ void __launch_bounds__(256) k_build_hops(const PlanScalars pl, int32_t* __restrict__ hm1,
+                                                    unsigned long long* __restrict__ mask) {
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= pl.P) return;
+    mask[e] = move_mask(pl, e);
     int j = e / pl.Q, l = e - j * pl.Q, hops = 0;
     for (; l; l /= pl.rl) hops += (l % pl.rl) != 0;
     for (; j; j /= pl.rg) hops += (j % pl.rg) != 0;
@@ -201,10 +222,16 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
                                                   const int64_t* __restrict__ sdispls,
                                                   const int64_t* __restrict__ rdispls,
                                                   int P, unsigned long long* __restrict__ partial,
-                                                  const int32_t* __restrict__ hm1, int Q, int N) {
+                                                  const int32_t* __restrict__ hm1, int Q, int N,
+                                                  const unsigned long long* __restrict__ mask, int nph,
+                                                  unsigned long long* __restrict__ cls_chunks) {
     __shared__ int tile[kValTile][kValTile + 1];
     __shared__ unsigned long long red[4][6];
+    extern __shared__ unsigned long long lcls[];          // class_count(nph) sums of this workgroup (with `mask`)
     const int tx = threadIdx.x, ty = threadIdx.y;
+    const int ncls = mask ? class_count(nph) : 0;
+    for (int i = ty * kValTile + tx; i < ncls; i += 4 * kValTile) lcls[i] = 0;
+    __syncthreads();
     const int tpr = (P + kValTile - 1) / kValTile;       // tiles per row
     const int ntile = tpr * tpr;
     unsigned int flags = 0, abits = 0;
@@ -238,6 +265,18 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
                     int dn = in - jn; if (dn < 0) dn += N;
                     int dg = ig - jg; if (dg < 0) dg += Q;
                     tchunks += ch * (unsigned long long)hm1[dn * Q + dg];
+                    if (mask) {
+                        // the block waits in T between every two consecutive phases in which it moves
+                        unsigned long long m = mask[dn * Q + dg];
+                        int f = __ffsll((long long)m) - 1;
+                        m &= m - 1;
+                        while (m) {
+                            const int y = __ffsll((long long)m) - 1;
+                            m &= m - 1;
+                            atomicAdd(&lcls[class_id(f, y, nph)], ch);
+                            f = y;
+                        }
+                    }
                 }
             }
             tile[a][tx] = c;
@@ -288,6 +327,15 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
         unsigned long long* o = partial + (size_t)blockIdx.x * kValPartial;
         o[0] = fa; o[1] = m; o[2] = by; o[3] = ch; o[4] = ex; o[5] = tc;
     }
+    // the class sums: one atomic per class and workgroup that holds any of it (cls_chunks starts at zero)
+    for (int i = ty * kValTile + tx; i < ncls; i += 4 * kValTile)
+        if (lcls[i]) atomicAdd(&cls_chunks[i], lcls[i]);
+}
+
+// k_zero64: n 64-bit words to zero (the class sums before a validation pass).
+__global__ void __launch_bounds__(256) k_zero64(unsigned long long* __restrict__ p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
 }
 
 // k_validate_finish: folds the workgroups' partial results into the status block (one workgroup).
@@ -458,10 +506,10 @@ struct PhaseLayoutArgs {
     SegDev seg;
     int nseg;
     int P, Q, N, dim, rx;
-    LayoutDev Ls, Lr, Lt;
+    LayoutDev Ls, Lr;
     int want_send;                  // 0: only the receive-side layout (one-kernel phases)
-    int want_tbound;                // 1: also the prefix over the T-bound blocks alone (exact-size T)
-    int* tpos;                      // [P][P]: that prefix again, by slot index, for the phases that forward the blocks
+    int want_tbound;                // 1: also lay out the blocks this phase stores into exact-size T (see ExactT)
+    ExactT x;
     unsigned long long* rank_bytes; // [P]: payload bytes every rank moves in this phase
     unsigned long long* phase_bytes;
     unsigned long long* phase_chunks;
@@ -508,7 +556,7 @@ __device__ __forceinline__ void block_scan_batch(const int (&c)[kScanItems], int
 // thread sums a contiguous range of ranks, the thread sums are scanned across the workgroup, then
 // every thread writes the bases of its range
 __device__ __forceinline__ void scan_rank_bases(int P, const LayoutDev& L, unsigned long long* phase_chunks,
-                                                long long* wc, int* wt, const ExactT* x = nullptr,
+                                                long long* wc, int* wt,
                                                 const unsigned long long* rank_bytes = nullptr,
                                                 unsigned long long* phase_bytes = nullptr,
                                                 unsigned int* units_out = nullptr) {
@@ -545,12 +593,9 @@ __device__ __forceinline__ void scan_rank_bases(int P, const LayoutDev& L, unsig
     }
     long long run_c = oc + ic - sc;
     int run_t = ot + it - st;
-    // exact-size T: this phase's arena starts where the previous one ends
-    const long long arena0 = (x && x->phase > 0) ? x->arena_end[x->phase - 1] : 0;
     for (int p = p0; p < p1; ++p) {
         const int c = L.tot[p];
         L.rank_base[p] = run_c;
-        if (x) x->tbase[(size_t)x->phase * P + p] = arena0 + run_c;
         if (L.unit_base) L.unit_base[p] = run_t;
         run_c += (c + ralign - 1) / ralign * ralign;
         run_t += (c + kUnitChunks - 1) / kUnitChunks;
@@ -560,7 +605,6 @@ __device__ __forceinline__ void scan_rank_bases(int P, const LayoutDev& L, unsig
         if (L.unit_base) { L.unit_base[P] = tott; *L.n_units = tott; }
         if (units_out) *units_out = (unsigned int)tott;
         if (phase_chunks) *phase_chunks = (unsigned long long)totc;
-        if (x) x->arena_end[x->phase] = arena0 + (totc + 15) / 16 * 16;
     }
     if (phase_bytes) {                                // payload bytes of the phase = sum of the ranks' sums
         unsigned long long b = 0;
@@ -596,18 +640,15 @@ __global__ void __launch_bounds__(kScanThreads) k_phase_layout(const PhaseLayout
     }
     int* pre_r = a.Lr.pre + (size_t)p * a.Lr.ld;
     int* pre_s = a.Ls.pre + (size_t)p * a.Ls.ld;
-    int* pre_t = a.want_tbound ? a.Lt.pre + (size_t)p * a.Lt.ld : nullptr;
-    int carry_r = 0, carry_s = 0, carry_t = 0;
+    int carry_r = 0, carry_s = 0;
     unsigned long long bytes = 0;
     for (int base = 0; base < a.nseg; base += kScanThreads * kScanItems) {
-        int cr[kScanItems], cs[kScanItems], ct[kScanItems];
+        int cr[kScanItems], cs[kScanItems];
 #pragma unroll
         for (int k = 0; k < kScanItems; ++k) {
             const int s = base + scan_item_index(k);
             int szr = 0, szs = 0, head = 0;
-            bool tbound = false;
             if (s < a.nseg) {
-                tbound = a.want_tbound && a.seg.dst[s] >= 0;
                 const int e = a.seg.e[s];
                 if (a.inline_exchange) {
                     const int ps = partner_up(pn, pg, a.Q, a.N, a.dim, a.seg.z[s] * a.rx);
@@ -628,7 +669,6 @@ __global__ void __launch_bounds__(kScanThreads) k_phase_layout(const PhaseLayout
             bytes += (unsigned long long)(a.want_send ? szs : szr);
             cr[k] = (head + szr + 15) >> 4;
             cs[k] = (szs + 15) >> 4;
-            ct[k] = tbound ? (szr + 15) >> 4 : 0;
         }
         int run[kScanItems];
         block_scan_batch(cr, run, carry_r, wsum);
@@ -645,16 +685,37 @@ __global__ void __launch_bounds__(kScanThreads) k_phase_layout(const PhaseLayout
                 if (s < a.nseg) pre_s[s] = run[k];
             }
         }
-        if (a.want_tbound) {
-            block_scan_batch(ct, run, carry_t, wsum);
+    }
+    if (a.want_tbound) {
+        // Exact-size T: the blocks this phase stores, class by class (a class = the blocks that move next in
+        // the same later phase); within a class in message order.  Every block's chunk offset inside this
+        // rank's part of its class goes to tpre (by segment, for this phase's own stores) and to tpos (by slot
+        // index, for the phase that forwards the block); the part's size goes to csub.
+        __syncthreads();                                  // the sizes this workgroup exchanged itself are in nrow
+        int* pre_t = a.x.tpre + (size_t)p * a.x.ld;
+        int* pos_t = a.x.tpos + ((size_t)a.x.phase * P + p) * P;
+        for (int cl = 0; cl < a.x.ncls; ++cl) {
+            const int cid = a.x.tcls[3 * cl], c0 = a.x.tcls[3 * cl + 1], cn = a.x.tcls[3 * cl + 2];
+            int carry_t = 0;
+            for (int base = 0; base < cn; base += kScanThreads * kScanItems) {
+                int ct[kScanItems], sg[kScanItems], se[kScanItems];
 #pragma unroll
-            for (int k = 0; k < kScanItems; ++k) {
-                const int s = base + scan_item_index(k);
-                if (s < a.nseg) {
-                    pre_t[s] = run[k];
-                    if (ct[k]) a.tpos[(size_t)p * P + a.seg.e[s]] = run[k];
+                for (int k = 0; k < kScanItems; ++k) {
+                    const int i = base + scan_item_index(k);
+                    ct[k] = 0; sg[k] = -1; se[k] = 0;
+                    if (i < cn) {
+                        sg[k] = a.x.tord[c0 + i];
+                        se[k] = a.seg.e[sg[k]];
+                        ct[k] = (nrow[se[k]] + 15) >> 4;
+                    }
                 }
+                int run[kScanItems];
+                block_scan_batch(ct, run, carry_t, wsum);
+#pragma unroll
+                for (int k = 0; k < kScanItems; ++k)
+                    if (sg[k] >= 0) { pre_t[sg[k]] = run[k]; pos_t[se[k]] = run[k]; }
             }
+            if (tid == 0) a.x.csub[(size_t)cid * P + p] = carry_t;
         }
     }
 #pragma unroll
@@ -673,28 +734,59 @@ __global__ void __launch_bounds__(kScanThreads) k_phase_layout(const PhaseLayout
     if (tid == 0) {
         pre_r[a.nseg] = carry_r; a.Lr.tot[p] = carry_r;
         if (a.want_send) { pre_s[a.nseg] = carry_s; a.Ls.tot[p] = carry_s; }
-        if (a.want_tbound) { pre_t[a.nseg] = carry_t; a.Lt.tot[p] = carry_t; }
     }
 }
 
 // ------------------------------------------------------------------------------------------
 // k_layout_base: exclusive scan over the P per-rank totals of a layout -> each rank's first chunk
 // in its staging buffer and its first wave unit.  One workgroup per layout the host lists (receive
-// side, send side, T-bound blocks).  A separate launch rather than a "last workgroup" step inside
-// k_phase_layout: the kernel boundary is the one device-wide release the totals need.
+// side, send side), then one per class of exact-size T that the phase stores into: there the scan
+// runs over the ranks' parts of the class and gives every rank's first chunk in T.  A separate
+// launch rather than a "last workgroup" step inside k_phase_layout: the kernel boundary is the one
+// device-wide release the totals need.
 // ------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(kScanThreads) k_layout_base(int P, LayoutDev L0, LayoutDev L1, LayoutDev L2,
+__global__ void __launch_bounds__(kScanThreads) k_layout_base(int P, LayoutDev L0, LayoutDev L1, int n_layouts,
                                                               unsigned long long* __restrict__ phase_chunks,
-                                                              int chunks_from, int tbound_at, ExactT x,
+                                                              int chunks_from, ExactT x,
                                                               const unsigned long long* __restrict__ rank_bytes,
                                                               unsigned long long* __restrict__ phase_bytes,
                                                               unsigned int* __restrict__ phase_units) {
     __shared__ long long wc[kScanThreads / kWave];
     __shared__ int wt[kScanThreads / kWave];
     const int which = blockIdx.x;
-    scan_rank_bases(P, which == 0 ? L0 : (which == 1 ? L1 : L2), which == chunks_from ? phase_chunks : nullptr, wc, wt,
-                    which == tbound_at ? &x : nullptr, rank_bytes, which == chunks_from ? phase_bytes : nullptr,
-                    which == tbound_at ? nullptr : phase_units + which);       // layout 0 is the receive side, 1 the send side
+    if (which < n_layouts) {
+        scan_rank_bases(P, which == 0 ? L0 : L1, which == chunks_from ? phase_chunks : nullptr, wc, wt,
+                        rank_bytes, which == chunks_from ? phase_bytes : nullptr,
+                        phase_units + which);             // layout 0 is the receive side, 1 the send side
+        return;
+    }
+    // a class of exact-size T: rank p's part starts at the class's first chunk plus the parts of the
+    // ranks before it, each rounded up to a 128-byte line
+    const int cid = x.tcls[3 * (which - n_layouts)];
+    const int* sub = x.csub + (size_t)cid * P;
+    long long* base = x.tbase + (size_t)cid * P;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    const int per = (P + kScanThreads - 1) / kScanThreads;
+    const int p0 = min(P, tid * per), p1 = min(P, p0 + per);
+    long long sc = 0;
+    for (int p = p0; p < p1; ++p) sc += (sub[p] + kRankAlignChunks - 1) / kRankAlignChunks * kRankAlignChunks;
+    long long ic = sc;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const long long uc = __shfl_up(ic, d, kWave);
+        if (lane >= d) ic += uc;
+    }
+    if (lane == kWave - 1) wc[wv] = ic;
+    __syncthreads();
+    long long oc = 0;
+#pragma unroll
+    for (int k = 0; k < kScanThreads / kWave; ++k)
+        if (k < wv) oc += wc[k];
+    long long run = x.cbase[cid] + oc + ic - sc;
+    for (int p = p0; p < p1; ++p) {
+        base[p] = run;
+        run += (sub[p] + kRankAlignChunks - 1) / kRankAlignChunks * kRankAlignChunks;
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -840,12 +932,12 @@ __device__ __forceinline__ unsigned long long block_address(int slot, bool far_i
 
 // Exact-size T: where rank p stores segment s of the phase being run, and where rank p holds the
 // block with slot index e that phase `ph` stored.
-__device__ __forceinline__ unsigned long long exact_t_dst(unsigned char* T, const ExactT& x, int P, int p, int s) {
-    return (unsigned long long)(T + ((x.tbase[(size_t)x.phase * P + p] + (long long)x.tpre[(size_t)p * x.ld + s]) << 4));
+__device__ __forceinline__ unsigned long long exact_t_dst(unsigned char* T, const ExactT& x, int P, int p, int s, int dcls) {
+    return (unsigned long long)(T + ((x.tbase[(size_t)dcls * P + p] + (long long)x.tpre[(size_t)p * x.ld + s]) << 4));
 }
-__device__ __forceinline__ unsigned long long exact_t_src(unsigned char* T, const ExactT& x, int P, int ph, int p, int e) {
-    const size_t row = (size_t)ph * P + p;
-    return (unsigned long long)(T + ((x.tbase[row] + (long long)x.tpos[row * P + e]) << 4));
+__device__ __forceinline__ unsigned long long exact_t_src(unsigned char* T, const ExactT& x, int P, int ph, int p, int e,
+                                                          int scls) {
+    return (unsigned long long)(T + ((x.tbase[(size_t)scls * P + p] + (long long)x.tpos[((size_t)ph * P + p) * P + e]) << 4));
 }
 
 // ------------------------------------------------------------------------------------------
@@ -897,7 +989,7 @@ __global__ void __launch_bounds__(256) k_resolve_hop(const ResolveArgs a) {
         src = (unsigned long long)(a.S + a.sdispls[(size_t)q * a.P + dn * a.Q + dg]);
     } else if (DENSE) {
         const size_t row = (size_t)a.seg.srcph[s] * a.P + q;
-        src = (((unsigned long long)(a.x.tbase[row] + (long long)a.x.tpos[row * a.P + e])) << 4) | kHopInT;
+        src = (((unsigned long long)(a.x.tbase[(size_t)a.seg.scls[s] * a.P + q] + (long long)a.x.tpos[row * a.P + e])) << 4) | kHopInT;
     } else {
         src = (unsigned long long)(((long long)q * a.slots + ssrc) * a.slot_bytes) | kHopInT;
     }
@@ -909,7 +1001,7 @@ __global__ void __launch_bounds__(256) k_resolve_hop(const ResolveArgs a) {
     } else {
         size = ((sz + 15) >> 4) << 4;    // T takes whole chunks
         if (DENSE)
-            dst = (((unsigned long long)(a.x.tbase[(size_t)a.x.phase * a.P + p] + (long long)a.x.tpre[(size_t)p * a.x.ld + s])) << 4) | kHopInT;
+            dst = (((unsigned long long)(a.x.tbase[(size_t)a.seg.dcls[s] * a.P + p] + (long long)a.x.tpre[(size_t)p * a.x.ld + s])) << 4) | kHopInT;
         else
             dst = (unsigned long long)(((long long)p * a.slots + sdst) * a.slot_bytes) | kHopInT | kHopFill;
     }
@@ -977,7 +1069,7 @@ k_copy(const CopyArgs a) {
         const int s = sw + lane;
         int pre_i, pre_w;                            // pre_w is wave-uniform: the first prefix of the next window
         // table fields this mode needs, fetched together with the prefix
-        int se = 0, sz_ = 0, ssrc = -1, sdst = -1, sph = -1;
+        int se = 0, sz_ = 0, ssrc = -1, sdst = -1, sph = -1, scl = -1;
         unsigned long long addr = 0, addr2 = 0;
         int size = 0, flag = 0;
         if (MODE == kFused) {
@@ -1017,9 +1109,12 @@ k_copy(const CopyArgs a) {
             if (MODE == kExchange) sz_ = a.seg.z[s];
             if (MODE == kPack) {
                 ssrc = a.seg.src[s];
-                if (DENSE) sph = a.seg.srcph[s];
+                if (DENSE) { sph = a.seg.srcph[s]; scl = a.seg.scls[s]; }
             }
-            if (MODE == kUnpack) sdst = a.seg.dst[s];
+            if (MODE == kUnpack) {
+                sdst = a.seg.dst[s];
+                if (DENSE) scl = a.seg.dcls[s];
+            }
         }
         const int wend = pre_w;                      // chunks below wend resolve in this window
         // unpack reads its own staging region: the payload loads of this window need only its bounds and
@@ -1047,7 +1142,7 @@ k_copy(const CopyArgs a) {
                 split_slot_index(se, a.Q, a.N, bj, bl);
                 if (MODE == kPack) {
                     if (DENSE && ssrc >= 0)
-                        addr = exact_t_src(a.T, a.x, a.P, sph, p, se);
+                        addr = exact_t_src(a.T, a.x, a.P, sph, p, se, scl);
                     else
                         addr = block_address(ssrc, false, p, n, g, bj, bl, a.P, a.Q, a.N, a.user, a.displs, a.T,
                                              a.slots, a.slot_bytes);
@@ -1057,7 +1152,7 @@ k_copy(const CopyArgs a) {
                     // a final block's size is the receiver's own recvcounts entry (validated equal to
                     // the sender's count), read next to its displacement
                     if (DENSE && sdst >= 0)           // exact-size T: blocks lie back to back, nothing to fill
-                        addr = exact_t_dst(a.T, a.x, a.P, p, s);
+                        addr = exact_t_dst(a.T, a.x, a.P, p, s, scl);
                     else
                         addr = block_address(sdst, true, p, n, g, bj, bl, a.P, a.Q, a.N, a.user, a.displs, a.T,
                                              a.slots, a.slot_bytes, a.counts, &size);

@@ -19,8 +19,8 @@
 
 namespace tuna {
 
-// One moving block of a phase, in message order (z ascending, then e ascending).  32 bytes, read
-// by the kernels as two 16-byte halves: {e, z, src_slot, dst_slot} and {j, l, -, -}.
+// One moving block of a phase, in message order (z ascending, then e ascending).  The device keeps
+// the fields it needs as one array per field (SegDev).
 struct SegInfo {
     int32_t e;         // slot index j*Q + l
     int32_t z;         // value of the phase's digit (1..r-1): which message, and the partner distance z*r^x
@@ -30,6 +30,7 @@ struct SegInfo {
     int32_t l;         // local distance
     int32_t src_phase; // phase in which the block last moved (it arrived in T then), or -1: still in S
     int32_t src_seg;   // its position in that phase's message order
+    int32_t nxt_phase; // phase in which the block moves next (it waits in T until then), or -1: final
 };
 
 struct PhaseHost {
@@ -53,6 +54,7 @@ struct PlanScalars {
     long long slots1;     // slots of one copy of T
     int fused;
     int w_l;              // number of local phases (they come first in the phase list)
+    int nph;              // number of phases
 };
 
 struct PhaseScalars {
@@ -103,6 +105,25 @@ TUNA_HD inline long long t_index(long long o, long long r) {
     const long long dz = o / v;
     return o - 1 - dx * (r - 1) - dz;
 }
+
+// Phases in which the block with slot index e moves: bit x of the mask for phase x of the phase
+// list (local phases first, then global ones) -- one hop per non-zero digit of its distance pair.
+TUNA_HD inline unsigned long long move_mask(const PlanScalars& pl, int e) {
+    const int j = e / pl.Q, l = e - j * pl.Q;
+    unsigned long long m = 0;
+    int x = 0;
+    for (int v = l; v; v /= pl.rl, ++x)
+        if (v % pl.rl) m |= 1ull << x;
+    x = pl.w_l;
+    for (int v = j; v; v /= pl.rg, ++x)
+        if (v % pl.rg) m |= 1ull << x;
+    return m;
+}
+
+// Exact-size T keeps the blocks that wait from phase f to phase y (f < y: stored when they arrive in
+// phase f, forwarded in phase y) together, as "class" (f, y); classes are numbered row by row.
+TUNA_HD inline int class_id(int f, int y, int nph) { return f * nph - f * (f + 1) / 2 + (y - f - 1); }
+TUNA_HD inline int class_count(int nph) { return nph * (nph - 1) / 2; }
 
 // Number of coordinates c in [0, size) whose digit x (base r) equals z.
 TUNA_HD inline long long count_with_digit(const PhaseScalars& ph, int z) {
@@ -209,6 +230,14 @@ TUNA_HD inline bool slot_entry(const PlanScalars& pl, const PhaseScalars& ph, in
     }
     s.src_phase = -1; s.src_seg = 0;
     if (s.src_slot >= 0) previous_move(pl, ph, e, &s.src_phase, &s.src_seg);
+    s.nxt_phase = -1;
+    if (s.dst_slot >= 0) {            // the lowest phase above this one in which the block moves again
+        const int cur = ph.dim == 0 ? ph.x : pl.w_l + ph.x;
+        const unsigned long long later = move_mask(pl, e) >> (cur + 1);
+        int d = 0;
+        while (d < 63 && !((later >> d) & 1ull)) ++d;
+        s.nxt_phase = cur + 1 + d;
+    }
     *out = s;
     return true;
 }
@@ -245,6 +274,7 @@ inline PlanHost make_plan(int P, int Q, int rl, int rg, bool fused = false, bool
     sc.slots1 = sc.global0 + (long long)pl.B_g * Q;
     sc.fused = fused ? 1 : 0;
     sc.w_l = pl.w_l;
+    sc.nph = pl.w_l + pl.w_g;
     pl.slots = fused ? 2 * sc.slots1 : sc.slots1;
     pl.fused = fused;
     for (int dim = 0; dim < 2; ++dim) {

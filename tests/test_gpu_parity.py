@@ -439,7 +439,9 @@ def test_temporary_buffer_too_large_is_an_error_not_a_crash(tuna, mode):
     """T has one M-byte slot per intermediate block: one 512 MiB block among 64 ranks at radix 2
     asks for terabytes.  The call must return TUNA_ERR_NOMEM, move nothing, and leave the library
     usable; the same problem runs at radix P, which needs no T -- and at radix 2 with T in exact
-    size, which then holds that one block three times (its index 27 has four non-zero bits)."""
+    size: the block (index 27: four non-zero bits) waits in T three times, one wait after the other, so
+    with three-stage phases T holds it once, and twice with one-kernel phases, where a phase reads one
+    wait's copy while it writes the next one's."""
     P = 64
     counts = np.zeros((P, P), dtype=np.int32)
     counts[3, 40] = 512 << 20
@@ -453,9 +455,10 @@ def test_temporary_buffer_too_large_is_an_error_not_a_crash(tuna, mode):
     if mode.endswith("exact"):
         assert rc == 0, tuna.tuna_strerror(rc)
         st = tuna.tuna_get_stats()
-        # the 100-byte block (7 chunks) has index 63: six hops, five stores; per phase 256 bytes of
-        # rounding and one 128-byte line per rank
-        assert st.temp_bytes == 3 * (512 << 20) + 5 * 7 * 16 + 6 * (256 + P * 128)
+        # the 100-byte block (index 63: six hops) adds little; rounding: a 128-byte line per rank and 256
+        # bytes for every group of blocks that wait together
+        copies = 2 if mode.startswith("fused") else 1
+        assert copies * (512 << 20) <= st.temp_bytes <= copies * (512 << 20) + 20 * (256 + P * 128) + 4096
     else:
         assert rc == tuna.TUNA_ERR_NOMEM, tuna.tuna_strerror(rc)
         torch.cuda.synchronize()

@@ -238,17 +238,26 @@ def test_exact_size_t_matches_the_oracle(tuna, P, Q, rl, rg, cfg, mode):
         assert tuna.tuna_plan_free(plan) == 0
 
 
-def test_exact_size_t_holds_what_waits_in_it(tuna):
-    """T in exact size takes the bytes that are stored into it, summed over the phases (each block
-    padded to 16 bytes, plus 256 bytes of rounding per phase and a 128-byte line per rank and phase): for every phase but the last that is the phase's
-    payload minus what reaches R.  With r = 2 and P = 2^k, phase x delivers the blocks whose index
-    is below 2^(x+1) among those with bit x set, 2^x of P/2.  Heavy-tailed sizes make the bound
-    of B slots of M bytes many times larger."""
+def _t_bounds(counts, Q, rl, rg, one_kernel):
+    """(bytes alive in T at one time, bytes that ever pass through T, classes) from tests/t_size.py."""
+    import t_size
+    cls, nph = t_size.waiting_bytes(counts, Q, rl, rg)
+    return t_size.alive_peak(cls, lambda f: one_kernel), t_size.passed_through(cls), len(cls)
+
+
+@pytest.mark.parametrize("fused", [0, 1])
+def test_exact_size_t_holds_what_waits_in_it(tuna, fused):
+    """T in exact size holds what waits in it at one time, not what ever passes through it: the blocks that
+    wait from phase f to phase y lie together and share memory with blocks whose wait does not overlap
+    theirs.  Its size lies between the most bytes alive at one time (counted independently here, blocks
+    padded to 16 bytes) and 1.15 times that plus the rounding (a 128-byte line per rank and 256 bytes per
+    group of blocks).  With r = 2 and three-stage phases that is about the payload, a third of what passes
+    through T; heavy-tailed sizes make the paper's bound of B slots of M bytes many times larger."""
     P = 256
     counts = wl.make_counts(3, P)
     lay = wl.make_layout(counts)
     res = Resident(lay)
-    code, plan = _dense_plan(tuna, res, P, 0, 2, 2)
+    code, plan = _dense_plan(tuna, res, P, 0, 2, 2, fused=fused)
     assert code == 0
     try:
         want = res.load(3)
@@ -259,16 +268,14 @@ def test_exact_size_t_holds_what_waits_in_it(tuna):
         dense_bytes = st.temp_bytes
     finally:
         assert tuna.tuna_plan_free(plan) == 0
-    # independent count of the chunks each phase stores into T: block (s -> d) has index
-    # i = (s - d) mod P; in phase x it moves when bit x of i is set and stays in T while a higher bit is set
-    idx = (np.arange(P)[:, None] - np.arange(P)[None, :]) % P
-    chunks = (counts.astype(np.int64) + 15) // 16
-    total = 0
-    for x in range(8):
-        stored = ((idx >> x) & 1 == 1) & ((idx >> (x + 1)) != 0)
-        total += int(chunks[stored].sum()) * 16
-    assert dense_bytes == total + 8 * (256 + P * 128)  # per phase: 256 bytes of rounding and one 128-byte line per rank
-    code, plan = _dense_plan(tuna, res, P, 0, 2, 2, dense=0)
+    alive, passed, ncls = _t_bounds(counts, 0, 2, 2, bool(fused))
+    rounding = ncls * (P * 128 + 256)
+    print("exact-size T: %d bytes; alive at one time %d, passed through %d, payload %d" % (dense_bytes, alive, passed, lay.payload_bytes))
+    assert alive <= dense_bytes <= 1.15 * alive + rounding
+    assert dense_bytes < 0.6 * passed
+    if not fused:
+        assert dense_bytes <= 1.1 * lay.payload_bytes + rounding
+    code, plan = _dense_plan(tuna, res, P, 0, 2, 2, fused=fused, dense=0)
     assert code == 0
     try:
         assert tuna.tuna_start(plan) == 0
@@ -276,8 +283,32 @@ def test_exact_size_t_holds_what_waits_in_it(tuna):
     finally:
         assert tuna.tuna_plan_free(plan) == 0
     M = int(counts.max())
-    assert strided == P * (P - 9) * (-(-M // 128) * 128)
+    assert strided == (2 if fused else 1) * P * (P - 9) * (-(-M // 128) * 128)
     assert strided > 4 * dense_bytes
+
+
+@pytest.mark.parametrize("r", [2, 4, 16])
+def test_exact_size_t_is_never_the_larger_layout(tuna, r):
+    """Block sizes of the headline workload (normal, 1 KiB +- 256 B), reduced to P = 256: the T the library
+    takes by default is never larger than the paper's B slots of M bytes, at any radix, in either mode."""
+    P = 256
+    counts = wl.make_counts(4, P)
+    lay = wl.make_layout(counts)
+    res = Resident(lay)
+    for fused in (0, 1):
+        sizes = {}
+        for dense in (2, 0):
+            code, plan = _dense_plan(tuna, res, P, 0, r, r, fused=fused, dense=dense)
+            assert code == 0
+            try:
+                assert tuna.tuna_start(plan) == 0
+                sizes[dense] = tuna.tuna_get_stats().temp_bytes
+            finally:
+                assert tuna.tuna_plan_free(plan) == 0
+        torch.cuda.synchronize()
+        assert sizes[2] <= sizes[0], (r, fused, sizes)
+        if not fused:
+            assert sizes[2] <= 1.1 * lay.payload_bytes + 64 * (P * 128 + 256)
 
 
 def test_device_source_tables_match_the_host(tuna):
@@ -295,10 +326,8 @@ def test_device_source_tables_match_the_host(tuna):
 
 @pytest.mark.parametrize("P,Q,rl,rg", [(96, 8, 3, 4), (120, 5, 2, 5), (64, 0, 4, 4)])
 def test_exact_size_t_bytes_hierarchical(tuna, P, Q, rl, rg):
-    """The bytes of T the library reports are sum over blocks of 16 ceil(size / 16) (hops - 1) plus 256 and
-    a 128-byte line per rank per phase, hops = non-zero digits of the block's local distance in base r_l and of its node
-    distance in base r_g (counted here with the model's digit function)."""
-    from oracle import tuna_model as tm
+    """The same bounds with a hierarchy: a block moves once per non-zero digit of its local distance in base
+    r_l, then once per non-zero digit of its node distance in base r_g, and waits in T between two moves."""
     counts = wl.make_counts(2, P)
     lay = wl.make_layout(counts)
     res = Resident(lay)
@@ -312,14 +341,9 @@ def test_exact_size_t_bytes_hierarchical(tuna, P, Q, rl, rg):
         st = tuna.tuna_get_stats()
     finally:
         assert tuna.tuna_plan_free(plan) == 0
-    Qe = Q if Q else P
-    N = P // Qe
-    total = 0
-    for i in range(P):
-        for d in range(P):
-            hops = tm.nonzero_digits((i % Qe - d % Qe) % Qe, rl) + tm.nonzero_digits((i // Qe - d // Qe) % N, rg)
-            total += (int(counts[i, d]) + 15) // 16 * 16 * max(hops - 1, 0)
-    assert st.temp_bytes == total + (256 + P * 128) * st.n_phases
+    alive, passed, ncls = _t_bounds(counts, Q, rl, rg, False)
+    assert alive <= st.temp_bytes <= 1.15 * alive + ncls * (P * 128 + 256)
+    assert st.temp_bytes <= passed + ncls * (P * 128 + 256)
 
 
 def test_t_layout_left_to_the_library(tuna):
