@@ -340,6 +340,20 @@ int tuna_plan_phase_device(int P, int ranks_per_node, int local_radix, int globa
                            int32_t* seg, int seg_capacity);
 
 /*
+ * For verification: the device's block-size matrix as the metadata exchange leaves it (Section
+ * "Two-phase communication": the sizes travel ahead of the blocks).  Builds a persistent plan for the
+ * problem, copies the P x P int32 matrix of current block sizes to the host array `sizes` before the
+ * first digit phase (entry 0: the initial rotation) and after every phase (entries 1 .. n_phases), row =
+ * rank, column = slot index j * Q + l, and frees the plan again.  `sizes` must hold capacity_phases >=
+ * n_phases + 1 matrices.  Allocates and synchronises; moves no payload.  With the staggered schedule
+ * (TUNA_OPT_STAGGERED) the global radix of the plan is N.
+ */
+int tuna_debug_phase_sizes(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls,
+                           void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls,
+                           int P, int ranks_per_node, int local_radix, int global_radix, void* stream,
+                           int32_t* sizes, int capacity_phases);
+
+/*
  * Radix, mode and T layout for one GPU, from a cost model fitted to timed calls.  The paper picks r
  * from P and the block size because each of its K rounds pays a network latency (Section "Performance
  * analysis of TuNA", "Radix selection": small blocks -> r near 2, medium -> r near sqrt(P), large -> r

@@ -34,7 +34,7 @@ TUNA_MODE_AUTO, TUNA_MODE_STAGED, TUNA_MODE_FUSED = 0, 1, 2
 TUNA_T_SLOTS, TUNA_T_EXACT, TUNA_T_AUTO = 0, 1, 2
 
 EXPORTS = ("tuna_alltoallv", "tuna_alltoallv_hier", "tuna_alltoallv_noalloc", "tuna_alltoallv_ex", "tuna_alltoallv_init_ex",
-           "tuna_opts_init", "tuna_ctx_create", "tuna_ctx_destroy", "tuna_ctx_get_stats", "tuna_build_id", "tuna_workspace_bytes", "tuna_set_workspace",
+           "tuna_opts_init", "tuna_ctx_create", "tuna_ctx_destroy", "tuna_ctx_get_stats", "tuna_build_id", "tuna_debug_phase_sizes", "tuna_workspace_bytes", "tuna_set_workspace",
            "tuna_release", "tuna_set_option", "tuna_get_stats", "tuna_plan_info", "tuna_plan_phase",
            "tuna_t_index", "tuna_plan_phase_device", "tuna_plan_phase_sources", "tuna_plain_copy", "tuna_select", "tuna_predict_ms", "tuna_calibrate", "tuna_alltoallv_init", "tuna_start", "tuna_plan_free",
            "tuna_strerror", "tuna_version")
@@ -118,6 +118,7 @@ def load() -> ctypes.CDLL:
     lib.tuna_ctx_create.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
     lib.tuna_ctx_destroy.argtypes = [vp]
     lib.tuna_ctx_get_stats.argtypes = [vp, ctypes.POINTER(tuna_stats_t)]
+    lib.tuna_debug_phase_sizes.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, vp, i]
     lib.tuna_build_id.argtypes = []
     lib.tuna_build_id.restype = ctypes.c_char_p
     lib.tuna_alltoallv_init.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, ctypes.POINTER(ctypes.c_void_p)]
@@ -249,6 +250,20 @@ def tuna_alltoallv_init_ex(ctx, sendbuf, sendcounts, sdispls, recvbuf, recvcount
                                        ctypes.byref(opts) if opts is not None else None, _stream(stream),
                                        ctypes.byref(plan))
     return rc, plan.value
+
+
+def tuna_debug_phase_sizes(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P: int, ranks_per_node: int,
+                           local_radix: int, global_radix: int, n_phases: int, stream=None):
+    """Returns (code, sizes[n_phases + 1, P, P] int32): the device's block-size matrix before the first
+    phase and after every phase."""
+    import numpy as np
+    import torch
+    sizes = np.zeros((n_phases + 1, P, P), dtype=np.int32)
+    rc = load().tuna_debug_phase_sizes(_ptr(sendbuf), _ptr(sendcounts, torch.int32), _ptr(sdispls, torch.int64),
+                                       _ptr(recvbuf), _ptr(recvcounts, torch.int32), _ptr(rdispls, torch.int64),
+                                       P, ranks_per_node, local_radix, global_radix, _stream(stream),
+                                       sizes.ctypes.data, n_phases + 1)
+    return rc, sizes
 
 
 def tuna_build_id() -> str:

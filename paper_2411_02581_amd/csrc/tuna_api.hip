@@ -506,6 +506,7 @@ struct Prepared {
     StatusBufs sb;
     Ctx* ctx = nullptr;                 // where profiling marks go (none for the entry point that allocates nothing)
     Options opt;
+    int32_t* debug_sizes = nullptr;     // host [phases + 1][P][P]: the block-size matrix before the first phase and after every phase (verification)
     bool fused = false, staggered = false;
     int gran = 1;
     const void* sendbuf = nullptr;
@@ -679,6 +680,16 @@ void fill_stats_header(const Prepared& pr, const Status& hs, tuna_stats_t& st) {
     }
 }
 
+// Problems beyond the kernels' 32-bit arithmetic.  Block sizes are rounded up to chunks and lines in
+// int: the largest block must leave room for that.  Chunk prefixes are 32-bit per rank: what one rank
+// stages in a phase is bounded both by all chunks there are and by P blocks of at most M bytes.
+bool too_large(int P, const Status& hs) {
+    if (hs.max_count > INT_MAX - 256) return true;
+    const unsigned long long by_m = (unsigned long long)P * (unsigned long long)((hs.max_count + 15) / 16 + 1);
+    const unsigned long long by_all = hs.total_chunks + (unsigned long long)P;
+    return std::min(by_m, by_all) >= (1ull << 31);
+}
+
 // Validation + sizing pass of a call whose arguments, schedule and status buffers are in `pr` (one
 // read-back).  On TUNA_OK with *empty == true there is nothing to move.
 int prepare_sizes(Prepared& pr, int dense_option, hipStream_t s, Status& hs, bool* empty) {
@@ -692,8 +703,7 @@ int prepare_sizes(Prepared& pr, int dense_option, hipStream_t s, Status& hs, boo
     if (hs.flags & 1u) return TUNA_ERR_NEGATIVE_COUNT;
     if (hs.flags & 2u) return TUNA_ERR_COUNT_MISMATCH;
     if (hs.flags & 4u) return TUNA_ERR_ARG;                 // a non-empty block at a negative displacement
-    // the kernels round block sizes up to chunks and lines in 32-bit arithmetic
-    if (hs.max_count > INT_MAX - 256) return TUNA_ERR_TOO_LARGE;
+    if (too_large(P, hs)) return TUNA_ERR_TOO_LARGE;
     if (dense_option != 0 && has_t)
         pr.t_chunks = colour_classes(pr.dp->host, pr.fused, pr.staggered, pr.sb.h_status->cls_chunks, pr.cbase);
     pr.exact_kernels = choose_exact_t(dense_option, pr.dp->host, hs, pr.t_chunks);
@@ -701,13 +711,6 @@ int prepare_sizes(Prepared& pr, int dense_option, hipStream_t s, Status& hs, boo
     *empty = hs.total_bytes == 0;
     if (*empty) return TUNA_OK;
     if (!pr.sendbuf || !pr.recvbuf) return TUNA_ERR_ARG;
-    // chunk prefixes are 32-bit per rank: what one rank stages in a phase is bounded both by all
-    // chunks there are and by P blocks of at most M bytes
-    {
-        const unsigned long long by_m = (unsigned long long)P * (unsigned long long)((hs.max_count + 15) / 16 + 1);
-        if ((hs.total_chunks + (unsigned long long)P < by_m ? hs.total_chunks + (unsigned long long)P : by_m) >= (1ull << 31))
-            return TUNA_ERR_TOO_LARGE;
-    }
     const unsigned int abits = hs.align_bits | (unsigned int)((uintptr_t)pr.sendbuf & 127u) |
                                (unsigned int)((uintptr_t)pr.recvbuf & 127u);
     pr.gran = (abits & 127u) == 0 ? 128 : ((abits & 15u) == 0 ? 16 : ((abits & 3u) == 0 ? 4 : 1));
@@ -1159,10 +1162,12 @@ int plan_build_metadata(Plan* plan, void* meta, size_t mbytes, hipStream_t s, bo
     rc = launch_self_metadata(pr, s);
     if (rc != TUNA_OK) return rc;
     if (with_marks) mark(pr.ctx, s, kCatPrepare, -1);
+    if (pr.debug_sizes) HIPCHK(hipMemcpyAsync(pr.debug_sizes, cur, P2 * 4, hipMemcpyDeviceToHost, s));
     for (size_t i = 0; i < nph; ++i) {
         rc = launch_phase_metadata(pr, i, cur, nxt, plan->Ls[i], plan->Lr[i], plan->hop[i], s);
         if (rc != TUNA_OK) return rc;
         if (with_marks) mark(pr.ctx, s, kCatMeta, (int)i);
+        if (pr.debug_sizes) HIPCHK(hipMemcpyAsync(pr.debug_sizes + (i + 1) * P2, nxt, P2 * 4, hipMemcpyDeviceToHost, s));
         std::swap(cur, nxt);
     }
     // exact unit counts, bytes and staged chunks per phase: one read-back of the status block
@@ -1216,10 +1221,11 @@ int plan_launch_data(const Plan* plan, hipStream_t s) {
 
 int plan_create(Ctx& c, const Options& opt, const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls,
                 void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
-                hipStream_t s, Plan** out) {
+                hipStream_t s, Plan** out, int32_t* debug_sizes = nullptr) {
     Plan* plan = new Plan();
     plan->ctx = &c;
     Prepared& pr = plan->pr;
+    pr.debug_sizes = debug_sizes;
     Status hs{};
     c.profile = false;
     int rc = prepare_call(c, opt, sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node, rl, rg, s,
@@ -1727,6 +1733,21 @@ int tuna_alltoallv_init(const void* sendbuf, const int32_t* sendcounts, const in
                                   local_radix, global_radix, nullptr, stream, plan);
 }
 
+int tuna_debug_phase_sizes(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
+                           const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node,
+                           int local_radix, int global_radix, void* stream, int32_t* sizes, int capacity_phases) {
+    if (!sizes) return TUNA_ERR_ARG;
+    tuna_plan_info_t info;
+    int rc = tuna_plan_info(P, ranks_per_node, local_radix, global_radix, &info);
+    if (rc != TUNA_OK) return rc;
+    if (capacity_phases < info.n_phases + 1) return TUNA_ERR_ARG;
+    Plan* p = nullptr;
+    rc = plan_create(g, sh.defaults, sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node,
+                     local_radix, global_radix, (hipStream_t)stream, &p, sizes);
+    if (rc != TUNA_OK) return rc;
+    return tuna_plan_free(reinterpret_cast<tuna_plan_t>(p));     // waits for the device: the copies have arrived
+}
+
 int tuna_start(tuna_plan_t plan, void* stream) {
     if (!plan) return TUNA_ERR_ARG;
     const int rc = ensure_device();        // the plan's memory lives on the library's device
@@ -1805,6 +1826,7 @@ int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node, i
     const bool exact_t = choose_exact_t(o.t_layout, pl, *h_status, t_chunks) && pl.slots > 0;
     dp->complete = true;                                  // run_validate synchronised the stream the tables were built on
     if (h_status->flags & 1u) return TUNA_ERR_NEGATIVE_COUNT;
+    if (too_large(P, *h_status)) return TUNA_ERR_TOO_LARGE;
     const DataSizes ds = data_sizes_for(pl, h_status->max_count, h_status->total_chunks, fused, staggered,
                                         exact_t, t_chunks);
     Prepared pr;

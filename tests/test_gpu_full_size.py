@@ -289,6 +289,58 @@ def test_own_blocks_of_64_mebibytes(tuna):
         assert st.ms_self < 10.0
 
 
+def test_byte_granular_two_pass_all_modes(tuna):
+    """P = 512, byte-granular sizes 0..2047 (any alignment), 256 MiB of payload, radix 8 (three digit phases):
+    large enough for the two-pass form of an immediate call, in all four modes (three stages / one-kernel
+    phases x T in slots / in exact size); whole receive buffer against the oracle."""
+    P = 512
+    counts = wl.counts_uniform_bytes(P, 512, 2047)
+    lay = wl.make_layout(counts, gap=3)
+    assert lay.payload_bytes > 250 << 20
+    send_host = wl.payload_position_hash(5120, lay.send_bytes)
+    want = np.full(lay.recv_bytes, 0x3C, dtype=np.uint8)
+    assert oracle.alltoallv(send_host, lay.sendcounts, lay.sdispls, want, lay.recvcounts, lay.rdispls) == 0
+    want_dev = torch.from_numpy(want).to("cuda:0")
+    send = torch.from_numpy(send_host).to("cuda:0")
+    sc, sd, rc, rd = _upload(lay)
+    recv = torch.empty(lay.recv_bytes, dtype=torch.uint8, device="cuda:0")
+    for mode in (tuna.TUNA_MODE_STAGED, tuna.TUNA_MODE_FUSED):
+        for tl in (tuna.TUNA_T_SLOTS, tuna.TUNA_T_EXACT):
+            o = tuna.tuna_opts_init()
+            o.mode, o.t_layout = mode, tl
+            recv.fill_(0x3C)
+            print("byte-granular two-pass: mode %d, T layout %d" % (mode, tl), flush=True)
+            code = tuna.tuna_alltoallv_ex(None, send, sc, sd, recv, rc, rd, P, 0, 8, 8, o)
+            assert code == 0, tuna.tuna_strerror(code)
+            torch.cuda.synchronize()
+            assert torch.equal(recv, want_dev), (mode, tl)
+            st = tuna.tuna_get_stats()
+            assert (st.granularity, st.n_phases, st.dense_t) == (1, 3, tl)
+
+
+def test_counts_beyond_the_supported_range(tuna):
+    """Counts only, no payload: problems whose per-rank chunk prefix would not fit 32 bits, or whose largest
+    block leaves no room for rounding in 32-bit arithmetic, are refused with TUNA_ERR_TOO_LARGE by the
+    sizing query and by the call itself (before anything moves)."""
+    P = 4096
+    sc = torch.zeros((P, P), dtype=torch.int32, device="cuda:0")
+    sc[7, :] = 16 << 20            # one rank sends 4096 blocks of 16 MiB: 2^32 chunks, and P * (M / 16) = 2^32 too
+    rc, nbytes = tuna.tuna_workspace_bytes(sc, P, 0, 2, 2)
+    assert rc == tuna.TUNA_ERR_TOO_LARGE, tuna.tuna_strerror(rc)
+    sc[7, :] = 1 << 20             # the same shape sixteen times smaller is fine
+    rc, nbytes = tuna.tuna_workspace_bytes(sc, P, 0, 2, 2)
+    assert rc == 0 and nbytes > 0
+    P = 4
+    sc = torch.zeros((P, P), dtype=torch.int32, device="cuda:0")
+    sc[1, 2] = 2**31 - 100
+    rc, nbytes = tuna.tuna_workspace_bytes(sc, P, 0, 2, 2)
+    assert rc == tuna.TUNA_ERR_TOO_LARGE
+    sd = torch.zeros((P, P), dtype=torch.int64, device="cuda:0")
+    buf = torch.zeros(64, dtype=torch.uint8, device="cuda:0")
+    rc = tuna.tuna_alltoallv(buf, sc, sd, buf, sc.t().contiguous(), sd, P, 2, 0)
+    assert rc == tuna.TUNA_ERR_TOO_LARGE
+
+
 def test_many_ranks_small_blocks(tuna):
     """P = 8192 (67 million blocks of 0..60 bytes, 4-byte granular): flat with radix 2 (13 digit
     phases) and radix P, and 64 ranks per node x 128 nodes; whole result against the oracle."""
