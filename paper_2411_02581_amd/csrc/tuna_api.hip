@@ -755,6 +755,10 @@ int prepare_call(Ctx& c, const Options& opt, const void* sendbuf, const int32_t*
     return prepare_sizes(pr, opt.t_layout, s, hs, empty);
 }
 
+// One-kernel phases of problems whose blocks all fit into 64 bytes run k_hop_small (one thread per block)
+// instead of the byte-balanced engine.
+bool small_blocks(const Prepared& pr) { return pr.max_count > 0 && pr.max_count <= kSmallBlockBytes; }
+
 int launch_phase_metadata(const Prepared& pr, size_t i, const int32_t* cur, int32_t* nxt, const LayoutDev& Ls,
                           const LayoutDev& Lr, const HopDev& hop, hipStream_t s) {
     const PhaseHost& ph = pr.dp->host.phases[i];
@@ -784,6 +788,7 @@ int launch_phase_metadata(const Prepared& pr, size_t i, const int32_t* cur, int3
     ra.slots = pr.ds.slots; ra.slot_bytes = pr.ds.slot_bytes;
     ra.x = exact_t_of(pr, i);
     ra.hop = hop;
+    ra.exact_sizes = small_blocks(pr) ? 1 : 0;
     const dim3 grid((unsigned)((ph.nseg + 255) / 256), (unsigned)pr.P);
     if (pr.exact_kernels) hipLaunchKernelGGL(k_resolve_hop<true>, grid, dim3(256), 0, s, ra);
     else hipLaunchKernelGGL(k_resolve_hop<false>, grid, dim3(256), 0, s, ra);
@@ -792,6 +797,7 @@ int launch_phase_metadata(const Prepared& pr, size_t i, const int32_t* cur, int3
 }
 
 bool any_one_kernel_phase(const Prepared& pr) { return pr.fused || pr.staggered; }
+
 
 // Resolved addresses of a one-kernel phase: row stride and bytes.
 int hop_ld_for(int nseg) { return (nseg + 31) / 32 * 32; }
@@ -919,6 +925,14 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
             if (row_units * (size_t)pr.P < unit_cap) { launch_units = row_units; a.batch_rows = 1; }
         }
         int rc;
+        if (phase_is_one_kernel(pr, ph) && small_blocks(pr)) {
+            const dim3 grid((unsigned)((a.seg_hi - a.seg_lo + 255) / 256), (unsigned)pr.P);
+            if (pr.gran >= 4) hipLaunchKernelGGL(k_hop_small<4>, grid, dim3(256), 0, s, hop, pr.T, a.seg_lo, a.seg_hi);
+            else hipLaunchKernelGGL(k_hop_small<1>, grid, dim3(256), 0, s, hop, pr.T, a.seg_lo, a.seg_hi);
+            HIPCHK(hipGetLastError());
+            mark(pr.ctx, s, kCatPack, (int)i);
+            continue;
+        }
         if (phase_is_one_kernel(pr, ph)) {
             // one hop in one kernel: S / T of the sender -> R / the other copy of T at the receiver
             a.stage = nullptr; a.L = Lr; a.hop = hop;

@@ -961,6 +961,7 @@ struct ResolveArgs {
     long long slot_bytes;
     ExactT x;                           // T in exact size
     HopDev hop;
+    int exact_sizes;                    // 1: every size is the block's byte count (k_hop_small copies exactly that), also into T
 };
 
 template <bool DENSE>
@@ -999,13 +1000,52 @@ __global__ void __launch_bounds__(256) k_resolve_hop(const ResolveArgs a) {
         int sg = g + l; if (sg >= a.Q) sg -= a.Q;
         dst = (unsigned long long)(a.R + a.rdispls[(size_t)p * a.P + sn * a.Q + sg]);
     } else {
-        size = ((sz + 15) >> 4) << 4;    // T takes whole chunks
+        if (!a.exact_sizes) size = ((sz + 15) >> 4) << 4;    // T takes whole chunks
         if (DENSE)
             dst = (((unsigned long long)(a.x.tbase[(size_t)a.seg.dcls[s] * a.P + p] + (long long)a.x.tpre[(size_t)p * a.x.ld + s])) << 4) | kHopInT;
         else
             dst = (unsigned long long)(((long long)p * a.slots + sdst) * a.slot_bytes) | kHopInT | kHopFill;
     }
     a.hop.src[o] = src; a.hop.dst[o] = dst; a.hop.size[o] = size;
+}
+
+// ------------------------------------------------------------------------------------------
+// k_hop_small: a one-kernel phase whose blocks all fit into 64 bytes (Section "Performance analysis of
+// TuNA": the small-message regime, S of a few bytes).  The byte-balanced engine above cuts work into
+// 4 KiB units and searches a window of block boundaries per unit; with blocks of a few bytes that
+// search is most of the work.  Here one thread moves one block: it reads the block's resolved source,
+// destination and size (k_resolve_hop) and copies its at most 16 words (or 64 bytes).  Neighbouring
+// threads hold neighbouring blocks of one receiver, whose destinations are neighbours in R or T, so a
+// wave's stores fall into a few lines.  grid (ceil(segments / 256), P); a batch of rounds covers the
+// segments [seg_lo, seg_hi).
+// ------------------------------------------------------------------------------------------
+constexpr int kSmallBlockBytes = 64;
+template <int GRAN>
+__global__ void __launch_bounds__(256) k_hop_small(HopDev hop, unsigned char* T, int seg_lo, int seg_hi) {
+    const int s = seg_lo + blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= seg_hi) return;
+    const size_t o = (size_t)blockIdx.y * hop.ld + s;
+    const int size = hop.size[o];
+    if (size <= 0) return;
+    const unsigned long long hs = hop.src[o], hd = hop.dst[o];
+    const unsigned long long tb = (unsigned long long)T;
+    const unsigned char* src = reinterpret_cast<const unsigned char*>((hs & ~(kHopInT | kHopFill)) + ((hs & kHopInT) ? tb : 0ull));
+    unsigned char* dst = reinterpret_cast<unsigned char*>((hd & ~(kHopInT | kHopFill)) + ((hd & kHopInT) ? tb : 0ull));
+    if (GRAN >= 4) {
+        // all loads first, then all stores; `size` is the block's exact byte count (ResolveArgs.exact_sizes)
+        const uint32_t* s4 = reinterpret_cast<const uint32_t*>(src);
+        uint32_t* d4 = reinterpret_cast<uint32_t*>(dst);
+        const int n = min(size, kSmallBlockBytes) >> 2;
+        uint32_t w[kSmallBlockBytes / 4];
+#pragma unroll
+        for (int i = 0; i < kSmallBlockBytes / 4; ++i) w[i] = i < n ? s4[i] : 0u;
+#pragma unroll
+        for (int i = 0; i < kSmallBlockBytes / 4; ++i)
+            if (i < n) d4[i] = w[i];
+    } else {
+        const int n = min(size, kSmallBlockBytes);
+        for (int i = 0; i < n; ++i) dst[i] = src[i];
+    }
 }
 
 // Compiled for 8 waves per SIMD (a workgroup is one wave per SIMD).  The host lowers the number of

@@ -240,6 +240,36 @@ def test_degenerate_inputs(tuna):
     run_hier(tuna, prob, 2, 2, 2)
 
 
+@pytest.mark.parametrize("quantum", [1, 4, 8])
+def test_tiny_blocks(tuna, quantum):
+    """Blocks of at most 64 bytes (the small-message regime of Section "Performance analysis of TuNA"):
+    one-kernel phases move them with one thread per block.  Byte-, 4-byte- and 8-byte-granular sizes from 0
+    to 64, many of them empty; flat for several radices, hierarchical, in batches of rounds and with the
+    staggered inter-node schedule."""
+    P = 45
+    counts = (wl.counts_uniform_bytes(P, 91 + quantum, 64) // quantum * quantum).astype(np.int32)
+    counts[counts % 3 == 0] = 0
+    counts[7, 11] = 64
+    lay = wl.make_layout(counts, gap=quantum, align=quantum)
+    prob = Problem(lay, wl.payload_position_hash(17, lay.send_bytes))
+    for r in (2, 3, 7, 45):
+        run_flat(tuna, prob, r)
+        assert tuna.tuna_get_stats().max_block_bytes == 64
+    run_hier(tuna, prob, 9, 3, 2)
+    run_hier(tuna, prob, 5, 5, 9)
+    tuna.tuna_set_option(tuna.TUNA_OPT_BLOCK_COUNT, 2)
+    try:
+        run_flat(tuna, prob, 45)
+        run_hier(tuna, prob, 9, 3, 5)
+    finally:
+        tuna.tuna_set_option(tuna.TUNA_OPT_BLOCK_COUNT, 0)
+    tuna.tuna_set_option(tuna.TUNA_OPT_STAGGERED, 1)
+    try:
+        run_hier(tuna, prob, 9, 2, 5)
+    finally:
+        tuna.tuna_set_option(tuna.TUNA_OPT_STAGGERED, 0)
+
+
 def test_large_own_blocks(tuna):
     """Blocks a rank keeps for itself above 64 KiB go through the byte-balanced copy engine (one more
     one-kernel phase of one block per rank) instead of one workgroup per rank: byte-granular sizes of
