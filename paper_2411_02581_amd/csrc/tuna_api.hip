@@ -126,6 +126,8 @@ struct Ctx {
     hipEvent_t ev_end = nullptr;
     bool end_recorded = false;
     hipStream_t last_stream = nullptr;  // stream of the last immediate call (its end is ev_end when end_recorded)
+    unsigned char* tiny_t = nullptr;    // T of the one-kernel call for tiny problems (kTinyTBytes, allocated at its first use)
+    const void* tiny_declined = nullptr; // sendcounts of the last problem that kernel declined: it is not asked again for it
     const void* stats_plan = nullptr;   // the statistics on file belong to this persistent plan (payload bytes known)
 };
 
@@ -181,6 +183,7 @@ void free_ctx(Ctx& c) {
     if (c.sb.d_vpart) (void)hipFree(c.sb.d_vpart);
     if (c.meta) (void)hipFree(c.meta);
     if (c.data) (void)hipFree(c.data);
+    if (c.tiny_t) (void)hipFree(c.tiny_t);
     if (c.ev_end) (void)hipEventDestroy(c.ev_end);
     for (hipEvent_t e : c.ev_pool) (void)hipEventDestroy(e);
     c = Ctx{};
@@ -1038,11 +1041,77 @@ int run_once(Ctx& c, const Options& opt, const void* sendbuf, const int32_t* sen
              void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
              void* stream);
 
+// A whole call in one kernel launch (k_tiny_call) for problems of at most 64 ranks and 1 MiB of payload,
+// where a call costs what its launches cost: about thirty launches and a synchronisation become one
+// launch and a synchronisation.  Only when everything was left to the library (mode, no batches, no
+// staggering, no profiling).  *done = false: the kernel declined (invalid counts, or not that small) and
+// nothing has moved; the caller goes on with the general path.
+constexpr size_t kTinyTBytes = 4u << 20;
+int run_tiny(Ctx& c, const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls, void* recvbuf,
+             const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
+             hipStream_t s, bool* done) {
+    *done = false;
+    int Q = 0;
+    if (resolve_hierarchy(P, ranks_per_node, &Q) != TUNA_OK || rl < 2 || rg < 2) return TUNA_OK;   // the general path reports it
+    if (!sendbuf || !recvbuf || !sendcounts || !recvcounts || !sdispls || !rdispls) return TUNA_OK;
+    int rc = ensure_ctx(c);
+    if (rc != TUNA_OK) return rc;
+    DevicePlan* dp = nullptr;
+    rc = get_plan(P, Q, rl, rg, /*fused=*/true, s, &dp);
+    if (rc != TUNA_OK) return rc;
+    const PlanHost& pl = dp->host;
+    if ((int)pl.phases.size() > kTinyMaxPhases) return TUNA_OK;
+    if (!c.tiny_t) {
+        const hipError_t e = hipMalloc((void**)&c.tiny_t, kTinyTBytes);
+        if (e != hipSuccess) { (void)hipGetLastError(); c.tiny_t = nullptr; return TUNA_OK; }
+    }
+    if (c.end_recorded && c.last_stream != s) HIPCHK(hipStreamWaitEvent(s, c.ev_end, 0));
+    TinyArgs a{};
+    a.S = (const unsigned char*)sendbuf; a.sendcounts = sendcounts; a.sdispls = sdispls;
+    a.R = (unsigned char*)recvbuf; a.recvcounts = recvcounts; a.rdispls = rdispls;
+    a.P = P; a.Q = Q; a.N = P / Q; a.nph = (int)pl.phases.size();
+    for (int i = 0; i < a.nph; ++i) {
+        const SegDev& sd = dp->d_seg[i];
+        a.ph[i] = TinyPhase{sd.e, sd.z, sd.src, sd.dst, pl.phases[i].nseg, pl.phases[i].dim, (int)pl.phases[i].rx};
+    }
+    a.T = c.tiny_t; a.slots = pl.slots; a.t_capacity = kTinyTBytes; a.st = c.sb.d_status;
+    hipLaunchKernelGGL(k_tiny_call, dim3(1), dim3(kTinyThreads), 0, s, a);
+    HIPCHK(hipGetLastError());
+    HIPCHK(hipMemcpyAsync(c.sb.h_status, c.sb.d_status, 64, hipMemcpyDeviceToHost, s));
+    HIPCHK(hipStreamSynchronize(s));
+    if (dp->built_on == s) dp->complete = true;
+    const Status& hs = *c.sb.h_status;
+    if (!hs.tiny_done) return TUNA_OK;
+    // statistics: the schedule's numbers; nothing is timed
+    Prepared pr;
+    pr.P = P; pr.Q = Q; pr.N = P / Q; pr.dp = dp; pr.fused = true;
+    const unsigned int abits = hs.align_bits | (unsigned int)((uintptr_t)sendbuf & 127u) | (unsigned int)((uintptr_t)recvbuf & 127u);
+    pr.gran = (abits & 127u) == 0 ? 128 : ((abits & 15u) == 0 ? 16 : ((abits & 3u) == 0 ? 4 : 1));
+    c.marks.clear();
+    c.stats_plan = nullptr;
+    fill_stats_header(pr, hs, c.stats);
+    c.stats.temp_bytes = (int64_t)P * pl.slots * (((int64_t)hs.max_count + 15) / 16 * 16);
+    c.stats.workspace_bytes = (int64_t)kTinyTBytes;
+    c.end_recorded = false;
+    c.last_stream = s;
+    c.have_stats = true;
+    *done = true;
+    return TUNA_OK;
+}
+
 // An immediate call.  When the T layout was left to the library and exact-size T could not be
 // allocated, the call is made again with the paper's slots before it gives up (nothing has moved yet).
 int run(Ctx& c, const Options& opt, const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls,
         void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls, int P, int ranks_per_node, int rl, int rg,
         void* stream) {
+    if (P <= kTinyMaxRanks && opt.mode == TUNA_MODE_AUTO && opt.t_layout == TUNA_T_AUTO && !opt.staggered &&
+        !opt.block_count && !opt.profile && !c.user_ws && c.tiny_declined != (const void*)sendcounts) {
+        bool done = false;
+        const int trc = run_tiny(c, sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node, rl, rg,
+                                 (hipStream_t)stream, &done);
+        if (trc != TUNA_OK || done) return trc;
+        c.tiny_declined = sendcounts;
+    }
     int rc = run_once(c, opt, sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, ranks_per_node, rl, rg, stream);
     if (rc == TUNA_ERR_NOMEM && opt.t_layout == TUNA_T_AUTO && c.stats.dense_t) {
         Options o = opt;

@@ -41,7 +41,7 @@ struct Status {
                                    // bit 2: negative displacement of a non-empty block
     unsigned int align_bits;       // OR of all counts and displacements, low 7 bits (they decide the granularity)
     int max_count;                 // M
-    int reserved;
+    int tiny_done;                 // k_tiny_call: 1 = the whole call was done by that one kernel, 0 = it declined (nothing moved)
     unsigned long long total_bytes;    // sum of sendcounts
     unsigned long long total_chunks;   // sum of ceil(count / 16)
     unsigned long long send_extent;    // max over non-empty blocks of sdispls + count: bytes of sendbuf that hold blocks
@@ -1326,6 +1326,220 @@ k_copy(const CopyArgs a) {
         if (wend >= cend) break;
         sw += kWave;
         __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// k_tiny_call: a whole call in one kernel, for problems so small that launches, not bytes, are
+// what a call costs (Section "Performance analysis of TuNA": with tiny messages the number of rounds
+// decides; here the number of kernel launches does).  One workgroup of 1024 threads does what the
+// other kernels do between them, in the same order: the validation pass (counts >= 0, recvcounts ==
+// transpose(sendcounts), M, total), the index-only initial rotation (Algorithm "TuNA", lines 4-5), the
+// ranks' own blocks, then every digit phase: the metadata exchange (line 14: block sizes travel to the
+// receiver's size array, here both arrays are in LDS) and the hop of every moving block from where its
+// sender holds it (S, or its slot of T) to where its receiver keeps it (R at the slot of its source
+// rank, or its slot of T; lines 15-20).  T is the paper's B slots of M bytes per rank, laid out twice:
+// a phase reads one copy and writes the other (the copy is the parity of a block's hop count, folded
+// into the slot tables of the schedule), so no slot is read and written in one phase.  One wave moves
+// one block at a time; workgroup barriers separate the phases.
+// The kernel declines -- writes tiny_done = 0 and moves nothing -- when the counts are invalid or the
+// problem is not tiny after all (payload above kTinyMaxPayload, T above its capacity); the host then
+// takes the general path, which reports the error or does the work.
+// ------------------------------------------------------------------------------------------
+constexpr int kTinyMaxRanks = 64;
+constexpr int kTinyMaxPhases = 8;
+constexpr int kTinyThreads = 1024;
+constexpr unsigned long long kTinyMaxPayload = 1ull << 20;      // bytes
+struct TinyPhase {
+    const int32_t* e;
+    const int32_t* z;
+    const int32_t* src;
+    const int32_t* dst;
+    int nseg, dim, rx;
+};
+struct TinyArgs {
+    const unsigned char* S;
+    const int32_t* sendcounts;
+    const int64_t* sdispls;
+    unsigned char* R;
+    const int32_t* recvcounts;
+    const int64_t* rdispls;
+    int P, Q, N, nph;
+    TinyPhase ph[kTinyMaxPhases];
+    unsigned char* T;               // capacity t_capacity bytes
+    long long slots;                // T slots per rank (both copies)
+    unsigned long long t_capacity;
+    Status* st;
+};
+
+// one wave copies `n` bytes; dword granular when everything is 4-byte aligned, else byte by byte
+__device__ __forceinline__ void tiny_copy(unsigned char* dst, const unsigned char* src, int n, int lane) {
+    if ((((unsigned long long)dst | (unsigned long long)src | (unsigned long long)n) & 3ull) == 0) {
+        const uint32_t* s4 = reinterpret_cast<const uint32_t*>(src);
+        uint32_t* d4 = reinterpret_cast<uint32_t*>(dst);
+        for (int i = lane; i < (n >> 2); i += kWave) d4[i] = s4[i];
+    } else {
+        for (int i = lane; i < n; i += kWave) dst[i] = src[i];
+    }
+}
+
+__global__ void __launch_bounds__(kTinyThreads) k_tiny_call(const TinyArgs a) {
+    __shared__ int cur[kTinyMaxRanks * kTinyMaxRanks];
+    __shared__ int nxt[kTinyMaxRanks * kTinyMaxRanks];
+    __shared__ unsigned long long red[kTinyThreads / kWave][4];
+    __shared__ int verdict;
+    const int P = a.P, Q = a.Q, N = a.N;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    constexpr int kWaves = kTinyThreads / kWave;
+    // ---- validation ------------------------------------------------------------------------------------
+    unsigned int flags = 0, abits = 0;
+    int mx = 0;
+    unsigned long long bytes = 0, chunks = 0, extent = 0;
+    for (int k = tid; k < P * P; k += kTinyThreads) {
+        const int i = k / P, j = k - i * P;
+        int c = a.sendcounts[k];
+        if (c < 0) { flags |= 1u; c = 0; }
+        const int rc = a.recvcounts[(size_t)j * P + i];
+        if (rc < 0) flags |= 1u;
+        else if (rc != c) flags |= 2u;
+        const int64_t sd = a.sdispls[k], rd = a.rdispls[(size_t)j * P + i];
+        abits |= (unsigned int)c | ((unsigned int)sd & 127u) | ((unsigned int)rd & 127u);
+        if (c > 0) {
+            if (sd < 0 || rd < 0) flags |= 4u;
+            else extent = max(extent, (unsigned long long)sd + (unsigned long long)c);
+        }
+        mx = max(mx, c);
+        bytes += (unsigned long long)c;
+        chunks += (unsigned long long)((c + 15) >> 4);
+    }
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) {
+        flags |= __shfl_xor(flags, d, kWave);
+        abits |= __shfl_xor(abits, d, kWave);
+        mx = max(mx, __shfl_xor(mx, d, kWave));
+        bytes += __shfl_xor(bytes, d, kWave);
+        chunks += __shfl_xor(chunks, d, kWave);
+        extent = max(extent, (unsigned long long)__shfl_xor(extent, d, kWave));
+    }
+    if (lane == 0) {
+        red[wv][0] = ((unsigned long long)flags << 40) | ((unsigned long long)(abits & 127u) << 32) | (unsigned int)mx;
+        red[wv][1] = bytes; red[wv][2] = chunks; red[wv][3] = extent;
+    }
+    __syncthreads();
+    long long slot_bytes = 0;
+    if (tid == 0) {
+        unsigned int fl = 0, ab = 0;
+        int m = 0;
+        unsigned long long by = 0, ch = 0, ex = 0;
+        for (int w = 0; w < kWaves; ++w) {
+            fl |= (unsigned int)(red[w][0] >> 40); ab |= (unsigned int)(red[w][0] >> 32) & 127u;
+            m = max(m, (int)(unsigned int)(red[w][0] & 0xffffffffull));
+            by += red[w][1]; ch += red[w][2]; ex = max(ex, red[w][3]);
+        }
+        slot_bytes = ((long long)m + 15) / 16 * 16;
+        const unsigned long long t_need = (unsigned long long)P * (unsigned long long)a.slots * (unsigned long long)slot_bytes;
+        const bool ok = fl == 0 && by <= kTinyMaxPayload && t_need <= a.t_capacity;
+        a.st->flags = fl; a.st->align_bits = ab; a.st->max_count = m; a.st->total_bytes = by; a.st->total_chunks = ch;
+        a.st->send_extent = ex; a.st->t_chunks = 0; a.st->tiny_done = ok ? 1 : 0;
+        verdict = ok ? m : -1;
+    }
+    __syncthreads();
+    if (verdict < 0) return;                             // uniform: declined, nothing has moved
+    slot_bytes = ((long long)verdict + 15) / 16 * 16;
+    // ---- initial rotation (index only) and the ranks' own blocks -----------------------------------------
+    for (int k = tid; k < P * P; k += kTinyThreads) {
+        const int p = k / P, e = k - p * P;
+        const int n = p / Q, g = p - n * Q, j = e / Q, l = e - j * Q;
+        int dn = n - j; if (dn < 0) dn += N;
+        int dg = g - l; if (dg < 0) dg += Q;
+        cur[k] = max(a.sendcounts[(size_t)p * P + dn * Q + dg], 0);
+    }
+    for (int p = wv; p < P; p += kWaves) {
+        const size_t d = (size_t)p * P + p;
+        const int n = a.sendcounts[d];
+        if (n > 0) tiny_copy(a.R + a.rdispls[d], a.S + a.sdispls[d], n, lane);
+    }
+    __syncthreads();
+    // ---- digit phases ----------------------------------------------------------------------------------------
+    int* c0 = cur;
+    int* c1 = nxt;
+    for (int x = 0; x < a.nph; ++x) {
+        const TinyPhase ph = a.ph[x];
+        // metadata exchange: sizes that do not move are carried over, the others arrive from the sender
+        for (int k = tid; k < P * P; k += kTinyThreads) c1[k] = c0[k];
+        __syncthreads();
+        for (int k = tid; k < P * ph.nseg; k += kTinyThreads) {
+            const int q = k / ph.nseg, s = k - q * ph.nseg;
+            const int e = ph.e[s];
+            const int qn = q / Q, qg = q - qn * Q;
+            const int sender = partner_up(qn, qg, Q, N, ph.dim, ph.z[s] * ph.rx);
+            c1[q * P + e] = c0[sender * P + e];
+        }
+        __syncthreads();
+        // the hops.  Every thread resolves one block (source, destination, size) per round of 1024 blocks,
+        // all address loads of the workgroup in flight together; then the 64 blocks of a wave are copied four
+        // at a time, sixteen lanes each, the lanes fetching the block's description from the lane that
+        // resolved it.
+        for (int base = 0; base < P * ph.nseg; base += kTinyThreads) {
+            const int k = base + tid;
+            unsigned long long src = 0, dst = 0;
+            int size = 0;
+            if (k < P * ph.nseg) {
+                const int q = k / ph.nseg, s = k - q * ph.nseg;
+                const int e = ph.e[s];
+                size = c1[q * P + e];
+                if (size > 0) {
+                    const int qn = q / Q, qg = q - qn * Q;
+                    const int sender = partner_up(qn, qg, Q, N, ph.dim, ph.z[s] * ph.rx);
+                    const int j = e / Q, l = e - j * Q;
+                    const int ssrc = ph.src[s], sdst = ph.dst[s];
+                    if (ssrc < 0) {
+                        const int sn = sender / Q, sg = sender - sn * Q;
+                        int dn = sn - j; if (dn < 0) dn += N;
+                        int dg = sg - l; if (dg < 0) dg += Q;
+                        src = (unsigned long long)(a.S + a.sdispls[(size_t)sender * P + dn * Q + dg]);
+                    } else {
+                        src = (unsigned long long)(a.T + ((long long)sender * a.slots + ssrc) * slot_bytes);
+                    }
+                    if (sdst < 0) {
+                        int on = qn + j; if (on >= N) on -= N;
+                        int og = qg + l; if (og >= Q) og -= Q;
+                        dst = (unsigned long long)(a.R + a.rdispls[(size_t)q * P + on * Q + og]);
+                    } else {
+                        dst = (unsigned long long)(a.T + ((long long)q * a.slots + sdst) * slot_bytes);
+                    }
+                }
+            }
+            const unsigned long long any = __ballot(size > 0);
+            const int sub = lane & 15;
+            for (int g0 = 0; g0 < kWave; g0 += 4) {
+                if (!((any >> g0) & 0xfull)) continue;           // wave-uniform
+                const int it = g0 + (lane >> 4);
+                const unsigned long long bs = __shfl(src, it, kWave), bd = __shfl(dst, it, kWave);
+                const int bn = __shfl(size, it, kWave);
+                const unsigned char* sp = reinterpret_cast<const unsigned char*>(bs);
+                unsigned char* dp = reinterpret_cast<unsigned char*>(bd);
+                if (((bs | bd | (unsigned long long)bn) & 3ull) == 0) {
+                    const uint32_t* s4 = reinterpret_cast<const uint32_t*>(sp);
+                    uint32_t* d4 = reinterpret_cast<uint32_t*>(dp);
+                    const int nw = bn >> 2;
+                    for (int i = sub; i < nw; i += 64) {     // four independent words per step
+                        const uint32_t w0 = s4[i];
+                        const uint32_t w1 = i + 16 < nw ? s4[i + 16] : 0u;
+                        const uint32_t w2 = i + 32 < nw ? s4[i + 32] : 0u;
+                        const uint32_t w3 = i + 48 < nw ? s4[i + 48] : 0u;
+                        d4[i] = w0;
+                        if (i + 16 < nw) d4[i + 16] = w1;
+                        if (i + 32 < nw) d4[i + 32] = w2;
+                        if (i + 48 < nw) d4[i + 48] = w3;
+                    }
+                } else {
+                    for (int i = sub; i < bn; i += 16) dp[i] = sp[i];
+                }
+            }
+        }
+        __syncthreads();                                  // the blocks stored into T are read in a later phase
+        int* t = c0; c0 = c1; c1 = t;
     }
 }
 
