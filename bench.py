@@ -104,6 +104,10 @@ class Resident:
         self.recv = torch.empty(lay.recv_bytes, dtype=torch.uint8, device=dev)
         self.meta = [torch.from_numpy(a).to(dev) for a in (lay.sendcounts, lay.sdispls, lay.recvcounts, lay.rdispls)]
         self.max_block = int(counts.max()) if counts.size else 0
+        # device addresses and the stream resolved once: a timed call is the foreign call, not tensor checks
+        sc, sd, rc_, rd = self.meta
+        self.ptrs = [t.data_ptr() for t in (self.send, sc, sd, self.recv, rc_, rd)]
+        self.stream = torch.cuda.current_stream().cuda_stream
         torch.cuda.synchronize()
 
     def opts(self, mode=0, t_layout=2, staggered=0, block_count=0, profile=0):
@@ -112,8 +116,7 @@ class Resident:
         return o
 
     def call(self, rl, rg, o):
-        sc, sd, rc_, rd = self.meta
-        rc = self.tuna.tuna_alltoallv_ex(None, self.send, sc, sd, self.recv, rc_, rd, self.P, self.rpn, rl, rg, o)
+        rc = self.tuna.tuna_alltoallv_ex(None, *self.ptrs, self.P, self.rpn, rl, rg, o, self.stream)
         if rc != 0:
             raise RuntimeError("tuna_alltoallv_ex failed: " + self.tuna.tuna_strerror(rc))
 
@@ -168,7 +171,8 @@ class Resident:
                "temp_bytes": st.temp_bytes, "workspace_bytes": st.workspace_bytes, "exact_size_t": st.dense_t,
                "one_kernel_phases": st.fused, "profiled_ms_per_step": prof_total / self.steps,
                "metadata_ms_per_step": meta_ms / self.steps, "prepare_ms_per_step": prep_ms / self.steps,
-               "own_blocks_ms_per_step": self_ms / self.steps, "kernels": kernels, "granularity": st.granularity}
+               "own_blocks_ms_per_step": self_ms / self.steps, "kernels": kernels, "granularity": st.granularity,
+               "max_block_bytes": int(st.max_block_bytes)}
         print("[bench] %s: %.3f ms/step, %.1f GB/s effective; " % (label, ms_per_step, row["effective_GBs"]) +
               ", ".join("%s %.0f GB/s" % (k, v["achieved_GBs"]) for k, v in kernels.items()) +
               (" [one-kernel phases]" if st.fused else " [three stages]"), file=sys.stderr, flush=True)
@@ -236,8 +240,10 @@ def radices_of(cfg, P, override=""):
     return [("r=%d" % min(r, P), min(r, P), min(r, P)) for r in rs]
 
 
-def kernel_name(stage, gran, exact):
+def kernel_name(stage, gran, exact, max_block_bytes=None):
     et = "true" if exact else "false"
+    if stage == "hop" and max_block_bytes is not None and 0 < max_block_bytes <= 64:
+        return "tuna::k_hop_small<%d>" % (4 if gran >= 4 else 1)      # one thread per block when all blocks fit into 64 bytes
     return {"pack": "tuna::k_copy<0, %d, %s>" % (gran, et), "exchange": "tuna::k_copy<1, 16, false>",
             "unpack": "tuna::k_copy<2, %d, %s>" % (min(gran, 16), et), "hop": "tuna::k_copy<3, %d, %s>" % (gran, et)}[stage]
 
@@ -257,7 +263,7 @@ def roofline_of(rows, steps, traffic, copy_ceiling):
     if not tot:
         return None
     name, (ms, n, alg) = max(tot.items(), key=lambda kv: kv[1][0])
-    kname = kernel_name(name, rows[0]["granularity"], bool(rows[0]["exact_size_t"]))
+    kname = kernel_name(name, rows[0]["granularity"], bool(rows[0]["exact_size_t"]), rows[0].get("max_block_bytes"))
     achieved = alg / (ms * 1e-3) / 1e9
     tr = traffic.get("bytes_per_launch", {}).get(kname) if traffic else None
     return {"bound": "hbm", "kernel": kname, "stage": name, "achieved": achieved, "peak": HBM_PEAK_GBS,

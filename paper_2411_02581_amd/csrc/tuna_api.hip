@@ -78,6 +78,7 @@ void build_class_tables(const PlanHost& pl, std::vector<std::vector<int32_t>>& t
 struct StatusBufs {
     Status* d_status = nullptr;              // device status block
     Status* h_status = nullptr;              // host mirror (pinned for the library's own)
+    Status* h_status_dev = nullptr;          // the device's address of the pinned mirror (nullptr: not mapped)
     unsigned long long* d_vpart = nullptr;   // partial results of the validation pass, one row per workgroup
     int num_cus = 256;
 };
@@ -170,6 +171,10 @@ int ensure_ctx(Ctx& c) {
     c.sb.num_cus = sh.num_cus;
     HIPCHK(hipMalloc((void**)&c.sb.d_status, align_up(sizeof(Status))));
     HIPCHK(hipHostMalloc((void**)&c.sb.h_status, sizeof(Status), hipHostMallocDefault));
+    if (hipHostGetDevicePointer((void**)&c.sb.h_status_dev, c.sb.h_status, 0) != hipSuccess) {
+        (void)hipGetLastError();
+        c.sb.h_status_dev = nullptr;
+    }
     HIPCHK(hipMalloc((void**)&c.sb.d_vpart, align_up(vpart_words(c.sb.num_cus) * 8)));
     HIPCHK(hipEventCreate(&c.ev_end));
     std::memset(&c.stats, 0, sizeof(c.stats));
@@ -1074,10 +1079,13 @@ int run_tiny(Ctx& c, const void* sendbuf, const int32_t* sendcounts, const int64
         const SegDev& sd = dp->d_seg[i];
         a.ph[i] = TinyPhase{sd.e, sd.z, sd.src, sd.dst, pl.phases[i].nseg, pl.phases[i].dim, (int)pl.phases[i].rx};
     }
-    a.T = c.tiny_t; a.slots = pl.slots; a.t_capacity = kTinyTBytes; a.st = c.sb.d_status;
+    // the kernel writes its 64 bytes of status straight into the pinned host mirror: a copy command after it
+    // would cost a fifth of the whole call
+    a.T = c.tiny_t; a.slots = pl.slots; a.t_capacity = kTinyTBytes; a.st = c.sb.h_status_dev ? c.sb.h_status_dev : c.sb.d_status;
+    c.sb.h_status->tiny_done = 0;
     hipLaunchKernelGGL(k_tiny_call, dim3(1), dim3(kTinyThreads), 0, s, a);
     HIPCHK(hipGetLastError());
-    HIPCHK(hipMemcpyAsync(c.sb.h_status, c.sb.d_status, 64, hipMemcpyDeviceToHost, s));
+    if (!c.sb.h_status_dev) HIPCHK(hipMemcpyAsync(c.sb.h_status, c.sb.d_status, 64, hipMemcpyDeviceToHost, s));
     HIPCHK(hipStreamSynchronize(s));
     if (dp->built_on == s) dp->complete = true;
     const Status& hs = *c.sb.h_status;

@@ -1369,7 +1369,8 @@ struct TinyArgs {
     unsigned char* T;               // capacity t_capacity bytes
     long long slots;                // T slots per rank (both copies)
     unsigned long long t_capacity;
-    Status* st;
+    Status* st;                     // the first 64 bytes are written; in pinned host memory, so that the host reads
+                                    // them after the stream's synchronisation without a copy of its own
 };
 
 // one wave copies `n` bytes; dword granular when everything is 4-byte aligned, else byte by byte
