@@ -5,9 +5,11 @@
  * its hierarchical coalesced variant TuNA_l^g (Section "Hierarchical Tunable Non-uniform
  * All-to-all", Algorithm "Coalesced TuNA_l^g") for P *virtual ranks* whose send and receive
  * buffers all live in one GPU's memory.  Every digit phase is device work: metadata (block
- * size) exchange, size/displacement scan, gather-pack of the blocks whose base-r digit is
- * non-zero, the exchange as an HBM-to-HBM move of the packed messages, scatter-unpack into the
- * receive buffer R or the temporary buffer T.
+ * size) exchange, size/displacement scan, and the move of the blocks whose base-r digit is
+ * non-zero -- either as the paper's three steps (gather-pack, the exchange as an HBM-to-HBM move of
+ * the packed messages, scatter-unpack into the receive buffer R or the temporary buffer T) or, by
+ * default, as one hop per block straight from where its sender holds it to where its receiver
+ * keeps it.
  *
  * Conventions for every entry point
  *   - Pointers named `sendbuf`, `recvbuf`, `*counts`, `*displs`, `workspace` are DEVICE pointers.
@@ -133,6 +135,10 @@ typedef struct tuna_plan_info {
  * are done in two passes -- the block-size exchange and the scans of every phase first, a second
  * read-back of the phases' exact work-list lengths, then the payload kernels -- which costs one
  * more synchronisation and saves launching every copy kernel for an upper bound of work.
+ * Problems of at most 64 ranks, 1 MiB of payload and 8 digit phases are done by one kernel launch
+ * (validation, all phases and the own blocks in one workgroup; options at their defaults, no
+ * profiling): there the launches, not the bytes, are what a call costs.  It returns after that
+ * kernel has finished.
  */
 int tuna_alltoallv(const void* sendbuf, const int32_t* sendcounts, const int64_t* sdispls,
                    void* recvbuf, const int32_t* recvcounts, const int64_t* rdispls,
@@ -282,15 +288,20 @@ int tuna_release(void);
  * for hierarchical calls: after the intra-node phase every one of the Q (N - 1) blocks bound
  * for another node is its own message and goes straight from where it lies (its T slot, or S)
  * to R of its destination -- no rearrangement of T, no packing; the global radix is N.
- * TUNA_OPT_DENSE_T: 1 = T in exact size, 0 = T in the paper's slots, 2 (default) = exact size
- * unless the slots would be at least 90 % full (blocks of nearly one size), where the slot
- * arithmetic is just as dense and cheaper to address.  Exact size: Section "Estimating
- * temporary buffer size" bounds T by B slots of M bytes, M the largest block of all; with skewed
- * sizes nearly all of that is padding.  Here every block size is on the device before the first
- * round, so the blocks a rank stores into T in one phase can lie back to back (padded to 16
- * bytes) in an arena of that phase: T then takes sum over blocks of ceil(size / 16) * 16 *
- * (hops - 1) bytes plus 256 + 128 P bytes of rounding per phase, whatever M is (a block makes
- * one hop per non-zero digit of its rank distance and waits in T between hops).
+ * TUNA_OPT_DENSE_T: 1 = T in exact size, 0 = T in the paper's slots, 2 (default) = left to the
+ * library: slots when they would be at least 90 % full (blocks of nearly one size, where the slot
+ * arithmetic is just as dense and cheaper to address), else exact size when it is not the larger
+ * of the two or still fits into half of the free device memory, else slots.  Exact size: Section
+ * "Estimating temporary buffer size" bounds T by B slots of M bytes, M the largest block of all;
+ * with skewed sizes nearly all of that is padding.  Here every block size is on the device before
+ * the first round, so the blocks that wait in T lie back to back, each padded to 16 bytes.  A
+ * block stored in phase f and forwarded in phase y occupies T from f to y; the blocks of one
+ * (f, y) pair form a class whose size the validation pass sums, and classes whose waits do not
+ * overlap share memory (with one-kernel hops a phase must not store where it reads, so the
+ * classes a phase stores and the classes it forwards count as overlapping).  T then takes about
+ * the largest number of bytes that wait at one time (at most 1.12 times that on the benchmark
+ * workloads: 1.1 times the payload at r = 2 with three-stage phases, 1.7 times with one-kernel
+ * hops, less at larger radices), whatever M is.
  * TUNA_OPT_BLOCK_COUNT: k > 0 = at most k rounds of a digit phase are moved per set of kernel
  * launches, in ascending round order; 0 (default) = all rounds of a phase at once.  This is the
  * block_count of Algorithms "Staggered TuNA_l^g" and "Coalesced TuNA_l^g" (the number of
@@ -358,12 +369,14 @@ int tuna_debug_phase_sizes(const void* sendbuf, const int32_t* sendcounts, const
  * from P and the block size because each of its K rounds pays a network latency (Section "Performance
  * analysis of TuNA", "Radix selection": small blocks -> r near 2, medium -> r near sqrt(P), large -> r
  * near P).  In one HBM a round has no latency of its own; the model of an immediate call is
- *     ms = c0 + c1 * phases + c2 * P^2 / 1e6 + c3 * hop bytes / 1e9 + c4 * moving blocks / 1e6,
- * phases = digits of the two radices, hop bytes = payload bytes times the average number of hops of a
+ *     ms = c0 + c1 * phases + c2 * (phases + 1) * P^2 / 1e6 + c3 * hop bytes / 1e9 + c4 * moving blocks / 1e6,
+ * phases = digits of the two radices (every phase, and the validation, passes once over the P x P block sizes), hop bytes = payload bytes times the average number of hops of a
  * block (the share of rank distances whose digit is non-zero, summed over the digit positions), moving
  * blocks = the same count in blocks; one set of constants for three-stage phases and one for one-kernel
- * hops; T in the paper's slots adds to the byte term by how empty the slots are (mean block / M).
- *   tuna_calibrate   times about forty immediate calls of dense synthetic problems on the current
+ * hops; T in the paper's slots adds to the byte term by how empty the slots are (mean block / M).  When no
+ * block exceeds 64 bytes the one-kernel hops run a kernel of their own (one thread per block), whose
+ * blocks and bytes are priced by constants of their own, c5 and c6, in place of c4 and c3.
+ *   tuna_calibrate   times about fifty immediate calls of dense synthetic problems on the current
  *                    device (a few hundred milliseconds; allocates up to about 8 GiB and frees it;
  *                    synchronises) and fits the constants to them.  Without it the constants are the
  *                    built-in ones, fitted the same way on an MI355X.
@@ -377,7 +390,8 @@ int tuna_debug_phase_sizes(const void* sendbuf, const int32_t* sendcounts, const
  *                    one GPU is the linear schedule (r = Q, r = N) with one-kernel hops for every
  *                    payload; the function exists so that callers do not hard-code that, and so that
  *                    the model can be checked against measurements (the GPU tests do).
- * All three are host functions; only tuna_calibrate touches the GPU.
+ * All three are host functions; only tuna_calibrate touches the GPU.  The model covers calls that take
+ * the general path; the single-launch path of tuna_alltoallv for tiny problems is not modelled.
  */
 typedef struct tuna_choice {
     int32_t local_radix, global_radix;
@@ -388,6 +402,12 @@ typedef struct tuna_choice {
     double predicted_ms;     /* of one immediate call with this setting */
 } tuna_choice_t;
 int tuna_calibrate(void* stream);
+/* Host only: the model's constants for `mode` (TUNA_MODE_STAGED or TUNA_MODE_FUSED) as they stand -- built in,
+ * or fitted by tuna_calibrate: c[0..6] = c0 .. c6 above, c[7] = the factor on the byte term's share that
+ * passes through T in slots, per unit of emptiness, c[8] = the factor on the byte term of byte-granular
+ * problems.  capacity >= TUNA_MODEL_CONSTANTS. */
+#define TUNA_MODEL_CONSTANTS 9
+int tuna_model_constants(int mode, double* c, int capacity);
 int tuna_predict_ms(int P, int ranks_per_node, int local_radix, int global_radix, int mode, int t_layout,
                     int64_t payload_bytes, int64_t max_block_bytes, int granularity, double* ms);
 int tuna_select(int P, int ranks_per_node, int64_t payload_bytes, int64_t max_block_bytes, int granularity,

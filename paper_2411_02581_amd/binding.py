@@ -36,7 +36,7 @@ TUNA_T_SLOTS, TUNA_T_EXACT, TUNA_T_AUTO = 0, 1, 2
 EXPORTS = ("tuna_alltoallv", "tuna_alltoallv_hier", "tuna_alltoallv_noalloc", "tuna_alltoallv_ex", "tuna_alltoallv_init_ex",
            "tuna_opts_init", "tuna_ctx_create", "tuna_ctx_destroy", "tuna_ctx_get_stats", "tuna_build_id", "tuna_debug_phase_sizes", "tuna_workspace_bytes", "tuna_set_workspace",
            "tuna_release", "tuna_set_option", "tuna_get_stats", "tuna_plan_info", "tuna_plan_phase",
-           "tuna_t_index", "tuna_plan_phase_device", "tuna_plan_phase_sources", "tuna_plain_copy", "tuna_select", "tuna_predict_ms", "tuna_calibrate", "tuna_alltoallv_init", "tuna_start", "tuna_plan_free",
+           "tuna_t_index", "tuna_plan_phase_device", "tuna_plan_phase_sources", "tuna_plain_copy", "tuna_select", "tuna_predict_ms", "tuna_calibrate", "tuna_model_constants", "tuna_alltoallv_init", "tuna_start", "tuna_plan_free",
            "tuna_strerror", "tuna_version")
 
 
@@ -134,6 +134,7 @@ def load() -> ctypes.CDLL:
     lib.tuna_select.argtypes = [i, i, ctypes.c_int64, ctypes.c_int64, i, ctypes.POINTER(tuna_choice_t)]
     lib.tuna_predict_ms.argtypes = [i, i, i, i, i, i, ctypes.c_int64, ctypes.c_int64, i, ctypes.POINTER(ctypes.c_double)]
     lib.tuna_calibrate.argtypes = [vp]
+    lib.tuna_model_constants.argtypes = [i, ctypes.POINTER(ctypes.c_double), i]
     lib.tuna_plan_phase_device.argtypes = [i, i, i, i, i, vp, i]
     lib.tuna_plan_phase_sources.argtypes = [i, i, i, i, i, i, vp, i]
     lib.tuna_t_index.argtypes = [i, i]
@@ -366,6 +367,16 @@ def tuna_predict_ms(P: int, ranks_per_node: int, local_radix: int, global_radix:
 
 def tuna_calibrate(stream=None) -> int:
     return load().tuna_calibrate(_stream(stream))
+
+
+TUNA_MODEL_CONSTANTS = 9
+
+
+def tuna_model_constants(mode: int):
+    """Returns (code, [c0 .. c6, slot factor, byte-granular factor]) of the cost model for `mode`.  Host only."""
+    c = (ctypes.c_double * TUNA_MODEL_CONSTANTS)()
+    rc = load().tuna_model_constants(mode, c, TUNA_MODEL_CONSTANTS)
+    return rc, list(c)
 
 
 def tuna_plan_phase_device(P: int, ranks_per_node: int, local_radix: int, global_radix: int, phase: int, nseg: int):

@@ -268,7 +268,7 @@ DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long tot
     // t_chunks: exact-size T as the host laid it out (colour_classes)
     DataSizes d{};
     const bool any_phase = !pl.phases.empty() && total_chunks > 0;
-    // every rank's region of a staging buffer (and of an arena of T) is rounded up to a 128-byte line
+    // every rank's region of a staging buffer (and of a class of exact-size T) is rounded up to a 128-byte line
     const size_t rank_pad = (size_t)pl.P * kRankAlignChunks;
     d.stage_chunks = any_phase ? (size_t)total_chunks + rank_pad : 0;
     // fused rounds cut chunks at destination lines: up to one more chunk per moving block
@@ -531,7 +531,8 @@ struct Prepared {
     v4u* stage_r = nullptr;
     unsigned char* T = nullptr;
     // exact-size T: the prefix over the T-bound blocks (per phase, or one reused by every phase) and
-    // the per-phase position tables; the arenas are assigned on the device, phase by phase
+    // the per-phase position tables; the classes' places in T come from the host (colour_classes), the
+    // ranks' places inside a class are assigned on the device, phase by phase
     bool exact_t = false;               // T in exact size, and the schedule has T at all
     bool exact_kernels = false;         // T in exact size was asked for
     std::vector<int*> tpre;             // per phase: the blocks' offsets in message order (one array shared, or one each)
@@ -650,7 +651,7 @@ unsigned long long colour_classes(const PlanHost& pl, bool fused, bool staggered
 
 // T in exact size or in the paper's slots of M bytes.  Left to the library (option value 2), slots
 // are kept when they would be at least 90 % full -- blocks of (nearly) one size, where the slot
-// arithmetic is as dense as the arenas and cheaper to address.  Otherwise both footprints are known
+// arithmetic is as dense as exact size and cheaper to address.  Otherwise both footprints are known
 // from the validation pass: exact size is taken when it is not the larger one, or when it still fits
 // into half of the device memory that is free (it is the faster layout: dense writes and reads);
 // else the paper's slots.
@@ -984,7 +985,7 @@ bool use_two_pass(const PlanHost& pl, const Status& hs) {
 }
 
 // Metadata bytes of a one-pass call: the two size matrices, one pair of layouts reused by every phase,
-// the exact-size T tables and, for one-kernel phases, the transposed send displacements.
+// the exact-size T tables and, for one-kernel phases, the resolved source, destination and size of every block.
 size_t one_pass_meta_bytes(const Prepared& pr) {
     const int hld = max_hop_ld(pr);
     return meta_bytes_for(pr.P) + (pr.exact_t ? exact_t_meta_bytes_for(pr.dp->host, false) : 0) +
@@ -1277,7 +1278,7 @@ int plan_build_metadata(Plan* plan, void* meta, size_t mbytes, hipStream_t s, bo
         if (!phase_is_one_kernel(pr, pl.phases[i])) max_chunks = std::max(max_chunks, plan->phase_chunks[i]);
     }
     // payload memory: staging sized by the largest phase; T by M and the slot count, or -- exact
-    // size -- one arena per phase that holds just the blocks that phase stores into T
+    // size -- by the host's placement of the classes of waiting blocks (colour_classes)
     // (phase_chunks is the send side's total; the receive side holds the same blocks, but every rank's
     // region is rounded up to a line on its own, so its total may be up to one line per rank larger)
     *stage_bytes = max_chunks ? align_up(((size_t)max_chunks + (size_t)P * kRankAlignChunks) * 16) : 0;
@@ -1525,41 +1526,46 @@ int run_static(const void* sendbuf, const int32_t* sendcounts, const int64_t* sd
 // of its own; what a call costs is a fixed part, a part per digit phase (its launches), a part per entry
 // of the P x P matrices (validation, rotation), the bytes its hops move and a part per moving block
 // (metadata; the whole cost when blocks are tiny):
-//     ms = c0 + c1 * phases + c2 * P^2 / 1e6 + c3 * hop bytes / 1e9 + c4 * moving blocks / 1e6
+//     ms = c0 + c1 * phases + c2 * (phases + 1) * P^2 / 1e6 + c3 * hop bytes / 1e9 + c4 * moving blocks / 1e6
 // with hop bytes = sum over phases of the payload bytes that move, moving blocks likewise.  One set of
-// constants per mode (three-stage, one-kernel).  The built-in constants were fitted to immediate calls
-// on MI355X (the five benchmark configurations and uniform [0, S] sizes at P = 2048, S = 16 B .. 8 KiB:
-// worst relative error 15 %); tuna_calibrate replaces them by a fit to calls timed on the device at hand.
+// constants per mode (three-stage, one-kernel).  One-kernel phases of problems whose blocks all fit into
+// 64 bytes run another kernel (k_hop_small, one thread per block), whose blocks and bytes are priced by
+// constants of their own, c5 and c6, in place of c4 and c3.  The built-in constants were fitted to
+// immediate calls on MI355X by tuna_calibrate; calling it replaces them by a fit to calls timed on the
+// device at hand.
+constexpr int kModelTerms = 7;
+static_assert(kModelTerms + 2 == TUNA_MODEL_CONSTANTS, "tuna_model_constants reports the terms and the two factors");
 struct Model {
-    double c[5];
+    double c[kModelTerms];
 };
 struct ModelSet {
-    Model m[2] = {{{0.05969, 0.03001, 0.00676, 0.96579, 0.05007}},     // [0] three stages
-                  {{0.05776, 0.02737, 0.00586, 0.37560, 0.03834}}};    // [1] one-kernel hops
+    Model m[2] = {{{0.0445, 0.0364, 0.0065, 0.9976, 0.0459, 0.0, 0.0}},            // [0] three stages
+                  {{0.0471, 0.0301, 0.0077, 0.4068, 0.0245, 0.0128, 1.515}}};     // [1] one-kernel hops
     // T in the paper's slots of M bytes: the bytes that pass through T cost more the emptier the slots are
     // (sparse writes and reads): their share of the byte term is scaled by 1 + k * (1 - mean / M)
     double slot_penalty[2] = {0.25, 0.45};
     // byte-granular problems (some count, displacement or buffer address is not a multiple of 4) run the
     // kernel variants that load and store single bytes at block edges: their byte term is scaled by this
-    double byte_granular[2] = {2.2, 3.0};
+    double byte_granular[2] = {1.4, 2.1};
     bool calibrated = false;
 };
 ModelSet g_model;
 
 struct Features {
-    double phases, p2, hop_gb, mblocks, t_share;    // t_share: share of the hop bytes that is written to or read from T
+    double phases, p2, hop_gb, mblocks, msmall, small_gb, t_share;    // t_share: share of the hop bytes that is written to or read from T
 };
 
-Features features_of(const PlanHost& pl, double payload_bytes) {
+// small: the problem's one-kernel phases run k_hop_small (one-kernel mode and no block above 64 bytes)
+Features features_of(const PlanHost& pl, double payload_bytes, bool small) {
     Features f{};
     const double P = (double)pl.P;
     f.phases = (double)pl.phases.size();
-    f.p2 = P * P / 1e6;
+    f.p2 = (f.phases + 1.0) * P * P / 1e6;      // the passes over the P x P size matrix: one per phase, one for validation and rotation
     double moving = 0.0;
     for (const auto& ph : pl.phases) moving += (double)ph.nseg * P;
-    f.mblocks = moving / 1e6;
+    (small ? f.msmall : f.mblocks) = moving / 1e6;
     // sizes are taken to be independent of the rank distance: every slot index carries payload / P^2
-    f.hop_gb = P > 0 ? payload_bytes * (moving / (P * P)) / 1e9 : 0.0;
+    (small ? f.small_gb : f.hop_gb) = P > 0 ? payload_bytes * (moving / (P * P)) / 1e9 : 0.0;
     // a block of h hops passes through T h - 1 times: it is written there h - 1 times and read h - 1 times,
     // of 2 h accesses in all
     const double hops = P > 0 ? moving / P : 0.0;                    // sum over slot indices of their hops
@@ -1569,35 +1575,52 @@ Features features_of(const PlanHost& pl, double payload_bytes) {
 }
 
 double model_ms(const Model& m, const Features& f) {
-    return m.c[0] + m.c[1] * f.phases + m.c[2] * f.p2 + m.c[3] * f.hop_gb + m.c[4] * f.mblocks;
+    return m.c[0] + m.c[1] * f.phases + m.c[2] * f.p2 + m.c[3] * f.hop_gb + m.c[4] * f.mblocks + m.c[5] * f.msmall +
+           m.c[6] * f.small_gb;
 }
+
+// the model's byte term
+double bytes_ms(const Model& m, const Features& f) { return m.c[3] * f.hop_gb + m.c[6] * f.small_gb; }
+
+bool small_block_path(bool fused, int64_t max_block) { return fused && max_block > 0 && max_block <= kSmallBlockBytes; }
 
 double predict_ms(int P, int Q, int rl, int rg, bool fused, int t_layout, int64_t payload_bytes, int64_t max_block,
                   int granularity) {
     const PlanHost pl = make_plan(P, Q, rl, rg, false, /*with_tables=*/false);
-    Features f = features_of(pl, (double)payload_bytes);
+    Features f = features_of(pl, (double)payload_bytes, small_block_path(fused, max_block));
     const Model& m = g_model.m[fused ? 1 : 0];
     double ms = model_ms(m, f);
-    if (granularity > 0 && granularity < 4) ms += m.c[3] * f.hop_gb * (g_model.byte_granular[fused ? 1 : 0] - 1.0);
+    if (granularity > 0 && granularity < 4) ms += bytes_ms(m, f) * (g_model.byte_granular[fused ? 1 : 0] - 1.0);
     if (t_layout == TUNA_T_SLOTS && max_block > 0 && pl.slots > 0) {
         const double mean = (double)payload_bytes / ((double)P * (double)P);
         const double m128 = (double)((max_block + 127) / 128 * 128);
         const double empty = 1.0 - std::min(1.0, mean / m128);
-        ms += m.c[3] * f.hop_gb * f.t_share * g_model.slot_penalty[fused ? 1 : 0] * empty;
+        ms += bytes_ms(m, f) * f.t_share * g_model.slot_penalty[fused ? 1 : 0] * empty;
     }
     return ms;
 }
 
-// Least squares for the five constants from timed calls, weighted for relative error; a constant that
-// comes out negative is set to zero and the others are fitted again.
+// Least squares for the constants from timed calls, weighted for relative error; a constant that
+// comes out negative is set to zero and the others are fitted again.  A term that no call exercises
+// (the small-block term of the three-stage mode) is zero from the start.
 bool fit_model(const std::vector<Features>& X, const std::vector<double>& y, Model* out) {
-    const int n = 5;
-    bool fixed[n] = {false, false, false, false, false};
+    constexpr int n = kModelTerms;
+    bool fixed[n] = {};
+    auto row_of = [](const Features& f, double* row) {
+        row[0] = 1.0; row[1] = f.phases; row[2] = f.p2; row[3] = f.hop_gb; row[4] = f.mblocks; row[5] = f.msmall;
+        row[6] = f.small_gb;
+    };
+    for (int i = 0; i < n; ++i) {
+        bool used = false;
+        for (const Features& f : X) { double row[n]; row_of(f, row); used = used || row[i] != 0.0; }
+        fixed[i] = !used;
+    }
     for (int round = 0; round < n; ++round) {
         double A[n][n + 1] = {};
         for (size_t k = 0; k < X.size(); ++k) {
             const double w = 1.0 / (y[k] * y[k]);
-            const double row[n] = {1.0, X[k].phases, X[k].p2, X[k].hop_gb, X[k].mblocks};
+            double row[n];
+            row_of(X[k], row);
             for (int i = 0; i < n; ++i) {
                 if (fixed[i]) continue;
                 for (int j = 0; j < n; ++j)
@@ -1651,6 +1674,7 @@ int calibrate(hipStream_t s) {
     // tiny (fixed costs), many tiny blocks (per-block and per-entry costs), large blocks beyond the caches
     // (bytes), and a mix; S is 4 bytes off a multiple of 16, the usual alignment of float payloads
     const Problem problems[] = {{32, 68, {2, 6, 32}}, {1024, 20, {2, 32, 1024}}, {2048, 36, {8, 2048, 0}},
+                                {2048, 4, {2, 2048, 0}}, {1024, 60, {4, 1024, 0}},
                                 {512, 4100, {2, 23, 512}}, {2048, 260, {8, 2048, 0}}};
     size_t max_entries = 0, max_bytes = 0;
     for (const Problem& pb : problems) {
@@ -1705,7 +1729,7 @@ int calibrate(hipStream_t s) {
                 }
                 std::sort(t + 1, t + 4);
                 const PlanHost pl = make_plan(pb.P, pb.P, r, r, false, false);
-                (is_odd ? Xo : X)[fused].push_back(features_of(pl, (double)entries * pb.S));
+                (is_odd ? Xo : X)[fused].push_back(features_of(pl, (double)entries * pb.S, small_block_path(fused != 0, pb.S)));
                 (is_odd ? yo : y)[fused].push_back(t[2]);                // median of the three timed calls
             }
         }
@@ -1717,10 +1741,10 @@ int calibrate(hipStream_t s) {
         // the factor on the byte term that explains the byte-granular calls best (least squares)
         double num = 0.0, den = 0.0;
         for (size_t k = 0; k < Xo[fused].size(); ++k) {
-            const double bytes_ms = fitted.m[fused].c[3] * Xo[fused][k].hop_gb;
-            const double rest = model_ms(fitted.m[fused], Xo[fused][k]) - bytes_ms;
-            num += (yo[fused][k] - rest) * bytes_ms;
-            den += bytes_ms * bytes_ms;
+            const double bms = bytes_ms(fitted.m[fused], Xo[fused][k]);
+            const double rest = model_ms(fitted.m[fused], Xo[fused][k]) - bms;
+            num += (yo[fused][k] - rest) * bms;
+            den += bms * bms;
         }
         if (den > 0) fitted.byte_granular[fused] = std::max(1.0, num / den);
     }
@@ -2172,6 +2196,15 @@ int tuna_select(int P, int ranks_per_node, int64_t payload_bytes, int64_t max_bl
 }
 
 int tuna_calibrate(void* stream) { return calibrate((hipStream_t)stream); }
+
+int tuna_model_constants(int mode, double* c, int capacity) {
+    if (!c || capacity < TUNA_MODEL_CONSTANTS || (mode != TUNA_MODE_STAGED && mode != TUNA_MODE_FUSED)) return TUNA_ERR_ARG;
+    const int k = mode == TUNA_MODE_FUSED ? 1 : 0;
+    for (int i = 0; i < kModelTerms; ++i) c[i] = g_model.m[k].c[i];
+    c[kModelTerms] = g_model.slot_penalty[k];
+    c[kModelTerms + 1] = g_model.byte_granular[k];
+    return TUNA_OK;
+}
 
 int tuna_t_index(int o, int radix) {
     if (radix < 2) return -1;

@@ -21,7 +21,7 @@ constexpr int kWave = 64;
 constexpr int kCopyThreads = 256;                        // 4 waves, each an independent work unit
 constexpr int kChunksPerLane = 4;
 constexpr int kUnitChunks = kWave * kChunksPerLane;      // 256 chunks = 4 KiB per wave unit
-constexpr int kRankAlignChunks = 8;                      // every rank's region of a staging buffer or arena starts on a 128-byte line
+constexpr int kRankAlignChunks = 8;                      // every rank's region of a staging buffer or of a class of exact-size T starts on a 128-byte line
 constexpr int kScanThreads = 256;
 constexpr int kScanItems = 4;
 constexpr int kExchangeRanks = 8;                        // ranks per thread of the elementwise size kernels
@@ -851,7 +851,7 @@ struct CopyArgs {
     // other side: caller buffer + T (pack, unpack, fused source)
     const int32_t* counts;              // recvcounts: exact sizes of the blocks that are final (unpack, fused)
     unsigned char* user;                // S (pack) or R (unpack)
-    const int64_t* displs;              // sdispls (pack), rdispls (unpack), transposed sdispls (fused source)
+    const int64_t* displs;              // sdispls (pack), rdispls (unpack); unused when fused (k_resolve_hop read them)
     unsigned long long user_limit;      // pack: address one past the last byte of S that holds a block
     unsigned char* T;                   // temporary buffer: slot s of rank p at ((p*slots + s) * slot_bytes)
     long long slots;
@@ -861,7 +861,7 @@ struct CopyArgs {
     LayoutDev Ls;
     // fused: every block's source and destination, resolved by k_resolve_hop
     HopDev hop;
-    // exact-size T (DENSE kernels): one arena per phase instead of slots
+    // exact-size T (DENSE kernels): the blocks that wait in T lie back to back, class by class, instead of in slots
     ExactT x;
     // a launch may cover only the rounds of one batch: the segments [seg_lo, seg_hi) of every rank
     int seg_lo, seg_hi;
@@ -1286,7 +1286,7 @@ k_copy(const CopyArgs a) {
             if (act[k]) {
                 if (MODE == kUnpack || MODE == kFused) {
                     unsigned char* dst = reinterpret_cast<unsigned char*>(MODE == kFused ? oa2[k] : oa[k]);
-                    // with exact-size T whole chunks stream into R and the arenas (measured: +3 to +9 %);
+                    // with exact-size T whole chunks stream into R and into T (measured: +3 to +9 %);
                     // slots of M bytes are written through the cache, where the fill completes their lines,
                     // and telling the two apart per chunk costs more registers than it gains.  Byte-granular
                     // calls keep plain stores: the address may have any alignment.

@@ -2,7 +2,7 @@
 analysis of TuNA", "Radix selection": the paper's choice of r depends on P and the block size through the
 network latency of a round; in one HBM the same question is answered by a model fitted to measurements).
 
-tuna_calibrate fits the constants to about forty timed calls of dense equal-block problems; the tests
+tuna_calibrate fits the constants to about fifty timed calls of dense equal-block problems; the tests
 then time immediate calls of OTHER problems -- the benchmark configurations 2 to 5 and the paper's
 uniform [0, S] sizes at P = 2048 for S = 16 B, 512 B, 8 KiB -- over their radix sweeps, in both modes,
 and check two things: the predicted time of every setting lies within PREDICT_TOL of the measured one,

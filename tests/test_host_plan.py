@@ -268,6 +268,17 @@ def test_select_model():
     rc, even = tuna.tuna_predict_ms(256, 0, 256, 256, tuna.TUNA_MODE_FUSED, tuna.TUNA_T_EXACT, 32 << 20, 1024, 4)
     assert odd > even                                          # byte-granular kernels cost more per byte
     assert tuna.tuna_predict_ms(12, 0, 2, 2, 5, 0, 100)[0] == tuna.TUNA_ERR_ARG
+    # the constants are readable; blocks of at most 64 bytes are priced by their own constant in one-kernel mode
+    rc, cf = tuna.tuna_model_constants(tuna.TUNA_MODE_FUSED)
+    rc2, cs = tuna.tuna_model_constants(tuna.TUNA_MODE_STAGED)
+    assert rc == 0 and rc2 == 0 and len(cf) == 9 and all(v >= 0 for v in cf + cs)
+    assert cs[3] > 2 * cf[3] and cs[5] == 0 and cs[6] == 0 and 0 < cf[5] < cf[4] and cf[6] > cf[3]
+    assert tuna.tuna_model_constants(tuna.TUNA_MODE_AUTO)[0] == tuna.TUNA_ERR_ARG
+    P, payload = 2048, 32 << 20
+    rc, tiny_blocks = tuna.tuna_predict_ms(P, 0, P, P, tuna.TUNA_MODE_FUSED, tuna.TUNA_T_EXACT, payload, 16, 4)
+    rc, larger_blocks = tuna.tuna_predict_ms(P, 0, P, P, tuna.TUNA_MODE_FUSED, tuna.TUNA_T_EXACT, payload, 80, 4)
+    moving, gb = P * (P - 1) / 1e6, payload * (P - 1) / P / 1e9
+    assert abs((larger_blocks - tiny_blocks) - ((cf[4] - cf[5]) * moving + (cf[3] - cf[6]) * gb)) < 1e-9
 
 
 def test_random_schedules_deliver_every_block():
