@@ -591,15 +591,17 @@ bool phase_is_one_kernel(const Prepared& pr, const PhaseHost& ph) {
 // line of rounding per rank, and it is alive from the kernel that stores it to the kernel that reads it:
 // with three stages from the unpack of phase f to the pack of phase y, with one-kernel phases from the
 // kernel of phase f to the kernel of phase y (which reads it while it stores the classes (y, .), so those
-// must lie elsewhere).  Every class is placed at the lowest offset where it overlaps no class alive at
-// the same time (first fit).  Returns the chunks of T; cbase[class] = first chunk.
-unsigned long long colour_classes(const PlanHost& pl, bool fused, bool staggered, const unsigned long long* cls_chunks,
-                                  std::vector<long long>& cbase) {
+// must lie elsewhere).  A phase run in batches of rounds (`batched`) is like a one-kernel phase in this
+// respect: the unpack of its first batch stores while the pack of its next batch still has to read.
+// Every class is placed at the lowest offset where it overlaps no class alive at the same time (first
+// fit).  Returns the chunks of T; cbase[class] = first chunk.
+unsigned long long colour_classes(const PlanHost& pl, bool fused, bool staggered, bool batched,
+                                  const unsigned long long* cls_chunks, std::vector<long long>& cbase) {
     const int nph = (int)pl.phases.size();
     struct Item { int cid, start, end; unsigned long long cap; long long off; };
     std::vector<Item> items;
     for (int f = 0; f < nph; ++f) {
-        const bool one_kernel = fused || (staggered && pl.phases[f].dim == 1);
+        const bool one_kernel = fused || batched || (staggered && pl.phases[f].dim == 1);
         for (int y = f + 1; y < nph; ++y) {
             const int cid = class_id(f, y, nph);
             if (!cls_chunks[cid]) continue;
@@ -714,7 +716,7 @@ int prepare_sizes(Prepared& pr, int dense_option, hipStream_t s, Status& hs, boo
     if (hs.flags & 4u) return TUNA_ERR_ARG;                 // a non-empty block at a negative displacement
     if (too_large(P, hs)) return TUNA_ERR_TOO_LARGE;
     if (dense_option != 0 && has_t)
-        pr.t_chunks = colour_classes(pr.dp->host, pr.fused, pr.staggered, pr.sb.h_status->cls_chunks, pr.cbase);
+        pr.t_chunks = colour_classes(pr.dp->host, pr.fused, pr.staggered, pr.block_count > 0, pr.sb.h_status->cls_chunks, pr.cbase);
     pr.exact_kernels = choose_exact_t(dense_option, pr.dp->host, hs, pr.t_chunks);
     pr.exact_t = pr.exact_kernels && has_t;
     *empty = hs.total_bytes == 0;
@@ -804,8 +806,6 @@ int launch_phase_metadata(const Prepared& pr, size_t i, const int32_t* cur, int3
     HIPCHK(hipGetLastError());
     return TUNA_OK;
 }
-
-bool any_one_kernel_phase(const Prepared& pr) { return pr.fused || pr.staggered; }
 
 
 // Resolved addresses of a one-kernel phase: row stride and bytes.
@@ -1937,7 +1937,7 @@ int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node, i
     const Status* h_status = g.sb.h_status;
     std::vector<long long> cbase;
     const unsigned long long t_chunks = (o.t_layout != 0 && pl.slots > 0)
-        ? colour_classes(pl, fused, staggered, h_status->cls_chunks, cbase) : 0;
+        ? colour_classes(pl, fused, staggered, o.block_count > 0, h_status->cls_chunks, cbase) : 0;
     const bool exact_t = choose_exact_t(o.t_layout, pl, *h_status, t_chunks) && pl.slots > 0;
     dp->complete = true;                                  // run_validate synchronised the stream the tables were built on
     if (h_status->flags & 1u) return TUNA_ERR_NEGATIVE_COUNT;

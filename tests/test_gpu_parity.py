@@ -503,7 +503,10 @@ def test_temporary_buffer_too_large_is_an_error_not_a_crash(tuna, mode):
 
 
 @pytest.mark.parametrize("P,Q,rl,rg,cfg,k", [(64, 0, 64, 64, 2, 1), (64, 0, 64, 64, 2, 7), (100, 0, 10, 10, 4, 3),
-                                              (96, 8, 8, 12, 3, 2), (96, 8, 3, 12, 2, 100), (30, 0, 2, 2, 2, 1)])
+                                              (96, 8, 8, 12, 3, 2), (96, 8, 3, 12, 2, 100), (30, 0, 2, 2, 2, 1),
+                                              # several batches per phase and several phases whose waiting blocks share T:
+                                              # a batch stores into T while the next batch of the same phase still reads
+                                              (24, 2, 2, 3, 4, 1), (81, 0, 3, 3, 4, 1), (125, 0, 5, 5, 3, 2)])
 def test_block_count_batches_move_the_same_bytes(tuna, P, Q, rl, rg, cfg, k, mode):
     """Rounds moved in batches of k (block_count; with r = P the scattered linear algorithm): the
     result is the same as with all rounds of a phase at once."""
