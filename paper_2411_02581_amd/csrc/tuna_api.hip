@@ -1084,7 +1084,15 @@ int run_tiny(Ctx& c, const void* sendbuf, const int32_t* sendcounts, const int64
     // would cost a fifth of the whole call
     a.T = c.tiny_t; a.slots = pl.slots; a.t_capacity = kTinyTBytes; a.st = c.sb.h_status_dev ? c.sb.h_status_dev : c.sb.d_status;
     c.sb.h_status->tiny_done = 0;
-    hipLaunchKernelGGL(k_tiny_call, dim3(1), dim3(kTinyThreads), 0, s, a);
+    // the kernel keeps the size and displacement matrices and every phase's tables in LDS: more than the
+    // 64 KiB a kernel may use without asking
+    int table_entries = 0;
+    for (int i = 0; i < a.nph; ++i) table_entries += pl.phases[i].nseg;
+    const size_t lds = tiny_lds_bytes(P, table_entries);
+    static const hipError_t lds_allowed = hipFuncSetAttribute(reinterpret_cast<const void*>(k_tiny_call),
+        hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiny_lds_bytes(kTinyMaxRanks, kTinyMaxPhases * kTinyMaxRanks));
+    if (lds_allowed != hipSuccess) { (void)hipGetLastError(); return TUNA_OK; }     // the general path does the call
+    hipLaunchKernelGGL(k_tiny_call, dim3(1), dim3(kTinyThreads), lds, s, a);
     HIPCHK(hipGetLastError());
     if (!c.sb.h_status_dev) HIPCHK(hipMemcpyAsync(c.sb.h_status, c.sb.d_status, 64, hipMemcpyDeviceToHost, s));
     HIPCHK(hipStreamSynchronize(s));

@@ -1336,15 +1336,21 @@ k_copy(const CopyArgs a) {
 // other kernels do between them, in the same order: the validation pass (counts >= 0, recvcounts ==
 // transpose(sendcounts), M, total), the index-only initial rotation (Algorithm "TuNA", lines 4-5), the
 // ranks' own blocks, then every digit phase: the metadata exchange (line 14: block sizes travel to the
-// receiver's size array, here both arrays are in LDS) and the hop of every moving block from where its
-// sender holds it (S, or its slot of T) to where its receiver keeps it (R at the slot of its source
-// rank, or its slot of T; lines 15-20).  T is the paper's B slots of M bytes per rank, laid out twice:
-// a phase reads one copy and writes the other (the copy is the parity of a block's hop count, folded
-// into the slot tables of the schedule), so no slot is read and written in one phase.  One wave moves
-// one block at a time; workgroup barriers separate the phases.
-// The kernel declines -- writes tiny_done = 0 and moves nothing -- when the counts are invalid or the
-// problem is not tiny after all (payload above kTinyMaxPayload, T above its capacity); the host then
-// takes the general path, which reports the error or does the work.
+// receiver's size array) and the hop of every moving block from where its sender holds it (S, or its
+// slot of T) to where its receiver keeps it (R at the slot of its source rank, or its slot of T; lines
+// 15-20).  T is the paper's B slots of M bytes per rank, laid out twice: a phase reads one copy and
+// writes the other (the copy is the parity of a block's hop count, folded into the slot tables of the
+// schedule), so no slot is read and written in one phase.  Sixteen lanes move one block at a time;
+// workgroup barriers separate the phases.
+// What a phase needs besides the payload is read from global memory once, at the start, all loads in
+// flight together, and kept in LDS: both size matrices, the low 32 bits of both displacement
+// matrices and the tables of every phase.  A phase then costs one round trip to memory -- the
+// payload's -- instead of four dependent ones (tables, sizes, displacements, payload).
+// The kernel declines -- writes tiny_done = 0 and moves nothing -- when the counts are invalid, when
+// the problem is not tiny after all (payload above kTinyMaxPayload, T above its capacity) or when a
+// displacement of a non-empty block does not fit into 32 bits; the host then takes the general path,
+// which reports the error or does the work.
+// Dynamic LDS: tiny_lds_bytes(P, total table entries).
 // ------------------------------------------------------------------------------------------
 constexpr int kTinyMaxRanks = 64;
 constexpr int kTinyMaxPhases = 8;
@@ -1373,6 +1379,11 @@ struct TinyArgs {
                                     // them after the stream's synchronisation without a copy of its own
 };
 
+// four P x P arrays of 4 bytes (two size matrices, two displacement matrices) and four ints per table entry
+inline size_t tiny_lds_bytes(int P, int table_entries) {
+    return ((size_t)4 * P * P + (size_t)4 * table_entries) * 4;
+}
+
 // one wave copies `n` bytes; dword granular when everything is 4-byte aligned, else byte by byte
 __device__ __forceinline__ void tiny_copy(unsigned char* dst, const unsigned char* src, int n, int lane) {
     if ((((unsigned long long)dst | (unsigned long long)src | (unsigned long long)n) & 3ull) == 0) {
@@ -1385,33 +1396,58 @@ __device__ __forceinline__ void tiny_copy(unsigned char* dst, const unsigned cha
 }
 
 __global__ void __launch_bounds__(kTinyThreads) k_tiny_call(const TinyArgs a) {
-    __shared__ int cur[kTinyMaxRanks * kTinyMaxRanks];
-    __shared__ int nxt[kTinyMaxRanks * kTinyMaxRanks];
+    extern __shared__ __align__(16) int tiny_lds[];
     __shared__ unsigned long long red[kTinyThreads / kWave][4];
     __shared__ int verdict;
-    const int P = a.P, Q = a.Q, N = a.N;
+    const int P = a.P, Q = a.Q, N = a.N, P2 = P * P;
+    int* cur = tiny_lds;                                            // [P][P] sizes by slot index (the rotation's result)
+    int* nxt = cur + P2;
+    unsigned int* sd32 = reinterpret_cast<unsigned int*>(nxt + P2); // [P][P] sdispls, low 32 bits
+    unsigned int* rd32 = sd32 + P2;                                 // [P][P] rdispls, low 32 bits
+    int* tab = reinterpret_cast<int*>(rd32 + P2);                   // per phase: e[nseg], z[nseg], src[nseg], dst[nseg]
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     constexpr int kWaves = kTinyThreads / kWave;
-    // ---- validation ------------------------------------------------------------------------------------
+    // ---- the tables of every phase: requested first, so that they travel together with the matrices ------
+    {
+        int off = 0;
+        for (int x = 0; x < a.nph; ++x) {
+            const TinyPhase& ph = a.ph[x];
+            for (int k = tid; k < 4 * ph.nseg; k += kTinyThreads) {
+                const int f = k / ph.nseg, s_ = k - f * ph.nseg;
+                const int32_t* srcp = f == 0 ? ph.e : (f == 1 ? ph.z : (f == 2 ? ph.src : ph.dst));
+                tab[off + k] = srcp[s_];
+            }
+            off += 4 * ph.nseg;
+        }
+    }
+    // ---- validation, and the initial rotation (index only) on the way ---------------------------------------
     unsigned int flags = 0, abits = 0;
     int mx = 0;
     unsigned long long bytes = 0, chunks = 0, extent = 0;
-    for (int k = tid; k < P * P; k += kTinyThreads) {
+    for (int k = tid; k < P2; k += kTinyThreads) {
         const int i = k / P, j = k - i * P;
         int c = a.sendcounts[k];
-        if (c < 0) { flags |= 1u; c = 0; }
         const int rc = a.recvcounts[(size_t)j * P + i];
+        const int64_t sd = a.sdispls[k], rd = a.rdispls[(size_t)j * P + i];
+        if (c < 0) { flags |= 1u; c = 0; }
         if (rc < 0) flags |= 1u;
         else if (rc != c) flags |= 2u;
-        const int64_t sd = a.sdispls[k], rd = a.rdispls[(size_t)j * P + i];
         abits |= (unsigned int)c | ((unsigned int)sd & 127u) | ((unsigned int)rd & 127u);
         if (c > 0) {
             if (sd < 0 || rd < 0) flags |= 4u;
             else extent = max(extent, (unsigned long long)sd + (unsigned long long)c);
+            if (((unsigned long long)sd | (unsigned long long)rd) >> 32) flags |= 8u;      // not an error: beyond this kernel
         }
         mx = max(mx, c);
         bytes += (unsigned long long)c;
         chunks += (unsigned long long)((c + 15) >> 4);
+        // rank i = (n, g) holds its block for rank j = (jn, jg) at the slot index of their distance
+        const int n = i / Q, g = i - n * Q, jn = j / Q, jg = j - jn * Q;
+        int dj = n - jn; if (dj < 0) dj += N;
+        int dl = g - jg; if (dl < 0) dl += Q;
+        cur[i * P + dj * Q + dl] = c;
+        sd32[k] = (unsigned int)sd;
+        rd32[j * P + i] = (unsigned int)rd;
     }
 #pragma unroll
     for (int d = kWave / 2; d > 0; d >>= 1) {
@@ -1440,103 +1476,103 @@ __global__ void __launch_bounds__(kTinyThreads) k_tiny_call(const TinyArgs a) {
         slot_bytes = ((long long)m + 15) / 16 * 16;
         const unsigned long long t_need = (unsigned long long)P * (unsigned long long)a.slots * (unsigned long long)slot_bytes;
         const bool ok = fl == 0 && by <= kTinyMaxPayload && t_need <= a.t_capacity;
-        a.st->flags = fl; a.st->align_bits = ab; a.st->max_count = m; a.st->total_bytes = by; a.st->total_chunks = ch;
+        a.st->flags = fl & 7u; a.st->align_bits = ab; a.st->max_count = m; a.st->total_bytes = by; a.st->total_chunks = ch;
         a.st->send_extent = ex; a.st->t_chunks = 0; a.st->tiny_done = ok ? 1 : 0;
         verdict = ok ? m : -1;
     }
     __syncthreads();
     if (verdict < 0) return;                             // uniform: declined, nothing has moved
     slot_bytes = ((long long)verdict + 15) / 16 * 16;
-    // ---- initial rotation (index only) and the ranks' own blocks -----------------------------------------
-    for (int k = tid; k < P * P; k += kTinyThreads) {
-        const int p = k / P, e = k - p * P;
-        const int n = p / Q, g = p - n * Q, j = e / Q, l = e - j * Q;
-        int dn = n - j; if (dn < 0) dn += N;
-        int dg = g - l; if (dg < 0) dg += Q;
-        cur[k] = max(a.sendcounts[(size_t)p * P + dn * Q + dg], 0);
-    }
+    // ---- the ranks' own blocks ---------------------------------------------------------------------------------
     for (int p = wv; p < P; p += kWaves) {
-        const size_t d = (size_t)p * P + p;
-        const int n = a.sendcounts[d];
-        if (n > 0) tiny_copy(a.R + a.rdispls[d], a.S + a.sdispls[d], n, lane);
+        const int n = cur[p * P];                        // slot index 0: the block a rank keeps
+        if (n > 0) tiny_copy(a.R + rd32[p * P + p], a.S + sd32[p * P + p], n, lane);
     }
-    __syncthreads();
     // ---- digit phases ----------------------------------------------------------------------------------------
     int* c0 = cur;
     int* c1 = nxt;
+    int off = 0;
     for (int x = 0; x < a.nph; ++x) {
-        const TinyPhase ph = a.ph[x];
+        const int nseg = a.ph[x].nseg, dim = a.ph[x].dim, rx = a.ph[x].rx;
+        const int* te = tab + off;
+        const int* tz = te + nseg;
+        const int* ts = tz + nseg;
+        const int* td = ts + nseg;
+        off += 4 * nseg;
         // metadata exchange: sizes that do not move are carried over, the others arrive from the sender
-        for (int k = tid; k < P * P; k += kTinyThreads) c1[k] = c0[k];
+        for (int k = tid; k < P2; k += kTinyThreads) c1[k] = c0[k];
         __syncthreads();
-        for (int k = tid; k < P * ph.nseg; k += kTinyThreads) {
-            const int q = k / ph.nseg, s = k - q * ph.nseg;
-            const int e = ph.e[s];
+        for (int k = tid; k < P * nseg; k += kTinyThreads) {
+            const int q = k / nseg, s = k - q * nseg;
+            const int e = te[s];
             const int qn = q / Q, qg = q - qn * Q;
-            const int sender = partner_up(qn, qg, Q, N, ph.dim, ph.z[s] * ph.rx);
+            const int sender = partner_up(qn, qg, Q, N, dim, tz[s] * rx);
             c1[q * P + e] = c0[sender * P + e];
         }
         __syncthreads();
-        // the hops.  Every thread resolves one block (source, destination, size) per round of 1024 blocks,
-        // all address loads of the workgroup in flight together; then the 64 blocks of a wave are copied four
-        // at a time, sixteen lanes each, the lanes fetching the block's description from the lane that
-        // resolved it.
-        for (int base = 0; base < P * ph.nseg; base += kTinyThreads) {
-            const int k = base + tid;
-            unsigned long long src = 0, dst = 0;
-            int size = 0;
-            if (k < P * ph.nseg) {
-                const int q = k / ph.nseg, s = k - q * ph.nseg;
-                const int e = ph.e[s];
-                size = c1[q * P + e];
-                if (size > 0) {
-                    const int qn = q / Q, qg = q - qn * Q;
-                    const int sender = partner_up(qn, qg, Q, N, ph.dim, ph.z[s] * ph.rx);
-                    const int j = e / Q, l = e - j * Q;
-                    const int ssrc = ph.src[s], sdst = ph.dst[s];
-                    if (ssrc < 0) {
-                        const int sn = sender / Q, sg = sender - sn * Q;
-                        int dn = sn - j; if (dn < 0) dn += N;
-                        int dg = sg - l; if (dg < 0) dg += Q;
-                        src = (unsigned long long)(a.S + a.sdispls[(size_t)sender * P + dn * Q + dg]);
-                    } else {
-                        src = (unsigned long long)(a.T + ((long long)sender * a.slots + ssrc) * slot_bytes);
-                    }
-                    if (sdst < 0) {
-                        int on = qn + j; if (on >= N) on -= N;
-                        int og = qg + l; if (og >= Q) og -= Q;
-                        dst = (unsigned long long)(a.R + a.rdispls[(size_t)q * P + on * Q + og]);
-                    } else {
-                        dst = (unsigned long long)(a.T + ((long long)q * a.slots + sdst) * slot_bytes);
-                    }
-                }
+        // the hops.  Sixteen lanes move one block; the 64 groups of the workgroup take the blocks 64 apart, two
+        // per step, so that the whole workgroup has loads in flight at once (with one thread per block and the
+        // copies done wave by wave, a phase of 128 blocks kept two waves busy and fourteen idle).  Every lane of
+        // a group resolves the block itself: source, destination and size come from LDS.
+        const int nb = P * nseg;
+        const int grp = tid >> 4, sub = tid & 15;
+        auto resolve = [&](int k, unsigned long long& src, unsigned long long& dst) -> int {
+            if (k >= nb) return 0;
+            const int q = k / nseg, s = k - q * nseg;
+            const int e = te[s];
+            const int size = c1[q * P + e];
+            if (size <= 0) return 0;
+            const int qn = q / Q, qg = q - qn * Q;
+            const int sender = partner_up(qn, qg, Q, N, dim, tz[s] * rx);
+            const int j = e / Q, l = e - j * Q;
+            const int ssrc = ts[s], sdst = td[s];
+            if (ssrc < 0) {
+                const int sn = sender / Q, sg = sender - sn * Q;
+                int dn = sn - j; if (dn < 0) dn += N;
+                int dg = sg - l; if (dg < 0) dg += Q;
+                src = (unsigned long long)(a.S + sd32[sender * P + dn * Q + dg]);
+            } else {
+                src = (unsigned long long)(a.T + ((long long)sender * a.slots + ssrc) * slot_bytes);
             }
-            const unsigned long long any = __ballot(size > 0);
-            const int sub = lane & 15;
-            for (int g0 = 0; g0 < kWave; g0 += 4) {
-                if (!((any >> g0) & 0xfull)) continue;           // wave-uniform
-                const int it = g0 + (lane >> 4);
-                const unsigned long long bs = __shfl(src, it, kWave), bd = __shfl(dst, it, kWave);
-                const int bn = __shfl(size, it, kWave);
-                const unsigned char* sp = reinterpret_cast<const unsigned char*>(bs);
-                unsigned char* dp = reinterpret_cast<unsigned char*>(bd);
-                if (((bs | bd | (unsigned long long)bn) & 3ull) == 0) {
-                    const uint32_t* s4 = reinterpret_cast<const uint32_t*>(sp);
-                    uint32_t* d4 = reinterpret_cast<uint32_t*>(dp);
-                    const int nw = bn >> 2;
-                    for (int i = sub; i < nw; i += 64) {     // four independent words per step
-                        const uint32_t w0 = s4[i];
-                        const uint32_t w1 = i + 16 < nw ? s4[i + 16] : 0u;
-                        const uint32_t w2 = i + 32 < nw ? s4[i + 32] : 0u;
-                        const uint32_t w3 = i + 48 < nw ? s4[i + 48] : 0u;
-                        d4[i] = w0;
-                        if (i + 16 < nw) d4[i + 16] = w1;
-                        if (i + 32 < nw) d4[i + 32] = w2;
-                        if (i + 48 < nw) d4[i + 48] = w3;
-                    }
-                } else {
-                    for (int i = sub; i < bn; i += 16) dp[i] = sp[i];
-                }
+            if (sdst < 0) {
+                int on = qn + j; if (on >= N) on -= N;
+                int og = qg + l; if (og >= Q) og -= Q;
+                dst = (unsigned long long)(a.R + rd32[q * P + on * Q + og]);
+            } else {
+                dst = (unsigned long long)(a.T + ((long long)q * a.slots + sdst) * slot_bytes);
+            }
+            return size;
+        };
+        for (int b0 = 0; b0 < nb; b0 += 2 * (kTinyThreads / 16)) {
+            unsigned long long sa = 0, da = 0, sb = 0, db = 0;
+            const int na = resolve(b0 + grp, sa, da);
+            const int nbb = resolve(b0 + kTinyThreads / 16 + grp, sb, db);
+            const bool wa = ((sa | da | (unsigned long long)na) & 3ull) == 0;
+            const bool wb = ((sb | db | (unsigned long long)nbb) & 3ull) == 0;
+            const uint32_t* a4 = reinterpret_cast<const uint32_t*>(sa);
+            const uint32_t* b4 = reinterpret_cast<const uint32_t*>(sb);
+            uint32_t* ad4 = reinterpret_cast<uint32_t*>(da);
+            uint32_t* bd4 = reinterpret_cast<uint32_t*>(db);
+            const int nwa = wa ? na >> 2 : 0, nwb = wb ? nbb >> 2 : 0;
+            for (int i = sub; i < max(nwa, nwb); i += 32) {     // four independent words per step
+                const uint32_t a0 = i < nwa ? a4[i] : 0u;
+                const uint32_t a1 = i + 16 < nwa ? a4[i + 16] : 0u;
+                const uint32_t c0_ = i < nwb ? b4[i] : 0u;
+                const uint32_t c1_ = i + 16 < nwb ? b4[i + 16] : 0u;
+                if (i < nwa) ad4[i] = a0;
+                if (i + 16 < nwa) ad4[i + 16] = a1;
+                if (i < nwb) bd4[i] = c0_;
+                if (i + 16 < nwb) bd4[i + 16] = c1_;
+            }
+            if (!wa) {
+                const unsigned char* sp = reinterpret_cast<const unsigned char*>(sa);
+                unsigned char* dp = reinterpret_cast<unsigned char*>(da);
+                for (int i = sub; i < na; i += 16) dp[i] = sp[i];
+            }
+            if (!wb) {
+                const unsigned char* sp = reinterpret_cast<const unsigned char*>(sb);
+                unsigned char* dp = reinterpret_cast<unsigned char*>(db);
+                for (int i = sub; i < nbb; i += 16) dp[i] = sp[i];
             }
         }
         __syncthreads();                                  // the blocks stored into T are read in a later phase
