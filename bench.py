@@ -157,8 +157,8 @@ class Resident:
         o.profile = 0
         st = tuna.tuna_get_stats()
         hop_bytes = sum(st.phase[x].payload_bytes for x in range(st.n_phases))
-        if st.fused:        # one kernel per phase; its time is reported in the pack column
-            kern = {"hop": kern["pack"]}
+        if st.fused:        # one kernel per phase; its time is reported in the pack column, that of the
+            kern = {"hop": kern["pack"], "final_hop": kern["unpack"]}     # destination-tiled final hop in the unpack column
         kernels = {}
         for name, (ms, n, pbytes) in kern.items():
             if n and ms > 0:
@@ -245,7 +245,8 @@ def kernel_name(stage, gran, exact, max_block_bytes=None):
     if stage == "hop" and max_block_bytes is not None and 0 < max_block_bytes <= 64:
         return "tuna::k_hop_small<%d>" % (4 if gran >= 4 else 1)      # one thread per block when all blocks fit into 64 bytes
     return {"pack": "tuna::k_copy<0, %d, %s>" % (gran, et), "exchange": "tuna::k_copy<1, 16, false>",
-            "unpack": "tuna::k_copy<2, %d, %s>" % (min(gran, 16), et), "hop": "tuna::k_copy<3, %d, %s>" % (gran, et)}[stage]
+            "unpack": "tuna::k_copy<2, %d, %s>" % (min(gran, 16), et), "hop": "tuna::k_copy<3, %d, %s>" % (gran, et),
+            "final_hop": "tuna::k_copy_final<%d>" % (16 if gran >= 16 else 4)}[stage]
 
 
 def roofline_of(rows, steps, traffic, copy_ceiling):

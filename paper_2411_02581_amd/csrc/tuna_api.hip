@@ -264,7 +264,8 @@ struct DataSizes {
 };
 
 DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long total_chunks, bool fused,
-                         bool staggered = false, bool dense = false, unsigned long long t_chunks = 0) {
+                         bool staggered = false, bool dense = false, unsigned long long t_chunks = 0,
+                         bool final_tiled = false) {
     // t_chunks: exact-size T as the host laid it out (colour_classes)
     DataSizes d{};
     const bool any_phase = !pl.phases.empty() && total_chunks > 0;
@@ -272,7 +273,9 @@ DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long tot
     const size_t rank_pad = (size_t)pl.P * kRankAlignChunks;
     d.stage_chunks = any_phase ? (size_t)total_chunks + rank_pad : 0;
     // fused rounds cut chunks at destination lines: up to one more chunk per moving block
-    const size_t head_chunks = (fused || staggered) ? (size_t)pl.P * pl.P : 0;
+    // the destination-tiled final hop counts 16-byte pieces of R: a block owns at most its chunks plus the
+    // 7 pieces from its line's start, 7 that complete the previous run's line, one for an unaligned end
+    const size_t head_chunks = ((fused || staggered) ? (size_t)pl.P * pl.P : 0) * (final_tiled ? 16 : 1);
     d.unit_cap = any_phase ? (size_t)((total_chunks + head_chunks) / kUnitChunks) + pl.P + 1 : 0;
     d.slots = pl.slots;
     d.slot_bytes = (M + 127) / 128 * 128;     // whole 128-byte lines per slot
@@ -535,6 +538,7 @@ struct Prepared {
     // ranks' places inside a class are assigned on the device, phase by phase
     bool exact_t = false;               // T in exact size, and the schedule has T at all
     bool exact_kernels = false;         // T in exact size was asked for
+    bool final_tiled = false;           // the last phase runs as the destination-tiled final hop (k_copy_final)
     std::vector<int*> tpre;             // per phase: the blocks' offsets in message order (one array shared, or one each)
     ExactT x{};
     long long* d_cbase = nullptr;       // [classes]: where the host placed every class in T
@@ -728,7 +732,14 @@ int prepare_sizes(Prepared& pr, int dense_option, hipStream_t s, Status& hs, boo
     pr.max_count = hs.max_count;
     pr.total_bytes = hs.total_bytes;
     pr.user_limit = (unsigned long long)(uintptr_t)pr.sendbuf + hs.send_extent;
-    pr.ds = data_sizes_for(pr.dp->host, hs.max_count, hs.total_chunks, pr.fused, pr.staggered, pr.exact_t, pr.t_chunks);
+    // The last phase as the destination-tiled final hop: one-kernel phases over all rounds at once, receive
+    // regions dense (validation flag), word- or chunk-granular data (whole-line data is as fast in the copy
+    // engine, byte-granular data would need the pieces at block edges put together byte by byte), blocks
+    // that are not all tiny (those have k_hop_small).
+    pr.final_tiled = pr.fused && !pr.staggered && pr.block_count == 0 && !(hs.flags & 8u) && (pr.gran == 4 || pr.gran == 16) &&
+                     hs.max_count > kSmallBlockBytes && !pr.dp->host.phases.empty();
+    pr.ds = data_sizes_for(pr.dp->host, hs.max_count, hs.total_chunks, pr.fused, pr.staggered, pr.exact_t, pr.t_chunks,
+                           pr.final_tiled);
     return TUNA_OK;
 }
 
@@ -770,10 +781,39 @@ int prepare_call(Ctx& c, const Options& opt, const void* sendbuf, const int32_t*
 // instead of the byte-balanced engine.
 bool small_blocks(const Prepared& pr) { return pr.max_count > 0 && pr.max_count <= kSmallBlockBytes; }
 
+bool phase_is_final_tiled(const Prepared& pr, size_t i) { return pr.final_tiled && i + 1 == pr.dp->host.phases.size(); }
+
+int launch_resolve(const Prepared& pr, size_t i, const int32_t* nxt, const HopDev& hop, hipStream_t s);
+
+// The metadata of the last phase when it runs as the destination-tiled final hop: the size exchange, every
+// block's source and destination, then the layout of the 16-byte pieces of R in place of the chunk scan.
+int launch_final_metadata(const Prepared& pr, size_t i, const int32_t* cur, int32_t* nxt, const LayoutDev& Ls,
+                          const LayoutDev& Lr, const HopDev& hop, hipStream_t s) {
+    const PhaseHost& ph = pr.dp->host.phases[i];
+    const int P = pr.P;
+    hipLaunchKernelGGL(k_size_exchange, dim3((unsigned)((P + 255) / 256), (unsigned)((P + kExchangeRanks - 1) / kExchangeRanks)),
+                       dim3(256), 0, s, cur, nxt, pr.dp->d_zt[i], P, pr.Q, pr.N, ph.dim, (int)ph.rx);
+    HIPCHK(hipGetLastError());
+    int rc = launch_resolve(pr, i, nxt, hop, s);
+    if (rc != TUNA_OK) return rc;
+    FinalLayoutArgs fa{};
+    fa.hop = hop; fa.nseg = ph.nseg; fa.P = P; fa.Lr = Lr; fa.rank_bytes = pr.rank_bytes;
+    hipLaunchKernelGGL(k_final_layout, dim3(P), dim3(kScanThreads), 0, s, fa);
+    HIPCHK(hipGetLastError());
+    hipLaunchKernelGGL(k_layout_base, dim3(1), dim3(kScanThreads), 0, s, P, Lr, Ls, 1, &pr.sb.d_status->phase_chunks[i], 0,
+                       ExactT{}, pr.rank_bytes, &pr.sb.d_status->phase_bytes[i], pr.sb.d_status->phase_units[i]);
+    HIPCHK(hipGetLastError());
+    const int lds_ints = ph.nseg + 1 <= kUnitsLdsMaxInts ? ph.nseg + 1 : 0;
+    hipLaunchKernelGGL(k_layout_units, dim3(P, 1), dim3(256), (size_t)lds_ints * 4, s, ph.nseg, Lr, Ls, lds_ints);
+    HIPCHK(hipGetLastError());
+    return TUNA_OK;
+}
+
 int launch_phase_metadata(const Prepared& pr, size_t i, const int32_t* cur, int32_t* nxt, const LayoutDev& Ls,
                           const LayoutDev& Lr, const HopDev& hop, hipStream_t s) {
     const PhaseHost& ph = pr.dp->host.phases[i];
     const bool one_kernel = phase_is_one_kernel(pr, ph);
+    if (phase_is_final_tiled(pr, i)) return launch_final_metadata(pr, i, cur, nxt, Ls, Lr, hop, s);
     PhaseLayoutArgs m{};
     m.cur = cur; m.nxt = nxt; m.zt = pr.dp->d_zt[i]; m.seg = pr.dp->d_seg[i]; m.nseg = ph.nseg;
     m.P = pr.P; m.Q = pr.Q; m.N = pr.N; m.dim = ph.dim; m.rx = (int)ph.rx;
@@ -790,7 +830,12 @@ int launch_phase_metadata(const Prepared& pr, size_t i, const int32_t* cur, int3
     m.inline_exchange = pr.P <= 128 ? 1 : 0;
     int rc = phase_metadata(m, s, exact_t_of(pr, i));
     if (rc != TUNA_OK || !one_kernel) return rc;
-    // one-kernel phase: where every block comes from and goes to, once per phase instead of once per wave
+    return launch_resolve(pr, i, nxt, hop, s);
+}
+
+// one-kernel phase: where every block comes from and goes to, once per phase instead of once per wave
+int launch_resolve(const Prepared& pr, size_t i, const int32_t* nxt, const HopDev& hop, hipStream_t s) {
+    const PhaseHost& ph = pr.dp->host.phases[i];
     ResolveArgs ra{};
     ra.nxt = nxt; ra.seg = pr.dp->d_seg[i]; ra.nseg = ph.nseg;
     ra.P = pr.P; ra.Q = pr.Q; ra.N = pr.N; ra.dim = ph.dim; ra.rx = (int)ph.rx;
@@ -940,6 +985,26 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
             else hipLaunchKernelGGL(k_hop_small<1>, grid, dim3(256), 0, s, hop, pr.T, a.seg_lo, a.seg_hi);
             HIPCHK(hipGetLastError());
             mark(pr.ctx, s, kCatPack, (int)i);
+            continue;
+        }
+        if (phase_is_final_tiled(pr, i)) {
+            // the last phase, tiled over the 16-byte pieces of R (k_copy_final); its time is reported as the
+            // phase's unpack time, so that it can be told from the copy engine's one-kernel hops
+            FinalCopyArgs fa{};
+            fa.L = Lr; fa.hop = hop; fa.nseg = ph.nseg; fa.T = pr.T;
+            const dim3 grid((unsigned)((launch_units + kCopyThreads / kWave - 1) / (kCopyThreads / kWave)));
+            if (grid.x) {
+                const int resident = short_launch ? 8 : 7;
+                if (pr.gran >= 16) {
+                    static const size_t lds = static_lds_of(k_copy_final<16>);
+                    hipLaunchKernelGGL(k_copy_final<16>, grid, dim3(kCopyThreads), occupancy_padding(resident, lds), s, fa);
+                } else {
+                    static const size_t lds = static_lds_of(k_copy_final<4>);
+                    hipLaunchKernelGGL(k_copy_final<4>, grid, dim3(kCopyThreads), occupancy_padding(resident, lds), s, fa);
+                }
+                HIPCHK(hipGetLastError());
+            }
+            mark(pr.ctx, s, kCatUnpack, (int)i);
             continue;
         }
         if (phase_is_one_kernel(pr, ph)) {
@@ -1547,14 +1612,14 @@ struct Model {
     double c[kModelTerms];
 };
 struct ModelSet {
-    Model m[2] = {{{0.0445, 0.0364, 0.0065, 0.9976, 0.0459, 0.0, 0.0}},            // [0] three stages
-                  {{0.0471, 0.0301, 0.0077, 0.4068, 0.0245, 0.0128, 1.515}}};     // [1] one-kernel hops
+    Model m[2] = {{{0.0494, 0.0341, 0.0070, 1.0013, 0.0454, 0.0, 0.0}},            // [0] three stages
+                  {{0.0465, 0.0302, 0.0047, 0.3875, 0.0241, 0.0201, 1.491}}};     // [1] one-kernel hops
     // T in the paper's slots of M bytes: the bytes that pass through T cost more the emptier the slots are
     // (sparse writes and reads): their share of the byte term is scaled by 1 + k * (1 - mean / M)
     double slot_penalty[2] = {0.25, 0.45};
     // byte-granular problems (some count, displacement or buffer address is not a multiple of 4) run the
     // kernel variants that load and store single bytes at block edges: their byte term is scaled by this
-    double byte_granular[2] = {1.4, 2.1};
+    double byte_granular[2] = {1.4, 2.3};
     bool calibrated = false;
 };
 ModelSet g_model;
@@ -1951,7 +2016,7 @@ int tuna_workspace_bytes(const int32_t* sendcounts, int P, int ranks_per_node, i
     if (h_status->flags & 1u) return TUNA_ERR_NEGATIVE_COUNT;
     if (too_large(P, *h_status)) return TUNA_ERR_TOO_LARGE;
     const DataSizes ds = data_sizes_for(pl, h_status->max_count, h_status->total_chunks, fused, staggered,
-                                        exact_t, t_chunks);
+                                        exact_t, t_chunks, fused && !staggered && o.block_count == 0);
     Prepared pr;
     pr.P = P; pr.Q = Q; pr.N = N; pr.dp = dp; pr.ds = ds; pr.exact_t = exact_t;
     pr.fused = fused; pr.staggered = staggered; pr.max_count = h_status->max_count;

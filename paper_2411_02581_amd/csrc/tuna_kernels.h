@@ -37,7 +37,7 @@ constexpr int kMaxClasses = 64 * 63 / 2;     // class_count(TUNA_MAX_PHASES)
 // Device-side status block: the validation pass writes the head, every phase its own entries of the
 // three arrays; the head is read back once after validation.
 struct Status {
-    unsigned int flags;            // bit 0: negative count, bit 1: recvcounts != transpose(sendcounts),
+    unsigned int flags;            // bit 0: negative count, bit 1: recvcounts != transpose(sendcounts), (bit 3: receive regions not dense)
                                    // bit 2: negative displacement of a non-empty block
     unsigned int align_bits;       // OR of all counts and displacements, low 7 bits (they decide the granularity)
     int max_count;                 // M
@@ -285,15 +285,26 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
         if (recvcounts) {
             for (int a = ty; a < kValTile; a += 4) {
                 const int jr = bj + a, i = bi + tx;     // recvcounts[jr][i] must equal sendcounts[i][jr]
-                if (i < P && jr < P) {
-                    int rc = recvcounts[(size_t)jr * P + i];
+                const bool in = i < P && jr < P;
+                int rc = 0;
+                long long d = 0;
+                if (in) {
+                    rc = recvcounts[(size_t)jr * P + i];
                     if (rc < 0) flags |= 1u;
                     else if (rc != tile[tx][a]) flags |= 2u;
                     if (rdispls) {
-                        const int64_t d = rdispls[(size_t)jr * P + i];
+                        d = rdispls[(size_t)jr * P + i];
                         abits |= (unsigned int)d & 127u;
                         if (rc > 0 && d < 0) flags |= 4u;
                     }
+                }
+                if (rdispls) {
+                    // dense receive regions: every block starts where its predecessor in source order ends
+                    // (flag 8 when not; the destination-tiled final hop needs it).  A wave holds 64
+                    // neighbours of one row; the last lane reads its successor itself.
+                    long long dn = __shfl_down(d, 1, kWave);
+                    if (tx == kValTile - 1 && in && i + 1 < P) dn = rdispls[(size_t)jr * P + i + 1];
+                    if (in && i + 1 < P && dn != d + (long long)max(rc, 0)) flags |= 8u;
                 }
             }
         }
@@ -973,13 +984,21 @@ __global__ void __launch_bounds__(256) k_resolve_hop(const ResolveArgs a) {
     const int e = a.seg.e[s];
     const int sz = a.nxt[(size_t)p * a.P + e];
     const size_t o = (size_t)p * a.hop.ld + s;
-    if (sz <= 0) {                       // an empty block owns no chunk: its entry is never used
-        a.hop.src[o] = 0; a.hop.dst[o] = 0; a.hop.size[o] = 0;
-        return;
-    }
     int j, l;
     split_slot_index(e, a.Q, a.N, j, l);
     const int ssrc = a.seg.src[s], sdst = a.seg.dst[s];
+    if (sz <= 0) {
+        // an empty block owns no chunk and is never copied; a final one still records where it would lie in
+        // R, so that the destination-tiled final hop sees the blocks around it as one contiguous run
+        unsigned long long d0 = 0;
+        if (sdst < 0) {
+            int sn = n + j; if (sn >= a.N) sn -= a.N;
+            int sg = g + l; if (sg >= a.Q) sg -= a.Q;
+            d0 = (unsigned long long)(a.R + a.rdispls[(size_t)p * a.P + sn * a.Q + sg]);
+        }
+        a.hop.src[o] = 0; a.hop.dst[o] = d0; a.hop.size[o] = 0;
+        return;
+    }
     // the sender: the rank at distance z r^x upwards in the phase's dimension
     const int q = partner_up(n, g, a.Q, a.N, a.dim, a.seg.z[s] * a.rx);
     unsigned long long src, dst;
@@ -1320,6 +1339,315 @@ k_copy(const CopyArgs a) {
                         unsigned char* base = reinterpret_cast<unsigned char*>(((unsigned long long)hi32 << 32) | lo32);
                         *reinterpret_cast<v4u*>(base + 16 * (lane + 1)) = zero;
                     }
+                }
+            }
+        }
+        if (wend >= cend) break;
+        sw += kWave;
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// The destination-tiled final hop.  In the last phase of a schedule every moving block is final
+// (Algorithm "TuNA", lines 16-18: no higher non-zero digit), and when the receive regions are dense
+// (every rank's blocks back to back in source order, the usual layout) what a rank receives lands in a
+// few long contiguous runs of R.  The copy engine cuts such a phase into 16-byte chunks per block; a
+// block that does not start on a 16-byte boundary shares a chunk with its predecessor, the chunk count
+// drifts against the addresses, and a wave's 64-lane store never covers whole 128-byte lines: measured,
+// streaming stores that begin and end inside lines cost 13 % of the hop's rate (blocks of whole lines,
+// destination 4 or 16 bytes off a line: 4.9 and 4.7 TB/s against 5.6 to 5.8 aligned).  Here the unit
+// of work is the destination itself: a run is cut into its 16-byte pieces from the 128-byte line it
+// starts in to the line it ends in, every piece belongs to exactly one lane, a piece that holds the
+// end of one block and the start of the next is assembled by that lane from both, and every wave store
+// covers eight whole lines.
+//
+// k_final_layout (one workgroup per rank, the scan machinery of k_phase_layout): from the resolved
+// destinations and sizes (k_resolve_hop) the number of pieces every segment owns.  Segment s with
+// destination a, size n, end E = a + n continues a run when its predecessor in message order ends at a
+// (empty blocks lie where they would lie, so they continue runs too); it then owns the pieces from
+// ceil(a / 16) to ceil(E / 16) -- the piece that holds its first bytes, if shared, belongs to a
+// predecessor.  A segment that starts a run owns the pieces from the start of a's 128-byte line, and
+// in front of them come the dead pieces that complete the previous run's last line, so that every run
+// starts at a multiple of 8 pieces.  The prefix row has the same form as a chunk prefix row:
+// k_layout_base and k_layout_units cut it into wave units of 256 pieces.
+// ------------------------------------------------------------------------------------------
+struct FinalLayoutArgs {
+    HopDev hop;
+    int nseg, P;
+    LayoutDev Lr;
+    unsigned long long* rank_bytes;     // [P]: payload bytes every rank receives in the phase
+};
+
+// pieces segment s owns, and the dead pieces in front of them
+__device__ __forceinline__ int final_pieces(unsigned long long a, int n, bool has_prev, unsigned long long e_prev,
+                                            int* dead) {
+    const unsigned long long e = a + (unsigned long long)n;
+    const bool new_run = !has_prev || e_prev != a;
+    const unsigned long long last = (e + 15) >> 4;
+    const unsigned long long first = new_run ? (a >> 7) << 3 : (a + 15) >> 4;
+    *dead = (new_run && has_prev) ? (int)((((e_prev + 127) >> 7) << 3) - ((e_prev + 15) >> 4)) : 0;
+    return last > first ? (int)(last - first) : 0;
+}
+
+__global__ void __launch_bounds__(kScanThreads) k_final_layout(const FinalLayoutArgs a) {
+    __shared__ int wsum[kScanThreads / kWave];
+    __shared__ unsigned long long wbytes[kScanThreads / kWave];
+    const int p = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const size_t o = (size_t)p * a.hop.ld;
+    int* pre_r = a.Lr.pre + (size_t)p * a.Lr.ld;
+    int carry = 0;
+    unsigned long long bytes = 0;
+    for (int base = 0; base < a.nseg; base += kScanThreads * kScanItems) {
+        int cr[kScanItems];
+#pragma unroll
+        for (int k = 0; k < kScanItems; ++k) {
+            const int s = base + scan_item_index(k);
+            cr[k] = 0;
+            if (s < a.nseg) {
+                const unsigned long long d = a.hop.dst[o + s];
+                const int n = a.hop.size[o + s];
+                unsigned long long e_prev = 0;
+                if (s > 0) e_prev = a.hop.dst[o + s - 1] + (unsigned long long)a.hop.size[o + s - 1];
+                int dead;
+                const int own = final_pieces(d, n, s > 0, e_prev, &dead);
+                cr[k] = dead + own;
+                bytes += (unsigned long long)n;
+            }
+        }
+        int run[kScanItems];
+        block_scan_batch(cr, run, carry, wsum);
+#pragma unroll
+        for (int k = 0; k < kScanItems; ++k) {
+            const int s = base + scan_item_index(k);
+            if (s < a.nseg) pre_r[s] = run[k];
+        }
+    }
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) bytes += __shfl_xor(bytes, d, kWave);
+    __syncthreads();
+    if (lane == 0) wbytes[tid / kWave] = bytes;
+    __syncthreads();
+    if (tid == 0) {
+        unsigned long long t = 0;
+#pragma unroll
+        for (int k = 0; k < kScanThreads / kWave; ++k) t += wbytes[k];
+        a.rank_bytes[p] = t;
+        pre_r[a.nseg] = carry; a.Lr.tot[p] = carry;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// k_copy_final: the payload kernel of the destination-tiled final hop.  Work unit = one wavefront x
+// 256 consecutive pieces of one rank (k_final_layout); no workgroup barrier.  Lane i of a window loads
+// the prefix and the resolved source, destination and size of segment s0 + i and derives the address of
+// the segment's first own piece; every lane finds the segment of each of its 4 pieces by the same
+// branch-free search as the copy engine.  A piece that lies inside its block is one 16-byte load at
+// the source's own alignment and one aligned streaming store.  A piece at a block's edge is put together
+// word by word (GRAN = 4: every size and address is a multiple of 4) from the blocks that follow each
+// other in the run -- read from the hop arrays, the window need not hold them -- and stored whole when
+// all four words belong to blocks, else word by word (the ends of a run: bytes outside every block
+// are never written).  With GRAN = 16 every piece is inside a block or outside all of them.
+// ------------------------------------------------------------------------------------------
+struct FinalCopyArgs {
+    LayoutDev L;
+    HopDev hop;
+    int nseg;
+    unsigned char* T;
+};
+
+template <int GRAN>
+__global__ void __launch_bounds__(kCopyThreads) k_copy_final(const FinalCopyArgs a) {
+    __shared__ int s_pre[kCopyThreads / kWave][kWave];
+    __shared__ int s_size[kCopyThreads / kWave][kWave];
+    __shared__ int s_off0[kCopyThreads / kWave][kWave];
+    __shared__ unsigned long long s_src[kCopyThreads / kWave][kWave];
+    __shared__ unsigned long long s_dst[kCopyThreads / kWave][kWave];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int unit = blockIdx.x * (kCopyThreads / kWave) + wv;
+    if (unit >= *a.L.n_units) return;                // no barrier below: a wave may leave alone
+    const int4 ud = a.L.units[unit];
+    const int p = __builtin_amdgcn_readfirstlane(ud.x);
+    int sw = __builtin_amdgcn_readfirstlane(ud.y);
+    const int c0 = __builtin_amdgcn_readfirstlane(ud.z);
+    const int cend = c0 + __builtin_amdgcn_readfirstlane(ud.w);
+    const int* prow = a.L.pre + (size_t)p * a.L.ld;
+    const size_t ho = (size_t)p * a.hop.ld;
+    int* wpre = s_pre[wv];
+    int* wsize = s_size[wv];
+    int* woff0 = s_off0[wv];
+    unsigned long long* wsrc = s_src[wv];
+    unsigned long long* wdst = s_dst[wv];
+    const unsigned long long tb = (unsigned long long)a.T;
+    int c[kChunksPerLane];
+    bool pend[kChunksPerLane];
+#pragma unroll
+    for (int k = 0; k < kChunksPerLane; ++k) {
+        c[k] = c0 + k * kWave + lane;
+        pend[k] = c[k] < cend;
+    }
+    for (;;) {
+        // ---- window: segments sw .. sw+63, one per lane; loads from clamped indices.  A unit of 256 pieces seldom
+        // overlaps more than a few blocks: the first kHopLanes lanes fetch their entries together with the
+        // prefix, the others only when the prefix shows that the unit reaches that far (two entries more than
+        // it reaches: the last piece of the unit may hold the first words of the blocks behind it).
+        const int s = sw + lane;
+        const int s_tab = min(s, a.nseg - 1);
+        const int pre_raw = prow[min(s, a.nseg)];
+        const int pre_w_raw = prow[min(sw + kWave, a.nseg)];
+        const bool early = lane < kHopLanes;
+        unsigned long long hs_ = 0, hd_ = 0;
+        int size = 0;
+        if (early) { hs_ = a.hop.src[ho + s_tab]; hd_ = a.hop.dst[ho + s_tab]; size = a.hop.size[ho + s_tab]; }
+        // the end of the block in front of the window, for its first segment
+        unsigned long long e_front = 0;
+        if (lane == 0 && sw > 0) e_front = a.hop.dst[ho + sw - 1] + (unsigned long long)a.hop.size[ho + sw - 1];
+        const int pre_i = s <= a.nseg ? pre_raw : INT_MAX;
+        const int pre_w = sw + kWave <= a.nseg ? pre_w_raw : INT_MAX;
+        const int nload = min(kWave, max(kHopLanes, __popcll(__ballot(pre_i < cend)) + 2));
+        if (nload > kHopLanes) {
+            if (!early && lane < nload) { hs_ = a.hop.src[ho + s_tab]; hd_ = a.hop.dst[ho + s_tab]; size = a.hop.size[ho + s_tab]; }
+        }
+        unsigned long long e_prev = __shfl_up(hd_ + (unsigned long long)size, 1, kWave);
+        if (lane == 0) e_prev = e_front;
+        // Offset of piece 0 of the segment's row from the block's first byte: a segment that starts a run owns
+        // the pieces from its 128-byte line's start, behind the dead pieces that complete the previous run's
+        // line; one that continues a run owns them from the first piece that begins inside the block.  Dead
+        // pieces and the pieces in front of the block come out with negative offsets and hold none of its bytes.
+        int dead;
+        (void)final_pieces(hd_, size, s_tab > 0, e_prev, &dead);
+        const bool new_run = s_tab == 0 || e_prev != hd_;
+        const int off0 = (new_run ? -(int)((unsigned int)hd_ & 127u) : (int)((0u - (unsigned int)hd_) & 15u)) - (dead << 4);
+        wpre[lane] = pre_i;
+        wsize[lane] = size;
+        woff0[lane] = off0;
+        wsrc[lane] = (hs_ & ~(kHopInT | kHopFill)) + ((hs_ & kHopInT) ? tb : 0ull);
+        wdst[lane] = hd_;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int wend = pre_w;                      // pieces below wend resolve in this window
+        const int nlive = __popcll(__ballot(pre_i < cend));
+        int steps = 0;
+        while ((1 << steps) < nlive) ++steps;
+        bool act[kChunksPerLane];
+        int lo[kChunksPerLane], hi[kChunksPerLane];
+#pragma unroll
+        for (int k = 0; k < kChunksPerLane; ++k) { act[k] = pend[k] && c[k] < wend; lo[k] = 0; hi[k] = nlive; }
+        for (int it = 0; it < steps; ++it) {
+#pragma unroll
+            for (int k = 0; k < kChunksPerLane; ++k) {
+                const int mid = (lo[k] + hi[k]) >> 1;
+                const bool up = wpre[mid] <= c[k];
+                const bool move = mid > lo[k];
+                lo[k] = (move && up) ? mid : lo[k];
+                hi[k] = (move && !up) ? mid : hi[k];
+            }
+        }
+        // every piece as a byte offset from its block's start: 32-bit arithmetic from here on
+        int off[kChunksPerLane];
+        bool whole[kChunksPerLane], edge[kChunksPerLane];
+        v4u v[kChunksPerLane];
+#pragma unroll
+        for (int k = 0; k < kChunksPerLane; ++k) {
+            const int idx = lo[k];
+            off[k] = woff0[idx] + ((c[k] - wpre[idx]) << 4);
+            const int n = wsize[idx];
+            whole[k] = act[k] && off[k] >= 0 && off[k] + 16 <= n;
+            edge[k] = act[k] && !whole[k] && off[k] > -16;
+            pend[k] = pend[k] && !act[k];
+        }
+        // ---- loads of the pieces inside their blocks, issued together ----------------------------------------
+#pragma unroll
+        for (int k = 0; k < kChunksPerLane; ++k)
+            if (whole[k]) __builtin_memcpy(&v[k], reinterpret_cast<const unsigned char*>(wsrc[lo[k]] + (unsigned long long)(long long)off[k]), 16);
+        // ---- pieces at block edges: a word lies in the piece's block, in the block behind it, or in none.  The
+        // loads go out at once and travel with the ones above; nothing loaded is looked at before the stores.
+        // A unit holds a handful of block edges, seldom two in one lane: every lane takes its first edge piece,
+        // then its second ..., so that the code below runs once or twice per wave, not once per piece index.
+        unsigned int emask = 0;                      // bit 4 k + q: word q of piece k was loaded
+        unsigned int raremask = 0;
+        if (GRAN < 16) {
+            unsigned int todo = (edge[0] ? 1u : 0u) | (edge[1] ? 2u : 0u) | (edge[2] ? 4u : 0u) | (edge[3] ? 8u : 0u);
+            static_assert(kChunksPerLane == 4, "the edge loop picks among four pieces");
+            while (__ballot(todo != 0)) {
+                bool on = todo != 0;
+                const int ks = on ? __ffs((int)todo) - 1 : 0;
+                todo &= todo - 1;
+                const int offk = ks == 0 ? off[0] : (ks == 1 ? off[1] : (ks == 2 ? off[2] : off[3]));
+                const int t = ks == 0 ? lo[0] : (ks == 1 ? lo[1] : (ks == 2 ? lo[2] : lo[3]));
+                const int n = wsize[t];
+                const bool has_next = sw + t + 1 < a.nseg;
+                const bool next_here = has_next && t + 1 < nload;
+                const int tn = min(t + 1, kWave - 1);
+                const int nn = wsize[tn];
+                const bool follows = next_here && wdst[tn] == wdst[t] + (unsigned long long)n;
+                const int over = offk + 16 - n;              // bytes of the piece behind this block's end
+                // the walk over several blocks is needed when the block behind is not in the window, is empty,
+                // or ends inside this piece too
+                if (on && over > 0 && has_next && (!next_here || (follows && nn < over && sw + t + 2 < a.nseg))) {
+                    raremask |= 1u << ks;
+                    on = false;
+                }
+                const unsigned long long sa = wsrc[t] + (unsigned long long)(long long)offk;
+                const unsigned long long sb = wsrc[tn] + (unsigned long long)(long long)(offk - n);
+                uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int o = offk + 4 * q, o2 = o - n;
+                    const bool mine = o >= 0 && o < n;
+                    const bool theirs = follows && o2 >= 0 && o2 < nn;
+                    if (on && (mine || theirs)) {
+                        w[q] = *reinterpret_cast<const uint32_t*>((mine ? sa : sb) + 4u * q);
+                        emask |= 1u << (4 * ks + q);
+                    }
+                }
+#pragma unroll
+                for (int kk = 0; kk < kChunksPerLane; ++kk)
+                    if (on && kk == ks) { v[kk][0] = w[0]; v[kk][1] = w[1]; v[kk][2] = w[2]; v[kk][3] = w[3]; }
+            }
+            // rare: the blocks of a piece reach past the entries the window holds, or several blocks end inside
+            // one piece (a row of tiny or empty blocks): a walk over the hop arrays in global memory
+#pragma unroll
+            for (int k = 0; k < kChunksPerLane; ++k) {
+                if (!(raremask & (1u << k))) continue;
+                int t = sw + lo[k];
+                unsigned long long ta = wdst[lo[k]], te = ta + (unsigned long long)wsize[lo[k]], ts = wsrc[lo[k]];
+                const unsigned long long d = ta + (unsigned long long)(long long)off[k];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const unsigned long long b = d + 4u * q;
+                    bool in_run = true;
+                    while (b >= te) {                // the word lies behind this block: the next one, if it follows directly
+                        ++t;
+                        if (t >= a.nseg) { in_run = false; break; }
+                        const unsigned long long na = a.hop.dst[ho + t];
+                        if (na != te) { in_run = false; break; }
+                        const unsigned long long nsrc = a.hop.src[ho + t];
+                        ta = na; te = na + (unsigned long long)a.hop.size[ho + t];
+                        ts = (nsrc & ~(kHopInT | kHopFill)) + ((nsrc & kHopInT) ? tb : 0ull);
+                    }
+                    if (!in_run) break;              // nothing behind the run's end belongs to a block
+                    if (b >= ta) { v[k][q] = *reinterpret_cast<const uint32_t*>(ts + (b - ta)); emask |= 1u << (4 * k + q); }
+                }
+            }
+        }
+        // ---- stores: whole pieces and edge pieces with all four words as aligned streaming stores (eight whole
+        // lines per wave store), the others word by word (the ends of a run) -----------------------------------
+#pragma unroll
+        for (int k = 0; k < kChunksPerLane; ++k) {
+            if (whole[k] || edge[k]) {
+                unsigned char* d = reinterpret_cast<unsigned char*>(wdst[lo[k]] + (unsigned long long)(long long)off[k]);
+                const unsigned int em = (emask >> (4 * k)) & 0xfu;
+                if (whole[k] || em == 0xfu) {
+                    __builtin_nontemporal_store(v[k], reinterpret_cast<v4u*>(d));
+                } else {
+                    uint32_t* d4 = reinterpret_cast<uint32_t*>(d);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        if (em & (1u << q)) d4[q] = v[k][q];
                 }
             }
         }
