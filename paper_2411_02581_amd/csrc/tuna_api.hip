@@ -781,7 +781,13 @@ int prepare_call(Ctx& c, const Options& opt, const void* sendbuf, const int32_t*
 // instead of the byte-balanced engine.
 bool small_blocks(const Prepared& pr) { return pr.max_count > 0 && pr.max_count <= kSmallBlockBytes; }
 
-bool phase_is_final_tiled(const Prepared& pr, size_t i) { return pr.final_tiled && i + 1 == pr.dp->host.phases.size(); }
+// Phases that run as the destination-tiled hop: the last one (all its blocks are final), and with T in exact
+// size every other one too -- the blocks a rank stores into T lie back to back inside their class, so their
+// destinations form runs just like those in R.  (T in slots keeps the copy engine: its slot tails are filled
+// up to the line by a path of their own.)
+bool phase_is_final_tiled(const Prepared& pr, size_t i) {
+    return pr.final_tiled && (i + 1 == pr.dp->host.phases.size() || pr.exact_t);
+}
 
 int launch_resolve(const Prepared& pr, size_t i, const int32_t* nxt, const HopDev& hop, hipStream_t s);
 
@@ -791,13 +797,32 @@ int launch_final_metadata(const Prepared& pr, size_t i, const int32_t* cur, int3
                           const LayoutDev& Lr, const HopDev& hop, hipStream_t s) {
     const PhaseHost& ph = pr.dp->host.phases[i];
     const int P = pr.P;
+    const bool last = i + 1 == pr.dp->host.phases.size();
     hipLaunchKernelGGL(k_size_exchange, dim3((unsigned)((P + 255) / 256), (unsigned)((P + kExchangeRanks - 1) / kExchangeRanks)),
                        dim3(256), 0, s, cur, nxt, pr.dp->d_zt[i], P, pr.Q, pr.N, ph.dim, (int)ph.rx);
     HIPCHK(hipGetLastError());
+    if (!last) {
+        // the blocks this phase stores into T: their places inside the classes (k_phase_layout's class scans,
+        // which also count the phase's payload bytes) and the ranks' parts of the classes (k_layout_base)
+        PhaseLayoutArgs m{};
+        m.cur = cur; m.nxt = nxt; m.zt = pr.dp->d_zt[i]; m.seg = pr.dp->d_seg[i]; m.nseg = ph.nseg;
+        m.P = P; m.Q = pr.Q; m.N = pr.N; m.dim = ph.dim; m.rx = (int)ph.rx;
+        m.Ls = Ls; m.Lr = Lr; m.want_send = 0; m.want_tbound = 1; m.x = exact_t_of(pr, i);
+        m.rank_bytes = pr.rank_bytes;
+        m.phase_bytes = &pr.sb.d_status->phase_bytes[i]; m.phase_chunks = &pr.sb.d_status->phase_chunks[i];
+        m.phase_units = pr.sb.d_status->phase_units[i];
+        hipLaunchKernelGGL(k_phase_layout, dim3(P), dim3(kScanThreads), 0, s, m);
+        HIPCHK(hipGetLastError());
+        if (m.x.ncls > 0) {
+            hipLaunchKernelGGL(k_layout_base, dim3(m.x.ncls), dim3(kScanThreads), 0, s, P, Lr, Ls, 0, m.phase_chunks, -1, m.x,
+                               m.rank_bytes, m.phase_bytes, m.phase_units);
+            HIPCHK(hipGetLastError());
+        }
+    }
     int rc = launch_resolve(pr, i, nxt, hop, s);
     if (rc != TUNA_OK) return rc;
     FinalLayoutArgs fa{};
-    fa.hop = hop; fa.nseg = ph.nseg; fa.P = P; fa.Lr = Lr; fa.rank_bytes = pr.rank_bytes;
+    fa.hop = hop; fa.nseg = ph.nseg; fa.P = P; fa.Lr = Lr; fa.rank_bytes = last ? pr.rank_bytes : nullptr;
     hipLaunchKernelGGL(k_final_layout, dim3(P), dim3(kScanThreads), 0, s, fa);
     HIPCHK(hipGetLastError());
     hipLaunchKernelGGL(k_layout_base, dim3(1), dim3(kScanThreads), 0, s, P, Lr, Ls, 1, &pr.sb.d_status->phase_chunks[i], 0,
@@ -991,7 +1016,7 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
             // the last phase, tiled over the 16-byte pieces of R (k_copy_final); its time is reported as the
             // phase's unpack time, so that it can be told from the copy engine's one-kernel hops
             FinalCopyArgs fa{};
-            fa.L = Lr; fa.hop = hop; fa.nseg = ph.nseg; fa.T = pr.T;
+            fa.L = Lr; fa.hop = hop; fa.nseg = ph.nseg; fa.T = pr.T; fa.user_limit = pr.user_limit;
             const dim3 grid((unsigned)((launch_units + kCopyThreads / kWave - 1) / (kCopyThreads / kWave)));
             if (grid.x) {
                 const int resident = short_launch ? 8 : 7;
@@ -1612,14 +1637,14 @@ struct Model {
     double c[kModelTerms];
 };
 struct ModelSet {
-    Model m[2] = {{{0.0494, 0.0341, 0.0070, 1.0013, 0.0454, 0.0, 0.0}},            // [0] three stages
-                  {{0.0465, 0.0302, 0.0047, 0.3875, 0.0241, 0.0201, 1.491}}};     // [1] one-kernel hops
+    Model m[2] = {{{0.0445, 0.0355, 0.0085, 1.0234, 0.0416, 0.0, 0.0}},            // [0] three stages
+                  {{0.0401, 0.0383, 0.0024, 0.3625, 0.0353, 0.0224, 1.431}}};     // [1] one-kernel hops
     // T in the paper's slots of M bytes: the bytes that pass through T cost more the emptier the slots are
     // (sparse writes and reads): their share of the byte term is scaled by 1 + k * (1 - mean / M)
     double slot_penalty[2] = {0.25, 0.45};
     // byte-granular problems (some count, displacement or buffer address is not a multiple of 4) run the
     // kernel variants that load and store single bytes at block edges: their byte term is scaled by this
-    double byte_granular[2] = {1.4, 2.3};
+    double byte_granular[2] = {1.3, 1.3};
     bool calibrated = false;
 };
 ModelSet g_model;
@@ -1746,7 +1771,7 @@ int calibrate(hipStream_t s) {
     const Problem odd = {256, 515, {2, 16, 256}};        // byte-granular: fitted after the others, as a factor on the byte term
     // tiny (fixed costs), many tiny blocks (per-block and per-entry costs), large blocks beyond the caches
     // (bytes), and a mix; S is 4 bytes off a multiple of 16, the usual alignment of float payloads
-    const Problem problems[] = {{32, 68, {2, 6, 32}}, {1024, 20, {2, 32, 1024}}, {2048, 36, {8, 2048, 0}},
+    const Problem problems[] = {{32, 68, {2, 6, 32}}, {256, 516, {2, 16, 256}}, {1024, 20, {2, 32, 1024}}, {2048, 36, {8, 2048, 0}},
                                 {2048, 4, {2, 2048, 0}}, {1024, 60, {4, 1024, 0}},
                                 {512, 4100, {2, 23, 512}}, {2048, 260, {8, 2048, 0}}};
     size_t max_entries = 0, max_bytes = 0;
@@ -1792,18 +1817,19 @@ int calibrate(hipStream_t s) {
                 Options o;
                 o.mode = fused ? TUNA_MODE_FUSED : TUNA_MODE_STAGED;
                 o.t_layout = TUNA_T_EXACT;
-                double t[4];
-                for (int it = 0; it < 4; ++it) {         // the first call warms up (allocations, schedule tables)
+                constexpr int kReps = 6;
+                double t[kReps];
+                for (int it = 0; it < kReps; ++it) {     // the first call warms up (allocations, schedule tables)
                     const auto t0 = std::chrono::steady_clock::now();
                     rc = run(*c, o, send, sc, sd, recv, rc_, rd, pb.P, 0, r, r, s);
                     if (rc == TUNA_OK && hipStreamSynchronize(s) != hipSuccess) rc = TUNA_ERR_HIP;
                     if (rc != TUNA_OK) { cleanup(); return rc; }
                     t[it] = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
                 }
-                std::sort(t + 1, t + 4);
+                std::sort(t + 1, t + kReps);
                 const PlanHost pl = make_plan(pb.P, pb.P, r, r, false, false);
                 (is_odd ? Xo : X)[fused].push_back(features_of(pl, (double)entries * pb.S, small_block_path(fused != 0, pb.S)));
-                (is_odd ? yo : y)[fused].push_back(t[2]);                // median of the three timed calls
+                (is_odd ? yo : y)[fused].push_back(t[1 + (kReps - 1) / 2]);      // median of the timed calls
             }
         }
     }

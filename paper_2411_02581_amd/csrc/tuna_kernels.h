@@ -1376,7 +1376,7 @@ struct FinalLayoutArgs {
     HopDev hop;
     int nseg, P;
     LayoutDev Lr;
-    unsigned long long* rank_bytes;     // [P]: payload bytes every rank receives in the phase
+    unsigned long long* rank_bytes;     // [P]: payload bytes every rank receives in the phase; nullptr: already known
 };
 
 // pieces segment s owns, and the dead pieces in front of them
@@ -1406,6 +1406,8 @@ __global__ void __launch_bounds__(kScanThreads) k_final_layout(const FinalLayout
             const int s = base + scan_item_index(k);
             cr[k] = 0;
             if (s < a.nseg) {
+                // a destination in T is an offset with the in-T bit set; T starts on a 256-byte boundary, so the
+                // raw values align and follow each other exactly like the addresses they stand for
                 const unsigned long long d = a.hop.dst[o + s];
                 const int n = a.hop.size[o + s];
                 unsigned long long e_prev = 0;
@@ -1433,7 +1435,7 @@ __global__ void __launch_bounds__(kScanThreads) k_final_layout(const FinalLayout
         unsigned long long t = 0;
 #pragma unroll
         for (int k = 0; k < kScanThreads / kWave; ++k) t += wbytes[k];
-        a.rank_bytes[p] = t;
+        if (a.rank_bytes) a.rank_bytes[p] = t;
         pre_r[a.nseg] = carry; a.Lr.tot[p] = carry;
     }
 }
@@ -1455,6 +1457,7 @@ struct FinalCopyArgs {
     HopDev hop;
     int nseg;
     unsigned char* T;
+    unsigned long long user_limit;      // address one past the last byte of S that holds a block
 };
 
 template <int GRAN>
@@ -1462,6 +1465,7 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy_final(const FinalCopyArgs
     __shared__ int s_pre[kCopyThreads / kWave][kWave];
     __shared__ int s_size[kCopyThreads / kWave][kWave];
     __shared__ int s_off0[kCopyThreads / kWave][kWave];
+    __shared__ int s_lim[kCopyThreads / kWave][kWave];
     __shared__ unsigned long long s_src[kCopyThreads / kWave][kWave];
     __shared__ unsigned long long s_dst[kCopyThreads / kWave][kWave];
     const int lane = threadIdx.x & (kWave - 1);
@@ -1478,6 +1482,7 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy_final(const FinalCopyArgs
     int* wpre = s_pre[wv];
     int* wsize = s_size[wv];
     int* woff0 = s_off0[wv];
+    int* wlim = s_lim[wv];
     unsigned long long* wsrc = s_src[wv];
     unsigned long long* wdst = s_dst[wv];
     const unsigned long long tb = (unsigned long long)a.T;
@@ -1520,11 +1525,18 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy_final(const FinalCopyArgs
         (void)final_pieces(hd_, size, s_tab > 0, e_prev, &dead);
         const bool new_run = s_tab == 0 || e_prev != hd_;
         const int off0 = (new_run ? -(int)((unsigned int)hd_ & 127u) : (int)((0u - (unsigned int)hd_) & 15u)) - (dead << 4);
+        const unsigned long long src_addr = (hs_ & ~(kHopInT | kHopFill)) + ((hs_ & kHopInT) ? tb : 0ull);
+        // A block bound for T takes whole chunks: its last piece is loaded whole and may run up to 15 bytes past
+        // the block's end.  In T that is padding; in S it is the next block, except at the very end of S: `lim` =
+        // the bytes that may be loaded from the block's start on.
+        int lim = size;
+        if (!(hs_ & kHopInT)) lim = (int)min((unsigned long long)size, a.user_limit > src_addr ? a.user_limit - src_addr : 0ull);
         wpre[lane] = pre_i;
         wsize[lane] = size;
         woff0[lane] = off0;
-        wsrc[lane] = (hs_ & ~(kHopInT | kHopFill)) + ((hs_ & kHopInT) ? tb : 0ull);
-        wdst[lane] = hd_;
+        wlim[lane] = lim;
+        wsrc[lane] = src_addr;
+        wdst[lane] = (hd_ & ~(kHopInT | kHopFill)) + ((hd_ & kHopInT) ? tb : 0ull);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -1554,8 +1566,7 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy_final(const FinalCopyArgs
         for (int k = 0; k < kChunksPerLane; ++k) {
             const int idx = lo[k];
             off[k] = woff0[idx] + ((c[k] - wpre[idx]) << 4);
-            const int n = wsize[idx];
-            whole[k] = act[k] && off[k] >= 0 && off[k] + 16 <= n;
+            whole[k] = act[k] && off[k] >= 0 && off[k] + 16 <= wlim[idx];
             edge[k] = act[k] && !whole[k] && off[k] > -16;
             pend[k] = pend[k] && !act[k];
         }
@@ -1579,6 +1590,7 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy_final(const FinalCopyArgs
                 const int offk = ks == 0 ? off[0] : (ks == 1 ? off[1] : (ks == 2 ? off[2] : off[3]));
                 const int t = ks == 0 ? lo[0] : (ks == 1 ? lo[1] : (ks == 2 ? lo[2] : lo[3]));
                 const int n = wsize[t];
+                const int nlim = wlim[t];                    // < n only for the last block of S when it is bound for T
                 const bool has_next = sw + t + 1 < a.nseg;
                 const bool next_here = has_next && t + 1 < nload;
                 const int tn = min(t + 1, kWave - 1);
@@ -1600,7 +1612,7 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy_final(const FinalCopyArgs
                     const bool mine = o >= 0 && o < n;
                     const bool theirs = follows && o2 >= 0 && o2 < nn;
                     if (on && (mine || theirs)) {
-                        w[q] = *reinterpret_cast<const uint32_t*>((mine ? sa : sb) + 4u * q);
+                        if (mine ? o < nlim : o2 < wlim[tn]) w[q] = *reinterpret_cast<const uint32_t*>((mine ? sa : sb) + 4u * q);
                         emask |= 1u << (4 * ks + q);
                     }
                 }
@@ -1615,6 +1627,7 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy_final(const FinalCopyArgs
                 if (!(raremask & (1u << k))) continue;
                 int t = sw + lo[k];
                 unsigned long long ta = wdst[lo[k]], te = ta + (unsigned long long)wsize[lo[k]], ts = wsrc[lo[k]];
+                bool in_t = (a.hop.src[ho + t] & kHopInT) != 0;     // a word of a block in S is loaded only inside S
                 const unsigned long long d = ta + (unsigned long long)(long long)off[k];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
@@ -1623,14 +1636,20 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy_final(const FinalCopyArgs
                     while (b >= te) {                // the word lies behind this block: the next one, if it follows directly
                         ++t;
                         if (t >= a.nseg) { in_run = false; break; }
-                        const unsigned long long na = a.hop.dst[ho + t];
+                        const unsigned long long nraw = a.hop.dst[ho + t];
+                        const unsigned long long na = (nraw & ~(kHopInT | kHopFill)) + ((nraw & kHopInT) ? tb : 0ull);
                         if (na != te) { in_run = false; break; }
                         const unsigned long long nsrc = a.hop.src[ho + t];
                         ta = na; te = na + (unsigned long long)a.hop.size[ho + t];
                         ts = (nsrc & ~(kHopInT | kHopFill)) + ((nsrc & kHopInT) ? tb : 0ull);
+                        in_t = (nsrc & kHopInT) != 0;
                     }
                     if (!in_run) break;              // nothing behind the run's end belongs to a block
-                    if (b >= ta) { v[k][q] = *reinterpret_cast<const uint32_t*>(ts + (b - ta)); emask |= 1u << (4 * k + q); }
+                    if (b >= ta) {
+                        const unsigned long long wa = ts + (b - ta);
+                        v[k][q] = (in_t || wa + 4 <= a.user_limit) ? *reinterpret_cast<const uint32_t*>(wa) : 0u;
+                        emask |= 1u << (4 * k + q);
+                    }
                 }
             }
         }
