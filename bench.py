@@ -157,8 +157,8 @@ class Resident:
         o.profile = 0
         st = tuna.tuna_get_stats()
         hop_bytes = sum(st.phase[x].payload_bytes for x in range(st.n_phases))
-        if st.fused:        # one kernel per phase; its time is reported in the pack column, that of the
-            kern = {"hop": kern["pack"], "final_hop": kern["unpack"]}     # destination-tiled final hop in the unpack column
+        if st.fused:        # one kernel per phase: the copy engine's hop is reported in the pack column, the
+            kern = {"hop": kern["pack"], "tiled_hop": kern["unpack"]}     # destination-tiled hop in the unpack column
         kernels = {}
         for name, (ms, n, pbytes) in kern.items():
             if n and ms > 0:
@@ -246,7 +246,7 @@ def kernel_name(stage, gran, exact, max_block_bytes=None):
         return "tuna::k_hop_small<%d>" % (4 if gran >= 4 else 1)      # one thread per block when all blocks fit into 64 bytes
     return {"pack": "tuna::k_copy<0, %d, %s>" % (gran, et), "exchange": "tuna::k_copy<1, 16, false>",
             "unpack": "tuna::k_copy<2, %d, %s>" % (min(gran, 16), et), "hop": "tuna::k_copy<3, %d, %s>" % (gran, et),
-            "final_hop": "tuna::k_copy_final<%d>" % (16 if gran >= 16 else 4)}[stage]
+            "tiled_hop": "tuna::k_copy_tiled<%d>" % (16 if gran >= 16 else 4)}[stage]
 
 
 def roofline_of(rows, steps, traffic, copy_ceiling):

@@ -76,9 +76,9 @@ typedef struct tuna_phase_stats {
     int64_t payload_bytes;  /* b_x: payload bytes of those blocks */
     int64_t staged_bytes;   /* bytes they occupy in a staging buffer (every block padded to 16 B) */
     float ms_metadata;      /* metadata exchange + scans (profiling mode only, else 0) */
-    float ms_pack;
+    float ms_pack;          /* one-kernel phases have one payload kernel: the copy engine's hop is reported here, */
     float ms_exchange;
-    float ms_unpack;
+    float ms_unpack;        /* the destination-tiled hop here */
 } tuna_phase_stats_t;
 
 typedef struct tuna_stats {
@@ -162,7 +162,10 @@ int tuna_alltoallv_hier(const void* sendbuf, const int32_t* sendcounts, const in
  *   mode         TUNA_MODE_AUTO (default): left to the library, which takes the one-kernel hops --
  *                with all ranks in one memory a hop needs no message, and moving a block straight from
  *                where its sender holds it to where its receiver keeps it reads and writes it once
- *                instead of three times.  TUNA_MODE_STAGED: pack -> exchange -> unpack, the paper's
+ *                instead of three times.  When the receive regions are dense (every rank's blocks back to
+ *                back in source order), sizes, displacements and buffer addresses are multiples of 4 and T
+ *                is kept in exact size, a phase is tiled over its destinations in 128-byte lines; otherwise
+ *                (and always for T in slots, batches of rounds and the staggered schedule) over the blocks.  TUNA_MODE_STAGED: pack -> exchange -> unpack, the paper's
  *                three steps as three kernels.  TUNA_MODE_FUSED: the one-kernel hops.
  *   staggered, t_layout, block_count, profile: as TUNA_OPT_STAGGERED, TUNA_OPT_DENSE_T,
  *                TUNA_OPT_BLOCK_COUNT, TUNA_OPT_PROFILE below.

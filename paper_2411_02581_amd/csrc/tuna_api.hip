@@ -265,7 +265,7 @@ struct DataSizes {
 
 DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long total_chunks, bool fused,
                          bool staggered = false, bool dense = false, unsigned long long t_chunks = 0,
-                         bool final_tiled = false) {
+                         bool tiled = false) {
     // t_chunks: exact-size T as the host laid it out (colour_classes)
     DataSizes d{};
     const bool any_phase = !pl.phases.empty() && total_chunks > 0;
@@ -273,9 +273,9 @@ DataSizes data_sizes_for(const PlanHost& pl, long long M, unsigned long long tot
     const size_t rank_pad = (size_t)pl.P * kRankAlignChunks;
     d.stage_chunks = any_phase ? (size_t)total_chunks + rank_pad : 0;
     // fused rounds cut chunks at destination lines: up to one more chunk per moving block
-    // the destination-tiled final hop counts 16-byte pieces of R: a block owns at most its chunks plus the
+    // the destination-tiled hop counts 16-byte pieces of R and T: a block owns at most its chunks plus the
     // 7 pieces from its line's start, 7 that complete the previous run's line, one for an unaligned end
-    const size_t head_chunks = ((fused || staggered) ? (size_t)pl.P * pl.P : 0) * (final_tiled ? 16 : 1);
+    const size_t head_chunks = ((fused || staggered) ? (size_t)pl.P * pl.P : 0) * (tiled ? 16 : 1);
     d.unit_cap = any_phase ? (size_t)((total_chunks + head_chunks) / kUnitChunks) + pl.P + 1 : 0;
     d.slots = pl.slots;
     d.slot_bytes = (M + 127) / 128 * 128;     // whole 128-byte lines per slot
@@ -538,7 +538,7 @@ struct Prepared {
     // ranks' places inside a class are assigned on the device, phase by phase
     bool exact_t = false;               // T in exact size, and the schedule has T at all
     bool exact_kernels = false;         // T in exact size was asked for
-    bool final_tiled = false;           // the last phase runs as the destination-tiled final hop (k_copy_final)
+    bool tiled = false;                 // one-kernel phases run as the destination-tiled hop (k_copy_tiled) where they can
     std::vector<int*> tpre;             // per phase: the blocks' offsets in message order (one array shared, or one each)
     ExactT x{};
     long long* d_cbase = nullptr;       // [classes]: where the host placed every class in T
@@ -732,14 +732,14 @@ int prepare_sizes(Prepared& pr, int dense_option, hipStream_t s, Status& hs, boo
     pr.max_count = hs.max_count;
     pr.total_bytes = hs.total_bytes;
     pr.user_limit = (unsigned long long)(uintptr_t)pr.sendbuf + hs.send_extent;
-    // The last phase as the destination-tiled final hop: one-kernel phases over all rounds at once, receive
-    // regions dense (validation flag), word- or chunk-granular data (whole-line data is as fast in the copy
-    // engine, byte-granular data would need the pieces at block edges put together byte by byte), blocks
-    // that are not all tiny (those have k_hop_small).
-    pr.final_tiled = pr.fused && !pr.staggered && pr.block_count == 0 && !(hs.flags & 8u) && (pr.gran == 4 || pr.gran == 16) &&
-                     hs.max_count > kSmallBlockBytes && !pr.dp->host.phases.empty();
+    // The destination-tiled hop: one-kernel phases over all rounds at once, receive regions dense (validation
+    // flag), word- or chunk-granular data (whole-line data is as fast in the copy engine, byte-granular data
+    // would need the pieces at block edges put together byte by byte), blocks that are not all tiny (those
+    // have k_hop_small).
+    pr.tiled = pr.fused && !pr.staggered && pr.block_count == 0 && !(hs.flags & 8u) && (pr.gran == 4 || pr.gran == 16) &&
+               hs.max_count > kSmallBlockBytes && !pr.dp->host.phases.empty();
     pr.ds = data_sizes_for(pr.dp->host, hs.max_count, hs.total_chunks, pr.fused, pr.staggered, pr.exact_t, pr.t_chunks,
-                           pr.final_tiled);
+                           pr.tiled);
     return TUNA_OK;
 }
 
@@ -785,15 +785,16 @@ bool small_blocks(const Prepared& pr) { return pr.max_count > 0 && pr.max_count 
 // size every other one too -- the blocks a rank stores into T lie back to back inside their class, so their
 // destinations form runs just like those in R.  (T in slots keeps the copy engine: its slot tails are filled
 // up to the line by a path of their own.)
-bool phase_is_final_tiled(const Prepared& pr, size_t i) {
-    return pr.final_tiled && (i + 1 == pr.dp->host.phases.size() || pr.exact_t);
+bool phase_is_tiled(const Prepared& pr, size_t i) {
+    return pr.tiled && (i + 1 == pr.dp->host.phases.size() || pr.exact_t);
 }
 
 int launch_resolve(const Prepared& pr, size_t i, const int32_t* nxt, const HopDev& hop, hipStream_t s);
 
-// The metadata of the last phase when it runs as the destination-tiled final hop: the size exchange, every
-// block's source and destination, then the layout of the 16-byte pieces of R in place of the chunk scan.
-int launch_final_metadata(const Prepared& pr, size_t i, const int32_t* cur, int32_t* nxt, const LayoutDev& Ls,
+// The metadata of a phase that runs as the destination-tiled hop: the size exchange, the places in T of the
+// blocks it stores there, every block's source and destination, then the layout of the 16-byte pieces of the
+// destinations in place of the chunk scan.
+int launch_tiled_metadata(const Prepared& pr, size_t i, const int32_t* cur, int32_t* nxt, const LayoutDev& Ls,
                           const LayoutDev& Lr, const HopDev& hop, hipStream_t s) {
     const PhaseHost& ph = pr.dp->host.phases[i];
     const int P = pr.P;
@@ -821,9 +822,9 @@ int launch_final_metadata(const Prepared& pr, size_t i, const int32_t* cur, int3
     }
     int rc = launch_resolve(pr, i, nxt, hop, s);
     if (rc != TUNA_OK) return rc;
-    FinalLayoutArgs fa{};
+    TiledLayoutArgs fa{};
     fa.hop = hop; fa.nseg = ph.nseg; fa.P = P; fa.Lr = Lr; fa.rank_bytes = last ? pr.rank_bytes : nullptr;
-    hipLaunchKernelGGL(k_final_layout, dim3(P), dim3(kScanThreads), 0, s, fa);
+    hipLaunchKernelGGL(k_tiled_layout, dim3(P), dim3(kScanThreads), 0, s, fa);
     HIPCHK(hipGetLastError());
     hipLaunchKernelGGL(k_layout_base, dim3(1), dim3(kScanThreads), 0, s, P, Lr, Ls, 1, &pr.sb.d_status->phase_chunks[i], 0,
                        ExactT{}, pr.rank_bytes, &pr.sb.d_status->phase_bytes[i], pr.sb.d_status->phase_units[i]);
@@ -838,7 +839,7 @@ int launch_phase_metadata(const Prepared& pr, size_t i, const int32_t* cur, int3
                           const LayoutDev& Lr, const HopDev& hop, hipStream_t s) {
     const PhaseHost& ph = pr.dp->host.phases[i];
     const bool one_kernel = phase_is_one_kernel(pr, ph);
-    if (phase_is_final_tiled(pr, i)) return launch_final_metadata(pr, i, cur, nxt, Ls, Lr, hop, s);
+    if (phase_is_tiled(pr, i)) return launch_tiled_metadata(pr, i, cur, nxt, Ls, Lr, hop, s);
     PhaseLayoutArgs m{};
     m.cur = cur; m.nxt = nxt; m.zt = pr.dp->d_zt[i]; m.seg = pr.dp->d_seg[i]; m.nseg = ph.nseg;
     m.P = pr.P; m.Q = pr.Q; m.N = pr.N; m.dim = ph.dim; m.rx = (int)ph.rx;
@@ -1012,20 +1013,20 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
             mark(pr.ctx, s, kCatPack, (int)i);
             continue;
         }
-        if (phase_is_final_tiled(pr, i)) {
-            // the last phase, tiled over the 16-byte pieces of R (k_copy_final); its time is reported as the
+        if (phase_is_tiled(pr, i)) {
+            // tiled over the 16-byte pieces of the destinations (k_copy_tiled); its time is reported as the
             // phase's unpack time, so that it can be told from the copy engine's one-kernel hops
-            FinalCopyArgs fa{};
+            TiledCopyArgs fa{};
             fa.L = Lr; fa.hop = hop; fa.nseg = ph.nseg; fa.T = pr.T; fa.user_limit = pr.user_limit;
             const dim3 grid((unsigned)((launch_units + kCopyThreads / kWave - 1) / (kCopyThreads / kWave)));
             if (grid.x) {
                 const int resident = short_launch ? 8 : 7;
                 if (pr.gran >= 16) {
-                    static const size_t lds = static_lds_of(k_copy_final<16>);
-                    hipLaunchKernelGGL(k_copy_final<16>, grid, dim3(kCopyThreads), occupancy_padding(resident, lds), s, fa);
+                    static const size_t lds = static_lds_of(k_copy_tiled<16>);
+                    hipLaunchKernelGGL(k_copy_tiled<16>, grid, dim3(kCopyThreads), occupancy_padding(resident, lds), s, fa);
                 } else {
-                    static const size_t lds = static_lds_of(k_copy_final<4>);
-                    hipLaunchKernelGGL(k_copy_final<4>, grid, dim3(kCopyThreads), occupancy_padding(resident, lds), s, fa);
+                    static const size_t lds = static_lds_of(k_copy_tiled<4>);
+                    hipLaunchKernelGGL(k_copy_tiled<4>, grid, dim3(kCopyThreads), occupancy_padding(resident, lds), s, fa);
                 }
                 HIPCHK(hipGetLastError());
             }

@@ -300,7 +300,7 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
                 }
                 if (rdispls) {
                     // dense receive regions: every block starts where its predecessor in source order ends
-                    // (flag 8 when not; the destination-tiled final hop needs it).  A wave holds 64
+                    // (flag 8 when not; the destination-tiled hop needs it).  A wave holds 64
                     // neighbours of one row; the last lane reads its successor itself.
                     long long dn = __shfl_down(d, 1, kWave);
                     if (tx == kValTile - 1 && in && i + 1 < P) dn = rdispls[(size_t)jr * P + i + 1];
@@ -989,7 +989,7 @@ __global__ void __launch_bounds__(256) k_resolve_hop(const ResolveArgs a) {
     const int ssrc = a.seg.src[s], sdst = a.seg.dst[s];
     if (sz <= 0) {
         // an empty block owns no chunk and is never copied; a final one still records where it would lie in
-        // R, so that the destination-tiled final hop sees the blocks around it as one contiguous run
+        // R, so that the destination-tiled hop sees the blocks around it as one contiguous run
         unsigned long long d0 = 0;
         if (sdst < 0) {
             int sn = n + j; if (sn >= a.N) sn -= a.N;
@@ -1349,20 +1349,20 @@ k_copy(const CopyArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
-// The destination-tiled final hop.  In the last phase of a schedule every moving block is final
-// (Algorithm "TuNA", lines 16-18: no higher non-zero digit), and when the receive regions are dense
-// (every rank's blocks back to back in source order, the usual layout) what a rank receives lands in a
-// few long contiguous runs of R.  The copy engine cuts such a phase into 16-byte chunks per block; a
-// block that does not start on a 16-byte boundary shares a chunk with its predecessor, the chunk count
-// drifts against the addresses, and a wave's 64-lane store never covers whole 128-byte lines: measured,
-// streaming stores that begin and end inside lines cost 13 % of the hop's rate (blocks of whole lines,
-// destination 4 or 16 bytes off a line: 4.9 and 4.7 TB/s against 5.6 to 5.8 aligned).  Here the unit
-// of work is the destination itself: a run is cut into its 16-byte pieces from the 128-byte line it
-// starts in to the line it ends in, every piece belongs to exactly one lane, a piece that holds the
-// end of one block and the start of the next is assembled by that lane from both, and every wave store
-// covers eight whole lines.
+// The destination-tiled hop.  What a rank receives in a one-kernel phase lands in a few long contiguous
+// runs: the final blocks in R (Algorithm "TuNA", lines 16-18) when the receive regions are dense -- every
+// rank's blocks back to back in source order, the usual layout --, the others in exact-size T, where
+// the blocks of a class lie back to back.  The copy engine cuts such a phase into 16-byte chunks per
+// block; a block that does not start on a 16-byte boundary shares a chunk with its predecessor, the
+// chunk count drifts against the addresses, and a wave's 64-lane store never covers whole 128-byte
+// lines: measured, streaming stores that begin and end inside lines cost 13 % of the hop's rate
+// (blocks of whole lines, destination 4 or 16 bytes off a line: 4.9 and 4.7 TB/s against 5.6 to 5.8
+// aligned).  Here the unit of work is the destination itself: a run is cut into its 16-byte pieces
+// from the 128-byte line it starts in to the line it ends in, every piece belongs to exactly one lane,
+// a piece that holds the end of one block and the start of the next is assembled by that lane from
+// both, and every wave store covers eight whole lines.
 //
-// k_final_layout (one workgroup per rank, the scan machinery of k_phase_layout): from the resolved
+// k_tiled_layout (one workgroup per rank, the scan machinery of k_phase_layout): from the resolved
 // destinations and sizes (k_resolve_hop) the number of pieces every segment owns.  Segment s with
 // destination a, size n, end E = a + n continues a run when its predecessor in message order ends at a
 // (empty blocks lie where they would lie, so they continue runs too); it then owns the pieces from
@@ -1372,7 +1372,7 @@ k_copy(const CopyArgs a) {
 // starts at a multiple of 8 pieces.  The prefix row has the same form as a chunk prefix row:
 // k_layout_base and k_layout_units cut it into wave units of 256 pieces.
 // ------------------------------------------------------------------------------------------
-struct FinalLayoutArgs {
+struct TiledLayoutArgs {
     HopDev hop;
     int nseg, P;
     LayoutDev Lr;
@@ -1380,7 +1380,7 @@ struct FinalLayoutArgs {
 };
 
 // pieces segment s owns, and the dead pieces in front of them
-__device__ __forceinline__ int final_pieces(unsigned long long a, int n, bool has_prev, unsigned long long e_prev,
+__device__ __forceinline__ int tiled_pieces(unsigned long long a, int n, bool has_prev, unsigned long long e_prev,
                                             int* dead) {
     const unsigned long long e = a + (unsigned long long)n;
     const bool new_run = !has_prev || e_prev != a;
@@ -1390,7 +1390,7 @@ __device__ __forceinline__ int final_pieces(unsigned long long a, int n, bool ha
     return last > first ? (int)(last - first) : 0;
 }
 
-__global__ void __launch_bounds__(kScanThreads) k_final_layout(const FinalLayoutArgs a) {
+__global__ void __launch_bounds__(kScanThreads) k_tiled_layout(const TiledLayoutArgs a) {
     __shared__ int wsum[kScanThreads / kWave];
     __shared__ unsigned long long wbytes[kScanThreads / kWave];
     const int p = blockIdx.x;
@@ -1413,7 +1413,7 @@ __global__ void __launch_bounds__(kScanThreads) k_final_layout(const FinalLayout
                 unsigned long long e_prev = 0;
                 if (s > 0) e_prev = a.hop.dst[o + s - 1] + (unsigned long long)a.hop.size[o + s - 1];
                 int dead;
-                const int own = final_pieces(d, n, s > 0, e_prev, &dead);
+                const int own = tiled_pieces(d, n, s > 0, e_prev, &dead);
                 cr[k] = dead + own;
                 bytes += (unsigned long long)n;
             }
@@ -1441,18 +1441,19 @@ __global__ void __launch_bounds__(kScanThreads) k_final_layout(const FinalLayout
 }
 
 // ------------------------------------------------------------------------------------------
-// k_copy_final: the payload kernel of the destination-tiled final hop.  Work unit = one wavefront x
-// 256 consecutive pieces of one rank (k_final_layout); no workgroup barrier.  Lane i of a window loads
+// k_copy_tiled: the payload kernel of the destination-tiled hop.  Work unit = one wavefront x
+// 256 consecutive pieces of one rank (k_tiled_layout); no workgroup barrier.  Lane i of a window loads
 // the prefix and the resolved source, destination and size of segment s0 + i and derives the address of
 // the segment's first own piece; every lane finds the segment of each of its 4 pieces by the same
 // branch-free search as the copy engine.  A piece that lies inside its block is one 16-byte load at
 // the source's own alignment and one aligned streaming store.  A piece at a block's edge is put together
-// word by word (GRAN = 4: every size and address is a multiple of 4) from the blocks that follow each
-// other in the run -- read from the hop arrays, the window need not hold them -- and stored whole when
-// all four words belong to blocks, else word by word (the ends of a run: bytes outside every block
-// are never written).  With GRAN = 16 every piece is inside a block or outside all of them.
+// word by word (GRAN = 4: every size and address is a multiple of 4) from its block and the one behind it
+// in the run (a walk over the hop arrays when more blocks than that meet in one piece) and stored whole
+// when all four words belong to blocks, else word by word (the ends of a run: bytes outside every block
+// are never written).  With GRAN = 16 every piece is inside a block or outside all of them.  Blocks bound
+// for T take whole chunks; a load never leaves the part of S that holds blocks.
 // ------------------------------------------------------------------------------------------
-struct FinalCopyArgs {
+struct TiledCopyArgs {
     LayoutDev L;
     HopDev hop;
     int nseg;
@@ -1461,7 +1462,7 @@ struct FinalCopyArgs {
 };
 
 template <int GRAN>
-__global__ void __launch_bounds__(kCopyThreads) k_copy_final(const FinalCopyArgs a) {
+__global__ void __launch_bounds__(kCopyThreads) k_copy_tiled(const TiledCopyArgs a) {
     __shared__ int s_pre[kCopyThreads / kWave][kWave];
     __shared__ int s_size[kCopyThreads / kWave][kWave];
     __shared__ int s_off0[kCopyThreads / kWave][kWave];
@@ -1522,7 +1523,7 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy_final(const FinalCopyArgs
         // line; one that continues a run owns them from the first piece that begins inside the block.  Dead
         // pieces and the pieces in front of the block come out with negative offsets and hold none of its bytes.
         int dead;
-        (void)final_pieces(hd_, size, s_tab > 0, e_prev, &dead);
+        (void)tiled_pieces(hd_, size, s_tab > 0, e_prev, &dead);
         const bool new_run = s_tab == 0 || e_prev != hd_;
         const int off0 = (new_run ? -(int)((unsigned int)hd_ & 127u) : (int)((0u - (unsigned int)hd_) & 15u)) - (dead << 4);
         const unsigned long long src_addr = (hs_ & ~(kHopInT | kHopFill)) + ((hs_ & kHopInT) ? tb : 0ull);

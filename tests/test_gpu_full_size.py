@@ -119,8 +119,8 @@ def test_config3_caller_workspace_and_phase_times(tuna):
             assert st.n_phases == 4 and st.ms_total > 0
             for x in range(st.n_phases):
                 ph = st.phase[x]
-                # one-kernel phases report one payload kernel: the hop as pack time, the destination-tiled
-                # final hop of the last phase as unpack time
+                # one-kernel phases report one payload kernel: the copy engine's hop as pack time, the
+                # destination-tiled hop as unpack time
                 assert ph.ms_metadata > 0 and (ph.ms_pack > 0 or (fused and ph.ms_unpack > 0))
                 assert (ph.ms_exchange > 0 and ph.ms_unpack > 0) or fused
             # the same exchange as a persistent plan (its staging is sized by the largest phase)

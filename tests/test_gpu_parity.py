@@ -380,7 +380,7 @@ def test_caller_workspace_and_profiling(tuna):
     try:
         run_flat(tuna, prob, 4)
         st = tuna.tuna_get_stats()
-        # every phase has a payload kernel (the destination-tiled final hop reports its time as unpack time)
+        # every phase has a payload kernel (the destination-tiled hop reports its time as unpack time)
         assert st.ms_total > 0 and all(st.phase[x].ms_pack > 0 or st.phase[x].ms_unpack > 0 for x in range(st.n_phases))
     finally:
         tuna.tuna_set_option(tuna.TUNA_OPT_PROFILE, 0)
