@@ -705,6 +705,8 @@ bool too_large(int P, const Status& hs) {
     return std::min(by_m, by_all) >= (1ull << 31);
 }
 
+constexpr int kTiledMinMeanBytes = 700;    // see prepare_sizes
+
 // Validation + sizing pass of a call whose arguments, schedule and status buffers are in `pr` (one
 // read-back).  On TUNA_OK with *empty == true there is nothing to move.
 int prepare_sizes(Prepared& pr, int dense_option, hipStream_t s, Status& hs, bool* empty) {
@@ -736,8 +738,13 @@ int prepare_sizes(Prepared& pr, int dense_option, hipStream_t s, Status& hs, boo
     // flag), word- or chunk-granular data (whole-line data is as fast in the copy engine, byte-granular data
     // would need the pieces at block edges put together byte by byte), blocks that are not all tiny (those
     // have k_hop_small).
+    // It pays when the blocks are mostly pieces inside blocks, not edges: measured, 1 KiB blocks gain 8 % per call
+    // at r = P and 512-byte blocks lose 2 %; Zipf sizes with four blocks in five under 256 bytes lose 8 %.  Hence
+    // a mean block of at least kTiledMinMeanBytes and at most a quarter of the blocks short.
+    const unsigned long long P2 = (unsigned long long)P * (unsigned long long)P;
     pr.tiled = pr.fused && !pr.staggered && pr.block_count == 0 && !(hs.flags & 8u) && (pr.gran == 4 || pr.gran == 16) &&
-               hs.max_count > kSmallBlockBytes && !pr.dp->host.phases.empty();
+               hs.max_count > kSmallBlockBytes && !pr.dp->host.phases.empty() &&
+               hs.total_bytes >= (unsigned long long)kTiledMinMeanBytes * P2 && hs.short_blocks * 4 <= P2;
     pr.ds = data_sizes_for(pr.dp->host, hs.max_count, hs.total_chunks, pr.fused, pr.staggered, pr.exact_t, pr.t_chunks,
                            pr.tiled);
     return TUNA_OK;
@@ -1638,14 +1645,14 @@ struct Model {
     double c[kModelTerms];
 };
 struct ModelSet {
-    Model m[2] = {{{0.0445, 0.0355, 0.0085, 1.0234, 0.0416, 0.0, 0.0}},            // [0] three stages
-                  {{0.0401, 0.0383, 0.0024, 0.3625, 0.0353, 0.0224, 1.431}}};     // [1] one-kernel hops
+    Model m[2] = {{{0.0510, 0.0352, 0.0084, 1.0182, 0.0414, 0.0, 0.0}},            // [0] three stages
+                  {{0.0487, 0.0311, 0.0096, 0.3673, 0.0346, 0.0086, 1.5334}}};    // [1] one-kernel hops
     // T in the paper's slots of M bytes: the bytes that pass through T cost more the emptier the slots are
     // (sparse writes and reads): their share of the byte term is scaled by 1 + k * (1 - mean / M)
     double slot_penalty[2] = {0.25, 0.45};
     // byte-granular problems (some count, displacement or buffer address is not a multiple of 4) run the
     // kernel variants that load and store single bytes at block edges: their byte term is scaled by this
-    double byte_granular[2] = {1.3, 1.3};
+    double byte_granular[2] = {1.14, 1.44};
     bool calibrated = false;
 };
 ModelSet g_model;
@@ -1769,7 +1776,9 @@ int calibrate(hipStream_t s) {
     int rc = ensure_device();
     if (rc != TUNA_OK) return rc;
     struct Problem { int P, S; int radices[3]; };
-    const Problem odd = {256, 515, {2, 16, 256}};        // byte-granular: fitted after the others, as a factor on the byte term
+    // byte-granular: fitted after the others, as a factor on the byte term; large enough for that term to be
+    // most of the call's time
+    const Problem odd = {1024, 515, {2, 32, 1024}};
     // tiny (fixed costs), many tiny blocks (per-block and per-entry costs), large blocks beyond the caches
     // (bytes), and a mix; S is 4 bytes off a multiple of 16, the usual alignment of float payloads
     const Problem problems[] = {{32, 68, {2, 6, 32}}, {256, 516, {2, 16, 256}}, {1024, 20, {2, 32, 1024}}, {2048, 36, {8, 2048, 0}},

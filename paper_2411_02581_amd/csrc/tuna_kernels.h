@@ -46,6 +46,7 @@ struct Status {
     unsigned long long total_chunks;   // sum of ceil(count / 16)
     unsigned long long send_extent;    // max over non-empty blocks of sdispls + count: bytes of sendbuf that hold blocks
     unsigned long long t_chunks;       // exact-size T: chunks stored into T over all phases
+    unsigned long long short_blocks;   // blocks of fewer than kShortBlockBytes bytes, empty ones included
     unsigned long long phase_bytes[64];   // payload bytes moved per phase
     unsigned long long phase_chunks[64];  // staged chunks per phase
     unsigned int phase_units[64][2];      // wave units per phase: [0] receive-side layout, [1] send-side layout
@@ -217,6 +218,7 @@ __global__ void __launch_bounds__(256) k_build_hops(const PlanScalars pl, int32_
 // ------------------------------------------------------------------------------------------
 constexpr int kValTile = 64;
 constexpr int kValPartial = 8;              // 64-bit words per workgroup in the partial-result array
+constexpr int kShortBlockBytes = 256;       // below this a block is mostly edges to the destination-tiled hop
 __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ sendcounts,
                                                   const int32_t* __restrict__ recvcounts,
                                                   const int64_t* __restrict__ sdispls,
@@ -226,7 +228,7 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
                                                   const unsigned long long* __restrict__ mask, int nph,
                                                   unsigned long long* __restrict__ cls_chunks) {
     __shared__ int tile[kValTile][kValTile + 1];
-    __shared__ unsigned long long red[4][6];
+    __shared__ unsigned long long red[4][7];
     extern __shared__ unsigned long long lcls[];          // class_count(nph) sums of this workgroup (with `mask`)
     const int tx = threadIdx.x, ty = threadIdx.y;
     const int ncls = mask ? class_count(nph) : 0;
@@ -236,7 +238,7 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
     const int ntile = tpr * tpr;
     unsigned int flags = 0, abits = 0;
     int mx = 0;
-    unsigned long long bytes = 0, chunks = 0, extent = 0, tchunks = 0;
+    unsigned long long bytes = 0, chunks = 0, extent = 0, tchunks = 0, shortb = 0;
     for (int t = blockIdx.x; t < ntile; t += gridDim.x) {        // a workgroup strides over tiles
         const int bi = (t / tpr) * kValTile, bj = (t % tpr) * kValTile;
         const int j = bj + tx;
@@ -258,6 +260,7 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
                 }
                 mx = max(mx, c);
                 bytes += (unsigned long long)c;
+                shortb += c < kShortBlockBytes ? 1u : 0u;
                 const unsigned long long ch = (unsigned long long)((c + 15) >> 4);
                 chunks += ch;
                 if (hm1 && c > 0) {
@@ -319,24 +322,25 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
         bytes += __shfl_xor(bytes, d, kWave);
         chunks += __shfl_xor(chunks, d, kWave);
         tchunks += __shfl_xor(tchunks, d, kWave);
+        shortb += __shfl_xor(shortb, d, kWave);
         extent = max(extent, (unsigned long long)__shfl_xor(extent, d, kWave));
     }
     if (tx == 0) {                                       // one wave per value of ty
         unsigned long long* r = red[ty];
         r[0] = ((unsigned long long)flags << 32) | (abits & 127u);
-        r[1] = (unsigned long long)mx; r[2] = bytes; r[3] = chunks; r[4] = extent; r[5] = tchunks;
+        r[1] = (unsigned long long)mx; r[2] = bytes; r[3] = chunks; r[4] = extent; r[5] = tchunks; r[6] = shortb;
     }
     __syncthreads();
     if (tx == 0 && ty == 0) {
-        unsigned long long fa = 0, m = 0, by = 0, ch = 0, ex = 0, tc = 0;
+        unsigned long long fa = 0, m = 0, by = 0, ch = 0, ex = 0, tc = 0, sb = 0;
         for (int w = 0; w < 4; ++w) {
             fa |= red[w][0]; m = max(m, red[w][1]); by += red[w][2]; ch += red[w][3]; ex = max(ex, red[w][4]);
-            tc += red[w][5];
+            tc += red[w][5]; sb += red[w][6];
         }
         // one row of partial results per workgroup, folded by k_validate_finish: thousands of atomics
         // on the same few addresses would take longer than reading the matrices
         unsigned long long* o = partial + (size_t)blockIdx.x * kValPartial;
-        o[0] = fa; o[1] = m; o[2] = by; o[3] = ch; o[4] = ex; o[5] = tc;
+        o[0] = fa; o[1] = m; o[2] = by; o[3] = ch; o[4] = ex; o[5] = tc; o[6] = sb;
     }
     // the class sums: one atomic per class and workgroup that holds any of it (cls_chunks starts at zero)
     for (int i = ty * kValTile + tx; i < ncls; i += 4 * kValTile)
@@ -352,11 +356,11 @@ __global__ void __launch_bounds__(256) k_zero64(unsigned long long* __restrict__
 // k_validate_finish: folds the workgroups' partial results into the status block (one workgroup).
 __global__ void __launch_bounds__(256) k_validate_finish(const unsigned long long* __restrict__ partial, int n,
                                                          Status* __restrict__ st) {
-    __shared__ unsigned long long red[4][6];
-    unsigned long long fa = 0, m = 0, by = 0, ch = 0, ex = 0, tc = 0;
+    __shared__ unsigned long long red[4][7];
+    unsigned long long fa = 0, m = 0, by = 0, ch = 0, ex = 0, tc = 0, sb = 0;
     for (int i = threadIdx.x; i < n; i += blockDim.x) {
         const unsigned long long* o = partial + (size_t)i * kValPartial;
-        fa |= o[0]; m = max(m, o[1]); by += o[2]; ch += o[3]; ex = max(ex, o[4]); tc += o[5];
+        fa |= o[0]; m = max(m, o[1]); by += o[2]; ch += o[3]; ex = max(ex, o[4]); tc += o[5]; sb += o[6];
     }
 #pragma unroll
     for (int d = kWave / 2; d > 0; d >>= 1) {
@@ -366,15 +370,16 @@ __global__ void __launch_bounds__(256) k_validate_finish(const unsigned long lon
         ch += __shfl_xor(ch, d, kWave);
         ex = max(ex, (unsigned long long)__shfl_xor(ex, d, kWave));
         tc += __shfl_xor(tc, d, kWave);
+        sb += __shfl_xor(sb, d, kWave);
     }
     const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
-    if (lane == 0) { red[wv][0] = fa; red[wv][1] = m; red[wv][2] = by; red[wv][3] = ch; red[wv][4] = ex; red[wv][5] = tc; }
+    if (lane == 0) { red[wv][0] = fa; red[wv][1] = m; red[wv][2] = by; red[wv][3] = ch; red[wv][4] = ex; red[wv][5] = tc; red[wv][6] = sb; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        fa = m = by = ch = ex = tc = 0;
+        fa = m = by = ch = ex = tc = sb = 0;
         for (int w = 0; w < 4; ++w) {
             fa |= red[w][0]; m = max(m, red[w][1]); by += red[w][2]; ch += red[w][3]; ex = max(ex, red[w][4]);
-            tc += red[w][5];
+            tc += red[w][5]; sb += red[w][6];
         }
         st->flags = (unsigned int)(fa >> 32);
         st->align_bits = (unsigned int)(fa & 127u);
@@ -383,6 +388,7 @@ __global__ void __launch_bounds__(256) k_validate_finish(const unsigned long lon
         st->total_chunks = ch;
         st->send_extent = ex;
         st->t_chunks = tc;
+        st->short_blocks = sb;
     }
 }
 
