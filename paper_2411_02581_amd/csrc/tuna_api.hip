@@ -878,9 +878,16 @@ int launch_resolve(const Prepared& pr, size_t i, const int32_t* nxt, const HopDe
     ra.x = exact_t_of(pr, i);
     ra.hop = hop;
     ra.exact_sizes = small_blocks(pr) ? 1 : 0;
-    const dim3 grid((unsigned)((ph.nseg + 255) / 256), (unsigned)pr.P);
-    if (pr.exact_kernels) hipLaunchKernelGGL(k_resolve_hop<true>, grid, dim3(256), 0, s, ra);
-    else hipLaunchKernelGGL(k_resolve_hop<false>, grid, dim3(256), 0, s, ra);
+    if (ph.nz >= kResolveTile) {     // many rounds: neighbouring segments come from neighbouring senders
+        constexpr int per = 256 / kResolveTile;
+        const dim3 grid((unsigned)((ph.nseg + per - 1) / per), (unsigned)((pr.P + kResolveTile - 1) / kResolveTile));
+        if (pr.exact_kernels) hipLaunchKernelGGL((k_resolve_hop<true, kResolveTile>), grid, dim3(256), 0, s, ra);
+        else hipLaunchKernelGGL((k_resolve_hop<false, kResolveTile>), grid, dim3(256), 0, s, ra);
+    } else {
+        const dim3 grid((unsigned)((ph.nseg + 255) / 256), (unsigned)pr.P);
+        if (pr.exact_kernels) hipLaunchKernelGGL((k_resolve_hop<true, 1>), grid, dim3(256), 0, s, ra);
+        else hipLaunchKernelGGL((k_resolve_hop<false, 1>), grid, dim3(256), 0, s, ra);
+    }
     HIPCHK(hipGetLastError());
     return TUNA_OK;
 }

@@ -962,8 +962,12 @@ __device__ __forceinline__ unsigned long long exact_t_src(unsigned char* T, cons
 // receives (Algorithm "TuNA", lines 15-20 collapsed into one hop: the block goes from where its sender
 // holds it -- S at sdispls[sender][destination], or the sender's T -- straight to where its receiver
 // keeps it -- R at rdispls[receiver][source], or the receiver's T), in the receiver's message order.
-// One thread per (segment, receiving rank); grid (ceil(nseg / 256), P).  Addresses in T are stored as
-// offsets (kHopInT) because a persistent plan resolves them before its T is allocated.
+// One thread per (segment, receiving rank).  TP = 1: a workgroup takes 256 segments of one rank, grid
+// (ceil(nseg / 256), P).  TP = 16: a workgroup takes 16 segments of each of 16 ranks, grid (ceil(nseg / 16),
+// ceil(P / 16)), for phases of many rounds: there neighbouring segments have neighbouring senders, the
+// never-moved blocks are looked up in a column of sdispls, and a tile of 16 x 16 touches 31 of its lines
+// where 256 segments of one rank touch 256.  Addresses in T are stored as offsets (kHopInT) because a
+// persistent plan resolves them before its T is allocated.
 // ------------------------------------------------------------------------------------------
 struct ResolveArgs {
     const int32_t* nxt;                 // [P][P] block sizes after the phase's size exchange (the receiver's view)
@@ -981,11 +985,14 @@ struct ResolveArgs {
     int exact_sizes;                    // 1: every size is the block's byte count (k_hop_small copies exactly that), also into T
 };
 
-template <bool DENSE>
+constexpr int kResolveTile = 16;
+
+template <bool DENSE, int TP>
 __global__ void __launch_bounds__(256) k_resolve_hop(const ResolveArgs a) {
-    const int s = blockIdx.x * blockDim.x + threadIdx.x;
-    if (s >= a.nseg) return;
-    const int p = blockIdx.y;
+    static_assert(TP == 1 || TP == kResolveTile, "one rank or a tile of ranks per workgroup");
+    const int s = TP == 1 ? blockIdx.x * 256 + threadIdx.x : blockIdx.x * (256 / TP) + (threadIdx.x % (256 / TP));
+    const int p = TP == 1 ? blockIdx.y : blockIdx.y * TP + threadIdx.x / (256 / TP);
+    if (s >= a.nseg || p >= a.P) return;
     const int n = p / a.Q, g = p - n * a.Q;
     const int e = a.seg.e[s];
     const int sz = a.nxt[(size_t)p * a.P + e];
