@@ -243,71 +243,104 @@ __global__ void __launch_bounds__(256) k_validate(const int32_t* __restrict__ se
         const int bi = (t / tpr) * kValTile, bj = (t % tpr) * kValTile;
         const int j = bj + tx;
         const int jn = hm1 ? j / Q : 0, jg = hm1 ? j - jn * Q : 0;   // the destination's node and local id
-        for (int a = ty; a < kValTile; a += 4) {
-            const int i = bi + a;
-            int c = 0;
-            if (i < P && j < P) {
-                c = sendcounts[(size_t)i * P + j];
-                if (c < 0) { flags |= 1u; c = 0; }
-                abits |= (unsigned int)c;
-                if (sdispls) {
-                    const int64_t d = sdispls[(size_t)i * P + j];
-                    abits |= (unsigned int)d & 127u;
-                    if (c > 0) {
-                        if (d >= 0) extent = max(extent, (unsigned long long)d + (unsigned long long)c);
-                        else flags |= 4u;
+        // four rows per step, their loads issued together from clamped indices: with one row per step the pass
+        // was a chain of 32 dependent memory round trips per tile (48 us for 1024 ranks)
+        for (int a0 = ty; a0 < kValTile; a0 += 16) {
+            int cv[4];
+            long long dv[4];
+            bool ok[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = bi + a0 + 4 * u;
+                ok[u] = i < P && j < P;
+                const size_t idx = ok[u] ? (size_t)i * P + j : 0;
+                cv[u] = sendcounts[idx];
+                dv[u] = sdispls ? sdispls[idx] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int a = a0 + 4 * u;
+                const int i = bi + a;
+                int c = 0;
+                if (ok[u]) {
+                    c = cv[u];
+                    if (c < 0) { flags |= 1u; c = 0; }
+                    abits |= (unsigned int)c;
+                    if (sdispls) {
+                        const int64_t d = dv[u];
+                        abits |= (unsigned int)d & 127u;
+                        if (c > 0) {
+                            if (d >= 0) extent = max(extent, (unsigned long long)d + (unsigned long long)c);
+                            else flags |= 4u;
+                        }
                     }
-                }
-                mx = max(mx, c);
-                bytes += (unsigned long long)c;
-                shortb += c < kShortBlockBytes ? 1u : 0u;
-                const unsigned long long ch = (unsigned long long)((c + 15) >> 4);
-                chunks += ch;
-                if (hm1 && c > 0) {
-                    const int in = i / Q, ig = i - in * Q;
-                    int dn = in - jn; if (dn < 0) dn += N;
-                    int dg = ig - jg; if (dg < 0) dg += Q;
-                    tchunks += ch * (unsigned long long)hm1[dn * Q + dg];
-                    if (mask) {
-                        // the block waits in T between every two consecutive phases in which it moves
-                        unsigned long long m = mask[dn * Q + dg];
-                        int f = __ffsll((long long)m) - 1;
-                        m &= m - 1;
-                        while (m) {
-                            const int y = __ffsll((long long)m) - 1;
+                    mx = max(mx, c);
+                    bytes += (unsigned long long)c;
+                    shortb += c < kShortBlockBytes ? 1u : 0u;
+                    const unsigned long long ch = (unsigned long long)((c + 15) >> 4);
+                    chunks += ch;
+                    if (hm1 && c > 0) {
+                        const int in = i / Q, ig = i - in * Q;
+                        int dn = in - jn; if (dn < 0) dn += N;
+                        int dg = ig - jg; if (dg < 0) dg += Q;
+                        tchunks += ch * (unsigned long long)hm1[dn * Q + dg];
+                        if (mask) {
+                            // the block waits in T between every two consecutive phases in which it moves
+                            unsigned long long m = mask[dn * Q + dg];
+                            int f = __ffsll((long long)m) - 1;
                             m &= m - 1;
-                            atomicAdd(&lcls[class_id(f, y, nph)], ch);
-                            f = y;
+                            while (m) {
+                                const int y = __ffsll((long long)m) - 1;
+                                m &= m - 1;
+                                atomicAdd(&lcls[class_id(f, y, nph)], ch);
+                                f = y;
+                            }
                         }
                     }
                 }
+                tile[a][tx] = c;
             }
-            tile[a][tx] = c;
         }
         __syncthreads();
         if (recvcounts) {
-            for (int a = ty; a < kValTile; a += 4) {
-                const int jr = bj + a, i = bi + tx;     // recvcounts[jr][i] must equal sendcounts[i][jr]
-                const bool in = i < P && jr < P;
-                int rc = 0;
-                long long d = 0;
-                if (in) {
-                    rc = recvcounts[(size_t)jr * P + i];
-                    if (rc < 0) flags |= 1u;
-                    else if (rc != tile[tx][a]) flags |= 2u;
-                    if (rdispls) {
-                        d = rdispls[(size_t)jr * P + i];
-                        abits |= (unsigned int)d & 127u;
-                        if (rc > 0 && d < 0) flags |= 4u;
-                    }
+            for (int a0 = ty; a0 < kValTile; a0 += 16) {
+                int rv[4];
+                long long dv[4], dx[4];
+                bool in[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int jr = bj + a0 + 4 * u, i = bi + tx;     // recvcounts[jr][i] must equal sendcounts[i][jr]
+                    in[u] = i < P && jr < P;
+                    const size_t idx = in[u] ? (size_t)jr * P + i : 0;
+                    rv[u] = recvcounts[idx];
+                    dv[u] = rdispls ? rdispls[idx] : 0;
+                    // the last lane of a row reads its successor's displacement itself (below)
+                    dx[u] = (rdispls && tx == kValTile - 1 && in[u] && i + 1 < P) ? rdispls[idx + 1] : 0;
                 }
-                if (rdispls) {
-                    // dense receive regions: every block starts where its predecessor in source order ends
-                    // (flag 8 when not; the destination-tiled hop needs it).  A wave holds 64
-                    // neighbours of one row; the last lane reads its successor itself.
-                    long long dn = __shfl_down(d, 1, kWave);
-                    if (tx == kValTile - 1 && in && i + 1 < P) dn = rdispls[(size_t)jr * P + i + 1];
-                    if (in && i + 1 < P && dn != d + (long long)max(rc, 0)) flags |= 8u;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int a = a0 + 4 * u;
+                    const int i = bi + tx;
+                    int rc = 0;
+                    long long d = 0;
+                    if (in[u]) {
+                        rc = rv[u];
+                        if (rc < 0) flags |= 1u;
+                        else if (rc != tile[tx][a]) flags |= 2u;
+                        if (rdispls) {
+                            d = dv[u];
+                            abits |= (unsigned int)d & 127u;
+                            if (rc > 0 && d < 0) flags |= 4u;
+                        }
+                    }
+                    if (rdispls) {
+                        // dense receive regions: every block starts where its predecessor in source order ends
+                        // (flag 8 when not; the destination-tiled hop needs it).  A wave holds 64
+                        // neighbours of one row.
+                        long long dn = __shfl_down(d, 1, kWave);
+                        if (tx == kValTile - 1) dn = dx[u];
+                        if (in[u] && i + 1 < P && dn != d + (long long)max(rc, 0)) flags |= 8u;
+                    }
                 }
             }
         }
