@@ -1668,13 +1668,14 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy_tiled(const TiledCopyArgs
                     if (on && kk == ks) { v[kk][0] = w[0]; v[kk][1] = w[1]; v[kk][2] = w[2]; v[kk][3] = w[3]; }
             }
             // rare: the blocks of a piece reach past the entries the window holds, or several blocks end inside
-            // one piece (a row of tiny or empty blocks): a walk over the hop arrays in global memory
+            // one piece (a row of tiny or empty blocks): a walk over the entries in the window, and over the hop
+            // arrays in global memory behind it
 #pragma unroll
             for (int k = 0; k < kChunksPerLane; ++k) {
                 if (!(raremask & (1u << k))) continue;
                 int t = sw + lo[k];
                 unsigned long long ta = wdst[lo[k]], te = ta + (unsigned long long)wsize[lo[k]], ts = wsrc[lo[k]];
-                bool in_t = (a.hop.src[ho + t] & kHopInT) != 0;     // a word of a block in S is loaded only inside S
+                long long tl = wlim[lo[k]];                         // bytes of the block that may be loaded
                 const unsigned long long d = ta + (unsigned long long)(long long)off[k];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
@@ -1683,18 +1684,27 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy_tiled(const TiledCopyArgs
                     while (b >= te) {                // the word lies behind this block: the next one, if it follows directly
                         ++t;
                         if (t >= a.nseg) { in_run = false; break; }
-                        const unsigned long long nraw = a.hop.dst[ho + t];
-                        const unsigned long long na = (nraw & ~(kHopInT | kHopFill)) + ((nraw & kHopInT) ? tb : 0ull);
+                        const int wi = t - sw;
+                        unsigned long long na, nsa;
+                        int nsz;
+                        long long nl;
+                        if (wi < nload) {            // the window holds the entry
+                            na = wdst[wi]; nsa = wsrc[wi]; nsz = wsize[wi]; nl = wlim[wi];
+                        } else {
+                            const unsigned long long nraw = a.hop.dst[ho + t], nsrc = a.hop.src[ho + t];
+                            na = (nraw & ~(kHopInT | kHopFill)) + ((nraw & kHopInT) ? tb : 0ull);
+                            nsa = (nsrc & ~(kHopInT | kHopFill)) + ((nsrc & kHopInT) ? tb : 0ull);
+                            nsz = a.hop.size[ho + t];
+                            nl = nsz;
+                            if (!(nsrc & kHopInT)) nl = (long long)min((unsigned long long)nsz, a.user_limit > nsa ? a.user_limit - nsa : 0ull);
+                        }
                         if (na != te) { in_run = false; break; }
-                        const unsigned long long nsrc = a.hop.src[ho + t];
-                        ta = na; te = na + (unsigned long long)a.hop.size[ho + t];
-                        ts = (nsrc & ~(kHopInT | kHopFill)) + ((nsrc & kHopInT) ? tb : 0ull);
-                        in_t = (nsrc & kHopInT) != 0;
+                        ta = na; te = na + (unsigned long long)nsz; ts = nsa; tl = nl;
                     }
                     if (!in_run) break;              // nothing behind the run's end belongs to a block
                     if (b >= ta) {
-                        const unsigned long long wa = ts + (b - ta);
-                        v[k][q] = (in_t || wa + 4 <= a.user_limit) ? *reinterpret_cast<const uint32_t*>(wa) : 0u;
+                        const unsigned long long o = b - ta;
+                        v[k][q] = (long long)o < tl ? *reinterpret_cast<const uint32_t*>(ts + o) : 0u;
                         emask |= 1u << (4 * k + q);
                     }
                 }
