@@ -163,10 +163,13 @@ int tuna_alltoallv_hier(const void* sendbuf, const int32_t* sendcounts, const in
  *                with all ranks in one memory a hop needs no message, and moving a block straight from
  *                where its sender holds it to where its receiver keeps it reads and writes it once
  *                instead of three times.  When the receive regions are dense (every rank's blocks back to
- *                back in source order), sizes, displacements and buffer addresses are multiples of 4 and T
- *                is kept in exact size, a phase is tiled over its destinations in 128-byte lines; otherwise
- *                (and always for T in slots, batches of rounds and the staggered schedule) over the blocks.  TUNA_MODE_STAGED: pack -> exchange -> unpack, the paper's
- *                three steps as three kernels.  TUNA_MODE_FUSED: the one-kernel hops.
+ *                back in source order), sizes, displacements and buffer addresses are multiples of 4, the
+ *                blocks are mostly longer than a few lines (mean of 700 bytes or more, at most a quarter
+ *                of them under 256 bytes) and T is kept in exact size, a phase is tiled over its
+ *                destinations in 128-byte lines; otherwise (and always for T in slots, batches of rounds
+ *                and the staggered schedule) over the blocks.  Which of the two ran changes no byte.
+ *                TUNA_MODE_STAGED: pack -> exchange -> unpack, the paper's three steps as three kernels.
+ *                TUNA_MODE_FUSED: the one-kernel hops.
  *   staggered, t_layout, block_count, profile: as TUNA_OPT_STAGGERED, TUNA_OPT_DENSE_T,
  *                TUNA_OPT_BLOCK_COUNT, TUNA_OPT_PROFILE below.
  */
@@ -379,14 +382,15 @@ int tuna_debug_phase_sizes(const void* sendbuf, const int32_t* sendcounts, const
  * hops; T in the paper's slots adds to the byte term by how empty the slots are (mean block / M).  When no
  * block exceeds 64 bytes the one-kernel hops run a kernel of their own (one thread per block), whose
  * blocks and bytes are priced by constants of their own, c5 and c6, in place of c4 and c3.
- *   tuna_calibrate   times about fifty immediate calls of dense synthetic problems on the current
+ *   tuna_calibrate   times about sixty immediate calls of dense synthetic problems on the current
  *                    device (a few hundred milliseconds; allocates up to about 8 GiB and frees it;
  *                    synchronises) and fits the constants to them.  Without it the constants are the
  *                    built-in ones, fitted the same way on an MI355X.
  *   tuna_predict_ms  the model's time for one setting.  max_block_bytes = 0: unknown (slots taken as full).
  *                    granularity: the largest of 1, 4, 16, 128 that divides every count, displacement
  *                    and both buffer addresses (tuna_stats_t.granularity), 0 = unknown (taken as 4);
- *                    byte-granular problems run kernel variants whose byte term costs a fitted factor more.
+ *                    byte-granular problems run kernel variants whose byte term costs a fitted factor more,
+ *                    line-granular ones (128) variants whose byte and block terms cost a fitted factor less.
  *   tuna_select      evaluates the model for the radices 2, 4, 8, ..., ceil(sqrt(size)), size of each
  *                    dimension, both modes and both T layouts and returns the minimiser.  Every term
  *                    falls as r grows and one-kernel hops move a third of the bytes, so the answer on
@@ -408,8 +412,9 @@ int tuna_calibrate(void* stream);
 /* Host only: the model's constants for `mode` (TUNA_MODE_STAGED or TUNA_MODE_FUSED) as they stand -- built in,
  * or fitted by tuna_calibrate: c[0..6] = c0 .. c6 above, c[7] = the factor on the byte term's share that
  * passes through T in slots, per unit of emptiness, c[8] = the factor on the byte term of byte-granular
- * problems.  capacity >= TUNA_MODEL_CONSTANTS. */
-#define TUNA_MODEL_CONSTANTS 9
+ * problems, c[9] = the factor on the byte and block terms of line-granular problems.
+ * capacity >= TUNA_MODEL_CONSTANTS. */
+#define TUNA_MODEL_CONSTANTS 10
 int tuna_model_constants(int mode, double* c, int capacity);
 int tuna_predict_ms(int P, int ranks_per_node, int local_radix, int global_radix, int mode, int t_layout,
                     int64_t payload_bytes, int64_t max_block_bytes, int granularity, double* ms);

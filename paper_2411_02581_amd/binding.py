@@ -369,11 +369,12 @@ def tuna_calibrate(stream=None) -> int:
     return load().tuna_calibrate(_stream(stream))
 
 
-TUNA_MODEL_CONSTANTS = 9
+TUNA_MODEL_CONSTANTS = 10
 
 
 def tuna_model_constants(mode: int):
-    """Returns (code, [c0 .. c6, slot factor, byte-granular factor]) of the cost model for `mode`.  Host only."""
+    """Returns (code, [c0 .. c6, slot factor, byte-granular factor, line-granular factor]) of the cost model for `mode`.
+    Host only."""
     c = (ctypes.c_double * TUNA_MODEL_CONSTANTS)()
     rc = load().tuna_model_constants(mode, c, TUNA_MODEL_CONSTANTS)
     return rc, list(c)

@@ -1647,19 +1647,23 @@ int run_static(const void* sendbuf, const int32_t* sendcounts, const int64_t* sd
 // immediate calls on MI355X by tuna_calibrate; calling it replaces them by a fit to calls timed on the
 // device at hand.
 constexpr int kModelTerms = 7;
-static_assert(kModelTerms + 2 == TUNA_MODEL_CONSTANTS, "tuna_model_constants reports the terms and the two factors");
+static_assert(kModelTerms + 3 == TUNA_MODEL_CONSTANTS, "tuna_model_constants reports the terms and the three factors");
 struct Model {
     double c[kModelTerms];
 };
 struct ModelSet {
-    Model m[2] = {{{0.0510, 0.0352, 0.0084, 1.0182, 0.0414, 0.0, 0.0}},            // [0] three stages
-                  {{0.0487, 0.0311, 0.0096, 0.3673, 0.0346, 0.0086, 1.5334}}};    // [1] one-kernel hops
+    Model m[2] = {{{0.0438, 0.0377, 0.0080, 1.0154, 0.0387, 0.0, 0.0}},            // [0] three stages
+                  {{0.0422, 0.0324, 0.0043, 0.3627, 0.0426, 0.0191, 1.3839}}};    // [1] one-kernel hops
     // T in the paper's slots of M bytes: the bytes that pass through T cost more the emptier the slots are
     // (sparse writes and reads): their share of the byte term is scaled by 1 + k * (1 - mean / M)
     double slot_penalty[2] = {0.25, 0.45};
     // byte-granular problems (some count, displacement or buffer address is not a multiple of 4) run the
     // kernel variants that load and store single bytes at block edges: their byte term is scaled by this
-    double byte_granular[2] = {1.14, 1.44};
+    double byte_granular[2] = {1.14, 1.45};
+    // line-granular problems (every count, displacement and buffer address is a multiple of 128) run the kernel
+    // variants that read their sources with streaming loads, and no block shares a line with its neighbour:
+    // their byte and block terms are scaled by this
+    double line_granular[2] = {0.94, 0.88};
     bool calibrated = false;
 };
 ModelSet g_model;
@@ -1695,6 +1699,9 @@ double model_ms(const Model& m, const Features& f) {
 // the model's byte term
 double bytes_ms(const Model& m, const Features& f) { return m.c[3] * f.hop_gb + m.c[6] * f.small_gb; }
 
+// the model's byte and block terms: what depends on the payload
+double data_ms(const Model& m, const Features& f) { return bytes_ms(m, f) + m.c[4] * f.mblocks + m.c[5] * f.msmall; }
+
 bool small_block_path(bool fused, int64_t max_block) { return fused && max_block > 0 && max_block <= kSmallBlockBytes; }
 
 double predict_ms(int P, int Q, int rl, int rg, bool fused, int t_layout, int64_t payload_bytes, int64_t max_block,
@@ -1704,6 +1711,7 @@ double predict_ms(int P, int Q, int rl, int rg, bool fused, int t_layout, int64_
     const Model& m = g_model.m[fused ? 1 : 0];
     double ms = model_ms(m, f);
     if (granularity > 0 && granularity < 4) ms += bytes_ms(m, f) * (g_model.byte_granular[fused ? 1 : 0] - 1.0);
+    if (granularity >= 128) ms += data_ms(m, f) * (g_model.line_granular[fused ? 1 : 0] - 1.0);
     if (t_layout == TUNA_T_SLOTS && max_block > 0 && pl.slots > 0) {
         const double mean = (double)payload_bytes / ((double)P * (double)P);
         const double m128 = (double)((max_block + 127) / 128 * 128);
@@ -1786,6 +1794,8 @@ int calibrate(hipStream_t s) {
     // byte-granular: fitted after the others, as a factor on the byte term; large enough for that term to be
     // most of the call's time
     const Problem odd = {1024, 515, {2, 32, 1024}};
+    // line-granular: fitted after the others too, as a factor on the byte and block terms
+    const Problem lines = {1024, 256, {2, 32, 1024}};
     // tiny (fixed costs), many tiny blocks (per-block and per-entry costs), large blocks beyond the caches
     // (bytes), and a mix; S is 4 bytes off a multiple of 16, the usual alignment of float payloads
     const Problem problems[] = {{32, 68, {2, 6, 32}}, {256, 516, {2, 16, 256}}, {1024, 20, {2, 32, 1024}}, {2048, 36, {8, 2048, 0}},
@@ -1819,12 +1829,13 @@ int calibrate(hipStream_t s) {
         return TUNA_ERR_NOMEM;
     }
     if (hipMemsetAsync(send, 0x5a, max_bytes + 256, s) != hipSuccess) { (void)hipGetLastError(); cleanup(); return TUNA_ERR_HIP; }
-    std::vector<Features> X[2], Xo[2];
-    std::vector<double> y[2], yo[2];
+    std::vector<Features> X[2], Xo[2], Xl[2];
+    std::vector<double> y[2], yo[2], yl[2];
     std::vector<Problem> all(std::begin(problems), std::end(problems));
     all.push_back(odd);
+    all.push_back(lines);
     for (const Problem& pb : all) {
-        const bool is_odd = (pb.S & 3) != 0;
+        const bool is_odd = (pb.S & 3) != 0, is_lines = (pb.S & 127) == 0;
         const size_t entries = (size_t)pb.P * pb.P;
         hipLaunchKernelGGL(k_fill_uniform, dim3((unsigned)((entries + 255) / 256)), dim3(256), 0, s, sc, sd, rc_, rd, pb.P, pb.S);
         if (hipGetLastError() != hipSuccess || hipStreamSynchronize(s) != hipSuccess) { cleanup(); return TUNA_ERR_HIP; }
@@ -1845,8 +1856,8 @@ int calibrate(hipStream_t s) {
                 }
                 std::sort(t + 1, t + kReps);
                 const PlanHost pl = make_plan(pb.P, pb.P, r, r, false, false);
-                (is_odd ? Xo : X)[fused].push_back(features_of(pl, (double)entries * pb.S, small_block_path(fused != 0, pb.S)));
-                (is_odd ? yo : y)[fused].push_back(t[1 + (kReps - 1) / 2]);      // median of the timed calls
+                (is_odd ? Xo : is_lines ? Xl : X)[fused].push_back(features_of(pl, (double)entries * pb.S, small_block_path(fused != 0, pb.S)));
+                (is_odd ? yo : is_lines ? yl : y)[fused].push_back(t[1 + (kReps - 1) / 2]);      // median of the timed calls
             }
         }
     }
@@ -1863,6 +1874,15 @@ int calibrate(hipStream_t s) {
             den += bms * bms;
         }
         if (den > 0) fitted.byte_granular[fused] = std::max(1.0, num / den);
+        // likewise the factor on the byte and block terms for the line-granular calls
+        num = den = 0.0;
+        for (size_t k = 0; k < Xl[fused].size(); ++k) {
+            const double dms = data_ms(fitted.m[fused], Xl[fused][k]);
+            const double rest = model_ms(fitted.m[fused], Xl[fused][k]) - dms;
+            num += (yl[fused][k] - rest) * dms;
+            den += dms * dms;
+        }
+        if (den > 0) fitted.line_granular[fused] = std::min(1.0, std::max(0.5, num / den));
     }
     fitted.calibrated = true;
     g_model = fitted;
@@ -2319,6 +2339,7 @@ int tuna_model_constants(int mode, double* c, int capacity) {
     for (int i = 0; i < kModelTerms; ++i) c[i] = g_model.m[k].c[i];
     c[kModelTerms] = g_model.slot_penalty[k];
     c[kModelTerms + 1] = g_model.byte_granular[k];
+    c[kModelTerms + 2] = g_model.line_granular[k];
     return TUNA_OK;
 }
 

@@ -267,11 +267,13 @@ def test_select_model():
     rc, odd = tuna.tuna_predict_ms(256, 0, 256, 256, tuna.TUNA_MODE_FUSED, tuna.TUNA_T_EXACT, 32 << 20, 1024, 1)
     rc, even = tuna.tuna_predict_ms(256, 0, 256, 256, tuna.TUNA_MODE_FUSED, tuna.TUNA_T_EXACT, 32 << 20, 1024, 4)
     assert odd > even                                          # byte-granular kernels cost more per byte
+    rc, lines = tuna.tuna_predict_ms(256, 0, 256, 256, tuna.TUNA_MODE_FUSED, tuna.TUNA_T_EXACT, 32 << 20, 1024, 128)
+    assert even > lines > 0.5 * even                           # whole-line blocks cost less per byte and per block
     assert tuna.tuna_predict_ms(12, 0, 2, 2, 5, 0, 100)[0] == tuna.TUNA_ERR_ARG
     # the constants are readable; blocks of at most 64 bytes are priced by their own constant in one-kernel mode
     rc, cf = tuna.tuna_model_constants(tuna.TUNA_MODE_FUSED)
     rc2, cs = tuna.tuna_model_constants(tuna.TUNA_MODE_STAGED)
-    assert rc == 0 and rc2 == 0 and len(cf) == 9 and all(v >= 0 for v in cf + cs)
+    assert rc == 0 and rc2 == 0 and len(cf) == 10 and all(v >= 0 for v in cf + cs) and 0.5 <= cf[9] <= 1 and 0.5 <= cs[9] <= 1
     assert cs[3] > 2 * cf[3] and cs[5] == 0 and cs[6] == 0 and 0 < cf[5] < cf[4] and cf[6] > cf[3]
     assert tuna.tuna_model_constants(tuna.TUNA_MODE_AUTO)[0] == tuna.TUNA_ERR_ARG
     P, payload = 2048, 32 << 20
