@@ -131,10 +131,14 @@ typedef struct tuna_plan_info {
  *                   with local radix min(radix, Q) and global radix min(radix, N), N = P / Q.
  * The call validates the counts on the device, reads a few integers back (one stream
  * synchronisation), sizes or grows the workspace, then enqueues all phases on `stream` and
- * returns without waiting for them.  Payloads of 64 MiB and more with at least two digit phases
- * are done in two passes -- the block-size exchange and the scans of every phase first, a second
- * read-back of the phases' exact work-list lengths, then the payload kernels -- which costs one
- * more synchronisation and saves launching every copy kernel for an upper bound of work.
+ * returns without waiting for them.  Payloads of 64 MiB and more with at least two digit phases:
+ * with one-kernel hops (the default) the block-size exchanges and scans of all phases run on a
+ * second stream owned by the context while `stream` moves the payload, each phase's payload kernel
+ * behind an event of its metadata; work enqueued on `stream` after the call is ordered behind all
+ * of it as usual.  With three-stage phases, or when the call is profiled, such a call is done in two
+ * passes instead -- the metadata of every phase first, a second read-back of the phases' exact
+ * work-list lengths, then the payload kernels -- which costs one more synchronisation and saves
+ * launching every copy kernel for an upper bound of work.
  * Problems of at most 64 ranks, 1 MiB of payload and 8 digit phases are done by one kernel launch
  * (validation, all phases and the own blocks in one workgroup; options at their defaults, no
  * profiling): there the launches, not the bytes, are what a call costs.  It returns after that

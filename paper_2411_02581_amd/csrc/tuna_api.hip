@@ -130,6 +130,11 @@ struct Ctx {
     unsigned char* tiny_t = nullptr;    // T of the one-kernel call for tiny problems (kTinyTBytes, allocated at its first use)
     const void* tiny_declined = nullptr; // sendcounts of the last problem that kernel declined: it is not asked again for it
     const void* stats_plan = nullptr;   // the statistics on file belong to this persistent plan (payload bytes known)
+    // pipelined calls (run_pipelined): the stream the metadata kernels run on, the event that lets it start, and one
+    // event per phase that lets the phase's payload kernel start; made at the first such call
+    hipStream_t meta_stream = nullptr;
+    hipEvent_t ev_fork = nullptr;
+    std::vector<hipEvent_t> ev_phase;
 };
 
 Ctx g;                                  // the default context
@@ -191,6 +196,9 @@ void free_ctx(Ctx& c) {
     if (c.tiny_t) (void)hipFree(c.tiny_t);
     if (c.ev_end) (void)hipEventDestroy(c.ev_end);
     for (hipEvent_t e : c.ev_pool) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c.ev_phase) (void)hipEventDestroy(e);
+    if (c.ev_fork) (void)hipEventDestroy(c.ev_fork);
+    if (c.meta_stream) (void)hipStreamDestroy(c.meta_stream);
     c = Ctx{};
 }
 
@@ -1080,6 +1088,7 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
 }
 
 int run_two_pass(Ctx& c, const Prepared& prepared, hipStream_t s);
+int run_pipelined(Ctx& c, const Prepared& prepared, hipStream_t s);
 size_t plan_meta_bytes(const Prepared& pr);
 
 // Immediate calls take the two-pass form (see run_two_pass) from this many staged chunks on (64 MiB),
@@ -1266,7 +1275,9 @@ int run_once(Ctx& c, const Options& opt, const void* sendbuf, const int32_t* sen
     fill_stats_header(pr, hs, st);
     if (empty) { c.have_stats = true; return TUNA_OK; }
     const PlanHost& pl = pr.dp->host;
-    if (use_two_pass(pl, hs)) {
+    if (use_two_pass(pl, hs) && pr.fused && !c.profile && !pr.debug_sizes) {
+        rc = run_pipelined(c, pr, s);
+    } else if (use_two_pass(pl, hs)) {
         rc = run_two_pass(c, pr, s);
     } else {
         // ---- workspace ---------------------------------------------------------------------------
@@ -1337,16 +1348,16 @@ size_t plan_meta_bytes(const Prepared& pr) {
 // Every phase's metadata in `meta` (plan_meta_bytes of it), then one read-back: exact unit counts,
 // per-phase bytes and chunks, and from them the payload memory the plan needs (*dbytes).
 // with_marks: record the profiling marks of an immediate call.
-int plan_build_metadata(Plan* plan, void* meta, size_t mbytes, hipStream_t s, bool with_marks, size_t* stage_bytes,
-                        size_t* dbytes) {
+// Carves a plan's metadata (plan_meta_bytes) out of `meta`: every phase gets layouts and hop arrays of its own.
+bool plan_carve_meta(Plan* plan, void* meta, size_t mbytes, int32_t** cur, int32_t** nxt) {
     Prepared& pr = plan->pr;
     const PlanHost& pl = pr.dp->host;
     const size_t nph = pl.phases.size();
     const int P = pr.P;
     const size_t P2 = (size_t)P * P;
     Carver cm(meta, mbytes);
-    int32_t* cur = cm.take<int32_t>(P2);
-    int32_t* nxt = cm.take<int32_t>(P2);
+    *cur = cm.take<int32_t>(P2);
+    *nxt = cm.take<int32_t>(P2);
     pr.rank_bytes = cm.take<unsigned long long>(P);
     plan->Ls.resize(nph); plan->Lr.resize(nph); plan->units.assign(nph, 0);
     for (size_t i = 0; i < nph; ++i) {
@@ -1358,7 +1369,18 @@ int plan_build_metadata(Plan* plan, void* meta, size_t mbytes, hipStream_t s, bo
     for (size_t i = 0; i < nph; ++i)
         if (phase_is_one_kernel(pr, pl.phases[i])) carve_hop(cm, P, hop_ld_for(pl.phases[i].nseg), plan->hop[i]);
     carve_self(cm, pr);
-    if (!cm.ok) return TUNA_ERR_WORKSPACE_TOO_SMALL;
+    return cm.ok;
+}
+
+int plan_build_metadata(Plan* plan, void* meta, size_t mbytes, hipStream_t s, bool with_marks, size_t* stage_bytes,
+                        size_t* dbytes) {
+    Prepared& pr = plan->pr;
+    const PlanHost& pl = pr.dp->host;
+    const size_t nph = pl.phases.size();
+    const int P = pr.P;
+    const size_t P2 = (size_t)P * P;
+    int32_t *cur = nullptr, *nxt = nullptr;
+    if (!plan_carve_meta(plan, meta, mbytes, &cur, &nxt)) return TUNA_ERR_WORKSPACE_TOO_SMALL;
     int rc = upload_cbase(pr, s);
     if (rc != TUNA_OK) return rc;
     const dim3 grot((unsigned)((P + 255) / 256), (unsigned)((P + kExchangeRanks - 1) / kExchangeRanks));
@@ -1515,6 +1537,85 @@ int run_two_pass(Ctx& c, const Prepared& prepared, hipStream_t s) {
     c.stats = plan.stats;
     mark(&c, s, kCatPrepare, -1);                 // the read-back between the passes counts as preparation
     return plan_launch_data(&plan, s);
+}
+
+// A large call whose phases are all one-kernel hops, pipelined: the metadata kernels of every phase run back to
+// back on a stream of the context's own (they depend on the block sizes only, never on the payload), the payload
+// kernel of phase i runs on the caller's stream as soon as the metadata of phase i is complete (an event), with
+// the grid of a one-pass call (an upper bound of units; the waves beyond the device's count leave at once).  The
+// metadata of phase i + 1 is then computed while the payload of phase i moves, and the host waits for nothing
+// after validation.  Every phase has metadata buffers of its own, as in a plan; T is sized from validation.
+// Nothing a metadata kernel reads is written by a payload kernel, and a payload kernel reads only its own phase's
+// buffers, S and T.  Not taken when the call is profiled (its per-kernel times are measured on one stream) or
+// its size matrices are captured for verification.
+int run_pipelined(Ctx& c, const Prepared& prepared, hipStream_t s) {
+    Plan plan;
+    plan.pr = prepared;
+    plan.ctx = &c;
+    Prepared& pr = plan.pr;
+    const PlanHost& pl = pr.dp->host;
+    const size_t nph = pl.phases.size();
+    if (!c.meta_stream) HIPCHK(hipStreamCreateWithFlags(&c.meta_stream, hipStreamNonBlocking));
+    if (!c.ev_fork) HIPCHK(hipEventCreateWithFlags(&c.ev_fork, hipEventDisableTiming));
+    while (c.ev_phase.size() < nph) {
+        hipEvent_t e;
+        HIPCHK(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        c.ev_phase.push_back(e);
+    }
+    const size_t mbytes = plan_meta_bytes(pr);
+    const size_t dbytes = pr.ds.t_bytes ? align_up(pr.ds.t_bytes + kTailSlack) : 0;
+    void *mbase = nullptr, *dbase = nullptr;
+    int rc;
+    if (c.user_ws) {
+        if (mbytes + dbytes > c.user_ws_bytes) return TUNA_ERR_WORKSPACE_TOO_SMALL;
+        mbase = c.user_ws;
+        dbase = (char*)c.user_ws + mbytes;
+    } else {
+        rc = grow(&c.meta, &c.meta_bytes, mbytes);
+        if (rc != TUNA_OK) return rc;
+        if (dbytes) {
+            rc = grow(&c.data, &c.data_bytes, dbytes);
+            if (rc != TUNA_OK) return rc;
+        }
+        mbase = c.meta;
+        dbase = c.data;
+    }
+    int32_t *cur = nullptr, *nxt = nullptr;
+    if (!plan_carve_meta(&plan, mbase, mbytes, &cur, &nxt)) return TUNA_ERR_WORKSPACE_TOO_SMALL;
+    if (dbytes) plan_carve_data(&plan, dbase, 0, dbytes);
+    c.stats.temp_bytes = (int64_t)pr.ds.t_bytes;
+    c.stats.staging_bytes = 0;
+    c.stats.workspace_bytes = (int64_t)(mbytes + dbytes);
+    hipStream_t m = c.meta_stream;
+    // the metadata stream starts behind everything the caller's stream holds so far
+    HIPCHK(hipEventRecord(c.ev_fork, s));
+    HIPCHK(hipStreamWaitEvent(m, c.ev_fork, 0));
+    rc = upload_cbase(pr, m);
+    if (rc != TUNA_OK) return rc;
+    const int P = pr.P;
+    const dim3 grot((unsigned)((P + 255) / 256), (unsigned)((P + kExchangeRanks - 1) / kExchangeRanks));
+    hipLaunchKernelGGL(k_rotate_init, grot, dim3(256), 0, m, pr.sendcounts, cur, P, pr.Q, pr.N);
+    HIPCHK(hipGetLastError());
+    // the own blocks on the caller's stream, while the first phase's metadata is computed
+    rc = launch_self_metadata(pr, s);
+    if (rc != TUNA_OK) return rc;
+    rc = launch_self_copy(pr, s);
+    if (rc != TUNA_OK) return rc;
+    for (size_t i = 0; i < nph; ++i) {
+        rc = launch_phase_metadata(pr, i, cur, nxt, plan.Ls[i], plan.Lr[i], plan.hop[i], m);
+        if (rc != TUNA_OK) break;
+        HIPCHK(hipEventRecord(c.ev_phase[i], m));
+        HIPCHK(hipStreamWaitEvent(s, c.ev_phase[i], 0));
+        rc = launch_phase_data(pr, i, plan.Ls[i], plan.Lr[i], plan.hop[i], pr.ds.unit_cap, s);
+        if (rc != TUNA_OK) break;
+        std::swap(cur, nxt);
+    }
+    if (rc != TUNA_OK) {
+        // whatever was launched on the metadata stream ends before the caller's stream goes on
+        (void)hipEventRecord(c.ev_fork, m);
+        (void)hipStreamWaitEvent(s, c.ev_fork, 0);
+    }
+    return rc;
 }
 
 }  // namespace

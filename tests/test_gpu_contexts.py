@@ -126,6 +126,62 @@ def test_one_context_two_streams_are_ordered(tuna):
         assert a.ok() and b.ok(), it
 
 
+def test_large_calls_with_metadata_on_a_second_stream(tuna):
+    """Calls of 64 MiB and more with several one-kernel phases compute every phase's metadata on a stream of
+    the context's own while the caller's stream moves the payload.  Two such problems back to back on two
+    streams of one context, with a small call between them, with no host synchronisation in between; then the
+    same call profiled (which keeps to one stream), on a context of its own, and on a caller-owned workspace
+    of the size the sizing query names."""
+    big = Prob(wl.counts_normal(320, 21, 1024.0, 256.0, 4), 8, gap=0)          # 100 MiB, the tiled hop
+    zipf = Prob(wl.counts_zipf(384, 22, 1.2, 16384, 4), 9)                    # 120 MiB, gaps: the copy engine's hop
+    small = Prob(wl.counts_uniform_bytes(50, 10, 900), 6)
+    assert big.lay.payload_bytes > (64 << 20) and zipf.lay.payload_bytes > (64 << 20)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for it, (r1, r2) in enumerate([(2, 4), (8, 20), (18, 2)]):
+        for p in (big, zipf, small):
+            p.recv.fill_(CANARY)
+        torch.cuda.synchronize()
+        print("pipelined calls, iteration", it, flush=True)
+        assert big.call(tuna, None, 0, r1, r1, None, s1) == 0
+        assert zipf.call(tuna, None, 16, 4, r2, None, s2) == 0
+        assert small.call(tuna, None, 0, 5, 5, None, s1) == 0
+        assert big.call(tuna, None, 0, r2, r2, None, s2) == 0
+        torch.cuda.synchronize()
+        assert big.ok() and zipf.ok() and small.ok(), it
+        st = tuna.tuna_get_stats()
+        assert st.n_phases >= 2 and sum(st.phase[x].payload_bytes for x in range(st.n_phases)) >= big.lay.payload_bytes
+    o = tuna.tuna_opts_init()
+    o.profile = 1
+    big.recv.fill_(CANARY)
+    assert big.call(tuna, None, 0, 4, 4, o) == 0
+    torch.cuda.synchronize()
+    st = tuna.tuna_get_stats()
+    assert big.ok() and all(st.phase[x].ms_metadata > 0 and st.phase[x].ms_unpack > 0 for x in range(st.n_phases))
+    rc, ctx = tuna.tuna_ctx_create()
+    assert rc == 0
+    try:
+        for r in (3, 7):
+            zipf.recv.fill_(CANARY)
+            assert zipf.call(tuna, ctx, 16, r, r, None, s1) == 0
+            torch.cuda.synchronize()
+            assert zipf.ok(), r
+    finally:
+        assert tuna.tuna_ctx_destroy(ctx) == 0
+    rc, need = tuna.tuna_workspace_bytes(big.meta[0], big.lay.P, 0, 4, 4)
+    assert rc == 0 and need > 0
+    ws = torch.empty(need + 256, dtype=torch.uint8, device="cuda:0")
+    base = (ws.data_ptr() + 255) // 256 * 256
+    assert tuna.tuna_set_workspace(base, need) == 0
+    try:
+        big.recv.fill_(CANARY)
+        assert big.call(tuna, None, 0, 4, 4) == 0
+        torch.cuda.synchronize()
+        assert big.ok() and tuna.tuna_get_stats().workspace_bytes <= need
+    finally:
+        assert tuna.tuna_set_workspace(None, 0) == 0
+
+
 def test_plan_with_options_and_context(tuna):
     prob = Prob(wl.counts_uniform_bytes(48, 11, 2000), 7)
     rc, ctx = tuna.tuna_ctx_create()
