@@ -1753,18 +1753,18 @@ struct Model {
     double c[kModelTerms];
 };
 struct ModelSet {
-    Model m[2] = {{{0.0438, 0.0377, 0.0080, 1.0154, 0.0387, 0.0, 0.0}},            // [0] three stages
-                  {{0.0422, 0.0324, 0.0043, 0.3627, 0.0426, 0.0191, 1.3839}}};    // [1] one-kernel hops
+    Model m[2] = {{{0.0393, 0.0360, 0.0071, 1.0192, 0.0412, 0.0, 0.0}},            // [0] three stages
+                  {{0.0368, 0.0312, 0.0061, 0.3481, 0.0398, 0.0150, 1.4108}}};    // [1] one-kernel hops
     // T in the paper's slots of M bytes: the bytes that pass through T cost more the emptier the slots are
     // (sparse writes and reads): their share of the byte term is scaled by 1 + k * (1 - mean / M)
     double slot_penalty[2] = {0.25, 0.45};
     // byte-granular problems (some count, displacement or buffer address is not a multiple of 4) run the
     // kernel variants that load and store single bytes at block edges: their byte term is scaled by this
-    double byte_granular[2] = {1.14, 1.45};
+    double byte_granular[2] = {1.15, 1.38};
     // line-granular problems (every count, displacement and buffer address is a multiple of 128) run the kernel
     // variants that read their sources with streaming loads, and no block shares a line with its neighbour:
     // their byte and block terms are scaled by this
-    double line_granular[2] = {0.94, 0.88};
+    double line_granular[2] = {0.90, 0.79};
     bool calibrated = false;
 };
 ModelSet g_model;
@@ -1896,7 +1896,7 @@ int calibrate(hipStream_t s) {
     // most of the call's time
     const Problem odd = {1024, 515, {2, 32, 1024}};
     // line-granular: fitted after the others too, as a factor on the byte and block terms
-    const Problem lines = {1024, 256, {2, 32, 1024}};
+    const Problem lines = {2048, 256, {8, 2048, 0}};
     // tiny (fixed costs), many tiny blocks (per-block and per-entry costs), large blocks beyond the caches
     // (bytes), and a mix; S is 4 bytes off a multiple of 16, the usual alignment of float payloads
     const Problem problems[] = {{32, 68, {2, 6, 32}}, {256, 516, {2, 16, 256}}, {1024, 20, {2, 32, 1024}}, {2048, 36, {8, 2048, 0}},
