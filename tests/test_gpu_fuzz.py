@@ -160,3 +160,60 @@ def test_random_problems_through_every_entry_point(tuna, seed):
         assert tuna.tuna_ctx_destroy(own_ctx) == 0
     print(seen, flush=True)
     assert all(seen[k] >= 5 for k in ("ex", "ctx", "plan", "noalloc", "flat_api")), seen
+
+
+def test_random_large_problems_back_to_back(tuna):
+    """Problems of 70 to 260 MiB -- where calls with one-kernel phases compute their metadata on a second stream
+    while the payload moves -- over random rank counts, hierarchies, radices, size distributions, alignments,
+    modes and T layouts; every problem is run twice in a row on two streams of the default context with
+    different radices and no host synchronisation between the calls."""
+    rng = np.random.default_rng(0x1124_0258)
+    dev = "cuda:0"
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for case in range(30):
+        P = int(rng.choice([64, 96, 128, 200, 256, 384, 512]))
+        mean = (int(rng.integers(70, 260)) << 20) // (P * P)
+        kind = int(rng.integers(0, 5))
+        if kind == 0:                                               # normal, word-granular
+            c = rng.normal(mean, mean / 4, size=(P, P)).clip(0) // 4 * 4
+        elif kind == 1:                                             # uniform, word-granular
+            c = rng.integers(0, 2 * mean, size=(P, P)) // 4 * 4
+        elif kind == 2:                                             # heavy tail
+            c = (rng.pareto(1.2, size=(P, P)) * mean / 5).clip(0, 40 * mean) // 4 * 4
+        elif kind == 3:                                             # one block in five empty, chunk-granular
+            c = rng.integers(0, 2 * mean, size=(P, P)) * (rng.random((P, P)) < 0.8) // 16 * 16
+        else:                                                       # byte-granular
+            c = rng.integers(0, 2 * mean, size=(P, P))
+        c = c.astype(np.int64)
+        if rng.random() < 0.3:
+            c[int(rng.integers(0, P))] = 0
+        divs = _divisors(P)
+        Q = int(rng.choice(divs)) if rng.random() < 0.5 else 0
+        size_l, size_g = (Q if Q else P), (P // Q if Q else 1)
+        rl = int(rng.choice([2, 3, 4, max(2, int(size_l ** 0.5)), max(2, size_l)]))
+        rg = int(rng.choice([2, 3, max(2, int(size_g ** 0.5)), max(2, size_g)]))
+        lay = wl.make_layout(c.astype(np.int32), gap=int(rng.choice([0, 0, 8])), align=int(rng.choice([1, 4, 16])))
+        host = wl.payload_position_hash(100 + case, lay.send_bytes)
+        want = np.full(lay.recv_bytes, CANARY, dtype=np.uint8)
+        assert oracle.alltoallv(host, lay.sendcounts, lay.sdispls, want, lay.recvcounts, lay.rdispls) == 0
+        send = torch.from_numpy(host).to(dev)
+        recv = torch.full((lay.recv_bytes,), CANARY, dtype=torch.uint8, device=dev)
+        sc, sd, rcn, rd = [torch.from_numpy(a).to(dev) for a in (lay.sendcounts, lay.sdispls, lay.recvcounts, lay.rdispls)]
+        o = tuna.tuna_opts_init()
+        o.mode = int(rng.choice([tuna.TUNA_MODE_AUTO, tuna.TUNA_MODE_FUSED, tuna.TUNA_MODE_STAGED], p=[0.5, 0.4, 0.1]))
+        o.t_layout = int(rng.choice([tuna.TUNA_T_AUTO, tuna.TUNA_T_EXACT]))
+        o.staggered = int(Q > 1 and P // Q > 1 and rng.random() < 0.2)
+        what = "large case %d: P=%d Q=%d r_l=%d r_g=%d mode=%d t=%d staggered=%d kind=%d, %d MiB" % (
+            case, P, Q, rl, rg, o.mode, o.t_layout, o.staggered, kind, lay.payload_bytes >> 20)
+        print(what, flush=True)
+        torch.cuda.synchronize()
+        for k, (a, b) in enumerate([(rl, rg), (max(2, rl // 2), rg)]):
+            code = tuna.tuna_alltoallv_ex(None, send, sc, sd, recv, rcn, rd, P, Q, a, b, o, streams[(case + k) % 2])
+            assert code == 0, what + ": " + tuna.tuna_strerror(code)
+        torch.cuda.synchronize()
+        got = recv.cpu().numpy()
+        if not np.array_equal(got, want):
+            bad = np.flatnonzero(got != want)
+            raise AssertionError("%s: %d bytes differ, first at offset %d" % (what, bad.size, bad[0]))
+        assert np.array_equal(send.cpu().numpy(), host), what + ": send buffer modified"
+        del send, recv, sc, sd, rcn, rd
