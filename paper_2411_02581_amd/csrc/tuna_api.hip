@@ -1091,8 +1091,8 @@ int run_two_pass(Ctx& c, const Prepared& prepared, hipStream_t s);
 int run_pipelined(Ctx& c, const Prepared& prepared, hipStream_t s);
 size_t plan_meta_bytes(const Prepared& pr);
 
-// Immediate calls take the two-pass form (see run_two_pass) from this many staged chunks on (64 MiB),
-// when the schedule has at least two phases.
+// Immediate calls take the pipelined form (run_pipelined: one-kernel phases, not profiled) or the two-pass
+// form (run_two_pass) from this many staged chunks on (64 MiB), when the schedule has at least two phases.
 constexpr unsigned long long kTwoPassMinChunks = 1ull << 22;
 bool use_two_pass(const PlanHost& pl, const Status& hs) {
     return pl.phases.size() >= 2 && hs.total_chunks >= kTwoPassMinChunks;

@@ -1494,7 +1494,8 @@ __global__ void __launch_bounds__(kScanThreads) k_tiled_layout(const TiledLayout
 // branch-free search as the copy engine.  A piece that lies inside its block is one 16-byte load at
 // the source's own alignment and one aligned streaming store.  A piece at a block's edge is put together
 // word by word (GRAN = 4: every size and address is a multiple of 4) from its block and the one behind it
-// in the run (a walk over the hop arrays when more blocks than that meet in one piece) and stored whole
+// in the run (a walk over the window's entries, and over the hop arrays behind the window, when more blocks
+// than that meet in one piece) and stored whole
 // when all four words belong to blocks, else word by word (the ends of a run: bytes outside every block
 // are never written).  With GRAN = 16 every piece is inside a block or outside all of them.  Blocks bound
 // for T take whole chunks; a load never leaves the part of S that holds blocks.

@@ -85,7 +85,7 @@ def test_config3_full_hierarchical(tuna):
 
 
 def test_config3_caller_workspace_and_phase_times(tuna):
-    """A call of this size is made in two passes (all metadata, a second read-back, then the payload
+    """A profiled call of this size is made in two passes (all metadata, a second read-back, then the payload
     kernels with exact grids).  Here it runs in a caller-owned workspace of tuna_workspace_bytes bytes,
     with per-kernel timing on: same bytes as the oracle, every stage of every phase timed, and the
     workspace it reports fits the one that was asked for."""
@@ -293,8 +293,9 @@ def test_own_blocks_of_64_mebibytes(tuna):
 
 def test_byte_granular_two_pass_all_modes(tuna):
     """P = 512, byte-granular sizes 0..2047 (any alignment), 256 MiB of payload, radix 8 (three digit phases):
-    large enough for the two-pass form of an immediate call, in all four modes (three stages / one-kernel
-    phases x T in slots / in exact size); whole receive buffer against the oracle."""
+    large enough for the two-pass form of an immediate call (three stages) and for its pipelined form
+    (one-kernel phases), in all four modes (three stages / one-kernel phases x T in slots / in exact size);
+    whole receive buffer against the oracle."""
     P = 512
     counts = wl.counts_uniform_bytes(P, 512, 2047)
     lay = wl.make_layout(counts, gap=3)
