@@ -167,11 +167,13 @@ int tuna_alltoallv_hier(const void* sendbuf, const int32_t* sendcounts, const in
  *                with all ranks in one memory a hop needs no message, and moving a block straight from
  *                where its sender holds it to where its receiver keeps it reads and writes it once
  *                instead of three times.  When the receive regions are dense (every rank's blocks back to
- *                back in source order), sizes, displacements and buffer addresses are multiples of 4, the
- *                blocks are mostly longer than a few lines (mean of 700 bytes or more, at most a quarter
- *                of them under 256 bytes) and T is kept in exact size, a phase is tiled over its
- *                destinations in 128-byte lines; otherwise (and always for T in slots, batches of rounds
- *                and the staggered schedule) over the blocks.  Which of the two ran changes no byte.
+ *                back in source order) and sizes, displacements and buffer addresses are multiples of 4,
+ *                a phase is tiled over its destinations in 128-byte lines: the last phase of a schedule
+ *                (all its blocks go into the receive buffer) when the blocks are mostly longer than a few
+ *                lines (mean of 700 bytes or more, at most a quarter of them under 256 bytes), the phases
+ *                before it (which store whole 16-byte chunks into T) when T is kept in exact size and
+ *                the mean block is 512 bytes or more; otherwise (and always for T in slots, batches of
+ *                rounds and the staggered schedule) over the blocks.  Which of the two ran changes no byte.
  *                TUNA_MODE_STAGED: pack -> exchange -> unpack, the paper's three steps as three kernels.
  *                TUNA_MODE_FUSED: the one-kernel hops.
  *   staggered, t_layout, block_count, profile: as TUNA_OPT_STAGGERED, TUNA_OPT_DENSE_T,

@@ -546,7 +546,8 @@ struct Prepared {
     // ranks' places inside a class are assigned on the device, phase by phase
     bool exact_t = false;               // T in exact size, and the schedule has T at all
     bool exact_kernels = false;         // T in exact size was asked for
-    bool tiled = false;                 // one-kernel phases run as the destination-tiled hop (k_copy_tiled) where they can
+    bool tiled = false;                 // one-kernel phases before the last run as the destination-tiled hop (k_copy_tiled) where they can
+    bool tiled_final = false;           // and so does the last phase
     std::vector<int*> tpre;             // per phase: the blocks' offsets in message order (one array shared, or one each)
     ExactT x{};
     long long* d_cbase = nullptr;       // [classes]: where the host placed every class in T
@@ -714,6 +715,7 @@ bool too_large(int P, const Status& hs) {
 }
 
 constexpr int kTiledMinMeanBytes = 700;    // see prepare_sizes
+constexpr int kTiledMinMeanBytesIntoT = 512;
 
 // Validation + sizing pass of a call whose arguments, schedule and status buffers are in `pr` (one
 // read-back).  On TUNA_OK with *empty == true there is nothing to move.
@@ -746,13 +748,17 @@ int prepare_sizes(Prepared& pr, int dense_option, hipStream_t s, Status& hs, boo
     // flag), word- or chunk-granular data (whole-line data is as fast in the copy engine, byte-granular data
     // would need the pieces at block edges put together byte by byte), blocks that are not all tiny (those
     // have k_hop_small).
-    // It pays when the blocks are mostly pieces inside blocks, not edges: measured, 1 KiB blocks gain 8 % per call
-    // at r = P and 512-byte blocks lose 2 %; Zipf sizes with four blocks in five under 256 bytes lose 8 %.  Hence
-    // a mean block of at least kTiledMinMeanBytes and at most a quarter of the blocks short.
+    // Into R it pays when the blocks are mostly pieces inside blocks, not edges: measured, 1 KiB blocks gain 8 %
+    // per call at r = P and 512-byte blocks lose 2 %; Zipf sizes with four blocks in five under 256 bytes lose 11 %
+    // in their last phase.  Hence, for a schedule's last phase (all its blocks are final), a mean block of at least
+    // kTiledMinMeanBytes and at most a quarter of the blocks short.  Into T every block is whole chunks and
+    // there are no edges: the phases before the last gain 6 to 10 % with those Zipf sizes and 2 to 4 % with a
+    // mean block of 256 bytes, and lose 2 to 8 % below that: a mean block of kTiledMinMeanBytesIntoT.
     const unsigned long long P2 = (unsigned long long)P * (unsigned long long)P;
     pr.tiled = pr.fused && !pr.staggered && pr.block_count == 0 && !(hs.flags & 8u) && (pr.gran == 4 || pr.gran == 16) &&
                hs.max_count > kSmallBlockBytes && !pr.dp->host.phases.empty() &&
-               hs.total_bytes >= (unsigned long long)kTiledMinMeanBytes * P2 && hs.short_blocks * 4 <= P2;
+               hs.total_bytes >= (unsigned long long)kTiledMinMeanBytesIntoT * P2;
+    pr.tiled_final = pr.tiled && hs.total_bytes >= (unsigned long long)kTiledMinMeanBytes * P2 && hs.short_blocks * 4 <= P2;
     pr.ds = data_sizes_for(pr.dp->host, hs.max_count, hs.total_chunks, pr.fused, pr.staggered, pr.exact_t, pr.t_chunks,
                            pr.tiled);
     return TUNA_OK;
@@ -796,12 +802,12 @@ int prepare_call(Ctx& c, const Options& opt, const void* sendbuf, const int32_t*
 // instead of the byte-balanced engine.
 bool small_blocks(const Prepared& pr) { return pr.max_count > 0 && pr.max_count <= kSmallBlockBytes; }
 
-// Phases that run as the destination-tiled hop: the last one (all its blocks are final), and with T in exact
-// size every other one too -- the blocks a rank stores into T lie back to back inside their class, so their
-// destinations form runs just like those in R.  (T in slots keeps the copy engine: its slot tails are filled
-// up to the line by a path of their own.)
+// Phases that run as the destination-tiled hop: the last one (all its blocks are final) when the blocks are
+// mostly interior, and with T in exact size the ones before it -- the blocks a rank stores into T lie back to
+// back inside their class, so their destinations form runs just like those in R, and they are whole chunks.
+// (T in slots keeps the copy engine: its slot tails are filled up to the line by a path of their own.)
 bool phase_is_tiled(const Prepared& pr, size_t i) {
-    return pr.tiled && (i + 1 == pr.dp->host.phases.size() || pr.exact_t);
+    return i + 1 == pr.dp->host.phases.size() ? pr.tiled_final : (pr.tiled && pr.exact_t);
 }
 
 int launch_resolve(const Prepared& pr, size_t i, const int32_t* nxt, const HopDev& hop, hipStream_t s);
