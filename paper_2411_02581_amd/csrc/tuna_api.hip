@@ -462,8 +462,8 @@ int launch_copy(int gran, size_t unit_cap, const CopyArgs& a, hipStream_t s, boo
 }
 
 // Metadata of one digit phase: sizes exchanged, both staging layouts scanned, wave units cut.
-int phase_metadata(const PhaseLayoutArgs& a, hipStream_t s, const ExactT& x) {
-    if (!a.inline_exchange) {
+int phase_metadata(const PhaseLayoutArgs& a, hipStream_t s, const ExactT& x, bool sizes_ready = false) {
+    if (!a.inline_exchange && !sizes_ready) {
         hipLaunchKernelGGL(k_size_exchange, dim3((unsigned)((a.P + 255) / 256), (unsigned)((a.P + kExchangeRanks - 1) / kExchangeRanks)),
                            dim3(256), 0, s, a.cur, a.nxt, a.zt, a.P, a.Q, a.N, a.dim, a.rx);
         HIPCHK(hipGetLastError());
@@ -548,6 +548,7 @@ struct Prepared {
     bool exact_kernels = false;         // T in exact size was asked for
     bool tiled = false;                 // one-kernel phases before the last run as the destination-tiled hop (k_copy_tiled) where they can
     bool tiled_final = false;           // and so does the last phase
+    bool sizes_direct = false;          // one phase: the receivers' sizes were taken from recvcounts (run_one_pass), no size exchange
     std::vector<int*> tpre;             // per phase: the blocks' offsets in message order (one array shared, or one each)
     ExactT x{};
     long long* d_cbase = nullptr;       // [classes]: where the host placed every class in T
@@ -820,9 +821,11 @@ int launch_tiled_metadata(const Prepared& pr, size_t i, const int32_t* cur, int3
     const PhaseHost& ph = pr.dp->host.phases[i];
     const int P = pr.P;
     const bool last = i + 1 == pr.dp->host.phases.size();
-    hipLaunchKernelGGL(k_size_exchange, dim3((unsigned)((P + 255) / 256), (unsigned)((P + kExchangeRanks - 1) / kExchangeRanks)),
-                       dim3(256), 0, s, cur, nxt, pr.dp->d_zt[i], P, pr.Q, pr.N, ph.dim, (int)ph.rx);
-    HIPCHK(hipGetLastError());
+    if (!pr.sizes_direct) {
+        hipLaunchKernelGGL(k_size_exchange, dim3((unsigned)((P + 255) / 256), (unsigned)((P + kExchangeRanks - 1) / kExchangeRanks)),
+                           dim3(256), 0, s, cur, nxt, pr.dp->d_zt[i], P, pr.Q, pr.N, ph.dim, (int)ph.rx);
+        HIPCHK(hipGetLastError());
+    }
     if (!last) {
         // the blocks this phase stores into T: their places inside the classes (k_phase_layout's class scans,
         // which also count the phase's payload bytes) and the ranks' parts of the classes (k_layout_base)
@@ -874,8 +877,8 @@ int launch_phase_metadata(const Prepared& pr, size_t i, const int32_t* cur, int3
     // with few ranks a launch costs more than the kernel (measured: 19 us per call at P = 16, nothing at
     // P = 256, while at P = 4096 the separate kernel saves 44 us per phase): the scan kernel then
     // exchanges the sizes itself
-    m.inline_exchange = pr.P <= 128 ? 1 : 0;
-    int rc = phase_metadata(m, s, exact_t_of(pr, i));
+    m.inline_exchange = (pr.P <= 128 && !pr.sizes_direct) ? 1 : 0;
+    int rc = phase_metadata(m, s, exact_t_of(pr, i), pr.sizes_direct);
     if (rc != TUNA_OK || !one_kernel) return rc;
     return launch_resolve(pr, i, nxt, hop, s);
 }
@@ -1140,7 +1143,12 @@ int run_one_pass(Prepared& pr, void* mbase, size_t mbytes, void* dbase, hipStrea
 
     // ---- initial rotation (index only) and the own block ----------------------------------------
     const dim3 grot((unsigned)((P + 255) / 256), (unsigned)((P + kExchangeRanks - 1) / kExchangeRanks));
-    hipLaunchKernelGGL(k_rotate_init, grot, dim3(256), 0, s, pr.sendcounts, mb.cur, P, pr.Q, pr.N);
+    // A schedule of one phase whose block sizes nobody asked to see: every block arrives in its only hop, so what
+    // the phase's metadata exchange would leave in the receivers' size arrays is recvcounts, rotated (validation
+    // has checked that it is the transpose of sendcounts): one kernel instead of the rotation and the exchange.
+    pr.sizes_direct = pl.phases.size() == 1 && pr.fused && !pr.debug_sizes;
+    if (pr.sizes_direct) hipLaunchKernelGGL(k_rotate_init, grot, dim3(256), 0, s, pr.recvcounts, mb.nxt, P, pr.Q, pr.N, 1);
+    else hipLaunchKernelGGL(k_rotate_init, grot, dim3(256), 0, s, pr.sendcounts, mb.cur, P, pr.Q, pr.N, 0);
     HIPCHK(hipGetLastError());
     mark(pr.ctx, s, kCatPrepare, -1);
     rc = launch_self_metadata(pr, s);
@@ -1390,7 +1398,7 @@ int plan_build_metadata(Plan* plan, void* meta, size_t mbytes, hipStream_t s, bo
     int rc = upload_cbase(pr, s);
     if (rc != TUNA_OK) return rc;
     const dim3 grot((unsigned)((P + 255) / 256), (unsigned)((P + kExchangeRanks - 1) / kExchangeRanks));
-    hipLaunchKernelGGL(k_rotate_init, grot, dim3(256), 0, s, pr.sendcounts, cur, P, pr.Q, pr.N);
+    hipLaunchKernelGGL(k_rotate_init, grot, dim3(256), 0, s, pr.sendcounts, cur, P, pr.Q, pr.N, 0);
     HIPCHK(hipGetLastError());
     rc = launch_self_metadata(pr, s);
     if (rc != TUNA_OK) return rc;
@@ -1600,7 +1608,7 @@ int run_pipelined(Ctx& c, const Prepared& prepared, hipStream_t s) {
     if (rc != TUNA_OK) return rc;
     const int P = pr.P;
     const dim3 grot((unsigned)((P + 255) / 256), (unsigned)((P + kExchangeRanks - 1) / kExchangeRanks));
-    hipLaunchKernelGGL(k_rotate_init, grot, dim3(256), 0, m, pr.sendcounts, cur, P, pr.Q, pr.N);
+    hipLaunchKernelGGL(k_rotate_init, grot, dim3(256), 0, m, pr.sendcounts, cur, P, pr.Q, pr.N, 0);
     HIPCHK(hipGetLastError());
     // the own blocks on the caller's stream, while the first phase's metadata is computed
     rc = launch_self_metadata(pr, s);

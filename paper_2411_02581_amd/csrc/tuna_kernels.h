@@ -429,9 +429,13 @@ __global__ void __launch_bounds__(256) k_validate_finish(const unsigned long lon
 // k_rotate_init: the index-only initial rotation (Algorithm "TuNA", lines 4-5; Algorithm
 // "Coalesced TuNA_l^g", line 5).  No payload moves: cur[p][j*Q + l] becomes the size of the
 // block rank p = (n, g) holds at distance (j, l), i.e. its block for rank ((n-j)%N, (g-l)%Q).
+// With `up` the row is rotated the other way, cur[p][j*Q + l] = counts[p][((n+j)%N, (g+l)%Q)]: applied to
+// recvcounts that is the size of the block rank p receives from the rank at distance (j, l) -- for a schedule
+// of one phase, where every block arrives in its first and only hop, exactly what the metadata exchange of
+// that phase leaves in the receiver's size array (Algorithm "TuNA", line 14), without the exchange.
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) k_rotate_init(const int32_t* __restrict__ sendcounts,
-                                                     int32_t* __restrict__ cur, int P, int Q, int N) {
+                                                     int32_t* __restrict__ cur, int P, int Q, int N, int up) {
     const int e = blockIdx.x * blockDim.x + threadIdx.x;      // grid (ceil(P / 256), ceil(P / kExchangeRanks))
     if (e >= P) return;
     const int j = e / Q, l = e - j * Q;
@@ -443,8 +447,8 @@ __global__ void __launch_bounds__(256) k_rotate_init(const int32_t* __restrict__
         v[k] = 0;
         if (p < P) {
             const int n = p / Q, g = p - n * Q;
-            int dn = n - j; if (dn < 0) dn += N;
-            int dg = g - l; if (dg < 0) dg += Q;
+            int dn = up ? n + j : n - j; if (dn < 0) dn += N; if (dn >= N) dn -= N;
+            int dg = up ? g + l : g - l; if (dg < 0) dg += Q; if (dg >= Q) dg -= Q;
             v[k] = sendcounts[(size_t)p * P + dn * Q + dg];
         }
     }
