@@ -1569,12 +1569,19 @@ int run_pipelined(Ctx& c, const Prepared& prepared, hipStream_t s) {
     Prepared& pr = plan.pr;
     const PlanHost& pl = pr.dp->host;
     const size_t nph = pl.phases.size();
-    if (!c.meta_stream) HIPCHK(hipStreamCreateWithFlags(&c.meta_stream, hipStreamNonBlocking));
-    if (!c.ev_fork) HIPCHK(hipEventCreateWithFlags(&c.ev_fork, hipEventDisableTiming));
-    while (c.ev_phase.size() < nph) {
+    // the second stream and the events are made at the first such call; where the runtime refuses them the call
+    // is made in two passes on the caller's stream instead
+    bool have = true;
+    if (!c.meta_stream && hipStreamCreateWithFlags(&c.meta_stream, hipStreamNonBlocking) != hipSuccess) { c.meta_stream = nullptr; have = false; }
+    if (have && !c.ev_fork && hipEventCreateWithFlags(&c.ev_fork, hipEventDisableTiming) != hipSuccess) { c.ev_fork = nullptr; have = false; }
+    while (have && c.ev_phase.size() < nph) {
         hipEvent_t e;
-        HIPCHK(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) { have = false; break; }
         c.ev_phase.push_back(e);
+    }
+    if (!have) {
+        (void)hipGetLastError();
+        return run_two_pass(c, prepared, s);
     }
     const size_t mbytes = plan_meta_bytes(pr);
     const size_t dbytes = pr.ds.t_bytes ? align_up(pr.ds.t_bytes + kTailSlack) : 0;

@@ -28,3 +28,18 @@ def read_golden(name):
 @pytest.fixture(scope="session")
 def golden():
     return read_golden
+
+
+@pytest.fixture(autouse=True, scope="module")
+def _release_the_default_workspace_after_each_module():
+    """The default context's workspace only grows (a test with T in the paper's slots can leave it at 200 GiB):
+    after every GPU test module it is released, and torch's cached blocks with it, so that no module depends on
+    what ran before it."""
+    yield
+    binding = sys.modules.get("paper_2411_02581_amd.binding")
+    torch = sys.modules.get("torch")
+    if binding is None or torch is None or getattr(binding, "_lib", None) is None or not torch.cuda.is_available():
+        return
+    torch.cuda.synchronize()
+    binding.tuna_release()             # refuses while persistent plans are alive; then nothing is freed
+    torch.cuda.empty_cache()

@@ -158,6 +158,9 @@ def test_random_problems_through_every_entry_point(tuna, seed):
             del send, recv, meta
     finally:
         assert tuna.tuna_ctx_destroy(own_ctx) == 0
+        # the default context's workspace only grows; a case with T in the paper's slots can leave it at 200 GiB
+        assert tuna.tuna_release() == 0
+        torch.cuda.empty_cache()
     print(seen, flush=True)
     assert all(seen[k] >= 5 for k in ("ex", "ctx", "plan", "noalloc", "flat_api")), seen
 
@@ -217,3 +220,5 @@ def test_random_large_problems_back_to_back(tuna):
             raise AssertionError("%s: %d bytes differ, first at offset %d" % (what, bad.size, bad[0]))
         assert np.array_equal(send.cpu().numpy(), host), what + ": send buffer modified"
         del send, recv, sc, sd, rcn, rd
+    assert tuna.tuna_release() == 0
+    torch.cuda.empty_cache()
