@@ -138,7 +138,7 @@ class Resident:
         torch.cuda.synchronize()
         ms_per_step = (time.perf_counter() - t_start) * 1e3 / self.steps
         o.profile = 1
-        kern = {"pack": [0.0, 0, 0], "exchange": [0.0, 0, 0], "unpack": [0.0, 0, 0]}   # ms, launches, payload bytes
+        kern = {"pack": [0.0, 0, 0], "exchange": [0.0, 0, 0], "unpack": [0.0, 0, 0], "unpack_last": [0.0, 0, 0]}   # ms, launches, payload bytes
         meta_ms = prep_ms = self_ms = prof_total = 0.0
         for _ in range(self.steps):
             self.call(rl, rg, o)
@@ -149,7 +149,10 @@ class Resident:
             for x in range(st.n_phases):
                 ph = st.phase[x]
                 meta_ms += ph.ms_metadata
-                for name, ms in (("pack", ph.ms_pack), ("exchange", ph.ms_exchange), ("unpack", ph.ms_unpack)):
+                # the tiled hop of a schedule's last phase is a kernel variant of its own when the data is word-granular
+                last_tiled = bool(st.fused) and x + 1 == st.n_phases and st.granularity < 16
+                for name, ms in (("pack", ph.ms_pack), ("exchange", ph.ms_exchange),
+                                 ("unpack_last" if last_tiled else "unpack", ph.ms_unpack)):
                     if ms > 0:
                         kern[name][0] += ms
                         kern[name][1] += 1
@@ -158,7 +161,10 @@ class Resident:
         st = tuna.tuna_get_stats()
         hop_bytes = sum(st.phase[x].payload_bytes for x in range(st.n_phases))
         if st.fused:        # one kernel per phase: the copy engine's hop is reported in the pack column, the
-            kern = {"hop": kern["pack"], "tiled_hop": kern["unpack"]}     # destination-tiled hop in the unpack column
+            kern = {"hop": kern["pack"], "tiled_hop": kern["unpack"],     # destination-tiled hop in the unpack column
+                    "tiled_hop_last": kern["unpack_last"]}
+        else:
+            kern.pop("unpack_last")
         kernels = {}
         for name, (ms, n, pbytes) in kern.items():
             if n and ms > 0:
@@ -246,7 +252,8 @@ def kernel_name(stage, gran, exact, max_block_bytes=None):
         return "tuna::k_hop_small<%d>" % (4 if gran >= 4 else 1)      # one thread per block when all blocks fit into 64 bytes
     return {"pack": "tuna::k_copy<0, %d, %s>" % (gran, et), "exchange": "tuna::k_copy<1, 16, false>",
             "unpack": "tuna::k_copy<2, %d, %s>" % (min(gran, 16), et), "hop": "tuna::k_copy<3, %d, %s>" % (gran, et),
-            "tiled_hop": "tuna::k_copy_tiled<%d>" % (16 if gran >= 16 else 4)}[stage]
+            "tiled_hop": "tuna::k_copy_tiled<%d, 4>" % (16 if gran >= 16 else 4),
+            "tiled_hop_last": "tuna::k_copy_tiled<4, 8>"}[stage]
 
 
 def roofline_of(rows, steps, traffic, copy_ceiling):

@@ -238,6 +238,7 @@ void carve_layout(Carver& cv, int P, LayoutDev& L) {
     L.unit_base = cv.take<int>(P + 1);
     L.n_units = cv.take<int>(1);
     L.units = nullptr;
+    L.unit_chunks = kUnitChunks;
 }
 
 MetaBuffers carve_meta(Carver& cv, int P) {
@@ -811,13 +812,27 @@ bool phase_is_tiled(const Prepared& pr, size_t i) {
     return i + 1 == pr.dp->host.phases.size() ? pr.tiled_final : (pr.tiled && pr.exact_t);
 }
 
+// The last phase of a word-granular schedule as a tiled hop takes units of twice the size (k_copy_tiled<4, 8>):
+// every block it writes has an edge piece, and what a wave spends on its edge pieces does not grow with the unit.
+bool phase_has_wide_units(const Prepared& pr, size_t i) {
+    return i + 1 == pr.dp->host.phases.size() && pr.tiled_final && pr.gran < 16;
+}
+
+// the receive-side layout of phase i with the unit size its payload kernel takes
+LayoutDev layout_of_phase(const Prepared& pr, size_t i, const LayoutDev& Lr) {
+    LayoutDev L = Lr;
+    L.unit_chunks = phase_has_wide_units(pr, i) ? kWideUnitChunks : kUnitChunks;
+    return L;
+}
+
 int launch_resolve(const Prepared& pr, size_t i, const int32_t* nxt, const HopDev& hop, hipStream_t s);
 
 // The metadata of a phase that runs as the destination-tiled hop: the size exchange, the places in T of the
 // blocks it stores there, every block's source and destination, then the layout of the 16-byte pieces of the
 // destinations in place of the chunk scan.
 int launch_tiled_metadata(const Prepared& pr, size_t i, const int32_t* cur, int32_t* nxt, const LayoutDev& Ls,
-                          const LayoutDev& Lr, const HopDev& hop, hipStream_t s) {
+                          const LayoutDev& Lr_, const HopDev& hop, hipStream_t s) {
+    const LayoutDev Lr = layout_of_phase(pr, i, Lr_);
     const PhaseHost& ph = pr.dp->host.phases[i];
     const int P = pr.P;
     const bool last = i + 1 == pr.dp->host.phases.size();
@@ -955,6 +970,7 @@ void carve_self(Carver& cv, Prepared& pr) {
     L.rank_base = cv.take<long long>(P + 1);
     L.unit_base = cv.take<int>(P + 1);
     L.n_units = cv.take<int>(1);
+    L.unit_chunks = kUnitChunks;
     pr.self_units = self_unit_bound(pr);
     L.units = cv.take<int4>(pr.self_units);
     carve_hop(cv, pr.P, 1, pr.selfH);
@@ -1048,16 +1064,19 @@ int launch_phase_data(const Prepared& pr, size_t i, const LayoutDev& Ls, const L
             // tiled over the 16-byte pieces of the destinations (k_copy_tiled); its time is reported as the
             // phase's unpack time, so that it can be told from the copy engine's one-kernel hops
             TiledCopyArgs fa{};
-            fa.L = Lr; fa.hop = hop; fa.nseg = ph.nseg; fa.T = pr.T; fa.user_limit = pr.user_limit;
+            fa.L = layout_of_phase(pr, i, Lr); fa.hop = hop; fa.nseg = ph.nseg; fa.T = pr.T; fa.user_limit = pr.user_limit;
             const dim3 grid((unsigned)((launch_units + kCopyThreads / kWave - 1) / (kCopyThreads / kWave)));
             if (grid.x) {
                 const int resident = short_launch ? 8 : 7;
                 if (pr.gran >= 16) {
-                    static const size_t lds = static_lds_of(k_copy_tiled<16>);
-                    hipLaunchKernelGGL(k_copy_tiled<16>, grid, dim3(kCopyThreads), occupancy_padding(resident, lds), s, fa);
+                    static const size_t lds = static_lds_of(k_copy_tiled<16, kChunksPerLane>);
+                    hipLaunchKernelGGL((k_copy_tiled<16, kChunksPerLane>), grid, dim3(kCopyThreads), occupancy_padding(resident, lds), s, fa);
+                } else if (phase_has_wide_units(pr, i)) {
+                    static const size_t lds = static_lds_of(k_copy_tiled<4, kWideChunksPerLane>);
+                    hipLaunchKernelGGL((k_copy_tiled<4, kWideChunksPerLane>), grid, dim3(kCopyThreads), occupancy_padding(resident, lds), s, fa);
                 } else {
-                    static const size_t lds = static_lds_of(k_copy_tiled<4>);
-                    hipLaunchKernelGGL(k_copy_tiled<4>, grid, dim3(kCopyThreads), occupancy_padding(resident, lds), s, fa);
+                    static const size_t lds = static_lds_of(k_copy_tiled<4, kChunksPerLane>);
+                    hipLaunchKernelGGL((k_copy_tiled<4, kChunksPerLane>), grid, dim3(kCopyThreads), occupancy_padding(resident, lds), s, fa);
                 }
                 HIPCHK(hipGetLastError());
             }

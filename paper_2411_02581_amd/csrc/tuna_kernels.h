@@ -21,6 +21,8 @@ constexpr int kWave = 64;
 constexpr int kCopyThreads = 256;                        // 4 waves, each an independent work unit
 constexpr int kChunksPerLane = 4;
 constexpr int kUnitChunks = kWave * kChunksPerLane;      // 256 chunks = 4 KiB per wave unit
+constexpr int kWideChunksPerLane = 8;
+constexpr int kWideUnitChunks = kWave * kWideChunksPerLane;   // 8 KiB: the last phase of a schedule as a word-granular tiled hop
 constexpr int kRankAlignChunks = 8;                      // every rank's region of a staging buffer or of a class of exact-size T starts on a 128-byte line
 constexpr int kScanThreads = 256;
 constexpr int kScanItems = 4;
@@ -103,6 +105,7 @@ struct LayoutDev {
     int4* units;                   // {rank, first segment, first chunk (rank-local), chunks in unit}
     int* n_units;                  // total units
     int ld;                        // row stride of pre (>= P + 1)
+    int unit_chunks;               // chunks (or pieces) per wave unit: kUnitChunks, or kWideUnitChunks for the units of k_copy_tiled<4, 8>
 };
 
 // One-kernel phases: where every block a rank receives in the phase is read from and written to,
@@ -626,7 +629,7 @@ __device__ __forceinline__ void scan_rank_bases(int P, const LayoutDev& L, unsig
     for (int p = p0; p < p1; ++p) {
         const int c = L.tot[p];
         sc += (c + ralign - 1) / ralign * ralign;
-        st += (c + kUnitChunks - 1) / kUnitChunks;
+        st += (c + L.unit_chunks - 1) / L.unit_chunks;
     }
     long long ic = sc;
     int it = st;
@@ -652,7 +655,7 @@ __device__ __forceinline__ void scan_rank_bases(int P, const LayoutDev& L, unsig
         L.rank_base[p] = run_c;
         if (L.unit_base) L.unit_base[p] = run_t;
         run_c += (c + ralign - 1) / ralign * ralign;
-        run_t += (c + kUnitChunks - 1) / kUnitChunks;
+        run_t += (c + L.unit_chunks - 1) / L.unit_chunks;
     }
     if (tid == 0) {
         L.rank_base[P] = totc;
@@ -844,7 +847,7 @@ __global__ void __launch_bounds__(kScanThreads) k_layout_base(int P, LayoutDev L
 }
 
 // ------------------------------------------------------------------------------------------
-// k_layout_units: cut every rank's staged chunks into wave units of kUnitChunks and record, per
+// k_layout_units: cut every rank's staged chunks into wave units of L.unit_chunks and record, per
 // unit, the rank and the first segment that overlaps it (binary search in the rank's prefix
 // row, which is staged in LDS when it fits: lds_ints = nseg + 1, else 0 and the search reads
 // global memory).  grid (P, layouts): one workgroup per rank and layout (y = 0 receive side,
@@ -856,7 +859,8 @@ __global__ void __launch_bounds__(256) k_layout_units(int nseg, LayoutDev Lr, La
     const LayoutDev& L = blockIdx.y == 0 ? Lr : Ls;
     const int p = blockIdx.x;
     const int tot = L.tot[p];
-    const int nu = (tot + kUnitChunks - 1) / kUnitChunks;
+    const int uc = L.unit_chunks;
+    const int nu = (tot + uc - 1) / uc;
     if (nu == 0) return;                       // uniform over the workgroup
     const int* pre = L.pre + (size_t)p * L.ld;
     if (lds_ints) {
@@ -866,13 +870,13 @@ __global__ void __launch_bounds__(256) k_layout_units(int nseg, LayoutDev Lr, La
     }
     const int ub = L.unit_base[p];
     for (int t = threadIdx.x; t < nu; t += blockDim.x) {
-        const int c0 = t * kUnitChunks;
+        const int c0 = t * uc;
         int lo = 0, hi = nseg;                 // largest s in [0, nseg) with pre[s] <= c0
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
             if (pre[mid] <= c0) lo = mid; else hi = mid;
         }
-        L.units[ub + t] = make_int4(p, lo, c0, min(kUnitChunks, tot - c0));
+        L.units[ub + t] = make_int4(p, lo, c0, min(uc, tot - c0));
     }
 }
 
@@ -1492,9 +1496,11 @@ __global__ void __launch_bounds__(kScanThreads) k_tiled_layout(const TiledLayout
 
 // ------------------------------------------------------------------------------------------
 // k_copy_tiled: the payload kernel of the destination-tiled hop.  Work unit = one wavefront x
-// 256 consecutive pieces of one rank (k_tiled_layout); no workgroup barrier.  Lane i of a window loads
+// 64 CPL consecutive pieces of one rank (k_tiled_layout; CPL = 4, or 8 for a word-granular last phase: what
+// a wave spends on its edge pieces does not grow with the unit, measured 4.6 % per start at r = P on the
+// 16 GiB workload, while phases without edge pieces lose 2 % with the larger unit); no workgroup barrier.  Lane i of a window loads
 // the prefix and the resolved source, destination and size of segment s0 + i and derives the address of
-// the segment's first own piece; every lane finds the segment of each of its 4 pieces by the same
+// the segment's first own piece; every lane finds the segment of each of its CPL pieces by the same
 // branch-free search as the copy engine.  A piece that lies inside its block is one 16-byte load at
 // the source's own alignment and one aligned streaming store.  A piece at a block's edge is put together
 // word by word (GRAN = 4: every size and address is a multiple of 4) from its block and the one behind it
@@ -1512,7 +1518,7 @@ struct TiledCopyArgs {
     unsigned long long user_limit;      // address one past the last byte of S that holds a block
 };
 
-template <int GRAN>
+template <int GRAN, int CPL>
 __global__ void __launch_bounds__(kCopyThreads) k_copy_tiled(const TiledCopyArgs a) {
     __shared__ int s_pre[kCopyThreads / kWave][kWave];
     __shared__ int s_size[kCopyThreads / kWave][kWave];
@@ -1538,10 +1544,10 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy_tiled(const TiledCopyArgs
     unsigned long long* wsrc = s_src[wv];
     unsigned long long* wdst = s_dst[wv];
     const unsigned long long tb = (unsigned long long)a.T;
-    int c[kChunksPerLane];
-    bool pend[kChunksPerLane];
+    int c[CPL];
+    bool pend[CPL];
 #pragma unroll
-    for (int k = 0; k < kChunksPerLane; ++k) {
+    for (int k = 0; k < CPL; ++k) {
         c[k] = c0 + k * kWave + lane;
         pend[k] = c[k] < cend;
     }
@@ -1596,13 +1602,13 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy_tiled(const TiledCopyArgs
         const int nlive = __popcll(__ballot(pre_i < cend));
         int steps = 0;
         while ((1 << steps) < nlive) ++steps;
-        bool act[kChunksPerLane];
-        int lo[kChunksPerLane], hi[kChunksPerLane];
+        bool act[CPL];
+        int lo[CPL], hi[CPL];
 #pragma unroll
-        for (int k = 0; k < kChunksPerLane; ++k) { act[k] = pend[k] && c[k] < wend; lo[k] = 0; hi[k] = nlive; }
+        for (int k = 0; k < CPL; ++k) { act[k] = pend[k] && c[k] < wend; lo[k] = 0; hi[k] = nlive; }
         for (int it = 0; it < steps; ++it) {
 #pragma unroll
-            for (int k = 0; k < kChunksPerLane; ++k) {
+            for (int k = 0; k < CPL; ++k) {
                 const int mid = (lo[k] + hi[k]) >> 1;
                 const bool up = wpre[mid] <= c[k];
                 const bool move = mid > lo[k];
@@ -1611,11 +1617,11 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy_tiled(const TiledCopyArgs
             }
         }
         // every piece as a byte offset from its block's start: 32-bit arithmetic from here on
-        int off[kChunksPerLane];
-        bool whole[kChunksPerLane], edge[kChunksPerLane];
-        v4u v[kChunksPerLane];
+        int off[CPL];
+        bool whole[CPL], edge[CPL];
+        v4u v[CPL];
 #pragma unroll
-        for (int k = 0; k < kChunksPerLane; ++k) {
+        for (int k = 0; k < CPL; ++k) {
             const int idx = lo[k];
             off[k] = woff0[idx] + ((c[k] - wpre[idx]) << 4);
             whole[k] = act[k] && off[k] >= 0 && off[k] + 16 <= wlim[idx];
@@ -1624,7 +1630,7 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy_tiled(const TiledCopyArgs
         }
         // ---- loads of the pieces inside their blocks, issued together ----------------------------------------
 #pragma unroll
-        for (int k = 0; k < kChunksPerLane; ++k)
+        for (int k = 0; k < CPL; ++k)
             if (whole[k]) __builtin_memcpy(&v[k], reinterpret_cast<const unsigned char*>(wsrc[lo[k]] + (unsigned long long)(long long)off[k]), 16);
         // ---- pieces at block edges: a word lies in the piece's block, in the block behind it, or in none.  The
         // loads go out at once and travel with the ones above; nothing loaded is looked at before the stores.
@@ -1633,14 +1639,17 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy_tiled(const TiledCopyArgs
         unsigned int emask = 0;                      // bit 4 k + q: word q of piece k was loaded
         unsigned int raremask = 0;
         if (GRAN < 16) {
-            unsigned int todo = (edge[0] ? 1u : 0u) | (edge[1] ? 2u : 0u) | (edge[2] ? 4u : 0u) | (edge[3] ? 8u : 0u);
-            static_assert(kChunksPerLane == 4, "the edge loop picks among four pieces");
+            static_assert(CPL <= 8, "emask holds four bits per piece");
+            unsigned int todo = 0;
+#pragma unroll
+            for (int k = 0; k < CPL; ++k) todo |= edge[k] ? 1u << k : 0u;
             while (__ballot(todo != 0)) {
                 bool on = todo != 0;
                 const int ks = on ? __ffs((int)todo) - 1 : 0;
                 todo &= todo - 1;
-                const int offk = ks == 0 ? off[0] : (ks == 1 ? off[1] : (ks == 2 ? off[2] : off[3]));
-                const int t = ks == 0 ? lo[0] : (ks == 1 ? lo[1] : (ks == 2 ? lo[2] : lo[3]));
+                int offk = off[0], t = lo[0];
+#pragma unroll
+                for (int k = 1; k < CPL; ++k) { offk = ks == k ? off[k] : offk; t = ks == k ? lo[k] : t; }
                 const int n = wsize[t];
                 const int nlim = wlim[t];                    // < n only for the last block of S when it is bound for T
                 const bool has_next = sw + t + 1 < a.nseg;
@@ -1669,14 +1678,14 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy_tiled(const TiledCopyArgs
                     }
                 }
 #pragma unroll
-                for (int kk = 0; kk < kChunksPerLane; ++kk)
+                for (int kk = 0; kk < CPL; ++kk)
                     if (on && kk == ks) { v[kk][0] = w[0]; v[kk][1] = w[1]; v[kk][2] = w[2]; v[kk][3] = w[3]; }
             }
             // rare: the blocks of a piece reach past the entries the window holds, or several blocks end inside
             // one piece (a row of tiny or empty blocks): a walk over the entries in the window, and over the hop
             // arrays in global memory behind it
 #pragma unroll
-            for (int k = 0; k < kChunksPerLane; ++k) {
+            for (int k = 0; k < CPL; ++k) {
                 if (!(raremask & (1u << k))) continue;
                 int t = sw + lo[k];
                 unsigned long long ta = wdst[lo[k]], te = ta + (unsigned long long)wsize[lo[k]], ts = wsrc[lo[k]];
@@ -1718,7 +1727,7 @@ __global__ void __launch_bounds__(kCopyThreads) k_copy_tiled(const TiledCopyArgs
         // ---- stores: whole pieces and edge pieces with all four words as aligned streaming stores (eight whole
         // lines per wave store), the others word by word (the ends of a run) -----------------------------------
 #pragma unroll
-        for (int k = 0; k < kChunksPerLane; ++k) {
+        for (int k = 0; k < CPL; ++k) {
             if (whole[k] || edge[k]) {
                 unsigned char* d = reinterpret_cast<unsigned char*>(wdst[lo[k]] + (unsigned long long)(long long)off[k]);
                 const unsigned int em = (emask >> (4 * k)) & 0xfu;
